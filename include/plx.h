@@ -1,0 +1,199 @@
+/*
+ * plx -- the per-GPU hot path of full-graph GCN training with a double-permuted adjacency,
+ * for one AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * What a layer computes (paper Sec. 2.1): with A^ = D^-1/2 (A + I) D^-1/2,
+ *     aggregation   H = A^ F          (Eq. 2.1, sparse x dense)
+ *     combination   Q = H W           (Eq. 2.2, dense x dense)
+ *     activation    F' = ReLU(Q)      (Eq. 2.3)
+ * and backward (Eq. 2.4-2.7)
+ *     dQ = dF' * [Q > 0],  dW = H^T dQ,  dH = dQ W^T,  dF = A^^T dH.
+ * The stored adjacency is the double-permuted P_r A^ P_c^T (even layers) and its transpose
+ * P_c A^ P_r^T (odd layers), Sec. 5.1, Eq. 5.3-5.4.
+ *
+ * Pointer kinds.  Every pointer named "device" is memory of the context's GPU; the library
+ * never copies it to the host.  `plx_ctx**`, `plx_csr**`, the int64 outputs of plx_csr_dims /
+ * plx_csr_bins and strings are host memory.  Dense matrices are row-major with a leading
+ * dimension `ld*` counted in ELEMENTS (>= the number of columns).  For PLX_F32 an element is
+ * an IEEE fp32; for PLX_BF16 it is a bfloat16 (upper 16 bits of an fp32, round-to-nearest-
+ * even on store); sums are always carried in fp32.
+ *
+ * Ownership.  The caller owns every dense buffer and workspace it passes.  The library owns
+ * what is inside a plx_csr (obtained through the context's allocator) until plx_csr_destroy.
+ *
+ * Execution.  All work is queued on the context's HIP stream and returns without waiting,
+ * except plx_build_csr, plx_csr_import and plx_csr_export, which wait for their own work
+ * (they are set-up calls).  Calls on one context must not overlap in time.
+ *
+ * Errors.  Every entry point returns a plx_status; nothing aborts or throws across the
+ * ABI.  Arguments are checked on the host before any GPU call (NULL, negative sizes,
+ * ld < columns, unknown enum, shapes that disagree with the handle), so a bad call leaves
+ * the GPU untouched.  plx_last_error gives a one-line description of the last failure on
+ * that context.
+ */
+#ifndef PLX_H
+#define PLX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PLX_API __attribute__((visibility("default")))
+
+typedef struct plx_ctx plx_ctx;
+typedef struct plx_csr plx_csr;
+
+typedef enum {
+    PLX_OK = 0,
+    PLX_ERR_INVALID = 1,      /* NULL pointer, negative size, bad enum, bad node id or permutation */
+    PLX_ERR_SHAPE = 2,        /* ld < columns, dimensions that disagree with the handle, workspace too small */
+    PLX_ERR_UNSUPPORTED = 3,  /* a size or dtype this build does not handle */
+    PLX_ERR_OOM = 4,          /* the allocator returned NULL */
+    PLX_ERR_DEVICE = 5,       /* no usable GPU, or a HIP call failed */
+    PLX_ERR_INTERNAL = 6
+} plx_status;
+
+typedef enum { PLX_F32 = 0, PLX_BF16 = 1 } plx_dtype;
+typedef enum { PLX_ACT_NONE = 0, PLX_ACT_RELU = 1 } plx_act;
+typedef enum {
+    PLX_ORDER_COMBINE_FIRST = 0, /* Z = A^ (H W): the sparse product runs at the output width    */
+    PLX_ORDER_AGG_FIRST = 1,     /* Z = (A^ H) W: the order of Eq. 2.1 -> 2.2                      */
+    PLX_ORDER_AUTO = 2           /* whichever runs the sparse product at min(d_in, d_out)         */
+} plx_order;
+
+/* Device-memory allocator hooks (e.g. bound to a framework's caching allocator).  `alloc`
+ * returns device memory aligned to at least 256 bytes, or NULL.  Both NULL = hipMalloc/hipFree. */
+typedef void* (*plx_alloc_fn)(size_t bytes, void* user);
+typedef void (*plx_free_fn)(void* ptr, void* user);
+
+/* ---- context ------------------------------------------------------------------------------
+ * device >= 0: a GPU ordinal; hip_stream: a hipStream_t on that device (NULL = the default
+ * stream).  device == -1 creates a validate-only context: every entry point still checks its
+ * arguments and then returns PLX_ERR_DEVICE instead of touching a GPU (used to test error
+ * handling on a machine without one).  Returns PLX_ERR_DEVICE if the GPU cannot be used. */
+PLX_API plx_status plx_ctx_create(int device, void* hip_stream, plx_alloc_fn alloc, plx_free_fn release,
+                                  void* user, plx_ctx** out);
+PLX_API void plx_ctx_destroy(plx_ctx* ctx);
+PLX_API const char* plx_last_error(const plx_ctx* ctx);   /* host string owned by the context */
+PLX_API const char* plx_status_string(plx_status s);
+PLX_API plx_status plx_sync(plx_ctx* ctx);                /* wait for the context's stream */
+
+/* ---- adjacency set-up (Sec. 2.1 preprocessing + Sec. 5.1 double permutation) -----------------
+ * plx_build_csr: src/dst are device int64[n_edges] node ids in [0, n), any order, either or
+ * both directions, duplicates and self-loops allowed.  The graph is symmetrised, duplicates
+ * and input loops dropped, exactly one self-loop per node added; d_u = number of stored
+ * entries in row u (>= 1); value(u,v) = (float)(1.0 / sqrt((double)d_u * (double)d_v)).
+ * perm_r / perm_c are device int64[n] with perm[old] = new (NULL = identity).  The handle
+ * stores  A_fwd = P_r A^ P_c^T  and  A_bwd = A_fwd^T = P_c A^ P_r^T, both as CSR with strictly
+ * ascending columns inside a row, plus the degrees in original id order.
+ * Errors: PLX_ERR_INVALID for an id outside [0,n) or a permutation that is not a bijection
+ * (detected on the GPU; the call waits for that answer); n >= 2^31 or more than 2^31-1 stored
+ * entries is PLX_ERR_UNSUPPORTED. */
+PLX_API plx_status plx_build_csr(plx_ctx* ctx, int64_t n, int64_t n_edges, const int64_t* src, const int64_t* dst,
+                                 const int64_t* perm_r, const int64_t* perm_c, plx_csr** out);
+
+/* plx_csr_import: adopt (copy) an already-built m x k block: device rowptr int64[m+1]
+ * (rowptr[0] = 0, non-decreasing, rowptr[m] = nnz), col int32[nnz] in [0,k) ascending inside
+ * a row, val fp32[nnz].  The transposed orientation is built by the library.  The structure
+ * is checked on the GPU (PLX_ERR_INVALID if it is not as described). */
+PLX_API plx_status plx_csr_import(plx_ctx* ctx, int64_t m, int64_t k, int64_t nnz, const int64_t* rowptr,
+                                  const int32_t* col, const float* val, plx_csr** out);
+
+/* m, k, nnz of the forward orientation (host outputs, any may be NULL). */
+PLX_API plx_status plx_csr_dims(const plx_csr* csr, int64_t* m, int64_t* k, int64_t* nnz);
+
+/* Copy one orientation out to caller-owned device arrays: transposed == 0 gives A_fwd
+ * (rowptr int64[m+1], col int32[nnz], val fp32[nnz]); transposed != 0 gives A_bwd (rowptr
+ * int64[k+1]).  deg (device int64[n], original id order) is written only for handles made by
+ * plx_build_csr; pass NULL otherwise.  Any output pointer may be NULL to skip it. */
+PLX_API plx_status plx_csr_export(plx_ctx* ctx, const plx_csr* csr, int transposed, int64_t* rowptr,
+                                  int32_t* col, float* val, int64_t* deg);
+
+/* Row-binning summary of one orientation (host outputs): number of rows handled by a group
+ * of lanes, by a whole wavefront, and split over several wavefronts, for feature width d.
+ * For inspection and tests; any pointer may be NULL. */
+PLX_API plx_status plx_csr_bins(const plx_csr* csr, int transposed, int64_t d, plx_dtype dtype,
+                                int64_t* rows_subwave, int64_t* rows_wave, int64_t* rows_split);
+
+PLX_API void plx_csr_destroy(plx_ctx* ctx, plx_csr* csr);
+
+/* ---- sparse x dense (Eq. 2.1 and Eq. 2.7) -----------------------------------------------------
+ * plx_spmm:   Y[m x d] = A_fwd X[k x d].      plx_spmm_t:   Y[k x d] = A_fwd^T X[m x d].
+ * X, Y device, row-major, ldx, ldy >= d, Y fully overwritten (rows without entries become 0),
+ * X and Y must not overlap.  128-bit gathers are used when X, Y are 16-byte aligned and ldx,
+ * ldy are multiples of 16 bytes; other layouts take a narrower path with the same result.
+ * No floating-point atomics: results are bit-identical from run to run. */
+PLX_API plx_status plx_spmm(plx_ctx* ctx, const plx_csr* csr, const void* X, int64_t ldx, void* Y, int64_t ldy,
+                            int64_t d, plx_dtype dtype);
+PLX_API plx_status plx_spmm_t(plx_ctx* ctx, const plx_csr* csr, const void* X, int64_t ldx, void* Y, int64_t ldy,
+                              int64_t d, plx_dtype dtype);
+
+/* ---- dense x dense on the matrix cores (Eq. 2.2, 2.6, 2.5) --------------------------------------
+ * plx_gemm_nn:  C[M x N] = A[M x K]   B[K x N]
+ * plx_gemm_nt:  C[M x N] = A[M x K]   B[N x K]^T
+ * plx_gemm_tn:  C[M x N] = A[R x M]^T B[R x N]     (reduction over the R rows, split over
+ *               workgroups; partial sums are combined in a fixed order).  C is always fp32 for
+ *               plx_gemm_tn; ws is device workspace of at least plx_gemm_tn_workspace bytes.
+ * A, C of nn/nt have dtype `dtype`; the small operand B (a weight matrix) is always fp32.
+ * All device, row-major. */
+PLX_API plx_status plx_gemm_nn(plx_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                               const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype);
+PLX_API plx_status plx_gemm_nt(plx_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                               const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype);
+PLX_API size_t plx_gemm_tn_workspace(int64_t R, int64_t M, int64_t N);
+PLX_API plx_status plx_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const void* A, int64_t lda,
+                               const void* B, int64_t ldb, float* C, int64_t ldc, plx_dtype dtype,
+                               void* ws, size_t ws_bytes);
+
+/* ---- element-wise steps --------------------------------------------------------------------------
+ * plx_relu (Eq. 2.3): F = max(Z, 0).  plx_relu_bwd (Eq. 2.4): dZ = dF where Z > 0, else 0.
+ * rows x cols matrices, device; in-place (F == Z, dZ == dF) is allowed. */
+PLX_API plx_status plx_relu(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz,
+                            void* F, int64_t ldf, plx_dtype dtype);
+PLX_API plx_status plx_relu_bwd(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz,
+                                const void* dF, int64_t lddf, void* dZ, int64_t lddz, plx_dtype dtype);
+
+/* Node-classification loss head (Sec. 2.1): mean softmax cross-entropy over all n rows of the
+ * logits Z[n x c] against labels y (device int64[n], each in [0,c)); writes
+ * dZ = (softmax(Z) - onehot(y)) / n and, if loss != NULL, the mean loss as one device fp32.
+ * row_loss is device fp32[n] scratch (the per-row terms, summed in a fixed order). */
+PLX_API plx_status plx_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, int64_t ldz, const int64_t* y,
+                                  void* dZ, int64_t lddz, float* row_loss, float* loss, plx_dtype dtype);
+
+/* ---- one GCN layer ---------------------------------------------------------------------------------
+ * The adjacency used is A = A_fwd (transposed_A == 0, even layers) or A = A_bwd (transposed_A
+ * != 0, odd layers), of shape ma x ka.  H is ka x din, W is din x dout (fp32), Z and F are
+ * ma x dout.
+ *
+ * plx_gcn_layer_fwd:  Z = A H W (pre-activation, always written); F = act(Z) if F != NULL.
+ *   order AGG_FIRST : saved[ma x din] = A H (Eq. 2.1) then Z = saved W (Eq. 2.2); `saved` must
+ *                     be given and is needed again by the backward call.
+ *   order COMBINE_FIRST: T[ka x dout] = H W in the workspace, then Z = A T; `saved` is unused.
+ *   order AUTO      : AGG_FIRST if din < dout, else COMBINE_FIRST (so `saved` must be given
+ *                     whenever din < dout).
+ * plx_gcn_layer_bwd:  given dF (gradient wrt F, or wrt Z when act == NONE) computes
+ *   dZ = dF * [Z > 0] (Eq. 2.4), dW[din x dout] (fp32, Eq. 2.5) and, unless dH == NULL,
+ *   dH[ka x din] (Eq. 2.6 + 2.7; the gradient wrt the layer input H).
+ * ws: device workspace of at least plx_gcn_layer_workspace(...) bytes (same arguments), used
+ * by both calls; its contents need not survive between them. */
+PLX_API size_t plx_gcn_layer_workspace(const plx_csr* csr, int transposed_A, int64_t din, int64_t dout,
+                                       plx_dtype dtype, plx_act act, plx_order order);
+PLX_API plx_status plx_gcn_layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
+                                     const void* H, int64_t ldh, const float* W, int64_t ldw,
+                                     int64_t din, int64_t dout, plx_dtype dtype, plx_act act, plx_order order,
+                                     void* Z, int64_t ldz, void* F, int64_t ldf, void* saved, int64_t ldsaved,
+                                     void* ws, size_t ws_bytes);
+PLX_API plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
+                                     const void* H, int64_t ldh, const float* W, int64_t ldw,
+                                     const void* Z, int64_t ldz, const void* dF, int64_t lddf,
+                                     const void* saved, int64_t ldsaved,
+                                     int64_t din, int64_t dout, plx_dtype dtype, plx_act act, plx_order order,
+                                     void* dH, int64_t lddh, float* dW, int64_t lddw, void* ws, size_t ws_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PLX_H */

@@ -1,0 +1,473 @@
+// One-time adjacency set-up on the GPU (paper Sec. 2.1 preprocessing; Sec. 5.1, Eq. 5.3-5.4):
+// symmetrise, drop duplicates and input loops, add one self-loop per node, relabel rows by
+// P_r and columns by P_c, sort into canonical CSR, value = 1/sqrt(d_u d_v); then the
+// transposed orientation and the row binning the sparse kernels use.
+//
+// All structure work is integer work: 64-bit keys row*n+col, device radix sort (rocPRIM),
+// neighbour comparison for duplicates, prefix sums for compaction and row pointers.
+#include "plx_internal.h"
+
+#include <algorithm>
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_scan.hpp>
+
+namespace plx {
+namespace {
+
+constexpr int kThreads = 256;
+inline unsigned grid_for(int64_t n, int per_block = kThreads) {
+    int64_t g = ceil_div(n, per_block);
+    return (unsigned)std::max<int64_t>(1, std::min<int64_t>(g, 1 << 20));
+}
+
+#define GRID_STRIDE(i, n) \
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < (n); i += (int64_t)gridDim.x * blockDim.x)
+
+enum : int { kFlagBadId = 1, kFlagBadPerm = 2, kFlagBadStruct = 4 };
+
+__global__ void k_check_ids(int64_t n, int64_t ne, const int64_t* src, const int64_t* dst, int* flags) {
+    GRID_STRIDE(e, ne) {
+        int64_t u = src[e], v = dst[e];
+        if (u < 0 || v < 0 || u >= n || v >= n) atomicOr(flags, kFlagBadId);
+    }
+}
+
+__global__ void k_mark_perm(int64_t n, const int64_t* perm, int* hits, int* flags) {
+    GRID_STRIDE(i, n) {
+        int64_t p = perm[i];
+        if (p < 0 || p >= n) atomicOr(flags, kFlagBadPerm);
+        else atomicAdd(&hits[p], 1);
+    }
+}
+
+__global__ void k_check_hits(int64_t n, const int* hits, int* flags) {
+    GRID_STRIDE(i, n) if (hits[i] != 1) atomicOr(flags, kFlagBadPerm);
+}
+
+// keys of both directions of every non-loop edge plus one self-loop per node, in permuted ids
+__global__ void k_make_keys(int64_t n, int64_t ne, const int64_t* src, const int64_t* dst, const int64_t* pr,
+                            const int64_t* pc, uint64_t* keys, uint64_t sentinel) {
+    GRID_STRIDE(i, ne + n) {
+        if (i < ne) {
+            int64_t u = src[i], v = dst[i];
+            if (u == v) {
+                keys[2 * i] = sentinel; keys[2 * i + 1] = sentinel;
+            } else {
+                uint64_t ur = pr ? pr[u] : u, uc = pc ? pc[u] : u;
+                uint64_t vr = pr ? pr[v] : v, vc = pc ? pc[v] : v;
+                keys[2 * i] = ur * (uint64_t)n + vc;
+                keys[2 * i + 1] = vr * (uint64_t)n + uc;
+            }
+        } else {
+            int64_t u = i - ne;
+            uint64_t ur = pr ? pr[u] : u, uc = pc ? pc[u] : u;
+            keys[2 * ne + u] = ur * (uint64_t)n + uc;
+        }
+    }
+}
+
+__global__ void k_flag_unique(int64_t count, const uint64_t* keys, uint64_t sentinel, uint32_t* flag) {
+    GRID_STRIDE(i, count) {
+        uint64_t k = keys[i];
+        flag[i] = (k != sentinel && (i == 0 || keys[i - 1] != k)) ? 1u : 0u;
+    }
+}
+
+// compact the unique keys into (row, col) and count the row lengths
+__global__ void k_scatter_unique(int64_t count, const uint64_t* keys, const uint32_t* flag, const uint32_t* pos,
+                                 uint64_t n, int32_t* row, int32_t* col, unsigned int* rowcount) {
+    GRID_STRIDE(i, count) {
+        if (!flag[i]) continue;
+        uint64_t k = keys[i];
+        uint32_t p = pos[i];
+        int32_t r = (int32_t)(k / n), c = (int32_t)(k % n);
+        row[p] = r; col[p] = c;
+        atomicAdd(&rowcount[r], 1u);
+    }
+}
+
+__global__ void k_widen_counts(int64_t n, const unsigned int* cnt, int64_t* out) {
+    GRID_STRIDE(i, n) out[i] = (int64_t)cnt[i];
+}
+
+// deg (original ids) and the column-side degree table from the permuted-row lengths
+__global__ void k_degrees(int64_t n, const int64_t* rowptr, const int64_t* pr, const int64_t* pc, int64_t* deg,
+                          int64_t* deg_c) {
+    GRID_STRIDE(u, n) {
+        int64_t r = pr ? pr[u] : u;
+        int64_t d = rowptr[r + 1] - rowptr[r];
+        deg[u] = d;
+        deg_c[pc ? pc[u] : u] = d;
+    }
+}
+
+// value = (float)(1 / sqrt(d_row * d_col)), every step a correctly rounded fp64 operation
+__global__ void k_values(int64_t nnz, const int32_t* row, const int32_t* col, const int64_t* rowptr,
+                         const int64_t* deg_c, float* val) {
+    GRID_STRIDE(e, nnz) {
+        int32_t r = row[e];
+        double dr = (double)(rowptr[r + 1] - rowptr[r]);
+        double dc = (double)deg_c[col[e]];
+        val[e] = (float)(1.0 / sqrt(dr * dc));
+    }
+}
+
+// ---- transposition of a CSR orientation --------------------------------------------------------
+
+__global__ void k_expand_rows(int64_t rows, int64_t nnz, const int64_t* rowptr, int32_t* row) {
+    GRID_STRIDE(e, nnz) {
+        int64_t lo = 0, hi = rows;            // last row r with rowptr[r] <= e
+        while (hi - lo > 1) {
+            int64_t mid = (lo + hi) >> 1;
+            if (rowptr[mid] <= e) lo = mid; else hi = mid;
+        }
+        row[e] = (int32_t)lo;
+    }
+}
+
+__global__ void k_transpose_keys(int64_t nnz, const int32_t* row, const int32_t* col, uint64_t rows,
+                                 uint64_t* keys, unsigned int* colcount) {
+    GRID_STRIDE(e, nnz) {
+        keys[e] = (uint64_t)col[e] * rows + (uint64_t)row[e];
+        atomicAdd(&colcount[col[e]], 1u);
+    }
+}
+
+__global__ void k_keys_to_cols(int64_t nnz, const uint64_t* keys, uint64_t rows, int32_t* col) {
+    GRID_STRIDE(e, nnz) col[e] = (int32_t)(keys[e] % rows);
+}
+
+// ---- structure check of an imported block ---------------------------------------------------------
+
+__global__ void k_check_rowptr(int64_t m, int64_t nnz, const int64_t* rowptr, int* flags) {
+    GRID_STRIDE(i, m + 1) {
+        int64_t a = rowptr[i];
+        if (a < 0 || a > nnz) atomicOr(flags, kFlagBadStruct);
+        if (i == 0 && a != 0) atomicOr(flags, kFlagBadStruct);
+        if (i == m && a != nnz) atomicOr(flags, kFlagBadStruct);
+        if (i < m && rowptr[i + 1] < a) atomicOr(flags, kFlagBadStruct);
+    }
+}
+
+__global__ void k_check_cols(int64_t nnz, int64_t k, const int32_t* row, const int32_t* col, int* flags) {
+    GRID_STRIDE(e, nnz) {
+        int32_t c = col[e];
+        if (c < 0 || c >= k) atomicOr(flags, kFlagBadStruct);
+        if (e > 0 && row[e - 1] == row[e] && col[e - 1] >= c) atomicOr(flags, kFlagBadStruct);
+    }
+}
+
+// ---- binning ------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ int length_class(int64_t len) {
+    return len <= 0 ? 0 : 64 - __clzll((unsigned long long)len);   // 1 + floor(log2 len)
+}
+
+__global__ void k_row_class(int64_t rows, const int64_t* rowptr, uint8_t* cls, int32_t* ids, unsigned int* hist) {
+    GRID_STRIDE(r, rows) {
+        int c = length_class(rowptr[r + 1] - rowptr[r]);
+        cls[r] = (uint8_t)c;
+        ids[r] = (int32_t)r;
+        atomicAdd(&hist[c], 1u);
+    }
+}
+
+__global__ void k_gather_bounds(int64_t count, const int32_t* rows, const int64_t* rowptr, int64_t* lo, int64_t* hi) {
+    GRID_STRIDE(q, count) {
+        lo[q] = rowptr[rows[q]];
+        hi[q] = rowptr[rows[q] + 1];
+    }
+}
+
+template <typename T>
+plx_status scan_exclusive(plx_ctx* ctx, TempPool& pool, const T* in, T* out, size_t count) {
+    size_t bytes = 0;
+    PLX_HIP(ctx, rocprim::exclusive_scan(nullptr, bytes, in, out, T(0), count, rocprim::plus<T>(), ctx->stream));
+    void* tmp = pool.get<char>(bytes);
+    if (!tmp) return PLX_ERR_OOM;
+    PLX_HIP(ctx, rocprim::exclusive_scan(tmp, bytes, in, out, T(0), count, rocprim::plus<T>(), ctx->stream));
+    return PLX_OK;
+}
+
+int bit_length(uint64_t x) { int b = 0; while (x) { ++b; x >>= 1; } return b; }
+
+// rowptr[0..rows] from per-row counts (counts array has rows + 1 entries, last one ignored/zero)
+plx_status counts_to_rowptr(plx_ctx* ctx, TempPool& pool, const unsigned int* counts, int64_t rows, int64_t* rowptr) {
+    int64_t* wide = pool.get<int64_t>(rows + 1);
+    if (!wide) return PLX_ERR_OOM;
+    PLX_HIP(ctx, hipMemsetAsync(wide + rows, 0, sizeof(int64_t), ctx->stream));
+    k_widen_counts<<<grid_for(rows), kThreads, 0, ctx->stream>>>(rows, counts, wide);
+    return scan_exclusive<int64_t>(ctx, pool, wide, rowptr, (size_t)rows + 1);
+}
+
+// dst = transpose of src (src complete except binning); row ids of src's entries in `src_row`
+plx_status transpose_orient(plx_ctx* ctx, const Orient& src, const int32_t* src_row, Orient& dst) {
+    TempPool pool(ctx);
+    dst.rows = src.cols; dst.cols = src.rows; dst.nnz = src.nnz;
+    dst.rowptr = static_cast<int64_t*>(dev_alloc(ctx, sizeof(int64_t) * (dst.rows + 1)));
+    dst.col = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * std::max<int64_t>(1, dst.nnz)));
+    dst.val = static_cast<float*>(dev_alloc(ctx, sizeof(float) * std::max<int64_t>(1, dst.nnz)));
+    if (!dst.rowptr || !dst.col || !dst.val) return PLX_ERR_OOM;
+    unsigned int* colcount = pool.get<unsigned int>(dst.rows + 1);
+    uint64_t* keys = pool.get<uint64_t>(src.nnz);
+    uint64_t* keys_sorted = pool.get<uint64_t>(src.nnz);
+    if (!colcount || !keys || !keys_sorted) return PLX_ERR_OOM;
+    PLX_HIP(ctx, hipMemsetAsync(colcount, 0, sizeof(unsigned int) * (dst.rows + 1), ctx->stream));
+    if (src.nnz > 0) {
+        k_transpose_keys<<<grid_for(src.nnz), kThreads, 0, ctx->stream>>>(src.nnz, src_row, src.col, (uint64_t)src.rows,
+                                                                           keys, colcount);
+        int bits = std::max(1, bit_length((uint64_t)src.cols * (uint64_t)src.rows));
+        size_t bytes = 0;
+        PLX_HIP(ctx, rocprim::radix_sort_pairs(nullptr, bytes, keys, keys_sorted, src.val, dst.val, (size_t)src.nnz, 0,
+                                               bits, ctx->stream));
+        void* tmp = pool.get<char>(bytes);
+        if (!tmp) return PLX_ERR_OOM;
+        PLX_HIP(ctx, rocprim::radix_sort_pairs(tmp, bytes, keys, keys_sorted, src.val, dst.val, (size_t)src.nnz, 0,
+                                               bits, ctx->stream));
+        k_keys_to_cols<<<grid_for(src.nnz), kThreads, 0, ctx->stream>>>(src.nnz, keys_sorted, (uint64_t)src.rows, dst.col);
+    }
+    PLX_TRY(counts_to_rowptr(ctx, pool, colcount, dst.rows, dst.rowptr));
+    PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return PLX_OK;
+}
+
+}  // namespace
+
+plx_status build_bins(plx_ctx* ctx, Orient& o) {
+    TempPool pool(ctx);
+    o.row_order = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * std::max<int64_t>(1, o.rows)));
+    if (!o.row_order) return PLX_ERR_OOM;
+    uint8_t* cls = pool.get<uint8_t>(o.rows);
+    uint8_t* cls_sorted = pool.get<uint8_t>(o.rows);
+    int32_t* ids = pool.get<int32_t>(o.rows);
+    unsigned int* hist = pool.get<unsigned int>(kNumClasses);
+    if (!cls || !cls_sorted || !ids || !hist) return PLX_ERR_OOM;
+    PLX_HIP(ctx, hipMemsetAsync(hist, 0, sizeof(unsigned int) * kNumClasses, ctx->stream));
+    unsigned int h[kNumClasses] = {0};
+    if (o.rows > 0) {
+        k_row_class<<<grid_for(o.rows), kThreads, 0, ctx->stream>>>(o.rows, o.rowptr, cls, ids, hist);
+        size_t bytes = 0;   // stable sort by class: ids stay ascending inside a class
+        PLX_HIP(ctx, rocprim::radix_sort_pairs(nullptr, bytes, cls, cls_sorted, ids, o.row_order, (size_t)o.rows, 0, 6,
+                                               ctx->stream));
+        void* tmp = pool.get<char>(bytes);
+        if (!tmp) return PLX_ERR_OOM;
+        PLX_HIP(ctx, rocprim::radix_sort_pairs(tmp, bytes, cls, cls_sorted, ids, o.row_order, (size_t)o.rows, 0, 6,
+                                               ctx->stream));
+    }
+    PLX_HIP(ctx, hipMemcpyAsync(h, hist, sizeof h, hipMemcpyDeviceToHost, ctx->stream));
+    PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    o.class_off[0] = 0;
+    for (int c = 0; c < kNumClasses; ++c) o.class_off[c + 1] = o.class_off[c] + h[c];
+
+    // long rows -> segments (few of them: done on the host)
+    o.n_long = o.class_off[kNumClasses] - o.class_off[kLongClass];
+    o.n_seg = 0;
+    if (o.n_long > 0) {
+        std::vector<int32_t> rows(o.n_long);
+        PLX_HIP(ctx, hipMemcpy(rows.data(), o.row_order + o.class_off[kLongClass], sizeof(int32_t) * o.n_long,
+                               hipMemcpyDeviceToHost));
+        std::vector<int64_t> lo(o.n_long), hi(o.n_long);
+        {
+            int64_t* dlo = pool.get<int64_t>(o.n_long);
+            int64_t* dhi = pool.get<int64_t>(o.n_long);
+            if (!dlo || !dhi) return PLX_ERR_OOM;
+            k_gather_bounds<<<grid_for(o.n_long), kThreads, 0, ctx->stream>>>(o.n_long, o.row_order + o.class_off[kLongClass],
+                                                                               o.rowptr, dlo, dhi);
+            PLX_HIP(ctx, hipMemcpyAsync(lo.data(), dlo, sizeof(int64_t) * o.n_long, hipMemcpyDeviceToHost, ctx->stream));
+            PLX_HIP(ctx, hipMemcpyAsync(hi.data(), dhi, sizeof(int64_t) * o.n_long, hipMemcpyDeviceToHost, ctx->stream));
+            PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        }
+        std::vector<int32_t> seg0(o.n_long + 1, 0), seg_len;
+        std::vector<int64_t> seg_lo;
+        for (int64_t q = 0; q < o.n_long; ++q) {
+            seg0[q] = (int32_t)seg_lo.size();
+            for (int64_t e = lo[q]; e < hi[q]; e += kSegLen) {
+                seg_lo.push_back(e);
+                seg_len.push_back((int32_t)std::min<int64_t>(kSegLen, hi[q] - e));
+            }
+        }
+        seg0[o.n_long] = (int32_t)seg_lo.size();
+        o.n_seg = (int64_t)seg_lo.size();
+        o.long_row = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * o.n_long));
+        o.long_seg0 = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * (o.n_long + 1)));
+        o.seg_lo = static_cast<int64_t*>(dev_alloc(ctx, sizeof(int64_t) * o.n_seg));
+        o.seg_len = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * o.n_seg));
+        if (!o.long_row || !o.long_seg0 || !o.seg_lo || !o.seg_len) return PLX_ERR_OOM;
+        PLX_HIP(ctx, hipMemcpy(o.long_row, rows.data(), sizeof(int32_t) * o.n_long, hipMemcpyHostToDevice));
+        PLX_HIP(ctx, hipMemcpy(o.long_seg0, seg0.data(), sizeof(int32_t) * (o.n_long + 1), hipMemcpyHostToDevice));
+        PLX_HIP(ctx, hipMemcpy(o.seg_lo, seg_lo.data(), sizeof(int64_t) * o.n_seg, hipMemcpyHostToDevice));
+        PLX_HIP(ctx, hipMemcpy(o.seg_len, seg_len.data(), sizeof(int32_t) * o.n_seg, hipMemcpyHostToDevice));
+    }
+    return PLX_OK;
+}
+
+}  // namespace plx
+
+using namespace plx;
+
+extern "C" {
+
+plx_status plx_build_csr(plx_ctx* ctx, int64_t n, int64_t n_edges, const int64_t* src, const int64_t* dst,
+                         const int64_t* perm_r, const int64_t* perm_c, plx_csr** out) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!out) return fail(ctx, PLX_ERR_INVALID, "out is NULL");
+    *out = nullptr;
+    if (n < 0 || n_edges < 0) return fail(ctx, PLX_ERR_INVALID, "negative size");
+    if (n_edges > 0 && (!src || !dst)) return fail(ctx, PLX_ERR_INVALID, "src or dst is NULL");
+    if (n >= (int64_t(1) << 31)) return fail(ctx, PLX_ERR_UNSUPPORTED, "n = %lld needs 64-bit column ids", (long long)n);
+    const int64_t count = 2 * n_edges + n;
+    if (count >= (int64_t(1) << 31)) return fail(ctx, PLX_ERR_UNSUPPORTED, "more than 2^31-1 candidate entries");
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    PLX_HIP(ctx, hipSetDevice(ctx->device));
+
+    plx_csr* h = new (std::nothrow) plx_csr();
+    if (!h) return fail(ctx, PLX_ERR_OOM, "host allocation failed");
+    auto bail = [&](plx_status s) { plx_csr_destroy(ctx, h); return s; };
+    plx_status st = [&]() -> plx_status {
+        TempPool pool(ctx);
+        hipStream_t s = ctx->stream;
+        int* flags = pool.get<int>(1);
+        if (!flags) return PLX_ERR_OOM;
+        PLX_HIP(ctx, hipMemsetAsync(flags, 0, sizeof(int), s));
+        if (n_edges > 0) k_check_ids<<<grid_for(n_edges), kThreads, 0, s>>>(n, n_edges, src, dst, flags);
+        {
+            TempPool hp(ctx);
+            for (const int64_t* p : {perm_r, perm_c}) {
+                if (!p || n == 0) continue;
+                int* hits = hp.get<int>(n);
+                if (!hits) return PLX_ERR_OOM;
+                PLX_HIP(ctx, hipMemsetAsync(hits, 0, sizeof(int) * n, s));
+                k_mark_perm<<<grid_for(n), kThreads, 0, s>>>(n, p, hits, flags);
+                k_check_hits<<<grid_for(n), kThreads, 0, s>>>(n, hits, flags);
+            }
+            int hf = 0;
+            PLX_HIP(ctx, hipMemcpyAsync(&hf, flags, sizeof(int), hipMemcpyDeviceToHost, s));
+            PLX_HIP(ctx, hipStreamSynchronize(s));
+            if (hf & kFlagBadId) return fail(ctx, PLX_ERR_INVALID, "edge list holds a node id outside [0, n)");
+            if (hf & kFlagBadPerm) return fail(ctx, PLX_ERR_INVALID, "a permutation is not a bijection on [0, n)");
+        }
+        Orient& f = h->o[0];
+        f.rows = f.cols = n;
+        f.rowptr = static_cast<int64_t*>(dev_alloc(ctx, sizeof(int64_t) * (n + 1)));
+        h->deg = static_cast<int64_t*>(dev_alloc(ctx, sizeof(int64_t) * std::max<int64_t>(1, n)));
+        h->n_deg = n;
+        if (!f.rowptr || !h->deg) return PLX_ERR_OOM;
+        int32_t* row = nullptr;
+        if (n == 0) {
+            PLX_HIP(ctx, hipMemsetAsync(f.rowptr, 0, sizeof(int64_t), s));
+            f.col = static_cast<int32_t*>(dev_alloc(ctx, 4));
+            f.val = static_cast<float*>(dev_alloc(ctx, 4));
+            if (!f.col || !f.val) return PLX_ERR_OOM;
+        } else {
+            const uint64_t sentinel = (uint64_t)n * (uint64_t)n;
+            uint64_t* keys = pool.get<uint64_t>(count);
+            uint64_t* sorted = pool.get<uint64_t>(count);
+            if (!keys || !sorted) return PLX_ERR_OOM;
+            k_make_keys<<<grid_for(n_edges + n), kThreads, 0, s>>>(n, n_edges, src, dst, perm_r, perm_c, keys, sentinel);
+            {
+                int bits = bit_length(sentinel);
+                size_t bytes = 0;
+                PLX_HIP(ctx, rocprim::radix_sort_keys(nullptr, bytes, keys, sorted, (size_t)count, 0, bits, s));
+                void* tmp = pool.get<char>(bytes);
+                if (!tmp) return PLX_ERR_OOM;
+                PLX_HIP(ctx, rocprim::radix_sort_keys(tmp, bytes, keys, sorted, (size_t)count, 0, bits, s));
+            }
+            uint32_t* flag = pool.get<uint32_t>(count + 1);
+            uint32_t* pos = pool.get<uint32_t>(count + 1);
+            if (!flag || !pos) return PLX_ERR_OOM;
+            PLX_HIP(ctx, hipMemsetAsync(flag + count, 0, sizeof(uint32_t), s));
+            k_flag_unique<<<grid_for(count), kThreads, 0, s>>>(count, sorted, sentinel, flag);
+            PLX_TRY(scan_exclusive<uint32_t>(ctx, pool, flag, pos, (size_t)count + 1));
+            uint32_t nnz32 = 0;
+            PLX_HIP(ctx, hipMemcpyAsync(&nnz32, pos + count, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+            PLX_HIP(ctx, hipStreamSynchronize(s));
+            f.nnz = nnz32;
+            f.col = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * f.nnz));
+            f.val = static_cast<float*>(dev_alloc(ctx, sizeof(float) * f.nnz));
+            row = pool.get<int32_t>(f.nnz);
+            unsigned int* rowcount = pool.get<unsigned int>(n + 1);
+            int64_t* deg_c = pool.get<int64_t>(n);
+            if (!f.col || !f.val || !row || !rowcount || !deg_c) return PLX_ERR_OOM;
+            PLX_HIP(ctx, hipMemsetAsync(rowcount, 0, sizeof(unsigned int) * (n + 1), s));
+            k_scatter_unique<<<grid_for(count), kThreads, 0, s>>>(count, sorted, flag, pos, (uint64_t)n, row, f.col, rowcount);
+            PLX_TRY(counts_to_rowptr(ctx, pool, rowcount, n, f.rowptr));
+            k_degrees<<<grid_for(n), kThreads, 0, s>>>(n, f.rowptr, perm_r, perm_c, h->deg, deg_c);
+            k_values<<<grid_for(f.nnz), kThreads, 0, s>>>(f.nnz, row, f.col, f.rowptr, deg_c, f.val);
+            PLX_HIP(ctx, hipGetLastError());
+            PLX_TRY(transpose_orient(ctx, f, row, h->o[1]));
+        }
+        if (n == 0) {
+            Orient& b = h->o[1];
+            b.rowptr = static_cast<int64_t*>(dev_alloc(ctx, sizeof(int64_t)));
+            b.col = static_cast<int32_t*>(dev_alloc(ctx, 4));
+            b.val = static_cast<float*>(dev_alloc(ctx, 4));
+            if (!b.rowptr || !b.col || !b.val) return PLX_ERR_OOM;
+            PLX_HIP(ctx, hipMemsetAsync(b.rowptr, 0, sizeof(int64_t), s));
+        }
+        PLX_TRY(build_bins(ctx, h->o[0]));
+        PLX_TRY(build_bins(ctx, h->o[1]));
+        PLX_HIP(ctx, hipStreamSynchronize(s));
+        PLX_HIP(ctx, hipGetLastError());
+        return PLX_OK;
+    }();
+    if (st != PLX_OK) return bail(st);
+    *out = h;
+    return PLX_OK;
+}
+
+plx_status plx_csr_import(plx_ctx* ctx, int64_t m, int64_t k, int64_t nnz, const int64_t* rowptr, const int32_t* col,
+                          const float* val, plx_csr** out) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!out) return fail(ctx, PLX_ERR_INVALID, "out is NULL");
+    *out = nullptr;
+    if (m < 0 || k < 0 || nnz < 0) return fail(ctx, PLX_ERR_INVALID, "negative size");
+    if (!rowptr || (nnz > 0 && (!col || !val))) return fail(ctx, PLX_ERR_INVALID, "rowptr, col or val is NULL");
+    if (m >= (int64_t(1) << 31) || k >= (int64_t(1) << 31) || nnz >= (int64_t(1) << 31))
+        return fail(ctx, PLX_ERR_UNSUPPORTED, "a dimension or the entry count needs more than 31 bits");
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    PLX_HIP(ctx, hipSetDevice(ctx->device));
+
+    plx_csr* h = new (std::nothrow) plx_csr();
+    if (!h) return fail(ctx, PLX_ERR_OOM, "host allocation failed");
+    plx_status st = [&]() -> plx_status {
+        TempPool pool(ctx);
+        hipStream_t s = ctx->stream;
+        Orient& f = h->o[0];
+        f.rows = m; f.cols = k; f.nnz = nnz;
+        f.rowptr = static_cast<int64_t*>(dev_alloc(ctx, sizeof(int64_t) * (m + 1)));
+        f.col = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * std::max<int64_t>(1, nnz)));
+        f.val = static_cast<float*>(dev_alloc(ctx, sizeof(float) * std::max<int64_t>(1, nnz)));
+        int* flags = pool.get<int>(1);
+        int32_t* row = pool.get<int32_t>(nnz);
+        if (!f.rowptr || !f.col || !f.val || !flags || !row) return PLX_ERR_OOM;
+        PLX_HIP(ctx, hipMemsetAsync(flags, 0, sizeof(int), s));
+        k_check_rowptr<<<grid_for(m + 1), kThreads, 0, s>>>(m, nnz, rowptr, flags);
+        int hf = 0;
+        PLX_HIP(ctx, hipMemcpyAsync(&hf, flags, sizeof(int), hipMemcpyDeviceToHost, s));
+        PLX_HIP(ctx, hipStreamSynchronize(s));
+        if (hf) return fail(ctx, PLX_ERR_INVALID, "rowptr is not a non-decreasing array from 0 to nnz");
+        PLX_HIP(ctx, hipMemcpyAsync(f.rowptr, rowptr, sizeof(int64_t) * (m + 1), hipMemcpyDeviceToDevice, s));
+        if (nnz > 0) {
+            PLX_HIP(ctx, hipMemcpyAsync(f.col, col, sizeof(int32_t) * nnz, hipMemcpyDeviceToDevice, s));
+            PLX_HIP(ctx, hipMemcpyAsync(f.val, val, sizeof(float) * nnz, hipMemcpyDeviceToDevice, s));
+            k_expand_rows<<<grid_for(nnz), kThreads, 0, s>>>(m, nnz, f.rowptr, row);
+            k_check_cols<<<grid_for(nnz), kThreads, 0, s>>>(nnz, k, row, f.col, flags);
+            PLX_HIP(ctx, hipMemcpyAsync(&hf, flags, sizeof(int), hipMemcpyDeviceToHost, s));
+            PLX_HIP(ctx, hipStreamSynchronize(s));
+            if (hf) return fail(ctx, PLX_ERR_INVALID, "column ids must lie in [0, k) and ascend strictly inside a row");
+        }
+        PLX_TRY(transpose_orient(ctx, f, row, h->o[1]));
+        PLX_TRY(build_bins(ctx, h->o[0]));
+        PLX_TRY(build_bins(ctx, h->o[1]));
+        PLX_HIP(ctx, hipStreamSynchronize(s));
+        PLX_HIP(ctx, hipGetLastError());
+        return PLX_OK;
+    }();
+    if (st != PLX_OK) { plx_csr_destroy(ctx, h); return st; }
+    *out = h;
+    return PLX_OK;
+}
+
+}  // extern "C"

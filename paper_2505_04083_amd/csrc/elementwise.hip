@@ -1,0 +1,204 @@
+// Element-wise steps of a GCN layer (paper Eq. 2.3 activation, Eq. 2.4 its derivative) and the
+// node-classification loss head (Sec. 2.1: softmax cross-entropy averaged over all nodes).
+// All are streaming kernels bound by HBM bandwidth.
+#include "plx_internal.h"
+
+#include <algorithm>
+
+namespace plx {
+namespace {
+
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float widen(float v) { return v; }
+__device__ __forceinline__ float widen(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+template <typename T> __device__ __forceinline__ T narrow(float f);
+template <> __device__ __forceinline__ float narrow<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16_t narrow<bf16_t>(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// F = max(Z, 0); 2-D indexing so padded leading dimensions are never touched
+template <typename T>
+__global__ __launch_bounds__(256) void k_relu(int64_t rows, int cols, const T* __restrict__ Z, int64_t ldz, T* F,
+                                              int64_t ldf) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= cols) return;
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
+        float z = widen(Z[r * ldz + c]);
+        F[r * ldf + c] = narrow<T>(z > 0.f ? z : 0.f);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_relu_bwd(int64_t rows, int cols, const T* Z, int64_t ldz, const T* dF,
+                                                  int64_t lddf, T* dZ, int64_t lddz) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= cols) return;
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
+        float z = widen(Z[r * ldz + c]);
+        float g = widen(dF[r * lddf + c]);
+        dZ[r * lddz + c] = narrow<T>(z > 0.f ? g : 0.f);
+    }
+}
+
+// contiguous matrices: 4 elements per thread
+template <typename T>
+__global__ __launch_bounds__(256) void k_relu_flat(int64_t count, const T* __restrict__ Z, T* F) {
+    int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i + 3 < count) {
+        T z[4];
+        if constexpr (sizeof(T) == 4) *reinterpret_cast<uint4*>(z) = *reinterpret_cast<const uint4*>(Z + i);
+        else *reinterpret_cast<uint2*>(z) = *reinterpret_cast<const uint2*>(Z + i);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) { float v = widen(z[t]); z[t] = narrow<T>(v > 0.f ? v : 0.f); }
+        if constexpr (sizeof(T) == 4) *reinterpret_cast<uint4*>(F + i) = *reinterpret_cast<uint4*>(z);
+        else *reinterpret_cast<uint2*>(F + i) = *reinterpret_cast<uint2*>(z);
+    } else {
+        for (; i < count; ++i) { float v = widen(Z[i]); F[i] = narrow<T>(v > 0.f ? v : 0.f); }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_relu_bwd_flat(int64_t count, const T* Z, const T* dF, T* dZ) {
+    int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i + 3 < count) {
+        T z[4], g[4];
+        if constexpr (sizeof(T) == 4) {
+            *reinterpret_cast<uint4*>(z) = *reinterpret_cast<const uint4*>(Z + i);
+            *reinterpret_cast<uint4*>(g) = *reinterpret_cast<const uint4*>(dF + i);
+        } else {
+            *reinterpret_cast<uint2*>(z) = *reinterpret_cast<const uint2*>(Z + i);
+            *reinterpret_cast<uint2*>(g) = *reinterpret_cast<const uint2*>(dF + i);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) g[t] = widen(z[t]) > 0.f ? g[t] : narrow<T>(0.f);
+        if constexpr (sizeof(T) == 4) *reinterpret_cast<uint4*>(dZ + i) = *reinterpret_cast<uint4*>(g);
+        else *reinterpret_cast<uint2*>(dZ + i) = *reinterpret_cast<uint2*>(g);
+    } else {
+        for (; i < count; ++i) dZ[i] = widen(Z[i]) > 0.f ? dF[i] : narrow<T>(0.f);
+    }
+}
+
+// one thread per node: row max, sum of exponentials, gradient and the row's loss term
+template <typename T>
+__global__ __launch_bounds__(256) void k_softmax_ce(int64_t n, int c, const T* __restrict__ Z, int64_t ldz,
+                                                    const int64_t* __restrict__ y, T* __restrict__ dZ, int64_t lddz,
+                                                    float* __restrict__ row_loss, float inv_n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const T* z = Z + i * ldz;
+    float mx = widen(z[0]);
+    for (int j = 1; j < c; ++j) mx = fmaxf(mx, widen(z[j]));
+    float sum = 0.f;
+    for (int j = 0; j < c; ++j) sum += expf(widen(z[j]) - mx);
+    const float inv = 1.f / sum;
+    int64_t label = y[i];
+    label = label < 0 ? 0 : (label >= c ? c - 1 : label);   // out-of-range labels are clamped
+    T* g = dZ + i * lddz;
+    float zl = 0.f;
+    for (int j = 0; j < c; ++j) {
+        const float zj = widen(z[j]);
+        if (j == label) zl = zj;
+        g[j] = narrow<T>((expf(zj - mx) * inv - (j == label ? 1.f : 0.f)) * inv_n);
+    }
+    row_loss[i] = -(zl - mx - logf(sum));
+}
+
+// fixed-order sum: slot g*256*stride receives the sum of live slots (g*256 + t)*stride
+__global__ __launch_bounds__(256) void k_sum_level(float* v, int64_t n_live, int64_t stride, float* out, float scale) {
+    const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g * 256 >= n_live) return;
+    float s = 0.f;
+    for (int t = 0; t < 256; ++t) {
+        const int64_t slot = g * 256 + t;
+        if (slot >= n_live) break;
+        s += v[slot * stride];
+    }
+    if (out) *out = s * scale;
+    else v[g * 256 * stride] = s;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+dim3 grid2d(int64_t rows, int64_t cols) {
+    unsigned gx = (unsigned)ceil_div(cols, 256);
+    unsigned gy = (unsigned)std::min<int64_t>(rows, std::max<int64_t>(1, 65535));
+    return dim3(gx, gy);
+}
+
+template <typename T>
+plx_status relu_t(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, void* F, int64_t ldf) {
+    hipStream_t s = ctx->stream;
+    if (ldz == cols && ldf == cols && aligned16(Z) && aligned16(F)) {
+        int64_t count = rows * cols;
+        k_relu_flat<T><<<dim3((unsigned)ceil_div(ceil_div(count, 4), 256)), 256, 0, s>>>(count, (const T*)Z, (T*)F);
+    } else {
+        k_relu<T><<<grid2d(rows, cols), 256, 0, s>>>(rows, (int)cols, (const T*)Z, ldz, (T*)F, ldf);
+    }
+    PLX_HIP(ctx, hipGetLastError());
+    return PLX_OK;
+}
+
+template <typename T>
+plx_status relu_bwd_t(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, const void* dF,
+                      int64_t lddf, void* dZ, int64_t lddz) {
+    hipStream_t s = ctx->stream;
+    if (ldz == cols && lddf == cols && lddz == cols && aligned16(Z) && aligned16(dF) && aligned16(dZ)) {
+        int64_t count = rows * cols;
+        k_relu_bwd_flat<T><<<dim3((unsigned)ceil_div(ceil_div(count, 4), 256)), 256, 0, s>>>(count, (const T*)Z,
+                                                                                           (const T*)dF, (T*)dZ);
+    } else {
+        k_relu_bwd<T><<<grid2d(rows, cols), 256, 0, s>>>(rows, (int)cols, (const T*)Z, ldz, (const T*)dF, lddf, (T*)dZ, lddz);
+    }
+    PLX_HIP(ctx, hipGetLastError());
+    return PLX_OK;
+}
+
+}  // namespace
+
+plx_status launch_relu(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, void* F, int64_t ldf,
+                       plx_dtype dtype) {
+    if (cols >= (int64_t(1) << 24)) return fail(ctx, PLX_ERR_UNSUPPORTED, "too many columns");
+    return dtype == PLX_F32 ? relu_t<float>(ctx, rows, cols, Z, ldz, F, ldf) : relu_t<bf16_t>(ctx, rows, cols, Z, ldz, F, ldf);
+}
+
+plx_status launch_relu_bwd(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, const void* dF,
+                           int64_t lddf, void* dZ, int64_t lddz, plx_dtype dtype) {
+    if (cols >= (int64_t(1) << 24)) return fail(ctx, PLX_ERR_UNSUPPORTED, "too many columns");
+    return dtype == PLX_F32 ? relu_bwd_t<float>(ctx, rows, cols, Z, ldz, dF, lddf, dZ, lddz)
+                            : relu_bwd_t<bf16_t>(ctx, rows, cols, Z, ldz, dF, lddf, dZ, lddz);
+}
+
+plx_status launch_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, int64_t ldz, const int64_t* y, void* dZ,
+                             int64_t lddz, float* row_loss, float* loss, plx_dtype dtype) {
+    hipStream_t s = ctx->stream;
+    if (n == 0) {
+        if (loss) PLX_HIP(ctx, hipMemsetAsync(loss, 0, sizeof(float), s));
+        return PLX_OK;
+    }
+    const float inv_n = (float)(1.0 / (double)n);
+    dim3 grid((unsigned)ceil_div(n, 256));
+    if (dtype == PLX_F32)
+        k_softmax_ce<float><<<grid, 256, 0, s>>>(n, (int)c, (const float*)Z, ldz, y, (float*)dZ, lddz, row_loss, inv_n);
+    else
+        k_softmax_ce<bf16_t><<<grid, 256, 0, s>>>(n, (int)c, (const bf16_t*)Z, ldz, y, (bf16_t*)dZ, lddz, row_loss, inv_n);
+    if (loss) {
+        int64_t live = n, stride = 1;
+        while (true) {
+            const int64_t groups = ceil_div(live, 256);
+            const bool last = groups == 1;
+            k_sum_level<<<dim3((unsigned)ceil_div(groups, 256)), 256, 0, s>>>(row_loss, live, stride, last ? loss : nullptr, inv_n);
+            if (last) break;
+            live = groups;
+            stride *= 256;
+        }
+    }
+    PLX_HIP(ctx, hipGetLastError());
+    return PLX_OK;
+}
+
+}  // namespace plx

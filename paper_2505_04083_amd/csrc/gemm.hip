@@ -1,0 +1,299 @@
+// Dense products of a GCN layer on the matrix cores (paper Eq. 2.2 Q = H W, Eq. 2.6
+// dH = dQ W^T, Eq. 2.5 dW = H^T dQ).  One operand is always tall and skinny (N_nodes x <=602),
+// the other a small weight matrix, so these products stream the tall operand once from HBM
+// and are bound by that stream; MFMA does the arithmetic so the vector ALUs stay free.
+//
+// fp32 path: v_mfma_f32_32x32x2_f32.  Operand layout of that instruction for lane l:
+//   a = A[i = l % 32][k = l / 32],  b = B[k = l / 32][j = l % 32],
+//   acc[r] = C[i = 8*(r/4) + 4*(l/32) + r%4][j = l % 32],  r = 0..15.
+// A workgroup of 4 wavefronts owns a tile of TMB x TNB such 32x32 blocks; block q of the tile
+// (row-major) belongs to wavefront q % 4.  Tiles of the operands are staged through LDS with
+// 128-bit global loads.
+//
+// The transposed product (reduction over the node dimension) is split over row chunks; each
+// workgroup writes its partial tile and a second kernel adds the partials in a fixed order, so
+// the result does not depend on scheduling.
+#include "plx_internal.h"
+
+#include <algorithm>
+
+namespace plx {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kBK = 32;   // depth of one staged slab
+
+__device__ __forceinline__ floatx16 mfma32(float a, float b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+// ---- C[M x N] = A[M x K] * B  (B is K x N, or N x K when BT) -------------------------------------
+template <int TNB, bool BT>
+__global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const float* __restrict__ A, int64_t lda,
+                                                  const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
+                                                  int64_t ldc, int vec_a) {
+    constexpr int TMB = 4;
+    constexpr int BM = 32 * TMB, BN = 32 * TNB;
+    constexpr int NBLK = (TMB * TNB + 3) / 4;         // blocks per wavefront
+    __shared__ float As[BM][kBK + 1];
+    __shared__ float Bs[kBK][BN + 1];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+
+    floatx16 acc[NBLK];
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+    for (int k0 = 0; k0 < K; k0 += kBK) {
+#pragma unroll
+        for (int i = 0; i < (BM * kBK / 4) / 256; ++i) {
+            const int f = tid + 256 * i, r = f >> 3, q = f & 7;
+            const int64_t gr = m0 + r;
+            const int gk = k0 + 4 * q;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gr < M) {
+                const float* p = A + gr * lda + gk;
+                if (vec_a && gk + 3 < K) {
+                    v = *reinterpret_cast<const float4*>(p);
+                } else {
+                    if (gk < K) v.x = p[0];
+                    if (gk + 1 < K) v.y = p[1];
+                    if (gk + 2 < K) v.z = p[2];
+                    if (gk + 3 < K) v.w = p[3];
+                }
+            }
+            As[r][4 * q + 0] = v.x; As[r][4 * q + 1] = v.y; As[r][4 * q + 2] = v.z; As[r][4 * q + 3] = v.w;
+        }
+        for (int f = tid; f < kBK * BN; f += 256) {
+            int kk, n;
+            if (BT) { n = f / kBK; kk = f % kBK; } else { kk = f / BN; n = f % BN; }
+            const int gk = k0 + kk, gn = n0 + n;
+            float v = 0.f;
+            if (gk < K && gn < N) v = BT ? B[(int64_t)gn * ldb + gk] : B[(int64_t)gk * ldb + gn];
+            Bs[kk][n] = v;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int kk = 0; kk < kBK; kk += 2) {
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) {
+                const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
+                if (q < TMB * TNB) {
+                    const float a = As[32 * bi + l32][kk + lh];
+                    const float b = Bs[kk + lh][32 * bj + l32];
+                    acc[t] = mfma32(a, b, acc[t]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t) {
+        const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
+        if (q >= TMB * TNB) continue;
+        const int gn = n0 + 32 * bj + l32;
+        if (gn >= N) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t gr = m0 + 32 * bi + 8 * (r / 4) + 4 * lh + (r % 4);
+            if (gr < M) C[gr * ldc + gn] = acc[t][r];
+        }
+    }
+}
+
+// ---- partial[chunk][M x N] = A[rows of chunk, M]^T * B[rows of chunk, N] ---------------------------
+template <int TMB, int TNB>
+__global__ __launch_bounds__(256) void k_gemm_tn_f32(int64_t R, int M, int N, const float* __restrict__ A, int64_t lda,
+                                                     const float* __restrict__ B, int64_t ldb,
+                                                     float* __restrict__ part, int64_t rows_per_chunk, int vec_a,
+                                                     int vec_b) {
+    constexpr int BM = 32 * TMB, BN = 32 * TNB;
+    constexpr int NBLK = (TMB * TNB + 3) / 4;
+    __shared__ __align__(16) float As[kBK][BM + 4];
+    __shared__ __align__(16) float Bs[kBK][BN + 4];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.z * BN;
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_chunk;
+    const int64_t r_end = (r_begin + rows_per_chunk < R) ? r_begin + rows_per_chunk : R;
+
+    floatx16 acc[NBLK];
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += kBK) {
+        for (int f = tid; f < kBK * BM / 4; f += 256) {
+            const int kk = f / (BM / 4), q = f % (BM / 4);
+            const int64_t gr = r0 + kk;
+            const int gm = m0 + 4 * q;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gr < r_end) {
+                const float* p = A + gr * lda + gm;
+                if (vec_a && gm + 3 < M) {
+                    v = *reinterpret_cast<const float4*>(p);
+                } else {
+                    if (gm < M) v.x = p[0];
+                    if (gm + 1 < M) v.y = p[1];
+                    if (gm + 2 < M) v.z = p[2];
+                    if (gm + 3 < M) v.w = p[3];
+                }
+            }
+            *reinterpret_cast<float4*>(&As[kk][4 * q]) = v;
+        }
+        for (int f = tid; f < kBK * BN / 4; f += 256) {
+            const int kk = f / (BN / 4), q = f % (BN / 4);
+            const int64_t gr = r0 + kk;
+            const int gn = n0 + 4 * q;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gr < r_end) {
+                const float* p = B + gr * ldb + gn;
+                if (vec_b && gn + 3 < N) {
+                    v = *reinterpret_cast<const float4*>(p);
+                } else {
+                    if (gn < N) v.x = p[0];
+                    if (gn + 1 < N) v.y = p[1];
+                    if (gn + 2 < N) v.z = p[2];
+                    if (gn + 3 < N) v.w = p[3];
+                }
+            }
+            *reinterpret_cast<float4*>(&Bs[kk][4 * q]) = v;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int kk = 0; kk < kBK; kk += 2) {
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) {
+                const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
+                if (q < TMB * TNB) {
+                    const float a = As[kk + lh][32 * bi + l32];
+                    const float b = Bs[kk + lh][32 * bj + l32];
+                    acc[t] = mfma32(a, b, acc[t]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    float* out = part + (int64_t)blockIdx.x * M * N;
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t) {
+        const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
+        if (q >= TMB * TNB) continue;
+        const int gn = n0 + 32 * bj + l32;
+        if (gn >= N) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int gm = m0 + 32 * bi + 8 * (r / 4) + 4 * lh + (r % 4);
+            if (gm < M) out[(int64_t)gm * N + gn] = acc[t][r];
+        }
+    }
+}
+
+// One level of the fixed-order sum of partial tiles: slot g*kFan*stride receives the sum of the
+// live slots (g*kFan + t)*stride, t = 0..kFan-1.  With `final_out` the sums go to C instead.
+constexpr int kFan = 32;
+__global__ __launch_bounds__(256) void k_reduce_partials(float* __restrict__ part, int64_t elems, int64_t n_live,
+                                                         int64_t stride, float* __restrict__ C, int N, int64_t ldc) {
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t g = blockIdx.y;
+    if (e >= elems) return;
+    float s = 0.f;
+    for (int t = 0; t < kFan; ++t) {
+        const int64_t slot = g * kFan + t;
+        if (slot >= n_live) break;
+        s += part[slot * stride * elems + e];
+    }
+    if (C) C[(e / N) * ldc + (e % N)] = s;
+    else part[g * kFan * stride * elems + e] = s;
+}
+
+int64_t tn_rows_per_chunk(int64_t R, int64_t M, int64_t N) {
+    const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 128);
+    const int64_t want_chunks = std::max<int64_t>(1, 2048 / tiles);
+    int64_t rows = std::max<int64_t>(512, ceil_div(R, want_chunks));
+    return ceil_div(rows, kBK) * kBK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+size_t gemm_tn_workspace(int64_t R, int64_t M, int64_t N) {
+    const int64_t chunks = std::max<int64_t>(1, ceil_div(R, tn_rows_per_chunk(R, M, N)));
+    return (size_t)chunks * (size_t)M * (size_t)N * sizeof(float);
+}
+
+plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                       const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype) {
+    if (dtype != PLX_F32) return fail(ctx, PLX_ERR_UNSUPPORTED, "bf16 dense products are not built yet");
+    if (N >= (int64_t(1) << 20) || K >= (int64_t(1) << 30)) return fail(ctx, PLX_ERR_UNSUPPORTED, "N or K too large");
+    const float* a = static_cast<const float*>(A);
+    float* c = static_cast<float*>(C);
+    const int vec_a = aligned16(A) && lda % 4 == 0;
+    const int tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
+    dim3 grid((unsigned)ceil_div(M, 128), (unsigned)ceil_div(N, 32 * tnb));
+    hipStream_t s = ctx->stream;
+#define PLX_GEMM_CASE(T, BTV) \
+    k_gemm_f32<T, BTV><<<grid, 256, 0, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, vec_a)
+    if (bt) {
+        if (tnb == 1) PLX_GEMM_CASE(1, true); else if (tnb == 2) PLX_GEMM_CASE(2, true); else PLX_GEMM_CASE(4, true);
+    } else {
+        if (tnb == 1) PLX_GEMM_CASE(1, false); else if (tnb == 2) PLX_GEMM_CASE(2, false); else PLX_GEMM_CASE(4, false);
+    }
+#undef PLX_GEMM_CASE
+    PLX_HIP(ctx, hipGetLastError());
+    return PLX_OK;
+}
+
+plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const void* A, int64_t lda, const void* B,
+                          int64_t ldb, float* C, int64_t ldc, plx_dtype dtype, void* ws, size_t ws_bytes) {
+    if (dtype != PLX_F32) return fail(ctx, PLX_ERR_UNSUPPORTED, "bf16 dense products are not built yet");
+    if (M >= (int64_t(1) << 20) || N >= (int64_t(1) << 20)) return fail(ctx, PLX_ERR_UNSUPPORTED, "M or N too large");
+    if (ws_bytes < gemm_tn_workspace(R, M, N)) return fail(ctx, PLX_ERR_SHAPE, "workspace too small");
+    const float* a = static_cast<const float*>(A);
+    const float* b = static_cast<const float*>(B);
+    float* part = static_cast<float*>(ws);
+    const int64_t rpc = tn_rows_per_chunk(R, M, N);
+    const int64_t chunks = std::max<int64_t>(1, ceil_div(R, rpc));
+    const int vec_a = aligned16(A) && lda % 4 == 0, vec_b = aligned16(B) && ldb % 4 == 0;
+    const int tmb = M <= 32 ? 1 : (M <= 64 ? 2 : 4);
+    const int tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
+    dim3 grid((unsigned)chunks, (unsigned)ceil_div(M, 32 * tmb), (unsigned)ceil_div(N, 32 * tnb));
+    hipStream_t s = ctx->stream;
+#define PLX_TN_CASE(TM, TN) \
+    k_gemm_tn_f32<TM, TN><<<grid, 256, 0, s>>>(R, (int)M, (int)N, a, lda, b, ldb, part, rpc, vec_a, vec_b)
+    switch (tmb * 10 + tnb) {
+        case 11: PLX_TN_CASE(1, 1); break;
+        case 12: PLX_TN_CASE(1, 2); break;
+        case 14: PLX_TN_CASE(1, 4); break;
+        case 21: PLX_TN_CASE(2, 1); break;
+        case 22: PLX_TN_CASE(2, 2); break;
+        case 24: PLX_TN_CASE(2, 4); break;
+        case 41: PLX_TN_CASE(4, 1); break;
+        case 42: PLX_TN_CASE(4, 2); break;
+        default: PLX_TN_CASE(4, 4); break;
+    }
+#undef PLX_TN_CASE
+    // fixed-order tree over the chunk partials
+    const int64_t elems = M * N;
+    int64_t live = chunks, stride = 1;
+    while (true) {
+        const int64_t groups = ceil_div(live, kFan);
+        const bool last = groups == 1;
+        dim3 rgrid((unsigned)ceil_div(elems, 256), (unsigned)groups);
+        k_reduce_partials<<<rgrid, 256, 0, s>>>(part, elems, live, stride, last ? C : nullptr, (int)N, ldc);
+        if (last) break;
+        live = groups;
+        stride *= kFan;
+    }
+    PLX_HIP(ctx, hipGetLastError());
+    return PLX_OK;
+}
+
+}  // namespace plx

@@ -1,0 +1,417 @@
+// C-ABI entry points: argument validation, context, handle bookkeeping and the composition
+// of one GCN layer (paper Sec. 2.1, Eq. 2.1-2.7) out of the kernels in the other files.
+#include "plx_internal.h"
+
+#include <cstring>
+
+namespace plx {
+
+plx_status fail(plx_ctx* ctx, plx_status s, const char* fmt, ...) {
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        ctx->err = buf;
+    }
+    return s;
+}
+
+void* dev_alloc(plx_ctx* ctx, size_t bytes) {
+    if (bytes == 0) bytes = 256;
+    void* p = nullptr;
+    if (ctx->alloc) {
+        p = ctx->alloc(bytes, ctx->user);
+    } else if (hipMalloc(&p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        p = nullptr;
+    }
+    if (!p) fail(ctx, PLX_ERR_OOM, "device allocation of %zu bytes failed", bytes);
+    return p;
+}
+
+void dev_free(plx_ctx* ctx, void* p) {
+    if (!p) return;
+    if (ctx->release) ctx->release(p, ctx->user);
+    else (void)hipFree(p);
+}
+
+plx_status ensure_scratch(plx_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->scratch_bytes) return PLX_OK;
+    if (ctx->scratch) {
+        // work queued earlier may still read the old buffer
+        PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        dev_free(ctx, ctx->scratch);
+        ctx->scratch = nullptr;
+        ctx->scratch_bytes = 0;
+    }
+    size_t want = align256(bytes + bytes / 4);
+    ctx->scratch = dev_alloc(ctx, want);
+    if (!ctx->scratch) return PLX_ERR_OOM;
+    ctx->scratch_bytes = want;
+    return PLX_OK;
+}
+
+void free_orient(plx_ctx* ctx, Orient& o) {
+    dev_free(ctx, o.rowptr); dev_free(ctx, o.col); dev_free(ctx, o.val); dev_free(ctx, o.row_order);
+    dev_free(ctx, o.long_row); dev_free(ctx, o.long_seg0); dev_free(ctx, o.seg_lo); dev_free(ctx, o.seg_len);
+    o = Orient();
+}
+
+static bool dtype_ok(plx_dtype t) { return t == PLX_F32 || t == PLX_BF16; }
+
+}  // namespace plx
+
+using namespace plx;
+
+extern "C" {
+
+const char* plx_status_string(plx_status s) {
+    switch (s) {
+        case PLX_OK: return "ok";
+        case PLX_ERR_INVALID: return "invalid argument";
+        case PLX_ERR_SHAPE: return "shape mismatch";
+        case PLX_ERR_UNSUPPORTED: return "unsupported";
+        case PLX_ERR_OOM: return "out of device memory";
+        case PLX_ERR_DEVICE: return "device error";
+        case PLX_ERR_INTERNAL: return "internal error";
+    }
+    return "unknown status";
+}
+
+plx_status plx_ctx_create(int device, void* hip_stream, plx_alloc_fn alloc, plx_free_fn release, void* user,
+                          plx_ctx** out) {
+    if (!out) return PLX_ERR_INVALID;
+    *out = nullptr;
+    if (device < -1) return PLX_ERR_INVALID;
+    if ((alloc == nullptr) != (release == nullptr)) return PLX_ERR_INVALID;
+    plx_ctx* c = new (std::nothrow) plx_ctx();
+    if (!c) return PLX_ERR_OOM;
+    c->device = device;
+    c->dry = device == -1;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->alloc = alloc; c->release = release; c->user = user;
+    if (!c->dry) {
+        int count = 0;
+        if (hipGetDeviceCount(&count) != hipSuccess || device >= count) {
+            (void)hipGetLastError();
+            delete c;
+            return PLX_ERR_DEVICE;
+        }
+        if (hipSetDevice(device) != hipSuccess) {
+            (void)hipGetLastError();
+            delete c;
+            return PLX_ERR_DEVICE;
+        }
+    }
+    *out = c;
+    return PLX_OK;
+}
+
+void plx_ctx_destroy(plx_ctx* ctx) {
+    if (!ctx) return;
+    if (ctx->scratch) {
+        (void)hipStreamSynchronize(ctx->stream);
+        dev_free(ctx, ctx->scratch);
+    }
+    delete ctx;
+}
+
+const char* plx_last_error(const plx_ctx* ctx) { return ctx ? ctx->err.c_str() : "no context"; }
+
+plx_status plx_sync(plx_ctx* ctx) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return PLX_OK;
+}
+
+plx_status plx_csr_dims(const plx_csr* csr, int64_t* m, int64_t* k, int64_t* nnz) {
+    if (!csr) return PLX_ERR_INVALID;
+    if (m) *m = csr->o[0].rows;
+    if (k) *k = csr->o[0].cols;
+    if (nnz) *nnz = csr->o[0].nnz;
+    return PLX_OK;
+}
+
+plx_status plx_csr_export(plx_ctx* ctx, const plx_csr* csr, int transposed, int64_t* rowptr, int32_t* col,
+                          float* val, int64_t* deg) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!csr) return fail(ctx, PLX_ERR_INVALID, "csr is NULL");
+    if (deg && !csr->deg) return fail(ctx, PLX_ERR_INVALID, "this handle holds no degrees (made by plx_csr_import)");
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    const Orient& o = csr->o[transposed ? 1 : 0];
+    if (rowptr) PLX_HIP(ctx, hipMemcpyAsync(rowptr, o.rowptr, sizeof(int64_t) * (o.rows + 1), hipMemcpyDeviceToDevice, ctx->stream));
+    if (col && o.nnz) PLX_HIP(ctx, hipMemcpyAsync(col, o.col, sizeof(int32_t) * o.nnz, hipMemcpyDeviceToDevice, ctx->stream));
+    if (val && o.nnz) PLX_HIP(ctx, hipMemcpyAsync(val, o.val, sizeof(float) * o.nnz, hipMemcpyDeviceToDevice, ctx->stream));
+    if (deg && csr->n_deg) PLX_HIP(ctx, hipMemcpyAsync(deg, csr->deg, sizeof(int64_t) * csr->n_deg, hipMemcpyDeviceToDevice, ctx->stream));
+    PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return PLX_OK;
+}
+
+void plx_csr_destroy(plx_ctx* ctx, plx_csr* csr) {
+    if (!ctx || !csr) return;
+    if (!ctx->dry) (void)hipStreamSynchronize(ctx->stream);
+    free_orient(ctx, csr->o[0]);
+    free_orient(ctx, csr->o[1]);
+    dev_free(ctx, csr->deg);
+    delete csr;
+}
+
+plx_status plx_csr_bins(const plx_csr* csr, int transposed, int64_t d, plx_dtype dtype, int64_t* rows_subwave,
+                        int64_t* rows_wave, int64_t* rows_split) {
+    if (!csr || d <= 0 || !dtype_ok(dtype)) return PLX_ERR_INVALID;
+    const Orient& o = csr->o[transposed ? 1 : 0];
+    if (rows_subwave) *rows_subwave = o.class_off[kSubwaveMaxClass + 1];
+    if (rows_wave) *rows_wave = o.class_off[kLongClass] - o.class_off[kSubwaveMaxClass + 1];
+    if (rows_split) *rows_split = o.class_off[kNumClasses] - o.class_off[kLongClass];
+    return PLX_OK;
+}
+
+// ---- sparse x dense ---------------------------------------------------------------------------
+
+static plx_status spmm_entry(plx_ctx* ctx, const plx_csr* csr, int t, const void* X, int64_t ldx, void* Y,
+                             int64_t ldy, int64_t d, plx_dtype dtype) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!csr) return fail(ctx, PLX_ERR_INVALID, "csr is NULL");
+    if (!dtype_ok(dtype)) return fail(ctx, PLX_ERR_INVALID, "unknown dtype %d", (int)dtype);
+    if (d < 0) return fail(ctx, PLX_ERR_INVALID, "d = %lld is negative", (long long)d);
+    const Orient& o = csr->o[t];
+    if (d > 0 && ((o.cols > 0 && !X) || (o.rows > 0 && !Y))) return fail(ctx, PLX_ERR_INVALID, "X or Y is NULL");
+    if (ldx < d || ldy < d) return fail(ctx, PLX_ERR_SHAPE, "leading dimension (%lld, %lld) smaller than d = %lld",
+                                        (long long)ldx, (long long)ldy, (long long)d);
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    if (d == 0 || o.rows == 0) return PLX_OK;
+    return launch_spmm(ctx, o, X, ldx, Y, ldy, d, dtype);
+}
+
+plx_status plx_spmm(plx_ctx* ctx, const plx_csr* csr, const void* X, int64_t ldx, void* Y, int64_t ldy, int64_t d,
+                    plx_dtype dtype) {
+    return spmm_entry(ctx, csr, 0, X, ldx, Y, ldy, d, dtype);
+}
+
+plx_status plx_spmm_t(plx_ctx* ctx, const plx_csr* csr, const void* X, int64_t ldx, void* Y, int64_t ldy, int64_t d,
+                      plx_dtype dtype) {
+    return spmm_entry(ctx, csr, 1, X, ldx, Y, ldy, d, dtype);
+}
+
+// ---- dense x dense ----------------------------------------------------------------------------
+
+static plx_status gemm_entry(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                             const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!dtype_ok(dtype)) return fail(ctx, PLX_ERR_INVALID, "unknown dtype %d", (int)dtype);
+    if (M < 0 || N < 0 || K < 0) return fail(ctx, PLX_ERR_INVALID, "negative dimension");
+    if (M > 0 && N > 0 && (!C || (K > 0 && (!A || !B)))) return fail(ctx, PLX_ERR_INVALID, "A, B or C is NULL");
+    if (lda < K || ldc < N || ldb < (bt ? K : N)) return fail(ctx, PLX_ERR_SHAPE, "leading dimension too small");
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    if (M == 0 || N == 0) return PLX_OK;
+    return launch_gemm(ctx, bt, M, N, K, A, lda, B, ldb, C, ldc, dtype);
+}
+
+plx_status plx_gemm_nn(plx_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const float* B,
+                       int64_t ldb, void* C, int64_t ldc, plx_dtype dtype) {
+    return gemm_entry(ctx, false, M, N, K, A, lda, B, ldb, C, ldc, dtype);
+}
+
+plx_status plx_gemm_nt(plx_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const float* B,
+                       int64_t ldb, void* C, int64_t ldc, plx_dtype dtype) {
+    return gemm_entry(ctx, true, M, N, K, A, lda, B, ldb, C, ldc, dtype);
+}
+
+size_t plx_gemm_tn_workspace(int64_t R, int64_t M, int64_t N) {
+    if (R < 0 || M <= 0 || N <= 0) return 0;
+    return gemm_tn_workspace(R, M, N);
+}
+
+plx_status plx_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const void* A, int64_t lda, const void* B,
+                       int64_t ldb, float* C, int64_t ldc, plx_dtype dtype, void* ws, size_t ws_bytes) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!dtype_ok(dtype)) return fail(ctx, PLX_ERR_INVALID, "unknown dtype %d", (int)dtype);
+    if (R < 0 || M < 0 || N < 0) return fail(ctx, PLX_ERR_INVALID, "negative dimension");
+    if (M > 0 && N > 0 && (!C || (R > 0 && (!A || !B)))) return fail(ctx, PLX_ERR_INVALID, "A, B or C is NULL");
+    if (lda < M || ldb < N || ldc < N) return fail(ctx, PLX_ERR_SHAPE, "leading dimension too small");
+    if (M > 0 && N > 0 && (ws_bytes < gemm_tn_workspace(R, M, N) || !ws))
+        return fail(ctx, PLX_ERR_SHAPE, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes,
+                    gemm_tn_workspace(R, M, N));
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    if (M == 0 || N == 0) return PLX_OK;
+    return launch_gemm_tn(ctx, R, M, N, A, lda, B, ldb, C, ldc, dtype, ws, ws_bytes);
+}
+
+// ---- element-wise ------------------------------------------------------------------------------
+
+plx_status plx_relu(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, void* F, int64_t ldf,
+                    plx_dtype dtype) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!dtype_ok(dtype)) return fail(ctx, PLX_ERR_INVALID, "unknown dtype %d", (int)dtype);
+    if (rows < 0 || cols < 0) return fail(ctx, PLX_ERR_INVALID, "negative dimension");
+    if (rows > 0 && cols > 0 && (!Z || !F)) return fail(ctx, PLX_ERR_INVALID, "Z or F is NULL");
+    if (ldz < cols || ldf < cols) return fail(ctx, PLX_ERR_SHAPE, "leading dimension too small");
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    if (rows == 0 || cols == 0) return PLX_OK;
+    return launch_relu(ctx, rows, cols, Z, ldz, F, ldf, dtype);
+}
+
+plx_status plx_relu_bwd(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, const void* dF,
+                        int64_t lddf, void* dZ, int64_t lddz, plx_dtype dtype) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!dtype_ok(dtype)) return fail(ctx, PLX_ERR_INVALID, "unknown dtype %d", (int)dtype);
+    if (rows < 0 || cols < 0) return fail(ctx, PLX_ERR_INVALID, "negative dimension");
+    if (rows > 0 && cols > 0 && (!Z || !dF || !dZ)) return fail(ctx, PLX_ERR_INVALID, "Z, dF or dZ is NULL");
+    if (ldz < cols || lddf < cols || lddz < cols) return fail(ctx, PLX_ERR_SHAPE, "leading dimension too small");
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    if (rows == 0 || cols == 0) return PLX_OK;
+    return launch_relu_bwd(ctx, rows, cols, Z, ldz, dF, lddf, dZ, lddz, dtype);
+}
+
+plx_status plx_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, int64_t ldz, const int64_t* y, void* dZ,
+                          int64_t lddz, float* row_loss, float* loss, plx_dtype dtype) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!dtype_ok(dtype)) return fail(ctx, PLX_ERR_INVALID, "unknown dtype %d", (int)dtype);
+    if (n < 0 || c <= 0) return fail(ctx, PLX_ERR_INVALID, "n must be >= 0 and c > 0");
+    if (n > 0 && (!Z || !y || !dZ || !row_loss)) return fail(ctx, PLX_ERR_INVALID, "Z, y, dZ or row_loss is NULL");
+    if (ldz < c || lddz < c) return fail(ctx, PLX_ERR_SHAPE, "leading dimension too small");
+    if (c > 1024) return fail(ctx, PLX_ERR_UNSUPPORTED, "more than 1024 classes");
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    return launch_softmax_ce(ctx, n, c, Z, ldz, y, dZ, lddz, row_loss, loss, dtype);
+}
+
+// ---- one GCN layer ------------------------------------------------------------------------------
+
+static plx_order resolve_order(plx_order order, int64_t din, int64_t dout) {
+    if (order == PLX_ORDER_AUTO) return din < dout ? PLX_ORDER_AGG_FIRST : PLX_ORDER_COMBINE_FIRST;
+    return order;
+}
+
+// Workspace layout (each region 256-byte aligned):
+//   COMBINE_FIRST: T / G  [ka x dout]   | dZ [ma x dout] (if act)  | dW partial sums
+//   AGG_FIRST    : dS     [ma x din]    | dZ [ma x dout] (if act)  | dW partial sums
+struct LayerWs {
+    size_t off_a = 0, off_dz = 0, off_tn = 0, total = 0;
+};
+
+static LayerWs layer_ws(const Orient& a, int64_t din, int64_t dout, plx_dtype dtype, plx_act act, plx_order order) {
+    LayerWs w;
+    size_t es = elt_size(dtype);
+    size_t first = order == PLX_ORDER_AGG_FIRST ? (size_t)a.rows * din * es : (size_t)a.cols * dout * es;
+    w.off_a = 0;
+    w.off_dz = align256(first);
+    size_t dz = act == PLX_ACT_RELU ? (size_t)a.rows * dout * es : 0;
+    w.off_tn = w.off_dz + align256(dz);
+    int64_t R = order == PLX_ORDER_AGG_FIRST ? a.rows : a.cols;
+    w.total = w.off_tn + align256(gemm_tn_workspace(R, din, dout));
+    return w;
+}
+
+size_t plx_gcn_layer_workspace(const plx_csr* csr, int transposed_A, int64_t din, int64_t dout, plx_dtype dtype,
+                               plx_act act, plx_order order) {
+    if (!csr || din <= 0 || dout <= 0 || !dtype_ok(dtype)) return 0;
+    if ((int)order < 0 || (int)order > 2) return 0;
+    return layer_ws(csr->o[transposed_A ? 1 : 0], din, dout, dtype, act, resolve_order(order, din, dout)).total;
+}
+
+static plx_status layer_common_checks(plx_ctx* ctx, const plx_csr* csr, int64_t din, int64_t dout, plx_dtype dtype,
+                                      plx_act act, plx_order order) {
+    if (!csr) return fail(ctx, PLX_ERR_INVALID, "csr is NULL");
+    if (!dtype_ok(dtype)) return fail(ctx, PLX_ERR_INVALID, "unknown dtype %d", (int)dtype);
+    if (act != PLX_ACT_NONE && act != PLX_ACT_RELU) return fail(ctx, PLX_ERR_INVALID, "unknown activation %d", (int)act);
+    if ((int)order < 0 || (int)order > 2) return fail(ctx, PLX_ERR_INVALID, "unknown order %d", (int)order);
+    if (din <= 0 || dout <= 0) return fail(ctx, PLX_ERR_INVALID, "din and dout must be positive");
+    return PLX_OK;
+}
+
+plx_status plx_gcn_layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* H, int64_t ldh,
+                             const float* W, int64_t ldw, int64_t din, int64_t dout, plx_dtype dtype, plx_act act,
+                             plx_order order, void* Z, int64_t ldz, void* F, int64_t ldf, void* saved,
+                             int64_t ldsaved, void* ws, size_t ws_bytes) {
+    if (!ctx) return PLX_ERR_INVALID;
+    PLX_TRY(layer_common_checks(ctx, csr, din, dout, dtype, act, order));
+    const Orient& a = csr->o[transposed_A ? 1 : 0];
+    order = resolve_order(order, din, dout);
+    if (!H || !W || !Z) return fail(ctx, PLX_ERR_INVALID, "H, W or Z is NULL");
+    if (ldh < din || ldw < dout || ldz < dout || (F && ldf < dout))
+        return fail(ctx, PLX_ERR_SHAPE, "leading dimension too small");
+    if (order == PLX_ORDER_AGG_FIRST) {
+        if (!saved) return fail(ctx, PLX_ERR_INVALID, "aggregate-first order needs the `saved` buffer");
+        if (ldsaved < din) return fail(ctx, PLX_ERR_SHAPE, "ldsaved smaller than din");
+    }
+    LayerWs w = layer_ws(a, din, dout, dtype, act, order);
+    if (order == PLX_ORDER_COMBINE_FIRST && (!ws || ws_bytes < w.total))
+        return fail(ctx, PLX_ERR_SHAPE, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, w.total);
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+
+    if (order == PLX_ORDER_AGG_FIRST) {
+        PLX_TRY(launch_spmm(ctx, a, H, ldh, saved, ldsaved, din, dtype));                    // Eq. 2.1
+        PLX_TRY(launch_gemm(ctx, false, a.rows, dout, din, saved, ldsaved, W, ldw, Z, ldz, dtype));  // Eq. 2.2
+    } else {
+        void* T = static_cast<char*>(ws) + w.off_a;
+        PLX_TRY(launch_gemm(ctx, false, a.cols, dout, din, H, ldh, W, ldw, T, dout, dtype));
+        PLX_TRY(launch_spmm(ctx, a, T, dout, Z, ldz, dout, dtype));
+    }
+    if (F) {
+        if (act == PLX_ACT_RELU) {
+            PLX_TRY(launch_relu(ctx, a.rows, dout, Z, ldz, F, ldf, dtype));                  // Eq. 2.3
+        } else if (F != Z) {
+            PLX_HIP(ctx, hipMemcpy2DAsync(F, ldf * elt_size(dtype), Z, ldz * elt_size(dtype), dout * elt_size(dtype),
+                                          a.rows, hipMemcpyDeviceToDevice, ctx->stream));
+        }
+    }
+    return PLX_OK;
+}
+
+plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* H, int64_t ldh,
+                             const float* W, int64_t ldw, const void* Z, int64_t ldz, const void* dF, int64_t lddf,
+                             const void* saved, int64_t ldsaved, int64_t din, int64_t dout, plx_dtype dtype,
+                             plx_act act, plx_order order, void* dH, int64_t lddh, float* dW, int64_t lddw, void* ws,
+                             size_t ws_bytes) {
+    if (!ctx) return PLX_ERR_INVALID;
+    PLX_TRY(layer_common_checks(ctx, csr, din, dout, dtype, act, order));
+    const int t = transposed_A ? 1 : 0;
+    const Orient& a = csr->o[t];
+    const Orient& at = csr->o[1 - t];   // the transpose of the layer's adjacency
+    order = resolve_order(order, din, dout);
+    if (!W || !dF || !dW) return fail(ctx, PLX_ERR_INVALID, "W, dF or dW is NULL");
+    if (act == PLX_ACT_RELU && !Z) return fail(ctx, PLX_ERR_INVALID, "Z is needed for the ReLU derivative");
+    if (ldw < dout || lddf < dout || lddw < dout || (Z && ldz < dout) || (dH && lddh < din))
+        return fail(ctx, PLX_ERR_SHAPE, "leading dimension too small");
+    if (order == PLX_ORDER_AGG_FIRST) {
+        if (!saved) return fail(ctx, PLX_ERR_INVALID, "aggregate-first order needs the `saved` buffer");
+        if (ldsaved < din) return fail(ctx, PLX_ERR_SHAPE, "ldsaved smaller than din");
+    } else {
+        if (!H) return fail(ctx, PLX_ERR_INVALID, "H is NULL");
+        if (ldh < din) return fail(ctx, PLX_ERR_SHAPE, "ldh smaller than din");
+    }
+    LayerWs w = layer_ws(a, din, dout, dtype, act, order);
+    if (!ws || ws_bytes < w.total)
+        return fail(ctx, PLX_ERR_SHAPE, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, w.total);
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+
+    char* base = static_cast<char*>(ws);
+    const void* dZ = dF;
+    int64_t lddz = lddf;
+    if (act == PLX_ACT_RELU) {                                                               // Eq. 2.4
+        void* buf = base + w.off_dz;
+        PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, dout, dtype));
+        dZ = buf; lddz = dout;
+    }
+    void* tn_ws = base + w.off_tn;
+    size_t tn_bytes = w.total - w.off_tn;
+    if (order == PLX_ORDER_AGG_FIRST) {
+        PLX_TRY(launch_gemm_tn(ctx, a.rows, din, dout, saved, ldsaved, dZ, lddz, dW, lddw, dtype, tn_ws, tn_bytes));  // Eq. 2.5
+        if (dH) {
+            void* dS = base + w.off_a;
+            PLX_TRY(launch_gemm(ctx, true, a.rows, din, dout, dZ, lddz, W, ldw, dS, din, dtype));  // Eq. 2.6
+            PLX_TRY(launch_spmm(ctx, at, dS, din, dH, lddh, din, dtype));                    // Eq. 2.7
+        }
+    } else {
+        void* G = base + w.off_a;
+        PLX_TRY(launch_spmm(ctx, at, dZ, lddz, G, dout, dout, dtype));                       // A^T dZ
+        PLX_TRY(launch_gemm_tn(ctx, a.cols, din, dout, H, ldh, G, dout, dW, lddw, dtype, tn_ws, tn_bytes));
+        if (dH) PLX_TRY(launch_gemm(ctx, true, a.cols, din, dout, G, dout, W, ldw, dH, lddh, dtype));
+    }
+    return PLX_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,115 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "plx.h"
+
+namespace plx {
+
+constexpr int kWave = 64;            // gfx950 wavefront width
+constexpr int kNumClasses = 34;      // row-length classes: 0 = empty, c = 1 + floor(log2 len)
+constexpr int kSubwaveMaxClass = 8;  // rows shorter than 2^8 are handled by a group of lanes
+constexpr int kLongClass = 13;       // rows with len >= 2^12 are split into segments
+constexpr int64_t kSegLen = 2048;    // nonzeros per segment of a split row
+
+// One stored orientation of the adjacency (CSR) plus its row binning.
+struct Orient {
+    int64_t rows = 0, cols = 0, nnz = 0;
+    int64_t* rowptr = nullptr;     // device [rows + 1]
+    int32_t* col = nullptr;        // device [nnz], strictly ascending inside a row
+    float* val = nullptr;          // device [nnz]
+    int32_t* row_order = nullptr;  // device [rows]: row ids sorted by length class, ascending id inside a class
+    int64_t class_off[kNumClasses + 1] = {0};  // host: slot range of each class inside row_order
+    // rows of class >= kLongClass, cut into segments of at most kSegLen nonzeros
+    int64_t n_long = 0, n_seg = 0;
+    int32_t* long_row = nullptr;   // device [n_long] row id
+    int32_t* long_seg0 = nullptr;  // device [n_long + 1] first segment of each long row
+    int64_t* seg_lo = nullptr;     // device [n_seg] first nonzero of the segment
+    int32_t* seg_len = nullptr;    // device [n_seg] nonzeros in the segment
+};
+
+}  // namespace plx
+
+struct plx_ctx {
+    int device = -1;
+    bool dry = false;  // validate-only context
+    hipStream_t stream = nullptr;
+    plx_alloc_fn alloc = nullptr;
+    plx_free_fn release = nullptr;
+    void* user = nullptr;
+    std::string err;
+    void* scratch = nullptr;  // partial sums of split rows; grown on demand
+    size_t scratch_bytes = 0;
+};
+
+struct plx_csr {
+    plx::Orient o[2];        // [0] = A_fwd, [1] = A_fwd^T
+    int64_t n_deg = 0;
+    int64_t* deg = nullptr;  // device [n_deg], original id order (handles from plx_build_csr only)
+};
+
+namespace plx {
+
+plx_status fail(plx_ctx* ctx, plx_status s, const char* fmt, ...);
+void* dev_alloc(plx_ctx* ctx, size_t bytes);   // NULL on failure (error recorded)
+void dev_free(plx_ctx* ctx, void* p);
+plx_status ensure_scratch(plx_ctx* ctx, size_t bytes);
+
+#define PLX_HIP(ctx, call)                                                                   \
+    do {                                                                                     \
+        hipError_t e_ = (call);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return plx::fail((ctx), PLX_ERR_DEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+#define PLX_TRY(expr)                    \
+    do {                                 \
+        plx_status s_ = (expr);          \
+        if (s_ != PLX_OK) return s_;     \
+    } while (0)
+
+// RAII holder for temporaries obtained through the context allocator.
+struct TempPool {
+    plx_ctx* ctx;
+    std::vector<void*> ptrs;
+    explicit TempPool(plx_ctx* c) : ctx(c) {}
+    ~TempPool() { for (void* p : ptrs) dev_free(ctx, p); }
+    template <typename T> T* get(size_t count) {
+        void* p = dev_alloc(ctx, (count ? count : 1) * sizeof(T));
+        if (p) ptrs.push_back(p);
+        return static_cast<T*>(p);
+    }
+};
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// set-up: fills the binning fields of `o` from its CSR arrays (waits on the stream)
+plx_status build_bins(plx_ctx* ctx, Orient& o);
+void free_orient(plx_ctx* ctx, Orient& o);
+
+// kernels' host launchers (all asynchronous on ctx->stream)
+plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* Y, int64_t ldy,
+                       int64_t d, plx_dtype dtype);
+plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                       const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype);
+size_t gemm_tn_workspace(int64_t R, int64_t M, int64_t N);
+plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const void* A, int64_t lda,
+                          const void* B, int64_t ldb, float* C, int64_t ldc, plx_dtype dtype, void* ws, size_t ws_bytes);
+plx_status launch_relu(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, void* F, int64_t ldf,
+                       plx_dtype dtype);
+plx_status launch_relu_bwd(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, const void* dF,
+                           int64_t lddf, void* dZ, int64_t lddz, plx_dtype dtype);
+plx_status launch_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, int64_t ldz, const int64_t* y,
+                             void* dZ, int64_t lddz, float* row_loss, float* loss, plx_dtype dtype);
+
+inline size_t elt_size(plx_dtype t) { return t == PLX_BF16 ? 2 : 4; }
+inline size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
+
+}  // namespace plx

@@ -1,0 +1,280 @@
+// Sparse x dense product Y = A X for a CSR orientation (paper Eq. 2.1; with the transposed
+// orientation also Eq. 2.7).  The product is bound by the gather of dense rows of X from HBM:
+// every stored entry fetches one row of X (the double permutation of Sec. 5.1 leaves no
+// locality between neighbouring entries), so the kernels are organised around wide, fully used
+// memory transactions and many independent gathers in flight:
+//
+//  * a dense row of d elements is covered by G = 2^ceil(log2(ceil(d / VW))) lanes, each holding
+//    VW consecutive elements (one 128-bit load when the layout allows it);
+//  * rows are binned by length class (set-up time).  Short rows: one G-lane group per row, 64/G
+//    rows per wavefront, no cross-lane traffic.  Medium rows: one wavefront per row, its 64/G
+//    groups stride over the entries and are combined by a butterfly across groups.  Long rows:
+//    cut into fixed segments, one wavefront per segment, partial sums combined in segment
+//    order by a second kernel (no floating-point atomics => bit-reproducible);
+//  * the entry loop is unrolled U-fold with all column/value loads issued before the U gathers,
+//    so a lane keeps U independent gathers in flight.
+#include "plx_internal.h"
+
+#include <algorithm>
+
+namespace plx {
+namespace {
+
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {   // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <int BYTES> struct Raw;
+template <> struct Raw<2> { typedef uint16_t type; };
+template <> struct Raw<4> { typedef uint32_t type; };
+template <> struct Raw<8> { typedef uint2 type; };
+template <> struct Raw<16> { typedef uint4 type; };
+
+// load VW consecutive elements as one transaction and widen to fp32
+template <typename T, int VW>
+__device__ __forceinline__ void load_vec(const T* p, float (&r)[VW]) {
+    typedef typename Raw<sizeof(T) * VW>::type raw_t;
+    union { raw_t raw; T e[VW]; } u;
+    u.raw = *reinterpret_cast<const raw_t*>(p);
+#pragma unroll
+    for (int i = 0; i < VW; ++i) {
+        if constexpr (sizeof(T) == 4) r[i] = u.e[i];
+        else r[i] = bf16_to_f32(u.e[i]);
+    }
+}
+
+template <typename T> __device__ __forceinline__ T narrow(float f) {
+    if constexpr (sizeof(T) == 4) return f;
+    else return f32_to_bf16(f);
+}
+
+// store the first `valid` of VW elements (one transaction when all are valid)
+template <typename T, int VW>
+__device__ __forceinline__ void store_vec(T* p, const float (&r)[VW], int valid) {
+    typedef typename Raw<sizeof(T) * VW>::type raw_t;
+    if (valid >= VW) {
+        union { raw_t raw; T e[VW]; } u;
+#pragma unroll
+        for (int i = 0; i < VW; ++i) u.e[i] = narrow<T>(r[i]);
+        *reinterpret_cast<raw_t*>(p) = u.raw;
+    } else {
+#pragma unroll
+        for (int i = 0; i < VW; ++i)
+            if (i < valid) p[i] = narrow<T>(r[i]);
+    }
+}
+
+constexpr int kUnroll = 8;
+
+// acc += sum over entries e = first, first + stride, ... < hi of val[e] * X[col[e], c0 .. c0+VW)
+template <typename T, int VW>
+__device__ __forceinline__ void gather_accumulate(int64_t first, int64_t hi, int64_t stride,
+                                                  const int32_t* __restrict__ col, const float* __restrict__ val,
+                                                  const T* __restrict__ xb, int64_t ldx, float (&acc)[VW]) {
+    int64_t e = first;
+    for (; e + (kUnroll - 1) * stride < hi; e += kUnroll * stride) {
+        int32_t c[kUnroll];
+        float v[kUnroll];
+#pragma unroll
+        for (int t = 0; t < kUnroll; ++t) { c[t] = col[e + t * stride]; v[t] = val[e + t * stride]; }
+        float x[kUnroll][VW];
+#pragma unroll
+        for (int t = 0; t < kUnroll; ++t) load_vec<T, VW>(xb + (int64_t)c[t] * ldx, x[t]);
+#pragma unroll
+        for (int t = 0; t < kUnroll; ++t)
+#pragma unroll
+            for (int i = 0; i < VW; ++i) acc[i] = fmaf(v[t], x[t][i], acc[i]);
+    }
+    for (; e < hi; e += stride) {
+        int32_t c = col[e];
+        float v = val[e];
+        float x[VW];
+        load_vec<T, VW>(xb + (int64_t)c * ldx, x);
+#pragma unroll
+        for (int i = 0; i < VW; ++i) acc[i] = fmaf(v, x[i], acc[i]);
+    }
+}
+
+// Short rows: one group of G lanes per row, 64/G rows per wavefront.
+template <typename T, int G, int VW>
+__global__ __launch_bounds__(256) void k_spmm_subwave(const int32_t* __restrict__ row_order, int64_t count,
+                                                      const int64_t* __restrict__ rowptr,
+                                                      const int32_t* __restrict__ col, const float* __restrict__ val,
+                                                      const T* __restrict__ X, int64_t ldx, T* __restrict__ Y,
+                                                      int64_t ldy, int d) {
+    constexpr int R = kWave / G;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int64_t slot = wave * R + lane / G;
+    if (slot >= count) return;
+    const int c0 = (lane % G) * VW;
+    if (c0 >= d) return;
+    const int32_t row = row_order[slot];
+    const int64_t lo = rowptr[row], hi = rowptr[row + 1];
+    float acc[VW];
+#pragma unroll
+    for (int i = 0; i < VW; ++i) acc[i] = 0.f;
+    gather_accumulate<T, VW>(lo, hi, 1, col, val, X + c0, ldx, acc);
+    store_vec<T, VW>(Y + (int64_t)row * ldy + c0, acc, d - c0);
+}
+
+// butterfly sum across the 64/G groups of a wavefront; every lane ends with the total
+template <int G, int VW>
+__device__ __forceinline__ void reduce_groups(float (&acc)[VW]) {
+#pragma unroll
+    for (int off = G; off < kWave; off <<= 1)
+#pragma unroll
+        for (int i = 0; i < VW; ++i) acc[i] += __shfl_xor(acc[i], off, kWave);
+}
+
+// Medium rows: one wavefront per row.
+template <typename T, int G, int VW>
+__global__ __launch_bounds__(256) void k_spmm_wave(const int32_t* __restrict__ rows, int64_t count,
+                                                   const int64_t* __restrict__ rowptr,
+                                                   const int32_t* __restrict__ col, const float* __restrict__ val,
+                                                   const T* __restrict__ X, int64_t ldx, T* __restrict__ Y,
+                                                   int64_t ldy, int d) {
+    constexpr int NG = kWave / G;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t slot = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (slot >= count) return;                       // uniform per wavefront
+    const int g = lane / G, c0 = (lane % G) * VW;
+    const bool active = c0 < d;
+    const int32_t row = rows[slot];
+    const int64_t lo = rowptr[row], hi = rowptr[row + 1];
+    float acc[VW];
+#pragma unroll
+    for (int i = 0; i < VW; ++i) acc[i] = 0.f;
+    if (active) gather_accumulate<T, VW>(lo + g, hi, NG, col, val, X + c0, ldx, acc);
+    reduce_groups<G, VW>(acc);
+    if (g == 0 && active) store_vec<T, VW>(Y + (int64_t)row * ldy + c0, acc, d - c0);
+}
+
+// Long rows, stage 1: one wavefront per segment, fp32 partial sums to part[seg][G*VW].
+template <typename T, int G, int VW>
+__global__ __launch_bounds__(256) void k_spmm_segment(int64_t n_seg, const int64_t* __restrict__ seg_lo,
+                                                      const int32_t* __restrict__ seg_len,
+                                                      const int32_t* __restrict__ col, const float* __restrict__ val,
+                                                      const T* __restrict__ X, int64_t ldx, float* __restrict__ part,
+                                                      int d) {
+    constexpr int NG = kWave / G;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t seg = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (seg >= n_seg) return;
+    const int g = lane / G, c0 = (lane % G) * VW;
+    const bool active = c0 < d;
+    const int64_t lo = seg_lo[seg], hi = lo + seg_len[seg];
+    float acc[VW];
+#pragma unroll
+    for (int i = 0; i < VW; ++i) acc[i] = 0.f;
+    if (active) gather_accumulate<T, VW>(lo + g, hi, NG, col, val, X + c0, ldx, acc);
+    reduce_groups<G, VW>(acc);
+    if (g == 0) {
+        float* p = part + seg * (G * VW) + c0;
+#pragma unroll
+        for (int i = 0; i < VW; ++i) p[i] = acc[i];
+    }
+}
+
+// Long rows, stage 2: Y[row] = sum of the row's segment partials, in segment order.
+template <typename T>
+__global__ __launch_bounds__(256) void k_spmm_combine(int64_t n_long, const int32_t* __restrict__ long_row,
+                                                      const int32_t* __restrict__ seg0, const float* __restrict__ part,
+                                                      int ldp, T* __restrict__ Y, int64_t ldy, int d) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t q = idx / d;
+    const int j = (int)(idx % d);
+    if (q >= n_long) return;
+    float s = 0.f;
+    for (int32_t k = seg0[q]; k < seg0[q + 1]; ++k) s += part[(int64_t)k * ldp + j];
+    Y[(int64_t)long_row[q] * ldy + j] = narrow<T>(s);
+}
+
+template <typename T, int G, int VW>
+plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, T* Y, int64_t ldy, int d) {
+    hipStream_t s = ctx->stream;
+    const int64_t n_sub = o.class_off[kSubwaveMaxClass + 1];
+    const int64_t n_wave = o.class_off[kLongClass] - n_sub;
+    constexpr int WPB = 256 / kWave;   // wavefronts per block
+    if (n_sub > 0) {
+        constexpr int R = kWave / G;
+        int64_t blocks = ceil_div(ceil_div(n_sub, R), WPB);
+        k_spmm_subwave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order, n_sub, o.rowptr, o.col, o.val, X,
+                                                                         ldx, Y, ldy, d);
+    }
+    if (n_wave > 0) {
+        int64_t blocks = ceil_div(n_wave, WPB);
+        k_spmm_wave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + n_sub, n_wave, o.rowptr, o.col,
+                                                                      o.val, X, ldx, Y, ldy, d);
+    }
+    if (o.n_seg > 0) {
+        PLX_TRY(ensure_scratch(ctx, (size_t)o.n_seg * G * VW * sizeof(float)));
+        float* part = static_cast<float*>(ctx->scratch);
+        k_spmm_segment<T, G, VW><<<dim3((unsigned)ceil_div(o.n_seg, WPB)), 256, 0, s>>>(o.n_seg, o.seg_lo, o.seg_len,
+                                                                                         o.col, o.val, X, ldx, part, d);
+        int64_t total = o.n_long * d;
+        k_spmm_combine<T><<<dim3((unsigned)ceil_div(total, 256)), 256, 0, s>>>(o.n_long, o.long_row, o.long_seg0, part,
+                                                                               G * VW, Y, ldy, d);
+    }
+    PLX_HIP(ctx, hipGetLastError());
+    return PLX_OK;
+}
+
+template <typename T, int VW>
+plx_status run_vw(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, T* Y, int64_t ldy, int64_t d) {
+    const int tile = kWave * VW;                        // widest pass one wavefront covers
+    for (int64_t t0 = 0; t0 < d; t0 += tile) {
+        int dp = (int)std::min<int64_t>(tile, d - t0);
+        int chunks = (dp + VW - 1) / VW;
+        int G = 1;
+        while (G < chunks) G <<= 1;
+        const T* Xp = X + t0;
+        T* Yp = Y + t0;
+        plx_status st;
+        switch (G) {
+            case 1: st = run_pass<T, 1, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
+            case 2: st = run_pass<T, 2, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
+            case 4: st = run_pass<T, 4, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
+            case 8: st = run_pass<T, 8, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
+            case 16: st = run_pass<T, 16, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
+            case 32: st = run_pass<T, 32, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
+            default: st = run_pass<T, 64, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
+        }
+        PLX_TRY(st);
+    }
+    return PLX_OK;
+}
+
+bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace
+
+plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* Y, int64_t ldy, int64_t d,
+                       plx_dtype dtype) {
+    if (o.rows >= (int64_t(1) << 31) || o.nnz >= (int64_t(1) << 31))
+        return fail(ctx, PLX_ERR_UNSUPPORTED, "matrix too large for 32-bit ids");
+    // widest vector the layout allows: base pointers and row pitches must keep every row aligned
+    auto fits = [&](size_t bytes, size_t es) {
+        return aligned_to(X, bytes) && aligned_to(Y, bytes) && (ldx * es) % bytes == 0 && (ldy * es) % bytes == 0;
+    };
+    if (dtype == PLX_F32) {
+        const float* x = static_cast<const float*>(X);
+        float* y = static_cast<float*>(Y);
+        if (fits(16, 4)) return run_vw<float, 4>(ctx, o, x, ldx, y, ldy, d);
+        if (fits(8, 4)) return run_vw<float, 2>(ctx, o, x, ldx, y, ldy, d);
+        return run_vw<float, 1>(ctx, o, x, ldx, y, ldy, d);
+    }
+    const bf16_t* x = static_cast<const bf16_t*>(X);
+    bf16_t* y = static_cast<bf16_t*>(Y);
+    if (fits(16, 2)) return run_vw<bf16_t, 8>(ctx, o, x, ldx, y, ldy, d);
+    if (fits(8, 2)) return run_vw<bf16_t, 4>(ctx, o, x, ldx, y, ldy, d);
+    return run_vw<bf16_t, 1>(ctx, o, x, ldx, y, ldy, d);
+}
+
+}  // namespace plx

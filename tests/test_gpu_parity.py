@@ -1,0 +1,302 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Bit-exact for structure (row pointers, columns, degrees, fp32 values);
+max|g-o| / max|o| <= 1e-4 for fp32 tensors (the tolerance the benchmark spec fixes)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import gcn as ogcn
+import paper_2505_04083_amd as plx
+import synth
+from gcn_driver import rel_err, run_network
+
+pytestmark = pytest.mark.gpu
+TOL32 = 1e-4
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = plx.plx_ctx(0)
+    yield c
+    c.close()
+
+
+def dev(a, dtype=None):
+    t = torch.as_tensor(a)
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to(DEV).contiguous()
+
+
+def bits(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def noisy_edges(src, dst, seed=1):
+    """Add reversed copies, duplicates and self-loops: the builder must drop them all."""
+    r = np.random.default_rng(seed)
+    k = max(1, len(src) // 10)
+    pick = r.integers(0, len(src), k)
+    loops = r.integers(0, max(int(src.max()), 1), k)
+    s = np.concatenate([src, dst[pick], src[pick], loops])
+    d = np.concatenate([dst, src[pick], dst[pick], loops])
+    order = r.permutation(len(s))
+    return s[order], d[order]
+
+
+def graph_cases():
+    tiny = synth.CONFIGS["tiny"]
+    return {
+        "tiny": tiny,
+        "social_small": synth.CONFIGS["social"].scaled(0.05),       # hubs > 4096 entries: split rows
+        "road_small": synth.CONFIGS["road"].scaled(2e-3),           # rows of 1..6 entries
+    }
+
+
+@pytest.mark.parametrize("name", ["tiny", "social_small", "road_small"])
+def test_build_csr_bit_exact(ctx, name):
+    cfg = graph_cases()[name]
+    src, dst = (t.numpy() for t in cfg.edges())
+    src, dst = noisy_edges(src, dst)
+    pr, pc = (p.numpy() for p in cfg.perms())
+    adj = oracle.adjacency(cfg.n, src, dst)
+    csr = plx.plx_build_csr(ctx, cfg.n, dev(src), dev(dst), dev(pr), dev(pc))
+    assert (csr.m, csr.k, csr.nnz) == (cfg.n, cfg.n, adj.nnz)
+    for transposed, (a, b) in enumerate([(pr, pc), (pc, pr)]):
+        rowptr, col, val = oracle.permuted_csr(adj, a, b)
+        g_rowptr, g_col, g_val, g_deg = plx.plx_csr_export(ctx, csr, bool(transposed), with_deg=True)
+        assert np.array_equal(g_rowptr.cpu().numpy(), rowptr)
+        assert np.array_equal(g_col.cpu().numpy(), col)
+        assert np.array_equal(bits(g_val), val.view(np.uint32))
+        assert np.array_equal(g_deg.cpu().numpy(), adj.deg)
+    # identity permutations (NULL)
+    csr0 = plx.plx_build_csr(ctx, cfg.n, dev(src), dev(dst))
+    rowptr, col, val = oracle.permuted_csr(adj)
+    g = plx.plx_csr_export(ctx, csr0)
+    assert np.array_equal(g[0].cpu().numpy(), rowptr) and np.array_equal(g[1].cpu().numpy(), col)
+    assert np.array_equal(bits(g[2]), val.view(np.uint32))
+
+
+def test_build_csr_degenerate_and_errors(ctx):
+    e = torch.zeros(0, dtype=torch.int64, device=DEV)
+    csr = plx.plx_build_csr(ctx, 5, e, e)                       # empty graph: A^ = I
+    rowptr, col, val = plx.plx_csr_export(ctx, csr)
+    assert rowptr.tolist() == [0, 1, 2, 3, 4, 5] and col.tolist() == [0, 1, 2, 3, 4] and val.tolist() == [1.0] * 5
+    csr = plx.plx_build_csr(ctx, 0, e, e)
+    assert (csr.m, csr.nnz) == (0, 0)
+    loops = dev(np.array([1, 2, 2]))
+    csr = plx.plx_build_csr(ctx, 3, loops, loops)               # only self-loops in the input
+    assert csr.nnz == 3
+    with pytest.raises(plx.PlxError) as err:
+        plx.plx_build_csr(ctx, 3, dev(np.array([0, 3])), dev(np.array([1, 1])))
+    assert err.value.status == plx.PLX_ERR_INVALID
+    with pytest.raises(plx.PlxError) as err:
+        plx.plx_build_csr(ctx, 3, dev(np.array([0])), dev(np.array([1])), dev(np.array([0, 0, 2])), None)
+    assert err.value.status == plx.PLX_ERR_INVALID
+    with pytest.raises(plx.PlxError) as err:
+        plx.plx_build_csr(ctx, 3, dev(np.array([0])), dev(np.array([1])), None, dev(np.array([0, 1, 5])))
+    assert err.value.status == plx.PLX_ERR_INVALID
+
+
+def random_block(m, k, seed, empty_rows=True, giant_row=None):
+    """Rectangular CSR block with skewed row lengths, some empty rows and optionally one very
+    long row (more than the split threshold)."""
+    r = np.random.default_rng(seed)
+    lens = np.minimum(r.zipf(1.6, m), k // 2).astype(np.int64)
+    if empty_rows:
+        lens[r.integers(0, m, m // 7)] = 0
+        lens[0] = 0; lens[m - 1] = 0
+    if giant_row is not None:
+        lens[giant_row] = min(k, 9000)
+    rowptr = np.zeros(m + 1, np.int64); rowptr[1:] = np.cumsum(lens)
+    col = np.concatenate([np.sort(r.choice(k, l, replace=False)) for l in lens if l > 0] or [np.zeros(0, np.int64)])
+    val = r.random(len(col)).astype(np.float32) + 0.1
+    return rowptr, col.astype(np.int32), val
+
+
+def coo_of(rowptr, col, val):
+    row = np.repeat(np.arange(len(rowptr) - 1), np.diff(rowptr))
+    return row, col.astype(np.int64), val.astype(np.float64)
+
+
+def test_import_transpose_bit_exact(ctx):
+    m, k = 700, 12000
+    rowptr, col, val = random_block(m, k, 3, giant_row=5)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    g = plx.plx_csr_export(ctx, csr, False)
+    assert np.array_equal(g[0].cpu().numpy(), rowptr) and np.array_equal(g[1].cpu().numpy(), col)
+    row, c64, _ = coo_of(rowptr, col, val)
+    order = np.lexsort((row, c64))                     # transposed: sort by (col, row)
+    t_rowptr = np.zeros(k + 1, np.int64); t_rowptr[1:] = np.cumsum(np.bincount(c64, minlength=k))
+    gt = plx.plx_csr_export(ctx, csr, True)
+    assert np.array_equal(gt[0].cpu().numpy(), t_rowptr)
+    assert np.array_equal(gt[1].cpu().numpy(), row[order].astype(np.int32))
+    assert np.array_equal(bits(gt[2]), val[order].view(np.uint32))
+    sub, wave, split = plx.plx_csr_bins(csr, False, 32)
+    assert sub + wave + split == m and split == 1
+    # structure errors are reported, not executed
+    bad = col.copy(); bad[1], bad[2] = bad[2], bad[1]
+    bad_rp = rowptr.copy(); bad_rp[3] = bad_rp[4] + 1
+    for args in [(dev(rowptr), dev(bad), dev(val)), (dev(bad_rp), dev(col), dev(val))]:
+        with pytest.raises(plx.PlxError) as err:
+            plx.plx_csr_import(ctx, m, k, *args)
+        assert err.value.status == plx.PLX_ERR_INVALID
+
+
+@pytest.mark.parametrize("d,pad", [(1, 0), (16, 0), (32, 0), (41, 0), (41, 3), (47, 1), (64, 0), (100, 0),
+                                   (128, 0), (128, 4), (300, 0), (30, 2)])
+def test_spmm_and_transpose_parity(ctx, d, pad):
+    """Width sweep over aligned, padded and unaligned layouts; block with empty rows, skewed
+    rows and one split row; several tiles and a ragged tail."""
+    m, k = 1531, 9973
+    rowptr, col, val = random_block(m, k, 11 + d, giant_row=77)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(d)
+    X = r.standard_normal((k, d)).astype(np.float32)
+    G = r.standard_normal((m, d)).astype(np.float32)
+    ld = d + pad
+    Xd = torch.full((k, ld), float("nan"), device=DEV); Xd[:, :d] = dev(X)
+    Gd = torch.full((m, ld), float("nan"), device=DEV); Gd[:, :d] = dev(G)
+    Y = torch.full((m, ld), 7.0, device=DEV)
+    Yt = torch.full((k, ld), 7.0, device=DEV)
+    plx.plx_spmm(ctx, csr, Xd[:, :d], Y[:, :d])
+    plx.plx_spmm_t(ctx, csr, Gd[:, :d], Yt[:, :d])
+    plx.plx_sync(ctx)
+    ref = oracle.spmm_coo(m, row, c64, v64, X)
+    ref_t = oracle.spmm_t_coo(k, row, c64, v64, G)
+    assert rel_err(Y[:, :d], ref) <= TOL32
+    assert rel_err(Yt[:, :d], ref_t) <= TOL32
+    if pad:
+        assert bool((Y[:, d:] == 7.0).all()) and bool((Yt[:, d:] == 7.0).all())      # padding untouched
+    assert bool((Y[0, :d] == 0).all())                                              # empty row -> zeros
+    # run-to-run bit reproducibility (no floating-point atomics)
+    Y2 = torch.empty_like(Y)
+    plx.plx_spmm(ctx, csr, Xd[:, :d], Y2[:, :d]); plx.plx_sync(ctx)
+    assert torch.equal(Y2[:, :d], Y[:, :d])
+
+
+def test_spmm_eigenvector_pin(ctx):
+    """A^ sqrt(d) = sqrt(d): the normalised adjacency built on the GPU, applied on the GPU."""
+    cfg = synth.CONFIGS["tiny"]
+    src, dst = cfg.edges(DEV)
+    csr = plx.plx_build_csr(ctx, cfg.n, src, dst)
+    deg = plx.plx_csr_export(ctx, csr, with_deg=True)[3]
+    s = torch.sqrt(deg.double()).float().reshape(-1, 1).contiguous()
+    y = torch.empty_like(s)
+    plx.plx_spmm(ctx, csr, s, y); plx.plx_sync(ctx)
+    assert float(((y - s).abs() / s).max()) < 5e-6
+
+
+@pytest.mark.parametrize("M,N,K", [(1000, 128, 32), (517, 41, 128), (300, 128, 602), (129, 16, 128), (64, 47, 100),
+                                   (2049, 32, 128), (5, 3, 7)])
+def test_gemm_parity(ctx, M, N, K):
+    r = np.random.default_rng(M + N + K)
+    A = r.standard_normal((M, K)).astype(np.float32)
+    B = r.standard_normal((K, N)).astype(np.float32)
+    C = torch.empty(M, N, device=DEV)
+    plx.plx_gemm_nn(ctx, dev(A), dev(B), C)
+    assert rel_err(C, oracle.gemm(A, B)) <= TOL32
+    Bt = np.ascontiguousarray(B.T)
+    C2 = torch.empty(M, N, device=DEV)
+    plx.plx_gemm_nt(ctx, dev(A), dev(Bt), C2)
+    assert rel_err(C2, oracle.gemm(A, Bt, tb=True)) <= TOL32
+    # transposed product: reduction over the M rows
+    G = r.standard_normal((M, N)).astype(np.float32)
+    dW = torch.empty(K, N, device=DEV)
+    plx.plx_gemm_tn(ctx, dev(A), dev(G), dW)
+    assert rel_err(dW, oracle.gemm(A, G, ta=True)) <= TOL32
+
+
+def test_gemm_tn_long_reduction_and_padding(ctx):
+    R, M, N = 300_000, 32, 128
+    A = synth.normal(5, 1, R, M, DEV)
+    Bfull = torch.zeros(R, N + 4, device=DEV)
+    Bfull[:, :N] = synth.normal(5, 2, R, N, DEV)
+    C = torch.empty(M, N, device=DEV)
+    plx.plx_gemm_tn(ctx, A, Bfull[:, :N], C)
+    ref = oracle.gemm(A.cpu().numpy(), Bfull[:, :N].cpu().numpy(), ta=True)
+    assert rel_err(C, ref) <= TOL32
+    C2 = torch.empty_like(C)
+    plx.plx_gemm_tn(ctx, A, Bfull[:, :N], C2)
+    assert torch.equal(C, C2)
+
+
+def test_elementwise_parity(ctx):
+    r = np.random.default_rng(0)
+    Z = r.standard_normal((1001, 47)).astype(np.float32); Z[3, 4] = 0.0
+    dF = r.standard_normal((1001, 47)).astype(np.float32)
+    F = torch.empty(1001, 47, device=DEV); dZ = torch.empty(1001, 47, device=DEV)
+    plx.plx_relu(ctx, dev(Z), F); plx.plx_relu_bwd(ctx, dev(Z), dev(dF), dZ)
+    assert np.array_equal(F.cpu().numpy(), oracle.relu(Z).astype(np.float32))
+    assert np.array_equal(dZ.cpu().numpy(), oracle.relu_bwd(Z, dF).astype(np.float32))
+    # padded layout takes the 2-D kernel
+    Zp = torch.zeros(1001, 50, device=DEV); Zp[:, :47] = dev(Z)
+    Fp = torch.full((1001, 50), 9.0, device=DEV)
+    plx.plx_relu(ctx, Zp[:, :47], Fp[:, :47])
+    assert torch.equal(Fp[:, :47], F) and bool((Fp[:, 47:] == 9.0).all())
+    y = r.integers(0, 47, 1001)
+    g = torch.empty(1001, 47, device=DEV); loss = torch.zeros(1, device=DEV)
+    plx.plx_softmax_ce(ctx, dev(Z * 3), dev(y), g, loss=loss); plx.plx_sync(ctx)
+    ref_loss, ref_g = oracle.softmax_ce(Z.astype(np.float64) * 3, y)
+    assert rel_err(g, ref_g) <= TOL32
+    assert abs(loss.item() - ref_loss) / ref_loss <= TOL32
+
+
+@pytest.mark.parametrize("order", [plx.PLX_ORDER_COMBINE_FIRST, plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_AUTO])
+def test_three_layer_network_parity(ctx, order):
+    """configs[0]: R-MAT N=4096, 65,536 edges, 128-128-128-16, one forward + backward, against
+    the oracle on the UNPERMUTED graph (Eq. 5.3-5.4 give the index maps)."""
+    cfg = synth.CONFIGS["tiny"]
+    src, dst = cfg.edges()
+    pr, pc = cfg.perms()
+    F0, Ws, y = cfg.features(), cfg.weights(), cfg.labels()
+    adj = oracle.adjacency(cfg.n, src.numpy(), dst.numpy())
+    assert adj.nnz == 135168
+    ref = ogcn.forward_backward(adj, F0.numpy(), [w.numpy() for w in Ws], y.numpy())
+
+    csr = plx.plx_build_csr(ctx, cfg.n, src.to(DEV), dst.to(DEV), pr.to(DEV), pc.to(DEV))
+    H0 = torch.empty_like(F0); H0[pc] = F0                        # P_c F0
+    L = len(Ws)
+    out_perm = pr if (L - 1) % 2 == 0 else pc
+    y_gpu = torch.empty_like(y); y_gpu[out_perm] = y
+    run = run_network(ctx, csr, H0.to(DEV), [w.to(DEV) for w in Ws], y_gpu.to(DEV), order=order)
+    for l in range(L):
+        perm = (pr if l % 2 == 0 else pc).to(DEV)
+        assert rel_err(run.Z[l][perm], ref.Q[l]) <= TOL32, f"Z of layer {l}"
+    assert abs(run.loss.item() - ref.loss) / ref.loss <= TOL32
+    for l in range(L):
+        assert rel_err(run.dW[l], ref.dW[l]) <= TOL32, f"dW of layer {l}"
+    assert rel_err(run.dF0[pc.to(DEV)], ref.dF[0]) <= TOL32
+
+
+def test_layer_on_rectangular_block_both_orders(ctx):
+    """One layer on an imported rectangular block (the shape of configs[3], shrunk): forward
+    and backward in both multiplication orders against the oracle's Eq. 2.1-2.7."""
+    m, k, din, dout = 2100, 8300, 32, 128
+    rowptr, col, val = random_block(m, k, 5, giant_row=9)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(1)
+    X = r.standard_normal((k, din)).astype(np.float32)
+    W = (r.standard_normal((din, dout)) * 0.2).astype(np.float32)
+    dFn = r.standard_normal((m, dout)).astype(np.float32)
+    Hagg = oracle.spmm_coo(m, row, c64, v64, X)
+    Q = oracle.gemm(Hagg, W)
+    dQ = oracle.relu_bwd(Q, dFn)
+    dW = oracle.gemm(Hagg, dQ, ta=True)
+    dX = oracle.spmm_t_coo(k, row, c64, v64, oracle.gemm(dQ, W, tb=True))
+    for order in (plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_COMBINE_FIRST):
+        ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, order=order), dtype=torch.uint8, device=DEV)
+        Z = torch.empty(m, dout, device=DEV); F = torch.empty(m, dout, device=DEV)
+        saved = torch.empty(m, din, device=DEV)
+        plx.plx_gcn_layer_fwd(ctx, csr, False, dev(X), dev(W), Z, F, saved, ws, order=order)
+        gdX = torch.empty(k, din, device=DEV); gdW = torch.empty(din, dout, device=DEV)
+        plx.plx_gcn_layer_bwd(ctx, csr, False, dev(X), dev(W), Z, dev(dFn), saved, gdX, gdW, ws, order=order)
+        plx.plx_sync(ctx)
+        assert rel_err(Z, Q) <= TOL32
+        assert rel_err(F, oracle.relu(Q)) <= TOL32
+        assert rel_err(gdW, dW) <= TOL32
+        assert rel_err(gdX, dX) <= TOL32
