@@ -81,6 +81,14 @@ PLX_API const char* plx_last_error(const plx_ctx* ctx);   /* host string owned b
 PLX_API const char* plx_status_string(plx_status s);
 PLX_API plx_status plx_sync(plx_ctx* ctx);                /* wait for the context's stream */
 
+/* Optional per-kernel timing for benchmarks.  While enabled, every kernel the library
+ * launches is bracketed by two HIP events on the context's stream (a few microseconds of
+ * host work per launch, nothing on the GPU).  plx_timing_report waits for the stream, writes
+ * one line per kernel name -- "<name> <launches> <total_ms>\n", NUL-terminated, truncated to
+ * buf_bytes -- into the HOST buffer `buf`, and clears the record. */
+PLX_API plx_status plx_timing_enable(plx_ctx* ctx, int on);
+PLX_API plx_status plx_timing_report(plx_ctx* ctx, char* buf, size_t buf_bytes);
+
 /* ---- adjacency set-up (Sec. 2.1 preprocessing + Sec. 5.1 double permutation) -----------------
  * plx_build_csr: src/dst are device int64[n_edges] node ids in [0, n), any order, either or
  * both directions, duplicates and self-loops allowed.  The graph is symmetrised, duplicates
@@ -112,11 +120,11 @@ PLX_API plx_status plx_csr_dims(const plx_csr* csr, int64_t* m, int64_t* k, int6
 PLX_API plx_status plx_csr_export(plx_ctx* ctx, const plx_csr* csr, int transposed, int64_t* rowptr,
                                   int32_t* col, float* val, int64_t* deg);
 
-/* Row-binning summary of one orientation (host outputs): number of rows handled by a group
- * of lanes, by a whole wavefront, and split over several wavefronts, for feature width d.
- * For inspection and tests; any pointer may be NULL. */
-PLX_API plx_status plx_csr_bins(const plx_csr* csr, int transposed, int64_t d, plx_dtype dtype,
-                                int64_t* rows_subwave, int64_t* rows_wave, int64_t* rows_split);
+/* Row-binning summary of one orientation (host outputs, each int64[3] or NULL): the number
+ * of rows, and of stored entries in those rows, that the sparse kernels handle [0] with a
+ * group of lanes per row, [1] with a whole wavefront per row, [2] split over several
+ * wavefronts.  For inspection, tests and the byte accounting of a benchmark. */
+PLX_API plx_status plx_csr_bins(const plx_csr* csr, int transposed, int64_t* rows, int64_t* entries);
 
 PLX_API void plx_csr_destroy(plx_ctx* ctx, plx_csr* csr);
 

@@ -23,6 +23,7 @@ PLX_ORDER_COMBINE_FIRST, PLX_ORDER_AGG_FIRST, PLX_ORDER_AUTO = 0, 1, 2
 
 EXPORTED = [
     "plx_ctx_create", "plx_ctx_destroy", "plx_last_error", "plx_status_string", "plx_sync",
+    "plx_timing_enable", "plx_timing_report",
     "plx_build_csr", "plx_csr_import", "plx_csr_dims", "plx_csr_export", "plx_csr_bins", "plx_csr_destroy",
     "plx_spmm", "plx_spmm_t", "plx_gemm_nn", "plx_gemm_nt", "plx_gemm_tn_workspace", "plx_gemm_tn",
     "plx_relu", "plx_relu_bwd", "plx_softmax_ce",
@@ -46,11 +47,13 @@ def _load() -> ctypes.CDLL:
         "plx_last_error": (ctypes.c_char_p, [_vp]),
         "plx_status_string": (ctypes.c_char_p, [_int]),
         "plx_sync": (_int, [_vp]),
+        "plx_timing_enable": (_int, [_vp, _int]),
+        "plx_timing_report": (_int, [_vp, ctypes.c_char_p, _sz]),
         "plx_build_csr": (_int, [_vp, _i64, _i64, _vp, _vp, _vp, _vp, ctypes.POINTER(_vp)]),
         "plx_csr_import": (_int, [_vp, _i64, _i64, _i64, _vp, _vp, _vp, ctypes.POINTER(_vp)]),
         "plx_csr_dims": (_int, [_vp, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(_i64)]),
         "plx_csr_export": (_int, [_vp, _vp, _int, _vp, _vp, _vp, _vp]),
-        "plx_csr_bins": (_int, [_vp, _int, _i64, _int, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(_i64)]),
+        "plx_csr_bins": (_int, [_vp, _int, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]),
         "plx_csr_destroy": (None, [_vp, _vp]),
         "plx_spmm": (_int, [_vp, _vp, _vp, _i64, _vp, _i64, _i64, _int]),
         "plx_spmm_t": (_int, [_vp, _vp, _vp, _i64, _vp, _i64, _i64, _int]),
@@ -221,12 +224,28 @@ def plx_csr_export(ctx: plx_ctx, csr: plx_csr, transposed: bool = False, with_de
     return (rowptr, col, val, deg) if with_deg else (rowptr, col, val)
 
 
-def plx_csr_bins(csr: plx_csr, transposed: bool, d: int, dtype: int = PLX_F32) -> Tuple[int, int, int]:
-    a, b, c = _i64(), _i64(), _i64()
-    st = _lib.plx_csr_bins(csr.handle, int(transposed), d, dtype, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+def plx_csr_bins(csr: plx_csr, transposed: bool = False):
+    """((rows_subwave, rows_wave, rows_split), (entries_subwave, entries_wave, entries_split))."""
+    rows, ent = (_i64 * 3)(), (_i64 * 3)()
+    st = _lib.plx_csr_bins(csr.handle, int(transposed), rows, ent)
     if st != PLX_OK:
         raise PlxError(st, "plx_csr_bins")
-    return a.value, b.value, c.value
+    return tuple(rows), tuple(ent)
+
+
+def plx_timing_enable(ctx: plx_ctx, on: bool) -> None:
+    ctx.check(_lib.plx_timing_enable(ctx.handle, int(on)))
+
+
+def plx_timing_report(ctx: plx_ctx):
+    """{kernel name: (launches, total_ms)} since the last report."""
+    buf = ctypes.create_string_buffer(1 << 16)
+    ctx.check(_lib.plx_timing_report(ctx.handle, buf, len(buf)))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, count, ms = line.rsplit(" ", 2)
+        out[name] = (int(count), float(ms))
+    return out
 
 
 def _spmm(fn, ctx, csr, X, Y, d):

@@ -165,12 +165,15 @@ __device__ __forceinline__ int length_class(int64_t len) {
     return len <= 0 ? 0 : 64 - __clzll((unsigned long long)len);   // 1 + floor(log2 len)
 }
 
-__global__ void k_row_class(int64_t rows, const int64_t* rowptr, uint8_t* cls, int32_t* ids, unsigned int* hist) {
+__global__ void k_row_class(int64_t rows, const int64_t* rowptr, uint8_t* cls, int32_t* ids, unsigned int* hist,
+                            unsigned long long* hist_nnz) {
     GRID_STRIDE(r, rows) {
-        int c = length_class(rowptr[r + 1] - rowptr[r]);
+        int64_t len = rowptr[r + 1] - rowptr[r];
+        int c = length_class(len);
         cls[r] = (uint8_t)c;
         ids[r] = (int32_t)r;
         atomicAdd(&hist[c], 1u);
+        atomicAdd(&hist_nnz[c], (unsigned long long)len);
     }
 }
 
@@ -243,11 +246,14 @@ plx_status build_bins(plx_ctx* ctx, Orient& o) {
     uint8_t* cls_sorted = pool.get<uint8_t>(o.rows);
     int32_t* ids = pool.get<int32_t>(o.rows);
     unsigned int* hist = pool.get<unsigned int>(kNumClasses);
-    if (!cls || !cls_sorted || !ids || !hist) return PLX_ERR_OOM;
+    unsigned long long* hist_nnz = pool.get<unsigned long long>(kNumClasses);
+    if (!cls || !cls_sorted || !ids || !hist || !hist_nnz) return PLX_ERR_OOM;
     PLX_HIP(ctx, hipMemsetAsync(hist, 0, sizeof(unsigned int) * kNumClasses, ctx->stream));
+    PLX_HIP(ctx, hipMemsetAsync(hist_nnz, 0, sizeof(unsigned long long) * kNumClasses, ctx->stream));
     unsigned int h[kNumClasses] = {0};
+    unsigned long long hn[kNumClasses] = {0};
     if (o.rows > 0) {
-        k_row_class<<<grid_for(o.rows), kThreads, 0, ctx->stream>>>(o.rows, o.rowptr, cls, ids, hist);
+        k_row_class<<<grid_for(o.rows), kThreads, 0, ctx->stream>>>(o.rows, o.rowptr, cls, ids, hist, hist_nnz);
         size_t bytes = 0;   // stable sort by class: ids stay ascending inside a class
         PLX_HIP(ctx, rocprim::radix_sort_pairs(nullptr, bytes, cls, cls_sorted, ids, o.row_order, (size_t)o.rows, 0, 6,
                                                ctx->stream));
@@ -257,9 +263,13 @@ plx_status build_bins(plx_ctx* ctx, Orient& o) {
                                                ctx->stream));
     }
     PLX_HIP(ctx, hipMemcpyAsync(h, hist, sizeof h, hipMemcpyDeviceToHost, ctx->stream));
+    PLX_HIP(ctx, hipMemcpyAsync(hn, hist_nnz, sizeof hn, hipMemcpyDeviceToHost, ctx->stream));
     PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
     o.class_off[0] = 0;
-    for (int c = 0; c < kNumClasses; ++c) o.class_off[c + 1] = o.class_off[c] + h[c];
+    for (int c = 0; c < kNumClasses; ++c) {
+        o.class_off[c + 1] = o.class_off[c] + h[c];
+        o.class_nnz[c] = (int64_t)hn[c];
+    }
 
     // long rows -> segments (few of them: done on the host)
     o.n_long = o.class_off[kNumClasses] - o.class_off[kLongClass];
@@ -406,6 +416,7 @@ plx_status plx_build_csr(plx_ctx* ctx, int64_t n, int64_t n_edges, const int64_t
             if (!b.rowptr || !b.col || !b.val) return PLX_ERR_OOM;
             PLX_HIP(ctx, hipMemsetAsync(b.rowptr, 0, sizeof(int64_t), s));
         }
+        h->o[1].tag = 1;
         PLX_TRY(build_bins(ctx, h->o[0]));
         PLX_TRY(build_bins(ctx, h->o[1]));
         PLX_HIP(ctx, hipStreamSynchronize(s));
@@ -459,6 +470,7 @@ plx_status plx_csr_import(plx_ctx* ctx, int64_t m, int64_t k, int64_t nnz, const
             if (hf) return fail(ctx, PLX_ERR_INVALID, "column ids must lie in [0, k) and ascend strictly inside a row");
         }
         PLX_TRY(transpose_orient(ctx, f, row, h->o[1]));
+        h->o[1].tag = 1;
         PLX_TRY(build_bins(ctx, h->o[0]));
         PLX_TRY(build_bins(ctx, h->o[1]));
         PLX_HIP(ctx, hipStreamSynchronize(s));

@@ -133,6 +133,7 @@ dim3 grid2d(int64_t rows, int64_t cols) {
 template <typename T>
 plx_status relu_t(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, void* F, int64_t ldf) {
     hipStream_t s = ctx->stream;
+    KernelTimer kt(ctx, "relu");
     if (ldz == cols && ldf == cols && aligned16(Z) && aligned16(F)) {
         int64_t count = rows * cols;
         k_relu_flat<T><<<dim3((unsigned)ceil_div(ceil_div(count, 4), 256)), 256, 0, s>>>(count, (const T*)Z, (T*)F);
@@ -147,6 +148,7 @@ template <typename T>
 plx_status relu_bwd_t(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, const void* dF,
                       int64_t lddf, void* dZ, int64_t lddz) {
     hipStream_t s = ctx->stream;
+    KernelTimer kt(ctx, "relu_bwd");
     if (ldz == cols && lddf == cols && lddz == cols && aligned16(Z) && aligned16(dF) && aligned16(dZ)) {
         int64_t count = rows * cols;
         k_relu_bwd_flat<T><<<dim3((unsigned)ceil_div(ceil_div(count, 4), 256)), 256, 0, s>>>(count, (const T*)Z,
@@ -181,6 +183,7 @@ plx_status launch_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, 
         return PLX_OK;
     }
     const float inv_n = (float)(1.0 / (double)n);
+    KernelTimer kt(ctx, "softmax_ce");
     dim3 grid((unsigned)ceil_div(n, 256));
     if (dtype == PLX_F32)
         k_softmax_ce<float><<<grid, 256, 0, s>>>(n, (int)c, (const float*)Z, ldz, y, (float*)dZ, lddz, row_loss, inv_n);

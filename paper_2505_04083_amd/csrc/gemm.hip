@@ -239,6 +239,9 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
     const int tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     dim3 grid((unsigned)ceil_div(M, 128), (unsigned)ceil_div(N, 32 * tnb));
     hipStream_t s = ctx->stream;
+    char label[64];
+    snprintf(label, sizeof label, "gemm_%s<f32>[N%lld,K%lld]", bt ? "nt" : "nn", (long long)N, (long long)K);
+    KernelTimer kt(ctx, label);
 #define PLX_GEMM_CASE(T, BTV) \
     k_gemm_f32<T, BTV><<<grid, 256, 0, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, vec_a)
     if (bt) {
@@ -266,6 +269,9 @@ plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const v
     const int tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     dim3 grid((unsigned)chunks, (unsigned)ceil_div(M, 32 * tmb), (unsigned)ceil_div(N, 32 * tnb));
     hipStream_t s = ctx->stream;
+    char label[64];
+    snprintf(label, sizeof label, "gemm_tn<f32>[M%lld,N%lld]", (long long)M, (long long)N);
+    KernelTimer* kt = new KernelTimer(ctx, label);
 #define PLX_TN_CASE(TM, TN) \
     k_gemm_tn_f32<TM, TN><<<grid, 256, 0, s>>>(R, (int)M, (int)N, a, lda, b, ldb, part, rpc, vec_a, vec_b)
     switch (tmb * 10 + tnb) {
@@ -280,6 +286,8 @@ plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const v
         default: PLX_TN_CASE(4, 4); break;
     }
 #undef PLX_TN_CASE
+    delete kt;
+    KernelTimer kt2(ctx, "gemm_tn_reduce");
     // fixed-order tree over the chunk partials
     const int64_t elems = M * N;
     int64_t live = chunks, stride = 1;

@@ -2,6 +2,7 @@
 // of one GCN layer (paper Sec. 2.1, Eq. 2.1-2.7) out of the kernels in the other files.
 #include "plx_internal.h"
 
+#include <algorithm>
 #include <cstring>
 
 namespace plx {
@@ -111,10 +112,9 @@ plx_status plx_ctx_create(int device, void* hip_stream, plx_alloc_fn alloc, plx_
 
 void plx_ctx_destroy(plx_ctx* ctx) {
     if (!ctx) return;
-    if (ctx->scratch) {
-        (void)hipStreamSynchronize(ctx->stream);
-        dev_free(ctx, ctx->scratch);
-    }
+    if (!ctx->dry) (void)hipStreamSynchronize(ctx->stream);
+    for (auto& t : ctx->timed) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+    if (ctx->scratch) dev_free(ctx, ctx->scratch);
     delete ctx;
 }
 
@@ -159,13 +159,54 @@ void plx_csr_destroy(plx_ctx* ctx, plx_csr* csr) {
     delete csr;
 }
 
-plx_status plx_csr_bins(const plx_csr* csr, int transposed, int64_t d, plx_dtype dtype, int64_t* rows_subwave,
-                        int64_t* rows_wave, int64_t* rows_split) {
-    if (!csr || d <= 0 || !dtype_ok(dtype)) return PLX_ERR_INVALID;
+plx_status plx_csr_bins(const plx_csr* csr, int transposed, int64_t* rows, int64_t* entries) {
+    if (!csr) return PLX_ERR_INVALID;
     const Orient& o = csr->o[transposed ? 1 : 0];
-    if (rows_subwave) *rows_subwave = o.class_off[kSubwaveMaxClass + 1];
-    if (rows_wave) *rows_wave = o.class_off[kLongClass] - o.class_off[kSubwaveMaxClass + 1];
-    if (rows_split) *rows_split = o.class_off[kNumClasses] - o.class_off[kLongClass];
+    const int edge[4] = {0, kSubwaveMaxClass + 1, kLongClass, kNumClasses};
+    for (int b = 0; b < 3; ++b) {
+        int64_t nz = 0;
+        for (int c = edge[b]; c < edge[b + 1]; ++c) nz += o.class_nnz[c];
+        if (rows) rows[b] = o.class_off[edge[b + 1]] - o.class_off[edge[b]];
+        if (entries) entries[b] = nz;
+    }
+    return PLX_OK;
+}
+
+plx_status plx_timing_enable(plx_ctx* ctx, int on) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    ctx->timing = on != 0;
+    return PLX_OK;
+}
+
+plx_status plx_timing_report(plx_ctx* ctx, char* buf, size_t buf_bytes) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!buf || buf_bytes == 0) return fail(ctx, PLX_ERR_INVALID, "buf is NULL or empty");
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    std::vector<std::string> names;
+    std::vector<double> total;
+    std::vector<long> count;
+    for (auto& t : ctx->timed) {
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, t.start, t.stop);
+        (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+        size_t i = 0;
+        while (i < names.size() && names[i] != t.name) ++i;
+        if (i == names.size()) { names.push_back(t.name); total.push_back(0.0); count.push_back(0); }
+        total[i] += ms; count[i] += 1;
+    }
+    ctx->timed.clear();
+    std::string out;
+    for (size_t i = 0; i < names.size(); ++i) {
+        char line[256];
+        snprintf(line, sizeof line, "%s %ld %.6f\n", names[i].c_str(), count[i], total[i]);
+        out += line;
+    }
+    size_t n = std::min(out.size(), buf_bytes - 1);
+    memcpy(buf, out.data(), n);
+    buf[n] = 0;
     return PLX_OK;
 }
 

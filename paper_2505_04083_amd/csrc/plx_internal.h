@@ -27,6 +27,8 @@ struct Orient {
     float* val = nullptr;          // device [nnz]
     int32_t* row_order = nullptr;  // device [rows]: row ids sorted by length class, ascending id inside a class
     int64_t class_off[kNumClasses + 1] = {0};  // host: slot range of each class inside row_order
+    int64_t class_nnz[kNumClasses] = {0};      // host: stored entries in the rows of each class
+    int tag = 0;                               // 0 = forward orientation, 1 = its transpose (timing labels)
     // rows of class >= kLongClass, cut into segments of at most kSegLen nonzeros
     int64_t n_long = 0, n_seg = 0;
     int32_t* long_row = nullptr;   // device [n_long] row id
@@ -47,6 +49,10 @@ struct plx_ctx {
     std::string err;
     void* scratch = nullptr;  // partial sums of split rows; grown on demand
     size_t scratch_bytes = 0;
+    // optional per-kernel timing (plx_timing_enable)
+    struct Timed { std::string name; hipEvent_t start, stop; };
+    bool timing = false;
+    std::vector<Timed> timed;
 };
 
 struct plx_csr {
@@ -85,6 +91,24 @@ struct TempPool {
         void* p = dev_alloc(ctx, (count ? count : 1) * sizeof(T));
         if (p) ptrs.push_back(p);
         return static_cast<T*>(p);
+    }
+};
+
+// Brackets the kernel launches made during its lifetime with two events when timing is on.
+struct KernelTimer {
+    plx_ctx* ctx;
+    bool on;
+    plx_ctx::Timed t;
+    KernelTimer(plx_ctx* c, const std::string& name) : ctx(c), on(c->timing) {
+        if (!on) return;
+        t.name = name;
+        if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) { on = false; return; }
+        (void)hipEventRecord(t.start, ctx->stream);
+    }
+    ~KernelTimer() {
+        if (!on) return;
+        (void)hipEventRecord(t.stop, ctx->stream);
+        ctx->timed.push_back(t);
     }
 };
 

@@ -202,13 +202,17 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, T* Y
     const int64_t n_sub = o.class_off[kSubwaveMaxClass + 1];
     const int64_t n_wave = o.class_off[kLongClass] - n_sub;
     constexpr int WPB = 256 / kWave;   // wavefronts per block
+    char label[64];
+    snprintf(label, sizeof label, "<%s,G%d,VW%d>[%s]", sizeof(T) == 4 ? "f32" : "bf16", G, VW, o.tag ? "At" : "A");
     if (n_sub > 0) {
+        KernelTimer kt(ctx, std::string("spmm_subwave") + label);
         constexpr int R = kWave / G;
         int64_t blocks = ceil_div(ceil_div(n_sub, R), WPB);
         k_spmm_subwave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order, n_sub, o.rowptr, o.col, o.val, X,
                                                                          ldx, Y, ldy, d);
     }
     if (n_wave > 0) {
+        KernelTimer kt(ctx, std::string("spmm_wave") + label);
         int64_t blocks = ceil_div(n_wave, WPB);
         k_spmm_wave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + n_sub, n_wave, o.rowptr, o.col,
                                                                       o.val, X, ldx, Y, ldy, d);
@@ -216,6 +220,7 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, T* Y
     if (o.n_seg > 0) {
         PLX_TRY(ensure_scratch(ctx, (size_t)o.n_seg * G * VW * sizeof(float)));
         float* part = static_cast<float*>(ctx->scratch);
+        KernelTimer kt(ctx, std::string("spmm_split") + label);
         k_spmm_segment<T, G, VW><<<dim3((unsigned)ceil_div(o.n_seg, WPB)), 256, 0, s>>>(o.n_seg, o.seg_lo, o.seg_len,
                                                                                          o.col, o.val, X, ldx, part, d);
         int64_t total = o.n_long * d;

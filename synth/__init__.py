@@ -355,7 +355,7 @@ CONFIGS = {
     # configs[2]: ogbn-products-shaped (Table 4 row 2)
     "copurchase": GraphConfig("copurchase", 3, "rmat", n=2_449_029, n_edges=61_860_000, dims=[100, 128, 128, 47], n_classes=47),
     # configs[3]: one GPU's block of a billion-edge graph; layer is 32 -> 128 on the block
-    "shard": GraphConfig("shard", 4, "shard", m=7_000_000, k=28_000_000, n_samples=340_000_000, dims=[32, 128]),
+    "shard": GraphConfig("shard", 4, "shard", m=7_000_000, k=28_000_000, n_samples=210_000_000, dims=[32, 128]),
     # configs[4]: europe_osm-shaped thinned grid (Table 4 row 5)
     "road": GraphConfig("road", 5, "road", n=50_000_000, grid=(10_000, 5_000), keep_prob=0.53, long_frac=0.02,
                         dims=[64, 128, 16], n_classes=16),

@@ -134,8 +134,8 @@ def test_import_transpose_bit_exact(ctx):
     assert np.array_equal(gt[0].cpu().numpy(), t_rowptr)
     assert np.array_equal(gt[1].cpu().numpy(), row[order].astype(np.int32))
     assert np.array_equal(bits(gt[2]), val[order].view(np.uint32))
-    sub, wave, split = plx.plx_csr_bins(csr, False, 32)
-    assert sub + wave + split == m and split >= 1 and wave >= 1
+    (sub, wave, split), ent = plx.plx_csr_bins(csr, False)
+    assert sub + wave + split == m and split >= 1 and wave >= 1 and sum(ent) == len(col)
     # structure errors are reported, not executed
     bad = col.copy(); bad[1], bad[2] = bad[2], bad[1]
     bad_rp = rowptr.copy(); bad_rp[3] = bad_rp[4] + 1
