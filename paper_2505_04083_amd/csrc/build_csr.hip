@@ -167,20 +167,47 @@ __device__ __forceinline__ int length_class(int64_t len) {
 
 __global__ void k_row_class(int64_t rows, const int64_t* rowptr, uint8_t* cls, int32_t* ids, unsigned int* hist,
                             unsigned long long* hist_nnz) {
+    __shared__ unsigned int h[kNumClasses];
+    __shared__ unsigned long long hn[kNumClasses];
+    for (int c = threadIdx.x; c < kNumClasses; c += blockDim.x) { h[c] = 0; hn[c] = 0; }
+    __syncthreads();
     GRID_STRIDE(r, rows) {
         int64_t len = rowptr[r + 1] - rowptr[r];
         int c = length_class(len);
         cls[r] = (uint8_t)c;
         ids[r] = (int32_t)r;
-        atomicAdd(&hist[c], 1u);
-        atomicAdd(&hist_nnz[c], (unsigned long long)len);
+        atomicAdd(&h[c], 1u);
+        atomicAdd(&hn[c], (unsigned long long)len);
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < kNumClasses; c += blockDim.x)
+        if (h[c]) { atomicAdd(&hist[c], h[c]); atomicAdd(&hist_nnz[c], hn[c]); }
+}
+
+// length of the row held by each slot of the binned order (slot `rows` gets 0 for the scan)
+__global__ void k_slot_len(int64_t rows, const int32_t* row_order, const int64_t* rowptr, int32_t* len) {
+    GRID_STRIDE(s, rows + 1) {
+        if (s < rows) { int32_t r = row_order[s]; len[s] = (int32_t)(rowptr[r + 1] - rowptr[r]); }
+        else len[s] = 0;
     }
 }
 
-__global__ void k_gather_bounds(int64_t count, const int32_t* rows, const int64_t* rowptr, int64_t* lo, int64_t* hi) {
-    GRID_STRIDE(q, count) {
-        lo[q] = rowptr[rows[q]];
-        hi[q] = rowptr[rows[q] + 1];
+// Entry e of the binned storage belongs to slot s (bptr[s] <= e < bptr[s+1]); its place in the
+// canonical CSR is rowptr[row_order[s]] + (e - bptr[s]).  to_binned copies canonical -> binned,
+// otherwise binned -> canonical.
+__global__ void k_move_entries(int64_t rows, int64_t nnz, const int32_t* bptr, const int32_t* row_order,
+                               const int64_t* rowptr, const int32_t* col_in, const float* val_in, int32_t* col_out,
+                               float* val_out, int to_binned) {
+    GRID_STRIDE(e, nnz) {
+        int64_t lo = 0, hi = rows;            // last slot with bptr[slot] <= e
+        while (hi - lo > 1) {
+            int64_t mid = (lo + hi) >> 1;
+            if (bptr[mid] <= e) lo = mid; else hi = mid;
+        }
+        const int64_t canon = rowptr[row_order[lo]] + (e - bptr[lo]);
+        const int64_t src = to_binned ? canon : e, dst = to_binned ? e : canon;
+        if (col_in) col_out[dst] = col_in[src];
+        if (val_in) val_out[dst] = val_in[src];
     }
 }
 
@@ -253,7 +280,7 @@ plx_status build_bins(plx_ctx* ctx, Orient& o) {
     unsigned int h[kNumClasses] = {0};
     unsigned long long hn[kNumClasses] = {0};
     if (o.rows > 0) {
-        k_row_class<<<grid_for(o.rows), kThreads, 0, ctx->stream>>>(o.rows, o.rowptr, cls, ids, hist, hist_nnz);
+        k_row_class<<<std::min(grid_for(o.rows), 2048u), kThreads, 0, ctx->stream>>>(o.rows, o.rowptr, cls, ids, hist, hist_nnz);
         size_t bytes = 0;   // stable sort by class: ids stay ascending inside a class
         PLX_HIP(ctx, rocprim::radix_sort_pairs(nullptr, bytes, cls, cls_sorted, ids, o.row_order, (size_t)o.rows, 0, 6,
                                                ctx->stream));
@@ -271,24 +298,38 @@ plx_status build_bins(plx_ctx* ctx, Orient& o) {
         o.class_nnz[c] = (int64_t)hn[c];
     }
 
-    // long rows -> segments (few of them: done on the host)
+    // binned storage: slot pointers, then move the entries so that the rows of a bin are contiguous
+    o.bptr = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * (o.rows + 1)));
+    if (!o.bptr) return PLX_ERR_OOM;
+    {
+        int32_t* len = pool.get<int32_t>(o.rows + 1);
+        if (!len) return PLX_ERR_OOM;
+        k_slot_len<<<grid_for(o.rows + 1), kThreads, 0, ctx->stream>>>(o.rows, o.row_order, o.rowptr, len);
+        PLX_TRY(scan_exclusive<int32_t>(ctx, pool, len, o.bptr, (size_t)o.rows + 1));
+        if (o.nnz > 0) {
+            int32_t* col_b = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * o.nnz));
+            float* val_b = static_cast<float*>(dev_alloc(ctx, sizeof(float) * o.nnz));
+            if (!col_b || !val_b) { dev_free(ctx, col_b); dev_free(ctx, val_b); return PLX_ERR_OOM; }
+            k_move_entries<<<grid_for(o.nnz), kThreads, 0, ctx->stream>>>(o.rows, o.nnz, o.bptr, o.row_order, o.rowptr,
+                                                                          o.col, o.val, col_b, val_b, 1);
+            PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+            dev_free(ctx, o.col); dev_free(ctx, o.val);
+            o.col = col_b; o.val = val_b;
+        }
+    }
+
+    // long rows -> segments (few of them: done on the host), in binned coordinates
     o.n_long = o.class_off[kNumClasses] - o.class_off[kLongClass];
     o.n_seg = 0;
     if (o.n_long > 0) {
         std::vector<int32_t> rows(o.n_long);
         PLX_HIP(ctx, hipMemcpy(rows.data(), o.row_order + o.class_off[kLongClass], sizeof(int32_t) * o.n_long,
                                hipMemcpyDeviceToHost));
+        std::vector<int32_t> bp(o.n_long + 1);
+        PLX_HIP(ctx, hipMemcpy(bp.data(), o.bptr + o.class_off[kLongClass], sizeof(int32_t) * (o.n_long + 1),
+                               hipMemcpyDeviceToHost));
         std::vector<int64_t> lo(o.n_long), hi(o.n_long);
-        {
-            int64_t* dlo = pool.get<int64_t>(o.n_long);
-            int64_t* dhi = pool.get<int64_t>(o.n_long);
-            if (!dlo || !dhi) return PLX_ERR_OOM;
-            k_gather_bounds<<<grid_for(o.n_long), kThreads, 0, ctx->stream>>>(o.n_long, o.row_order + o.class_off[kLongClass],
-                                                                               o.rowptr, dlo, dhi);
-            PLX_HIP(ctx, hipMemcpyAsync(lo.data(), dlo, sizeof(int64_t) * o.n_long, hipMemcpyDeviceToHost, ctx->stream));
-            PLX_HIP(ctx, hipMemcpyAsync(hi.data(), dhi, sizeof(int64_t) * o.n_long, hipMemcpyDeviceToHost, ctx->stream));
-            PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        }
+        for (int64_t q = 0; q < o.n_long; ++q) { lo[q] = bp[q]; hi[q] = bp[q + 1]; }
         std::vector<int32_t> seg0(o.n_long + 1, 0), seg_len;
         std::vector<int64_t> seg_lo;
         for (int64_t q = 0; q < o.n_long; ++q) {
@@ -310,6 +351,14 @@ plx_status build_bins(plx_ctx* ctx, Orient& o) {
         PLX_HIP(ctx, hipMemcpy(o.seg_lo, seg_lo.data(), sizeof(int64_t) * o.n_seg, hipMemcpyHostToDevice));
         PLX_HIP(ctx, hipMemcpy(o.seg_len, seg_len.data(), sizeof(int32_t) * o.n_seg, hipMemcpyHostToDevice));
     }
+    return PLX_OK;
+}
+
+plx_status export_entries(plx_ctx* ctx, const Orient& o, int32_t* col, float* val) {
+    if (o.nnz == 0 || (!col && !val)) return PLX_OK;
+    k_move_entries<<<grid_for(o.nnz), kThreads, 0, ctx->stream>>>(o.rows, o.nnz, o.bptr, o.row_order, o.rowptr,
+                                                                  col ? o.col : nullptr, val ? o.val : nullptr, col, val, 0);
+    PLX_HIP(ctx, hipGetLastError());
     return PLX_OK;
 }
 

@@ -56,6 +56,7 @@ plx_status ensure_scratch(plx_ctx* ctx, size_t bytes) {
 
 void free_orient(plx_ctx* ctx, Orient& o) {
     dev_free(ctx, o.rowptr); dev_free(ctx, o.col); dev_free(ctx, o.val); dev_free(ctx, o.row_order);
+    dev_free(ctx, o.bptr);
     dev_free(ctx, o.long_row); dev_free(ctx, o.long_seg0); dev_free(ctx, o.seg_lo); dev_free(ctx, o.seg_len);
     o = Orient();
 }
@@ -105,6 +106,8 @@ plx_status plx_ctx_create(int device, void* hip_stream, plx_alloc_fn alloc, plx_
             delete c;
             return PLX_ERR_DEVICE;
         }
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0) c->n_cu = cus;
     }
     *out = c;
     return PLX_OK;
@@ -143,8 +146,7 @@ plx_status plx_csr_export(plx_ctx* ctx, const plx_csr* csr, int transposed, int6
     if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
     const Orient& o = csr->o[transposed ? 1 : 0];
     if (rowptr) PLX_HIP(ctx, hipMemcpyAsync(rowptr, o.rowptr, sizeof(int64_t) * (o.rows + 1), hipMemcpyDeviceToDevice, ctx->stream));
-    if (col && o.nnz) PLX_HIP(ctx, hipMemcpyAsync(col, o.col, sizeof(int32_t) * o.nnz, hipMemcpyDeviceToDevice, ctx->stream));
-    if (val && o.nnz) PLX_HIP(ctx, hipMemcpyAsync(val, o.val, sizeof(float) * o.nnz, hipMemcpyDeviceToDevice, ctx->stream));
+    PLX_TRY(export_entries(ctx, o, col, val));
     if (deg && csr->n_deg) PLX_HIP(ctx, hipMemcpyAsync(deg, csr->deg, sizeof(int64_t) * csr->n_deg, hipMemcpyDeviceToDevice, ctx->stream));
     PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
     return PLX_OK;

@@ -22,9 +22,13 @@ constexpr int64_t kSegLen = 2048;    // nonzeros per segment of a split row
 // One stored orientation of the adjacency (CSR) plus its row binning.
 struct Orient {
     int64_t rows = 0, cols = 0, nnz = 0;
-    int64_t* rowptr = nullptr;     // device [rows + 1]
-    int32_t* col = nullptr;        // device [nnz], strictly ascending inside a row
+    int64_t* rowptr = nullptr;     // device [rows + 1], canonical row pointers (row id order)
+    // Entries are STORED IN BINNED ORDER: slot s of row_order holds row row_order[s], whose entries
+    // (columns strictly ascending) are col/val[bptr[s] .. bptr[s+1]).  Rows of one length class are
+    // therefore contiguous in memory and the kernels stream the CSR arrays.
+    int32_t* col = nullptr;        // device [nnz]
     float* val = nullptr;          // device [nnz]
+    int32_t* bptr = nullptr;       // device [rows + 1]: slot pointers into col/val
     int32_t* row_order = nullptr;  // device [rows]: row ids sorted by length class, ascending id inside a class
     int64_t class_off[kNumClasses + 1] = {0};  // host: slot range of each class inside row_order
     int64_t class_nnz[kNumClasses] = {0};      // host: stored entries in the rows of each class
@@ -33,7 +37,7 @@ struct Orient {
     int64_t n_long = 0, n_seg = 0;
     int32_t* long_row = nullptr;   // device [n_long] row id
     int32_t* long_seg0 = nullptr;  // device [n_long + 1] first segment of each long row
-    int64_t* seg_lo = nullptr;     // device [n_seg] first nonzero of the segment
+    int64_t* seg_lo = nullptr;     // device [n_seg] first entry of the segment (binned storage)
     int32_t* seg_len = nullptr;    // device [n_seg] nonzeros in the segment
 };
 
@@ -43,6 +47,7 @@ struct plx_ctx {
     int device = -1;
     bool dry = false;  // validate-only context
     hipStream_t stream = nullptr;
+    int n_cu = 256;    // compute units of the device
     plx_alloc_fn alloc = nullptr;
     plx_free_fn release = nullptr;
     void* user = nullptr;
@@ -116,6 +121,8 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // set-up: fills the binning fields of `o` from its CSR arrays (waits on the stream)
 plx_status build_bins(plx_ctx* ctx, Orient& o);
+// copies the entries of `o` back into canonical CSR order (either output may be NULL)
+plx_status export_entries(plx_ctx* ctx, const Orient& o, int32_t* col, float* val);
 void free_orient(plx_ctx* ctx, Orient& o);
 
 // kernels' host launchers (all asynchronous on ctx->stream)

@@ -70,7 +70,10 @@ __device__ __forceinline__ void store_vec(T* p, const float (&r)[VW], int valid)
     }
 }
 
-constexpr int kUnroll = 8;
+#ifndef PLX_SPMM_UNROLL
+#define PLX_SPMM_UNROLL 8
+#endif
+constexpr int kUnroll = PLX_SPMM_UNROLL;
 
 // acc += sum over entries e = first, first + stride, ... < hi of val[e] * X[col[e], c0 .. c0+VW)
 template <typename T, int VW>
@@ -101,27 +104,80 @@ __device__ __forceinline__ void gather_accumulate(int64_t first, int64_t hi, int
     }
 }
 
+// Tuning switches of the short-row kernel (compile time).
+#ifndef PLX_SUB_STAGED
+#define PLX_SUB_STAGED 1      // 1: a group loads its (column, value) pairs once, coalesced, and shares them by lane shuffles
+#endif
+#ifndef PLX_SUB_PERSIST
+#define PLX_SUB_PERSIST 32    // N > 0: grid of N workgroups per CU, every group of lanes walks several rows
+#endif
+
+// Same sum as gather_accumulate for a contiguous entry range, but the G lanes of a group fetch
+// up to CH entries with one coalesced load each for columns and values and pass them round by
+// shuffles, instead of every lane loading every entry.  All lanes of the group must call it.
+template <typename T, int G, int VW>
+__device__ __forceinline__ void gather_staged(int64_t lo, int64_t hi, const int32_t* __restrict__ col,
+                                              const float* __restrict__ val, const T* __restrict__ xb, int64_t ldx,
+                                              bool active, int lane, float (&acc)[VW]) {
+    constexpr int CH = G < 8 ? G : 8;
+    const int j = lane % G, gbase = lane - j;
+    for (int64_t e = lo; e < hi; e += CH) {
+        const int n = (hi - e) < CH ? (int)(hi - e) : CH;
+        int32_t cj = 0;
+        float vj = 0.f;
+        if (j < n) { cj = col[e + j]; vj = val[e + j]; }
+        int32_t c[CH];
+        float v[CH];
+#pragma unroll
+        for (int t = 0; t < CH; ++t) { c[t] = __shfl(cj, gbase + t, kWave); v[t] = __shfl(vj, gbase + t, kWave); }
+        float x[CH][VW];
+#pragma unroll
+        for (int t = 0; t < CH; ++t) {
+            if (active && t < n) {
+                load_vec<T, VW>(xb + (int64_t)c[t] * ldx, x[t]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < VW; ++i) x[t][i] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < CH; ++t)
+#pragma unroll
+            for (int i = 0; i < VW; ++i) acc[i] = fmaf(v[t], x[t][i], acc[i]);
+    }
+}
+
 // Short rows: one group of G lanes per row, 64/G rows per wavefront.
 template <typename T, int G, int VW>
 __global__ __launch_bounds__(256) void k_spmm_subwave(const int32_t* __restrict__ row_order, int64_t count,
-                                                      const int64_t* __restrict__ rowptr,
+                                                      const int32_t* __restrict__ bptr,
                                                       const int32_t* __restrict__ col, const float* __restrict__ val,
                                                       const T* __restrict__ X, int64_t ldx, T* __restrict__ Y,
                                                       int64_t ldy, int d) {
     constexpr int R = kWave / G;
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    const int64_t slot = wave * R + lane / G;
-    if (slot >= count) return;
     const int c0 = (lane % G) * VW;
-    if (c0 >= d) return;
-    const int32_t row = row_order[slot];
-    const int64_t lo = rowptr[row], hi = rowptr[row + 1];
-    float acc[VW];
+    const bool active = c0 < d;
+#if PLX_SUB_PERSIST
+    const int64_t stride = (int64_t)gridDim.x * (blockDim.x / kWave) * R;
+#else
+    const int64_t stride = count;   // one row per group
+#endif
+    for (int64_t slot = wave * R + lane / G; slot < count; slot += stride) {
+        const int32_t row = row_order[slot];
+        const int64_t lo = bptr[slot], hi = bptr[slot + 1];
+        float acc[VW];
 #pragma unroll
-    for (int i = 0; i < VW; ++i) acc[i] = 0.f;
-    gather_accumulate<T, VW>(lo, hi, 1, col, val, X + c0, ldx, acc);
-    store_vec<T, VW>(Y + (int64_t)row * ldy + c0, acc, d - c0);
+        for (int i = 0; i < VW; ++i) acc[i] = 0.f;
+#if PLX_SUB_STAGED
+        if constexpr (G >= 8) gather_staged<T, G, VW>(lo, hi, col, val, X + c0, ldx, active, lane, acc);
+        else if (active) gather_accumulate<T, VW>(lo, hi, 1, col, val, X + c0, ldx, acc);
+#else
+        if (active) gather_accumulate<T, VW>(lo, hi, 1, col, val, X + c0, ldx, acc);
+#endif
+        if (active) store_vec<T, VW>(Y + (int64_t)row * ldy + c0, acc, d - c0);
+    }
 }
 
 // butterfly sum across the 64/G groups of a wavefront; every lane ends with the total
@@ -136,7 +192,7 @@ __device__ __forceinline__ void reduce_groups(float (&acc)[VW]) {
 // Medium rows: one wavefront per row.
 template <typename T, int G, int VW>
 __global__ __launch_bounds__(256) void k_spmm_wave(const int32_t* __restrict__ rows, int64_t count,
-                                                   const int64_t* __restrict__ rowptr,
+                                                   const int32_t* __restrict__ bptr,
                                                    const int32_t* __restrict__ col, const float* __restrict__ val,
                                                    const T* __restrict__ X, int64_t ldx, T* __restrict__ Y,
                                                    int64_t ldy, int d) {
@@ -147,7 +203,7 @@ __global__ __launch_bounds__(256) void k_spmm_wave(const int32_t* __restrict__ r
     const int g = lane / G, c0 = (lane % G) * VW;
     const bool active = c0 < d;
     const int32_t row = rows[slot];
-    const int64_t lo = rowptr[row], hi = rowptr[row + 1];
+    const int64_t lo = bptr[slot], hi = bptr[slot + 1];
     float acc[VW];
 #pragma unroll
     for (int i = 0; i < VW; ++i) acc[i] = 0.f;
@@ -204,17 +260,21 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, T* Y
     constexpr int WPB = 256 / kWave;   // wavefronts per block
     char label[64];
     snprintf(label, sizeof label, "<%s,G%d,VW%d>[%s]", sizeof(T) == 4 ? "f32" : "bf16", G, VW, o.tag ? "At" : "A");
-    if (n_sub > 0) {
+    const int64_t sub_count = n_sub;
+    if (sub_count > 0) {
         KernelTimer kt(ctx, std::string("spmm_subwave") + label);
         constexpr int R = kWave / G;
-        int64_t blocks = ceil_div(ceil_div(n_sub, R), WPB);
-        k_spmm_subwave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order, n_sub, o.rowptr, o.col, o.val, X,
+        int64_t blocks = ceil_div(ceil_div(sub_count, R), WPB);
+#if PLX_SUB_PERSIST
+        blocks = std::min<int64_t>(blocks, (int64_t)ctx->n_cu * PLX_SUB_PERSIST);
+#endif
+        k_spmm_subwave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order, sub_count, o.bptr, o.col, o.val, X,
                                                                          ldx, Y, ldy, d);
     }
     if (n_wave > 0) {
         KernelTimer kt(ctx, std::string("spmm_wave") + label);
         int64_t blocks = ceil_div(n_wave, WPB);
-        k_spmm_wave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + n_sub, n_wave, o.rowptr, o.col,
+        k_spmm_wave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + n_sub, n_wave, o.bptr + n_sub, o.col,
                                                                       o.val, X, ldx, Y, ldy, d);
     }
     if (o.n_seg > 0) {
