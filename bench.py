@@ -88,13 +88,13 @@ def main():
     order = plx.PLX_ORDER_AGG_FIRST
     ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, plx.PLX_F32, plx.PLX_ACT_RELU, order),
                      dtype=torch.uint8, device=dev)
-    Z = torch.empty(cfg.m, dout, device=dev); F = torch.empty(cfg.m, dout, device=dev)
+    F = torch.empty(cfg.m, dout, device=dev)      # only the activated output is stored (its sign serves Eq. 2.4)
     saved = torch.empty(cfg.m, din, device=dev)
     dX = torch.empty(cfg.k, din, device=dev); dW = torch.empty(din, dout, device=dev)
 
     def step():
-        plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, Z, F, saved, ws, act=plx.PLX_ACT_RELU, order=order)
-        plx.plx_gcn_layer_bwd(ctx, csr, False, X, W, Z, dF, saved, dX, dW, ws, act=plx.PLX_ACT_RELU, order=order)
+        plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, None, F, saved, ws, act=plx.PLX_ACT_RELU, order=order)
+        plx.plx_gcn_layer_bwd(ctx, csr, False, X, W, F, dF, saved, dX, dW, ws, act=plx.PLX_ACT_RELU, order=order)
 
     if args.copy_ref:
         # 2^30 fp32 read + 2^30 fp32 written by one plain copy kernel: the known-size dispatch the
@@ -131,6 +131,8 @@ def main():
             b, fl = spmm_bytes(rows[i], ent[i], din), 2 * ent[i] * din
         elif name.startswith("gemm_nn"):
             b, fl = 4 * (m * din + din * dout + m * dout), 2 * m * din * dout
+        elif name.startswith("bwd_dense"):       # reads dF, F (mask), saved; writes dS; two products
+            b, fl = 4 * (2 * m * dout + 2 * m * din + din * dout), 4 * m * din * dout
         elif name.startswith("gemm_nt"):
             b, fl = 4 * (m * dout + din * dout + m * din), 2 * m * din * dout
         elif name.startswith("gemm_tn<"):

@@ -176,15 +176,19 @@ PLX_API plx_status plx_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void
  * != 0, odd layers), of shape ma x ka.  H is ka x din, W is din x dout (fp32), Z and F are
  * ma x dout.
  *
- * plx_gcn_layer_fwd:  Z = A H W (pre-activation, always written); F = act(Z) if F != NULL.
+ * plx_gcn_layer_fwd:  Z = A H W (pre-activation) if Z != NULL; F = act(Z) if F != NULL; at least one
+ *   of them must be given.  Storing only F saves one pass over the output: for ReLU the backward
+ *   call accepts F in place of Z (F > 0 exactly where Z > 0).
  *   order AGG_FIRST : saved[ma x din] = A H (Eq. 2.1) then Z = saved W (Eq. 2.2); `saved` must
  *                     be given and is needed again by the backward call.
  *   order COMBINE_FIRST: T[ka x dout] = H W in the workspace, then Z = A T; `saved` is unused.
  *   order AUTO      : AGG_FIRST if din < dout, else COMBINE_FIRST (so `saved` must be given
  *                     whenever din < dout).
  * plx_gcn_layer_bwd:  given dF (gradient wrt F, or wrt Z when act == NONE) computes
- *   dZ = dF * [Z > 0] (Eq. 2.4), dW[din x dout] (fp32, Eq. 2.5) and, unless dH == NULL,
- *   dH[ka x din] (Eq. 2.6 + 2.7; the gradient wrt the layer input H).
+ *   dZ = dF * [Z > 0] (Eq. 2.4; `Z` may be the pre-activation or the ReLU output, only its sign is
+ *   used; ignored when act == NONE), dW[din x dout] (fp32, Eq. 2.5) and, unless dH == NULL,
+ *   dH[ka x din] (Eq. 2.6 + 2.7; the gradient wrt the layer input H).  H is read only in
+ *   combine-first order, `saved` only in aggregate-first order.
  * ws: device workspace of at least plx_gcn_layer_workspace(...) bytes (same arguments), used
  * by both calls; its contents need not survive between them. */
 PLX_API size_t plx_gcn_layer_workspace(const plx_csr* csr, int transposed_A, int64_t din, int64_t dout,

@@ -1,0 +1,208 @@
+// Fused dense part of a GCN layer's backward pass (paper Eq. 2.4, 2.5, 2.6) on the matrix cores.
+//
+// With Q' = Q * [Zm > 0] (Eq. 2.4; no mask when Zm is NULL) one pass over the rows computes
+//     dOut[R x Mp] = Q' W^T          (Eq. 2.6)
+//     dW  [Mp x N] = P^T Q'          (Eq. 2.5, reduction over the R rows)
+// so the gradient tile Q' is read from HBM once (from its two sources), never written, and
+// serves both products from LDS.  P is the aggregated input (aggregate-first order) or the layer
+// input (combine-first order); Q is the incoming gradient (or A^T dZ).  All three tall operands
+// are streamed exactly once: the kernel is bound by that stream.
+//
+// Work split: a workgroup (4 wavefronts) owns a chunk of rows and walks it in tiles of 64 rows.
+//   dOut tile (64 x Mp): v_mfma_f32_16x16x4_f32, wavefront w owns rows 16w..16w+15, all columns;
+//       lane l supplies a = Q'[16w + l%16][k + l/16], b = W[16c + l%16][k + l/16] and receives
+//       acc[r] = dOut[16w + 4*(l/16) + r][16c + l%16].
+//   dW (Mp x N): v_mfma_f32_32x32x2_f32 over the 64 rows of the tile, accumulated in registers for
+//       the whole chunk; block q of the (Mp/32) x (N/32) grid belongs to wavefront q % 4.
+// Chunk partials of dW are summed afterwards in a fixed order (bit-reproducible).
+#include "plx_internal.h"
+
+#include <algorithm>
+
+namespace plx {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kTR = 64;   // rows per tile
+
+// global (rows r0.., cols 0..ncols) -> LDS tile [kTR][COLS + 4], zero padded; optional ReLU mask source
+template <int COLS>
+__device__ __forceinline__ void stage_tile(float (*dst)[COLS + 4], const float* __restrict__ src, int64_t ld,
+                                           const float* __restrict__ mask, int64_t ldm, int64_t r0, int64_t r_end,
+                                           int ncols, bool vec, int tid) {
+    constexpr int Q4 = COLS / 4;
+#pragma unroll 4
+    for (int f = tid; f < kTR * Q4; f += 256) {
+        const int r = f / Q4, q = f % Q4;
+        const int64_t gr = r0 + r;
+        const int gc = 4 * q;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gr < r_end && gc < ncols) {
+            const float* p = src + gr * ld + gc;
+            if (vec && gc + 3 < ncols) {
+                v = *reinterpret_cast<const float4*>(p);
+                if (mask) {
+                    const float4 z = *reinterpret_cast<const float4*>(mask + gr * ldm + gc);
+                    v.x = z.x > 0.f ? v.x : 0.f; v.y = z.y > 0.f ? v.y : 0.f;
+                    v.z = z.z > 0.f ? v.z : 0.f; v.w = z.w > 0.f ? v.w : 0.f;
+                }
+            } else {
+                const float* z = mask ? mask + gr * ldm + gc : nullptr;
+                v.x = (!z || z[0] > 0.f) ? p[0] : 0.f;
+                if (gc + 1 < ncols) v.y = (!z || z[1] > 0.f) ? p[1] : 0.f;
+                if (gc + 2 < ncols) v.z = (!z || z[2] > 0.f) ? p[2] : 0.f;
+                if (gc + 3 < ncols) v.w = (!z || z[3] > 0.f) ? p[3] : 0.f;
+            }
+        }
+        *reinterpret_cast<float4*>(&dst[r][gc]) = v;
+    }
+}
+
+template <int TMB, int TNB>   // Mp <= 32*TMB, N <= 32*TNB
+__global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N, const float* __restrict__ P, int64_t ldp,
+                                                       const float* __restrict__ Q, int64_t ldq,
+                                                       const float* __restrict__ Zm, int64_t ldz,
+                                                       const float* __restrict__ W, int64_t ldw,
+                                                       float* __restrict__ dOut, int64_t ldo, float* __restrict__ part,
+                                                       int64_t rows_per_chunk, int vec_p, int vec_q) {
+    constexpr int MP = 32 * TMB, NP = 32 * TNB;
+    constexpr int NBLK = (TMB * TNB + 3) / 4;     // 32x32 blocks of dW per wavefront
+    constexpr int NCB = MP / 16;                   // 16-column blocks of dOut
+    extern __shared__ __align__(16) float smem[];
+    float (*Qs)[NP + 4] = reinterpret_cast<float (*)[NP + 4]>(smem);
+    float (*Ps)[MP + 4] = reinterpret_cast<float (*)[MP + 4]>(smem + kTR * (NP + 4));
+    float (*Ws)[NP + 4] = reinterpret_cast<float (*)[NP + 4]>(smem + kTR * (NP + 4) + kTR * (MP + 4));
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int l32 = lane & 31, lh = lane >> 5, l16 = lane & 15, lq = lane >> 4;
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_chunk;
+    const int64_t r_end = (r_begin + rows_per_chunk < R) ? r_begin + rows_per_chunk : R;
+
+    for (int f = tid; f < MP * NP; f += 256) {
+        const int i = f / NP, n = f % NP;
+        Ws[i][n] = (i < Mp && n < N) ? W[(int64_t)i * ldw + n] : 0.f;
+    }
+
+    floatx16 acc_w[NBLK];
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_w[t][r] = 0.f;
+
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += kTR) {
+        stage_tile<NP>(Qs, Q, ldq, Zm, ldz, r0, r_end, N, vec_q, tid);
+        stage_tile<MP>(Ps, P, ldp, nullptr, 0, r0, r_end, Mp, vec_p, tid);
+        __syncthreads();
+
+        if (dOut) {                                                    // Eq. 2.6 on this tile
+            floatx4 acc_o[NCB];
+#pragma unroll
+            for (int c = 0; c < NCB; ++c) acc_o[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+            for (int k = 0; k < NP; k += 4) {
+                const float a = Qs[16 * w + l16][k + lq];
+#pragma unroll
+                for (int c = 0; c < NCB; ++c)
+                    acc_o[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Ws[16 * c + l16][k + lq], acc_o[c], 0, 0, 0);
+            }
+#pragma unroll
+            for (int c = 0; c < NCB; ++c) {
+                const int gc = 16 * c + l16;
+                if (gc < Mp) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int64_t gr = r0 + 16 * w + 4 * lq + r;
+                        if (gr < r_end) dOut[gr * ldo + gc] = acc_o[c][r];
+                    }
+                }
+            }
+        }
+
+#pragma unroll 4
+        for (int kk = 0; kk < kTR; kk += 2) {                          // Eq. 2.5, partial over this tile
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) {
+                const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
+                if (q < TMB * TNB)
+                    acc_w[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(Ps[kk + lh][32 * bi + l32], Qs[kk + lh][32 * bj + l32],
+                                                                    acc_w[t], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+    }
+
+    float* out = part + (int64_t)blockIdx.x * Mp * N;
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t) {
+        const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
+        if (q >= TMB * TNB) continue;
+        const int gn = 32 * bj + l32;
+        if (gn >= N) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int gm = 32 * bi + 8 * (r / 4) + 4 * lh + (r % 4);
+            if (gm < Mp) out[(int64_t)gm * N + gn] = acc_w[t][r];
+        }
+    }
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+template <int TMB, int TNB>
+plx_status run(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
+               const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
+               int64_t rpc, int64_t chunks) {
+    constexpr int MP = 32 * TMB, NP = 32 * TNB;
+    const size_t lds = sizeof(float) * (kTR * (NP + 4) + kTR * (MP + 4) + MP * (NP + 4));
+    const int vec_p = aligned16(P) && ldp % 4 == 0;
+    const int vec_q = aligned16(Q) && ldq % 4 == 0 && (!Zm || (aligned16(Zm) && ldz % 4 == 0));
+    auto kern = k_bwd_dense_f32<TMB, TNB>;
+    if (lds > 48 * 1024)
+        PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    kern<<<dim3((unsigned)chunks), 256, lds, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc,
+                                                           vec_p, vec_q);
+    PLX_HIP(ctx, hipGetLastError());
+    return PLX_OK;
+}
+
+}  // namespace
+
+bool bwd_dense_supported(int64_t Mp, int64_t N, plx_dtype dtype) { return dtype == PLX_F32 && Mp <= 128 && N <= 128; }
+
+plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, const void* P, int64_t ldp, const void* Q,
+                            int64_t ldq, const void* Zm, int64_t ldz, const float* W, int64_t ldw, void* dOut, int64_t ldo,
+                            float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes) {
+    if (!bwd_dense_supported(Mp, N, dtype)) return fail(ctx, PLX_ERR_INTERNAL, "fused backward called outside its range");
+    if (ws_bytes < gemm_tn_workspace(R, Mp, N)) return fail(ctx, PLX_ERR_SHAPE, "workspace too small");
+    const int64_t rpc = tn_rows_per_chunk(R, Mp, N);
+    const int64_t chunks = std::max<int64_t>(1, ceil_div(R, rpc));
+    float* part = static_cast<float*>(ws);
+    const int tmb = Mp <= 32 ? 1 : (Mp <= 64 ? 2 : 4), tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
+    char label[64];
+    snprintf(label, sizeof label, "bwd_dense<f32>[M%lld,N%lld]", (long long)Mp, (long long)N);
+    plx_status st;
+    {
+        KernelTimer kt(ctx, label);
+#define PLX_BD(TM, TN)                                                                                              \
+    st = run<TM, TN>(ctx, R, (int)Mp, (int)N, (const float*)P, ldp, (const float*)Q, ldq, (const float*)Zm, ldz, W, ldw, \
+                     (float*)dOut, ldo, part, rpc, chunks)
+        switch (tmb * 10 + tnb) {
+            case 11: PLX_BD(1, 1); break;
+            case 12: PLX_BD(1, 2); break;
+            case 14: PLX_BD(1, 4); break;
+            case 21: PLX_BD(2, 1); break;
+            case 22: PLX_BD(2, 2); break;
+            case 24: PLX_BD(2, 4); break;
+            case 41: PLX_BD(4, 1); break;
+            case 42: PLX_BD(4, 2); break;
+            default: PLX_BD(4, 4); break;
+        }
+#undef PLX_BD
+    }
+    PLX_TRY(st);
+    return reduce_partials(ctx, part, chunks, Mp, N, dW, lddw);
+}
+
+}  // namespace plx

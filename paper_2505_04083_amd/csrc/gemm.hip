@@ -32,7 +32,7 @@ __device__ __forceinline__ floatx16 mfma32(float a, float b, floatx16 c) {
 template <int TNB, bool BT>
 __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const float* __restrict__ A, int64_t lda,
                                                   const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
-                                                  int64_t ldc, int vec_a) {
+                                                  int64_t ldc, float* __restrict__ F, int64_t ldf, int vec_a) {
     constexpr int TMB = 4;
     constexpr int BM = 32 * TMB, BN = 32 * TNB;
     constexpr int NBLK = (TMB * TNB + 3) / 4;         // blocks per wavefront
@@ -101,7 +101,11 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int64_t gr = m0 + 32 * bi + 8 * (r / 4) + 4 * lh + (r % 4);
-            if (gr < M) C[gr * ldc + gn] = acc[t][r];
+            if (gr < M) {
+                const float v = acc[t][r];
+                if (C) C[gr * ldc + gn] = v;
+                if (F) F[gr * ldf + gn] = v > 0.f ? v : 0.f;      // Eq. 2.3 fused into the store
+            }
         }
     }
 }
@@ -213,16 +217,34 @@ __global__ __launch_bounds__(256) void k_reduce_partials(float* __restrict__ par
     else part[g * kFan * stride * elems + e] = s;
 }
 
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
 int64_t tn_rows_per_chunk(int64_t R, int64_t M, int64_t N) {
     const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 128);
     const int64_t want_chunks = std::max<int64_t>(1, 2048 / tiles);
     int64_t rows = std::max<int64_t>(512, ceil_div(R, want_chunks));
-    return ceil_div(rows, kBK) * kBK;
+    return ceil_div(rows, 64) * 64;
 }
 
-bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
-
-}  // namespace
+// fixed-order tree over `chunks` partial M x N tiles; the total goes to C
+plx_status reduce_partials(plx_ctx* ctx, float* part, int64_t chunks, int64_t M, int64_t N, float* C, int64_t ldc) {
+    KernelTimer kt(ctx, "dw_partials_reduce");
+    const int64_t elems = M * N;
+    int64_t live = chunks, stride = 1;
+    while (true) {
+        const int64_t groups = ceil_div(live, kFan);
+        const bool last = groups == 1;
+        dim3 rgrid((unsigned)ceil_div(elems, 256), (unsigned)groups);
+        k_reduce_partials<<<rgrid, 256, 0, ctx->stream>>>(part, elems, live, stride, last ? C : nullptr, (int)N, ldc);
+        if (last) break;
+        live = groups;
+        stride *= kFan;
+    }
+    PLX_HIP(ctx, hipGetLastError());
+    return PLX_OK;
+}
 
 size_t gemm_tn_workspace(int64_t R, int64_t M, int64_t N) {
     const int64_t chunks = std::max<int64_t>(1, ceil_div(R, tn_rows_per_chunk(R, M, N)));
@@ -230,11 +252,12 @@ size_t gemm_tn_workspace(int64_t R, int64_t M, int64_t N) {
 }
 
 plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
-                       const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype) {
+                       const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype, void* Fact, int64_t ldf) {
     if (dtype != PLX_F32) return fail(ctx, PLX_ERR_UNSUPPORTED, "bf16 dense products are not built yet");
     if (N >= (int64_t(1) << 20) || K >= (int64_t(1) << 30)) return fail(ctx, PLX_ERR_UNSUPPORTED, "N or K too large");
     const float* a = static_cast<const float*>(A);
     float* c = static_cast<float*>(C);
+    float* fa = static_cast<float*>(Fact);
     const int vec_a = aligned16(A) && lda % 4 == 0;
     const int tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     dim3 grid((unsigned)ceil_div(M, 128), (unsigned)ceil_div(N, 32 * tnb));
@@ -243,7 +266,7 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
     snprintf(label, sizeof label, "gemm_%s<f32>[N%lld,K%lld]", bt ? "nt" : "nn", (long long)N, (long long)K);
     KernelTimer kt(ctx, label);
 #define PLX_GEMM_CASE(T, BTV) \
-    k_gemm_f32<T, BTV><<<grid, 256, 0, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, vec_a)
+    k_gemm_f32<T, BTV><<<grid, 256, 0, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf, vec_a)
     if (bt) {
         if (tnb == 1) PLX_GEMM_CASE(1, true); else if (tnb == 2) PLX_GEMM_CASE(2, true); else PLX_GEMM_CASE(4, true);
     } else {
@@ -287,21 +310,8 @@ plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const v
     }
 #undef PLX_TN_CASE
     delete kt;
-    KernelTimer kt2(ctx, "gemm_tn_reduce");
-    // fixed-order tree over the chunk partials
-    const int64_t elems = M * N;
-    int64_t live = chunks, stride = 1;
-    while (true) {
-        const int64_t groups = ceil_div(live, kFan);
-        const bool last = groups == 1;
-        dim3 rgrid((unsigned)ceil_div(elems, 256), (unsigned)groups);
-        k_reduce_partials<<<rgrid, 256, 0, s>>>(part, elems, live, stride, last ? C : nullptr, (int)N, ldc);
-        if (last) break;
-        live = groups;
-        stride *= kFan;
-    }
     PLX_HIP(ctx, hipGetLastError());
-    return PLX_OK;
+    return reduce_partials(ctx, part, chunks, M, N, C, ldc);
 }
 
 }  // namespace plx

@@ -373,8 +373,9 @@ plx_status plx_gcn_layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
     PLX_TRY(layer_common_checks(ctx, csr, din, dout, dtype, act, order));
     const Orient& a = csr->o[transposed_A ? 1 : 0];
     order = resolve_order(order, din, dout);
-    if (!H || !W || !Z) return fail(ctx, PLX_ERR_INVALID, "H, W or Z is NULL");
-    if (ldh < din || ldw < dout || ldz < dout || (F && ldf < dout))
+    if (!H || !W) return fail(ctx, PLX_ERR_INVALID, "H or W is NULL");
+    if (!Z && !F) return fail(ctx, PLX_ERR_INVALID, "Z and F are both NULL");
+    if (ldh < din || ldw < dout || (Z && ldz < dout) || (F && ldf < dout))
         return fail(ctx, PLX_ERR_SHAPE, "leading dimension too small");
     if (order == PLX_ORDER_AGG_FIRST) {
         if (!saved) return fail(ctx, PLX_ERR_INVALID, "aggregate-first order needs the `saved` buffer");
@@ -385,22 +386,26 @@ plx_status plx_gcn_layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
         return fail(ctx, PLX_ERR_SHAPE, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, w.total);
     if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
 
+    // The last product of the layer stores the pre-activation (if wanted) and the activated
+    // output (Eq. 2.3) from the same registers.
+    void* plain = Z;
+    void* activated = nullptr;
+    if (F) {
+        if (act == PLX_ACT_RELU) activated = F;
+        else if (!Z) plain = F;              // no activation and only F wanted: F is the plain output
+    }
+    const int64_t ld_plain = plain == Z ? ldz : ldf;
     if (order == PLX_ORDER_AGG_FIRST) {
         PLX_TRY(launch_spmm(ctx, a, H, ldh, saved, ldsaved, din, dtype));                    // Eq. 2.1
-        PLX_TRY(launch_gemm(ctx, false, a.rows, dout, din, saved, ldsaved, W, ldw, Z, ldz, dtype));  // Eq. 2.2
+        PLX_TRY(launch_gemm(ctx, false, a.rows, dout, din, saved, ldsaved, W, ldw, plain, ld_plain, dtype, activated, ldf));  // Eq. 2.2 (+2.3)
     } else {
         void* T = static_cast<char*>(ws) + w.off_a;
         PLX_TRY(launch_gemm(ctx, false, a.cols, dout, din, H, ldh, W, ldw, T, dout, dtype));
-        PLX_TRY(launch_spmm(ctx, a, T, dout, Z, ldz, dout, dtype));
+        PLX_TRY(launch_spmm(ctx, a, T, dout, plain, ld_plain, dout, dtype, activated, ldf));
     }
-    if (F) {
-        if (act == PLX_ACT_RELU) {
-            PLX_TRY(launch_relu(ctx, a.rows, dout, Z, ldz, F, ldf, dtype));                  // Eq. 2.3
-        } else if (F != Z) {
-            PLX_HIP(ctx, hipMemcpy2DAsync(F, ldf * elt_size(dtype), Z, ldz * elt_size(dtype), dout * elt_size(dtype),
-                                          a.rows, hipMemcpyDeviceToDevice, ctx->stream));
-        }
-    }
+    if (F && act == PLX_ACT_NONE && Z && F != Z)
+        PLX_HIP(ctx, hipMemcpy2DAsync(F, ldf * elt_size(dtype), Z, ldz * elt_size(dtype), dout * elt_size(dtype), a.rows,
+                                      hipMemcpyDeviceToDevice, ctx->stream));
     return PLX_OK;
 }
 
@@ -432,15 +437,38 @@ plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
     if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
 
     char* base = static_cast<char*>(ws);
+    void* tn_ws = base + w.off_tn;
+    size_t tn_bytes = w.total - w.off_tn;
+    const void* mask = act == PLX_ACT_RELU ? Z : nullptr;
+    if (bwd_dense_supported(din, dout, dtype)) {
+        // Eq. 2.4 is applied while the gradient tile is loaded; it is never written back
+        if (order == PLX_ORDER_AGG_FIRST) {
+            void* dS = dH ? base + w.off_a : nullptr;
+            PLX_TRY(launch_bwd_dense(ctx, a.rows, din, dout, saved, ldsaved, dF, lddf, mask, ldz, W, ldw, dS, din, dW, lddw,
+                                     dtype, tn_ws, tn_bytes));                               // Eq. 2.4 + 2.5 + 2.6
+            if (dH) PLX_TRY(launch_spmm(ctx, at, dS, din, dH, lddh, din, dtype));            // Eq. 2.7
+        } else {
+            const void* dZ = dF;
+            int64_t lddz = lddf;
+            if (mask) {
+                void* buf = base + w.off_dz;
+                PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, dout, dtype));
+                dZ = buf; lddz = dout;
+            }
+            void* G = base + w.off_a;
+            PLX_TRY(launch_spmm(ctx, at, dZ, lddz, G, dout, dout, dtype));                   // A^T dZ
+            PLX_TRY(launch_bwd_dense(ctx, a.cols, din, dout, H, ldh, G, dout, nullptr, 0, W, ldw, dH, lddh, dW, lddw, dtype,
+                                     tn_ws, tn_bytes));
+        }
+        return PLX_OK;
+    }
     const void* dZ = dF;
     int64_t lddz = lddf;
-    if (act == PLX_ACT_RELU) {                                                               // Eq. 2.4
+    if (mask) {                                                                              // Eq. 2.4
         void* buf = base + w.off_dz;
         PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, dout, dtype));
         dZ = buf; lddz = dout;
     }
-    void* tn_ws = base + w.off_tn;
-    size_t tn_bytes = w.total - w.off_tn;
     if (order == PLX_ORDER_AGG_FIRST) {
         PLX_TRY(launch_gemm_tn(ctx, a.rows, din, dout, saved, ldsaved, dZ, lddz, dW, lddw, dtype, tn_ws, tn_bytes));  // Eq. 2.5
         if (dH) {

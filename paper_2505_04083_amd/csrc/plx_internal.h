@@ -126,11 +126,21 @@ plx_status export_entries(plx_ctx* ctx, const Orient& o, int32_t* col, float* va
 void free_orient(plx_ctx* ctx, Orient& o);
 
 // kernels' host launchers (all asynchronous on ctx->stream)
+// Y = A X (Y may be NULL); if Yact != NULL it also receives max(A X, 0)
 plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* Y, int64_t ldy,
-                       int64_t d, plx_dtype dtype);
+                       int64_t d, plx_dtype dtype, void* Yact = nullptr, int64_t ldyact = 0);
+// C = A op(B) (C may be NULL); if Fact != NULL it also receives max(C, 0)
 plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
-                       const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype);
+                       const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype, void* Fact = nullptr,
+                       int64_t ldf = 0);
 size_t gemm_tn_workspace(int64_t R, int64_t M, int64_t N);
+int64_t tn_rows_per_chunk(int64_t R, int64_t M, int64_t N);
+plx_status reduce_partials(plx_ctx* ctx, float* part, int64_t chunks, int64_t M, int64_t N, float* C, int64_t ldc);
+// fused Eq. 2.4 + 2.5 + 2.6: dOut = (Q*[Zm>0]) W^T (dOut may be NULL), dW = P^T (Q*[Zm>0]); Zm may be NULL
+bool bwd_dense_supported(int64_t Mp, int64_t N, plx_dtype dtype);
+plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, const void* P, int64_t ldp, const void* Q,
+                            int64_t ldq, const void* Zm, int64_t ldz, const float* W, int64_t ldw, void* dOut, int64_t ldo,
+                            float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes);
 plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const void* A, int64_t lda,
                           const void* B, int64_t ldb, float* C, int64_t ldc, plx_dtype dtype, void* ws, size_t ws_bytes);
 plx_status launch_relu(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, void* F, int64_t ldf,

@@ -70,6 +70,22 @@ __device__ __forceinline__ void store_vec(T* p, const float (&r)[VW], int valid)
     }
 }
 
+// Where a finished output row goes: Y (plain) and / or Yact (after ReLU, Eq. 2.3); either may be NULL.
+template <typename T> struct Out {
+    T* y; int64_t ldy;
+    T* ya; int64_t ldya;
+};
+
+template <typename T, int VW>
+__device__ __forceinline__ void emit(const Out<T>& o, int64_t row, int c0, float (&acc)[VW], int valid) {
+    if (o.y) store_vec<T, VW>(o.y + row * o.ldy + c0, acc, valid);
+    if (o.ya) {
+#pragma unroll
+        for (int i = 0; i < VW; ++i) acc[i] = acc[i] > 0.f ? acc[i] : 0.f;
+        store_vec<T, VW>(o.ya + row * o.ldya + c0, acc, valid);
+    }
+}
+
 #ifndef PLX_SPMM_UNROLL
 #define PLX_SPMM_UNROLL 8
 #endif
@@ -152,8 +168,7 @@ template <typename T, int G, int VW>
 __global__ __launch_bounds__(256) void k_spmm_subwave(const int32_t* __restrict__ row_order, int64_t count,
                                                       const int32_t* __restrict__ bptr,
                                                       const int32_t* __restrict__ col, const float* __restrict__ val,
-                                                      const T* __restrict__ X, int64_t ldx, T* __restrict__ Y,
-                                                      int64_t ldy, int d) {
+                                                      const T* __restrict__ X, int64_t ldx, Out<T> out, int d) {
     constexpr int R = kWave / G;
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
@@ -176,7 +191,7 @@ __global__ __launch_bounds__(256) void k_spmm_subwave(const int32_t* __restrict_
 #else
         if (active) gather_accumulate<T, VW>(lo, hi, 1, col, val, X + c0, ldx, acc);
 #endif
-        if (active) store_vec<T, VW>(Y + (int64_t)row * ldy + c0, acc, d - c0);
+        if (active) emit<T, VW>(out, row, c0, acc, d - c0);
     }
 }
 
@@ -194,8 +209,7 @@ template <typename T, int G, int VW>
 __global__ __launch_bounds__(256) void k_spmm_wave(const int32_t* __restrict__ rows, int64_t count,
                                                    const int32_t* __restrict__ bptr,
                                                    const int32_t* __restrict__ col, const float* __restrict__ val,
-                                                   const T* __restrict__ X, int64_t ldx, T* __restrict__ Y,
-                                                   int64_t ldy, int d) {
+                                                   const T* __restrict__ X, int64_t ldx, Out<T> out, int d) {
     constexpr int NG = kWave / G;
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t slot = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
@@ -209,7 +223,7 @@ __global__ __launch_bounds__(256) void k_spmm_wave(const int32_t* __restrict__ r
     for (int i = 0; i < VW; ++i) acc[i] = 0.f;
     if (active) gather_accumulate<T, VW>(lo + g, hi, NG, col, val, X + c0, ldx, acc);
     reduce_groups<G, VW>(acc);
-    if (g == 0 && active) store_vec<T, VW>(Y + (int64_t)row * ldy + c0, acc, d - c0);
+    if (g == 0 && active) emit<T, VW>(out, row, c0, acc, d - c0);
 }
 
 // Long rows, stage 1: one wavefront per segment, fp32 partial sums to part[seg][G*VW].
@@ -242,18 +256,20 @@ __global__ __launch_bounds__(256) void k_spmm_segment(int64_t n_seg, const int64
 template <typename T>
 __global__ __launch_bounds__(256) void k_spmm_combine(int64_t n_long, const int32_t* __restrict__ long_row,
                                                       const int32_t* __restrict__ seg0, const float* __restrict__ part,
-                                                      int ldp, T* __restrict__ Y, int64_t ldy, int d) {
+                                                      int ldp, Out<T> out, int d) {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t q = idx / d;
     const int j = (int)(idx % d);
     if (q >= n_long) return;
     float s = 0.f;
     for (int32_t k = seg0[q]; k < seg0[q + 1]; ++k) s += part[(int64_t)k * ldp + j];
-    Y[(int64_t)long_row[q] * ldy + j] = narrow<T>(s);
+    const int64_t row = long_row[q];
+    if (out.y) out.y[row * out.ldy + j] = narrow<T>(s);
+    if (out.ya) out.ya[row * out.ldya + j] = narrow<T>(s > 0.f ? s : 0.f);
 }
 
 template <typename T, int G, int VW>
-plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, T* Y, int64_t ldy, int d) {
+plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, Out<T> out, int d) {
     hipStream_t s = ctx->stream;
     const int64_t n_sub = o.class_off[kSubwaveMaxClass + 1];
     const int64_t n_wave = o.class_off[kLongClass] - n_sub;
@@ -269,13 +285,13 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, T* Y
         blocks = std::min<int64_t>(blocks, (int64_t)ctx->n_cu * PLX_SUB_PERSIST);
 #endif
         k_spmm_subwave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order, sub_count, o.bptr, o.col, o.val, X,
-                                                                         ldx, Y, ldy, d);
+                                                                         ldx, out, d);
     }
     if (n_wave > 0) {
         KernelTimer kt(ctx, std::string("spmm_wave") + label);
         int64_t blocks = ceil_div(n_wave, WPB);
         k_spmm_wave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + n_sub, n_wave, o.bptr + n_sub, o.col,
-                                                                      o.val, X, ldx, Y, ldy, d);
+                                                                      o.val, X, ldx, out, d);
     }
     if (o.n_seg > 0) {
         PLX_TRY(ensure_scratch(ctx, (size_t)o.n_seg * G * VW * sizeof(float)));
@@ -285,14 +301,14 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, T* Y
                                                                                          o.col, o.val, X, ldx, part, d);
         int64_t total = o.n_long * d;
         k_spmm_combine<T><<<dim3((unsigned)ceil_div(total, 256)), 256, 0, s>>>(o.n_long, o.long_row, o.long_seg0, part,
-                                                                               G * VW, Y, ldy, d);
+                                                                               G * VW, out, d);
     }
     PLX_HIP(ctx, hipGetLastError());
     return PLX_OK;
 }
 
 template <typename T, int VW>
-plx_status run_vw(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, T* Y, int64_t ldy, int64_t d) {
+plx_status run_vw(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, Out<T> out, int64_t d) {
     const int tile = kWave * VW;                        // widest pass one wavefront covers
     for (int64_t t0 = 0; t0 < d; t0 += tile) {
         int dp = (int)std::min<int64_t>(tile, d - t0);
@@ -300,16 +316,16 @@ plx_status run_vw(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, T* Y, 
         int G = 1;
         while (G < chunks) G <<= 1;
         const T* Xp = X + t0;
-        T* Yp = Y + t0;
+        Out<T> op{out.y ? out.y + t0 : nullptr, out.ldy, out.ya ? out.ya + t0 : nullptr, out.ldya};
         plx_status st;
         switch (G) {
-            case 1: st = run_pass<T, 1, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
-            case 2: st = run_pass<T, 2, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
-            case 4: st = run_pass<T, 4, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
-            case 8: st = run_pass<T, 8, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
-            case 16: st = run_pass<T, 16, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
-            case 32: st = run_pass<T, 32, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
-            default: st = run_pass<T, 64, VW>(ctx, o, Xp, ldx, Yp, ldy, dp); break;
+            case 1: st = run_pass<T, 1, VW>(ctx, o, Xp, ldx, op, dp); break;
+            case 2: st = run_pass<T, 2, VW>(ctx, o, Xp, ldx, op, dp); break;
+            case 4: st = run_pass<T, 4, VW>(ctx, o, Xp, ldx, op, dp); break;
+            case 8: st = run_pass<T, 8, VW>(ctx, o, Xp, ldx, op, dp); break;
+            case 16: st = run_pass<T, 16, VW>(ctx, o, Xp, ldx, op, dp); break;
+            case 32: st = run_pass<T, 32, VW>(ctx, o, Xp, ldx, op, dp); break;
+            default: st = run_pass<T, 64, VW>(ctx, o, Xp, ldx, op, dp); break;
         }
         PLX_TRY(st);
     }
@@ -321,25 +337,27 @@ bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p
 }  // namespace
 
 plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* Y, int64_t ldy, int64_t d,
-                       plx_dtype dtype) {
+                       plx_dtype dtype, void* Yact, int64_t ldyact) {
     if (o.rows >= (int64_t(1) << 31) || o.nnz >= (int64_t(1) << 31))
         return fail(ctx, PLX_ERR_UNSUPPORTED, "matrix too large for 32-bit ids");
     // widest vector the layout allows: base pointers and row pitches must keep every row aligned
     auto fits = [&](size_t bytes, size_t es) {
-        return aligned_to(X, bytes) && aligned_to(Y, bytes) && (ldx * es) % bytes == 0 && (ldy * es) % bytes == 0;
+        return aligned_to(X, bytes) && (ldx * es) % bytes == 0 &&
+               (!Y || (aligned_to(Y, bytes) && (ldy * es) % bytes == 0)) &&
+               (!Yact || (aligned_to(Yact, bytes) && (ldyact * es) % bytes == 0));
     };
     if (dtype == PLX_F32) {
         const float* x = static_cast<const float*>(X);
-        float* y = static_cast<float*>(Y);
-        if (fits(16, 4)) return run_vw<float, 4>(ctx, o, x, ldx, y, ldy, d);
-        if (fits(8, 4)) return run_vw<float, 2>(ctx, o, x, ldx, y, ldy, d);
-        return run_vw<float, 1>(ctx, o, x, ldx, y, ldy, d);
+        Out<float> out{static_cast<float*>(Y), ldy, static_cast<float*>(Yact), ldyact};
+        if (fits(16, 4)) return run_vw<float, 4>(ctx, o, x, ldx, out, d);
+        if (fits(8, 4)) return run_vw<float, 2>(ctx, o, x, ldx, out, d);
+        return run_vw<float, 1>(ctx, o, x, ldx, out, d);
     }
     const bf16_t* x = static_cast<const bf16_t*>(X);
-    bf16_t* y = static_cast<bf16_t*>(Y);
-    if (fits(16, 2)) return run_vw<bf16_t, 8>(ctx, o, x, ldx, y, ldy, d);
-    if (fits(8, 2)) return run_vw<bf16_t, 4>(ctx, o, x, ldx, y, ldy, d);
-    return run_vw<bf16_t, 1>(ctx, o, x, ldx, y, ldy, d);
+    Out<bf16_t> out{static_cast<bf16_t*>(Y), ldy, static_cast<bf16_t*>(Yact), ldyact};
+    if (fits(16, 2)) return run_vw<bf16_t, 8>(ctx, o, x, ldx, out, d);
+    if (fits(8, 2)) return run_vw<bf16_t, 4>(ctx, o, x, ldx, out, d);
+    return run_vw<bf16_t, 1>(ctx, o, x, ldx, out, d);
 }
 
 }  // namespace plx

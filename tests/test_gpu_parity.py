@@ -300,3 +300,44 @@ def test_layer_on_rectangular_block_both_orders(ctx):
         assert rel_err(F, oracle.relu(Q)) <= TOL32
         assert rel_err(gdW, dW) <= TOL32
         assert rel_err(gdX, dX) <= TOL32
+        # only the activated output stored; the backward call takes it in place of Z
+        F2 = torch.empty(m, dout, device=DEV)
+        plx.plx_gcn_layer_fwd(ctx, csr, False, dev(X), dev(W), None, F2, saved, ws, order=order)
+        gdX2 = torch.empty(k, din, device=DEV); gdW2 = torch.empty(din, dout, device=DEV)
+        plx.plx_gcn_layer_bwd(ctx, csr, False, dev(X), dev(W), F2, dev(dFn), saved, gdX2, gdW2, ws, order=order)
+        plx.plx_sync(ctx)
+        assert torch.equal(F2, F) and torch.equal(gdX2, gdX) and torch.equal(gdW2, gdW)
+        # weight gradient only
+        gdW3 = torch.empty(din, dout, device=DEV)
+        plx.plx_gcn_layer_bwd(ctx, csr, False, dev(X), dev(W), F2, dev(dFn), saved, None, gdW3, ws, order=order)
+        plx.plx_sync(ctx)
+        assert torch.equal(gdW3, gdW)
+
+
+@pytest.mark.parametrize("din,dout", [(32, 128), (128, 128), (100, 47), (128, 16), (64, 128), (33, 65), (602, 128)])
+def test_layer_backward_shapes(ctx, din, dout):
+    """Backward of one layer over the width pairs of the five workloads (ragged widths, widths
+    above the fused kernel's range fall back to the separate products), both orders."""
+    m, k = 1300, 1700
+    rowptr, col, val = random_block(m, k, din + dout)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(din * 7 + dout)
+    X = r.standard_normal((k, din)).astype(np.float32)
+    W = (r.standard_normal((din, dout)) * 0.2).astype(np.float32)
+    dFn = r.standard_normal((m, dout)).astype(np.float32)
+    Hagg = oracle.spmm_coo(m, row, c64, v64, X)
+    Q = oracle.gemm(Hagg, W)
+    dQ = oracle.relu_bwd(Q, dFn)
+    dW = oracle.gemm(Hagg, dQ, ta=True)
+    dX = oracle.spmm_t_coo(k, row, c64, v64, oracle.gemm(dQ, W, tb=True))
+    for order in (plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_COMBINE_FIRST):
+        ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, order=order), dtype=torch.uint8, device=DEV)
+        F = torch.empty(m, dout, device=DEV); saved = torch.empty(m, din, device=DEV)
+        plx.plx_gcn_layer_fwd(ctx, csr, False, dev(X), dev(W), None, F, saved, ws, order=order)
+        gdX = torch.empty(k, din, device=DEV); gdW = torch.empty(din, dout, device=DEV)
+        plx.plx_gcn_layer_bwd(ctx, csr, False, dev(X), dev(W), F, dev(dFn), saved, gdX, gdW, ws, order=order)
+        plx.plx_sync(ctx)
+        assert rel_err(F, oracle.relu(Q)) <= TOL32
+        assert rel_err(gdW, dW) <= TOL32
+        assert rel_err(gdX, dX) <= TOL32
