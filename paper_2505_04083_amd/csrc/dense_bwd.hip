@@ -25,17 +25,18 @@ namespace {
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kTR = 64;   // rows per tile
 
-// global (rows r0.., cols 0..ncols) -> LDS tile [kTR][COLS + 4], zero padded; optional ReLU mask source
-template <int COLS>
-__device__ __forceinline__ void stage_tile(float (*dst)[COLS + 4], const float* __restrict__ src, int64_t ld,
-                                           const float* __restrict__ mask, int64_t ldm, int64_t r0, int64_t r_end,
-                                           int ncols, bool vec, int tid) {
+// A kTR x COLS tile held in registers between its global load and its LDS store, so that the
+// loads of the next tile are in flight while the matrix cores work on the current one.
+template <int TR, int COLS> struct TileRegs { float4 v[TR * COLS / 1024]; };   // TR * COLS / 4 float4 over 256 threads
+
+template <int TR, int COLS>
+__device__ __forceinline__ void fetch_tile(TileRegs<TR, COLS>& t, const float* __restrict__ src, int64_t ld, int64_t r0,
+                                           int64_t r_end, int ncols, bool vec, int tid) {
     constexpr int Q4 = COLS / 4;
-#pragma unroll 4
-    for (int f = tid; f < kTR * Q4; f += 256) {
-        const int r = f / Q4, q = f % Q4;
+#pragma unroll
+    for (int i = 0; i < TR * COLS / 1024; ++i) {
+        const int f = tid + 256 * i, r = f / Q4, q = f % Q4;
         const int64_t gr = r0 + r;
         const int gc = 4 * q;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -43,24 +44,36 @@ __device__ __forceinline__ void stage_tile(float (*dst)[COLS + 4], const float* 
             const float* p = src + gr * ld + gc;
             if (vec && gc + 3 < ncols) {
                 v = *reinterpret_cast<const float4*>(p);
-                if (mask) {
-                    const float4 z = *reinterpret_cast<const float4*>(mask + gr * ldm + gc);
-                    v.x = z.x > 0.f ? v.x : 0.f; v.y = z.y > 0.f ? v.y : 0.f;
-                    v.z = z.z > 0.f ? v.z : 0.f; v.w = z.w > 0.f ? v.w : 0.f;
-                }
             } else {
-                const float* z = mask ? mask + gr * ldm + gc : nullptr;
-                v.x = (!z || z[0] > 0.f) ? p[0] : 0.f;
-                if (gc + 1 < ncols) v.y = (!z || z[1] > 0.f) ? p[1] : 0.f;
-                if (gc + 2 < ncols) v.z = (!z || z[2] > 0.f) ? p[2] : 0.f;
-                if (gc + 3 < ncols) v.w = (!z || z[3] > 0.f) ? p[3] : 0.f;
+                v.x = p[0];
+                if (gc + 1 < ncols) v.y = p[1];
+                if (gc + 2 < ncols) v.z = p[2];
+                if (gc + 3 < ncols) v.w = p[3];
             }
         }
-        *reinterpret_cast<float4*>(&dst[r][gc]) = v;
+        t.v[i] = v;
     }
 }
 
-template <int TMB, int TNB>   // Mp <= 32*TMB, N <= 32*TNB
+// registers -> LDS tile [TR][COLS + 4]; with a mask tile, elements whose mask is <= 0 become 0 (Eq. 2.4)
+template <int TR, int COLS, bool MASK>
+__device__ __forceinline__ void commit_tile(float (*dst)[COLS + 4], const TileRegs<TR, COLS>& t,
+                                            const TileRegs<TR, COLS>& m, int tid) {
+    constexpr int Q4 = COLS / 4;
+#pragma unroll
+    for (int i = 0; i < TR * COLS / 1024; ++i) {
+        const int f = tid + 256 * i, r = f / Q4, q = f % Q4;
+        float4 v = t.v[i];
+        if (MASK) {
+            const float4 z = m.v[i];
+            v.x = z.x > 0.f ? v.x : 0.f; v.y = z.y > 0.f ? v.y : 0.f;
+            v.z = z.z > 0.f ? v.z : 0.f; v.w = z.w > 0.f ? v.w : 0.f;
+        }
+        *reinterpret_cast<float4*>(&dst[r][4 * q]) = v;
+    }
+}
+
+template <int TMB, int TNB, bool MASK, int kTR>   // Mp <= 32*TMB, N <= 32*TNB; kTR rows per tile (32 or 64)
 __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N, const float* __restrict__ P, int64_t ldp,
                                                        const float* __restrict__ Q, int64_t ldq,
                                                        const float* __restrict__ Zm, int64_t ldz,
@@ -68,15 +81,23 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
                                                        float* __restrict__ dOut, int64_t ldo, float* __restrict__ part,
                                                        int64_t rows_per_chunk, int vec_p, int vec_q) {
     constexpr int MP = 32 * TMB, NP = 32 * TNB;
-    constexpr int NBLK = (TMB * TNB + 3) / 4;     // 32x32 blocks of dW per wavefront
+    // dW blocks over 4 wavefronts: NB >= 4 gives NB/4 blocks each; with NB < 4 the 4/NB wavefronts
+    // sharing a block take interleaved row pairs of every tile and write separate partial tiles.
+    constexpr int NB = TMB * TNB, KS = NB >= 4 ? 1 : 4 / NB, NBLK = NB >= 4 ? NB / 4 : 1;
     constexpr int NCB = MP / 16;                   // 16-column blocks of dOut
+    // dOut tile = (kTR/16) x NCB blocks of 16x16: with 64 rows wavefront w owns row block w and all
+    // column blocks; with 32 rows it owns row block w%2 and every second column block from w/2.
+    constexpr int CPW = kTR == 64 ? NCB : NCB / 2;  // column blocks per wavefront
+    static_assert(kTR == 64 || kTR == 32, "tile rows");
     extern __shared__ __align__(16) float smem[];
     float (*Qs)[NP + 4] = reinterpret_cast<float (*)[NP + 4]>(smem);
     float (*Ps)[MP + 4] = reinterpret_cast<float (*)[MP + 4]>(smem + kTR * (NP + 4));
     float (*Ws)[NP + 4] = reinterpret_cast<float (*)[NP + 4]>(smem + kTR * (NP + 4) + kTR * (MP + 4));
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lh = lane >> 5, l16 = lane & 15, lq = lane >> 4;
+    const int wq = NB >= 4 ? w : w % NB, ks = NB >= 4 ? 0 : w / NB;
+    const int orb = kTR == 64 ? w : (w & 1), ocb0 = kTR == 64 ? 0 : (w >> 1), ocbs = kTR == 64 ? 1 : 2;
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_chunk;
     const int64_t r_end = (r_begin + rows_per_chunk < R) ? r_begin + rows_per_chunk : R;
 
@@ -91,53 +112,72 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_w[t][r] = 0.f;
 
-    for (int64_t r0 = r_begin; r0 < r_end; r0 += kTR) {
-        stage_tile<NP>(Qs, Q, ldq, Zm, ldz, r0, r_end, N, vec_q, tid);
-        stage_tile<MP>(Ps, P, ldp, nullptr, 0, r0, r_end, Mp, vec_p, tid);
-        __syncthreads();
+    // Order inside an iteration: issue the next tile's global loads, run both products from LDS,
+    // barrier, write the prefetched tile to LDS, and only then issue this tile's dOut stores --
+    // so the wait for the prefetched loads never includes waiting for store acknowledgements.
+    TileRegs<kTR, NP> rq, rz;
+    TileRegs<kTR, MP> rp;
+    fetch_tile<kTR, NP>(rq, Q, ldq, r_begin, r_end, N, vec_q, tid);
+    if (MASK) fetch_tile<kTR, NP>(rz, Zm, ldz, r_begin, r_end, N, vec_q, tid);
+    fetch_tile<kTR, MP>(rp, P, ldp, r_begin, r_end, Mp, vec_p, tid);
+    commit_tile<kTR, NP, MASK>(Qs, rq, rz, tid);
+    commit_tile<kTR, MP, false>(Ps, rp, rp, tid);
+    __syncthreads();
 
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += kTR) {
+        const bool more = r0 + kTR < r_end;
+        if (more) {
+            fetch_tile<kTR, NP>(rq, Q, ldq, r0 + kTR, r_end, N, vec_q, tid);
+            if (MASK) fetch_tile<kTR, NP>(rz, Zm, ldz, r0 + kTR, r_end, N, vec_q, tid);
+            fetch_tile<kTR, MP>(rp, P, ldp, r0 + kTR, r_end, Mp, vec_p, tid);
+        }
+
+        floatx4 acc_o[CPW];
         if (dOut) {                                                    // Eq. 2.6 on this tile
-            floatx4 acc_o[NCB];
 #pragma unroll
-            for (int c = 0; c < NCB; ++c) acc_o[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int c = 0; c < CPW; ++c) acc_o[c] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
             for (int k = 0; k < NP; k += 4) {
-                const float a = Qs[16 * w + l16][k + lq];
+                const float a = Qs[16 * orb + l16][k + lq];
 #pragma unroll
-                for (int c = 0; c < NCB; ++c)
-                    acc_o[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Ws[16 * c + l16][k + lq], acc_o[c], 0, 0, 0);
+                for (int c = 0; c < CPW; ++c)
+                    acc_o[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Ws[16 * (ocb0 + ocbs * c) + l16][k + lq], acc_o[c], 0, 0, 0);
             }
+        }
+#pragma unroll 4
+        for (int kk = 2 * ks; kk < kTR; kk += 2 * KS) {                // Eq. 2.5, partial over this tile
 #pragma unroll
-            for (int c = 0; c < NCB; ++c) {
-                const int gc = 16 * c + l16;
+            for (int t = 0; t < NBLK; ++t) {
+                const int q = wq + 4 * t, bi = q / TNB, bj = q % TNB;
+                acc_w[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(Ps[kk + lh][32 * bi + l32], Qs[kk + lh][32 * bj + l32],
+                                                                acc_w[t], 0, 0, 0);
+            }
+        }
+        __syncthreads();                                               // every wavefront is done reading the tile
+        if (more) {
+            commit_tile<kTR, NP, MASK>(Qs, rq, rz, tid);
+            commit_tile<kTR, MP, false>(Ps, rp, rp, tid);
+        }
+        if (dOut) {
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) {
+                const int gc = 16 * (ocb0 + ocbs * c) + l16;
                 if (gc < Mp) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const int64_t gr = r0 + 16 * w + 4 * lq + r;
+                        const int64_t gr = r0 + 16 * orb + 4 * lq + r;
                         if (gr < r_end) dOut[gr * ldo + gc] = acc_o[c][r];
                     }
                 }
             }
         }
-
-#pragma unroll 4
-        for (int kk = 0; kk < kTR; kk += 2) {                          // Eq. 2.5, partial over this tile
-#pragma unroll
-            for (int t = 0; t < NBLK; ++t) {
-                const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-                if (q < TMB * TNB)
-                    acc_w[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(Ps[kk + lh][32 * bi + l32], Qs[kk + lh][32 * bj + l32],
-                                                                    acc_w[t], 0, 0, 0);
-            }
-        }
         __syncthreads();
     }
 
-    float* out = part + (int64_t)blockIdx.x * Mp * N;
+    float* out = part + ((int64_t)blockIdx.x * KS + ks) * Mp * N;
 #pragma unroll
     for (int t = 0; t < NBLK; ++t) {
-        const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-        if (q >= TMB * TNB) continue;
+        const int q = wq + 4 * t, bi = q / TNB, bj = q % TNB;
         const int gn = 32 * bj + l32;
         if (gn >= N) continue;
 #pragma unroll
@@ -150,21 +190,33 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-template <int TMB, int TNB>
-plx_status run(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
+#ifndef PLX_BWD_TILE_ROWS
+#define PLX_BWD_TILE_ROWS 64
+#endif
+
+template <int TMB, int TNB, bool MASK>
+plx_status run_masked(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
                const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
                int64_t rpc, int64_t chunks) {
-    constexpr int MP = 32 * TMB, NP = 32 * TNB;
+    constexpr int MP = 32 * TMB, NP = 32 * TNB, kTR = PLX_BWD_TILE_ROWS;
     const size_t lds = sizeof(float) * (kTR * (NP + 4) + kTR * (MP + 4) + MP * (NP + 4));
     const int vec_p = aligned16(P) && ldp % 4 == 0;
     const int vec_q = aligned16(Q) && ldq % 4 == 0 && (!Zm || (aligned16(Zm) && ldz % 4 == 0));
-    auto kern = k_bwd_dense_f32<TMB, TNB>;
+    auto kern = k_bwd_dense_f32<TMB, TNB, MASK, kTR>;
     if (lds > 48 * 1024)
         PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     kern<<<dim3((unsigned)chunks), 256, lds, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc,
                                                            vec_p, vec_q);
     PLX_HIP(ctx, hipGetLastError());
     return PLX_OK;
+}
+
+template <int TMB, int TNB>
+plx_status run(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
+               const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
+               int64_t rpc, int64_t chunks) {
+    return Zm ? run_masked<TMB, TNB, true>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks)
+              : run_masked<TMB, TNB, false>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks);
 }
 
 }  // namespace
@@ -202,7 +254,7 @@ plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, cons
 #undef PLX_BD
     }
     PLX_TRY(st);
-    return reduce_partials(ctx, part, chunks, Mp, N, dW, lddw);
+    return reduce_partials(ctx, part, chunks * tn_kslices(Mp, N), Mp, N, dW, lddw);
 }
 
 }  // namespace plx

@@ -35,10 +35,10 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
                                                   int64_t ldc, float* __restrict__ F, int64_t ldf, int vec_a) {
     constexpr int TMB = 4;
     constexpr int BM = 32 * TMB, BN = 32 * TNB;
-    constexpr int NBLK = (TMB * TNB + 3) / 4;         // blocks per wavefront
+    constexpr int NBLK = TMB * TNB / 4;               // blocks per wavefront
     __shared__ float As[BM][kBK + 1];
     __shared__ float Bs[kBK][BN + 1];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lh = lane >> 5;
     const int64_t m0 = (int64_t)blockIdx.x * BM;
     const int n0 = blockIdx.y * BN;
@@ -81,13 +81,9 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
 #pragma unroll 4
         for (int kk = 0; kk < kBK; kk += 2) {
 #pragma unroll
-            for (int t = 0; t < NBLK; ++t) {
+            for (int t = 0; t < NBLK; ++t) {       // TMB * TNB is a multiple of 4: every block index is valid
                 const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-                if (q < TMB * TNB) {
-                    const float a = As[32 * bi + l32][kk + lh];
-                    const float b = Bs[kk + lh][32 * bj + l32];
-                    acc[t] = mfma32(a, b, acc[t]);
-                }
+                acc[t] = mfma32(As[32 * bi + l32][kk + lh], Bs[kk + lh][32 * bj + l32], acc[t]);
             }
         }
         __syncthreads();
@@ -95,7 +91,6 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
 #pragma unroll
     for (int t = 0; t < NBLK; ++t) {
         const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-        if (q >= TMB * TNB) continue;
         const int gn = n0 + 32 * bj + l32;
         if (gn >= N) continue;
 #pragma unroll
@@ -110,6 +105,114 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
     }
 }
 
+// ---- C[M x N] = A[M x K] * B[K x N] for K, N <= 128: weights resident in LDS, persistent row loop -----
+// The weight matrix is loaded into LDS once per workgroup; the workgroup then walks over 64-row
+// tiles of A (tile index strided by the grid), fetching the next tile into registers while the
+// matrix cores work on the current one.  Output: C and / or max(C, 0).
+// Rows per tile are 32 * RB with RB * TNB a multiple of 4, so every wavefront owns the same number
+// of 32x32 output blocks and no matrix instruction sits under a condition.
+template <int TKB, int TNB, int RB>   // K <= 32*TKB, N <= 32*TNB
+__global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K, const float* __restrict__ A,
+                                                        int64_t lda, const float* __restrict__ B, int64_t ldb,
+                                                        float* __restrict__ C, int64_t ldc, float* __restrict__ F,
+                                                        int64_t ldf, int vec_a) {
+    constexpr int KP = 32 * TKB, NP = 32 * TNB, kFwdRows = 32 * RB;
+    constexpr int NBLK = RB * TNB / 4;                // 32x32 blocks per wavefront
+    constexpr int NLD = kFwdRows * KP / 4 / 256;      // float4 per thread per tile
+    static_assert((RB * TNB) % 4 == 0, "tile must split evenly over 4 wavefronts");
+    extern __shared__ __align__(16) float smem[];
+    // two A buffers: the next tile is written to LDS BEFORE this tile's stores are issued, so the
+    // wait for the prefetched loads never has to wait for store acknowledgements as well
+    typedef float (*ATile)[KP + 4];
+    auto a_buf = [&](int b) { return reinterpret_cast<ATile>(smem + b * kFwdRows * (KP + 4)); };
+    float (*Bs)[NP + 4] = reinterpret_cast<float (*)[NP + 4]>(smem + 2 * kFwdRows * (KP + 4));
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    for (int f = tid; f < KP * NP; f += 256) {
+        const int kk = f / NP, n = f % NP;
+        Bs[kk][n] = (kk < K && n < N) ? B[(int64_t)kk * ldb + n] : 0.f;
+    }
+
+    const int64_t n_tiles = (M + kFwdRows - 1) / kFwdRows;
+    float4 reg[NLD];
+    auto fetch = [&](int64_t tile) {
+        const int64_t m0 = tile * kFwdRows;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int f = tid + 256 * i, r = f / (KP / 4), q = f % (KP / 4);
+            const int64_t gr = m0 + r;
+            const int gk = 4 * q;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gr < M && gk < K) {
+                const float* p = A + gr * lda + gk;
+                if (vec_a && gk + 3 < K) {
+                    v = *reinterpret_cast<const float4*>(p);
+                } else {
+                    v.x = p[0];
+                    if (gk + 1 < K) v.y = p[1];
+                    if (gk + 2 < K) v.z = p[2];
+                    if (gk + 3 < K) v.w = p[3];
+                }
+            }
+            reg[i] = v;
+        }
+    };
+    auto commit = [&](ATile As) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int f = tid + 256 * i, r = f / (KP / 4), q = f % (KP / 4);
+            *reinterpret_cast<float4*>(&As[r][4 * q]) = reg[i];
+        }
+    };
+
+    int64_t tile = blockIdx.x;
+    int cur = 0;
+    if (tile < n_tiles) { fetch(tile); commit(a_buf(0)); }
+    __syncthreads();
+    for (; tile < n_tiles; tile += gridDim.x) {
+        const bool more = tile + gridDim.x < n_tiles;
+        if (more) fetch(tile + gridDim.x);
+        ATile As = a_buf(cur);
+
+        floatx16 acc[NBLK];
+#pragma unroll
+        for (int t = 0; t < NBLK; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+#pragma unroll 4
+        for (int kk = 0; kk < KP; kk += 2) {
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) {
+                const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
+                acc[t] = mfma32(As[32 * bi + l32][kk + lh], Bs[kk + lh][32 * bj + l32], acc[t]);
+            }
+        }
+        if (more) commit(a_buf(cur ^ 1));
+        const int64_t m0 = tile * kFwdRows;
+#pragma unroll
+        for (int t = 0; t < NBLK; ++t) {
+            const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
+            const int gn = 32 * bj + l32;
+            if (gn >= N) continue;
+            const int64_t row0 = m0 + 32 * bi + 4 * lh;
+            float* cp = C ? C + row0 * ldc + gn : nullptr;
+            float* fp = F ? F + row0 * ldf + gn : nullptr;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = 8 * (r / 4) + (r % 4);
+                if (row0 + dr < M) {
+                    const float v = acc[t][r];
+                    if (cp) cp[dr * ldc] = v;
+                    if (fp) fp[dr * ldf] = v > 0.f ? v : 0.f;          // Eq. 2.3 fused into the store
+                }
+            }
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+}
+
 // ---- partial[chunk][M x N] = A[rows of chunk, M]^T * B[rows of chunk, N] ---------------------------
 template <int TMB, int TNB>
 __global__ __launch_bounds__(256) void k_gemm_tn_f32(int64_t R, int M, int N, const float* __restrict__ A, int64_t lda,
@@ -117,10 +220,14 @@ __global__ __launch_bounds__(256) void k_gemm_tn_f32(int64_t R, int M, int N, co
                                                      float* __restrict__ part, int64_t rows_per_chunk, int vec_a,
                                                      int vec_b) {
     constexpr int BM = 32 * TMB, BN = 32 * TNB;
-    constexpr int NBLK = (TMB * TNB + 3) / 4;
+    // NB output blocks over 4 wavefronts: NB >= 4 gives NB/4 blocks each; with NB < 4 the 4/NB
+    // wavefronts that share a block take interleaved row pairs of every slab and write separate
+    // partial tiles (slot = chunk * KS + slice), so no matrix instruction sits under a condition.
+    constexpr int NB = TMB * TNB, KS = NB >= 4 ? 1 : 4 / NB, NBLK = NB >= 4 ? NB / 4 : 1;
     __shared__ __align__(16) float As[kBK][BM + 4];
     __shared__ __align__(16) float Bs[kBK][BN + 4];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wq = NB >= 4 ? w : w % NB, ks = NB >= 4 ? 0 : w / NB;
     const int l32 = lane & 31, lh = lane >> 5;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.z * BN;
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_chunk;
@@ -171,24 +278,19 @@ __global__ __launch_bounds__(256) void k_gemm_tn_f32(int64_t R, int M, int N, co
         }
         __syncthreads();
 #pragma unroll 4
-        for (int kk = 0; kk < kBK; kk += 2) {
+        for (int kk = 2 * ks; kk < kBK; kk += 2 * KS) {
 #pragma unroll
             for (int t = 0; t < NBLK; ++t) {
-                const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-                if (q < TMB * TNB) {
-                    const float a = As[kk + lh][32 * bi + l32];
-                    const float b = Bs[kk + lh][32 * bj + l32];
-                    acc[t] = mfma32(a, b, acc[t]);
-                }
+                const int q = wq + 4 * t, bi = q / TNB, bj = q % TNB;
+                acc[t] = mfma32(As[kk + lh][32 * bi + l32], Bs[kk + lh][32 * bj + l32], acc[t]);
             }
         }
         __syncthreads();
     }
-    float* out = part + (int64_t)blockIdx.x * M * N;
+    float* out = part + ((int64_t)blockIdx.x * KS + ks) * M * N;
 #pragma unroll
     for (int t = 0; t < NBLK; ++t) {
-        const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-        if (q >= TMB * TNB) continue;
+        const int q = wq + 4 * t, bi = q / TNB, bj = q % TNB;
         const int gn = n0 + 32 * bj + l32;
         if (gn >= N) continue;
 #pragma unroll
@@ -246,9 +348,15 @@ plx_status reduce_partials(plx_ctx* ctx, float* part, int64_t chunks, int64_t M,
     return PLX_OK;
 }
 
+// wavefronts sharing one output block (see the kernels): 4 / (number of 32x32 blocks) when that is < 4
+int tn_kslices(int64_t M, int64_t N) {
+    const int tmb = M <= 32 ? 1 : (M <= 64 ? 2 : 4), tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
+    return tmb * tnb >= 4 ? 1 : 4 / (tmb * tnb);
+}
+
 size_t gemm_tn_workspace(int64_t R, int64_t M, int64_t N) {
     const int64_t chunks = std::max<int64_t>(1, ceil_div(R, tn_rows_per_chunk(R, M, N)));
-    return (size_t)chunks * (size_t)M * (size_t)N * sizeof(float);
+    return (size_t)chunks * tn_kslices(M, N) * (size_t)M * (size_t)N * sizeof(float);
 }
 
 plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
@@ -265,6 +373,36 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
     char label[64];
     snprintf(label, sizeof label, "gemm_%s<f32>[N%lld,K%lld]", bt ? "nt" : "nn", (long long)N, (long long)K);
     KernelTimer kt(ctx, label);
+    if (!bt && K <= 128 && N <= 128 && K > 0) {
+        const int tkb = K <= 32 ? 1 : (K <= 64 ? 2 : 4);
+        const int rb = tnb == 1 ? 4 : 2;
+        const int rows = 32 * rb;
+        const size_t lds = sizeof(float) * (2 * rows * (32 * tkb + 4) + 32 * tkb * (32 * tnb + 4));
+        const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(8, (150 * 1024) / lds));
+        const int64_t blocks = std::min<int64_t>(ceil_div(M, rows), (int64_t)ctx->n_cu * per_cu);
+#define PLX_SMALL(TK, TN, RBV)                                                                                 \
+    do {                                                                                                       \
+        auto kern = k_gemm_small_f32<TK, TN, RBV>;                                                             \
+        if (lds > 48 * 1024)                                                                                   \
+            PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                              \
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));           \
+        kern<<<dim3((unsigned)blocks), 256, lds, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf, vec_a); \
+    } while (0)
+        switch (tkb * 10 + tnb) {
+            case 11: PLX_SMALL(1, 1, 4); break;
+            case 12: PLX_SMALL(1, 2, 2); break;
+            case 14: PLX_SMALL(1, 4, 2); break;
+            case 21: PLX_SMALL(2, 1, 4); break;
+            case 22: PLX_SMALL(2, 2, 2); break;
+            case 24: PLX_SMALL(2, 4, 2); break;
+            case 41: PLX_SMALL(4, 1, 4); break;
+            case 42: PLX_SMALL(4, 2, 2); break;
+            default: PLX_SMALL(4, 4, 2); break;
+        }
+#undef PLX_SMALL
+        PLX_HIP(ctx, hipGetLastError());
+        return PLX_OK;
+    }
 #define PLX_GEMM_CASE(T, BTV) \
     k_gemm_f32<T, BTV><<<grid, 256, 0, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf, vec_a)
     if (bt) {
@@ -311,7 +449,7 @@ plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const v
 #undef PLX_TN_CASE
     delete kt;
     PLX_HIP(ctx, hipGetLastError());
-    return reduce_partials(ctx, part, chunks, M, N, C, ldc);
+    return reduce_partials(ctx, part, chunks * tn_kslices(M, N), M, N, C, ldc);
 }
 
 }  // namespace plx

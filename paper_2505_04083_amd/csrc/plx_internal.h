@@ -135,6 +135,7 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
                        int64_t ldf = 0);
 size_t gemm_tn_workspace(int64_t R, int64_t M, int64_t N);
 int64_t tn_rows_per_chunk(int64_t R, int64_t M, int64_t N);
+int tn_kslices(int64_t M, int64_t N);
 plx_status reduce_partials(plx_ctx* ctx, float* part, int64_t chunks, int64_t M, int64_t N, float* C, int64_t ldc);
 // fused Eq. 2.4 + 2.5 + 2.6: dOut = (Q*[Zm>0]) W^T (dOut may be NULL), dW = P^T (Q*[Zm>0]); Zm may be NULL
 bool bwd_dense_supported(int64_t Mp, int64_t N, plx_dtype dtype);
