@@ -62,7 +62,7 @@ def lib():
         L.orc_spmm_rows_csr.argtypes = [_i64p, _i32p, _f32p, _f32p, ctypes.c_int64, ctypes.c_int64,
                                         _i64p, ctypes.c_int64, _f64p]
         L.orc_spmm_t_rows_csr.restype = None
-        L.orc_spmm_t_rows_csr.argtypes = [ctypes.c_int64, ctypes.c_int64, _i64p, _i32p, _f32p, _f32p,
+        L.orc_spmm_t_rows_csr.argtypes = [ctypes.c_int64, ctypes.c_int64, _i64p, _i32p, _f32p, _f64p,
                                           ctypes.c_int64, ctypes.c_int64, _i64p, ctypes.c_int64, _f64p]
         L.orc_gemm.restype = None
         L.orc_gemm.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
@@ -165,12 +165,12 @@ def spmm_rows_csr(rowptr, col, val, X, sample) -> np.ndarray:
 
 
 def spmm_t_rows_csr(m: int, k: int, rowptr, col, val, X, sample) -> np.ndarray:
-    """Rows `sample` of A^T X for the same kind of block."""
+    """Rows `sample` of A^T X for the same kind of block (X is widened to fp64)."""
     rowptr, col, val = _c(rowptr, np.int64), _c(col, np.int32), _c(val, np.float32)
-    X, sample = _c(X, np.float32), _c(sample, np.int64)
+    X, sample = _c(X, np.float64), _c(sample, np.int64)
     d = X.shape[1]
     out = np.empty((sample.shape[0], d), np.float64)
-    lib().orc_spmm_t_rows_csr(m, k, _p(rowptr, _i64p), _p(col, _i32p), _p(val, _f32p), _p(X, _f32p), d, d,
+    lib().orc_spmm_t_rows_csr(m, k, _p(rowptr, _i64p), _p(col, _i32p), _p(val, _f32p), _p(X, _f64p), d, d,
                               _p(sample, _i64p), sample.shape[0], _p(out, _f64p))
     return out
 

@@ -200,8 +200,9 @@ ORC_API void orc_spmm_rows_csr(const int64_t* rowptr, const int32_t* col, const 
     }
 }
 
+/* X is fp64 here (it may itself be an fp64 oracle result); values stay the stored fp32 */
 ORC_API void orc_spmm_t_rows_csr(int64_t m, int64_t k, const int64_t* rowptr, const int32_t* col, const float* val,
-                                 const float* X, int64_t ldx, int64_t d,
+                                 const double* X, int64_t ldx, int64_t d,
                                  const int64_t* sample, int64_t ns, double* out) {
     int64_t* slot = (int64_t*)malloc(sizeof(int64_t) * (size_t)(k > 0 ? k : 1));
     for (int64_t c = 0; c < k; ++c) slot[c] = -1;
@@ -211,9 +212,9 @@ ORC_API void orc_spmm_t_rows_csr(int64_t m, int64_t k, const int64_t* rowptr, co
         for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
             int64_t s = slot[col[e]];
             if (s < 0) continue;
-            const float* x = X + i * ldx;
+            const double* x = X + i * ldx;
             double a = (double)val[e];
-            for (int64_t j = 0; j < d; ++j) out[s * d + j] += a * (double)x[j];
+            for (int64_t j = 0; j < d; ++j) out[s * d + j] += a * x[j];
         }
     /* repeated samples: copy from the slot that accumulated */
     for (int64_t s = 0; s < ns; ++s) {
