@@ -53,6 +53,33 @@ def spmm_bytes(rows, entries, d, s=4):
     return entries * (8 + s * d) + rows * (4 + s * d)
 
 
+def measured_traffic(name):
+    """HBM bytes per launch of the kernel behind a timing label, from the committed rocprofv3
+    FETCH_SIZE / WRITE_SIZE summary of this same workload (profiles/traffic_layer_shard_f32.json,
+    counters already scaled by a plain 4 GiB copy); None if the summary has no such kernel."""
+    path = os.path.join(ROOT, "profiles", "traffic_layer_shard_f32.json")
+    if not os.path.exists(path):
+        return None
+    k = json.load(open(path))["kernels"]
+    import re
+    m = re.match(r"spmm_(subwave|wave|split)<(f32|bf16),G(\d+),VW(\d+)>\[(A|At)\]", name)
+    keys = []
+    if m:
+        kind, dt, g, vw, o = m.groups()
+        t = "float" if dt == "f32" else "unsigned short"
+        base = {"subwave": ["k_spmm_subwave"], "wave": ["k_spmm_wave"], "split": ["k_spmm_segment"]}[kind]
+        keys = [f"{b}<{t}, {g}, {vw}> [{o}]" for b in base]
+        if kind == "split":
+            keys.append(f"k_spmm_combine<{t}> [{o}]")
+    elif name.startswith("gemm_nn"):
+        keys = [x for x in k if x.startswith("k_gemm_small_f32") or x.startswith("k_gemm_f32")]
+    elif name.startswith("bwd_dense"):
+        keys = [x for x in k if x.startswith("k_bwd_dense_f32")]
+    if not keys or any(x not in k for x in keys):
+        return None
+    return sum(k[x]["fetch_bytes"] + k[x]["write_bytes"] for x in keys)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -154,7 +181,8 @@ def main():
     d_bytes = alg[dominant][0]
     achieved = d_bytes / d_avg / 1e6
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": measured_traffic(dominant) if args.scale == 1.0 else None,
                 "algorithmic_bytes_per_launch": int(d_bytes), "avg_launch_ms": round(d_avg, 4)}
     # whole sparse products (all their kernels), the figure the metric names
     def spmm_total(tag, rows, ent):
