@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only; <1 is not the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-div", type=int, default=8, help="oracle sample = 1/div of the rows")
+    ap.add_argument("--cpu-sample-div", type=int, default=2, help="oracle sample = 1/div of the rows")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run one plain device copy of known size (reference dispatch for counter scaling)")
     return ap.parse_args()
@@ -203,7 +203,8 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "configs[3]: one GPU's 7M x 28M shard block of a billion-edge graph, fp32, "
                                "layer 32 -> 128, aggregate-first" + ("" if args.scale == 1.0 else f" (SHRUNK x{args.scale})"),
-                   "m": m, "k": k, "nnz": nnz, "din": din, "dout": dout, "order": "agg_first"},
+                   "m": m, "k": k, "nnz": nnz, "din": din, "dout": dout, "order": "agg_first",
+                   "rows_entries_by_bin(<256,<4096,>=4096)": {"A": [list(rows_f), list(ent_f)], "At": [list(rows_b), list(ent_b)]}},
         "roofline": roofline, "cpu_baseline": cpu, "spmm": spmm, "kernels": kernels,
         "setup_s": {"generate": round(t_gen, 2), "csr_import_transpose_bins": round(t_import, 2)},
     }
