@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only; <1 is not the metric)")
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
+                    help="storage type of activations / gradients (the headline metric is f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-div", type=int, default=2, help="oracle sample = 1/div of the rows")
     ap.add_argument("--copy-ref", action="store_true",
@@ -45,11 +47,15 @@ def parse():
     return ap.parse_args()
 
 
-def spmm_bytes(rows, entries, d, s=4):
+ELT = 4   # bytes per dense element (set from --dtype)
+
+
+def spmm_bytes(rows, entries, d, s=None):
     """Algorithmic bytes of a sparse product over `rows` rows holding `entries` stored entries:
     8 B of CSR per entry (value + column), one s*d-byte gathered operand row per entry (the
     double permutation leaves no reuse between entries), a 4 B row pointer and one s*d-byte
     output row per row."""
+    s = ELT if s is None else s
     return entries * (8 + s * d) + rows * (4 + s * d)
 
 
@@ -98,14 +104,18 @@ def main():
     if args.scale != 1.0:
         cfg = cfg.scaled(args.scale)
     din, dout = cfg.dims
+    global ELT
+    tdt = torch.float32 if args.dtype == "f32" else torch.bfloat16
+    ELT = 4 if args.dtype == "f32" else 2
+    code = plx.PLX_F32 if args.dtype == "f32" else plx.PLX_BF16
 
     t0 = time.time()
     rowptr, col, val = synth.shard_block(cfg.seed, cfg.m, cfg.k, cfg.n_samples, dev)
     torch.cuda.synchronize()
     t_gen = time.time() - t0
     nnz = int(col.numel())
-    X = synth.normal(cfg.seed, synth.S_FEAT, cfg.k, din, dev)
-    dF = synth.normal(cfg.seed, synth.S_AUX, cfg.m, dout, dev)
+    X = synth.normal(cfg.seed, synth.S_FEAT, cfg.k, din, dev, tdt)
+    dF = synth.normal(cfg.seed, synth.S_AUX, cfg.m, dout, dev, tdt)
     W = synth.glorot(cfg.seed, 0, din, dout, dev)
 
     ctx = plx.plx_ctx(0)
@@ -113,11 +123,11 @@ def main():
     csr = plx.plx_csr_import(ctx, cfg.m, cfg.k, rowptr, col, val)
     t_import = time.time() - t0
     order = plx.PLX_ORDER_AGG_FIRST
-    ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, plx.PLX_F32, plx.PLX_ACT_RELU, order),
+    ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, code, plx.PLX_ACT_RELU, order),
                      dtype=torch.uint8, device=dev)
-    F = torch.empty(cfg.m, dout, device=dev)      # only the activated output is stored (its sign serves Eq. 2.4)
-    saved = torch.empty(cfg.m, din, device=dev)
-    dX = torch.empty(cfg.k, din, device=dev); dW = torch.empty(din, dout, device=dev)
+    F = torch.empty(cfg.m, dout, device=dev, dtype=tdt)   # only the activated output is stored (its sign serves Eq. 2.4)
+    saved = torch.empty(cfg.m, din, device=dev, dtype=tdt)
+    dX = torch.empty(cfg.k, din, device=dev, dtype=tdt); dW = torch.empty(din, dout, device=dev)
 
     def step():
         plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, None, F, saved, ws, act=plx.PLX_ACT_RELU, order=order)
@@ -157,9 +167,9 @@ def main():
             i = {"spmm_subwave": 0, "spmm_wave": 1, "spmm_split": 2}[name.split("<")[0]]
             b, fl = spmm_bytes(rows[i], ent[i], din), 2 * ent[i] * din
         elif name.startswith("gemm_nn"):
-            b, fl = 4 * (m * din + din * dout + m * dout), 2 * m * din * dout
+            b, fl = ELT * (m * din + m * dout) + 4 * din * dout, 2 * m * din * dout
         elif name.startswith("bwd_dense"):       # reads dF, F (mask), saved; writes dS; two products
-            b, fl = 4 * (2 * m * dout + 2 * m * din + din * dout), 4 * m * din * dout
+            b, fl = ELT * (2 * m * dout + 2 * m * din) + 4 * din * dout, 4 * m * din * dout
         elif name.startswith("gemm_nt"):
             b, fl = 4 * (m * dout + din * dout + m * din), 2 * m * din * dout
         elif name.startswith("gemm_tn<"):
@@ -182,7 +192,7 @@ def main():
     achieved = d_bytes / d_avg / 1e6
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(dominant) if args.scale == 1.0 else None,
+                "traffic": measured_traffic(dominant) if (args.scale == 1.0 and args.dtype == "f32") else None,
                 "algorithmic_bytes_per_launch": int(d_bytes), "avg_launch_ms": round(d_avg, 4)}
     # whole sparse products (all their kernels), the figure the metric names
     def spmm_total(tag, rows, ent):
@@ -195,13 +205,13 @@ def main():
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, rowptr, col, val, X, W, dF, args.cpu_sample_div)
+        cpu = cpu_baseline(cfg, rowptr, col, val, X.float(), W, dF.float(), args.cpu_sample_div)
 
     out = {
         "metric": METRIC, "value": round(ms_per_step, 4), "unit": "ms per GCN layer fwd+bwd",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "configs[3]: one GPU's 7M x 28M shard block of a billion-edge graph, fp32, "
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[3]: one GPU's 7M x 28M shard block of a billion-edge graph, {args.dtype}, "
                                "layer 32 -> 128, aggregate-first" + ("" if args.scale == 1.0 else f" (SHRUNK x{args.scale})"),
                    "m": m, "k": k, "nnz": nnz, "din": din, "dout": dout, "order": "agg_first",
                    "rows_entries_by_bin(<256,<4096,>=4096)": {"A": [list(rows_f), list(ent_f)], "At": [list(rows_b), list(ent_b)]}},

@@ -221,12 +221,14 @@ plx_status run(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t l
 
 }  // namespace
 
-bool bwd_dense_supported(int64_t Mp, int64_t N, plx_dtype dtype) { return dtype == PLX_F32 && Mp <= 128 && N <= 128; }
+bool bwd_dense_supported(int64_t Mp, int64_t N, plx_dtype dtype) { return (dtype == PLX_F32 || dtype == PLX_BF16) && Mp <= 128 && N <= 128; }
 
 plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, const void* P, int64_t ldp, const void* Q,
                             int64_t ldq, const void* Zm, int64_t ldz, const float* W, int64_t ldw, void* dOut, int64_t ldo,
                             float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes) {
     if (!bwd_dense_supported(Mp, N, dtype)) return fail(ctx, PLX_ERR_INTERNAL, "fused backward called outside its range");
+    if (dtype == PLX_BF16)
+        return launch_bwd_dense_bf16(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, dW, lddw, ws, ws_bytes);
     if (ws_bytes < gemm_tn_workspace(R, Mp, N)) return fail(ctx, PLX_ERR_SHAPE, "workspace too small");
     const int64_t rpc = tn_rows_per_chunk(R, Mp, N);
     const int64_t chunks = std::max<int64_t>(1, ceil_div(R, rpc));

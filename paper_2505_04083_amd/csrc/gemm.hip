@@ -361,7 +361,10 @@ size_t gemm_tn_workspace(int64_t R, int64_t M, int64_t N) {
 
 plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                        const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype, void* Fact, int64_t ldf) {
-    if (dtype != PLX_F32) return fail(ctx, PLX_ERR_UNSUPPORTED, "bf16 dense products are not built yet");
+    if (dtype == PLX_BF16) {
+        if (bt) return fail(ctx, PLX_ERR_UNSUPPORTED, "the bf16 A B^T product exists only inside the fused backward kernel");
+        return launch_gemm_small_bf16(ctx, M, N, K, A, lda, B, ldb, C, ldc, Fact, ldf);
+    }
     if (N >= (int64_t(1) << 20) || K >= (int64_t(1) << 30)) return fail(ctx, PLX_ERR_UNSUPPORTED, "N or K too large");
     const float* a = static_cast<const float*>(A);
     float* c = static_cast<float*>(C);
@@ -417,7 +420,8 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
 
 plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const void* A, int64_t lda, const void* B,
                           int64_t ldb, float* C, int64_t ldc, plx_dtype dtype, void* ws, size_t ws_bytes) {
-    if (dtype != PLX_F32) return fail(ctx, PLX_ERR_UNSUPPORTED, "bf16 dense products are not built yet");
+    if (dtype == PLX_BF16)   // the fused kernel without its second product and without a mask
+        return launch_bwd_dense_bf16(ctx, R, M, N, A, lda, B, ldb, nullptr, 0, nullptr, 0, nullptr, 0, C, ldc, ws, ws_bytes);
     if (M >= (int64_t(1) << 20) || N >= (int64_t(1) << 20)) return fail(ctx, PLX_ERR_UNSUPPORTED, "M or N too large");
     if (ws_bytes < gemm_tn_workspace(R, M, N)) return fail(ctx, PLX_ERR_SHAPE, "workspace too small");
     const float* a = static_cast<const float*>(A);

@@ -151,6 +151,13 @@ plx_status launch_relu_bwd(plx_ctx* ctx, int64_t rows, int64_t cols, const void*
 plx_status launch_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, int64_t ldz, const int64_t* y,
                              void* dZ, int64_t lddz, float* row_loss, float* loss, plx_dtype dtype);
 
+// bf16 storage / fp32 accumulation variants (widths up to 128)
+plx_status launch_gemm_small_bf16(plx_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                                  const float* W, int64_t ldw, void* C, int64_t ldc, void* Fact, int64_t ldf);
+plx_status launch_bwd_dense_bf16(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, const void* P, int64_t ldp, const void* Q,
+                                 int64_t ldq, const void* Zm, int64_t ldz, const float* W, int64_t ldw, void* dOut,
+                                 int64_t ldo, float* dW, int64_t lddw, void* ws, size_t ws_bytes);
+
 inline size_t elt_size(plx_dtype t) { return t == PLX_BF16 ? 2 : 4; }
 inline size_t align256(size_t b) { return (b + 255) & ~size_t(255); }
 
