@@ -1,18 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the per-GPU GCN hot path on one MI355X.
 
-One "step" = one GCN layer forward + backward (every row of the hot path: sparse product,
-dense product, activation, activation gradient, transposed sparse product, the two backward
-dense products) on the workload the headline metric is quoted on: ONE GPU's SHARD of a
+Default workload (the one the headline metric is quoted on): configs[3], ONE GPU's SHARD of a
 billion-edge graph -- a 7M x 28M double-permuted adjacency block with ~200M stored entries,
-feature slice 28M x 32, weight slice 32 x 128 (fp32), run in the paper's order (Eq. 2.1 then
-2.2: aggregate at width 32, then combine).  Inputs are synthetic, seeded, generated on the GPU
-and resident in HBM before the timed region.
+feature slice 28M x 32, weight slice 32 x 128 (fp32).  One "step" = one GCN layer forward +
+backward over it (every row of the hot path: sparse product, dense product, activation, activation
+gradient, transposed sparse product, the two backward dense products), run in the paper's order
+(Eq. 2.1 then 2.2: aggregate at width 32, then combine).  `--workload tiny|social|copurchase|road`
+times a whole L-layer network forward + backward (with the loss head) on the other workloads of
+the benchmark spec instead.  Inputs are synthetic, seeded, generated on the GPU and resident in HBM
+before the timed region.
 
 Prints ONE JSON line.  Besides the contract keys it carries
   "roofline":     the dominant kernel's algorithmic HBM bytes / its average duration (HIP events
                   recorded around every launch inside the timed steps) against 8 TB/s,
-  "cpu_baseline": the CPU oracle timed on a bounded sample of the same workload,
+  "cpu_baseline": the CPU oracle timed on a bounded sample of the same workload (default workload),
   "kernels":      per-kernel ms / GB/s / GFLOP/s of one step (information only).
 """
 from __future__ import annotations
@@ -20,6 +22,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -28,7 +31,6 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-MFMA_F32_PEAK_TFLOPS = 157.3
 METRIC = "GCN layer fwd+bwd ms; SpMM achieved HBM GB/s (% roofline) on 1 MI355X"
 
 
@@ -37,49 +39,72 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", choices=["shard", "tiny", "social", "copurchase", "road"], default="shard")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only; <1 is not the metric)")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
                     help="storage type of activations / gradients (the headline metric is f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-div", type=int, default=2, help="oracle sample = 1/div of the rows")
     ap.add_argument("--copy-ref", action="store_true",
-                    help="also run one plain device copy of known size (reference dispatch for counter scaling)")
+                    help="also run plain device copies of known size (reference dispatch for counter scaling)")
     return ap.parse_args()
 
 
-ELT = 4   # bytes per dense element (set from --dtype)
+def kernel_cost(name, bins):
+    """(algorithmic HBM bytes, flops) of one launch, from the sizes in the timing label.
 
-
-def spmm_bytes(rows, entries, d, s=None):
-    """Algorithmic bytes of a sparse product over `rows` rows holding `entries` stored entries:
-    8 B of CSR per entry (value + column), one s*d-byte gathered operand row per entry (the
-    double permutation leaves no reuse between entries), a 4 B row pointer and one s*d-byte
-    output row per row."""
-    s = ELT if s is None else s
-    return entries * (8 + s * d) + rows * (4 + s * d)
+    Sparse product over `rows` rows holding `entries` stored entries at width d: 8 B of CSR per
+    entry (value + column), one s*d-byte gathered operand row per entry (the double permutation
+    leaves no reuse between entries), a 4 B row pointer and one s*d-byte output row per row.
+    Dense products: every operand and result once."""
+    m = re.match(r"spmm_(subwave|wave|split)<(f32|bf16),G\d+,VW\d+,d(\d+)>\[(A|At)\]", name)
+    if m:
+        kind, dt, d, o = m.groups()
+        s, d = (4 if dt == "f32" else 2), int(d)
+        rows, ent = bins[o]
+        i = {"subwave": 0, "wave": 1, "split": 2}[kind]
+        return ent[i] * (8 + s * d) + rows[i] * (4 + s * d), 2 * ent[i] * d
+    m = re.match(r"gemm_(nn|nt)<(f32|bf16)>\[M(\d+),N(\d+),K(\d+)\]", name)
+    if m:
+        s = 4 if m.group(2) == "f32" else 2
+        M, N, K = map(int, m.groups()[2:])
+        return s * (M * K + M * N) + 4 * K * N, 2 * M * N * K
+    m = re.match(r"gemm_tn<(f32|bf16)>\[R(\d+),M(\d+),N(\d+)\]", name)
+    if m:
+        s = 4 if m.group(1) == "f32" else 2
+        R, M, N = map(int, m.groups()[1:])
+        return s * R * (M + N) + 4 * M * N, 2 * R * M * N
+    m = re.match(r"bwd_dense<(f32|bf16)>\[R(\d+),M(\d+),N(\d+)\]", name)
+    if m:       # reads the gradient, the mask source and P; writes dOut; two products
+        s = 4 if m.group(1) == "f32" else 2
+        R, M, N = map(int, m.groups()[1:])
+        return s * R * (2 * N + 2 * M) + 4 * M * N, 4 * R * M * N
+    m = re.match(r"(relu|relu_bwd|softmax_ce)\[R(\d+),C(\d+)\]", name)
+    if m:
+        R, C = int(m.group(2)), int(m.group(3))
+        return 4 * R * C * {"relu": 2, "relu_bwd": 3, "softmax_ce": 2}[m.group(1)], 0
+    return None, None
 
 
 def measured_traffic(name):
     """HBM bytes per launch of the kernel behind a timing label, from the committed rocprofv3
-    FETCH_SIZE / WRITE_SIZE summary of this same workload (profiles/traffic_layer_shard_f32.json,
+    FETCH_SIZE / WRITE_SIZE summary of the default workload (profiles/traffic_layer_shard_f32.json,
     counters already scaled by a plain 4 GiB copy); None if the summary has no such kernel."""
     path = os.path.join(ROOT, "profiles", "traffic_layer_shard_f32.json")
     if not os.path.exists(path):
         return None
     k = json.load(open(path))["kernels"]
-    import re
-    m = re.match(r"spmm_(subwave|wave|split)<(f32|bf16),G(\d+),VW(\d+)>\[(A|At)\]", name)
+    m = re.match(r"spmm_(subwave|wave|split)<f32,G(\d+),VW(\d+),d\d+>\[(A|At)\]", name)
     keys = []
     if m:
-        kind, dt, g, vw, o = m.groups()
-        t = "float" if dt == "f32" else "unsigned short"
-        base = {"subwave": ["k_spmm_subwave"], "wave": ["k_spmm_wave"], "split": ["k_spmm_segment"]}[kind]
-        keys = [f"{b}<{t}, {g}, {vw}> [{o}]" for b in base]
+        kind, g, vw, o = m.groups()
+        base = {"subwave": "k_spmm_subwave", "wave": "k_spmm_wave", "split": "k_spmm_segment"}[kind]
+        keys = [f"{base}<float, {g}, {vw}> [{o}]"]
         if kind == "split":
-            keys.append(f"k_spmm_combine<{t}> [{o}]")
-    elif name.startswith("gemm_nn"):
+            keys.append(f"k_spmm_combine<float> [{o}]")
+    elif name.startswith("gemm_nn<f32>"):
         keys = [x for x in k if x.startswith("k_gemm_small_f32") or x.startswith("k_gemm_f32")]
-    elif name.startswith("bwd_dense"):
+    elif name.startswith("bwd_dense<f32>"):
         keys = [x for x in k if x.startswith("k_bwd_dense_f32")]
     if not keys or any(x not in k for x in keys):
         return None
@@ -95,46 +120,75 @@ def main():
 
     import torch
     import paper_2505_04083_amd as plx
+    from paper_2505_04083_amd.network import GcnNetwork
     import synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
-    cfg = synth.CONFIGS["shard"]
+    cfg = synth.CONFIGS[args.workload]
     if args.scale != 1.0:
         cfg = cfg.scaled(args.scale)
-    din, dout = cfg.dims
-    global ELT
     tdt = torch.float32 if args.dtype == "f32" else torch.bfloat16
-    ELT = 4 if args.dtype == "f32" else 2
     code = plx.PLX_F32 if args.dtype == "f32" else plx.PLX_BF16
-
-    t0 = time.time()
-    rowptr, col, val = synth.shard_block(cfg.seed, cfg.m, cfg.k, cfg.n_samples, dev)
-    torch.cuda.synchronize()
-    t_gen = time.time() - t0
-    nnz = int(col.numel())
-    X = synth.normal(cfg.seed, synth.S_FEAT, cfg.k, din, dev, tdt)
-    dF = synth.normal(cfg.seed, synth.S_AUX, cfg.m, dout, dev, tdt)
-    W = synth.glorot(cfg.seed, 0, din, dout, dev)
-
     ctx = plx.plx_ctx(0)
-    t0 = time.time()
-    csr = plx.plx_csr_import(ctx, cfg.m, cfg.k, rowptr, col, val)
-    t_import = time.time() - t0
-    order = plx.PLX_ORDER_AGG_FIRST
-    ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, code, plx.PLX_ACT_RELU, order),
-                     dtype=torch.uint8, device=dev)
-    F = torch.empty(cfg.m, dout, device=dev, dtype=tdt)   # only the activated output is stored (its sign serves Eq. 2.4)
-    saved = torch.empty(cfg.m, din, device=dev, dtype=tdt)
-    dX = torch.empty(cfg.k, din, device=dev, dtype=tdt); dW = torch.empty(din, dout, device=dev)
+    cpu_inputs = None
 
-    def step():
-        plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, None, F, saved, ws, act=plx.PLX_ACT_RELU, order=order)
-        plx.plx_gcn_layer_bwd(ctx, csr, False, X, W, F, dF, saved, dX, dW, ws, act=plx.PLX_ACT_RELU, order=order)
+    t0 = time.time()
+    if cfg.kind == "shard":
+        din, dout = cfg.dims
+        rowptr, col, val = synth.shard_block(cfg.seed, cfg.m, cfg.k, cfg.n_samples, dev)
+        torch.cuda.synchronize()
+        t_gen = time.time() - t0
+        X = synth.normal(cfg.seed, synth.S_FEAT, cfg.k, din, dev, tdt)
+        dF = synth.normal(cfg.seed, synth.S_AUX, cfg.m, dout, dev, tdt)
+        W = synth.glorot(cfg.seed, 0, din, dout, dev)
+        t0 = time.time()
+        csr = plx.plx_csr_import(ctx, cfg.m, cfg.k, rowptr, col, val)
+        t_build = time.time() - t0
+        order = plx.PLX_ORDER_AGG_FIRST
+        ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, code, plx.PLX_ACT_RELU, order),
+                         dtype=torch.uint8, device=dev)
+        F = torch.empty(cfg.m, dout, device=dev, dtype=tdt)   # only the activated output is stored (its sign serves Eq. 2.4)
+        saved = torch.empty(cfg.m, din, device=dev, dtype=tdt)
+        dX = torch.empty(cfg.k, din, device=dev, dtype=tdt); dW = torch.empty(din, dout, device=dev)
+
+        def step():
+            plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, None, F, saved, ws, act=plx.PLX_ACT_RELU, order=order)
+            plx.plx_gcn_layer_bwd(ctx, csr, False, X, W, F, dF, saved, dX, dW, ws, act=plx.PLX_ACT_RELU, order=order)
+
+        cpu_inputs = (rowptr, col, val, X, W, dF)
+        workload = (f"configs[3]: one GPU's 7M x 28M shard block of a billion-edge graph, {args.dtype}, "
+                    "layer 32 -> 128, aggregate-first")
+        unit = "ms per GCN layer fwd+bwd"
+        shape = {"m": cfg.m, "k": cfg.k, "din": din, "dout": dout, "order": "agg_first"}
+    else:
+        src, dst = cfg.edges(dev)
+        pr, pc = cfg.perms(dev)
+        torch.cuda.synchronize()
+        t_gen = time.time() - t0
+        t0 = time.time()
+        csr = plx.plx_build_csr(ctx, cfg.n, src, dst, pr, pc)
+        t_build = time.time() - t0
+        del src, dst
+        H0 = synth.normal(cfg.seed, synth.S_FEAT, cfg.n, cfg.dims[0], dev, tdt)       # random rows: any order is P_c order
+        Ws = cfg.weights(dev)
+        y = cfg.labels(dev)
+        net = GcnNetwork(ctx, csr, Ws, dtype=tdt)
+
+        def step():
+            net.step(H0, y)
+
+        idx = {"tiny": 0, "social": 1, "copurchase": 2, "road": 4}[args.workload]
+        workload = (f"configs[{idx}]: {args.workload} graph, {args.dtype}, {len(Ws)}-layer GCN "
+                    + "-".join(map(str, cfg.dims)) + ", whole forward + backward with loss head, AUTO order")
+        unit = f"ms per {len(Ws)}-layer network fwd+bwd"
+        shape = {"n": cfg.n, "dims": cfg.dims}
+    if args.scale != 1.0:
+        workload += f" (SHRUNK x{args.scale})"
 
     if args.copy_ref:
-        # 2^30 fp32 read + 2^30 fp32 written by one plain copy kernel: the known-size dispatch the
+        # 2^30 fp32 read + 2^30 fp32 written by a plain copy: the known-size dispatch the
         # FETCH_SIZE / WRITE_SIZE counters are scaled by
         ref_src = torch.ones(1 << 30, dtype=torch.float32, device=dev)
         ref_dst = torch.empty_like(ref_src)
@@ -144,6 +198,7 @@ def main():
         del ref_src, ref_dst
     for _ in range(args.warmup):
         step()
+    plx.plx_sync(ctx)
     torch.cuda.synchronize()
     plx.plx_timing_enable(ctx, True)
     t0 = time.perf_counter()
@@ -157,66 +212,44 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
 
     # ---- per-kernel accounting (algorithmic bytes / flops of one launch) -------------------------
-    (rows_f, ent_f), (rows_b, ent_b) = plx.plx_csr_bins(csr, False), plx.plx_csr_bins(csr, True)
-    m, k = cfg.m, cfg.k
-    alg = {}
-    for name in timing:
-        b = fl = None
-        if name.startswith("spmm_"):
-            rows, ent = (rows_b, ent_b) if name.endswith("[At]") else (rows_f, ent_f)
-            i = {"spmm_subwave": 0, "spmm_wave": 1, "spmm_split": 2}[name.split("<")[0]]
-            b, fl = spmm_bytes(rows[i], ent[i], din), 2 * ent[i] * din
-        elif name.startswith("gemm_nn"):
-            b, fl = ELT * (m * din + m * dout) + 4 * din * dout, 2 * m * din * dout
-        elif name.startswith("bwd_dense"):       # reads dF, F (mask), saved; writes dS; two products
-            b, fl = ELT * (2 * m * dout + 2 * m * din) + 4 * din * dout, 4 * m * din * dout
-        elif name.startswith("gemm_nt"):
-            b, fl = 4 * (m * dout + din * dout + m * din), 2 * m * din * dout
-        elif name.startswith("gemm_tn<"):
-            b, fl = 4 * (m * din + m * dout + din * dout), 2 * m * din * dout
-        elif name == "relu":
-            b, fl = 4 * 2 * m * dout, 0
-        elif name == "relu_bwd":
-            b, fl = 4 * 3 * m * dout, 0
-        alg[name] = (b, fl)
+    bins = {"A": plx.plx_csr_bins(csr, False), "At": plx.plx_csr_bins(csr, True)}
+    cost = {name: kernel_cost(name, bins) for name in timing}
     kernels = {}
     for name, (count, total_ms) in timing.items():
         avg = total_ms / max(count, 1)
-        b, fl = alg.get(name, (None, None))
+        b, fl = cost[name]
         kernels[name] = {"launches_per_step": count / args.steps, "avg_ms": round(avg, 4),
                          "GBps": None if not b else round(b / avg / 1e6, 1),
                          "GFLOPs": None if not fl else round(fl / avg / 1e6, 1)}
-    dominant = max(timing, key=lambda n: timing[n][1])
+    dominant = max((n for n in timing if cost[n][0]), key=lambda n: timing[n][1])
     d_avg = timing[dominant][1] / timing[dominant][0]
-    d_bytes = alg[dominant][0]
+    d_bytes = cost[dominant][0]
     achieved = d_bytes / d_avg / 1e6
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(dominant) if (args.scale == 1.0 and args.dtype == "f32") else None,
+                "traffic": measured_traffic(dominant) if (args.scale == 1.0 and cfg.kind == "shard") else None,
                 "algorithmic_bytes_per_launch": int(d_bytes), "avg_launch_ms": round(d_avg, 4)}
-    # whole sparse products (all their kernels), the figure the metric names
-    def spmm_total(tag, rows, ent):
-        ms = sum(t / c for n, (c, t) in timing.items() if n.startswith("spmm_") and n.endswith(tag))
-        by = sum(spmm_bytes(rows[i], ent[i], din) for i in range(3))
-        return {"ms": round(ms, 4), "GBps": round(by / ms / 1e6, 1), "frac_of_8TBps": round(by / ms / 1e6 / HBM_PEAK_GBS, 4),
-                "GFLOPs": round(2 * sum(ent) * din / ms / 1e6, 1)}
-    spmm = {"A_x_X": spmm_total("[A]", rows_f, ent_f), "At_x_G": spmm_total("[At]", rows_b, ent_b)}
+    # all sparse-product kernels together, the figure the metric names
+    sp = [(n, c, t) for n, (c, t) in timing.items() if n.startswith("spmm_")]
+    sp_ms = sum(t for _, _, t in sp) / args.steps
+    sp_by = sum(cost[n][0] * c for n, c, _ in sp) / args.steps
+    sp_fl = sum(cost[n][1] * c for n, c, _ in sp) / args.steps
+    spmm = {"ms_per_step": round(sp_ms, 4), "GBps": round(sp_by / sp_ms / 1e6, 1),
+            "frac_of_8TBps": round(sp_by / sp_ms / 1e6 / HBM_PEAK_GBS, 4), "GFLOPs": round(sp_fl / sp_ms / 1e6, 1)}
 
-    # ---- CPU oracle on a bounded sample of the same workload ----------------------------------------
     cpu = None
-    if not args.no_cpu_baseline:
+    if cfg.kind == "shard" and not args.no_cpu_baseline:
+        rowptr, col, val, X, W, dF = cpu_inputs
         cpu = cpu_baseline(cfg, rowptr, col, val, X.float(), W, dF.float(), args.cpu_sample_div)
 
     out = {
-        "metric": METRIC, "value": round(ms_per_step, 4), "unit": "ms per GCN layer fwd+bwd",
+        "metric": METRIC, "value": round(ms_per_step, 4), "unit": unit,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": f"configs[3]: one GPU's 7M x 28M shard block of a billion-edge graph, {args.dtype}, "
-                               "layer 32 -> 128, aggregate-first" + ("" if args.scale == 1.0 else f" (SHRUNK x{args.scale})"),
-                   "m": m, "k": k, "nnz": nnz, "din": din, "dout": dout, "order": "agg_first",
-                   "rows_entries_by_bin(<256,<4096,>=4096)": {"A": [list(rows_f), list(ent_f)], "At": [list(rows_b), list(ent_b)]}},
+        "config": {"workload": workload, **shape, "nnz": csr.nnz,
+                   "rows_entries_by_bin(<256,<4096,>=4096)": {k_: [list(v[0]), list(v[1])] for k_, v in bins.items()}},
         "roofline": roofline, "cpu_baseline": cpu, "spmm": spmm, "kernels": kernels,
-        "setup_s": {"generate": round(t_gen, 2), "csr_import_transpose_bins": round(t_import, 2)},
+        "setup_s": {"generate": round(t_gen, 2), "csr_build_transpose_bins": round(t_build, 2)},
     }
     print(json.dumps(out))
 

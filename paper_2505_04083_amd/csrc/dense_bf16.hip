@@ -324,7 +324,7 @@ plx_status launch_gemm_small_bf16(plx_ctx* ctx, int64_t M, int64_t N, int64_t K,
     const int64_t blocks = std::min<int64_t>(ceil_div(M, rows), (int64_t)ctx->n_cu * per_cu);
     const int vec_a = aligned16(A) && lda % 8 == 0;
     char label[64];
-    snprintf(label, sizeof label, "gemm_nn<bf16>[N%lld,K%lld]", (long long)N, (long long)K);
+    snprintf(label, sizeof label, "gemm_nn<bf16>[M%lld,N%lld,K%lld]", (long long)M, (long long)N, (long long)K);
     KernelTimer kt(ctx, label);
 #define PLX_SMALL(TK, TN, RBV)                                                                                  \
     do {                                                                                                        \
@@ -359,7 +359,7 @@ plx_status launch_bwd_dense_bf16(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N,
     float* part = static_cast<float*>(ws);
     const int tmb = Mp <= 32 ? 1 : (Mp <= 64 ? 2 : 4), tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     char label[64];
-    snprintf(label, sizeof label, "bwd_dense<bf16>[M%lld,N%lld]", (long long)Mp, (long long)N);
+    snprintf(label, sizeof label, "bwd_dense<bf16>[R%lld,M%lld,N%lld]", (long long)R, (long long)Mp, (long long)N);
     plx_status st;
     {
         KernelTimer kt(ctx, label);

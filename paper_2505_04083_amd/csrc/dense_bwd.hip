@@ -30,9 +30,12 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // loads of the next tile are in flight while the matrix cores work on the current one.
 template <int TR, int COLS> struct TileRegs { float4 v[TR * COLS / 1024]; };   // TR * COLS / 4 float4 over 256 threads
 
-template <int TR, int COLS>
+// VEC: rows are 16-byte aligned and ncols is a multiple of 4, so a thread's 4 columns are all valid
+// or all out of range, and rows past the end are read from the last valid row and zeroed by a
+// select -- no per-element branches on the fast path.
+template <int TR, int COLS, bool VEC>
 __device__ __forceinline__ void fetch_tile(TileRegs<TR, COLS>& t, const float* __restrict__ src, int64_t ld, int64_t r0,
-                                           int64_t r_end, int ncols, bool vec, int tid) {
+                                           int64_t r_end, int ncols, int tid) {
     constexpr int Q4 = COLS / 4;
 #pragma unroll
     for (int i = 0; i < TR * COLS / 1024; ++i) {
@@ -40,16 +43,18 @@ __device__ __forceinline__ void fetch_tile(TileRegs<TR, COLS>& t, const float* _
         const int64_t gr = r0 + r;
         const int gc = 4 * q;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (gr < r_end && gc < ncols) {
-            const float* p = src + gr * ld + gc;
-            if (vec && gc + 3 < ncols) {
-                v = *reinterpret_cast<const float4*>(p);
-            } else {
-                v.x = p[0];
-                if (gc + 1 < ncols) v.y = p[1];
-                if (gc + 2 < ncols) v.z = p[2];
-                if (gc + 3 < ncols) v.w = p[3];
+        if constexpr (VEC) {
+            if (COLS == ncols || gc < ncols) {
+                const int64_t rr = gr < r_end ? gr : r_end - 1;
+                v = *reinterpret_cast<const float4*>(src + rr * ld + gc);
+                if (gr >= r_end) v = make_float4(0.f, 0.f, 0.f, 0.f);
             }
+        } else if (gr < r_end && gc < ncols) {
+            const float* p = src + gr * ld + gc;
+            v.x = p[0];
+            if (gc + 1 < ncols) v.y = p[1];
+            if (gc + 2 < ncols) v.z = p[2];
+            if (gc + 3 < ncols) v.w = p[3];
         }
         t.v[i] = v;
     }
@@ -73,13 +78,13 @@ __device__ __forceinline__ void commit_tile(float (*dst)[COLS + 4], const TileRe
     }
 }
 
-template <int TMB, int TNB, bool MASK, int kTR>   // Mp <= 32*TMB, N <= 32*TNB; kTR rows per tile (32 or 64)
+template <int TMB, int TNB, bool MASK, int kTR, bool VEC>   // Mp <= 32*TMB, N <= 32*TNB; kTR rows per tile (32 or 64)
 __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N, const float* __restrict__ P, int64_t ldp,
                                                        const float* __restrict__ Q, int64_t ldq,
                                                        const float* __restrict__ Zm, int64_t ldz,
                                                        const float* __restrict__ W, int64_t ldw,
                                                        float* __restrict__ dOut, int64_t ldo, float* __restrict__ part,
-                                                       int64_t rows_per_chunk, int vec_p, int vec_q) {
+                                                       int64_t rows_per_chunk) {
     constexpr int MP = 32 * TMB, NP = 32 * TNB;
     // dW blocks over 4 wavefronts: NB >= 4 gives NB/4 blocks each; with NB < 4 the 4/NB wavefronts
     // sharing a block take interleaved row pairs of every tile and write separate partial tiles.
@@ -117,9 +122,9 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
     // so the wait for the prefetched loads never includes waiting for store acknowledgements.
     TileRegs<kTR, NP> rq, rz;
     TileRegs<kTR, MP> rp;
-    fetch_tile<kTR, NP>(rq, Q, ldq, r_begin, r_end, N, vec_q, tid);
-    if (MASK) fetch_tile<kTR, NP>(rz, Zm, ldz, r_begin, r_end, N, vec_q, tid);
-    fetch_tile<kTR, MP>(rp, P, ldp, r_begin, r_end, Mp, vec_p, tid);
+    fetch_tile<kTR, NP, VEC>(rq, Q, ldq, r_begin, r_end, N, tid);
+    if (MASK) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, r_begin, r_end, N, tid);
+    fetch_tile<kTR, MP, VEC>(rp, P, ldp, r_begin, r_end, Mp, tid);
     commit_tile<kTR, NP, MASK>(Qs, rq, rz, tid);
     commit_tile<kTR, MP, false>(Ps, rp, rp, tid);
     __syncthreads();
@@ -127,9 +132,9 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
     for (int64_t r0 = r_begin; r0 < r_end; r0 += kTR) {
         const bool more = r0 + kTR < r_end;
         if (more) {
-            fetch_tile<kTR, NP>(rq, Q, ldq, r0 + kTR, r_end, N, vec_q, tid);
-            if (MASK) fetch_tile<kTR, NP>(rz, Zm, ldz, r0 + kTR, r_end, N, vec_q, tid);
-            fetch_tile<kTR, MP>(rp, P, ldp, r0 + kTR, r_end, Mp, vec_p, tid);
+            fetch_tile<kTR, NP, VEC>(rq, Q, ldq, r0 + kTR, r_end, N, tid);
+            if (MASK) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, r0 + kTR, r_end, N, tid);
+            fetch_tile<kTR, MP, VEC>(rp, P, ldp, r0 + kTR, r_end, Mp, tid);
         }
 
         floatx4 acc_o[CPW];
@@ -159,14 +164,19 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
             commit_tile<kTR, MP, false>(Ps, rp, rp, tid);
         }
         if (dOut) {
+            const bool full = r0 + kTR <= r_end;                       // uniform: only the last tile is partial
 #pragma unroll
             for (int c = 0; c < CPW; ++c) {
                 const int gc = 16 * (ocb0 + ocbs * c) + l16;
+                float* o = dOut + (r0 + 16 * orb + 4 * lq) * ldo + gc;
                 if (gc < Mp) {
+                    if (full) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int64_t gr = r0 + 16 * orb + 4 * lq + r;
-                        if (gr < r_end) dOut[gr * ldo + gc] = acc_o[c][r];
+                        for (int r = 0; r < 4; ++r) o[r * ldo] = acc_o[c][r];
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (r0 + 16 * orb + 4 * lq + r < r_end) o[r * ldo] = acc_o[c][r];
                     }
                 }
             }
@@ -190,25 +200,37 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-#ifndef PLX_BWD_TILE_ROWS
-#define PLX_BWD_TILE_ROWS 64
-#endif
+template <int TMB, int TNB, bool MASK, int kTR>
+plx_status run_tile(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
+                    const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
+                    int64_t rpc, int64_t chunks) {
+    constexpr int MP = 32 * TMB, NP = 32 * TNB;
+    const size_t lds = sizeof(float) * (kTR * (NP + 4) + kTR * (MP + 4) + MP * (NP + 4));
+    const bool vec = aligned16(P) && ldp % 4 == 0 && Mp % 4 == 0 && aligned16(Q) && ldq % 4 == 0 && N % 4 == 0 &&
+                     (!Zm || (aligned16(Zm) && ldz % 4 == 0)) && R > 0;
+    auto launch = [&](auto kern) -> plx_status {
+        if (lds > 48 * 1024)
+            PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        kern<<<dim3((unsigned)chunks), 256, lds, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc);
+        PLX_HIP(ctx, hipGetLastError());
+        return PLX_OK;
+    };
+    return vec ? launch(k_bwd_dense_f32<TMB, TNB, MASK, kTR, true>) : launch(k_bwd_dense_f32<TMB, TNB, MASK, kTR, false>);
+}
 
+// 64-row tiles halve the per-tile overheads; 32-row tiles need less LDS.  Take 32 rows when that
+// lets more workgroups share a CU (their phases then overlap), else 64.
 template <int TMB, int TNB, bool MASK>
 plx_status run_masked(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
-               const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
-               int64_t rpc, int64_t chunks) {
-    constexpr int MP = 32 * TMB, NP = 32 * TNB, kTR = PLX_BWD_TILE_ROWS;
-    const size_t lds = sizeof(float) * (kTR * (NP + 4) + kTR * (MP + 4) + MP * (NP + 4));
-    const int vec_p = aligned16(P) && ldp % 4 == 0;
-    const int vec_q = aligned16(Q) && ldq % 4 == 0 && (!Zm || (aligned16(Zm) && ldz % 4 == 0));
-    auto kern = k_bwd_dense_f32<TMB, TNB, MASK, kTR>;
-    if (lds > 48 * 1024)
-        PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    kern<<<dim3((unsigned)chunks), 256, lds, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc,
-                                                           vec_p, vec_q);
-    PLX_HIP(ctx, hipGetLastError());
-    return PLX_OK;
+                      const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
+                      int64_t rpc, int64_t chunks) {
+    constexpr int MP = 32 * TMB, NP = 32 * TNB;
+    constexpr size_t kLdsPerCu = 160 * 1024;
+    constexpr size_t lds64 = sizeof(float) * (64 * (NP + 4) + 64 * (MP + 4) + MP * (NP + 4));
+    constexpr size_t lds32 = sizeof(float) * (32 * (NP + 4) + 32 * (MP + 4) + MP * (NP + 4));
+    if (kLdsPerCu / lds32 > kLdsPerCu / lds64)
+        return run_tile<TMB, TNB, MASK, 32>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks);
+    return run_tile<TMB, TNB, MASK, 64>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks);
 }
 
 template <int TMB, int TNB>
@@ -235,7 +257,7 @@ plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, cons
     float* part = static_cast<float*>(ws);
     const int tmb = Mp <= 32 ? 1 : (Mp <= 64 ? 2 : 4), tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     char label[64];
-    snprintf(label, sizeof label, "bwd_dense<f32>[M%lld,N%lld]", (long long)Mp, (long long)N);
+    snprintf(label, sizeof label, "bwd_dense<f32>[R%lld,M%lld,N%lld]", (long long)R, (long long)Mp, (long long)N);
     plx_status st;
     {
         KernelTimer kt(ctx, label);

@@ -83,43 +83,69 @@ __global__ __launch_bounds__(256) void k_relu_bwd_flat(int64_t count, const T* Z
     }
 }
 
-// one thread per node: row max, sum of exponentials, gradient and the row's loss term
-template <typename T>
+// One group of GS lanes per node (GS a power of two <= 64): lane t of the group holds classes
+// t, t + GS, ... so the row is read and the gradient written with coalesced accesses; row max and
+// sum of exponentials are butterfly reductions inside the group.
+template <typename T, int GS, int MAXV>   // c <= GS * MAXV
 __global__ __launch_bounds__(256) void k_softmax_ce(int64_t n, int c, const T* __restrict__ Z, int64_t ldz,
                                                     const int64_t* __restrict__ y, T* __restrict__ dZ, int64_t lddz,
                                                     float* __restrict__ row_loss, float inv_n) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const T* z = Z + i * ldz;
-    float mx = widen(z[0]);
-    for (int j = 1; j < c; ++j) mx = fmaxf(mx, widen(z[j]));
+    const int t = threadIdx.x % GS;
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / GS;
+    const bool live = i < n;
+    const T* z = Z + (live ? i : 0) * ldz;
+    float v[MAXV];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < MAXV; ++q) {
+        const int j = t + q * GS;
+        v[q] = (live && j < c) ? widen(z[j]) : -INFINITY;
+        mx = fmaxf(mx, v[q]);
+    }
+#pragma unroll
+    for (int off = GS / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, GS));
     float sum = 0.f;
-    for (int j = 0; j < c; ++j) sum += expf(widen(z[j]) - mx);
+#pragma unroll
+    for (int q = 0; q < MAXV; ++q) {
+        v[q] = (t + q * GS < c) ? expf(v[q] - mx) : 0.f;
+        sum += v[q];
+    }
+#pragma unroll
+    for (int off = GS / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off, GS);
+    if (!live) return;
     const float inv = 1.f / sum;
     int64_t label = y[i];
     label = label < 0 ? 0 : (label >= c ? c - 1 : label);   // out-of-range labels are clamped
     T* g = dZ + i * lddz;
-    float zl = 0.f;
-    for (int j = 0; j < c; ++j) {
-        const float zj = widen(z[j]);
-        if (j == label) zl = zj;
-        g[j] = narrow<T>((expf(zj - mx) * inv - (j == label ? 1.f : 0.f)) * inv_n);
+#pragma unroll
+    for (int q = 0; q < MAXV; ++q) {
+        const int j = t + q * GS;
+        if (j < c) g[j] = narrow<T>((v[q] * inv - (j == label ? 1.f : 0.f)) * inv_n);
     }
-    row_loss[i] = -(zl - mx - logf(sum));
+    if (t == 0) row_loss[i] = -(widen(z[label]) - mx - logf(sum));
 }
 
-// fixed-order sum: slot g*256*stride receives the sum of live slots (g*256 + t)*stride
+// Fixed-order sum: the live slots are `stride` apart; block b adds the 2048 live slots of its range
+// (8 per thread, then a tree in LDS) into the first of them.  Repeated until one slot is left.
 __global__ __launch_bounds__(256) void k_sum_level(float* v, int64_t n_live, int64_t stride, float* out, float scale) {
-    const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (g * 256 >= n_live) return;
+    __shared__ float sh[256];
+    const int64_t base = (int64_t)blockIdx.x * 2048;
     float s = 0.f;
-    for (int t = 0; t < 256; ++t) {
-        const int64_t slot = g * 256 + t;
-        if (slot >= n_live) break;
-        s += v[slot * stride];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int64_t slot = base + threadIdx.x + 256 * q;
+        if (slot < n_live) s += v[slot * stride];
     }
-    if (out) *out = s * scale;
-    else v[g * 256 * stride] = s;
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) sh[threadIdx.x] += sh[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        if (out) *out = sh[0] * scale;
+        else v[base * stride] = sh[0];
+    }
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -133,7 +159,9 @@ dim3 grid2d(int64_t rows, int64_t cols) {
 template <typename T>
 plx_status relu_t(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, void* F, int64_t ldf) {
     hipStream_t s = ctx->stream;
-    KernelTimer kt(ctx, "relu");
+    char label[64];
+    snprintf(label, sizeof label, "relu[R%lld,C%lld]", (long long)rows, (long long)cols);
+    KernelTimer kt(ctx, label);
     if (ldz == cols && ldf == cols && aligned16(Z) && aligned16(F)) {
         int64_t count = rows * cols;
         k_relu_flat<T><<<dim3((unsigned)ceil_div(ceil_div(count, 4), 256)), 256, 0, s>>>(count, (const T*)Z, (T*)F);
@@ -148,7 +176,9 @@ template <typename T>
 plx_status relu_bwd_t(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, const void* dF,
                       int64_t lddf, void* dZ, int64_t lddz) {
     hipStream_t s = ctx->stream;
-    KernelTimer kt(ctx, "relu_bwd");
+    char label[64];
+    snprintf(label, sizeof label, "relu_bwd[R%lld,C%lld]", (long long)rows, (long long)cols);
+    KernelTimer kt(ctx, label);
     if (ldz == cols && lddf == cols && lddz == cols && aligned16(Z) && aligned16(dF) && aligned16(dZ)) {
         int64_t count = rows * cols;
         k_relu_bwd_flat<T><<<dim3((unsigned)ceil_div(ceil_div(count, 4), 256)), 256, 0, s>>>(count, (const T*)Z,
@@ -183,21 +213,28 @@ plx_status launch_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, 
         return PLX_OK;
     }
     const float inv_n = (float)(1.0 / (double)n);
-    KernelTimer kt(ctx, "softmax_ce");
-    dim3 grid((unsigned)ceil_div(n, 256));
-    if (dtype == PLX_F32)
-        k_softmax_ce<float><<<grid, 256, 0, s>>>(n, (int)c, (const float*)Z, ldz, y, (float*)dZ, lddz, row_loss, inv_n);
-    else
-        k_softmax_ce<bf16_t><<<grid, 256, 0, s>>>(n, (int)c, (const bf16_t*)Z, ldz, y, (bf16_t*)dZ, lddz, row_loss, inv_n);
+    char label[64];
+    snprintf(label, sizeof label, "softmax_ce[R%lld,C%lld]", (long long)n, (long long)c);
+    KernelTimer kt(ctx, label);
+    const int gs = c <= 32 ? 8 : (c <= 64 ? 16 : (c <= 128 ? 32 : 64));
+    dim3 grid((unsigned)ceil_div(n * gs, 256));
+#define PLX_SM(TT, GSV) \
+    k_softmax_ce<TT, GSV, (GSV == 64 ? 16 : 4)><<<grid, 256, 0, s>>>(n, (int)c, (const TT*)Z, ldz, y, (TT*)dZ, lddz, row_loss, inv_n)
+    if (dtype == PLX_F32) {
+        if (gs == 8) PLX_SM(float, 8); else if (gs == 16) PLX_SM(float, 16); else if (gs == 32) PLX_SM(float, 32); else PLX_SM(float, 64);
+    } else {
+        if (gs == 8) PLX_SM(bf16_t, 8); else if (gs == 16) PLX_SM(bf16_t, 16); else if (gs == 32) PLX_SM(bf16_t, 32); else PLX_SM(bf16_t, 64);
+    }
+#undef PLX_SM
     if (loss) {
         int64_t live = n, stride = 1;
         while (true) {
-            const int64_t groups = ceil_div(live, 256);
+            const int64_t groups = ceil_div(live, 2048);
             const bool last = groups == 1;
-            k_sum_level<<<dim3((unsigned)ceil_div(groups, 256)), 256, 0, s>>>(row_loss, live, stride, last ? loss : nullptr, inv_n);
+            k_sum_level<<<dim3((unsigned)groups), 256, 0, s>>>(row_loss, live, stride, last ? loss : nullptr, inv_n);
             if (last) break;
             live = groups;
-            stride *= 256;
+            stride *= 2048;
         }
     }
     PLX_HIP(ctx, hipGetLastError());

@@ -109,25 +109,33 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
 // The weight matrix is loaded into LDS once per workgroup; the workgroup then walks over 64-row
 // tiles of A (tile index strided by the grid), fetching the next tile into registers while the
 // matrix cores work on the current one.  Output: C and / or max(C, 0).
-// Rows per tile are 32 * RB with RB * TNB a multiple of 4, so every wavefront owns the same number
-// of 32x32 output blocks and no matrix instruction sits under a condition.
-template <int TKB, int TNB, int RB>   // K <= 32*TKB, N <= 32*TNB
+// v_mfma_f32_16x16x4_f32: wavefront w owns rows 16w..16w+15 of the tile and all CB 16-column blocks
+// (N is padded to 16, not 32, and K to 4: no matrix work on padding beyond that); lane l supplies
+// a = A[16w + l%16][k + l/16], b = B[k + l/16][16c + l%16] and receives
+// acc[r] = C[16w + 4*(l/16) + r][16c + l%16].
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+constexpr int kFwdRows = 64;
+
+// For N > 64 the 64 x N tile is instead cut into 32x32 blocks (v_mfma_f32_32x32x2_f32, two per
+// wavefront for N = 128; block q belongs to wavefront q % 4): measured faster at that width.
+template <int TKB, int CB, bool VEC>   // K <= 32*TKB, N <= 16*CB; VEC: 16-byte aligned rows, K % 4 == 0
 __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K, const float* __restrict__ A,
                                                         int64_t lda, const float* __restrict__ B, int64_t ldb,
                                                         float* __restrict__ C, int64_t ldc, float* __restrict__ F,
-                                                        int64_t ldf, int vec_a) {
-    constexpr int KP = 32 * TKB, NP = 32 * TNB, kFwdRows = 32 * RB;
-    constexpr int NBLK = RB * TNB / 4;                // 32x32 blocks per wavefront
+                                                        int64_t ldf) {
+    constexpr bool WIDE = CB > 4;                     // 32x32 blocks (N padded to 32) instead of 16x16
+    constexpr int KP = 32 * TKB, NP = WIDE ? 32 * ((CB + 1) / 2) : 16 * CB;
+    constexpr int TNB = NP / 32, NBLK = WIDE ? (2 * TNB + 3) / 4 : 1;
+    static_assert(!WIDE || (2 * TNB) % 4 == 0, "wide tiles must split evenly over 4 wavefronts");
     constexpr int NLD = kFwdRows * KP / 4 / 256;      // float4 per thread per tile
-    static_assert((RB * TNB) % 4 == 0, "tile must split evenly over 4 wavefronts");
     extern __shared__ __align__(16) float smem[];
-    // two A buffers: the next tile is written to LDS BEFORE this tile's stores are issued, so the
-    // wait for the prefetched loads never has to wait for store acknowledgements as well
+    // two A buffers: the next tile is written to LDS before this tile's stores are issued
     typedef float (*ATile)[KP + 4];
     auto a_buf = [&](int b) { return reinterpret_cast<ATile>(smem + b * kFwdRows * (KP + 4)); };
     float (*Bs)[NP + 4] = reinterpret_cast<float (*)[NP + 4]>(smem + 2 * kFwdRows * (KP + 4));
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l32 = lane & 31, lh = lane >> 5;
+    const int l16 = lane & 15, lq = lane >> 4, l32 = lane & 31, lh = lane >> 5;
+    const int k_end = (K + 3) & ~3;
 
     for (int f = tid; f < KP * NP; f += 256) {
         const int kk = f / NP, n = f % NP;
@@ -144,16 +152,18 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
             const int64_t gr = m0 + r;
             const int gk = 4 * q;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (gr < M && gk < K) {
-                const float* p = A + gr * lda + gk;
-                if (vec_a && gk + 3 < K) {
-                    v = *reinterpret_cast<const float4*>(p);
-                } else {
-                    v.x = p[0];
-                    if (gk + 1 < K) v.y = p[1];
-                    if (gk + 2 < K) v.z = p[2];
-                    if (gk + 3 < K) v.w = p[3];
+            if constexpr (VEC) {           // rows past the end are read from the last row and zeroed by a select
+                if (KP == K || gk < K) {
+                    const int64_t rr = gr < M ? gr : M - 1;
+                    v = *reinterpret_cast<const float4*>(A + rr * lda + gk);
+                    if (gr >= M) v = make_float4(0.f, 0.f, 0.f, 0.f);
                 }
+            } else if (gr < M && gk < K) {
+                const float* p = A + gr * lda + gk;
+                v.x = p[0];
+                if (gk + 1 < K) v.y = p[1];
+                if (gk + 2 < K) v.z = p[2];
+                if (gk + 3 < K) v.w = p[3];
             }
             reg[i] = v;
         }
@@ -175,36 +185,66 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
         if (more) fetch(tile + gridDim.x);
         ATile As = a_buf(cur);
 
-        floatx16 acc[NBLK];
+        const bool full = (tile + 1) * kFwdRows <= M;                   // uniform: only the last tile is partial
+        if constexpr (!WIDE) {
+            floatx4 acc[CB];
 #pragma unroll
-        for (int t = 0; t < NBLK; ++t)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+            for (int c = 0; c < CB; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
-        for (int kk = 0; kk < KP; kk += 2) {
+            for (int kk = 0; kk < k_end; kk += 4) {
+                const float a = As[16 * w + l16][kk + lq];
+#pragma unroll
+                for (int c = 0; c < CB; ++c)
+                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Bs[kk + lq][16 * c + l16], acc[c], 0, 0, 0);
+            }
+            if (more) commit(a_buf(cur ^ 1));
+            const int64_t row0 = tile * kFwdRows + 16 * w + 4 * lq;
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+                const int gn = 16 * c + l16;
+                if (gn >= N) continue;
+                float* cp = C ? C + row0 * ldc + gn : nullptr;
+                float* fp = F ? F + row0 * ldf + gn : nullptr;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if (full || row0 + r < M) {
+                        const float v = acc[c][r];
+                        if (cp) cp[r * ldc] = v;
+                        if (fp) fp[r * ldf] = v > 0.f ? v : 0.f;        // Eq. 2.3 fused into the store
+                    }
+                }
+            }
+        } else {
+            floatx16 acc[NBLK];
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+#pragma unroll 4
+            for (int kk = 0; kk < k_end; kk += 2) {
+#pragma unroll
+                for (int t = 0; t < NBLK; ++t) {
+                    const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
+                    acc[t] = mfma32(As[32 * bi + l32][kk + lh], Bs[kk + lh][32 * bj + l32], acc[t]);
+                }
+            }
+            if (more) commit(a_buf(cur ^ 1));
 #pragma unroll
             for (int t = 0; t < NBLK; ++t) {
                 const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-                acc[t] = mfma32(As[32 * bi + l32][kk + lh], Bs[kk + lh][32 * bj + l32], acc[t]);
-            }
-        }
-        if (more) commit(a_buf(cur ^ 1));
-        const int64_t m0 = tile * kFwdRows;
+                const int gn = 32 * bj + l32;
+                if (gn >= N) continue;
+                const int64_t row0 = tile * kFwdRows + 32 * bi + 4 * lh;
+                float* cp = C ? C + row0 * ldc + gn : nullptr;
+                float* fp = F ? F + row0 * ldf + gn : nullptr;
 #pragma unroll
-        for (int t = 0; t < NBLK; ++t) {
-            const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-            const int gn = 32 * bj + l32;
-            if (gn >= N) continue;
-            const int64_t row0 = m0 + 32 * bi + 4 * lh;
-            float* cp = C ? C + row0 * ldc + gn : nullptr;
-            float* fp = F ? F + row0 * ldf + gn : nullptr;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int dr = 8 * (r / 4) + (r % 4);
-                if (row0 + dr < M) {
-                    const float v = acc[t][r];
-                    if (cp) cp[dr * ldc] = v;
-                    if (fp) fp[dr * ldf] = v > 0.f ? v : 0.f;          // Eq. 2.3 fused into the store
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 8 * (r / 4) + (r % 4);
+                    if (full || row0 + dr < M) {
+                        const float v = acc[t][r];
+                        if (cp) cp[dr * ldc] = v;
+                        if (fp) fp[dr * ldf] = v > 0.f ? v : 0.f;      // Eq. 2.3 fused into the store
+                    }
                 }
             }
         }
@@ -374,34 +414,39 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
     dim3 grid((unsigned)ceil_div(M, 128), (unsigned)ceil_div(N, 32 * tnb));
     hipStream_t s = ctx->stream;
     char label[64];
-    snprintf(label, sizeof label, "gemm_%s<f32>[N%lld,K%lld]", bt ? "nt" : "nn", (long long)N, (long long)K);
+    snprintf(label, sizeof label, "gemm_%s<f32>[M%lld,N%lld,K%lld]", bt ? "nt" : "nn", (long long)M, (long long)N, (long long)K);
     KernelTimer kt(ctx, label);
     if (!bt && K <= 128 && N <= 128 && K > 0) {
         const int tkb = K <= 32 ? 1 : (K <= 64 ? 2 : 4);
-        const int rb = tnb == 1 ? 4 : 2;
-        const int rows = 32 * rb;
-        const size_t lds = sizeof(float) * (2 * rows * (32 * tkb + 4) + 32 * tkb * (32 * tnb + 4));
+        int cb = (int)ceil_div(N, 16);
+        if (cb > 4) cb = 8;                    // wide tiles are 128 columns (four 32x32 column blocks)
+        const size_t lds = sizeof(float) * (2 * kFwdRows * (32 * tkb + 4) + 32 * tkb * (16 * cb + 4));
         const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(8, (150 * 1024) / lds));
-        const int64_t blocks = std::min<int64_t>(ceil_div(M, rows), (int64_t)ctx->n_cu * per_cu);
-#define PLX_SMALL(TK, TN, RBV)                                                                                 \
-    do {                                                                                                       \
-        auto kern = k_gemm_small_f32<TK, TN, RBV>;                                                             \
-        if (lds > 48 * 1024)                                                                                   \
-            PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                              \
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));           \
-        kern<<<dim3((unsigned)blocks), 256, lds, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf, vec_a); \
+        const int64_t blocks = std::min<int64_t>(ceil_div(M, kFwdRows), (int64_t)ctx->n_cu * per_cu);
+        const bool vec = vec_a && K % 4 == 0 && M > 0;
+        auto launch_small = [&](auto kern) -> plx_status {
+            if (lds > 48 * 1024)
+                PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            kern<<<dim3((unsigned)blocks), 256, lds, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf);
+            return PLX_OK;
+        };
+#define PLX_SMALL(TK, CBV) \
+    PLX_TRY(vec ? launch_small(k_gemm_small_f32<TK, CBV, true>) : launch_small(k_gemm_small_f32<TK, CBV, false>))
+#define PLX_SMALL_K(CBV)                                         \
+    do {                                                         \
+        if (tkb == 1) PLX_SMALL(1, CBV);                         \
+        else if (tkb == 2) PLX_SMALL(2, CBV);                    \
+        else PLX_SMALL(4, CBV);                                  \
     } while (0)
-        switch (tkb * 10 + tnb) {
-            case 11: PLX_SMALL(1, 1, 4); break;
-            case 12: PLX_SMALL(1, 2, 2); break;
-            case 14: PLX_SMALL(1, 4, 2); break;
-            case 21: PLX_SMALL(2, 1, 4); break;
-            case 22: PLX_SMALL(2, 2, 2); break;
-            case 24: PLX_SMALL(2, 4, 2); break;
-            case 41: PLX_SMALL(4, 1, 4); break;
-            case 42: PLX_SMALL(4, 2, 2); break;
-            default: PLX_SMALL(4, 4, 2); break;
+        switch (cb) {
+            case 1: PLX_SMALL_K(1); break;
+            case 2: PLX_SMALL_K(2); break;
+            case 3: PLX_SMALL_K(3); break;
+            case 4: PLX_SMALL_K(4); break;
+            default: PLX_SMALL_K(8); break;
         }
+#undef PLX_SMALL_K
 #undef PLX_SMALL
         PLX_HIP(ctx, hipGetLastError());
         return PLX_OK;
@@ -435,7 +480,7 @@ plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const v
     dim3 grid((unsigned)chunks, (unsigned)ceil_div(M, 32 * tmb), (unsigned)ceil_div(N, 32 * tnb));
     hipStream_t s = ctx->stream;
     char label[64];
-    snprintf(label, sizeof label, "gemm_tn<f32>[M%lld,N%lld]", (long long)M, (long long)N);
+    snprintf(label, sizeof label, "gemm_tn<f32>[R%lld,M%lld,N%lld]", (long long)R, (long long)M, (long long)N);
     KernelTimer* kt = new KernelTimer(ctx, label);
 #define PLX_TN_CASE(TM, TN) \
     k_gemm_tn_f32<TM, TN><<<grid, 256, 0, s>>>(R, (int)M, (int)N, a, lda, b, ldb, part, rpc, vec_a, vec_b)

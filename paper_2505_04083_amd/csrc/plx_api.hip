@@ -331,17 +331,25 @@ static plx_order resolve_order(plx_order order, int64_t din, int64_t dout) {
 // Workspace layout (each region 256-byte aligned):
 //   COMBINE_FIRST: T / G  [ka x dout]   | dZ [ma x dout] (if act)  | dW partial sums
 //   AGG_FIRST    : dS     [ma x din]    | dZ [ma x dout] (if act)  | dW partial sums
+// Internal matrices get a leading dimension padded to 16 bytes so every row allows 128-bit accesses.
 struct LayerWs {
     size_t off_a = 0, off_dz = 0, off_tn = 0, total = 0;
+    int64_t ld_in = 0, ld_out = 0;   // padded din / dout in elements
 };
+
+static int64_t pad16(int64_t cols, plx_dtype dtype) {
+    const int64_t q = 16 / (int64_t)elt_size(dtype);
+    return (cols + q - 1) / q * q;
+}
 
 static LayerWs layer_ws(const Orient& a, int64_t din, int64_t dout, plx_dtype dtype, plx_act act, plx_order order) {
     LayerWs w;
     size_t es = elt_size(dtype);
-    size_t first = order == PLX_ORDER_AGG_FIRST ? (size_t)a.rows * din * es : (size_t)a.cols * dout * es;
+    w.ld_in = pad16(din, dtype); w.ld_out = pad16(dout, dtype);
+    size_t first = order == PLX_ORDER_AGG_FIRST ? (size_t)a.rows * w.ld_in * es : (size_t)a.cols * w.ld_out * es;
     w.off_a = 0;
     w.off_dz = align256(first);
-    size_t dz = act == PLX_ACT_RELU ? (size_t)a.rows * dout * es : 0;
+    size_t dz = act == PLX_ACT_RELU ? (size_t)a.rows * w.ld_out * es : 0;
     w.off_tn = w.off_dz + align256(dz);
     int64_t R = order == PLX_ORDER_AGG_FIRST ? a.rows : a.cols;
     w.total = w.off_tn + align256(gemm_tn_workspace(R, din, dout));
@@ -400,8 +408,8 @@ plx_status plx_gcn_layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
         PLX_TRY(launch_gemm(ctx, false, a.rows, dout, din, saved, ldsaved, W, ldw, plain, ld_plain, dtype, activated, ldf));  // Eq. 2.2 (+2.3)
     } else {
         void* T = static_cast<char*>(ws) + w.off_a;
-        PLX_TRY(launch_gemm(ctx, false, a.cols, dout, din, H, ldh, W, ldw, T, dout, dtype));
-        PLX_TRY(launch_spmm(ctx, a, T, dout, plain, ld_plain, dout, dtype, activated, ldf));
+        PLX_TRY(launch_gemm(ctx, false, a.cols, dout, din, H, ldh, W, ldw, T, w.ld_out, dtype));
+        PLX_TRY(launch_spmm(ctx, a, T, w.ld_out, plain, ld_plain, dout, dtype, activated, ldf));
     }
     if (F && act == PLX_ACT_NONE && Z && F != Z)
         PLX_HIP(ctx, hipMemcpy2DAsync(F, ldf * elt_size(dtype), Z, ldz * elt_size(dtype), dout * elt_size(dtype), a.rows,
@@ -444,20 +452,20 @@ plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
         // Eq. 2.4 is applied while the gradient tile is loaded; it is never written back
         if (order == PLX_ORDER_AGG_FIRST) {
             void* dS = dH ? base + w.off_a : nullptr;
-            PLX_TRY(launch_bwd_dense(ctx, a.rows, din, dout, saved, ldsaved, dF, lddf, mask, ldz, W, ldw, dS, din, dW, lddw,
+            PLX_TRY(launch_bwd_dense(ctx, a.rows, din, dout, saved, ldsaved, dF, lddf, mask, ldz, W, ldw, dS, w.ld_in, dW, lddw,
                                      dtype, tn_ws, tn_bytes));                               // Eq. 2.4 + 2.5 + 2.6
-            if (dH) PLX_TRY(launch_spmm(ctx, at, dS, din, dH, lddh, din, dtype));            // Eq. 2.7
+            if (dH) PLX_TRY(launch_spmm(ctx, at, dS, w.ld_in, dH, lddh, din, dtype));        // Eq. 2.7
         } else {
             const void* dZ = dF;
             int64_t lddz = lddf;
             if (mask) {
                 void* buf = base + w.off_dz;
-                PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, dout, dtype));
-                dZ = buf; lddz = dout;
+                PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, w.ld_out, dtype));
+                dZ = buf; lddz = w.ld_out;
             }
             void* G = base + w.off_a;
-            PLX_TRY(launch_spmm(ctx, at, dZ, lddz, G, dout, dout, dtype));                   // A^T dZ
-            PLX_TRY(launch_bwd_dense(ctx, a.cols, din, dout, H, ldh, G, dout, nullptr, 0, W, ldw, dH, lddh, dW, lddw, dtype,
+            PLX_TRY(launch_spmm(ctx, at, dZ, lddz, G, w.ld_out, dout, dtype));               // A^T dZ
+            PLX_TRY(launch_bwd_dense(ctx, a.cols, din, dout, H, ldh, G, w.ld_out, nullptr, 0, W, ldw, dH, lddh, dW, lddw, dtype,
                                      tn_ws, tn_bytes));
         }
         return PLX_OK;
@@ -466,21 +474,21 @@ plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
     int64_t lddz = lddf;
     if (mask) {                                                                              // Eq. 2.4
         void* buf = base + w.off_dz;
-        PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, dout, dtype));
-        dZ = buf; lddz = dout;
+        PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, w.ld_out, dtype));
+        dZ = buf; lddz = w.ld_out;
     }
     if (order == PLX_ORDER_AGG_FIRST) {
         PLX_TRY(launch_gemm_tn(ctx, a.rows, din, dout, saved, ldsaved, dZ, lddz, dW, lddw, dtype, tn_ws, tn_bytes));  // Eq. 2.5
         if (dH) {
             void* dS = base + w.off_a;
-            PLX_TRY(launch_gemm(ctx, true, a.rows, din, dout, dZ, lddz, W, ldw, dS, din, dtype));  // Eq. 2.6
-            PLX_TRY(launch_spmm(ctx, at, dS, din, dH, lddh, din, dtype));                    // Eq. 2.7
+            PLX_TRY(launch_gemm(ctx, true, a.rows, din, dout, dZ, lddz, W, ldw, dS, w.ld_in, dtype));  // Eq. 2.6
+            PLX_TRY(launch_spmm(ctx, at, dS, w.ld_in, dH, lddh, din, dtype));                // Eq. 2.7
         }
     } else {
         void* G = base + w.off_a;
-        PLX_TRY(launch_spmm(ctx, at, dZ, lddz, G, dout, dout, dtype));                       // A^T dZ
-        PLX_TRY(launch_gemm_tn(ctx, a.cols, din, dout, H, ldh, G, dout, dW, lddw, dtype, tn_ws, tn_bytes));
-        if (dH) PLX_TRY(launch_gemm(ctx, true, a.cols, din, dout, G, dout, W, ldw, dH, lddh, dtype));
+        PLX_TRY(launch_spmm(ctx, at, dZ, lddz, G, w.ld_out, dout, dtype));                   // A^T dZ
+        PLX_TRY(launch_gemm_tn(ctx, a.cols, din, dout, H, ldh, G, w.ld_out, dW, lddw, dtype, tn_ws, tn_bytes));
+        if (dH) PLX_TRY(launch_gemm(ctx, true, a.cols, din, dout, G, w.ld_out, W, ldw, dH, lddh, dtype));
     }
     return PLX_OK;
 }

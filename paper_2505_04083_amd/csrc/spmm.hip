@@ -275,7 +275,7 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, Out<
     const int64_t n_wave = o.class_off[kLongClass] - n_sub;
     constexpr int WPB = 256 / kWave;   // wavefronts per block
     char label[64];
-    snprintf(label, sizeof label, "<%s,G%d,VW%d>[%s]", sizeof(T) == 4 ? "f32" : "bf16", G, VW, o.tag ? "At" : "A");
+    snprintf(label, sizeof label, "<%s,G%d,VW%d,d%d>[%s]", sizeof(T) == 4 ? "f32" : "bf16", G, VW, d, o.tag ? "At" : "A");
     const int64_t sub_count = n_sub;
     if (sub_count > 0) {
         KernelTimer kt(ctx, std::string("spmm_subwave") + label);

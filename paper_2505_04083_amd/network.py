@@ -1,0 +1,80 @@
+"""L-layer GCN forward + backward as a fixed sequence of C-ABI calls (no arithmetic here).
+
+Layer l uses the stored orientation l % 2 (Eq. 5.3-5.4 of the paper: P_r A P_c^T for even layers,
+P_c A P_r^T for odd ones).  All buffers are allocated once, so a training step allocates nothing.
+Hidden layers store only the activated output (its sign serves Eq. 2.4); the last layer stores
+the logits.  The input must be in P_c order and the labels in the order of the last layer's output."""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import torch
+
+from . import (PLX_ACT_NONE, PLX_ACT_RELU, PLX_BF16, PLX_F32, PLX_ORDER_AUTO, plx_gcn_layer_bwd,
+               plx_gcn_layer_fwd, plx_gcn_layer_workspace, plx_softmax_ce, plx_sync)
+
+
+def _matrix(rows: int, cols: int, dtype, dev) -> torch.Tensor:
+    """rows x cols view whose leading dimension is padded to 16 bytes (128-bit row accesses)."""
+    q = 4 if dtype == torch.float32 else 8
+    ld = (cols + q - 1) // q * q
+    return torch.empty(rows, ld, dtype=dtype, device=dev)[:, :cols]
+
+
+class GcnNetwork:
+    def __init__(self, ctx, csr, Ws: List[torch.Tensor], dtype=torch.float32, order: int = PLX_ORDER_AUTO,
+                 keep_preactivation: bool = False):
+        self.ctx, self.csr, self.Ws, self.order = ctx, csr, Ws, order
+        self.L = len(Ws)
+        dev = Ws[0].device
+        code = PLX_F32 if dtype == torch.float32 else PLX_BF16
+        self.act = [PLX_ACT_RELU if l + 1 < self.L else PLX_ACT_NONE for l in range(self.L)]
+        nbytes = 1
+        for l, W in enumerate(Ws):
+            nbytes = max(nbytes, plx_gcn_layer_workspace(csr, bool(l % 2), W.shape[0], W.shape[1], code, self.act[l], order))
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        self.Z: List[Optional[torch.Tensor]] = []
+        self.F: List[Optional[torch.Tensor]] = []
+        self.saved: List[torch.Tensor] = []
+        self.dH: List[torch.Tensor] = []
+        self.dW: List[torch.Tensor] = []
+        for l, W in enumerate(Ws):
+            rows, cols = csr.shape(bool(l % 2))
+            din, dout = W.shape
+            last = l + 1 == self.L
+            self.Z.append(_matrix(rows, dout, dtype, dev) if (last or keep_preactivation) else None)
+            self.F.append(None if last else _matrix(rows, dout, dtype, dev))
+            agg_first = order == 1 or (order == PLX_ORDER_AUTO and din < dout)
+            self.saved.append(_matrix(rows if agg_first else 1, din, dtype, dev))
+            self.dH.append(_matrix(cols, din, dtype, dev))
+            self.dW.append(torch.empty(din, dout, dtype=torch.float32, device=dev))
+        rows_last = csr.shape(bool((self.L - 1) % 2))[0]
+        self.dZ_last = _matrix(rows_last, Ws[-1].shape[1], dtype, dev)
+        self.row_loss = torch.empty(max(1, rows_last), dtype=torch.float32, device=dev)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+
+    def forward(self, H0: torch.Tensor) -> torch.Tensor:
+        h = H0
+        for l, W in enumerate(self.Ws):
+            plx_gcn_layer_fwd(self.ctx, self.csr, bool(l % 2), h, W, self.Z[l], self.F[l], self.saved[l], self.ws,
+                              act=self.act[l], order=self.order)
+            if l + 1 < self.L:
+                h = self.F[l]
+        return self.Z[-1]
+
+    def backward(self, H0: torch.Tensor, y: torch.Tensor) -> None:
+        plx_softmax_ce(self.ctx, self.Z[-1], y, self.dZ_last, row_loss=self.row_loss, loss=self.loss)
+        grad = self.dZ_last
+        for l in range(self.L - 1, -1, -1):
+            h = H0 if l == 0 else self.F[l - 1]
+            mask_src = None if self.act[l] == PLX_ACT_NONE else (self.Z[l] if self.Z[l] is not None else self.F[l])
+            plx_gcn_layer_bwd(self.ctx, self.csr, bool(l % 2), h, self.Ws[l], mask_src, grad, self.saved[l],
+                              self.dH[l], self.dW[l], self.ws, act=self.act[l], order=self.order)
+            grad = self.dH[l]
+
+    def step(self, H0: torch.Tensor, y: torch.Tensor) -> None:
+        self.forward(H0)
+        self.backward(H0, y)
+
+    def sync(self) -> None:
+        plx_sync(self.ctx)

@@ -1,75 +1,30 @@
-"""Multi-layer GCN forward + backward through the C ABI (test helper; calls only the
-library's entry points, no torch arithmetic on the path)."""
+"""Test helpers around the library's multi-layer sequencer."""
 from __future__ import annotations
 
-from typing import List, Optional
+from typing import List
 
 import numpy as np
 import torch
 
 import paper_2505_04083_amd as plx
+from paper_2505_04083_amd.network import GcnNetwork
 
 
 class GpuRun:
-    def __init__(self):
-        self.Z: List[torch.Tensor] = []
-        self.F: List[torch.Tensor] = []
-        self.saved: List[Optional[torch.Tensor]] = []
-        self.dW: List[torch.Tensor] = []
-        self.dF0: Optional[torch.Tensor] = None
-        self.loss: Optional[torch.Tensor] = None
+    pass
 
 
 def run_network(ctx, csr, H0: torch.Tensor, Ws: List[torch.Tensor], y: torch.Tensor, order=plx.PLX_ORDER_AUTO,
                 backward: bool = True) -> GpuRun:
     """Layer l uses orientation l % 2 (Eq. 5.3-5.4).  H0 is in P_c order; y in the order of the
-    last layer's output."""
-    dev = H0.device
-    dt = H0.dtype
-    code = plx.PLX_F32 if dt == torch.float32 else plx.PLX_BF16
-    L = len(Ws)
+    last layer's output.  Pre-activations are kept so that tests can compare every layer."""
+    net = GcnNetwork(ctx, csr, Ws, dtype=H0.dtype, order=order, keep_preactivation=True)
+    net.forward(H0)
+    if backward:
+        net.backward(H0, y)
+    net.sync()
     run = GpuRun()
-    run.F.append(H0)
-    ws_bytes = 1
-    for l, W in enumerate(Ws):
-        act = plx.PLX_ACT_RELU if l + 1 < L else plx.PLX_ACT_NONE
-        ws_bytes = max(ws_bytes, plx.plx_gcn_layer_workspace(csr, bool(l % 2), W.shape[0], W.shape[1], code, act, order))
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    for l, W in enumerate(Ws):
-        t = bool(l % 2)
-        rows, cols = csr.shape(t)
-        din, dout = W.shape
-        last = l + 1 == L
-        Z = torch.empty(rows, dout, dtype=dt, device=dev)
-        F = None if last else torch.empty(rows, dout, dtype=dt, device=dev)
-        saved = torch.empty(rows, din, dtype=dt, device=dev)
-        plx.plx_gcn_layer_fwd(ctx, csr, t, run.F[l], W, Z, F, saved, ws,
-                              act=plx.PLX_ACT_NONE if last else plx.PLX_ACT_RELU, order=order)
-        run.Z.append(Z); run.saved.append(saved)
-        if not last:
-            run.F.append(F)
-    if not backward:
-        plx.plx_sync(ctx)
-        return run
-    n, c = run.Z[-1].shape
-    dZ = torch.empty_like(run.Z[-1])
-    run.loss = torch.zeros(1, dtype=torch.float32, device=dev)
-    plx.plx_softmax_ce(ctx, run.Z[-1], y, dZ, loss=run.loss)
-    grad = dZ
-    run.dW = [None] * L
-    for l in range(L - 1, -1, -1):
-        t = bool(l % 2)
-        rows, cols = csr.shape(t)
-        din, dout = Ws[l].shape
-        last = l + 1 == L
-        dH = torch.empty(cols, din, dtype=dt, device=dev)
-        dW = torch.empty(din, dout, dtype=torch.float32, device=dev)
-        plx.plx_gcn_layer_bwd(ctx, csr, t, run.F[l], Ws[l], run.Z[l], grad, run.saved[l], dH, dW, ws,
-                              act=plx.PLX_ACT_NONE if last else plx.PLX_ACT_RELU, order=order)
-        run.dW[l] = dW
-        grad = dH
-    run.dF0 = grad
-    plx.plx_sync(ctx)
+    run.Z, run.F, run.dW, run.dF0, run.loss = net.Z, net.F, net.dW, net.dH[0], net.loss
     return run
 
 
