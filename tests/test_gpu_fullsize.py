@@ -117,3 +117,85 @@ def test_shard_backward_dense_gradient_samples(shard):
         J, ref = J[keep], ref[keep]
     assert len(J) > 100
     assert rel_err(dX[torch.as_tensor(J, device=DEV)], ref) <= TOL32
+
+
+# ---------------------------------------------------------------- the other workloads at full size
+from oracle import sampled as osampled
+
+
+@pytest.mark.parametrize("name,layer", [("social", 1), ("copurchase", 0), ("road", 0)])
+def test_graph_workloads_full_size(name, layer):
+    """configs[1], [2], [4] at full size: the double-permuted CSR is built on the GPU and checked
+    bit-exactly on sampled rows the oracle derives one by one from the edge list; then one layer
+    (the given layer's widths, AUTO order as the benchmark runs it) forward and backward with a
+    gradient supported on the sampled rows, against the oracle's Eq. 2.1-2.7 on those rows."""
+    cfg = synth.CONFIGS[name]
+    din, dout = cfg.dims[layer], cfg.dims[layer + 1]
+    src, dst = cfg.edges(DEV)
+    pr, pc = cfg.perms(DEV)
+    # the generator's contract the sampled oracle relies on: distinct undirected edges, no loops
+    lo, hi = torch.minimum(src, dst), torch.maximum(src, dst)
+    assert bool((lo != hi).all())
+    ctx = plx.plx_ctx(0)
+    csr = plx.plx_build_csr(ctx, cfg.n, src, dst, pr, pc)
+    n_unique = int(torch.unique(lo * cfg.n + hi).numel())
+    s_h, d_h, pr_h, pc_h = (t.cpu().numpy() for t in (src, dst, pr, pc))
+    if n_unique != src.numel():            # the road recipe may repeat a pair: dedupe the host copy
+        key = np.unique(np.minimum(s_h, d_h) * cfg.n + np.maximum(s_h, d_h))
+        s_h, d_h = key // cfg.n, key % cfg.n
+    del lo, hi
+    assert csr.nnz == 2 * len(s_h) + cfg.n
+    deg = osampled.degrees(cfg.n, s_h, d_h)
+    r = np.random.default_rng(cfg.cid)
+    nodes = np.unique(np.concatenate([r.integers(0, cfg.n, 600), np.argsort(deg)[-40:], np.argsort(deg)[:40]]))
+    rows = osampled.permuted_rows(cfg.n, s_h, d_h, deg, pr_h, pc_h, nodes)
+
+    rowptr, col, val, gdeg = plx.plx_csr_export(ctx, csr, False, with_deg=True)
+    assert np.array_equal(gdeg[torch.as_tensor(nodes, device=DEV)].cpu().numpy(), deg[nodes])
+    S = np.array(sorted(rows), np.int64)
+    rp = rowptr[torch.as_tensor(np.stack([S, S + 1]), device=DEV)].cpu().numpy()
+    for k_, i in enumerate(S):
+        a, b = int(rp[0, k_]), int(rp[1, k_])
+        c_ref, v_ref = rows[int(i)]
+        assert b - a == len(c_ref)
+        assert np.array_equal(col[a:b].cpu().numpy(), c_ref)
+        assert np.array_equal(val[a:b].cpu().numpy().view(np.uint32), v_ref.view(np.uint32))
+    del rowptr, col, val
+
+    # one layer on the full graph
+    H = synth.normal(cfg.seed, synth.S_FEAT, cfg.n, din, DEV)
+    W = synth.glorot(cfg.seed, layer, din, dout, DEV)
+    ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout), dtype=torch.uint8, device=DEV)
+    F = torch.empty(cfg.n, dout, device=DEV)
+    saved = torch.empty(cfg.n if din < dout else 1, din, device=DEV)
+    plx.plx_gcn_layer_fwd(ctx, csr, False, H, W, None, F, saved, ws)
+    plx.plx_sync(ctx)
+    need = np.unique(np.concatenate([rows[int(i)][0] for i in S])).astype(np.int64)      # operand rows the samples touch
+    Hn = H[torch.as_tensor(need, device=DEV)].cpu().numpy().astype(np.float64)
+    pos = {int(c): k_ for k_, c in enumerate(need)}
+    Wd = W.cpu().numpy().astype(np.float64)
+    Hagg = np.stack([sum(float(v) * Hn[pos[int(c)]] for c, v in zip(*rows[int(i)])) for i in S])    # Eq. 2.1
+    Q = oracle.gemm(Hagg, Wd)                                                                       # Eq. 2.2
+    Sd = torch.as_tensor(S, device=DEV)
+    assert rel_err(F[Sd], oracle.relu(Q)) <= TOL32
+    if din < dout:
+        assert rel_err(saved[Sd], Hagg) <= TOL32
+
+    dFs = r.standard_normal((len(S), dout)).astype(np.float32)
+    dFs[np.abs(Q).min(axis=1) < 1e-5] = 0.0
+    dF = torch.zeros(cfg.n, dout, device=DEV)
+    dF[Sd] = torch.as_tensor(dFs, device=DEV)
+    dH = torch.empty(cfg.n, din, device=DEV); dW = torch.empty(din, dout, device=DEV)
+    plx.plx_gcn_layer_bwd(ctx, csr, False, H, W, F, dF, saved, dH, dW, ws)
+    plx.plx_sync(ctx)
+    dQ = oracle.relu_bwd(Q, dFs)                                      # Eq. 2.4
+    assert rel_err(dW, oracle.gemm(Hagg, dQ, ta=True)) <= TOL32       # Eq. 2.5
+    dS = oracle.gemm(dQ, Wd, tb=True)                                 # Eq. 2.6
+    ref = np.zeros((len(need), din))                                  # Eq. 2.7 on the touched columns
+    for k_, i in enumerate(S):
+        for c, v in zip(*rows[int(i)]):
+            ref[pos[int(c)]] += float(v) * dS[k_]
+    assert rel_err(dH[torch.as_tensor(need, device=DEV)], ref) <= TOL32
+    others = torch.ones(cfg.n, dtype=torch.bool, device=DEV); others[torch.as_tensor(need, device=DEV)] = False
+    assert float(dH[others].abs().max()) == 0.0                       # untouched rows get exactly zero
+    csr.close(); ctx.close()

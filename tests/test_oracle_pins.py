@@ -315,3 +315,24 @@ def test_block_balance_table3():
     assert abs(single - expect_single) / expect_single < 0.02
     assert double < 1.03
     assert abs(t3["double_permutation"] - 1.0) < 0.01
+
+
+def test_sampled_rows_against_dense_brute_force():
+    """oracle.sampled (single rows from the definition, used at full size) against the dense
+    P_r A^ P_c^T built from permutation matrices."""
+    from oracle import sampled as osampled
+    n = 37
+    r = np.random.default_rng(4)
+    pairs = {(min(u, v), max(u, v)) for u, v in zip(r.integers(0, n, 120).tolist(), r.integers(0, n, 120).tolist()) if u != v}
+    src = np.array([p[0] for p in pairs]); dst = np.array([p[1] for p in pairs])      # distinct, loop-free
+    A, d = odense.dense_adjacency(n, src, dst)
+    pr, pc = r.permutation(n), r.permutation(n)
+    B = (odense.permutation_matrix(pr) @ A @ odense.permutation_matrix(pc).T).astype(np.float32)
+    deg = osampled.degrees(n, src, dst)
+    assert np.array_equal(deg, d)
+    rows = osampled.permuted_rows(n, src, dst, deg, pr, pc, np.arange(n))
+    assert sorted(rows) == list(range(n))
+    for i, (cols, vals) in rows.items():
+        assert np.all(np.diff(cols) > 0)
+        dense_row = np.zeros(n, np.float32); dense_row[cols] = vals
+        assert np.array_equal(dense_row, B[i])
