@@ -1,0 +1,120 @@
+#!/usr/bin/env python3
+"""Two measurement studies on one MI355X, analogues of the paper's Table 3 and Table 2 on the
+synthetic workloads (the paper's datasets are not available).  Each prints one JSON object.
+
+  python studies.py balance [--workload road] [--scale 1.0]
+      Block balance under no / single / double permutation (Table 3: max / mean of the stored
+      entries over an 8 x 8 tiling), plus the sparse product's time on each of the three stored
+      matrices at width 64 -- what the double permutation costs in locality on ONE GPU.
+
+  python studies.py skinny
+      Tall-skinny sensitivity (Sec. 4.1, Table 2): at equal flops, configuration U_g (the
+      adjacency block has K/g columns, the dense operand keeps width 128) against V_g (full K,
+      dense operand 128/g wide), g = 1, 4, 16, 64.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import torch
+
+import paper_2505_04083_amd as plx
+import synth
+
+DEV = torch.device("cuda", 0)
+
+
+def time_spmm(ctx, csr, X, Y, reps=5):
+    plx.plx_spmm(ctx, csr, X, Y)
+    plx.plx_sync(ctx)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        plx.plx_spmm(ctx, csr, X, Y)
+    plx.plx_sync(ctx)
+    return (time.perf_counter() - t0) * 1e3 / reps
+
+
+def spmm_bytes(csr, d, transposed=False):
+    rows, ent = plx.plx_csr_bins(csr, transposed)
+    return sum(ent) * (8 + 4 * d) + sum(rows) * (4 + 4 * d)
+
+
+def block_ratio(ctx, csr, n, blocks=8):
+    """max / mean of the entry counts over a blocks x blocks tiling of the stored matrix."""
+    rowptr, col, _ = plx.plx_csr_export(ctx, csr)
+    edges = (torch.arange(blocks + 1, device=DEV, dtype=torch.int64) * n) // blocks
+    row_block = torch.bucketize(torch.arange(n, device=DEV), edges[1:], right=True)
+    rb = torch.repeat_interleave(row_block, rowptr[1:] - rowptr[:-1])
+    cb = torch.bucketize(col.to(torch.int64), edges[1:], right=True)
+    cnt = torch.bincount(rb * blocks + cb, minlength=blocks * blocks).double()
+    return float(cnt.max() / cnt.mean())
+
+
+def balance(args):
+    cfg = synth.CONFIGS[args.workload]
+    if args.scale != 1.0:
+        cfg = cfg.scaled(args.scale)
+    ctx = plx.plx_ctx(0)
+    src, dst = cfg.edges(DEV)
+    pr, pc = cfg.perms(DEV)
+    d = 64
+    X = synth.normal(cfg.seed, synth.S_FEAT, cfg.n, d, DEV)
+    Y = torch.empty(cfg.n, d, device=DEV)
+    out = {"study": "block balance and locality under permutation (Table 3 analogue)", "workload": cfg.name,
+           "n": cfg.n, "blocks": "8x8", "width": d, "cases": {}}
+    for name, (a, b) in {"original": (None, None), "single_permutation": (pr, pr), "double_permutation": (pr, pc)}.items():
+        csr = plx.plx_build_csr(ctx, cfg.n, src, dst, a, b)
+        ms = time_spmm(ctx, csr, X, Y)
+        by = spmm_bytes(csr, d)
+        out["cases"][name] = {"max_over_mean": round(block_ratio(ctx, csr, cfg.n), 4), "spmm_ms": round(ms, 3),
+                              "algorithmic_GBps": round(by / ms / 1e6, 1)}
+        out["nnz"] = csr.nnz
+        csr.close()
+    nnz, n, B = out["nnz"], cfg.n, 8
+    out["single_permutation_closed_form"] = round(((nnz - n) / B**2 + n / B) / (nnz / B**2), 4)
+    print(json.dumps(out))
+
+
+def skinny(args):
+    ctx = plx.plx_ctx(0)
+    m, k, samples, width = 2_000_000, 8_000_000, 64_000_000, 128
+    out = {"study": "tall-skinny sensitivity at equal flops (Table 2 analogue)", "m": m, "k": k, "cases": []}
+    for g in (1, 4, 16, 64):
+        for label, kk, ss, d in (("U", k // g, samples // g, width), ("V", k, samples, width // g)):
+            if g == 1 and label == "V":
+                continue
+            rowptr, col, val = synth.shard_block(synth.BASE_SEED + 40 + g, m, kk, ss, DEV)
+            csr = plx.plx_csr_import(ctx, m, kk, rowptr, col, val)
+            X = synth.normal(7, synth.S_FEAT, kk, d, DEV)
+            Y = torch.empty(m, d, device=DEV)
+            ms = time_spmm(ctx, csr, X, Y)
+            out["cases"].append({"config": f"{label}_{g}", "cols": kk, "nnz": csr.nnz, "width": d,
+                                 "GFLOP": round(2 * csr.nnz * d / 1e9, 2), "spmm_ms": round(ms, 3),
+                                 "GFLOPs": round(2 * csr.nnz * d / ms / 1e6, 1),
+                                 "algorithmic_GBps": round(spmm_bytes(csr, d) / ms / 1e6, 1)})
+            csr.close()
+            del rowptr, col, val, X, Y
+    print(json.dumps(out))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("study", choices=["balance", "skinny"])
+    ap.add_argument("--workload", default="road", choices=["tiny", "social", "copurchase", "road"])
+    ap.add_argument("--scale", type=float, default=1.0)
+    args = ap.parse_args()
+    assert torch.cuda.is_available(), "studies.py needs a GPU"
+    torch.cuda.set_device(DEV)
+    {"balance": balance, "skinny": skinny}[args.study](args)
+
+
+if __name__ == "__main__":
+    main()
