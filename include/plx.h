@@ -139,6 +139,20 @@ PLX_API plx_status plx_spmm(plx_ctx* ctx, const plx_csr* csr, const void* X, int
 PLX_API plx_status plx_spmm_t(plx_ctx* ctx, const plx_csr* csr, const void* X, int64_t ldx, void* Y, int64_t ldy,
                               int64_t d, plx_dtype dtype);
 
+/* Blocked aggregation (Sec. 5.2: the adjacency is cut into row blocks, the product of each block
+ * is formed -- and, on several GPUs, all-reduced -- separately, and the blocks are concatenated).
+ * plx_csr_set_row_blocks re-bins both orientations into n_blocks (1..64) blocks of
+ * ceil(rows / n_blocks) consecutive rows each (a set-up call: it waits, and moves the stored
+ * entries).  plx_spmm_block then computes only the rows of one block of Y = A X (transposed == 0)
+ * or Y = A^T X (transposed != 0); Y is the base of the WHOLE output matrix and rows outside the
+ * block are not touched, so calling it for every block in any order gives exactly the result of
+ * plx_spmm / plx_spmm_t (which keep working and walk over all blocks).
+ * plx_csr_row_blocks reports the current blocking (host outputs). */
+PLX_API plx_status plx_csr_set_row_blocks(plx_ctx* ctx, plx_csr* csr, int n_blocks);
+PLX_API plx_status plx_csr_row_blocks(const plx_csr* csr, int transposed, int* n_blocks, int64_t* rows_per_block);
+PLX_API plx_status plx_spmm_block(plx_ctx* ctx, const plx_csr* csr, int transposed, int block, const void* X,
+                                  int64_t ldx, void* Y, int64_t ldy, int64_t d, plx_dtype dtype);
+
 /* ---- dense x dense on the matrix cores (Eq. 2.2, 2.6, 2.5) --------------------------------------
  * plx_gemm_nn:  C[M x N] = A[M x K]   B[K x N]
  * plx_gemm_nt:  C[M x N] = A[M x K]   B[N x K]^T

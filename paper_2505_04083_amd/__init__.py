@@ -25,7 +25,7 @@ EXPORTED = [
     "plx_ctx_create", "plx_ctx_destroy", "plx_last_error", "plx_status_string", "plx_sync",
     "plx_timing_enable", "plx_timing_report",
     "plx_build_csr", "plx_csr_import", "plx_csr_dims", "plx_csr_export", "plx_csr_bins", "plx_csr_destroy",
-    "plx_spmm", "plx_spmm_t", "plx_gemm_nn", "plx_gemm_nt", "plx_gemm_tn_workspace", "plx_gemm_tn",
+    "plx_csr_set_row_blocks", "plx_csr_row_blocks", "plx_spmm_block", "plx_spmm", "plx_spmm_t", "plx_gemm_nn", "plx_gemm_nt", "plx_gemm_tn_workspace", "plx_gemm_tn",
     "plx_relu", "plx_relu_bwd", "plx_softmax_ce",
     "plx_gcn_layer_workspace", "plx_gcn_layer_fwd", "plx_gcn_layer_bwd",
 ]
@@ -55,6 +55,9 @@ def _load() -> ctypes.CDLL:
         "plx_csr_export": (_int, [_vp, _vp, _int, _vp, _vp, _vp, _vp]),
         "plx_csr_bins": (_int, [_vp, _int, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]),
         "plx_csr_destroy": (None, [_vp, _vp]),
+        "plx_csr_set_row_blocks": (_int, [_vp, _vp, _int]),
+        "plx_csr_row_blocks": (_int, [_vp, _int, ctypes.POINTER(_int), ctypes.POINTER(_i64)]),
+        "plx_spmm_block": (_int, [_vp, _vp, _int, _int, _vp, _i64, _vp, _i64, _i64, _int]),
         "plx_spmm": (_int, [_vp, _vp, _vp, _i64, _vp, _i64, _i64, _int]),
         "plx_spmm_t": (_int, [_vp, _vp, _vp, _i64, _vp, _i64, _i64, _int]),
         "plx_gemm_nn": (_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int]),
@@ -246,6 +249,30 @@ def plx_timing_report(ctx: plx_ctx):
         name, count, ms = line.rsplit(" ", 2)
         out[name] = (int(count), float(ms))
     return out
+
+
+def plx_csr_set_row_blocks(ctx: plx_ctx, csr: plx_csr, n_blocks: int) -> None:
+    ctx.check(_lib.plx_csr_set_row_blocks(ctx.handle, csr.handle, n_blocks))
+
+
+def plx_csr_row_blocks(csr: plx_csr, transposed: bool = False) -> Tuple[int, int]:
+    """(number of row blocks, rows per block) of one orientation."""
+    nb, rpb = _int(), _i64()
+    st = _lib.plx_csr_row_blocks(csr.handle, int(transposed), ctypes.byref(nb), ctypes.byref(rpb))
+    if st != PLX_OK:
+        raise PlxError(st, "plx_csr_row_blocks")
+    return nb.value, rpb.value
+
+
+def plx_spmm_block(ctx: plx_ctx, csr: plx_csr, transposed: bool, block: int, X: torch.Tensor, Y: torch.Tensor,
+                   d: Optional[int] = None) -> torch.Tensor:
+    """Rows of row block `block` of Y = A X (or A^T X); Y is the whole output matrix."""
+    xp, ldx = _mat(X)
+    yp, ldy = _mat(Y)
+    if d is None:
+        d = X.shape[1]
+    ctx.check(_lib.plx_spmm_block(ctx.handle, csr.handle, int(transposed), block, xp, ldx, yp, ldy, d, _dtype_code(X)))
+    return Y
 
 
 def _spmm(fn, ctx, csr, X, Y, d):

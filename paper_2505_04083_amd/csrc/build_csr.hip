@@ -165,22 +165,24 @@ __device__ __forceinline__ int length_class(int64_t len) {
     return len <= 0 ? 0 : 64 - __clzll((unsigned long long)len);   // 1 + floor(log2 len)
 }
 
-__global__ void k_row_class(int64_t rows, const int64_t* rowptr, uint8_t* cls, int32_t* ids, unsigned int* hist,
-                            unsigned long long* hist_nnz) {
-    __shared__ unsigned int h[kNumClasses];
-    __shared__ unsigned long long hn[kNumClasses];
-    for (int c = threadIdx.x; c < kNumClasses; c += blockDim.x) { h[c] = 0; hn[c] = 0; }
+// sort key of a row = block * 64 + length class; histograms of rows and entries per key
+__global__ void k_row_class(int64_t rows, const int64_t* rowptr, int64_t rows_per_block, int n_keys, uint16_t* key,
+                            int32_t* ids, unsigned int* hist, unsigned long long* hist_nnz) {
+    extern __shared__ unsigned long long sh[];          // [n_keys] entry counts, then [n_keys] row counts
+    unsigned long long* hn = sh;
+    unsigned int* h = reinterpret_cast<unsigned int*>(sh + n_keys);
+    for (int c = threadIdx.x; c < n_keys; c += blockDim.x) { h[c] = 0; hn[c] = 0; }
     __syncthreads();
     GRID_STRIDE(r, rows) {
         int64_t len = rowptr[r + 1] - rowptr[r];
-        int c = length_class(len);
-        cls[r] = (uint8_t)c;
+        int k = (int)(r / rows_per_block) * 64 + length_class(len);
+        key[r] = (uint16_t)k;
         ids[r] = (int32_t)r;
-        atomicAdd(&h[c], 1u);
-        atomicAdd(&hn[c], (unsigned long long)len);
+        atomicAdd(&h[k], 1u);
+        atomicAdd(&hn[k], (unsigned long long)len);
     }
     __syncthreads();
-    for (int c = threadIdx.x; c < kNumClasses; c += blockDim.x)
+    for (int c = threadIdx.x; c < n_keys; c += blockDim.x)
         if (h[c]) { atomicAdd(&hist[c], h[c]); atomicAdd(&hist_nnz[c], hn[c]); }
 }
 
@@ -265,37 +267,50 @@ plx_status transpose_orient(plx_ctx* ctx, const Orient& src, const int32_t* src_
 
 }  // namespace
 
-plx_status build_bins(plx_ctx* ctx, Orient& o) {
+plx_status build_bins(plx_ctx* ctx, Orient& o, int n_blocks) {
     TempPool pool(ctx);
+    if (n_blocks < 1) n_blocks = 1;
+    o.n_blocks = n_blocks;
+    o.rows_per_block = std::max<int64_t>(1, ceil_div(o.rows, n_blocks));
+    const int n_keys = n_blocks * 64;
     o.row_order = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * std::max<int64_t>(1, o.rows)));
     if (!o.row_order) return PLX_ERR_OOM;
-    uint8_t* cls = pool.get<uint8_t>(o.rows);
-    uint8_t* cls_sorted = pool.get<uint8_t>(o.rows);
+    uint16_t* key = pool.get<uint16_t>(o.rows);
+    uint16_t* key_sorted = pool.get<uint16_t>(o.rows);
     int32_t* ids = pool.get<int32_t>(o.rows);
-    unsigned int* hist = pool.get<unsigned int>(kNumClasses);
-    unsigned long long* hist_nnz = pool.get<unsigned long long>(kNumClasses);
-    if (!cls || !cls_sorted || !ids || !hist || !hist_nnz) return PLX_ERR_OOM;
-    PLX_HIP(ctx, hipMemsetAsync(hist, 0, sizeof(unsigned int) * kNumClasses, ctx->stream));
-    PLX_HIP(ctx, hipMemsetAsync(hist_nnz, 0, sizeof(unsigned long long) * kNumClasses, ctx->stream));
-    unsigned int h[kNumClasses] = {0};
-    unsigned long long hn[kNumClasses] = {0};
+    unsigned int* hist = pool.get<unsigned int>(n_keys);
+    unsigned long long* hist_nnz = pool.get<unsigned long long>(n_keys);
+    if (!key || !key_sorted || !ids || !hist || !hist_nnz) return PLX_ERR_OOM;
+    PLX_HIP(ctx, hipMemsetAsync(hist, 0, sizeof(unsigned int) * n_keys, ctx->stream));
+    PLX_HIP(ctx, hipMemsetAsync(hist_nnz, 0, sizeof(unsigned long long) * n_keys, ctx->stream));
+    std::vector<unsigned int> h(n_keys, 0);
+    std::vector<unsigned long long> hn(n_keys, 0);
     if (o.rows > 0) {
-        k_row_class<<<std::min(grid_for(o.rows), 2048u), kThreads, 0, ctx->stream>>>(o.rows, o.rowptr, cls, ids, hist, hist_nnz);
-        size_t bytes = 0;   // stable sort by class: ids stay ascending inside a class
-        PLX_HIP(ctx, rocprim::radix_sort_pairs(nullptr, bytes, cls, cls_sorted, ids, o.row_order, (size_t)o.rows, 0, 6,
+        const size_t lds = (sizeof(unsigned long long) + sizeof(unsigned int)) * n_keys;
+        k_row_class<<<std::min(grid_for(o.rows), 2048u), kThreads, lds, ctx->stream>>>(o.rows, o.rowptr, o.rows_per_block, n_keys,
+                                                                                        key, ids, hist, hist_nnz);
+        const int bits = std::max(6, bit_length((uint64_t)n_keys - 1));
+        size_t bytes = 0;   // stable sort by (block, class): ids stay ascending inside a class
+        PLX_HIP(ctx, rocprim::radix_sort_pairs(nullptr, bytes, key, key_sorted, ids, o.row_order, (size_t)o.rows, 0, bits,
                                                ctx->stream));
         void* tmp = pool.get<char>(bytes);
         if (!tmp) return PLX_ERR_OOM;
-        PLX_HIP(ctx, rocprim::radix_sort_pairs(tmp, bytes, cls, cls_sorted, ids, o.row_order, (size_t)o.rows, 0, 6,
+        PLX_HIP(ctx, rocprim::radix_sort_pairs(tmp, bytes, key, key_sorted, ids, o.row_order, (size_t)o.rows, 0, bits,
                                                ctx->stream));
     }
-    PLX_HIP(ctx, hipMemcpyAsync(h, hist, sizeof h, hipMemcpyDeviceToHost, ctx->stream));
-    PLX_HIP(ctx, hipMemcpyAsync(hn, hist_nnz, sizeof hn, hipMemcpyDeviceToHost, ctx->stream));
+    PLX_HIP(ctx, hipMemcpyAsync(h.data(), hist, sizeof(unsigned int) * n_keys, hipMemcpyDeviceToHost, ctx->stream));
+    PLX_HIP(ctx, hipMemcpyAsync(hn.data(), hist_nnz, sizeof(unsigned long long) * n_keys, hipMemcpyDeviceToHost, ctx->stream));
     PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    o.class_off[0] = 0;
-    for (int c = 0; c < kNumClasses; ++c) {
-        o.class_off[c + 1] = o.class_off[c] + h[c];
-        o.class_nnz[c] = (int64_t)hn[c];
+    o.boff.assign((size_t)n_blocks * (kNumClasses + 1), 0);
+    o.bnnz.assign((size_t)n_blocks * kNumClasses, 0);
+    int64_t run = 0;
+    for (int b = 0; b < n_blocks; ++b) {
+        for (int c = 0; c < kNumClasses; ++c) {
+            o.boff[(size_t)b * (kNumClasses + 1) + c] = run;
+            run += h[b * 64 + c];
+            o.bnnz[(size_t)b * kNumClasses + c] = (int64_t)hn[b * 64 + c];
+        }
+        o.boff[(size_t)b * (kNumClasses + 1) + kNumClasses] = run;
     }
 
     // binned storage: slot pointers, then move the entries so that the rows of a bin are contiguous
@@ -318,39 +333,64 @@ plx_status build_bins(plx_ctx* ctx, Orient& o) {
         }
     }
 
-    // long rows -> segments (few of them: done on the host), in binned coordinates
-    o.n_long = o.class_off[kNumClasses] - o.class_off[kLongClass];
-    o.n_seg = 0;
-    if (o.n_long > 0) {
-        std::vector<int32_t> rows(o.n_long);
-        PLX_HIP(ctx, hipMemcpy(rows.data(), o.row_order + o.class_off[kLongClass], sizeof(int32_t) * o.n_long,
-                               hipMemcpyDeviceToHost));
-        std::vector<int32_t> bp(o.n_long + 1);
-        PLX_HIP(ctx, hipMemcpy(bp.data(), o.bptr + o.class_off[kLongClass], sizeof(int32_t) * (o.n_long + 1),
-                               hipMemcpyDeviceToHost));
-        std::vector<int64_t> lo(o.n_long), hi(o.n_long);
-        for (int64_t q = 0; q < o.n_long; ++q) { lo[q] = bp[q]; hi[q] = bp[q + 1]; }
-        std::vector<int32_t> seg0(o.n_long + 1, 0), seg_len;
-        std::vector<int64_t> seg_lo;
-        for (int64_t q = 0; q < o.n_long; ++q) {
-            seg0[q] = (int32_t)seg_lo.size();
-            for (int64_t e = lo[q]; e < hi[q]; e += kSegLen) {
+    // long rows -> segments (few of them: done on the host), in binned coordinates, block by block
+    o.long0.assign(n_blocks + 1, 0);
+    o.seg0b.assign(n_blocks + 1, 0);
+    std::vector<int32_t> long_rows, seg0, seg_len;
+    std::vector<int64_t> seg_lo;
+    for (int b = 0; b < n_blocks; ++b) {
+        const int64_t s0 = o.off(b, kLongClass), cnt = o.off(b, kNumClasses) - s0;
+        o.long0[b] = (int64_t)long_rows.size();
+        o.seg0b[b] = (int64_t)seg_lo.size();
+        if (cnt == 0) continue;
+        std::vector<int32_t> rows(cnt), bp(cnt + 1);
+        PLX_HIP(ctx, hipMemcpy(rows.data(), o.row_order + s0, sizeof(int32_t) * cnt, hipMemcpyDeviceToHost));
+        PLX_HIP(ctx, hipMemcpy(bp.data(), o.bptr + s0, sizeof(int32_t) * (cnt + 1), hipMemcpyDeviceToHost));
+        for (int64_t q = 0; q < cnt; ++q) {
+            long_rows.push_back(rows[q]);
+            seg0.push_back((int32_t)seg_lo.size());
+            for (int64_t e = bp[q]; e < bp[q + 1]; e += kSegLen) {
                 seg_lo.push_back(e);
-                seg_len.push_back((int32_t)std::min<int64_t>(kSegLen, hi[q] - e));
+                seg_len.push_back((int32_t)std::min<int64_t>(kSegLen, bp[q + 1] - e));
             }
         }
-        seg0[o.n_long] = (int32_t)seg_lo.size();
-        o.n_seg = (int64_t)seg_lo.size();
+    }
+    o.long0[n_blocks] = (int64_t)long_rows.size();
+    o.seg0b[n_blocks] = (int64_t)seg_lo.size();
+    seg0.push_back((int32_t)seg_lo.size());
+    o.n_long = (int64_t)long_rows.size();
+    o.n_seg = (int64_t)seg_lo.size();
+    if (o.n_long > 0) {
         o.long_row = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * o.n_long));
         o.long_seg0 = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * (o.n_long + 1)));
         o.seg_lo = static_cast<int64_t*>(dev_alloc(ctx, sizeof(int64_t) * o.n_seg));
         o.seg_len = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * o.n_seg));
         if (!o.long_row || !o.long_seg0 || !o.seg_lo || !o.seg_len) return PLX_ERR_OOM;
-        PLX_HIP(ctx, hipMemcpy(o.long_row, rows.data(), sizeof(int32_t) * o.n_long, hipMemcpyHostToDevice));
+        PLX_HIP(ctx, hipMemcpy(o.long_row, long_rows.data(), sizeof(int32_t) * o.n_long, hipMemcpyHostToDevice));
         PLX_HIP(ctx, hipMemcpy(o.long_seg0, seg0.data(), sizeof(int32_t) * (o.n_long + 1), hipMemcpyHostToDevice));
         PLX_HIP(ctx, hipMemcpy(o.seg_lo, seg_lo.data(), sizeof(int64_t) * o.n_seg, hipMemcpyHostToDevice));
         PLX_HIP(ctx, hipMemcpy(o.seg_len, seg_len.data(), sizeof(int32_t) * o.n_seg, hipMemcpyHostToDevice));
     }
+    return PLX_OK;
+}
+
+plx_status unbin(plx_ctx* ctx, Orient& o) {
+    if (o.nnz > 0) {
+        int32_t* col_c = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * o.nnz));
+        float* val_c = static_cast<float*>(dev_alloc(ctx, sizeof(float) * o.nnz));
+        if (!col_c || !val_c) { dev_free(ctx, col_c); dev_free(ctx, val_c); return PLX_ERR_OOM; }
+        k_move_entries<<<grid_for(o.nnz), kThreads, 0, ctx->stream>>>(o.rows, o.nnz, o.bptr, o.row_order, o.rowptr, o.col,
+                                                                      o.val, col_c, val_c, 0);
+        PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        dev_free(ctx, o.col); dev_free(ctx, o.val);
+        o.col = col_c; o.val = val_c;
+    } else {
+        PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    }
+    dev_free(ctx, o.row_order); dev_free(ctx, o.bptr);
+    dev_free(ctx, o.long_row); dev_free(ctx, o.long_seg0); dev_free(ctx, o.seg_lo); dev_free(ctx, o.seg_len);
+    o.row_order = nullptr; o.bptr = nullptr; o.long_row = nullptr; o.long_seg0 = nullptr; o.seg_lo = nullptr; o.seg_len = nullptr;
+    o.n_long = o.n_seg = 0;
     return PLX_OK;
 }
 
@@ -528,6 +568,22 @@ plx_status plx_csr_import(plx_ctx* ctx, int64_t m, int64_t k, int64_t nnz, const
     }();
     if (st != PLX_OK) { plx_csr_destroy(ctx, h); return st; }
     *out = h;
+    return PLX_OK;
+}
+
+plx_status plx_csr_set_row_blocks(plx_ctx* ctx, plx_csr* csr, int n_blocks) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!csr) return fail(ctx, PLX_ERR_INVALID, "csr is NULL");
+    if (n_blocks < 1 || n_blocks > 64) return fail(ctx, PLX_ERR_INVALID, "n_blocks must be between 1 and 64");
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    PLX_HIP(ctx, hipSetDevice(ctx->device));
+    for (int t = 0; t < 2; ++t) {
+        Orient& o = csr->o[t];
+        if (o.n_blocks == n_blocks) continue;
+        PLX_TRY(unbin(ctx, o));
+        PLX_TRY(build_bins(ctx, o, n_blocks));
+    }
+    PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
     return PLX_OK;
 }
 

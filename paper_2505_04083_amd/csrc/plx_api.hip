@@ -166,9 +166,12 @@ plx_status plx_csr_bins(const plx_csr* csr, int transposed, int64_t* rows, int64
     const Orient& o = csr->o[transposed ? 1 : 0];
     const int edge[4] = {0, kSubwaveMaxClass + 1, kLongClass, kNumClasses};
     for (int b = 0; b < 3; ++b) {
-        int64_t nz = 0;
-        for (int c = edge[b]; c < edge[b + 1]; ++c) nz += o.class_nnz[c];
-        if (rows) rows[b] = o.class_off[edge[b + 1]] - o.class_off[edge[b]];
+        int64_t nz = 0, nr = 0;
+        for (int blk = 0; blk < o.n_blocks; ++blk) {
+            for (int c = edge[b]; c < edge[b + 1]; ++c) nz += o.bnnz[(size_t)blk * kNumClasses + c];
+            nr += o.off(blk, edge[b + 1]) - o.off(blk, edge[b]);
+        }
+        if (rows) rows[b] = nr;
         if (entries) entries[b] = nz;
     }
     return PLX_OK;
@@ -227,6 +230,29 @@ static plx_status spmm_entry(plx_ctx* ctx, const plx_csr* csr, int t, const void
     if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
     if (d == 0 || o.rows == 0) return PLX_OK;
     return launch_spmm(ctx, o, X, ldx, Y, ldy, d, dtype);
+}
+
+plx_status plx_csr_row_blocks(const plx_csr* csr, int transposed, int* n_blocks, int64_t* rows_per_block) {
+    if (!csr) return PLX_ERR_INVALID;
+    const Orient& o = csr->o[transposed ? 1 : 0];
+    if (n_blocks) *n_blocks = o.n_blocks;
+    if (rows_per_block) *rows_per_block = o.rows_per_block;
+    return PLX_OK;
+}
+
+plx_status plx_spmm_block(plx_ctx* ctx, const plx_csr* csr, int transposed, int block, const void* X, int64_t ldx,
+                          void* Y, int64_t ldy, int64_t d, plx_dtype dtype) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!csr) return fail(ctx, PLX_ERR_INVALID, "csr is NULL");
+    const Orient& o = csr->o[transposed ? 1 : 0];
+    if (block < 0 || block >= o.n_blocks) return fail(ctx, PLX_ERR_INVALID, "block %d outside [0, %d)", block, o.n_blocks);
+    if (!dtype_ok(dtype)) return fail(ctx, PLX_ERR_INVALID, "unknown dtype %d", (int)dtype);
+    if (d < 0) return fail(ctx, PLX_ERR_INVALID, "d = %lld is negative", (long long)d);
+    if (d > 0 && ((o.cols > 0 && !X) || (o.rows > 0 && !Y))) return fail(ctx, PLX_ERR_INVALID, "X or Y is NULL");
+    if (ldx < d || ldy < d) return fail(ctx, PLX_ERR_SHAPE, "leading dimension smaller than d");
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    if (d == 0 || o.rows == 0) return PLX_OK;
+    return launch_spmm(ctx, o, X, ldx, Y, ldy, d, dtype, nullptr, 0, block);
 }
 
 plx_status plx_spmm(plx_ctx* ctx, const plx_csr* csr, const void* X, int64_t ldx, void* Y, int64_t ldy, int64_t d,

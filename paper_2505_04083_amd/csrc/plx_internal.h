@@ -29,9 +29,16 @@ struct Orient {
     int32_t* col = nullptr;        // device [nnz]
     float* val = nullptr;          // device [nnz]
     int32_t* bptr = nullptr;       // device [rows + 1]: slot pointers into col/val
-    int32_t* row_order = nullptr;  // device [rows]: row ids sorted by length class, ascending id inside a class
-    int64_t class_off[kNumClasses + 1] = {0};  // host: slot range of each class inside row_order
-    int64_t class_nnz[kNumClasses] = {0};      // host: stored entries in the rows of each class
+    int32_t* row_order = nullptr;  // device [rows]: row ids sorted by (row block, length class), ascending id inside
+    // Row blocks (blocked aggregation, paper Sec. 5.2): block b holds rows [b*rows_per_block, ...).  The
+    // slot list is sorted by block first, so every block owns one contiguous slot range per class.
+    int n_blocks = 1;
+    int64_t rows_per_block = 0;
+    std::vector<int64_t> boff;     // host [n_blocks * (kNumClasses + 1)]: first slot of class c in block b
+    std::vector<int64_t> bnnz;     // host [n_blocks * kNumClasses]: stored entries per (block, class)
+    std::vector<int64_t> long0;    // host [n_blocks + 1]: first long row (index into long_row) of block b
+    std::vector<int64_t> seg0b;    // host [n_blocks + 1]: first segment of block b
+    int64_t off(int b, int c) const { return boff[(size_t)b * (kNumClasses + 1) + c]; }
     int tag = 0;                               // 0 = forward orientation, 1 = its transpose (timing labels)
     // rows of class >= kLongClass, cut into segments of at most kSegLen nonzeros
     int64_t n_long = 0, n_seg = 0;
@@ -119,16 +126,20 @@ struct KernelTimer {
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// set-up: fills the binning fields of `o` from its CSR arrays (waits on the stream)
-plx_status build_bins(plx_ctx* ctx, Orient& o);
+// set-up: fills the binning fields of `o` from its canonical CSR arrays and re-orders the entries
+// into binned storage (waits on the stream)
+plx_status build_bins(plx_ctx* ctx, Orient& o, int n_blocks = 1);
+// undoes build_bins: entries back in canonical CSR order, binning fields released
+plx_status unbin(plx_ctx* ctx, Orient& o);
 // copies the entries of `o` back into canonical CSR order (either output may be NULL)
 plx_status export_entries(plx_ctx* ctx, const Orient& o, int32_t* col, float* val);
 void free_orient(plx_ctx* ctx, Orient& o);
 
 // kernels' host launchers (all asynchronous on ctx->stream)
-// Y = A X (Y may be NULL); if Yact != NULL it also receives max(A X, 0)
+// Y = A X (Y may be NULL); if Yact != NULL it also receives max(A X, 0).  block >= 0 restricts the
+// product to the rows of that row block (other rows of Y are not touched)
 plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* Y, int64_t ldy,
-                       int64_t d, plx_dtype dtype, void* Yact = nullptr, int64_t ldyact = 0);
+                       int64_t d, plx_dtype dtype, void* Yact = nullptr, int64_t ldyact = 0, int block = -1);
 // C = A op(B) (C may be NULL); if Fact != NULL it also receives max(C, 0)
 plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                        const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype, void* Fact = nullptr,

@@ -269,10 +269,13 @@ __global__ __launch_bounds__(256) void k_spmm_combine(int64_t n_long, const int3
 }
 
 template <typename T, int G, int VW>
-plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, Out<T> out, int d) {
+plx_status run_pass(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t ldx, Out<T> out, int d) {
     hipStream_t s = ctx->stream;
-    const int64_t n_sub = o.class_off[kSubwaveMaxClass + 1];
-    const int64_t n_wave = o.class_off[kLongClass] - n_sub;
+    const int64_t s0 = o.off(blk, 0);                                  // first slot of this row block
+    const int64_t n_sub = o.off(blk, kSubwaveMaxClass + 1) - s0;
+    const int64_t n_wave = o.off(blk, kLongClass) - s0 - n_sub;
+    const int64_t n_long = o.long0[blk + 1] - o.long0[blk], l0 = o.long0[blk];
+    const int64_t n_seg = o.seg0b[blk + 1] - o.seg0b[blk], g0 = o.seg0b[blk];
     constexpr int WPB = 256 / kWave;   // wavefronts per block
     char label[64];
     snprintf(label, sizeof label, "<%s,G%d,VW%d,d%d>[%s]", sizeof(T) == 4 ? "f32" : "bf16", G, VW, d, o.tag ? "At" : "A");
@@ -284,23 +287,23 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, Out<
 #if PLX_SUB_PERSIST
         blocks = std::min<int64_t>(blocks, (int64_t)ctx->n_cu * PLX_SUB_PERSIST);
 #endif
-        k_spmm_subwave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order, sub_count, o.bptr, o.col, o.val, X,
+        k_spmm_subwave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + s0, sub_count, o.bptr + s0, o.col, o.val, X,
                                                                          ldx, out, d);
     }
     if (n_wave > 0) {
         KernelTimer kt(ctx, std::string("spmm_wave") + label);
         int64_t blocks = ceil_div(n_wave, WPB);
-        k_spmm_wave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + n_sub, n_wave, o.bptr + n_sub, o.col,
+        k_spmm_wave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + s0 + n_sub, n_wave, o.bptr + s0 + n_sub, o.col,
                                                                       o.val, X, ldx, out, d);
     }
-    if (o.n_seg > 0) {
+    if (n_seg > 0) {
         PLX_TRY(ensure_scratch(ctx, (size_t)o.n_seg * G * VW * sizeof(float)));
-        float* part = static_cast<float*>(ctx->scratch);
+        float* part = static_cast<float*>(ctx->scratch);                // indexed by the global segment number
         KernelTimer kt(ctx, std::string("spmm_split") + label);
-        k_spmm_segment<T, G, VW><<<dim3((unsigned)ceil_div(o.n_seg, WPB)), 256, 0, s>>>(o.n_seg, o.seg_lo, o.seg_len,
-                                                                                         o.col, o.val, X, ldx, part, d);
-        int64_t total = o.n_long * d;
-        k_spmm_combine<T><<<dim3((unsigned)ceil_div(total, 256)), 256, 0, s>>>(o.n_long, o.long_row, o.long_seg0, part,
+        k_spmm_segment<T, G, VW><<<dim3((unsigned)ceil_div(n_seg, WPB)), 256, 0, s>>>(n_seg, o.seg_lo + g0, o.seg_len + g0, o.col,
+                                                                                       o.val, X, ldx, part + g0 * (G * VW), d);
+        int64_t total = n_long * d;
+        k_spmm_combine<T><<<dim3((unsigned)ceil_div(total, 256)), 256, 0, s>>>(n_long, o.long_row + l0, o.long_seg0 + l0, part,
                                                                                G * VW, out, d);
     }
     PLX_HIP(ctx, hipGetLastError());
@@ -308,7 +311,7 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, Out<
 }
 
 template <typename T, int VW>
-plx_status run_vw(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, Out<T> out, int64_t d) {
+plx_status run_vw(plx_ctx* ctx, const Orient& o, int block, const T* X, int64_t ldx, Out<T> out, int64_t d) {
     const int tile = kWave * VW;                        // widest pass one wavefront covers
     for (int64_t t0 = 0; t0 < d; t0 += tile) {
         int dp = (int)std::min<int64_t>(tile, d - t0);
@@ -317,17 +320,20 @@ plx_status run_vw(plx_ctx* ctx, const Orient& o, const T* X, int64_t ldx, Out<T>
         while (G < chunks) G <<= 1;
         const T* Xp = X + t0;
         Out<T> op{out.y ? out.y + t0 : nullptr, out.ldy, out.ya ? out.ya + t0 : nullptr, out.ldya};
+        const int b_lo = block < 0 ? 0 : block, b_hi = block < 0 ? o.n_blocks : block + 1;
+        for (int blk = b_lo; blk < b_hi; ++blk) {
         plx_status st;
         switch (G) {
-            case 1: st = run_pass<T, 1, VW>(ctx, o, Xp, ldx, op, dp); break;
-            case 2: st = run_pass<T, 2, VW>(ctx, o, Xp, ldx, op, dp); break;
-            case 4: st = run_pass<T, 4, VW>(ctx, o, Xp, ldx, op, dp); break;
-            case 8: st = run_pass<T, 8, VW>(ctx, o, Xp, ldx, op, dp); break;
-            case 16: st = run_pass<T, 16, VW>(ctx, o, Xp, ldx, op, dp); break;
-            case 32: st = run_pass<T, 32, VW>(ctx, o, Xp, ldx, op, dp); break;
-            default: st = run_pass<T, 64, VW>(ctx, o, Xp, ldx, op, dp); break;
+            case 1: st = run_pass<T, 1, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
+            case 2: st = run_pass<T, 2, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
+            case 4: st = run_pass<T, 4, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
+            case 8: st = run_pass<T, 8, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
+            case 16: st = run_pass<T, 16, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
+            case 32: st = run_pass<T, 32, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
+            default: st = run_pass<T, 64, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
         }
         PLX_TRY(st);
+        }
     }
     return PLX_OK;
 }
@@ -337,7 +343,7 @@ bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p
 }  // namespace
 
 plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* Y, int64_t ldy, int64_t d,
-                       plx_dtype dtype, void* Yact, int64_t ldyact) {
+                       plx_dtype dtype, void* Yact, int64_t ldyact, int block) {
     if (o.rows >= (int64_t(1) << 31) || o.nnz >= (int64_t(1) << 31))
         return fail(ctx, PLX_ERR_UNSUPPORTED, "matrix too large for 32-bit ids");
     // widest vector the layout allows: base pointers and row pitches must keep every row aligned
@@ -349,15 +355,15 @@ plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx
     if (dtype == PLX_F32) {
         const float* x = static_cast<const float*>(X);
         Out<float> out{static_cast<float*>(Y), ldy, static_cast<float*>(Yact), ldyact};
-        if (fits(16, 4)) return run_vw<float, 4>(ctx, o, x, ldx, out, d);
-        if (fits(8, 4)) return run_vw<float, 2>(ctx, o, x, ldx, out, d);
-        return run_vw<float, 1>(ctx, o, x, ldx, out, d);
+        if (fits(16, 4)) return run_vw<float, 4>(ctx, o, block, x, ldx, out, d);
+        if (fits(8, 4)) return run_vw<float, 2>(ctx, o, block, x, ldx, out, d);
+        return run_vw<float, 1>(ctx, o, block, x, ldx, out, d);
     }
     const bf16_t* x = static_cast<const bf16_t*>(X);
     Out<bf16_t> out{static_cast<bf16_t*>(Y), ldy, static_cast<bf16_t*>(Yact), ldyact};
-    if (fits(16, 2)) return run_vw<bf16_t, 8>(ctx, o, x, ldx, out, d);
-    if (fits(8, 2)) return run_vw<bf16_t, 4>(ctx, o, x, ldx, out, d);
-    return run_vw<bf16_t, 1>(ctx, o, x, ldx, out, d);
+    if (fits(16, 2)) return run_vw<bf16_t, 8>(ctx, o, block, x, ldx, out, d);
+    if (fits(8, 2)) return run_vw<bf16_t, 4>(ctx, o, block, x, ldx, out, d);
+    return run_vw<bf16_t, 1>(ctx, o, block, x, ldx, out, d);
 }
 
 }  // namespace plx

@@ -11,6 +11,12 @@ synthetic workloads (the paper's datasets are not available).  Each prints one J
       Tall-skinny sensitivity (Sec. 4.1, Table 2): at equal flops, configuration U_g (the
       adjacency block has K/g columns, the dense operand keeps width 128) against V_g (full K,
       dense operand 128/g wide), g = 1, 4, 16, 64.
+
+  python studies.py blocks [--scale 1.0]
+      Blocked aggregation (Sec. 5.2) on the shard block: the forward product at width 32 and the
+      transposed product (also width 32, as in the layer's backward pass) with the rows cut into 1, 2, 4, 8, 16, 32 blocks -- the
+      one-GPU cost of issuing the aggregation as separate per-block launches, which is what a
+      multi-GPU run overlaps with the per-block all-reduce.
 """
 from __future__ import annotations
 
@@ -105,15 +111,49 @@ def skinny(args):
     print(json.dumps(out))
 
 
+def blocks(args):
+    ctx = plx.plx_ctx(0)
+    cfg = synth.CONFIGS["shard"]
+    m, k, samples = (int(cfg.m * args.scale), int(cfg.k * args.scale), int(cfg.n_samples * args.scale))
+    rowptr, col, val = synth.shard_block(cfg.seed, m, k, samples, DEV)
+    csr = plx.plx_csr_import(ctx, m, k, rowptr, col, val)
+    del rowptr, col, val
+    X = synth.normal(cfg.seed, synth.S_FEAT, k, 32, DEV)
+    Y = torch.empty(m, 32, device=DEV)
+    G = synth.normal(cfg.seed, synth.S_AUX, m, 32, DEV)
+    Gt = torch.empty(k, 32, device=DEV)
+    out = {"study": "blocked aggregation, per-block launches on one GPU (Sec. 5.2)", "m": m, "k": k, "nnz": csr.nnz,
+           "cases": []}
+    for nb in (1, 2, 4, 8, 16, 32):
+        plx.plx_csr_set_row_blocks(ctx, csr, nb)
+        fwd = time_spmm(ctx, csr, X, Y)
+        plx.plx_spmm_t(ctx, csr, G, Gt); plx.plx_sync(ctx)
+        reps = 5
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            plx.plx_spmm_t(ctx, csr, G, Gt)
+        plx.plx_sync(ctx)
+        bwd = (time.perf_counter() - t0) * 1e3 / reps
+        per_block = []
+        for b in range(nb):
+            plx.plx_spmm_block(ctx, csr, False, b, X, Y); plx.plx_sync(ctx)
+            t0 = time.perf_counter()
+            plx.plx_spmm_block(ctx, csr, False, b, X, Y); plx.plx_sync(ctx)
+            per_block.append((time.perf_counter() - t0) * 1e3)
+        out["cases"].append({"n_blocks": nb, "spmm_d32_ms": round(fwd, 3), "spmm_t_d32_ms": round(bwd, 3),
+                             "block_ms_min": round(min(per_block), 3), "block_ms_max": round(max(per_block), 3)})
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["balance", "skinny"])
+    ap.add_argument("study", choices=["balance", "skinny", "blocks"])
     ap.add_argument("--workload", default="road", choices=["tiny", "social", "copurchase", "road"])
     ap.add_argument("--scale", type=float, default=1.0)
     args = ap.parse_args()
     assert torch.cuda.is_available(), "studies.py needs a GPU"
     torch.cuda.set_device(DEV)
-    {"balance": balance, "skinny": skinny}[args.study](args)
+    {"balance": balance, "skinny": skinny, "blocks": blocks}[args.study](args)
 
 
 if __name__ == "__main__":

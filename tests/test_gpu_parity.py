@@ -178,6 +178,61 @@ def test_spmm_and_transpose_parity(ctx, d, pad):
     assert torch.equal(Y2[:, :d], Y[:, :d])
 
 
+@pytest.mark.parametrize("n_blocks", [1, 3, 8, 64])
+def test_blocked_aggregation(ctx, n_blocks):
+    """Row-blocked aggregation (Sec. 5.2): each block's product against the oracle restricted to
+    that block's rows; untouched rows stay untouched; all blocks together reproduce the
+    unblocked result bit for bit; the stored structure is unchanged by re-blocking."""
+    m, k, d = 1531, 9973, 48
+    rowptr, col, val = random_block(m, k, 91, giant_row=1200)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(5)
+    X = r.standard_normal((k, d)).astype(np.float32)
+    G = r.standard_normal((m, d)).astype(np.float32)
+    whole = torch.empty(m, d, device=DEV); whole_t = torch.empty(k, d, device=DEV)
+    plx.plx_spmm(ctx, csr, dev(X), whole)
+    plx.plx_spmm_t(ctx, csr, dev(G), whole_t)
+    bins_before = plx.plx_csr_bins(csr, False), plx.plx_csr_bins(csr, True)
+    plx.plx_csr_set_row_blocks(ctx, csr, n_blocks)
+    assert (plx.plx_csr_bins(csr, False), plx.plx_csr_bins(csr, True)) == bins_before
+    for t in (False, True):
+        g = plx.plx_csr_export(ctx, csr, t)
+        if not t:
+            assert np.array_equal(g[0].cpu().numpy(), rowptr) and np.array_equal(g[1].cpu().numpy(), col)
+            assert np.array_equal(bits(g[2]), val.view(np.uint32))
+    ref = oracle.spmm_coo(m, row, c64, v64, X)
+    ref_t = oracle.spmm_t_coo(k, row, c64, v64, G)
+    for t, rows, src, full, want in ((False, m, X, whole, ref), (True, k, G, whole_t, ref_t)):
+        nb, rpb = plx.plx_csr_row_blocks(csr, t)
+        assert nb == n_blocks and rpb == -(-rows // n_blocks)
+        Y = torch.full((rows, d), 7.0, device=DEV)
+        for b in reversed(range(nb)):                               # any order
+            lo, hi = min(rows, b * rpb), min(rows, (b + 1) * rpb)
+            before = Y.clone()
+            plx.plx_spmm_block(ctx, csr, t, b, dev(src), Y)
+            plx.plx_sync(ctx)
+            if hi > lo:
+                assert rel_err(Y[lo:hi], want[lo:hi]) <= TOL32 or float(np.abs(want[lo:hi]).max()) == 0.0
+            assert torch.equal(Y[:lo], before[:lo]) and torch.equal(Y[hi:], before[hi:])
+        assert torch.equal(Y, full)
+        # the whole-matrix entry points walk over the blocks
+        Y2 = torch.empty_like(Y)
+        (plx.plx_spmm_t if t else plx.plx_spmm)(ctx, csr, dev(src), Y2)
+        plx.plx_sync(ctx)
+        assert torch.equal(Y2, full)
+    with pytest.raises(plx.PlxError) as err:
+        plx.plx_spmm_block(ctx, csr, False, n_blocks, dev(X), whole)
+    assert err.value.status == plx.PLX_ERR_INVALID
+    with pytest.raises(plx.PlxError):
+        plx.plx_csr_set_row_blocks(ctx, csr, 65)
+    plx.plx_csr_set_row_blocks(ctx, csr, 1)
+    Y3 = torch.empty_like(whole)
+    plx.plx_spmm(ctx, csr, dev(X), Y3); plx.plx_sync(ctx)
+    assert torch.equal(Y3, whole)
+    csr.close()
+
+
 def test_spmm_eigenvector_pin(ctx):
     """A^ sqrt(d) = sqrt(d): the normalised adjacency built on the GPU, applied on the GPU."""
     cfg = synth.CONFIGS["tiny"]
