@@ -15,7 +15,10 @@ Prints ONE JSON line.  Besides the contract keys it carries
   "roofline":     the dominant kernel's algorithmic HBM bytes / its average duration (HIP events
                   recorded around every launch inside the timed steps) against 8 TB/s,
   "cpu_baseline": the CPU oracle timed on a bounded sample of the same workload (default workload),
-  "kernels":      per-kernel ms / GB/s / GFLOP/s of one step (information only).
+  "spmm_calls":   each sparse product of one step (all its kernels together): ms, GFLOP/s = 2 nnz D / t
+                  (Eq. 4.3) and GB/s on the no-reuse byte count and on the perfect-reuse lower bound,
+  "kernels":      per-kernel ms, GB/s, TFLOP/s and the fraction of the HBM and matrix-core peaks,
+  "trials":       ms per step of `--trials` repetitions of the K timed steps (mean and min).
 """
 from __future__ import annotations
 
@@ -31,6 +34,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # dense matrix-core peaks of the part
 METRIC = "GCN layer fwd+bwd ms; SpMM achieved HBM GB/s (% roofline) on 1 MI355X"
 
 
@@ -43,8 +47,10 @@ def parse():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only; <1 is not the metric)")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
                     help="storage type of activations / gradients (the headline metric is f32)")
+    ap.add_argument("--trials", type=int, default=3, help="repetitions of the K timed steps (the first one is `value`)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-div", type=int, default=2, help="oracle sample = 1/div of the rows")
+    ap.add_argument("--cpu-sample-div", type=int, default=0,
+                    help="oracle sample = 1/div of the workload (0: 2 for the shard, 1 for tiny, 4 for social / copurchase, 32 for road)")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run plain device copies of known size (reference dispatch for counter scaling)")
     return ap.parse_args()
@@ -210,6 +216,14 @@ def main():
     timing = plx.plx_timing_report(ctx)
     plx.plx_timing_enable(ctx, False)
     ms_per_step = elapsed * 1e3 / args.steps
+    trial_ms = [ms_per_step]
+    for _ in range(args.trials - 1):
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        plx.plx_sync(ctx)
+        torch.cuda.synchronize()
+        trial_ms.append((time.perf_counter() - t0) * 1e3 / args.steps)
 
     # ---- per-kernel accounting (algorithmic bytes / flops of one launch) -------------------------
     bins = {"A": plx.plx_csr_bins(csr, False), "At": plx.plx_csr_bins(csr, True)}
@@ -221,6 +235,12 @@ def main():
         kernels[name] = {"launches_per_step": count / args.steps, "avg_ms": round(avg, 4),
                          "GBps": None if not b else round(b / avg / 1e6, 1),
                          "GFLOPs": None if not fl else round(fl / avg / 1e6, 1)}
+        if b:
+            kernels[name]["frac_hbm"] = round(b / avg / 1e6 / HBM_PEAK_GBS, 4)
+        if fl and not name.startswith("spmm_"):      # dense products run on the matrix cores
+            peak = MFMA_PEAK_TFLOPS["bf16" if "<bf16>" in name else "f32"]
+            kernels[name]["frac_mfma"] = round(fl / avg / 1e9 / peak, 4)
+            kernels[name]["binding"] = "hbm" if kernels[name]["frac_hbm"] >= kernels[name]["frac_mfma"] else "mfma"
     dominant = max((n for n in timing if cost[n][0]), key=lambda n: timing[n][1])
     d_avg = timing[dominant][1] / timing[dominant][0]
     d_bytes = cost[dominant][0]
@@ -237,10 +257,32 @@ def main():
     spmm = {"ms_per_step": round(sp_ms, 4), "GBps": round(sp_by / sp_ms / 1e6, 1),
             "frac_of_8TBps": round(sp_by / sp_ms / 1e6 / HBM_PEAK_GBS, 4), "GFLOPs": round(sp_fl / sp_ms / 1e6, 1)}
 
+    # one entry per sparse product (orientation, width): its kernels together
+    calls = {}
+    for n, c, t in sp:
+        m_ = re.match(r"spmm_\w+<(f32|bf16),G\d+,VW\d+,d(\d+)>\[(A|At)\]", n)
+        key = (m_.group(3), int(m_.group(2)), m_.group(1))
+        e = calls.setdefault(key, {"ms": 0.0, "bytes": 0.0, "flops": 0.0, "launches": 0.0})
+        e["ms"] += t / args.steps; e["bytes"] += cost[n][0] * c / args.steps; e["flops"] += cost[n][1] * c / args.steps
+        e["launches"] = max(e["launches"], c / args.steps)
+    spmm_calls = []
+    for (o, d, dt), e in sorted(calls.items()):
+        rows_o = sum(bins[o][0]); cols_o = sum(bins["At" if o == "A" else "A"][0]); s_ = 4 if dt == "f32" else 2
+        b_min = (8 * csr.nnz + 4 * (rows_o + 1) + s_ * d * (rows_o + cols_o)) * e["launches"]
+        spmm_calls.append({"matrix": o, "width": d, "dtype": dt, "calls_per_step": e["launches"], "ms": round(e["ms"], 4),
+                           "GFLOPs": round(e["flops"] / e["ms"] / 1e6, 1),
+                           "GBps_no_reuse": round(e["bytes"] / e["ms"] / 1e6, 1),
+                           "frac_of_8TBps": round(e["bytes"] / e["ms"] / 1e6 / HBM_PEAK_GBS, 4),
+                           "GBps_perfect_reuse_bound": round(b_min / e["ms"] / 1e6, 1)})
+
     cpu = None
-    if cfg.kind == "shard" and not args.no_cpu_baseline:
-        rowptr, col, val, X, W, dF = cpu_inputs
-        cpu = cpu_baseline(cfg, rowptr, col, val, X.float(), W, dF.float(), args.cpu_sample_div)
+    if not args.no_cpu_baseline:
+        div = args.cpu_sample_div or {"shard": 2, "tiny": 1, "road": 32}.get(args.workload, 4)
+        if cfg.kind == "shard":
+            rowptr, col, val, X, W, dF = cpu_inputs
+            cpu = cpu_baseline(cfg, rowptr, col, val, X.float(), W, dF.float(), div)
+        else:
+            cpu = cpu_baseline_network(cfg, div, unit)
 
     out = {
         "metric": METRIC, "value": round(ms_per_step, 4), "unit": unit,
@@ -248,7 +290,9 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": workload, **shape, "nnz": csr.nnz,
                    "rows_entries_by_bin(<256,<4096,>=4096)": {k_: [list(v[0]), list(v[1])] for k_, v in bins.items()}},
-        "roofline": roofline, "cpu_baseline": cpu, "spmm": spmm, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu, "spmm": spmm, "spmm_calls": spmm_calls, "kernels": kernels,
+        "trials": {"ms_per_step": [round(x, 4) for x in trial_ms], "mean": round(sum(trial_ms) / len(trial_ms), 4),
+                   "min": round(min(trial_ms), 4)},
         "setup_s": {"generate": round(t_gen, 2), "csr_build_transpose_bins": round(t_build, 2)},
     }
     print(json.dumps(out))
@@ -284,6 +328,26 @@ def cpu_baseline(cfg, rowptr, col, val, X, W, dF, div):
             "sample": f"1/{div} of the block (rows [0,{mb}) for Eq. 2.1-2.6, output rows [0,{kb}) for Eq. 2.7), "
                       f"{total:.1f} s of CPU work, each part scaled by {div}",
             "parts_s": {k_: round(v_, 3) for k_, v_ in t.items()}}
+
+
+def cpu_baseline_network(cfg, div, unit):
+    """The oracle's whole-network forward + backward (Eq. 2.1-2.7 and the loss head) on the same
+    recipe shrunk to 1/div of the nodes and edges (same degree distribution and widths); time
+    scaled by div."""
+    import oracle
+    from oracle import gcn as ogcn
+    small = cfg if div == 1 else cfg.scaled(1.0 / div)
+    src, dst = small.edges()
+    F0 = small.features().numpy()
+    Ws = [w.numpy() for w in small.weights()]
+    y = small.labels().numpy()
+    adj = oracle.adjacency(small.n, src.numpy(), dst.numpy())
+    t0 = time.perf_counter()
+    ogcn.forward_backward(adj, F0, Ws, y)
+    total = time.perf_counter() - t0
+    return {"value": round(total * div * 1e3, 1), "unit": unit, "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"same generator at 1/{div} of the nodes and edges (n = {small.n}, nnz = {adj.nnz}), "
+                      f"{total:.1f} s of CPU work, scaled by {div}"}
 
 
 if __name__ == "__main__":
