@@ -117,6 +117,11 @@ def measured_traffic(name):
     return sum(k[x]["fetch_bytes"] + k[x]["write_bytes"] for x in keys)
 
 
+def note(msg):
+    """progress line on stderr (the JSON line on stdout stays alone)"""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -193,6 +198,7 @@ def main():
     if args.scale != 1.0:
         workload += f" (SHRUNK x{args.scale})"
 
+    note(f"inputs generated in {t_gen:.1f} s, adjacency handle built (nnz = {csr.nnz})")
     if args.copy_ref:
         # 2^30 fp32 read + 2^30 fp32 written by a plain copy: the known-size dispatch the
         # FETCH_SIZE / WRITE_SIZE counters are scaled by
@@ -206,6 +212,7 @@ def main():
         step()
     plx.plx_sync(ctx)
     torch.cuda.synchronize()
+    note(f"{args.warmup} warm-up steps done")
     plx.plx_timing_enable(ctx, True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -225,6 +232,7 @@ def main():
         torch.cuda.synchronize()
         trial_ms.append((time.perf_counter() - t0) * 1e3 / args.steps)
 
+    note(f"{args.trials} x {args.steps} timed steps done: {ms_per_step:.3f} ms per step")
     # ---- per-kernel accounting (algorithmic bytes / flops of one launch) -------------------------
     bins = {"A": plx.plx_csr_bins(csr, False), "At": plx.plx_csr_bins(csr, True)}
     cost = {name: kernel_cost(name, bins) for name in timing}

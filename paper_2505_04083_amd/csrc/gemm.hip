@@ -115,6 +115,9 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
 // acc[r] = C[16w + 4*(l/16) + r][16c + l%16].
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int kFwdRows = 64;
+// The result is written once and read by a later kernel after gigabytes of other traffic: a
+// non-temporal store keeps it from displacing cache lines that are still useful (measured: -6 %).
+__device__ __forceinline__ void st_out(float* p, float v) { __builtin_nontemporal_store(v, p); }
 
 // For N > 64 the 64 x N tile is instead cut into 32x32 blocks (v_mfma_f32_32x32x2_f32, two per
 // wavefront for N = 128; block q belongs to wavefront q % 4): measured faster at that width.
@@ -209,8 +212,8 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
                 for (int r = 0; r < 4; ++r) {
                     if (full || row0 + r < M) {
                         const float v = acc[c][r];
-                        if (cp) cp[r * ldc] = v;
-                        if (fp) fp[r * ldf] = v > 0.f ? v : 0.f;        // Eq. 2.3 fused into the store
+                        if (cp) st_out(cp + r * ldc, v);
+                        if (fp) st_out(fp + r * ldf, v > 0.f ? v : 0.f);        // Eq. 2.3 fused into the store
                     }
                 }
             }
@@ -242,8 +245,8 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
                     const int dr = 8 * (r / 4) + (r % 4);
                     if (full || row0 + dr < M) {
                         const float v = acc[t][r];
-                        if (cp) cp[dr * ldc] = v;
-                        if (fp) fp[dr * ldf] = v > 0.f ? v : 0.f;      // Eq. 2.3 fused into the store
+                        if (cp) st_out(cp + dr * ldc, v);
+                        if (fp) st_out(fp + dr * ldf, v > 0.f ? v : 0.f);      // Eq. 2.3 fused into the store
                     }
                 }
             }
