@@ -113,8 +113,9 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
     if (tile < n_tiles) { fetch(tile); commit(a_buf(0)); }
     __syncthreads();
     for (; tile < n_tiles; tile += gridDim.x) {
-        const bool more = tile + gridDim.x < n_tiles;
-        if (more) fetch(tile + gridDim.x);
+        // unconditional prefetch (the last pass re-reads its own tile): straight-line code keeps the
+        // only wait for loads right before the LDS write
+        fetch(tile + gridDim.x < n_tiles ? tile + gridDim.x : tile);
         const bf16_t* As = a_buf(cur);
         floatx16 acc[NBLK];
 #pragma unroll
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
                                                                  acc[t], 0, 0, 0);
             }
         }
-        if (more) commit(a_buf(cur ^ 1));
+        commit(a_buf(cur ^ 1));
         const int64_t m0 = tile * ROWS;
 #pragma unroll
         for (int t = 0; t < NBLK; ++t) {
@@ -229,8 +230,7 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
     commit();
     __syncthreads();
     for (int64_t r0 = r_begin; r0 < r_end; r0 += kTR) {
-        const bool more = r0 + kTR < r_end;
-        if (more) fetch(r0 + kTR);
+        fetch(r0 + kTR < r_end ? r0 + kTR : r0);      // unconditional, as in the forward kernel
 
         floatx4 acc_o[NCB];
         if (dOut) {                                                  // Eq. 2.6: wavefront w owns rows 16w..16w+15
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
             }
         }
         __syncthreads();
-        if (more) commit();
+        commit();
         if (dOut) {
 #pragma unroll
             for (int c = 0; c < NCB; ++c) {

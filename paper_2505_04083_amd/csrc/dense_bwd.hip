@@ -8,11 +8,12 @@
 // input (combine-first order); Q is the incoming gradient (or A^T dZ).  All three tall operands
 // are streamed exactly once: the kernel is bound by that stream.
 //
-// Work split: a workgroup (4 wavefronts) owns a chunk of rows and walks it in tiles of 64 rows.
-//   dOut tile (64 x Mp): v_mfma_f32_16x16x4_f32, wavefront w owns rows 16w..16w+15, all columns;
-//       lane l supplies a = Q'[16w + l%16][k + l/16], b = W[16c + l%16][k + l/16] and receives
-//       acc[r] = dOut[16w + 4*(l/16) + r][16c + l%16].
-//   dW (Mp x N): v_mfma_f32_32x32x2_f32 over the 64 rows of the tile, accumulated in registers for
+// Work split: a workgroup (4 wavefronts) owns a chunk of rows and walks it in tiles of 32 rows.
+//   dOut tile (32 x Mp): v_mfma_f32_16x16x4_f32; a wavefront owns a few 16-column blocks of dOut and
+//       keeps the matching rows of W in registers for the whole kernel (LDS holds only the two
+//       row tiles, so several workgroups fit on a CU); lane l supplies a = Q'[row l%16][k + l/16],
+//       b = W[16c + l%16][k + l/16] and receives acc[r] = dOut[4*(l/16) + r][16c + l%16].
+//   dW (Mp x N): v_mfma_f32_32x32x2_f32 over the 32 rows of the tile, accumulated in registers for
 //       the whole chunk; block q of the (Mp/32) x (N/32) grid belongs to wavefront q % 4.
 // Chunk partials of dW are summed afterwards in a fixed order (bit-reproducible).
 #include "plx_internal.h"
@@ -78,7 +79,9 @@ __device__ __forceinline__ void commit_tile(float (*dst)[COLS + 4], const TileRe
     }
 }
 
-template <int TMB, int TNB, bool MASK, int kTR, bool VEC>   // Mp <= 32*TMB, N <= 32*TNB; kTR rows per tile (32 or 64)
+constexpr int kTR = 32;      // rows per tile
+
+template <int TMB, int TNB, bool MASK, bool VEC>   // Mp <= 32*TMB, N <= 32*TNB
 __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N, const float* __restrict__ P, int64_t ldp,
                                                        const float* __restrict__ Q, int64_t ldq,
                                                        const float* __restrict__ Zm, int64_t ldz,
@@ -89,27 +92,36 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
     // dW blocks over 4 wavefronts: NB >= 4 gives NB/4 blocks each; with NB < 4 the 4/NB wavefronts
     // sharing a block take interleaved row pairs of every tile and write separate partial tiles.
     constexpr int NB = TMB * TNB, KS = NB >= 4 ? 1 : 4 / NB, NBLK = NB >= 4 ? NB / 4 : 1;
-    constexpr int NCB = MP / 16;                   // 16-column blocks of dOut
-    // dOut tile = (kTR/16) x NCB blocks of 16x16: with 64 rows wavefront w owns row block w and all
-    // column blocks; with 32 rows it owns row block w%2 and every second column block from w/2.
-    constexpr int CPW = kTR == 64 ? NCB : NCB / 2;  // column blocks per wavefront
-    static_assert(kTR == 64 || kTR == 32, "tile rows");
+    // dOut tile = 2 x NCB blocks of 16x16.  A wavefront owns NCW column blocks (and with them NCW
+    // slices of W, kept in registers as ready-made B operands for the whole kernel) of NRW row blocks:
+    // Mp >= 64: column blocks w*NCW.., both row blocks; Mp <= 32: column block w/2 of row block w%2.
+    constexpr int NCB = MP / 16, NCW = NCB >= 4 ? NCB / 4 : 1, NRW = NCB >= 4 ? 2 : 1;
+    constexpr int NKS = NP / 4, CHUNK = 8;
     extern __shared__ __align__(16) float smem[];
     float (*Qs)[NP + 4] = reinterpret_cast<float (*)[NP + 4]>(smem);
     float (*Ps)[MP + 4] = reinterpret_cast<float (*)[MP + 4]>(smem + kTR * (NP + 4));
-    float (*Ws)[NP + 4] = reinterpret_cast<float (*)[NP + 4]>(smem + kTR * (NP + 4) + kTR * (MP + 4));
 
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lh = lane >> 5, l16 = lane & 15, lq = lane >> 4;
     const int wq = NB >= 4 ? w : w % NB, ks = NB >= 4 ? 0 : w / NB;
-    const int orb = kTR == 64 ? w : (w & 1), ocb0 = kTR == 64 ? 0 : (w >> 1), ocbs = kTR == 64 ? 1 : 2;
+    const int cb0 = NCB >= 4 ? w * NCW : (w >> 1), rb0 = NCB >= 4 ? 0 : (w & 1);
+    const int n_end = (N + 3) & ~3;
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_chunk;
     const int64_t r_end = (r_begin + rows_per_chunk < R) ? r_begin + rows_per_chunk : R;
 
-    for (int f = tid; f < MP * NP; f += 256) {
-        const int i = f / NP, n = f % NP;
-        Ws[i][n] = (i < Mp && n < N) ? W[(int64_t)i * ldw + n] : 0.f;
+    float wreg[NCW][NKS];                  // wreg[c][s] = W[16*(cb0+c) + l%16][4s + l/16]
+#pragma unroll
+    for (int c = 0; c < NCW; ++c) {
+        const int i = 16 * (cb0 + c) + l16;
+#pragma unroll
+        for (int s2 = 0; s2 < NKS; ++s2) {
+            const int n = 4 * s2 + lq;
+            wreg[c][s2] = (dOut && i < Mp && n < N) ? W[(int64_t)i * ldw + n] : 0.f;
+        }
     }
+    // the weights must have landed before the row loop: otherwise their first use inside the loop
+    // would wait for all outstanding loads, the prefetch of the next tile included
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0), other counters untouched
 
     floatx16 acc_w[NBLK];
 #pragma unroll
@@ -118,8 +130,7 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
         for (int r = 0; r < 16; ++r) acc_w[t][r] = 0.f;
 
     // Order inside an iteration: issue the next tile's global loads, run both products from LDS,
-    // barrier, write the prefetched tile to LDS, and only then issue this tile's dOut stores --
-    // so the wait for the prefetched loads never includes waiting for store acknowledgements.
+    // barrier, write the prefetched tile to LDS, and only then issue this tile's dOut stores.
     TileRegs<kTR, NP> rq, rz;
     TileRegs<kTR, MP> rp;
     fetch_tile<kTR, NP, VEC>(rq, Q, ldq, r_begin, r_end, N, tid);
@@ -130,23 +141,34 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
     __syncthreads();
 
     for (int64_t r0 = r_begin; r0 < r_end; r0 += kTR) {
-        const bool more = r0 + kTR < r_end;
-        if (more) {
-            fetch_tile<kTR, NP, VEC>(rq, Q, ldq, r0 + kTR, r_end, N, tid);
-            if (MASK) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, r0 + kTR, r_end, N, tid);
-            fetch_tile<kTR, MP, VEC>(rp, P, ldp, r0 + kTR, r_end, Mp, tid);
-        }
+        // No condition around the prefetch and its LDS write (the last pass re-reads its own tile):
+        // with straight-line code the only wait for loads sits right before the LDS write and
+        // nothing waits for the previous tile's stores to be acknowledged.
+        const int64_t rn = r0 + kTR < r_end ? r0 + kTR : r0;
+        fetch_tile<kTR, NP, VEC>(rq, Q, ldq, rn, r_end, N, tid);
+        if (MASK) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, rn, r_end, N, tid);
+        fetch_tile<kTR, MP, VEC>(rp, P, ldp, rn, r_end, Mp, tid);
 
-        floatx4 acc_o[CPW];
+        floatx4 acc_o[NRW][NCW];
         if (dOut) {                                                    // Eq. 2.6 on this tile
 #pragma unroll
-            for (int c = 0; c < CPW; ++c) acc_o[c] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-            for (int k = 0; k < NP; k += 4) {
-                const float a = Qs[16 * orb + l16][k + lq];
+            for (int rr = 0; rr < NRW; ++rr)
 #pragma unroll
-                for (int c = 0; c < CPW; ++c)
-                    acc_o[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Ws[16 * (ocb0 + ocbs * c) + l16][k + lq], acc_o[c], 0, 0, 0);
+                for (int c = 0; c < NCW; ++c) acc_o[rr][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s0 = 0; s0 < NKS; s0 += CHUNK) {
+                if (4 * s0 >= n_end) break;                            // uniform: no matrix work on padding beyond a chunk
+#pragma unroll
+                for (int s2 = s0; s2 < s0 + CHUNK; ++s2) {
+                    float a[NRW];
+#pragma unroll
+                    for (int rr = 0; rr < NRW; ++rr) a[rr] = Qs[16 * (rb0 + rr) + l16][4 * s2 + lq];
+#pragma unroll
+                    for (int rr = 0; rr < NRW; ++rr)
+#pragma unroll
+                        for (int c = 0; c < NCW; ++c)
+                            acc_o[rr][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[rr], wreg[c][s2], acc_o[rr][c], 0, 0, 0);
+                }
             }
         }
 #pragma unroll 4
@@ -159,24 +181,26 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
             }
         }
         __syncthreads();                                               // every wavefront is done reading the tile
-        if (more) {
-            commit_tile<kTR, NP, MASK>(Qs, rq, rz, tid);
-            commit_tile<kTR, MP, false>(Ps, rp, rp, tid);
-        }
+        commit_tile<kTR, NP, MASK>(Qs, rq, rz, tid);
+        commit_tile<kTR, MP, false>(Ps, rp, rp, tid);
         if (dOut) {
             const bool full = r0 + kTR <= r_end;                       // uniform: only the last tile is partial
 #pragma unroll
-            for (int c = 0; c < CPW; ++c) {
-                const int gc = 16 * (ocb0 + ocbs * c) + l16;
-                float* o = dOut + (r0 + 16 * orb + 4 * lq) * ldo + gc;
-                if (gc < Mp) {
-                    if (full) {
+            for (int rr = 0; rr < NRW; ++rr) {
+                const int64_t row0 = r0 + 16 * (rb0 + rr) + 4 * lq;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) o[r * ldo] = acc_o[c][r];
-                    } else {
+                for (int c = 0; c < NCW; ++c) {
+                    const int gc = 16 * (cb0 + c) + l16;
+                    float* o = dOut + row0 * ldo + gc;
+                    if (gc < Mp) {
+                        if (full) {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (r0 + 16 * orb + 4 * lq + r < r_end) o[r * ldo] = acc_o[c][r];
+                            for (int r = 0; r < 4; ++r) o[r * ldo] = acc_o[rr][c][r];
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                if (row0 + r < r_end) o[r * ldo] = acc_o[rr][c][r];
+                        }
                     }
                 }
             }
@@ -200,37 +224,20 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-template <int TMB, int TNB, bool MASK, int kTR>
-plx_status run_tile(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
-                    const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
-                    int64_t rpc, int64_t chunks) {
-    constexpr int MP = 32 * TMB, NP = 32 * TNB;
-    const size_t lds = sizeof(float) * (kTR * (NP + 4) + kTR * (MP + 4) + MP * (NP + 4));
-    const bool vec = aligned16(P) && ldp % 4 == 0 && Mp % 4 == 0 && aligned16(Q) && ldq % 4 == 0 && N % 4 == 0 &&
-                     (!Zm || (aligned16(Zm) && ldz % 4 == 0)) && R > 0;
-    auto launch = [&](auto kern) -> plx_status {
-        if (lds > 48 * 1024)
-            PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        kern<<<dim3((unsigned)chunks), 256, lds, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc);
-        PLX_HIP(ctx, hipGetLastError());
-        return PLX_OK;
-    };
-    return vec ? launch(k_bwd_dense_f32<TMB, TNB, MASK, kTR, true>) : launch(k_bwd_dense_f32<TMB, TNB, MASK, kTR, false>);
-}
-
-// 64-row tiles halve the per-tile overheads; 32-row tiles need less LDS.  Take 32 rows when that
-// lets more workgroups share a CU (their phases then overlap), else 64.
 template <int TMB, int TNB, bool MASK>
 plx_status run_masked(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
                       const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
                       int64_t rpc, int64_t chunks) {
     constexpr int MP = 32 * TMB, NP = 32 * TNB;
-    constexpr size_t kLdsPerCu = 160 * 1024;
-    constexpr size_t lds64 = sizeof(float) * (64 * (NP + 4) + 64 * (MP + 4) + MP * (NP + 4));
-    constexpr size_t lds32 = sizeof(float) * (32 * (NP + 4) + 32 * (MP + 4) + MP * (NP + 4));
-    if (kLdsPerCu / lds32 > kLdsPerCu / lds64)
-        return run_tile<TMB, TNB, MASK, 32>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks);
-    return run_tile<TMB, TNB, MASK, 64>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks);
+    const size_t lds = sizeof(float) * (kTR * (NP + 4) + kTR * (MP + 4));
+    const bool vec = aligned16(P) && ldp % 4 == 0 && Mp % 4 == 0 && aligned16(Q) && ldq % 4 == 0 && N % 4 == 0 &&
+                     (!Zm || (aligned16(Zm) && ldz % 4 == 0)) && R > 0;
+    auto launch = [&](auto kern) -> plx_status {
+        kern<<<dim3((unsigned)chunks), 256, lds, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc);
+        PLX_HIP(ctx, hipGetLastError());
+        return PLX_OK;
+    };
+    return vec ? launch(k_bwd_dense_f32<TMB, TNB, MASK, true>) : launch(k_bwd_dense_f32<TMB, TNB, MASK, false>);
 }
 
 template <int TMB, int TNB>

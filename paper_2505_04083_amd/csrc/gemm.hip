@@ -105,50 +105,78 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
     }
 }
 
-// ---- C[M x N] = A[M x K] * B[K x N] for K, N <= 128: weights resident in LDS, persistent row loop -----
-// The weight matrix is loaded into LDS once per workgroup; the workgroup then walks over 64-row
-// tiles of A (tile index strided by the grid), fetching the next tile into registers while the
-// matrix cores work on the current one.  Output: C and / or max(C, 0).
-// v_mfma_f32_16x16x4_f32: wavefront w owns rows 16w..16w+15 of the tile and all CB 16-column blocks
-// (N is padded to 16, not 32, and K to 4: no matrix work on padding beyond that); lane l supplies
-// a = A[16w + l%16][k + l/16], b = B[k + l/16][16c + l%16] and receives
-// acc[r] = C[16w + 4*(l/16) + r][16c + l%16].
+// ---- C[M x N] = A[M x K] * B[K x N] for K, N <= 128: persistent row loop, weights in registers ------
+// A workgroup walks over TR-row tiles of A (tile index strided by the grid).  Every wavefront keeps
+// its share of the weight matrix in registers, already in the lane layout the matrix instruction
+// wants, for the whole kernel; LDS holds only the double-buffered tile of A, so several workgroups
+// fit on a CU and their load, MFMA and store phases overlap.  The next tile is fetched into
+// registers while the matrix cores work on the current one.  Output: C and / or max(C, 0).
+//
+// N > 64 (WIDE): v_mfma_f32_32x32x2_f32; wavefront w owns the 32-column block w (N padded to 128)
+//   of every 32-row block of the tile; lane l holds b[s] = B[2s + l/32][32w + l%32].
+// N <= 64: v_mfma_f32_16x16x4_f32 (N padded to 16 only); lane l supplies a = A[row l%16][4s + l/16],
+//   b = B[4s + l/16][16c + l%16] and receives acc[r] = C[4*(l/16) + r][16c + l%16].  With 64-row
+//   tiles wavefront w owns row block w and every column block; with 32-row tiles (taken when the
+//   weight registers would not fit otherwise) row block w%2 and column blocks w/2 and w/2 + 2.
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-constexpr int kFwdRows = 64;
+
 // The result is written once and read by a later kernel after gigabytes of other traffic: a
 // non-temporal store keeps it from displacing cache lines that are still useful (measured: -6 %).
 __device__ __forceinline__ void st_out(float* p, float v) { __builtin_nontemporal_store(v, p); }
 
-// For N > 64 the 64 x N tile is instead cut into 32x32 blocks (v_mfma_f32_32x32x2_f32, two per
-// wavefront for N = 128; block q belongs to wavefront q % 4): measured faster at that width.
-template <int TKB, int CB, bool VEC>   // K <= 32*TKB, N <= 16*CB; VEC: 16-byte aligned rows, K % 4 == 0
+#ifndef PLX_FWD_WIDE_TR_K128
+#define PLX_FWD_WIDE_TR_K128 32
+#endif
+#ifndef PLX_FWD_WIDE_TR
+#define PLX_FWD_WIDE_TR 64
+#endif
+// rows per tile for a (K, N) class: 32 when 64 would need too many registers for the weights
+constexpr int fwd_tile_rows(int tkb, int cb) {
+    if (cb > 4) return tkb == 4 ? PLX_FWD_WIDE_TR_K128 : PLX_FWD_WIDE_TR;
+    return cb * (32 * tkb / 4) > 64 ? 32 : 64;
+}
+
+template <int TKB, int CB, bool VEC>   // K <= 32*TKB; N <= 16*CB (CB <= 4) or N <= 128 (CB == 8); VEC: 16-byte aligned rows, K % 4 == 0
 __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K, const float* __restrict__ A,
                                                         int64_t lda, const float* __restrict__ B, int64_t ldb,
                                                         float* __restrict__ C, int64_t ldc, float* __restrict__ F,
                                                         int64_t ldf) {
-    constexpr bool WIDE = CB > 4;                     // 32x32 blocks (N padded to 32) instead of 16x16
-    constexpr int KP = 32 * TKB, NP = WIDE ? 32 * ((CB + 1) / 2) : 16 * CB;
-    constexpr int TNB = NP / 32, NBLK = WIDE ? (2 * TNB + 3) / 4 : 1;
-    static_assert(!WIDE || (2 * TNB) % 4 == 0, "wide tiles must split evenly over 4 wavefronts");
-    constexpr int NLD = kFwdRows * KP / 4 / 256;      // float4 per thread per tile
+    constexpr bool WIDE = CB > 4;
+    constexpr int TR = fwd_tile_rows(TKB, CB);
+    constexpr int KP = 32 * TKB;
+    constexpr int NLD = TR * KP / 4 / 256;                               // float4 per thread per tile
+    constexpr int NRB = WIDE ? TR / 32 : 1;                              // row blocks per wavefront
+    constexpr int NCW = WIDE ? 1 : (TR == 64 ? CB : (CB + 1) / 2);       // column blocks per wavefront
+    constexpr int KSTEP = WIDE ? 2 : 4, NKS = KP / KSTEP, CHUNK = 8;     // k per instruction, instructions, guard granularity
+    static_assert(NLD >= 1 && NKS % CHUNK == 0, "tile shape");
     extern __shared__ __align__(16) float smem[];
     // two A buffers: the next tile is written to LDS before this tile's stores are issued
     typedef float (*ATile)[KP + 4];
-    auto a_buf = [&](int b) { return reinterpret_cast<ATile>(smem + b * kFwdRows * (KP + 4)); };
-    float (*Bs)[NP + 4] = reinterpret_cast<float (*)[NP + 4]>(smem + 2 * kFwdRows * (KP + 4));
+    auto a_buf = [&](int b) { return reinterpret_cast<ATile>(smem + b * TR * (KP + 4)); };
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, lq = lane >> 4, l32 = lane & 31, lh = lane >> 5;
-    const int k_end = (K + 3) & ~3;
+    const int k_end = (K + KSTEP - 1) / KSTEP * KSTEP;
+    const int rowblk = WIDE ? 0 : (TR == 64 ? w : (w & 1));
+    auto col_block = [&](int c) { return WIDE ? w : (TR == 64 ? c : (w >> 1) + 2 * c); };
 
-    for (int f = tid; f < KP * NP; f += 256) {
-        const int kk = f / NP, n = f % NP;
-        Bs[kk][n] = (kk < K && n < N) ? B[(int64_t)kk * ldb + n] : 0.f;
+    float breg[NCW][NKS];
+#pragma unroll
+    for (int c = 0; c < NCW; ++c) {
+        const int n = WIDE ? 32 * w + l32 : 16 * col_block(c) + l16;
+#pragma unroll
+        for (int s = 0; s < NKS; ++s) {
+            const int kk = KSTEP * s + (WIDE ? lh : lq);
+            breg[c][s] = (kk < K && n < N) ? B[(int64_t)kk * ldb + n] : 0.f;
+        }
     }
+    // The weights must have landed before the row loop starts: otherwise their first use inside the
+    // loop waits for ALL outstanding loads, the freshly issued prefetch of the next tile included.
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0), other counters untouched
 
-    const int64_t n_tiles = (M + kFwdRows - 1) / kFwdRows;
+    const int64_t n_tiles = (M + TR - 1) / TR;
     float4 reg[NLD];
     auto fetch = [&](int64_t tile) {
-        const int64_t m0 = tile * kFwdRows;
+        const int64_t m0 = tile * TR;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int f = tid + 256 * i, r = f / (KP / 4), q = f % (KP / 4);
@@ -184,27 +212,66 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
     if (tile < n_tiles) { fetch(tile); commit(a_buf(0)); }
     __syncthreads();
     for (; tile < n_tiles; tile += gridDim.x) {
+        // No condition around the prefetch and its LDS write (the last pass re-reads its own tile):
+        // with straight-line code the only wait for loads sits right before the LDS write, after the
+        // matrix work, and nothing ever waits for the previous tile's stores to be acknowledged.
         const bool more = tile + gridDim.x < n_tiles;
-        if (more) fetch(tile + gridDim.x);
+        fetch(more ? tile + gridDim.x : tile);
         ATile As = a_buf(cur);
+        const bool full = (tile + 1) * TR <= M;                         // uniform: only the last tile is partial
 
-        const bool full = (tile + 1) * kFwdRows <= M;                   // uniform: only the last tile is partial
-        if constexpr (!WIDE) {
-            floatx4 acc[CB];
+        if constexpr (WIDE) {
+            floatx16 acc[NRB];
 #pragma unroll
-            for (int c = 0; c < CB; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-            for (int kk = 0; kk < k_end; kk += 4) {
-                const float a = As[16 * w + l16][kk + lq];
+            for (int t = 0; t < NRB; ++t)
 #pragma unroll
-                for (int c = 0; c < CB; ++c)
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Bs[kk + lq][16 * c + l16], acc[c], 0, 0, 0);
+                for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+#pragma unroll
+            for (int s0 = 0; s0 < NKS; s0 += CHUNK) {
+                if (KSTEP * s0 >= k_end) break;                          // uniform: no matrix work on k-padding beyond a chunk
+#pragma unroll
+                for (int s = s0; s < s0 + CHUNK; ++s)
+#pragma unroll
+                    for (int t = 0; t < NRB; ++t) acc[t] = mfma32(As[32 * t + l32][2 * s + lh], breg[0][s], acc[t]);
             }
-            if (more) commit(a_buf(cur ^ 1));
-            const int64_t row0 = tile * kFwdRows + 16 * w + 4 * lq;
+            commit(a_buf(cur ^ 1));
+            const int gn = 32 * w + l32;
+            if (gn < N) {
 #pragma unroll
-            for (int c = 0; c < CB; ++c) {
-                const int gn = 16 * c + l16;
+                for (int t = 0; t < NRB; ++t) {
+                    const int64_t row0 = tile * TR + 32 * t + 4 * lh;
+                    float* cp = C ? C + row0 * ldc + gn : nullptr;
+                    float* fp = F ? F + row0 * ldf + gn : nullptr;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int dr = 8 * (r / 4) + (r % 4);
+                        if (full || row0 + dr < M) {
+                            const float v = acc[t][r];
+                            if (cp) st_out(cp + dr * ldc, v);
+                            if (fp) st_out(fp + dr * ldf, v > 0.f ? v : 0.f);      // Eq. 2.3 fused into the store
+                        }
+                    }
+                }
+            }
+        } else {
+            floatx4 acc[NCW];
+#pragma unroll
+            for (int c = 0; c < NCW; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s0 = 0; s0 < NKS; s0 += CHUNK) {
+                if (KSTEP * s0 >= k_end) break;
+#pragma unroll
+                for (int s = s0; s < s0 + CHUNK; ++s) {
+                    const float a = As[16 * rowblk + l16][4 * s + lq];
+#pragma unroll
+                    for (int c = 0; c < NCW; ++c) acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, breg[c][s], acc[c], 0, 0, 0);
+                }
+            }
+            commit(a_buf(cur ^ 1));
+            const int64_t row0 = tile * TR + 16 * rowblk + 4 * lq;
+#pragma unroll
+            for (int c = 0; c < NCW; ++c) {
+                const int gn = 16 * col_block(c) + l16;
                 if (gn >= N) continue;
                 float* cp = C ? C + row0 * ldc + gn : nullptr;
                 float* fp = F ? F + row0 * ldf + gn : nullptr;
@@ -213,40 +280,7 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
                     if (full || row0 + r < M) {
                         const float v = acc[c][r];
                         if (cp) st_out(cp + r * ldc, v);
-                        if (fp) st_out(fp + r * ldf, v > 0.f ? v : 0.f);        // Eq. 2.3 fused into the store
-                    }
-                }
-            }
-        } else {
-            floatx16 acc[NBLK];
-#pragma unroll
-            for (int t = 0; t < NBLK; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-#pragma unroll 4
-            for (int kk = 0; kk < k_end; kk += 2) {
-#pragma unroll
-                for (int t = 0; t < NBLK; ++t) {
-                    const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-                    acc[t] = mfma32(As[32 * bi + l32][kk + lh], Bs[kk + lh][32 * bj + l32], acc[t]);
-                }
-            }
-            if (more) commit(a_buf(cur ^ 1));
-#pragma unroll
-            for (int t = 0; t < NBLK; ++t) {
-                const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-                const int gn = 32 * bj + l32;
-                if (gn >= N) continue;
-                const int64_t row0 = tile * kFwdRows + 32 * bi + 4 * lh;
-                float* cp = C ? C + row0 * ldc + gn : nullptr;
-                float* fp = F ? F + row0 * ldf + gn : nullptr;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int dr = 8 * (r / 4) + (r % 4);
-                    if (full || row0 + dr < M) {
-                        const float v = acc[t][r];
-                        if (cp) st_out(cp + dr * ldc, v);
-                        if (fp) st_out(fp + dr * ldf, v > 0.f ? v : 0.f);      // Eq. 2.3 fused into the store
+                        if (fp) st_out(fp + r * ldf, v > 0.f ? v : 0.f);            // Eq. 2.3 fused into the store
                     }
                 }
             }
@@ -423,14 +457,17 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
         const int tkb = K <= 32 ? 1 : (K <= 64 ? 2 : 4);
         int cb = (int)ceil_div(N, 16);
         if (cb > 4) cb = 8;                    // wide tiles are 128 columns (four 32x32 column blocks)
-        const size_t lds = sizeof(float) * (2 * kFwdRows * (32 * tkb + 4) + 32 * tkb * (16 * cb + 4));
-        const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(8, (150 * 1024) / lds));
-        const int64_t blocks = std::min<int64_t>(ceil_div(M, kFwdRows), (int64_t)ctx->n_cu * per_cu);
+        const int tr = fwd_tile_rows(tkb, cb);
+        const size_t lds = sizeof(float) * 2 * tr * (32 * tkb + 4);
         const bool vec = vec_a && K % 4 == 0 && M > 0;
         auto launch_small = [&](auto kern) -> plx_status {
             if (lds > 48 * 1024)
                 PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            int per_cu = 0;                    // resident workgroups per CU for this kernel's registers and LDS
+            PLX_HIP(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds));
+            if (cb > 4) per_cu = std::min(per_cu, 3);   // measured: a 4th resident workgroup slows the store-bound K = 32 case by 5 %
+            const int64_t blocks = std::min<int64_t>(ceil_div(M, tr), (int64_t)ctx->n_cu * std::max(1, per_cu));
             kern<<<dim3((unsigned)blocks), 256, lds, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf);
             return PLX_OK;
         };
