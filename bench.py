@@ -199,14 +199,26 @@ def main():
         workload += f" (SHRUNK x{args.scale})"
 
     note(f"inputs generated in {t_gen:.1f} s, adjacency handle built (nnz = {csr.nnz})")
+    stream_ref = None
     if args.copy_ref:
         # 2^30 fp32 read + 2^30 fp32 written by a plain copy: the known-size dispatch the
-        # FETCH_SIZE / WRITE_SIZE counters are scaled by
+        # FETCH_SIZE / WRITE_SIZE counters are scaled by; its rate and a plain fill's rate are also
+        # the practical ceilings a streaming kernel can be compared with
         ref_src = torch.ones(1 << 30, dtype=torch.float32, device=dev)
         ref_dst = torch.empty_like(ref_src)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ref_dst.copy_(ref_src); ref_dst.fill_(2.0)
+        ev[0].record()
         for _ in range(3):
             ref_dst.copy_(ref_src)
+        ev[1].record()
+        for _ in range(3):
+            ref_dst.fill_(2.0)
+        ev[2].record()
         torch.cuda.synchronize()
+        gib4 = 4 * (1 << 30)
+        stream_ref = {"copy_GBps_read_plus_write": round(2 * gib4 * 3 / ev[0].elapsed_time(ev[1]) / 1e6, 1),
+                      "fill_GBps": round(gib4 * 3 / ev[1].elapsed_time(ev[2]) / 1e6, 1), "bytes_each_way": gib4}
         del ref_src, ref_dst
     for _ in range(args.warmup):
         step()
@@ -303,6 +315,8 @@ def main():
                    "min": round(min(trial_ms), 4)},
         "setup_s": {"generate": round(t_gen, 2), "csr_build_transpose_bins": round(t_build, 2)},
     }
+    if stream_ref:
+        out["stream_ref"] = stream_ref
     print(json.dumps(out))
 
 
