@@ -1,15 +1,24 @@
 // Dense products of a GCN layer with bf16 storage and fp32 accumulation (Eq. 2.2, 2.3 forward;
 // Eq. 2.4, 2.5, 2.6 fused backward), for widths up to 128.  Activations and gradients are bf16 in
-// HBM, the weight matrix is fp32 in HBM and rounded to bf16 (nearest even) when it is staged in
-// LDS, products are exact in fp32 and accumulated in fp32 by v_mfma_f32_32x32x16_bf16 /
-// v_mfma_f32_16x16x32_bf16.  At these widths the matrix work is a few percent of the time: the
-// kernels are streaming kernels bound by HBM, organised like their fp32 counterparts (persistent
-// workgroups, weights resident in LDS, next tile prefetched into registers during the MFMAs).
+// HBM, the weight matrix is fp32 in HBM and rounded to bf16 (nearest even) when a wavefront loads
+// its share into registers, products are exact in fp32 and accumulated in fp32 by
+// v_mfma_f32_32x32x16_bf16 / v_mfma_f32_16x16x32_bf16.  At these widths the matrix work is a few
+// percent of the time: the kernels are streaming kernels bound by HBM, organised like their fp32
+// counterparts (weights in registers, LDS holds only row tiles, next tile prefetched into
+// registers during the MFMAs, unconditional prefetch).
 //
 // Operand convention of both instructions: lane l supplies 8 consecutive k-values of row/column
 // (l % 32 or l % 16), the k-slab chosen by l / 32 (or l / 16).  Both operands are fed with the
 // same slab mapping, so the contraction is over all k whatever the hardware's numbering.
 // Accumulator layouts equal those of the fp32 instructions of the same tile shape.
+//
+// Where the contraction runs over the ROWS of a row-major LDS tile (dW = P^T Q'), an operand is a
+// column of the tile.  It is fetched with the LDS transpose read of gfx950 (ds_read_b64_tr_b16):
+// inside each group of 16 lanes, lane L passes the address of 4 consecutive elements of row
+// L / 4, columns 4*(L % 4).., and receives rows 0..3 of column L of that 4 x 16 block.
+//
+// Results leave through a small per-wavefront LDS staging area so that every lane stores 16
+// bytes (8 bf16) with one non-temporal store instead of eight 2-byte stores.
 #include "plx_internal.h"
 
 #include <algorithm>
@@ -19,12 +28,17 @@ namespace {
 
 typedef uint16_t bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+#define PLX_LDS __attribute__((address_space(3)))
 
 union Frag {
     uint4 u;
+    u32x4 x;
     bf16x8 v;
+    bf16x4_t h[2];
     bf16_t e[8];
 };
 
@@ -42,23 +56,35 @@ __device__ __forceinline__ bf16x8 frag_contig(const bf16_t* p) {
     f.u = *reinterpret_cast<const uint4*>(p);
     return f.v;
 }
-// 8 bf16 one row apart each (a column of a row-major tile)
-__device__ __forceinline__ bf16x8 frag_strided(const bf16_t* p, int stride) {
+
+// Column fragment of a row-major LDS tile for a 32x32x16 operand: lane l receives rows
+// k0 + 8*(l/32) .. +7 of column c0 + l%32.  Two transpose reads of 4 rows each.
+__device__ __forceinline__ bf16x8 frag_column(const bf16_t* tile, int pitch, int k0, int c0, int lane) {
+    const int L = lane & 15, half = (lane >> 4) & 1, lh = lane >> 5;
+    const bf16_t* p = tile + (k0 + 8 * lh + (L >> 2)) * pitch + c0 + 16 * half + 4 * (L & 3);
     Frag f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) f.e[i] = p[i * stride];
+    f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((PLX_LDS bf16x4_t*)(p));
+    f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((PLX_LDS bf16x4_t*)(p + 4 * pitch));
     return f.v;
 }
 
-// guarded load of 8 consecutive bf16 of a global row (zero beyond ncols / the last row)
-__device__ __forceinline__ uint4 load8(const bf16_t* __restrict__ src, int64_t ld, int64_t gr, int64_t r_end, int gc,
-                                       int ncols, bool vec) {
+// guarded load of 8 consecutive bf16 of a global row (zero beyond ncols / the last row).  With
+// vec (16-byte aligned base and leading dimension) a chunk that straddles ncols still lies inside
+// the row's pitch: it is loaded whole and the surplus elements are zeroed -- except on the very
+// last row of the matrix, where the bytes behind the last column need not exist.
+__device__ __forceinline__ uint4 load8(const bf16_t* __restrict__ src, int64_t ld, int64_t gr, int64_t r_end,
+                                       int64_t r_total, int gc, int ncols, bool vec) {
     Frag f;
     f.u = make_uint4(0, 0, 0, 0);
     if (gr < r_end && gc < ncols) {
         const bf16_t* p = src + gr * ld + gc;
-        if (vec && gc + 7 < ncols) {
+        if (vec && (gc + 7 < ncols || gr + 1 < r_total)) {
             f.u = *reinterpret_cast<const uint4*>(p);
+            if (gc + 7 >= ncols) {
+#pragma unroll
+                for (int i = 1; i < 8; ++i)
+                    if (gc + i >= ncols) f.e[i] = 0;
+            }
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
@@ -68,28 +94,74 @@ __device__ __forceinline__ uint4 load8(const bf16_t* __restrict__ src, int64_t l
     return f.u;
 }
 
+// One wavefront writes a ROWS16*16 x COLS block of results: the values go through the
+// wavefront's own staging area (row-major, pitch COLS + 8) and leave as 16-byte non-temporal
+// stores when the destination allows it (vec), else as single elements.  LDS operations of one
+// wavefront execute in order, so no barrier is needed between the two phases; the fences keep
+// the compiler from reordering them.
+template <int COLS>
+__device__ __forceinline__ void stage_store(bf16_t* stage, int nrows, bf16_t* __restrict__ dst, int64_t ld, int64_t row0,
+                                            int64_t r_end, int col0, int ncols, bool vec, int lane) {
+    constexpr int PITCH = COLS + 8, CH = COLS / 8;            // 16-byte chunks per row
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int i = lane; i < nrows * CH; i += 64) {
+        const int r = i / CH, c = 8 * (i % CH);
+        const int64_t gr = row0 + r;
+        const int gc = col0 + c;
+        if (gr >= r_end || gc >= ncols) continue;
+        Frag f;
+        f.u = *reinterpret_cast<const uint4*>(stage + r * PITCH + c);
+        bf16_t* p = dst + gr * ld + gc;
+        if (vec && gc + 7 < ncols) {
+            __builtin_nontemporal_store(f.x, reinterpret_cast<u32x4*>(p));
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (gc + e < ncols) p[e] = f.e[e];
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // ---- forward: C[M x N] = A[M x K] W[K x N] (+ ReLU copy), K, N <= 128 --------------------------------
+// Block q = w + 4t of the RB x TNB grid of 32x32 blocks belongs to wavefront w; 4 % TNB == 0, so a
+// wavefront always works on column block w % TNB and keeps that slice of W in registers.
 template <int TKB, int TNB, int RB>
 __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K, const bf16_t* __restrict__ A,
                                                          int64_t lda, const float* __restrict__ W, int64_t ldw,
                                                          bf16_t* __restrict__ C, int64_t ldc, bf16_t* __restrict__ F,
-                                                         int64_t ldf, int vec_a) {
-    constexpr int KP = 32 * TKB, NP = 32 * TNB, ROWS = 32 * RB;
-    constexpr int NBLK = RB * TNB / 4;
+                                                         int64_t ldf, int vec_a, int vec_c, int vec_f) {
+    constexpr int KP = 32 * TKB, ROWS = 32 * RB;
+    constexpr int NBLK = RB * TNB / 4, NKS = KP / 16;
     constexpr int NLD = (ROWS * KP / 8 + 255) / 256;       // 16-byte pieces per thread per tile
     constexpr int SA = KP + 8;                              // LDS row pitch in elements (16-byte multiple)
-    static_assert((RB * TNB) % 4 == 0, "tile must split evenly over 4 wavefronts");
+    static_assert((RB * TNB) % 4 == 0 && 4 % TNB == 0, "tile must split evenly over 4 wavefronts");
     extern __shared__ __align__(16) unsigned char smem_raw[];
     bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
     auto a_buf = [&](int b) { return smem + b * ROWS * SA; };
-    bf16_t* Wt = smem + 2 * ROWS * SA;                      // W transposed: Wt[n][k]
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lh = lane >> 5;
+    const int bj = w % TNB;
+    bf16_t* stage = smem + 2 * ROWS * SA + w * 32 * 40;    // per wavefront: 32 rows x (32 + 8)
 
-    for (int f = tid; f < KP * NP; f += 256) {
-        const int kk = f / NP, n = f % NP;
-        Wt[n * SA + kk] = (kk < K && n < N) ? f32_to_bf16(W[(int64_t)kk * ldw + n]) : (bf16_t)0;
+    bf16x8 breg[NKS];                                       // breg[s] = W[16s + 8*lh .. +7][32*bj + l32]
+    {
+        const int n = 32 * bj + l32;
+#pragma unroll
+        for (int s2 = 0; s2 < NKS; ++s2) {
+            Frag f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int kk = 16 * s2 + 8 * lh + e;
+                f.e[e] = (kk < K && n < N) ? f32_to_bf16(W[(int64_t)kk * ldw + n]) : (bf16_t)0;
+            }
+            breg[s2] = f.v;
+        }
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // weights landed before the row loop (vmcnt(0))
 
     const int64_t n_tiles = (M + ROWS - 1) / ROWS;
     uint4 reg[NLD];
@@ -97,7 +169,7 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int f = tid + 256 * i, r = f / (KP / 8), q = f % (KP / 8);
-            reg[i] = (f < ROWS * KP / 8) ? load8(A, lda, tile * ROWS + r, M, 8 * q, K, vec_a) : make_uint4(0, 0, 0, 0);
+            reg[i] = (f < ROWS * KP / 8) ? load8(A, lda, tile * ROWS + r, M, M, 8 * q, K, vec_a) : make_uint4(0, 0, 0, 0);
         }
     };
     auto commit = [&](bf16_t* As) {
@@ -112,6 +184,7 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
     int cur = 0;
     if (tile < n_tiles) { fetch(tile); commit(a_buf(0)); }
     __syncthreads();
+    const int k_end = (K + 15) & ~15;
     for (; tile < n_tiles; tile += gridDim.x) {
         // unconditional prefetch (the last pass re-reads its own tile): straight-line code keeps the
         // only wait for loads right before the LDS write
@@ -123,31 +196,32 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < KP; kk += 16) {
+        for (int s2 = 0; s2 < NKS; ++s2) {
+            if (16 * s2 >= k_end) break;                    // uniform
 #pragma unroll
             for (int t = 0; t < NBLK; ++t) {
-                const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_contig(As + (32 * bi + l32) * SA + kk + 8 * lh),
-                                                                 frag_contig(Wt + (32 * bj + l32) * SA + kk + 8 * lh),
-                                                                 acc[t], 0, 0, 0);
+                const int bi = (w + 4 * t) / TNB;
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_contig(As + (32 * bi + l32) * SA + 16 * s2 + 8 * lh),
+                                                                 breg[s2], acc[t], 0, 0, 0);
             }
         }
         commit(a_buf(cur ^ 1));
         const int64_t m0 = tile * ROWS;
 #pragma unroll
         for (int t = 0; t < NBLK; ++t) {
-            const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-            const int gn = 32 * bj + l32;
-            if (gn >= N) continue;
-            const int64_t row0 = m0 + 32 * bi + 4 * lh;
+            const int bi = (w + 4 * t) / TNB;
+            if (32 * bj >= N) continue;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int dr = 8 * (r / 4) + (r % 4);
-                if (row0 + dr < M) {
+            for (int pass = 0; pass < 2; ++pass) {          // plain result, then its ReLU (Eq. 2.3)
+                bf16_t* dst = pass == 0 ? C : F;
+                if (!dst) continue;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
                     const float v = acc[t][r];
-                    if (C) C[(row0 + dr) * ldc + gn] = f32_to_bf16(v);
-                    if (F) F[(row0 + dr) * ldf + gn] = f32_to_bf16(v > 0.f ? v : 0.f);   // Eq. 2.3
+                    stage[(8 * (r / 4) + 4 * lh + (r % 4)) * 40 + l32] = f32_to_bf16(pass == 0 ? v : (v > 0.f ? v : 0.f));
                 }
+                stage_store<32>(stage, 32, dst, pass == 0 ? ldc : ldf, m0 + 32 * bi, M, 32 * bj, N,
+                                pass == 0 ? vec_c : vec_f, lane);
             }
         }
         __syncthreads();
@@ -156,7 +230,10 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
 }
 
 // ---- backward: dOut = (Q*[Zm>0]) W^T, dW partial = P^T (Q*[Zm>0]) ---------------------------------------
-constexpr int kTR = 64;
+#ifndef PLX_BF16_TR
+#define PLX_BF16_TR 32
+#endif
+constexpr int kTR = PLX_BF16_TR;      // rows per tile
 
 template <int TMB, int TNB, bool MASK>
 __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N, const bf16_t* __restrict__ P,
@@ -164,25 +241,42 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
                                                         const bf16_t* __restrict__ Zm, int64_t ldz,
                                                         const float* __restrict__ W, int64_t ldw,
                                                         bf16_t* __restrict__ dOut, int64_t ldo, float* __restrict__ part,
-                                                        int64_t rows_per_chunk, int vec_p, int vec_q) {
+                                                        int64_t rows_per_chunk, int vec_p, int vec_q, int vec_o) {
     constexpr int MP = 32 * TMB, NP = 32 * TNB, SQ = NP + 8, SP = MP + 8;
     constexpr int NB = TMB * TNB, KS = NB >= 4 ? 1 : 4 / NB, NBLK = NB >= 4 ? NB / 4 : 1;
-    constexpr int NCB = MP / 16;
-    constexpr int NQ = kTR * NP / 8 / 256, NPR = (kTR * MP / 8 + 255) / 256;   // 16-byte pieces per thread
+    // dOut tile = (kTR/16) x NCB blocks of 16x16; a wavefront owns NCW column blocks (their W rows
+    // live in its registers) of NRW row blocks: Mp >= 64: column blocks w*NCW.., all row blocks;
+    // Mp <= 32: column block w/2 of row blocks w%2, w%2 + 2, ...
+    constexpr int NCB = MP / 16, NCW = NCB >= 4 ? NCB / 4 : 1, NRW = NCB >= 4 ? kTR / 16 : kTR / 32, NKS = NP / 32;
+    constexpr int NQ = (kTR * NP / 8 + 255) / 256, NPR = (kTR * MP / 8 + 255) / 256;   // 16-byte pieces per thread
+    constexpr int SO = 16 * NCW + 8;                                           // staging pitch
     extern __shared__ __align__(16) unsigned char smem_raw[];
     bf16_t* Qs = reinterpret_cast<bf16_t*>(smem_raw);
     bf16_t* Ps = Qs + kTR * SQ;
-    bf16_t* Ws = Ps + kTR * SP;                             // W as stored: Ws[i][n]
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lh = lane >> 5, l16 = lane & 15, lq = lane >> 4;
     const int wq = NB >= 4 ? w : w % NB, ks = NB >= 4 ? 0 : w / NB;
+    const int cb0 = NCB >= 4 ? w * NCW : (w >> 1), rb0 = NCB >= 4 ? 0 : (w & 1), rbs = NCB >= 4 ? 1 : 2;
+    bf16_t* stage = Ps + kTR * SP + w * 16 * SO;            // per wavefront: 16 rows x (16*NCW + 8)
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_chunk;
     const int64_t r_end = (r_begin + rows_per_chunk < R) ? r_begin + rows_per_chunk : R;
 
-    for (int f = tid; f < MP * NP; f += 256) {
-        const int i = f / NP, n = f % NP;
-        Ws[i * SQ + n] = (W && i < Mp && n < N) ? f32_to_bf16(W[(int64_t)i * ldw + n]) : (bf16_t)0;
+    bf16x8 wreg[NCW][NKS];                                  // wreg[c][s] = W[16*(cb0+c) + l16][32s + 8*lq .. +7]
+#pragma unroll
+    for (int c = 0; c < NCW; ++c) {
+        const int i = 16 * (cb0 + c) + l16;
+#pragma unroll
+        for (int s2 = 0; s2 < NKS; ++s2) {
+            Frag f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int n = 32 * s2 + 8 * lq + e;
+                f.e[e] = (W && dOut && i < Mp && n < N) ? f32_to_bf16(W[(int64_t)i * ldw + n]) : (bf16_t)0;
+            }
+            wreg[c][s2] = f.v;
+        }
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // weights landed before the row loop (vmcnt(0))
 
     floatx16 acc_w[NBLK];
 #pragma unroll
@@ -195,13 +289,14 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
 #pragma unroll
         for (int i = 0; i < NQ; ++i) {
             const int f = tid + 256 * i, r = f / (NP / 8), q = f % (NP / 8);
-            rq[i] = load8(Q, ldq, r0 + r, r_end, 8 * q, N, vec_q);
-            if (MASK) rz[i] = load8(Zm, ldz, r0 + r, r_end, 8 * q, N, vec_q);
+            const bool in = f < kTR * NP / 8;
+            rq[i] = in ? load8(Q, ldq, r0 + r, r_end, R, 8 * q, N, vec_q) : make_uint4(0, 0, 0, 0);
+            if (MASK) rz[i] = in ? load8(Zm, ldz, r0 + r, r_end, R, 8 * q, N, vec_q) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < NPR; ++i) {
             const int f = tid + 256 * i, r = f / (MP / 8), q = f % (MP / 8);
-            rp[i] = (f < kTR * MP / 8) ? load8(P, ldp, r0 + r, r_end, 8 * q, Mp, vec_p) : make_uint4(0, 0, 0, 0);
+            rp[i] = (f < kTR * MP / 8) ? load8(P, ldp, r0 + r, r_end, R, 8 * q, Mp, vec_p) : make_uint4(0, 0, 0, 0);
         }
     };
     auto commit = [&]() {
@@ -217,7 +312,7 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
                 for (int e = 0; e < 8; ++e)
                     if (!bf16_positive(z.e[e])) v.e[e] = 0;
             }
-            *reinterpret_cast<uint4*>(Qs + r * SQ + 8 * q) = v.u;
+            if (f < kTR * NP / 8) *reinterpret_cast<uint4*>(Qs + r * SQ + 8 * q) = v.u;
         }
 #pragma unroll
         for (int i = 0; i < NPR; ++i) {
@@ -229,20 +324,26 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
     fetch(r_begin);
     commit();
     __syncthreads();
+    const int n_end = (N + 31) & ~31;
     for (int64_t r0 = r_begin; r0 < r_end; r0 += kTR) {
         fetch(r0 + kTR < r_end ? r0 + kTR : r0);      // unconditional, as in the forward kernel
 
-        floatx4 acc_o[NCB];
-        if (dOut) {                                                  // Eq. 2.6: wavefront w owns rows 16w..16w+15
+        floatx4 acc_o[NRW][NCW];
+        if (dOut) {                                                  // Eq. 2.6
 #pragma unroll
-            for (int c = 0; c < NCB; ++c) acc_o[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int rr = 0; rr < NRW; ++rr)
 #pragma unroll
-            for (int k = 0; k < NP; k += 32) {
-                const bf16x8 a = frag_contig(Qs + (16 * w + l16) * SQ + k + 8 * lq);
+                for (int c = 0; c < NCW; ++c) acc_o[rr][c] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int c = 0; c < NCB; ++c)
-                    acc_o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, frag_contig(Ws + (16 * c + l16) * SQ + k + 8 * lq),
-                                                                       acc_o[c], 0, 0, 0);
+            for (int s2 = 0; s2 < NKS; ++s2) {
+                if (32 * s2 >= n_end) break;                          // uniform
+#pragma unroll
+                for (int rr = 0; rr < NRW; ++rr) {
+                    const bf16x8 a = frag_contig(Qs + (16 * (rb0 + rbs * rr) + l16) * SQ + 32 * s2 + 8 * lq);
+#pragma unroll
+                    for (int c = 0; c < NCW; ++c)
+                        acc_o[rr][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, wreg[c][s2], acc_o[rr][c], 0, 0, 0);
+                }
             }
         }
 #pragma unroll
@@ -250,24 +351,20 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
 #pragma unroll
             for (int t = 0; t < NBLK; ++t) {
                 const int q = wq + 4 * t, bi = q / TNB, bj = q % TNB;
-                acc_w[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_strided(Ps + (kk + 8 * lh) * SP + 32 * bi + l32, SP),
-                                                                   frag_strided(Qs + (kk + 8 * lh) * SQ + 32 * bj + l32, SQ),
-                                                                   acc_w[t], 0, 0, 0);
+                acc_w[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_column(Ps, SP, kk, 32 * bi, lane),
+                                                                   frag_column(Qs, SQ, kk, 32 * bj, lane), acc_w[t], 0, 0, 0);
             }
         }
         __syncthreads();
         commit();
         if (dOut) {
 #pragma unroll
-            for (int c = 0; c < NCB; ++c) {
-                const int gc = 16 * c + l16;
-                if (gc < Mp) {
+            for (int rr = 0; rr < NRW; ++rr) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int64_t gr = r0 + 16 * w + 4 * lq + r;
-                        if (gr < r_end) dOut[gr * ldo + gc] = f32_to_bf16(acc_o[c][r]);
-                    }
-                }
+                for (int c = 0; c < NCW; ++c)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) stage[(4 * lq + r) * SO + 16 * c + l16] = f32_to_bf16(acc_o[rr][c][r]);
+                stage_store<16 * NCW>(stage, 16, dOut, ldo, r0 + 16 * (rb0 + rbs * rr), r_end, 16 * cb0, Mp, vec_o, lane);
             }
         }
         __syncthreads();
@@ -301,13 +398,15 @@ plx_status run_bwd(plx_ctx* ctx, int64_t R, int Mp, int N, const bf16_t* P, int6
                    const bf16_t* Zm, int64_t ldz, const float* W, int64_t ldw, bf16_t* dOut, int64_t ldo, float* part,
                    int64_t rpc, int64_t chunks) {
     constexpr int MP = 32 * TMB, NP = 32 * TNB;
-    const size_t lds = sizeof(bf16_t) * (kTR * (NP + 8) + kTR * (MP + 8) + MP * (NP + 8));
+    constexpr int NCW = MP / 16 >= 4 ? MP / 64 : 1;
+    const size_t lds = sizeof(bf16_t) * (kTR * (NP + 8) + kTR * (MP + 8) + 4 * 16 * (16 * NCW + 8));
     const int vec_p = aligned16(P) && ldp % 8 == 0;
     const int vec_q = aligned16(Q) && ldq % 8 == 0 && (!Zm || (aligned16(Zm) && ldz % 8 == 0));
+    const int vec_o = aligned16(dOut) && ldo % 8 == 0;
     auto kern = k_bwd_dense_bf16<TMB, TNB, MASK>;
     PLX_TRY(set_lds(ctx, kern, lds));
     kern<<<dim3((unsigned)chunks), 256, lds, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc,
-                                                           vec_p, vec_q);
+                                                           vec_p, vec_q, vec_o);
     PLX_HIP(ctx, hipGetLastError());
     return PLX_OK;
 }
@@ -319,10 +418,9 @@ plx_status launch_gemm_small_bf16(plx_ctx* ctx, int64_t M, int64_t N, int64_t K,
     if (K > 128 || N > 128 || K <= 0) return fail(ctx, PLX_ERR_UNSUPPORTED, "bf16 dense products are built for widths up to 128");
     const int tkb = K <= 32 ? 1 : (K <= 64 ? 2 : 4), tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     const int rb = tnb == 1 ? 4 : 2, rows = 32 * rb;
-    const size_t lds = sizeof(bf16_t) * (2 * rows * (32 * tkb + 8) + 32 * tnb * (32 * tkb + 8));
-    const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(8, (150 * 1024) / lds));
-    const int64_t blocks = std::min<int64_t>(ceil_div(M, rows), (int64_t)ctx->n_cu * per_cu);
+    const size_t lds = sizeof(bf16_t) * (2 * rows * (32 * tkb + 8) + 4 * 32 * 40);
     const int vec_a = aligned16(A) && lda % 8 == 0;
+    const int vec_c = C && aligned16(C) && ldc % 8 == 0, vec_f = Fact && aligned16(Fact) && ldf % 8 == 0;
     char label[64];
     snprintf(label, sizeof label, "gemm_nn<bf16>[M%lld,N%lld,K%lld]", (long long)M, (long long)N, (long long)K);
     KernelTimer kt(ctx, label);
@@ -330,8 +428,12 @@ plx_status launch_gemm_small_bf16(plx_ctx* ctx, int64_t M, int64_t N, int64_t K,
     do {                                                                                                        \
         auto kern = k_gemm_small_bf16<TK, TN, RBV>;                                                             \
         PLX_TRY(set_lds(ctx, kern, lds));                                                                       \
+        int per_cu = 0;                                                                                         \
+        PLX_HIP(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds));                    \
+        const int64_t blocks = std::min<int64_t>(ceil_div(M, rows), (int64_t)ctx->n_cu * std::max(1, per_cu));  \
         kern<<<dim3((unsigned)blocks), 256, lds, ctx->stream>>>(M, (int)N, (int)K, (const bf16_t*)A, lda, W, ldw, \
-                                                               (bf16_t*)C, ldc, (bf16_t*)Fact, ldf, vec_a);     \
+                                                               (bf16_t*)C, ldc, (bf16_t*)Fact, ldf, vec_a, vec_c, \
+                                                               vec_f);                                           \
     } while (0)
     switch (tkb * 10 + tnb) {
         case 11: PLX_SMALL(1, 1, 4); break;

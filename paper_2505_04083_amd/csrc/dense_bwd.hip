@@ -31,12 +31,14 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // loads of the next tile are in flight while the matrix cores work on the current one.
 template <int TR, int COLS> struct TileRegs { float4 v[TR * COLS / 1024]; };   // TR * COLS / 4 float4 over 256 threads
 
-// VEC: rows are 16-byte aligned and ncols is a multiple of 4, so a thread's 4 columns are all valid
-// or all out of range, and rows past the end are read from the last valid row and zeroed by a
-// select -- no per-element branches on the fast path.
+// VEC: rows are 16-byte aligned (base and leading dimension), so a thread's 4 columns are one
+// 128-bit load.  Rows past the end are read from the last valid row and zeroed by a select.  When
+// ncols is not a multiple of 4 the last chunk of a row still lies inside the row's pitch: it is
+// loaded whole and the surplus elements are zeroed -- except on the very last row of the matrix,
+// where the bytes behind the last column need not exist and single loads are used.
 template <int TR, int COLS, bool VEC>
 __device__ __forceinline__ void fetch_tile(TileRegs<TR, COLS>& t, const float* __restrict__ src, int64_t ld, int64_t r0,
-                                           int64_t r_end, int ncols, int tid) {
+                                           int64_t r_end, int64_t r_total, int ncols, int tid) {
     constexpr int Q4 = COLS / 4;
 #pragma unroll
     for (int i = 0; i < TR * COLS / 1024; ++i) {
@@ -47,7 +49,20 @@ __device__ __forceinline__ void fetch_tile(TileRegs<TR, COLS>& t, const float* _
         if constexpr (VEC) {
             if (COLS == ncols || gc < ncols) {
                 const int64_t rr = gr < r_end ? gr : r_end - 1;
-                v = *reinterpret_cast<const float4*>(src + rr * ld + gc);
+                const float* p = src + rr * ld + gc;
+                const bool ragged = COLS != ncols && gc + 3 >= ncols;
+                if (!ragged || rr + 1 < r_total) {
+                    v = *reinterpret_cast<const float4*>(p);
+                    if (ragged) {
+                        if (gc + 1 >= ncols) v.y = 0.f;
+                        if (gc + 2 >= ncols) v.z = 0.f;
+                        v.w = 0.f;
+                    }
+                } else {
+                    v.x = p[0];
+                    if (gc + 1 < ncols) v.y = p[1];
+                    if (gc + 2 < ncols) v.z = p[2];
+                }
                 if (gr >= r_end) v = make_float4(0.f, 0.f, 0.f, 0.f);
             }
         } else if (gr < r_end && gc < ncols) {
@@ -133,9 +148,9 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
     // barrier, write the prefetched tile to LDS, and only then issue this tile's dOut stores.
     TileRegs<kTR, NP> rq, rz;
     TileRegs<kTR, MP> rp;
-    fetch_tile<kTR, NP, VEC>(rq, Q, ldq, r_begin, r_end, N, tid);
-    if (MASK) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, r_begin, r_end, N, tid);
-    fetch_tile<kTR, MP, VEC>(rp, P, ldp, r_begin, r_end, Mp, tid);
+    fetch_tile<kTR, NP, VEC>(rq, Q, ldq, r_begin, r_end, R, N, tid);
+    if (MASK) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, r_begin, r_end, R, N, tid);
+    fetch_tile<kTR, MP, VEC>(rp, P, ldp, r_begin, r_end, R, Mp, tid);
     commit_tile<kTR, NP, MASK>(Qs, rq, rz, tid);
     commit_tile<kTR, MP, false>(Ps, rp, rp, tid);
     __syncthreads();
@@ -145,9 +160,9 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
         // with straight-line code the only wait for loads sits right before the LDS write and
         // nothing waits for the previous tile's stores to be acknowledged.
         const int64_t rn = r0 + kTR < r_end ? r0 + kTR : r0;
-        fetch_tile<kTR, NP, VEC>(rq, Q, ldq, rn, r_end, N, tid);
-        if (MASK) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, rn, r_end, N, tid);
-        fetch_tile<kTR, MP, VEC>(rp, P, ldp, rn, r_end, Mp, tid);
+        fetch_tile<kTR, NP, VEC>(rq, Q, ldq, rn, r_end, R, N, tid);
+        if (MASK) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, rn, r_end, R, N, tid);
+        fetch_tile<kTR, MP, VEC>(rp, P, ldp, rn, r_end, R, Mp, tid);
 
         floatx4 acc_o[NRW][NCW];
         if (dOut) {                                                    // Eq. 2.6 on this tile
@@ -230,8 +245,8 @@ plx_status run_masked(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, in
                       int64_t rpc, int64_t chunks) {
     constexpr int MP = 32 * TMB, NP = 32 * TNB;
     const size_t lds = sizeof(float) * (kTR * (NP + 4) + kTR * (MP + 4));
-    const bool vec = aligned16(P) && ldp % 4 == 0 && Mp % 4 == 0 && aligned16(Q) && ldq % 4 == 0 && N % 4 == 0 &&
-                     (!Zm || (aligned16(Zm) && ldz % 4 == 0)) && R > 0;
+    const bool vec = aligned16(P) && ldp % 4 == 0 && aligned16(Q) && ldq % 4 == 0 && (!Zm || (aligned16(Zm) && ldz % 4 == 0)) &&
+                     R > 0;
     auto launch = [&](auto kern) -> plx_status {
         kern<<<dim3((unsigned)chunks), 256, lds, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc);
         PLX_HIP(ctx, hipGetLastError());

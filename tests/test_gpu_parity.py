@@ -398,6 +398,54 @@ def test_layer_backward_shapes(ctx, din, dout):
         assert rel_err(gdX, dX) <= TOL32
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("din,dout", [(100, 47), (33, 65), (128, 41)])
+def test_layer_ragged_widths_in_padded_rows(ctx, din, dout, dtype):
+    """Ragged widths stored with a padded leading dimension (what the network sequencer does): the
+    padding holds NaN, so any padding element that reaches a product or any result written outside
+    its width shows up.  Covers the whole-chunk-then-mask loads and the single-element path of the
+    matrix's last row."""
+    m, k = 777, 1111
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    code = plx.PLX_F32 if dtype == "f32" else plx.PLX_BF16
+    tol = TOL32 if dtype == "f32" else 2e-2
+    rowptr, col, val = random_block(m, k, 5 * din + dout)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(din + 3 * dout)
+
+    def padded(a, width):
+        ld = -(-width // 16) * 16
+        t = torch.full((a.shape[0], ld), float("nan"), dtype=tdt, device=DEV)
+        t[:, :width] = torch.as_tensor(a.astype(np.float32)).to(tdt).to(DEV)
+        return t, t[:, :width].double().cpu().numpy()
+
+    Xp, X64 = padded(r.standard_normal((k, din)), din)
+    W = (r.standard_normal((din, dout)) * 0.2).astype(np.float32)
+    Hagg = oracle.spmm_coo(m, row, c64, v64, X64)
+    Q = oracle.gemm(Hagg, W)
+    dF = r.standard_normal((m, dout)) * (np.abs(Q) > 2e-2 * np.abs(Q).max())     # keep clear of the mask's rounding band
+    dFp, dF64 = padded(dF, dout)
+    dQ = oracle.relu_bwd(Q, dF64)
+    dW = oracle.gemm(Hagg, dQ, ta=True)
+    dX = oracle.spmm_t_coo(k, row, c64, v64, oracle.gemm(dQ, W, tb=True))
+    for order in (plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_COMBINE_FIRST):
+        ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, dtype=code, order=order), dtype=torch.uint8, device=DEV)
+        Fp, _ = padded(np.zeros((m, dout)), dout)
+        Sp, _ = padded(np.zeros((m, din)), din)
+        gXp, _ = padded(np.zeros((k, din)), din)
+        gdW = torch.empty(din, dout, device=DEV)
+        plx.plx_gcn_layer_fwd(ctx, csr, False, Xp[:, :din], dev(W), None, Fp[:, :dout], Sp[:, :din], ws, order=order)
+        plx.plx_gcn_layer_bwd(ctx, csr, False, Xp[:, :din], dev(W), Fp[:, :dout], dFp[:, :dout], Sp[:, :din], gXp[:, :din],
+                              gdW, ws, order=order)
+        plx.plx_sync(ctx)
+        assert rel_err(Fp[:, :dout].float(), oracle.relu(Q)) <= tol
+        assert rel_err(gdW, dW) <= tol
+        assert rel_err(gXp[:, :din].float(), dX) <= tol
+        for t, wdt in ((Fp, dout), (gXp, din)):                                 # padding untouched
+            assert bool(torch.isnan(t[:, wdt:].float()).all())
+
+
 # ---------------------------------------------------------------- bf16 storage, fp32 accumulation
 TOLBF = 2e-2
 
