@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-div", type=int, default=0,
                     help="oracle sample = 1/div of the workload (0: 2 for the shard, 1 for tiny, 4 for social / copurchase, 32 for road)")
+    ap.add_argument("--graph", action="store_true",
+                    help="graph workloads only: also record the step into a HIP graph and time K replays (graph_ms_per_step)")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run plain device copies of known size (reference dispatch for counter scaling)")
     return ap.parse_args()
@@ -142,7 +144,8 @@ def main():
         cfg = cfg.scaled(args.scale)
     tdt = torch.float32 if args.dtype == "f32" else torch.bfloat16
     code = plx.PLX_F32 if args.dtype == "f32" else plx.PLX_BF16
-    ctx = plx.plx_ctx(0)
+    side = torch.cuda.Stream(device=dev) if args.graph else None      # graph capture needs a non-default stream
+    ctx = plx.plx_ctx(0, stream=side.cuda_stream) if side else plx.plx_ctx(0)
     cpu_inputs = None
 
     t0 = time.time()
@@ -245,6 +248,16 @@ def main():
         trial_ms.append((time.perf_counter() - t0) * 1e3 / args.steps)
 
     note(f"{args.trials} x {args.steps} timed steps done: {ms_per_step:.3f} ms per step")
+    graph_ms = None
+    if args.graph and cfg.kind != "shard":
+        graph = net.capture(H0, y, side)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     # ---- per-kernel accounting (algorithmic bytes / flops of one launch) -------------------------
     bins = {"A": plx.plx_csr_bins(csr, False), "At": plx.plx_csr_bins(csr, True)}
     cost = {name: kernel_cost(name, bins) for name in timing}
@@ -317,6 +330,8 @@ def main():
     }
     if stream_ref:
         out["stream_ref"] = stream_ref
+    if graph_ms is not None:
+        out["graph_ms_per_step"] = round(graph_ms, 4)
     print(json.dumps(out))
 
 

@@ -402,8 +402,11 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 
 int64_t tn_rows_per_chunk(int64_t R, int64_t M, int64_t N) {
     const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 128);
-    const int64_t want_chunks = std::max<int64_t>(1, 2048 / tiles);
-    int64_t rows = std::max<int64_t>(512, ceil_div(R, want_chunks));
+    const int64_t want_chunks = std::max<int64_t>(1, 2048 / tiles);     // measured flat between 2048 and 16384
+    // a chunk's partial tile costs a write and a read of M x N floats: chunks keep at least 512 rows
+    // unless the matrix is so short that this would leave most CUs without work
+    const int64_t min_rows = std::min<int64_t>(512, std::max<int64_t>(64, R / 1024));
+    int64_t rows = std::max<int64_t>(min_rows, ceil_div(R, want_chunks));
     return ceil_div(rows, 64) * 64;
 }
 

@@ -446,6 +446,38 @@ def test_layer_ragged_widths_in_padded_rows(ctx, din, dout, dtype):
             assert bool(torch.isnan(t[:, wdt:].float()).all())
 
 
+def test_network_step_in_hip_graph():
+    """One whole forward + backward of configs[0] recorded into a HIP graph: every replay, with
+    eager work and synchronisations in between, reproduces the eager step bit for bit (the
+    kernels are deterministic; the recorded step holds no memset node and allocates nothing)."""
+    from paper_2505_04083_amd.network import GcnNetwork
+    cfg = synth.CONFIGS["tiny"]
+    side = torch.cuda.Stream(device=DEV)
+    gctx = plx.plx_ctx(0, stream=side.cuda_stream)
+    src, dst = cfg.edges(DEV)
+    pr, pc = cfg.perms(DEV)
+    H0 = cfg.features(DEV); Ws = cfg.weights(DEV); y = cfg.labels(DEV)
+    torch.cuda.synchronize()
+    csr = plx.plx_build_csr(gctx, cfg.n, src, dst, pr, pc)
+    net = GcnNetwork(gctx, csr, Ws)
+    net.step(H0, y); net.sync()
+    want = [w.clone() for w in net.dW] + [net.dH[0].clone(), net.loss.clone()]
+    graph = net.capture(H0, y, side)
+    for rep in range(4):
+        for t in net.dW + [net.dH[0], net.loss]:
+            t.fill_(float("nan"))                                   # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = net.dW + [net.dH[0], net.loss]
+        for g, w in zip(got, want):
+            assert torch.equal(g, w), f"replay {rep} differs from the eager step"
+        if rep == 1:                                                # an eager step between replays
+            net.step(H0, y); net.sync()
+    del graph
+    csr.close(); gctx.close()
+
+
 # ---------------------------------------------------------------- bf16 storage, fp32 accumulation
 TOLBF = 2e-2
 
