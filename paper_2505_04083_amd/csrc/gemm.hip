@@ -113,7 +113,8 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
 // registers while the matrix cores work on the current one.  Output: C and / or max(C, 0).
 //
 // N > 64 (WIDE): v_mfma_f32_32x32x2_f32; wavefront w owns the 32-column block w (N padded to 128)
-//   of every 32-row block of the tile; lane l holds b[s] = B[2s + l/32][32w + l%32].
+//   of every 32-row block of the tile; lane l holds b[s] = B[k(s, l/32)][32w + l%32] with the k order
+//   chosen so that four consecutive instructions read one 128-bit piece of an A row from LDS.
 // N <= 64: v_mfma_f32_16x16x4_f32 (N padded to 16 only); lane l supplies a = A[row l%16][4s + l/16],
 //   b = B[4s + l/16][16c + l%16] and receives acc[r] = C[4*(l/16) + r][16c + l%16].  With 64-row
 //   tiles wavefront w owns row block w and every column block; with 32-row tiles (taken when the
@@ -165,7 +166,9 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
         const int n = WIDE ? 32 * w + l32 : 16 * col_block(c) + l16;
 #pragma unroll
         for (int s = 0; s < NKS; ++s) {
-            const int kk = KSTEP * s + (WIDE ? lh : lq);
+            // WIDE: instruction s of a group of four takes k = 8*(s/4) + 4*(l/32) + s%4, so that a lane's
+            // four A values of the group are one 128-bit LDS read (any order of k gives the same sum)
+            const int kk = WIDE ? 8 * (s / 4) + 4 * lh + (s % 4) : 4 * s + lq;
             breg[c][s] = (kk < K && n < N) ? B[(int64_t)kk * ldb + n] : 0.f;
         }
     }
@@ -230,9 +233,18 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
             for (int s0 = 0; s0 < NKS; s0 += CHUNK) {
                 if (KSTEP * s0 >= k_end) break;                          // uniform: no matrix work on k-padding beyond a chunk
 #pragma unroll
-                for (int s = s0; s < s0 + CHUNK; ++s)
+                for (int g = s0 / 4; g < (s0 + CHUNK) / 4; ++g) {
+                    float4 a4[NRB];
 #pragma unroll
-                    for (int t = 0; t < NRB; ++t) acc[t] = mfma32(As[32 * t + l32][2 * s + lh], breg[0][s], acc[t]);
+                    for (int t = 0; t < NRB; ++t) a4[t] = *reinterpret_cast<const float4*>(&As[32 * t + l32][8 * g + 4 * lh]);
+#pragma unroll
+                    for (int t = 0; t < NRB; ++t) {
+                        acc[t] = mfma32(a4[t].x, breg[0][4 * g + 0], acc[t]);
+                        acc[t] = mfma32(a4[t].y, breg[0][4 * g + 1], acc[t]);
+                        acc[t] = mfma32(a4[t].z, breg[0][4 * g + 2], acc[t]);
+                        acc[t] = mfma32(a4[t].w, breg[0][4 * g + 3], acc[t]);
+                    }
+                }
             }
             commit(a_buf(cur ^ 1));
             const int gn = 32 * w + l32;
