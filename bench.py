@@ -7,8 +7,8 @@ feature slice 28M x 32, weight slice 32 x 128 (fp32).  One "step" = one GCN laye
 backward over it (every row of the hot path: sparse product, dense product, activation, activation
 gradient, transposed sparse product, the two backward dense products), run in the paper's order
 (Eq. 2.1 then 2.2: aggregate at width 32, then combine).  `--workload tiny|social|copurchase|road`
-times a whole L-layer network forward + backward (with the loss head) on the other workloads of
-the benchmark spec instead.  Inputs are synthetic, seeded, generated on the GPU and resident in HBM
+times a whole L-layer network forward + backward (with the loss head) on one of the four graph
+workloads instead.  Inputs are synthetic, seeded, generated on the GPU and resident in HBM
 before the timed region.
 
 Prints ONE JSON line.  Besides the contract keys it carries

@@ -26,7 +26,7 @@ def dense_adjacency(n: int, src, dst) -> Tuple[np.ndarray, np.ndarray]:
 
 
 def permutation_matrix(perm) -> np.ndarray:
-    """P with P[perm[i], i] = 1, so (P x)[perm[i]] = x[i] ("maps original to permuted ids")."""
+    """P with P[perm[i], i] = 1, so (P x)[perm[i]] = x[i]: perm sends an original id to its new id (Sec. 5.1)."""
     perm = np.asarray(perm)
     n = perm.shape[0]
     P = np.zeros((n, n), np.float64)
