@@ -43,7 +43,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", choices=["shard", "tiny", "social", "copurchase", "road"], default="shard")
+    ap.add_argument("--workload", choices=["shard", "tiny", "social", "copurchase", "road", "shard_sparse", "road_full"],
+                    default="shard")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only; <1 is not the metric)")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
                     help="storage type of activations / gradients (the headline metric is f32)")
@@ -174,6 +175,8 @@ def main():
         cpu_inputs = (rowptr, col, val, X, W, dF)
         workload = (f"configs[3]: one GPU's 7M x 28M shard block of a billion-edge graph, {args.dtype}, "
                     "layer 32 -> 128, aggregate-first")
+        if args.workload == "shard_sparse":
+            workload = workload.replace("configs[3]:", "configs[3], secondary row with ~50 M entries:")
         unit = "ms per GCN layer fwd+bwd"
         shape = {"m": cfg.m, "k": cfg.k, "din": din, "dout": dout, "order": "agg_first"}
     else:
@@ -193,7 +196,7 @@ def main():
         def step():
             net.step(H0, y)
 
-        idx = {"tiny": 0, "social": 1, "copurchase": 2, "road": 4}[args.workload]
+        idx = {"tiny": 0, "social": 1, "copurchase": 2, "road": 4, "road_full": 4}[args.workload]
         workload = (f"configs[{idx}]: {args.workload} graph, {args.dtype}, {len(Ws)}-layer GCN "
                     + "-".join(map(str, cfg.dims)) + ", whole forward + backward with loss head, AUTO order")
         unit = f"ms per {len(Ws)}-layer network fwd+bwd"
@@ -280,7 +283,7 @@ def main():
     achieved = d_bytes / d_avg / 1e6
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(dominant) if (args.scale == 1.0 and cfg.kind == "shard") else None,
+                "traffic": measured_traffic(dominant) if (args.scale == 1.0 and args.workload == "shard" and args.dtype == "f32") else None,
                 "algorithmic_bytes_per_launch": int(d_bytes), "avg_launch_ms": round(d_avg, 4)}
     # all sparse-product kernels together, the figure the metric names
     sp = [(n, c, t) for n, (c, t) in timing.items() if n.startswith("spmm_")]
@@ -310,7 +313,7 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        div = args.cpu_sample_div or {"shard": 2, "tiny": 1, "road": 32}.get(args.workload, 4)
+        div = args.cpu_sample_div or {"shard": 2, "shard_sparse": 1, "tiny": 1, "road": 32, "road_full": 32}.get(args.workload, 4)
         if cfg.kind == "shard":
             rowptr, col, val, X, W, dF = cpu_inputs
             cpu = cpu_baseline(cfg, rowptr, col, val, X.float(), W, dF.float(), div)

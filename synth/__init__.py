@@ -359,4 +359,9 @@ CONFIGS = {
     # configs[4]: europe_osm-shaped thinned grid (Table 4 row 5)
     "road": GraphConfig("road", 5, "road", n=50_000_000, grid=(10_000, 5_000), keep_prob=0.53, long_frac=0.02,
                         dims=[64, 128, 16], n_classes=16),
+    # secondary rows: the shard block at the entry count a 1/16 x 1/4 block of a 3.2 B-entry matrix
+    # would really hold (~50 M), and the road grid with every 4-neighbour edge kept (~250 M entries)
+    "shard_sparse": GraphConfig("shard_sparse", 6, "shard", m=7_000_000, k=28_000_000, n_samples=51_000_000, dims=[32, 128]),
+    "road_full": GraphConfig("road_full", 7, "road", n=50_000_000, grid=(10_000, 5_000), keep_prob=1.0, long_frac=0.02,
+                             dims=[64, 128, 16], n_classes=16),
 }
