@@ -147,7 +147,10 @@ PLX_API plx_status plx_spmm_t(plx_ctx* ctx, const plx_csr* csr, const void* X, i
  * or Y = A^T X (transposed != 0); Y is the base of the WHOLE output matrix and rows outside the
  * block are not touched, so calling it for every block in any order gives exactly the result of
  * plx_spmm / plx_spmm_t (which keep working and walk over all blocks).
- * plx_csr_row_blocks reports the current blocking (host outputs). */
+ * plx_csr_row_blocks reports the current blocking (host outputs).
+ * Errors: PLX_ERR_INVALID for n_blocks outside 1..64 or a block index outside the current
+ * blocking (nothing is changed); if plx_csr_set_row_blocks itself fails with PLX_ERR_OOM or
+ * PLX_ERR_DEVICE the handle may be left half re-binned and must be destroyed. */
 PLX_API plx_status plx_csr_set_row_blocks(plx_ctx* ctx, plx_csr* csr, int n_blocks);
 PLX_API plx_status plx_csr_row_blocks(const plx_csr* csr, int transposed, int* n_blocks, int64_t* rows_per_block);
 PLX_API plx_status plx_spmm_block(plx_ctx* ctx, const plx_csr* csr, int transposed, int block, const void* X,

@@ -6,9 +6,10 @@
 // fp32 path: v_mfma_f32_32x32x2_f32.  Operand layout of that instruction for lane l:
 //   a = A[i = l % 32][k = l / 32],  b = B[k = l / 32][j = l % 32],
 //   acc[r] = C[i = 8*(r/4) + 4*(l/32) + r%4][j = l % 32],  r = 0..15.
-// A workgroup of 4 wavefronts owns a tile of TMB x TNB such 32x32 blocks; block q of the tile
-// (row-major) belongs to wavefront q % 4.  Tiles of the operands are staged through LDS with
-// 128-bit global loads.
+// General kernel (any K, N): a workgroup of 4 wavefronts owns a tile of TMB x TNB such 32x32
+// blocks; block q of the tile (row-major) belongs to wavefront q % 4; tiles of both operands are
+// staged through LDS with 128-bit global loads.  Layer-sized products (K, N <= 128) take the
+// persistent kernel further down, which keeps the weights in registers.
 //
 // The transposed product (reduction over the node dimension) is split over row chunks; each
 // workgroup writes its partial tile and a second kernel adds the partials in a fixed order, so
