@@ -52,6 +52,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-div", type=int, default=0,
                     help="oracle sample = 1/div of the workload (0: 2 for the shard, 1 for tiny, 4 for social / copurchase, 32 for road)")
+    ap.add_argument("--windows", type=int, default=0, help="column windows of the sparse product (0 = the library's default)")
     ap.add_argument("--graph", action="store_true",
                     help="graph workloads only: also record the step into a HIP graph and time K replays (graph_ms_per_step)")
     ap.add_argument("--copy-ref", action="store_true",
@@ -59,7 +60,7 @@ def parse():
     return ap.parse_args()
 
 
-def kernel_cost(name, bins):
+def kernel_cost(name, bins, names=()):
     """(algorithmic HBM bytes, flops) of one launch, from the sizes in the timing label.
 
     Sparse product over `rows` rows holding `entries` stored entries at width d: 8 B of CSR per
@@ -72,7 +73,10 @@ def kernel_cost(name, bins):
         s, d = (4 if dt == "f32" else 2), int(d)
         rows, ent = bins[o]
         i = {"subwave": 0, "wave": 1, "split": 2}[kind]
-        return ent[i] * (8 + s * d) + rows[i] * (4 + s * d), 2 * ent[i] * d
+        e, r = ent[i], rows[i]
+        if kind == "split" and name.replace("spmm_split", "spmm_wave") not in names:
+            e, r = e + ent[1], r + rows[1]       # column windows on: the segment kernels take every row of 256+ entries
+        return e * (8 + s * d) + r * (4 + s * d), 2 * e * d
     m = re.match(r"gemm_(nn|nt)<(f32|bf16)>\[M(\d+),N(\d+),K(\d+)\]", name)
     if m:
         s = 4 if m.group(2) == "f32" else 2
@@ -147,6 +151,8 @@ def main():
     code = plx.PLX_F32 if args.dtype == "f32" else plx.PLX_BF16
     side = torch.cuda.Stream(device=dev) if args.graph else None      # graph capture needs a non-default stream
     ctx = plx.plx_ctx(0, stream=side.cuda_stream) if side else plx.plx_ctx(0)
+    if args.windows:
+        plx.plx_ctx_set_column_windows(ctx, args.windows)
     cpu_inputs = None
 
     t0 = time.time()
@@ -263,7 +269,7 @@ def main():
         graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     # ---- per-kernel accounting (algorithmic bytes / flops of one launch) -------------------------
     bins = {"A": plx.plx_csr_bins(csr, False), "At": plx.plx_csr_bins(csr, True)}
-    cost = {name: kernel_cost(name, bins) for name in timing}
+    cost = {name: kernel_cost(name, bins, timing) for name in timing}
     kernels = {}
     for name, (count, total_ms) in timing.items():
         avg = total_ms / max(count, 1)

@@ -79,6 +79,14 @@ PLX_API plx_status plx_ctx_create(int device, void* hip_stream, plx_alloc_fn all
 PLX_API void plx_ctx_destroy(plx_ctx* ctx);
 PLX_API const char* plx_last_error(const plx_ctx* ctx);   /* host string owned by the context */
 PLX_API const char* plx_status_string(plx_status s);
+/* Column windows (a tuning knob; the default of 8 needs no call).  Rows of 256 entries and more
+ * are processed as segments cut at the boundaries of n_windows equal column ranges and launched
+ * window by window, so that the wavefronts running at any moment gather from a band of the dense
+ * operand that stays in the Infinity Cache / L2 instead of coming from HBM each time; the partial
+ * sums of a row are added in a fixed order (bit-reproducible).  1 switches the windows off (then
+ * only rows of 4096 entries and more are split).  Applies to handles built or re-blocked AFTER the
+ * call.  1 <= n_windows <= 64, else PLX_ERR_INVALID. */
+PLX_API plx_status plx_ctx_set_column_windows(plx_ctx* ctx, int n_windows);
 PLX_API plx_status plx_sync(plx_ctx* ctx);                /* wait for the context's stream */
 
 /* Optional per-kernel timing for benchmarks.  While enabled, every kernel the library

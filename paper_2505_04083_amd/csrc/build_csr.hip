@@ -186,6 +186,61 @@ __global__ void k_row_class(int64_t rows, const int64_t* rowptr, int64_t rows_pe
         if (h[c]) { atomicAdd(&hist[c], h[c]); atomicAdd(&hist_nnz[c], hn[c]); }
 }
 
+// ---- segments of the long rows ----------------------------------------------------------------------
+// first entry of [lo, hi) whose column is >= c (columns ascend inside a row)
+__device__ __forceinline__ int32_t lower_bound_col(const int32_t* __restrict__ col, int32_t lo, int32_t hi, int64_t c) {
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        if (col[mid] < c) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// entry range of long row q inside column window w
+__device__ __forceinline__ void window_range(const int32_t* __restrict__ bptr, const int32_t* __restrict__ col, int32_t slot,
+                                             int w, int n_windows, int64_t win_cols, int32_t* lo, int32_t* hi) {
+    const int32_t b0 = bptr[slot], b1 = bptr[slot + 1];
+    *lo = w == 0 ? b0 : lower_bound_col(col, b0, b1, (int64_t)w * win_cols);
+    *hi = w + 1 == n_windows ? b1 : lower_bound_col(col, b0, b1, (int64_t)(w + 1) * win_cols);
+}
+
+// cnt[q * n_windows + w] = number of segments of (long row q, window w)
+__global__ void k_seg_count(int64_t n_long, const int32_t* __restrict__ long_slot, const int32_t* __restrict__ bptr,
+                            const int32_t* __restrict__ col, int n_windows, int64_t win_cols, int32_t seg_max,
+                            int32_t* __restrict__ cnt) {
+    GRID_STRIDE(i, n_long * n_windows) {
+        const int64_t q = i / n_windows;
+        const int w = (int)(i % n_windows);
+        int32_t lo, hi;
+        window_range(bptr, col, long_slot[q], w, n_windows, win_cols, &lo, &hi);
+        cnt[i] = (hi - lo + seg_max - 1) / seg_max;
+    }
+}
+
+// segment arrays; first[i] = exclusive scan of cnt (row-major: the order partial sums are added in)
+__global__ void k_seg_fill(int64_t n_long, const int32_t* __restrict__ long_slot, const int32_t* __restrict__ row_order,
+                           const int32_t* __restrict__ bptr, const int32_t* __restrict__ col, int n_windows, int64_t win_cols,
+                           int32_t seg_max, const int32_t* __restrict__ first, int64_t rows_per_block,
+                           int32_t* __restrict__ long_row, int32_t* __restrict__ long_seg0, int64_t* __restrict__ seg_lo,
+                           int32_t* __restrict__ seg_len, uint16_t* __restrict__ key, int32_t* __restrict__ id) {
+    GRID_STRIDE(i, n_long * n_windows) {
+        const int64_t q = i / n_windows;
+        const int w = (int)(i % n_windows);
+        const int32_t slot = long_slot[q], row = row_order[slot];
+        if (w == 0) { long_row[q] = row; long_seg0[q] = first[i]; }
+        int32_t lo, hi;
+        window_range(bptr, col, slot, w, n_windows, win_cols, &lo, &hi);
+        const uint16_t k = (uint16_t)((row / rows_per_block) * n_windows + w);
+        int32_t s2 = first[i];
+        for (int32_t e = lo; e < hi; e += seg_max, ++s2) {
+            seg_lo[s2] = e;
+            seg_len[s2] = hi - e < seg_max ? hi - e : seg_max;
+            key[s2] = k;
+            id[s2] = s2;
+        }
+    }
+}
+
 // length of the row held by each slot of the binned order (slot `rows` gets 0 for the scan)
 __global__ void k_slot_len(int64_t rows, const int32_t* row_order, const int64_t* rowptr, int32_t* len) {
     GRID_STRIDE(s, rows + 1) {
@@ -267,6 +322,18 @@ plx_status transpose_orient(plx_ctx* ctx, const Orient& src, const int32_t* src_
 
 }  // namespace
 
+void segment_policy(const plx_ctx* ctx, int64_t rows, int64_t cols, int64_t nnz, int* n_windows, int* long_class, int32_t* seg_max) {
+    (void)rows; (void)nnz;
+    *seg_max = (int32_t)kSegLen;
+    if (ctx->n_windows <= 1 || cols < 2 * ctx->n_windows) {     // no windows: only the very long rows are split
+        *n_windows = 1;
+        *long_class = kLongClass;
+        return;
+    }
+    *n_windows = ctx->n_windows;
+    *long_class = kSubwaveMaxClass + 1;         // every row that is not handled by a group of lanes
+}
+
 plx_status build_bins(plx_ctx* ctx, Orient& o, int n_blocks) {
     TempPool pool(ctx);
     if (n_blocks < 1) n_blocks = 1;
@@ -333,44 +400,70 @@ plx_status build_bins(plx_ctx* ctx, Orient& o, int n_blocks) {
         }
     }
 
-    // long rows -> segments (few of them: done on the host), in binned coordinates, block by block
+    // long rows -> segments, in binned coordinates
+    segment_policy(ctx, o.rows, o.cols, o.nnz, &o.n_windows, &o.long_class, &o.seg_max);
+    const int NW = o.n_windows;
+    const int64_t win_cols = std::max<int64_t>(1, ceil_div(o.cols, NW));
     o.long0.assign(n_blocks + 1, 0);
     o.seg0b.assign(n_blocks + 1, 0);
-    std::vector<int32_t> long_rows, seg0, seg_len;
-    std::vector<int64_t> seg_lo;
+    std::vector<int32_t> long_slot_h;
     for (int b = 0; b < n_blocks; ++b) {
-        const int64_t s0 = o.off(b, kLongClass), cnt = o.off(b, kNumClasses) - s0;
-        o.long0[b] = (int64_t)long_rows.size();
-        o.seg0b[b] = (int64_t)seg_lo.size();
-        if (cnt == 0) continue;
-        std::vector<int32_t> rows(cnt), bp(cnt + 1);
-        PLX_HIP(ctx, hipMemcpy(rows.data(), o.row_order + s0, sizeof(int32_t) * cnt, hipMemcpyDeviceToHost));
-        PLX_HIP(ctx, hipMemcpy(bp.data(), o.bptr + s0, sizeof(int32_t) * (cnt + 1), hipMemcpyDeviceToHost));
-        for (int64_t q = 0; q < cnt; ++q) {
-            long_rows.push_back(rows[q]);
-            seg0.push_back((int32_t)seg_lo.size());
-            for (int64_t e = bp[q]; e < bp[q + 1]; e += kSegLen) {
-                seg_lo.push_back(e);
-                seg_len.push_back((int32_t)std::min<int64_t>(kSegLen, bp[q + 1] - e));
-            }
-        }
+        o.long0[b] = (int64_t)long_slot_h.size();
+        for (int64_t sl = o.off(b, o.long_class); sl < o.off(b, kNumClasses); ++sl) long_slot_h.push_back((int32_t)sl);
     }
-    o.long0[n_blocks] = (int64_t)long_rows.size();
-    o.seg0b[n_blocks] = (int64_t)seg_lo.size();
-    seg0.push_back((int32_t)seg_lo.size());
-    o.n_long = (int64_t)long_rows.size();
-    o.n_seg = (int64_t)seg_lo.size();
+    o.long0[n_blocks] = (int64_t)long_slot_h.size();
+    o.n_long = (int64_t)long_slot_h.size();
+    o.n_seg = 0;
     if (o.n_long > 0) {
+        if (o.n_long * NW >= (int64_t(1) << 31)) return fail(ctx, PLX_ERR_UNSUPPORTED, "too many (long row, window) pairs");
+        const int64_t pairs = o.n_long * NW;
+        int32_t* long_slot = pool.get<int32_t>(o.n_long);
+        int32_t* cnt = pool.get<int32_t>(pairs + 1);
+        int32_t* first = pool.get<int32_t>(pairs + 1);
+        if (!long_slot || !cnt || !first) return PLX_ERR_OOM;
+        PLX_HIP(ctx, hipMemcpyAsync(long_slot, long_slot_h.data(), sizeof(int32_t) * o.n_long, hipMemcpyHostToDevice, ctx->stream));
+        PLX_HIP(ctx, hipMemsetAsync(cnt + pairs, 0, sizeof(int32_t), ctx->stream));
+        k_seg_count<<<grid_for(pairs), kThreads, 0, ctx->stream>>>(o.n_long, long_slot, o.bptr, o.col, NW, win_cols, o.seg_max, cnt);
+        PLX_TRY(scan_exclusive<int32_t>(ctx, pool, cnt, first, (size_t)pairs + 1));
+        int32_t n_seg32 = 0;
+        PLX_HIP(ctx, hipMemcpyAsync(&n_seg32, first + pairs, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+        PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));      // also: long_slot_h has been read
+        o.n_seg = n_seg32;
+        const int64_t ns = std::max<int64_t>(1, o.n_seg);
         o.long_row = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * o.n_long));
         o.long_seg0 = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * (o.n_long + 1)));
-        o.seg_lo = static_cast<int64_t*>(dev_alloc(ctx, sizeof(int64_t) * o.n_seg));
-        o.seg_len = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * o.n_seg));
-        if (!o.long_row || !o.long_seg0 || !o.seg_lo || !o.seg_len) return PLX_ERR_OOM;
-        PLX_HIP(ctx, hipMemcpy(o.long_row, long_rows.data(), sizeof(int32_t) * o.n_long, hipMemcpyHostToDevice));
-        PLX_HIP(ctx, hipMemcpy(o.long_seg0, seg0.data(), sizeof(int32_t) * (o.n_long + 1), hipMemcpyHostToDevice));
-        PLX_HIP(ctx, hipMemcpy(o.seg_lo, seg_lo.data(), sizeof(int64_t) * o.n_seg, hipMemcpyHostToDevice));
-        PLX_HIP(ctx, hipMemcpy(o.seg_len, seg_len.data(), sizeof(int32_t) * o.n_seg, hipMemcpyHostToDevice));
+        o.seg_lo = static_cast<int64_t*>(dev_alloc(ctx, sizeof(int64_t) * ns));
+        o.seg_len = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * ns));
+        o.seg_launch = static_cast<int32_t*>(dev_alloc(ctx, sizeof(int32_t) * ns));
+        uint16_t* skey = pool.get<uint16_t>(ns);
+        uint16_t* skey_sorted = pool.get<uint16_t>(ns);
+        int32_t* sid = pool.get<int32_t>(ns);
+        if (!o.long_row || !o.long_seg0 || !o.seg_lo || !o.seg_len || !o.seg_launch || !skey || !skey_sorted || !sid)
+            return PLX_ERR_OOM;
+        k_seg_fill<<<grid_for(pairs), kThreads, 0, ctx->stream>>>(o.n_long, long_slot, o.row_order, o.bptr, o.col, NW, win_cols,
+                                                                   o.seg_max, first, o.rows_per_block, o.long_row, o.long_seg0,
+                                                                   o.seg_lo, o.seg_len, skey, sid);
+        PLX_HIP(ctx, hipMemcpyAsync(o.long_seg0 + o.n_long, first + pairs, sizeof(int32_t), hipMemcpyDeviceToDevice, ctx->stream));
+        if (o.n_seg > 0) {                                    // launch order: stable sort of the segment ids by (block, window)
+            const int bits = std::max(1, bit_length((uint64_t)n_blocks * NW - 1));
+            size_t bytes = 0;
+            PLX_HIP(ctx, rocprim::radix_sort_pairs(nullptr, bytes, skey, skey_sorted, sid, o.seg_launch, (size_t)o.n_seg, 0, bits,
+                                                   ctx->stream));
+            void* tmp = pool.get<char>(bytes);
+            if (!tmp) return PLX_ERR_OOM;
+            PLX_HIP(ctx, rocprim::radix_sort_pairs(tmp, bytes, skey, skey_sorted, sid, o.seg_launch, (size_t)o.n_seg, 0, bits,
+                                                   ctx->stream));
+        }
+        for (int b = 0; b <= n_blocks; ++b) {                 // first segment of every block
+            int32_t v = n_seg32;
+            if (o.long0[b] < o.n_long)
+                PLX_HIP(ctx, hipMemcpyAsync(&v, first + o.long0[b] * NW, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+            PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+            o.seg0b[b] = v;
+        }
     }
+    PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    PLX_HIP(ctx, hipGetLastError());
     return PLX_OK;
 }
 
@@ -389,6 +482,7 @@ plx_status unbin(plx_ctx* ctx, Orient& o) {
     }
     dev_free(ctx, o.row_order); dev_free(ctx, o.bptr);
     dev_free(ctx, o.long_row); dev_free(ctx, o.long_seg0); dev_free(ctx, o.seg_lo); dev_free(ctx, o.seg_len);
+    dev_free(ctx, o.seg_launch); o.seg_launch = nullptr;
     o.row_order = nullptr; o.bptr = nullptr; o.long_row = nullptr; o.long_seg0 = nullptr; o.seg_lo = nullptr; o.seg_len = nullptr;
     o.n_long = o.n_seg = 0;
     return PLX_OK;

@@ -58,6 +58,7 @@ void free_orient(plx_ctx* ctx, Orient& o) {
     dev_free(ctx, o.rowptr); dev_free(ctx, o.col); dev_free(ctx, o.val); dev_free(ctx, o.row_order);
     dev_free(ctx, o.bptr);
     dev_free(ctx, o.long_row); dev_free(ctx, o.long_seg0); dev_free(ctx, o.seg_lo); dev_free(ctx, o.seg_len);
+    dev_free(ctx, o.seg_launch);
     o = Orient();
 }
 
@@ -109,6 +110,7 @@ plx_status plx_ctx_create(int device, void* hip_stream, plx_alloc_fn alloc, plx_
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0) c->n_cu = cus;
     }
+
     *out = c;
     return PLX_OK;
 }
@@ -119,6 +121,13 @@ void plx_ctx_destroy(plx_ctx* ctx) {
     for (auto& t : ctx->timed) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
     if (ctx->scratch) dev_free(ctx, ctx->scratch);
     delete ctx;
+}
+
+plx_status plx_ctx_set_column_windows(plx_ctx* ctx, int n_windows) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (n_windows < 1 || n_windows > 64) return fail(ctx, PLX_ERR_INVALID, "n_windows must be between 1 and 64");
+    ctx->n_windows = n_windows;
+    return PLX_OK;
 }
 
 const char* plx_last_error(const plx_ctx* ctx) { return ctx ? ctx->err.c_str() : "no context"; }

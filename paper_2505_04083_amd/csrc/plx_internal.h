@@ -40,7 +40,13 @@ struct Orient {
     std::vector<int64_t> seg0b;    // host [n_blocks + 1]: first segment of block b
     int64_t off(int b, int c) const { return boff[(size_t)b * (kNumClasses + 1) + c]; }
     int tag = 0;                               // 0 = forward orientation, 1 = its transpose (timing labels)
-    // rows of class >= kLongClass, cut into segments of at most kSegLen nonzeros
+    // Rows of class >= long_class are cut into segments: at the boundaries of n_windows equal column
+    // windows, and to at most seg_max nonzeros.  Segments are numbered row by row (the order their
+    // partial sums are added in) and launched window by window (seg_launch), so that the wavefronts
+    // running at any moment gather from a narrow band of the dense operand that stays in cache.
+    int n_windows = 1, long_class = kLongClass;
+    int32_t seg_max = (int32_t)kSegLen;
+    int32_t* seg_launch = nullptr; // device [n_seg] segment ids in launch order (block, window, row)
     int64_t n_long = 0, n_seg = 0;
     int32_t* long_row = nullptr;   // device [n_long] row id
     int32_t* long_seg0 = nullptr;  // device [n_long + 1] first segment of each long row
@@ -61,6 +67,7 @@ struct plx_ctx {
     std::string err;
     void* scratch = nullptr;  // partial sums of split rows; grown on demand
     size_t scratch_bytes = 0;
+    int n_windows = 8;        // column windows for the rows handled through segments (1 = none); measured optimum 4-12
     // optional per-kernel timing (plx_timing_enable)
     struct Timed { std::string name; hipEvent_t start, stop; };
     bool timing = false;
@@ -129,6 +136,8 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // set-up: fills the binning fields of `o` from its canonical CSR arrays and re-orders the entries
 // into binned storage (waits on the stream)
 plx_status build_bins(plx_ctx* ctx, Orient& o, int n_blocks = 1);
+// column windows / segment length used by build_bins for an orientation with the given shape
+void segment_policy(const plx_ctx* ctx, int64_t rows, int64_t cols, int64_t nnz, int* n_windows, int* long_class, int32_t* seg_max);
 // undoes build_bins: entries back in canonical CSR order, binning fields released
 plx_status unbin(plx_ctx* ctx, Orient& o);
 // copies the entries of `o` back into canonical CSR order (either output may be NULL)

@@ -240,15 +240,17 @@ __global__ __launch_bounds__(256) void k_spmm_wave(const int32_t* __restrict__ r
 
 // Long rows, stage 1: one wavefront per segment, fp32 partial sums to part[seg][G*VW].
 template <typename T, int G, int VW>
-__global__ __launch_bounds__(256) void k_spmm_segment(int64_t n_seg, const int64_t* __restrict__ seg_lo,
+__global__ __launch_bounds__(256) void k_spmm_segment(int64_t n_seg, const int32_t* __restrict__ launch,
+                                                      const int64_t* __restrict__ seg_lo,
                                                       const int32_t* __restrict__ seg_len,
                                                       const int32_t* __restrict__ col, const float* __restrict__ val,
                                                       const T* __restrict__ X, int64_t ldx, float* __restrict__ part,
                                                       int d) {
     constexpr int NG = kWave / G;
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t seg = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    if (seg >= n_seg) return;
+    const int64_t pos = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (pos >= n_seg) return;
+    const int64_t seg = launch[pos];                 // launch order (column window by window) -> segment id
     const int g = lane / G, c0 = (lane % G) * VW;
     const bool active = c0 < d;
     const int64_t lo = seg_lo[seg], hi = lo + seg_len[seg];
@@ -285,7 +287,7 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t 
     hipStream_t s = ctx->stream;
     const int64_t s0 = o.off(blk, 0);                                  // first slot of this row block
     const int64_t n_sub = o.off(blk, kSubwaveMaxClass + 1) - s0;
-    const int64_t n_wave = o.off(blk, kLongClass) - s0 - n_sub;
+    const int64_t n_wave = o.off(blk, o.long_class) - s0 - n_sub;      // none when every such row goes through segments
     const int64_t n_long = o.long0[blk + 1] - o.long0[blk], l0 = o.long0[blk];
     const int64_t n_seg = o.seg0b[blk + 1] - o.seg0b[blk], g0 = o.seg0b[blk];
     constexpr int WPB = 256 / kWave;   // wavefronts per block
@@ -312,8 +314,8 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t 
         PLX_TRY(ensure_scratch(ctx, (size_t)o.n_seg * G * VW * sizeof(float)));
         float* part = static_cast<float*>(ctx->scratch);                // indexed by the global segment number
         KernelTimer kt(ctx, std::string("spmm_split") + label);
-        k_spmm_segment<T, G, VW><<<dim3((unsigned)ceil_div(n_seg, WPB)), 256, 0, s>>>(n_seg, o.seg_lo + g0, o.seg_len + g0, o.col,
-                                                                                       o.val, X, ldx, part + g0 * (G * VW), d);
+        k_spmm_segment<T, G, VW><<<dim3((unsigned)ceil_div(n_seg, WPB)), 256, 0, s>>>(n_seg, o.seg_launch + g0, o.seg_lo, o.seg_len,
+                                                                                       o.col, o.val, X, ldx, part, d);
         int64_t total = n_long * d;
         k_spmm_combine<T><<<dim3((unsigned)ceil_div(total, 256)), 256, 0, s>>>(n_long, o.long_row + l0, o.long_seg0 + l0, part,
                                                                                G * VW, out, d);
