@@ -17,6 +17,10 @@ synthetic workloads (the paper's datasets are not available).  Each prints one J
       transposed product (also width 32, as in the layer's backward pass) with the rows cut into 1, 2, 4, 8, 16, 32 blocks -- the
       one-GPU cost of issuing the aggregation as separate per-block launches, which is what a
       multi-GPU run overlaps with the per-block all-reduce.
+
+  python studies.py windows [--workload shard|social|copurchase]
+      Column windows of the sparse product: time of A X and A^T G with the rows of 256+ entries
+      cut into 1 (off), 2, 4, 8, 16, 32 column windows, at the widths the workload uses.
 """
 from __future__ import annotations
 
@@ -145,15 +149,54 @@ def blocks(args):
     print(json.dumps(out))
 
 
+def windows(args):
+    cfg = synth.CONFIGS[args.workload if args.workload in ("shard", "social", "copurchase") else "shard"]
+    ctx = plx.plx_ctx(0)
+    if cfg.kind == "shard":
+        rowptr, col, val = synth.shard_block(cfg.seed, cfg.m, cfg.k, cfg.n_samples, DEV)
+        m, k, widths = cfg.m, cfg.k, [cfg.dims[0]]
+    else:
+        src, dst = cfg.edges(DEV)
+        pr, pc = cfg.perms(DEV)
+        m = k = cfg.n
+        widths = sorted(set(min(a, b) for a, b in zip(cfg.dims[:-1], cfg.dims[1:])))    # the narrower side of every layer
+    out = {"study": "column windows of the sparse product", "workload": cfg.name, "rows": m, "cols": k, "cases": []}
+    for nw in (1, 2, 4, 8, 16, 32):
+        plx.plx_ctx_set_column_windows(ctx, nw)
+        if cfg.kind == "shard":
+            csr = plx.plx_csr_import(ctx, m, k, rowptr, col, val)
+        else:
+            csr = plx.plx_build_csr(ctx, cfg.n, src, dst, pr, pc)
+        case = {"n_windows": nw}
+        for d in widths:
+            ld = -(-d // 16) * 16                    # rows padded to 64 bytes, as the network sequencer stores them
+            X = torch.zeros(k, ld, device=DEV)[:, :d]; X.copy_(synth.normal(cfg.seed, synth.S_FEAT, k, d, DEV))
+            G = torch.zeros(m, ld, device=DEV)[:, :d]; G.copy_(synth.normal(cfg.seed, synth.S_AUX, m, d, DEV))
+            Y = torch.empty(m, ld, device=DEV)[:, :d]
+            Yt = torch.empty(k, ld, device=DEV)[:, :d]
+            case[f"AX_d{d}_ms"] = round(time_spmm(ctx, csr, X, Y), 3)
+            plx.plx_spmm_t(ctx, csr, G, Yt); plx.plx_sync(ctx)
+            t0 = time.perf_counter()
+            for _ in range(5):
+                plx.plx_spmm_t(ctx, csr, G, Yt)
+            plx.plx_sync(ctx)
+            case[f"AtG_d{d}_ms"] = round((time.perf_counter() - t0) * 1e3 / 5, 3)
+            del X, Y, G, Yt
+        out["nnz"] = csr.nnz
+        out["cases"].append(case)
+        csr.close()
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["balance", "skinny", "blocks"])
-    ap.add_argument("--workload", default="road", choices=["tiny", "social", "copurchase", "road"])
+    ap.add_argument("study", choices=["balance", "skinny", "blocks", "windows"])
+    ap.add_argument("--workload", default="road", choices=["tiny", "social", "copurchase", "road", "shard"])
     ap.add_argument("--scale", type=float, default=1.0)
     args = ap.parse_args()
     assert torch.cuda.is_available(), "studies.py needs a GPU"
     torch.cuda.set_device(DEV)
-    {"balance": balance, "skinny": skinny, "blocks": blocks}[args.study](args)
+    {"balance": balance, "skinny": skinny, "blocks": blocks, "windows": windows}[args.study](args)
 
 
 if __name__ == "__main__":
