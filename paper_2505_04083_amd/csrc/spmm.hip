@@ -6,11 +6,15 @@
 //
 //  * a dense row of d elements is covered by G = 2^ceil(log2(ceil(d / VW))) lanes, each holding
 //    VW consecutive elements (one 128-bit load when the layout allows it);
-//  * rows are binned by length class (set-up time).  Short rows: one G-lane group per row, 64/G
-//    rows per wavefront, no cross-lane traffic.  Medium rows: one wavefront per row, its 64/G
-//    groups stride over the entries and are combined by a butterfly across groups.  Long rows:
-//    cut into fixed segments, one wavefront per segment, partial sums combined in segment
-//    order by a second kernel (no floating-point atomics => bit-reproducible);
+//  * rows are binned by length class (set-up time).  Short rows (< 256 entries): one G-lane group
+//    per row, 64/G rows per wavefront, no cross-lane traffic.  Longer rows are cut into segments
+//    at the boundaries of a few equal column windows (and to a maximum length); one wavefront per
+//    segment, its 64/G groups stride over the entries and are combined by a butterfly across
+//    groups; the partial sums of a row are added in segment order by a second kernel (no
+//    floating-point atomics => bit-reproducible).  Segments are launched window by window: a
+//    row's entries are sorted by column, so the wavefronts running at any moment gather from one
+//    band of X, which is read from HBM once and then hits in the Infinity Cache / L2.  With the
+//    windows switched off, rows below 4096 entries take a wavefront-per-row kernel instead;
 //  * the entry loop is unrolled U-fold with all column/value loads issued before the U gathers,
 //    so a lane keeps U independent gathers in flight.
 #include "plx_internal.h"
