@@ -50,9 +50,15 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
-    for (int k0 = 0; k0 < K; k0 += kBK) {
+    // Slabs of kBK columns of A and rows of B go global -> registers -> LDS; the loads of the next
+    // slab are in flight while the matrix cores work on the current one (the last pass re-reads
+    // its own slab, so the loop body has no condition around the prefetch).
+    constexpr int NA = (BM * kBK / 4) / 256, NB = (kBK * BN) / 256;
+    float4 ra[NA];
+    float rb[NB];
+    auto fetch = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < (BM * kBK / 4) / 256; ++i) {
+        for (int i = 0; i < NA; ++i) {
             const int f = tid + 256 * i, r = f >> 3, q = f & 7;
             const int64_t gr = m0 + r;
             const int gk = k0 + 4 * q;
@@ -68,17 +74,38 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
                     if (gk + 3 < K) v.w = p[3];
                 }
             }
-            As[r][4 * q + 0] = v.x; As[r][4 * q + 1] = v.y; As[r][4 * q + 2] = v.z; As[r][4 * q + 3] = v.w;
+            ra[i] = v;
         }
-        for (int f = tid; f < kBK * BN; f += 256) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int f = tid + 256 * i;
             int kk, n;
             if (BT) { n = f / kBK; kk = f % kBK; } else { kk = f / BN; n = f % BN; }
             const int gk = k0 + kk, gn = n0 + n;
             float v = 0.f;
             if (gk < K && gn < N) v = BT ? B[(int64_t)gn * ldb + gk] : B[(int64_t)gk * ldb + gn];
-            Bs[kk][n] = v;
+            rb[i] = v;
         }
-        __syncthreads();
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int f = tid + 256 * i, r = f >> 3, q = f & 7;
+            As[r][4 * q + 0] = ra[i].x; As[r][4 * q + 1] = ra[i].y; As[r][4 * q + 2] = ra[i].z; As[r][4 * q + 3] = ra[i].w;
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int f = tid + 256 * i;
+            int kk, n;
+            if (BT) { n = f / kBK; kk = f % kBK; } else { kk = f / BN; n = f % BN; }
+            Bs[kk][n] = rb[i];
+        }
+    };
+    fetch(0);
+    commit();
+    __syncthreads();
+    for (int k0 = 0; k0 < K; k0 += kBK) {
+        fetch(k0 + kBK < K ? k0 + kBK : k0);
 #pragma unroll 4
         for (int kk = 0; kk < kBK; kk += 2) {
 #pragma unroll
@@ -87,6 +114,8 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
                 acc[t] = mfma32(As[32 * bi + l32][kk + lh], Bs[kk + lh][32 * bj + l32], acc[t]);
             }
         }
+        __syncthreads();                           // every wavefront is done with the slab
+        commit();
         __syncthreads();
     }
 #pragma unroll
