@@ -128,10 +128,12 @@ PLX_API plx_status plx_csr_dims(const plx_csr* csr, int64_t* m, int64_t* k, int6
 PLX_API plx_status plx_csr_export(plx_ctx* ctx, const plx_csr* csr, int transposed, int64_t* rowptr,
                                   int32_t* col, float* val, int64_t* deg);
 
-/* Row-binning summary of one orientation (host outputs, each int64[3] or NULL): the number
- * of rows, and of stored entries in those rows, that the sparse kernels handle [0] with a
- * group of lanes per row, [1] with a whole wavefront per row, [2] split over several
- * wavefronts.  For inspection, tests and the byte accounting of a benchmark. */
+/* Row-length summary of one orientation (host outputs, each int64[3] or NULL): the number of
+ * rows, and of stored entries in those rows, with [0] fewer than 256, [1] 256..4095, [2] 4096 or
+ * more entries.  Rows of bin [0] are handled by a group of lanes each; with column windows on
+ * (the default) bins [1] and [2] go through the segment kernels, with the windows off bin [1]
+ * takes one wavefront per row and only bin [2] is split.  For inspection, tests and the byte
+ * accounting of a benchmark. */
 PLX_API plx_status plx_csr_bins(const plx_csr* csr, int transposed, int64_t* rows, int64_t* entries);
 
 PLX_API void plx_csr_destroy(plx_ctx* ctx, plx_csr* csr);

@@ -16,8 +16,8 @@ namespace plx {
 constexpr int kWave = 64;            // gfx950 wavefront width
 constexpr int kNumClasses = 34;      // row-length classes: 0 = empty, c = 1 + floor(log2 len)
 constexpr int kSubwaveMaxClass = 8;  // rows shorter than 2^8 are handled by a group of lanes
-constexpr int kLongClass = 13;       // rows with len >= 2^12 are split into segments
-constexpr int64_t kSegLen = 2048;    // nonzeros per segment of a split row
+constexpr int kLongClass = 13;       // without column windows only rows with len >= 2^12 are split into segments
+constexpr int64_t kSegLen = 2048;    // most nonzeros a segment may hold
 
 // One stored orientation of the adjacency (CSR) plus its row binning.
 struct Orient {

@@ -93,3 +93,10 @@ def test_dense_and_elementwise_argument_checks(dry):
     assert L.plx_gcn_layer_fwd(h, None, 0, p, 4, p, 4, 4, 4, 0, 1, 0, p, 4, None, 0, None, 0, None, 0) == plx.PLX_ERR_INVALID
     assert L.plx_gcn_layer_workspace(None, 0, 4, 4, 0, 1, 0) == 0
     assert L.plx_csr_dims(None, None, None, None) == plx.PLX_ERR_INVALID
+    # tuning knob and blocked aggregation: argument rules hold without a device
+    assert L.plx_ctx_set_column_windows(h, 0) == plx.PLX_ERR_INVALID
+    assert L.plx_ctx_set_column_windows(h, 65) == plx.PLX_ERR_INVALID
+    assert L.plx_ctx_set_column_windows(h, 8) == plx.PLX_OK
+    assert L.plx_ctx_set_column_windows(None, 8) == plx.PLX_ERR_INVALID
+    assert L.plx_csr_set_row_blocks(h, None, 4) == plx.PLX_ERR_INVALID
+    assert L.plx_spmm_block(h, None, 0, 0, p, 4, p, 4, 4, 0) == plx.PLX_ERR_INVALID
