@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-div", type=int, default=0,
                     help="oracle sample = 1/div of the workload (0: 2 for the shard, 1 for tiny, 4 for social / copurchase, 32 for road)")
+    ap.add_argument("--mask", choices=["bits", "values"], default="bits",
+                    help="what the backward pass reads for the ReLU derivative: one sign bit per element written by the "
+                         "forward pass, or the activated output itself")
     ap.add_argument("--windows", type=int, default=0, help="column windows of the sparse product (0 = the library's default)")
     ap.add_argument("--graph", action="store_true",
                     help="graph workloads only: also record the step into a HIP graph and time K replays (graph_ms_per_step)")
@@ -88,10 +91,11 @@ def kernel_cost(name, bins, names=()):
         R, M, N = map(int, m.groups()[1:])
         return s * R * (M + N) + 4 * M * N, 2 * R * M * N
     m = re.match(r"bwd_dense<(f32|bf16)>\[R(\d+),M(\d+),N(\d+)\]", name)
-    if m:       # reads the gradient, the mask source and P; writes dOut; two products
+    if m:       # reads the gradient, the mask source (values, or one bit per element) and P; writes dOut; two products
         s = 4 if m.group(1) == "f32" else 2
         R, M, N = map(int, m.groups()[1:])
-        return s * R * (2 * N + 2 * M) + 4 * M * N, 4 * R * M * N
+        mask = 4 * R * ((N + 31) // 32) if name.endswith("bits") else s * R * N
+        return s * R * (N + 2 * M) + mask + 4 * M * N, 4 * R * M * N
     m = re.match(r"(relu|relu_bwd|softmax_ce)\[R(\d+),C(\d+)\]", name)
     if m:
         R, C = int(m.group(2)), int(m.group(3))
@@ -170,13 +174,15 @@ def main():
         order = plx.PLX_ORDER_AGG_FIRST
         ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, code, plx.PLX_ACT_RELU, order),
                          dtype=torch.uint8, device=dev)
-        F = torch.empty(cfg.m, dout, device=dev, dtype=tdt)   # only the activated output is stored (its sign serves Eq. 2.4)
+        F = torch.empty(cfg.m, dout, device=dev, dtype=tdt)   # the activated output, and its sign as one bit per element (Eq. 2.4)
+        act = plx.PLX_ACT_RELU if args.mask == "values" else plx.PLX_ACT_RELU_BITS
+        Zm = F if args.mask == "values" else torch.empty(cfg.m, (dout + 31) // 32, device=dev, dtype=torch.int32)
         saved = torch.empty(cfg.m, din, device=dev, dtype=tdt)
         dX = torch.empty(cfg.k, din, device=dev, dtype=tdt); dW = torch.empty(din, dout, device=dev)
 
         def step():
-            plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, None, F, saved, ws, act=plx.PLX_ACT_RELU, order=order)
-            plx.plx_gcn_layer_bwd(ctx, csr, False, X, W, F, dF, saved, dX, dW, ws, act=plx.PLX_ACT_RELU, order=order)
+            plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, None if args.mask == "values" else Zm, F, saved, ws, act=act, order=order)
+            plx.plx_gcn_layer_bwd(ctx, csr, False, X, W, Zm, dF, saved, dX, dW, ws, act=act, order=order)
 
         cpu_inputs = (rowptr, col, val, X, W, dF)
         workload = (f"configs[3]: one GPU's 7M x 28M shard block of a billion-edge graph, {args.dtype}, "
@@ -197,7 +203,7 @@ def main():
         H0 = synth.normal(cfg.seed, synth.S_FEAT, cfg.n, cfg.dims[0], dev, tdt)       # random rows: any order is P_c order
         Ws = cfg.weights(dev)
         y = cfg.labels(dev)
-        net = GcnNetwork(ctx, csr, Ws, dtype=tdt)
+        net = GcnNetwork(ctx, csr, Ws, dtype=tdt, sign_bits=args.mask == "bits")
 
         def step():
             net.step(H0, y)

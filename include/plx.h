@@ -57,7 +57,7 @@ typedef enum {
 } plx_status;
 
 typedef enum { PLX_F32 = 0, PLX_BF16 = 1 } plx_dtype;
-typedef enum { PLX_ACT_NONE = 0, PLX_ACT_RELU = 1 } plx_act;
+typedef enum { PLX_ACT_NONE = 0, PLX_ACT_RELU = 1, PLX_ACT_RELU_BITS = 2 } plx_act;
 typedef enum {
     PLX_ORDER_COMBINE_FIRST = 0, /* Z = A^ (H W): the sparse product runs at the output width    */
     PLX_ORDER_AGG_FIRST = 1,     /* Z = (A^ H) W: the order of Eq. 2.1 -> 2.2                      */
@@ -211,6 +211,12 @@ PLX_API plx_status plx_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void
  *   order COMBINE_FIRST: T[ka x dout] = H W in the workspace, then Z = A T; `saved` is unused.
  *   order AUTO      : AGG_FIRST if din < dout, else COMBINE_FIRST (so `saved` must be given
  *                     whenever din < dout).
+ *   act RELU_BITS   : as RELU, but all the backward call needs of Z is kept, one bit per element: Z
+ *                     (4-byte aligned, both Z and F required) receives uint32 words, ldz counts
+ *                     words per row (>= ceil(dout / 32)); bit j % 32 of word j / 32 of row i is
+ *                     [F[i][j] > 0], bits of columns >= dout inside the last word are 0.  The
+ *                     backward call with act RELU_BITS reads the same words through `Z`, 1/32 of
+ *                     the bytes of the value matrix.
  * plx_gcn_layer_bwd:  given dF (gradient wrt F, or wrt Z when act == NONE) computes
  *   dZ = dF * [Z > 0] (Eq. 2.4; `Z` may be the pre-activation or the ReLU output, only its sign is
  *   used; ignored when act == NONE), dW[din x dout] (fp32, Eq. 2.5) and, unless dH == NULL,

@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libplx.so")
 
 PLX_OK, PLX_ERR_INVALID, PLX_ERR_SHAPE, PLX_ERR_UNSUPPORTED, PLX_ERR_OOM, PLX_ERR_DEVICE, PLX_ERR_INTERNAL = range(7)
 PLX_F32, PLX_BF16 = 0, 1
-PLX_ACT_NONE, PLX_ACT_RELU = 0, 1
+PLX_ACT_NONE, PLX_ACT_RELU, PLX_ACT_RELU_BITS = 0, 1, 2
 PLX_ORDER_COMBINE_FIRST, PLX_ORDER_AGG_FIRST, PLX_ORDER_AUTO = 0, 1, 2
 
 EXPORTED = [

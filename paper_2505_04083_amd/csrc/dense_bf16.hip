@@ -133,7 +133,8 @@ template <int TKB, int TNB, int RB>
 __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K, const bf16_t* __restrict__ A,
                                                          int64_t lda, const float* __restrict__ W, int64_t ldw,
                                                          bf16_t* __restrict__ C, int64_t ldc, bf16_t* __restrict__ F,
-                                                         int64_t ldf, int vec_a, int vec_c, int vec_f) {
+                                                         int64_t ldf, uint32_t* __restrict__ bits, int64_t ldbits, int vec_a,
+                                                         int vec_c, int vec_f, int bits_vec) {
     constexpr int KP = 32 * TKB, ROWS = 32 * RB;
     constexpr int NBLK = RB * TNB / 4, NKS = KP / 16;
     constexpr int NLD = (ROWS * KP / 8 + 255) / 256;       // 16-byte pieces per thread per tile
@@ -146,6 +147,9 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
     const int l32 = lane & 31, lh = lane >> 5;
     const int bj = w % TNB;
     bf16_t* stage = smem + 2 * ROWS * SA + w * 32 * 40;    // per wavefront: 32 rows x (32 + 8)
+    // sign bits of a tile (only when bits != NULL): two buffers [word][row]; the wavefronts drop their
+    // ballots here and the words leave one tile later as one store per row
+    uint32_t* sb = reinterpret_cast<uint32_t*>(smem + 2 * ROWS * SA + 4 * 32 * 40);
 
     bf16x8 breg[NKS];                                       // breg[s] = W[16s + 8*lh .. +7][32*bj + l32]
     {
@@ -180,7 +184,25 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
         }
     };
 
-    int64_t tile = blockIdx.x;
+    const int nw = (N + 31) >> 5;
+    auto flush_bits = [&](int buf, int64_t t) {             // words of tile t, written by the pass before
+        const int64_t row = t * ROWS + tid;
+        if (tid < ROWS && row < M) {
+            uint32_t wds[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wds[j] = j < TNB ? sb[(buf * 4 + j) * ROWS + tid] : 0u;
+            uint32_t* dst = bits + row * ldbits;
+            if (bits_vec == 4) *reinterpret_cast<uint4*>(dst) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+            else if (bits_vec == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(wds[0], wds[1]);
+            else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (j < nw) dst[j] = wds[j];
+            }
+        }
+    };
+
+    int64_t tile = blockIdx.x, prev = -1;
     int cur = 0;
     if (tile < n_tiles) { fetch(tile); commit(a_buf(0)); }
     __syncthreads();
@@ -189,6 +211,8 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
         // unconditional prefetch (the last pass re-reads its own tile): straight-line code keeps the
         // only wait for loads right before the LDS write
         fetch(tile + gridDim.x < n_tiles ? tile + gridDim.x : tile);
+        if (bits && prev >= 0) flush_bits(cur ^ 1, prev);
+        prev = tile;
         const bf16_t* As = a_buf(cur);
         floatx16 acc[NBLK];
 #pragma unroll
@@ -223,10 +247,24 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
                 stage_store<32>(stage, 32, dst, pass == 0 ? ldc : ldf, m0 + 32 * bi, M, 32 * bj, N,
                                 pass == 0 ? vec_c : vec_f, lane);
             }
+            if (bits) {        // sign of the rounded result; one ballot = 32 columns of two rows (lanes 0-31, lanes 32-63)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    uint32_t wv[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const unsigned long long b = __ballot(bf16_positive(f32_to_bf16(acc[t][4 * g + j])));
+                        wv[j] = lh ? (uint32_t)(b >> 32) : (uint32_t)b;
+                    }
+                    if (l32 == 0)
+                        *reinterpret_cast<uint4*>(&sb[(cur * 4 + bj) * ROWS + 32 * bi + 8 * g + 4 * lh]) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
+                }
+            }
         }
         __syncthreads();
         cur ^= 1;
     }
+    if (bits && prev >= 0) flush_bits(cur ^ 1, prev);       // the last pass ended with a barrier
 }
 
 // ---- backward: dOut = (Q*[Zm>0]) W^T, dW partial = P^T (Q*[Zm>0]) ---------------------------------------
@@ -235,7 +273,7 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
 #endif
 constexpr int kTR = PLX_BF16_TR;      // rows per tile
 
-template <int TMB, int TNB, bool MASK>
+template <int TMB, int TNB, int MASK>   // MASK: 0 none, 1 Zm holds values, 2 Zm holds sign bits (ldz in words)
 __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N, const bf16_t* __restrict__ P,
                                                         int64_t ldp, const bf16_t* __restrict__ Q, int64_t ldq,
                                                         const bf16_t* __restrict__ Zm, int64_t ldz,
@@ -285,18 +323,31 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
         for (int r = 0; r < 16; ++r) acc_w[t][r] = 0.f;
 
     uint4 rq[NQ], rz[NQ], rp[NPR];
+    // MASK == 2: piece i of thread tid (8 columns) lies in word tid / 4 + 64 i of the tile's 32 * NP / 32
+    // words; lane l < 16 * NQ loads word 16 * wavefront + l % 16 + 64 * (l / 16), and at commit time
+    // piece i takes its word from lane l / 4 + 16 i and its byte at bit 8 * (tid % 4)
+    static_assert(MASK != 2 || kTR == 32, "word numbering assumes 32-row tiles");
+    uint32_t zb = 0;
+    const uint32_t* Zbits = reinterpret_cast<const uint32_t*>(Zm);
     auto fetch = [&](int64_t r0) {
 #pragma unroll
         for (int i = 0; i < NQ; ++i) {
             const int f = tid + 256 * i, r = f / (NP / 8), q = f % (NP / 8);
             const bool in = f < kTR * NP / 8;
             rq[i] = in ? load8(Q, ldq, r0 + r, r_end, R, 8 * q, N, vec_q) : make_uint4(0, 0, 0, 0);
-            if (MASK) rz[i] = in ? load8(Zm, ldz, r0 + r, r_end, R, 8 * q, N, vec_q) : make_uint4(0, 0, 0, 0);
+            if (MASK == 1) rz[i] = in ? load8(Zm, ldz, r0 + r, r_end, R, 8 * q, N, vec_q) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < NPR; ++i) {
             const int f = tid + 256 * i, r = f / (MP / 8), q = f % (MP / 8);
             rp[i] = (f < kTR * MP / 8) ? load8(P, ldp, r0 + r, r_end, R, 8 * q, Mp, vec_p) : make_uint4(0, 0, 0, 0);
+        }
+        if (MASK == 2) {
+            constexpr int WPR = NP / 32;
+            const int wi = 16 * w + (lane & 15) + 64 * (lane >> 4);
+            const int64_t gr = r0 + wi / WPR;
+            const int cw = wi % WPR;
+            zb = (lane < 16 * NQ && wi < 32 * WPR && gr < r_end && 32 * cw < N) ? Zbits[gr * ldz + cw] : 0u;
         }
     };
     auto commit = [&]() {
@@ -305,12 +356,17 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
             const int f = tid + 256 * i, r = f / (NP / 8), q = f % (NP / 8);
             Frag v;
             v.u = rq[i];
-            if (MASK) {                                              // Eq. 2.4
+            if (MASK == 1) {                                         // Eq. 2.4
                 Frag z;
                 z.u = rz[i];
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     if (!bf16_positive(z.e[e])) v.e[e] = 0;
+            } else if (MASK == 2) {
+                const uint32_t b = __shfl(zb, (lane >> 2) + 16 * i) >> (8 * (tid & 3));
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (!(b >> e & 1u)) v.e[e] = 0;
             }
             if (f < kTR * NP / 8) *reinterpret_cast<uint4*>(Qs + r * SQ + 8 * q) = v.u;
         }
@@ -393,7 +449,7 @@ plx_status set_lds(plx_ctx* ctx, Kern kern, size_t lds) {
     return PLX_OK;
 }
 
-template <int TMB, int TNB, bool MASK>
+template <int TMB, int TNB, int MASK>
 plx_status run_bwd(plx_ctx* ctx, int64_t R, int Mp, int N, const bf16_t* P, int64_t ldp, const bf16_t* Q, int64_t ldq,
                    const bf16_t* Zm, int64_t ldz, const float* W, int64_t ldw, bf16_t* dOut, int64_t ldo, float* part,
                    int64_t rpc, int64_t chunks) {
@@ -401,7 +457,7 @@ plx_status run_bwd(plx_ctx* ctx, int64_t R, int Mp, int N, const bf16_t* P, int6
     constexpr int NCW = MP / 16 >= 4 ? MP / 64 : 1;
     const size_t lds = sizeof(bf16_t) * (kTR * (NP + 8) + kTR * (MP + 8) + 4 * 16 * (16 * NCW + 8));
     const int vec_p = aligned16(P) && ldp % 8 == 0;
-    const int vec_q = aligned16(Q) && ldq % 8 == 0 && (!Zm || (aligned16(Zm) && ldz % 8 == 0));
+    const int vec_q = aligned16(Q) && ldq % 8 == 0 && (MASK != 1 || (aligned16(Zm) && ldz % 8 == 0));
     const int vec_o = aligned16(dOut) && ldo % 8 == 0;
     auto kern = k_bwd_dense_bf16<TMB, TNB, MASK>;
     PLX_TRY(set_lds(ctx, kern, lds));
@@ -414,11 +470,15 @@ plx_status run_bwd(plx_ctx* ctx, int64_t R, int Mp, int N, const bf16_t* P, int6
 }  // namespace
 
 plx_status launch_gemm_small_bf16(plx_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
-                                  const float* W, int64_t ldw, void* C, int64_t ldc, void* Fact, int64_t ldf) {
+                                  const float* W, int64_t ldw, void* C, int64_t ldc, void* Fact, int64_t ldf,
+                                  uint32_t* bits, int64_t ldbits) {
     if (K > 128 || N > 128 || K <= 0) return fail(ctx, PLX_ERR_UNSUPPORTED, "bf16 dense products are built for widths up to 128");
     const int tkb = K <= 32 ? 1 : (K <= 64 ? 2 : 4), tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     const int rb = tnb == 1 ? 4 : 2, rows = 32 * rb;
-    const size_t lds = sizeof(bf16_t) * (2 * rows * (32 * tkb + 8) + 4 * 32 * 40);
+    const size_t lds = sizeof(bf16_t) * (2 * rows * (32 * tkb + 8) + 4 * 32 * 40) + (bits ? 2 * 4 * rows * 4 : 0);
+    const int nw = (int)ceil_div(N, 32);
+    const uintptr_t bp = reinterpret_cast<uintptr_t>(bits);
+    const int bits_vec = (nw == 4 && ldbits % 4 == 0 && bp % 16 == 0) ? 4 : ((nw == 2 && ldbits % 2 == 0 && bp % 8 == 0) ? 2 : 1);
     const int vec_a = aligned16(A) && lda % 8 == 0;
     const int vec_c = C && aligned16(C) && ldc % 8 == 0, vec_f = Fact && aligned16(Fact) && ldf % 8 == 0;
     char label[64];
@@ -432,8 +492,8 @@ plx_status launch_gemm_small_bf16(plx_ctx* ctx, int64_t M, int64_t N, int64_t K,
         PLX_HIP(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds));                    \
         const int64_t blocks = std::min<int64_t>(ceil_div(M, rows), (int64_t)ctx->n_cu * std::max(1, per_cu));  \
         kern<<<dim3((unsigned)blocks), 256, lds, ctx->stream>>>(M, (int)N, (int)K, (const bf16_t*)A, lda, W, ldw, \
-                                                               (bf16_t*)C, ldc, (bf16_t*)Fact, ldf, vec_a, vec_c, \
-                                                               vec_f);                                           \
+                                                               (bf16_t*)C, ldc, (bf16_t*)Fact, ldf, bits, ldbits, \
+                                                               vec_a, vec_c, vec_f, bits_vec);                   \
     } while (0)
     switch (tkb * 10 + tnb) {
         case 11: PLX_SMALL(1, 1, 4); break;
@@ -453,7 +513,7 @@ plx_status launch_gemm_small_bf16(plx_ctx* ctx, int64_t M, int64_t N, int64_t K,
 
 plx_status launch_bwd_dense_bf16(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, const void* P, int64_t ldp, const void* Q,
                                  int64_t ldq, const void* Zm, int64_t ldz, const float* W, int64_t ldw, void* dOut,
-                                 int64_t ldo, float* dW, int64_t lddw, void* ws, size_t ws_bytes) {
+                                 int64_t ldo, float* dW, int64_t lddw, void* ws, size_t ws_bytes, bool mask_bits) {
     if (Mp > 128 || N > 128) return fail(ctx, PLX_ERR_UNSUPPORTED, "bf16 dense products are built for widths up to 128");
     if (ws_bytes < gemm_tn_workspace(R, Mp, N)) return fail(ctx, PLX_ERR_SHAPE, "workspace too small");
     const int64_t rpc = tn_rows_per_chunk(R, Mp, N);
@@ -461,15 +521,18 @@ plx_status launch_bwd_dense_bf16(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N,
     float* part = static_cast<float*>(ws);
     const int tmb = Mp <= 32 ? 1 : (Mp <= 64 ? 2 : 4), tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     char label[64];
-    snprintf(label, sizeof label, "bwd_dense<bf16>[R%lld,M%lld,N%lld]", (long long)R, (long long)Mp, (long long)N);
+    snprintf(label, sizeof label, "bwd_dense<bf16>[R%lld,M%lld,N%lld]%s", (long long)R, (long long)Mp, (long long)N,
+             (Zm && mask_bits) ? "bits" : "");
     plx_status st;
     {
         KernelTimer kt(ctx, label);
 #define PLX_BD(TM, TN)                                                                                                  \
-    st = Zm ? run_bwd<TM, TN, true>(ctx, R, (int)Mp, (int)N, (const bf16_t*)P, ldp, (const bf16_t*)Q, ldq,              \
-                                    (const bf16_t*)Zm, ldz, W, ldw, (bf16_t*)dOut, ldo, part, rpc, chunks)              \
-            : run_bwd<TM, TN, false>(ctx, R, (int)Mp, (int)N, (const bf16_t*)P, ldp, (const bf16_t*)Q, ldq, nullptr, 0, \
-                                     W, ldw, (bf16_t*)dOut, ldo, part, rpc, chunks)
+    st = !Zm ? run_bwd<TM, TN, 0>(ctx, R, (int)Mp, (int)N, (const bf16_t*)P, ldp, (const bf16_t*)Q, ldq, nullptr, 0,        \
+                                  W, ldw, (bf16_t*)dOut, ldo, part, rpc, chunks)                                        \
+         : mask_bits ? run_bwd<TM, TN, 2>(ctx, R, (int)Mp, (int)N, (const bf16_t*)P, ldp, (const bf16_t*)Q, ldq,          \
+                                          (const bf16_t*)Zm, ldz, W, ldw, (bf16_t*)dOut, ldo, part, rpc, chunks)        \
+                     : run_bwd<TM, TN, 1>(ctx, R, (int)Mp, (int)N, (const bf16_t*)P, ldp, (const bf16_t*)Q, ldq,          \
+                                          (const bf16_t*)Zm, ldz, W, ldw, (bf16_t*)dOut, ldo, part, rpc, chunks)
         switch (tmb * 10 + tnb) {
             case 11: PLX_BD(1, 1); break;
             case 12: PLX_BD(1, 2); break;

@@ -76,19 +76,45 @@ __device__ __forceinline__ void fetch_tile(TileRegs<TR, COLS>& t, const float* _
     }
 }
 
-// registers -> LDS tile [TR][COLS + 4]; with a mask tile, elements whose mask is <= 0 become 0 (Eq. 2.4)
-template <int TR, int COLS, bool MASK>
+// How Eq. 2.4 reaches the kernel: no mask, the matrix whose sign decides, or that sign packed one bit per element
+enum { kMaskNone = 0, kMaskValues = 1, kMaskBits = 2 };
+
+// Sign bits of a 32-row tile (bit j % 32 of word j / 32 of a row belongs to column j): COLS / 32 words
+// per row, 32 * (COLS / 32) words per tile.  Chunk i of thread tid (4 columns) lies in word
+// tid / 8 + 32 i of the tile, so a wavefront needs only 8 words per i: lane l < 8 * (COLS / 32) loads
+// word 8 * wavefront + l % 8 + 32 * (l / 8), and at commit time chunk i takes its word from lane
+// l / 8 + 8 i with a cross-lane read and its nibble at bit 4 * (tid % 8).
+template <int TR, int COLS> struct TileBits { uint32_t w; };
+
+template <int TR, int COLS>
+__device__ __forceinline__ void fetch_bits(TileBits<TR, COLS>& t, const uint32_t* __restrict__ bits, int64_t ldbits,
+                                           int64_t r0, int64_t r_end, int ncols, int tid) {
+    static_assert(TR == 32, "word numbering assumes 32-row tiles");
+    constexpr int WPR = COLS / 32;
+    const int lane = tid & 63, wv = tid >> 6;
+    const int wi = 8 * wv + (lane & 7) + 32 * (lane >> 3);
+    const int64_t gr = r0 + wi / WPR;
+    const int cw = wi % WPR;
+    t.w = (lane < 8 * WPR && gr < r_end && 32 * cw < ncols) ? bits[gr * ldbits + cw] : 0u;
+}
+
+// registers -> LDS tile [TR][COLS + 4]; with a mask, elements whose mask is <= 0 (whose bit is clear) become 0 (Eq. 2.4)
+template <int TR, int COLS, int MASK>
 __device__ __forceinline__ void commit_tile(float (*dst)[COLS + 4], const TileRegs<TR, COLS>& t,
-                                            const TileRegs<TR, COLS>& m, int tid) {
+                                            const TileRegs<TR, COLS>& m, const TileBits<TR, COLS>& mb, int tid) {
     constexpr int Q4 = COLS / 4;
 #pragma unroll
     for (int i = 0; i < TR * COLS / 1024; ++i) {
         const int f = tid + 256 * i, r = f / Q4, q = f % Q4;
         float4 v = t.v[i];
-        if (MASK) {
+        if (MASK == kMaskValues) {
             const float4 z = m.v[i];
             v.x = z.x > 0.f ? v.x : 0.f; v.y = z.y > 0.f ? v.y : 0.f;
             v.z = z.z > 0.f ? v.z : 0.f; v.w = z.w > 0.f ? v.w : 0.f;
+        } else if (MASK == kMaskBits) {
+            const uint32_t b = __shfl(mb.w, ((tid & 63) >> 3) + 8 * i) >> (4 * (tid & 7));
+            v.x = (b & 1u) ? v.x : 0.f; v.y = (b & 2u) ? v.y : 0.f;
+            v.z = (b & 4u) ? v.z : 0.f; v.w = (b & 8u) ? v.w : 0.f;
         }
         *reinterpret_cast<float4*>(&dst[r][4 * q]) = v;
     }
@@ -96,7 +122,7 @@ __device__ __forceinline__ void commit_tile(float (*dst)[COLS + 4], const TileRe
 
 constexpr int kTR = 32;      // rows per tile
 
-template <int TMB, int TNB, bool MASK, bool VEC>   // Mp <= 32*TMB, N <= 32*TNB
+template <int TMB, int TNB, int MASK, bool VEC>   // Mp <= 32*TMB, N <= 32*TNB; with kMaskBits Zm points at words
 __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N, const float* __restrict__ P, int64_t ldp,
                                                        const float* __restrict__ Q, int64_t ldq,
                                                        const float* __restrict__ Zm, int64_t ldz,
@@ -148,11 +174,15 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
     // barrier, write the prefetched tile to LDS, and only then issue this tile's dOut stores.
     TileRegs<kTR, NP> rq, rz;
     TileRegs<kTR, MP> rp;
+    TileBits<kTR, NP> zb;
+    TileBits<kTR, MP> nb;                  // never read
+    const uint32_t* Zbits = reinterpret_cast<const uint32_t*>(Zm);
     fetch_tile<kTR, NP, VEC>(rq, Q, ldq, r_begin, r_end, R, N, tid);
-    if (MASK) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, r_begin, r_end, R, N, tid);
+    if (MASK == kMaskValues) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, r_begin, r_end, R, N, tid);
+    if (MASK == kMaskBits) fetch_bits<kTR, NP>(zb, Zbits, ldz, r_begin, r_end, N, tid);
     fetch_tile<kTR, MP, VEC>(rp, P, ldp, r_begin, r_end, R, Mp, tid);
-    commit_tile<kTR, NP, MASK>(Qs, rq, rz, tid);
-    commit_tile<kTR, MP, false>(Ps, rp, rp, tid);
+    commit_tile<kTR, NP, MASK>(Qs, rq, rz, zb, tid);
+    commit_tile<kTR, MP, kMaskNone>(Ps, rp, rp, nb, tid);
     __syncthreads();
 
     for (int64_t r0 = r_begin; r0 < r_end; r0 += kTR) {
@@ -161,7 +191,8 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
         // nothing waits for the previous tile's stores to be acknowledged.
         const int64_t rn = r0 + kTR < r_end ? r0 + kTR : r0;
         fetch_tile<kTR, NP, VEC>(rq, Q, ldq, rn, r_end, R, N, tid);
-        if (MASK) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, rn, r_end, R, N, tid);
+        if (MASK == kMaskValues) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, rn, r_end, R, N, tid);
+        if (MASK == kMaskBits) fetch_bits<kTR, NP>(zb, Zbits, ldz, rn, r_end, N, tid);
         fetch_tile<kTR, MP, VEC>(rp, P, ldp, rn, r_end, R, Mp, tid);
 
         floatx4 acc_o[NRW][NCW];
@@ -196,8 +227,8 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
             }
         }
         __syncthreads();                                               // every wavefront is done reading the tile
-        commit_tile<kTR, NP, MASK>(Qs, rq, rz, tid);
-        commit_tile<kTR, MP, false>(Ps, rp, rp, tid);
+        commit_tile<kTR, NP, MASK>(Qs, rq, rz, zb, tid);
+        commit_tile<kTR, MP, kMaskNone>(Ps, rp, rp, nb, tid);
         if (dOut) {
             const bool full = r0 + kTR <= r_end;                       // uniform: only the last tile is partial
 #pragma unroll
@@ -239,13 +270,13 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-template <int TMB, int TNB, bool MASK>
+template <int TMB, int TNB, int MASK>
 plx_status run_masked(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
                       const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
                       int64_t rpc, int64_t chunks) {
     constexpr int MP = 32 * TMB, NP = 32 * TNB;
     const size_t lds = sizeof(float) * (kTR * (NP + 4) + kTR * (MP + 4));
-    const bool vec = aligned16(P) && ldp % 4 == 0 && aligned16(Q) && ldq % 4 == 0 && (!Zm || (aligned16(Zm) && ldz % 4 == 0)) &&
+    const bool vec = aligned16(P) && ldp % 4 == 0 && aligned16(Q) && ldq % 4 == 0 && (MASK != kMaskValues || (aligned16(Zm) && ldz % 4 == 0)) &&
                      R > 0;
     auto launch = [&](auto kern) -> plx_status {
         kern<<<dim3((unsigned)chunks), 256, lds, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc);
@@ -258,9 +289,10 @@ plx_status run_masked(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, in
 template <int TMB, int TNB>
 plx_status run(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
                const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
-               int64_t rpc, int64_t chunks) {
-    return Zm ? run_masked<TMB, TNB, true>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks)
-              : run_masked<TMB, TNB, false>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks);
+               int64_t rpc, int64_t chunks, bool mask_bits) {
+    if (!Zm) return run_masked<TMB, TNB, kMaskNone>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks);
+    return mask_bits ? run_masked<TMB, TNB, kMaskBits>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks)
+                     : run_masked<TMB, TNB, kMaskValues>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks);
 }
 
 }  // namespace
@@ -269,23 +301,24 @@ bool bwd_dense_supported(int64_t Mp, int64_t N, plx_dtype dtype) { return (dtype
 
 plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, const void* P, int64_t ldp, const void* Q,
                             int64_t ldq, const void* Zm, int64_t ldz, const float* W, int64_t ldw, void* dOut, int64_t ldo,
-                            float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes) {
+                            float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes, bool mask_bits) {
     if (!bwd_dense_supported(Mp, N, dtype)) return fail(ctx, PLX_ERR_INTERNAL, "fused backward called outside its range");
     if (dtype == PLX_BF16)
-        return launch_bwd_dense_bf16(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, dW, lddw, ws, ws_bytes);
+        return launch_bwd_dense_bf16(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, dW, lddw, ws, ws_bytes, mask_bits);
     if (ws_bytes < gemm_tn_workspace(R, Mp, N)) return fail(ctx, PLX_ERR_SHAPE, "workspace too small");
     const int64_t rpc = tn_rows_per_chunk(R, Mp, N);
     const int64_t chunks = std::max<int64_t>(1, ceil_div(R, rpc));
     float* part = static_cast<float*>(ws);
     const int tmb = Mp <= 32 ? 1 : (Mp <= 64 ? 2 : 4), tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     char label[64];
-    snprintf(label, sizeof label, "bwd_dense<f32>[R%lld,M%lld,N%lld]", (long long)R, (long long)Mp, (long long)N);
+    snprintf(label, sizeof label, "bwd_dense<f32>[R%lld,M%lld,N%lld]%s", (long long)R, (long long)Mp, (long long)N,
+             (Zm && mask_bits) ? "bits" : "");
     plx_status st;
     {
         KernelTimer kt(ctx, label);
 #define PLX_BD(TM, TN)                                                                                              \
     st = run<TM, TN>(ctx, R, (int)Mp, (int)N, (const float*)P, ldp, (const float*)Q, ldq, (const float*)Zm, ldz, W, ldw, \
-                     (float*)dOut, ldo, part, rpc, chunks)
+                     (float*)dOut, ldo, part, rpc, chunks, mask_bits)
         switch (tmb * 10 + tnb) {
             case 11: PLX_BD(1, 1); break;
             case 12: PLX_BD(1, 2); break;

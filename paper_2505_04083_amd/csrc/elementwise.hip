@@ -45,6 +45,32 @@ __global__ __launch_bounds__(256) void k_relu_bwd(int64_t rows, int cols, const 
     }
 }
 
+// bits[r][j / 32] bit j % 32 = [F[r][j] > 0]: one wavefront per 64 columns of a row, two words per ballot
+template <typename T>
+__global__ __launch_bounds__(256) void k_bits_from_act(int64_t rows, int cols, const T* __restrict__ F, int64_t ldf,
+                                                       uint32_t* __restrict__ bits, int64_t ldbits) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + lane;
+    for (int64_t r = (int64_t)blockIdx.y * 4 + wv; r < rows; r += (int64_t)gridDim.y * 4) {
+        const bool pos = c < cols && widen(F[r * ldf + c]) > 0.f;
+        const unsigned long long b = __ballot(pos);
+        const int word = blockIdx.x * 2 + (lane >> 5);
+        if ((lane & 31) == 0 && word * 32 < cols) bits[r * ldbits + word] = (uint32_t)(b >> (32 * (lane >> 5)));
+    }
+}
+
+// dZ = dF where the sign bit of the forward product is set, else 0
+template <typename T>
+__global__ __launch_bounds__(256) void k_relu_bwd_bits(int64_t rows, int cols, const uint32_t* __restrict__ bits,
+                                                       int64_t ldbits, const T* dF, int64_t lddf, T* dZ, int64_t lddz) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= cols) return;
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
+        const uint32_t m = bits[r * ldbits + (c >> 5)] >> (c & 31) & 1u;
+        dZ[r * lddz + c] = m ? dF[r * lddf + c] : narrow<T>(0.f);
+    }
+}
+
 // contiguous matrices: 4 elements per thread
 template <typename T>
 __global__ __launch_bounds__(256) void k_relu_flat(int64_t count, const T* __restrict__ Z, T* F) {
@@ -198,9 +224,36 @@ plx_status launch_relu(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, 
     return dtype == PLX_F32 ? relu_t<float>(ctx, rows, cols, Z, ldz, F, ldf) : relu_t<bf16_t>(ctx, rows, cols, Z, ldz, F, ldf);
 }
 
-plx_status launch_relu_bwd(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, const void* dF,
-                           int64_t lddf, void* dZ, int64_t lddz, plx_dtype dtype) {
+plx_status launch_bits_from_act(plx_ctx* ctx, int64_t rows, int64_t cols, const void* F, int64_t ldf, uint32_t* bits,
+                                int64_t ldbits, plx_dtype dtype) {
     if (cols >= (int64_t(1) << 24)) return fail(ctx, PLX_ERR_UNSUPPORTED, "too many columns");
+    if (rows == 0 || cols == 0) return PLX_OK;
+    char label[64];
+    snprintf(label, sizeof label, "sign_bits[R%lld,C%lld]", (long long)rows, (long long)cols);
+    KernelTimer kt(ctx, label);
+    dim3 grid((unsigned)ceil_div(cols, 64), (unsigned)std::min<int64_t>(ceil_div(rows, 4), 65535));
+    if (dtype == PLX_F32) k_bits_from_act<float><<<grid, 256, 0, ctx->stream>>>(rows, (int)cols, (const float*)F, ldf, bits, ldbits);
+    else k_bits_from_act<bf16_t><<<grid, 256, 0, ctx->stream>>>(rows, (int)cols, (const bf16_t*)F, ldf, bits, ldbits);
+    PLX_HIP(ctx, hipGetLastError());
+    return PLX_OK;
+}
+
+plx_status launch_relu_bwd(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, const void* dF,
+                           int64_t lddf, void* dZ, int64_t lddz, plx_dtype dtype, bool mask_bits) {
+    if (cols >= (int64_t(1) << 24)) return fail(ctx, PLX_ERR_UNSUPPORTED, "too many columns");
+    if (mask_bits) {
+        if (rows == 0 || cols == 0) return PLX_OK;
+        char label[64];
+        snprintf(label, sizeof label, "relu_bwd_bits[R%lld,C%lld]", (long long)rows, (long long)cols);
+        KernelTimer kt(ctx, label);
+        const uint32_t* b = (const uint32_t*)Z;
+        if (dtype == PLX_F32)
+            k_relu_bwd_bits<float><<<grid2d(rows, cols), 256, 0, ctx->stream>>>(rows, (int)cols, b, ldz, (const float*)dF, lddf, (float*)dZ, lddz);
+        else
+            k_relu_bwd_bits<bf16_t><<<grid2d(rows, cols), 256, 0, ctx->stream>>>(rows, (int)cols, b, ldz, (const bf16_t*)dF, lddf, (bf16_t*)dZ, lddz);
+        PLX_HIP(ctx, hipGetLastError());
+        return PLX_OK;
+    }
     return dtype == PLX_F32 ? relu_bwd_t<float>(ctx, rows, cols, Z, ldz, dF, lddf, dZ, lddz)
                             : relu_bwd_t<bf16_t>(ctx, rows, cols, Z, ldz, dF, lddf, dZ, lddz);
 }

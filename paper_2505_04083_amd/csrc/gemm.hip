@@ -171,7 +171,8 @@ template <int TKB, int CB, bool VEC>   // K <= 32*TKB; N <= 16*CB (CB <= 4) or N
 __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K, const float* __restrict__ A,
                                                         int64_t lda, const float* __restrict__ B, int64_t ldb,
                                                         float* __restrict__ C, int64_t ldc, float* __restrict__ F,
-                                                        int64_t ldf) {
+                                                        int64_t ldf, uint32_t* __restrict__ bits, int64_t ldbits,
+                                                        int bits_vec) {
     constexpr bool WIDE = CB > 4;
     constexpr int TR = fwd_tile_rows(TKB, CB);
     constexpr int KP = 32 * TKB;
@@ -184,6 +185,11 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
     // two A buffers: the next tile is written to LDS before this tile's stores are issued
     typedef float (*ATile)[KP + 4];
     auto a_buf = [&](int b) { return reinterpret_cast<ATile>(smem + b * TR * (KP + 4)); };
+    // Sign bits of a tile (only when bits != NULL): the wavefronts drop their ballots into LDS and the
+    // words leave one tile later as one store per row.  Two buffers of TR rows x 4 words; WIDE keeps
+    // them word-major ([word][row]: a lane's four consecutive rows are one 128-bit LDS write), the
+    // narrow tiles row-major as 8 half-words per row (a 16-column block is one half-word).
+    uint32_t* sb = reinterpret_cast<uint32_t*>(smem + 2 * TR * (KP + 4));
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, lq = lane >> 4, l32 = lane & 31, lh = lane >> 5;
     const int k_end = (K + KSTEP - 1) / KSTEP * KSTEP;
@@ -240,8 +246,28 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
         }
     };
 
-    int64_t tile = blockIdx.x;
+    const int nw = (N + 31) >> 5;
+    auto flush_bits = [&](int buf, int64_t t) {                          // words of tile t, written by the pass before
+        const int64_t row = t * TR + tid;
+        if (tid < TR && row < M) {
+            uint32_t wds[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wds[j] = WIDE ? sb[(buf * 4 + j) * TR + tid] : sb[(buf * TR + tid) * 4 + j];
+            uint32_t* dst = bits + row * ldbits;
+            if (bits_vec == 4) *reinterpret_cast<uint4*>(dst) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+            else if (bits_vec == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(wds[0], wds[1]);
+            else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (j < nw) dst[j] = wds[j];
+            }
+        }
+    };
+
+    int64_t tile = blockIdx.x, prev = -1;
     int cur = 0;
+    if (bits)
+        for (int i = tid; i < 2 * TR * 4; i += 256) sb[i] = 0;          // half-words no wavefront owns stay 0
     if (tile < n_tiles) { fetch(tile); commit(a_buf(0)); }
     __syncthreads();
     for (; tile < n_tiles; tile += gridDim.x) {
@@ -250,6 +276,8 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
         // matrix work, and nothing ever waits for the previous tile's stores to be acknowledged.
         const bool more = tile + gridDim.x < n_tiles;
         fetch(more ? tile + gridDim.x : tile);
+        if (bits && prev >= 0) flush_bits(cur ^ 1, prev);
+        prev = tile;
         ATile As = a_buf(cur);
         const bool full = (tile + 1) * TR <= M;                         // uniform: only the last tile is partial
 
@@ -295,6 +323,21 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
                     }
                 }
             }
+            if (bits) {       // one ballot = 32 columns of two rows (lanes 0-31: row dr, lanes 32-63: row dr + 4); columns >= N give 0
+#pragma unroll
+                for (int t = 0; t < NRB; ++t)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        uint32_t wv[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const unsigned long long b = __ballot(acc[t][4 * g + j] > 0.f);
+                            wv[j] = lh ? (uint32_t)(b >> 32) : (uint32_t)b;
+                        }
+                        if (l32 == 0)
+                            *reinterpret_cast<uint4*>(&sb[(cur * 4 + w) * TR + 32 * t + 8 * g + 4 * lh]) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
+                    }
+            }
         } else {
             floatx4 acc[NCW];
 #pragma unroll
@@ -326,10 +369,23 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
                     }
                 }
             }
+            if (bits) {       // one ballot = 16 columns of four rows (lanes 16q .. 16q+15: row 4q + r); columns >= N give 0
+                uint16_t* sh = reinterpret_cast<uint16_t*>(sb) + cur * TR * 8;
+#pragma unroll
+                for (int c = 0; c < NCW; ++c) {
+                    const int cb = col_block(c);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const unsigned long long b = __ballot(acc[c][r] > 0.f);
+                        if (l16 == 0 && cb < 8) sh[(16 * rowblk + 4 * lq + r) * 8 + cb] = (uint16_t)(b >> (16 * lq));
+                    }
+                }
+            }
         }
         __syncthreads();
         cur ^= 1;
     }
+    if (bits && prev >= 0) flush_bits(cur ^ 1, prev);                    // the last pass ended with a barrier
 }
 
 // ---- partial[chunk][M x N] = A[rows of chunk, M]^T * B[rows of chunk, N] ---------------------------
@@ -482,10 +538,12 @@ size_t gemm_tn_workspace(int64_t R, int64_t M, int64_t N) {
 }
 
 plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
-                       const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype, void* Fact, int64_t ldf) {
+                       const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype, void* Fact, int64_t ldf,
+                       uint32_t* bits, int64_t ldbits) {
+    if (bits && !Fact) return fail(ctx, PLX_ERR_INTERNAL, "sign bits are written next to the activated output");
     if (dtype == PLX_BF16) {
         if (bt) return fail(ctx, PLX_ERR_UNSUPPORTED, "the bf16 A B^T product exists only inside the fused backward kernel");
-        return launch_gemm_small_bf16(ctx, M, N, K, A, lda, B, ldb, C, ldc, Fact, ldf);
+        return launch_gemm_small_bf16(ctx, M, N, K, A, lda, B, ldb, C, ldc, Fact, ldf, bits, ldbits);
     }
     if (N >= (int64_t(1) << 20) || K >= (int64_t(1) << 30)) return fail(ctx, PLX_ERR_UNSUPPORTED, "N or K too large");
     const float* a = static_cast<const float*>(A);
@@ -503,8 +561,11 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
         int cb = (int)ceil_div(N, 16);
         if (cb > 4) cb = 8;                    // wide tiles are 128 columns (four 32x32 column blocks)
         const int tr = fwd_tile_rows(tkb, cb);
-        const size_t lds = sizeof(float) * 2 * tr * (32 * tkb + 4);
+        const size_t lds = sizeof(float) * 2 * tr * (32 * tkb + 4) + (bits ? 2 * tr * 16 : 0);
         const bool vec = vec_a && K % 4 == 0 && M > 0;
+        const int nw = (int)ceil_div(N, 32);
+        const uintptr_t bp = reinterpret_cast<uintptr_t>(bits);
+        const int bits_vec = (nw == 4 && ldbits % 4 == 0 && bp % 16 == 0) ? 4 : ((nw == 2 && ldbits % 2 == 0 && bp % 8 == 0) ? 2 : 1);
         auto launch_small = [&](auto kern) -> plx_status {
             if (lds > 48 * 1024)
                 PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -513,7 +574,7 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
             PLX_HIP(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds));
             if (cb > 4) per_cu = std::min(per_cu, 3);   // measured: a 4th resident workgroup slows the store-bound K = 32 case by 5 %
             const int64_t blocks = std::min<int64_t>(ceil_div(M, tr), (int64_t)ctx->n_cu * std::max(1, per_cu));
-            kern<<<dim3((unsigned)blocks), 256, lds, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf);
+            kern<<<dim3((unsigned)blocks), 256, lds, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf, bits, ldbits, bits_vec);
             return PLX_OK;
         };
 #define PLX_SMALL(TK, CBV) \
@@ -545,6 +606,7 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
     }
 #undef PLX_GEMM_CASE
     PLX_HIP(ctx, hipGetLastError());
+    if (bits) return launch_bits_from_act(ctx, M, N, Fact, ldf, bits, ldbits, dtype);    // no fused epilogue in the general kernel
     return PLX_OK;
 }
 

@@ -384,7 +384,7 @@ static LayerWs layer_ws(const Orient& a, int64_t din, int64_t dout, plx_dtype dt
     size_t first = order == PLX_ORDER_AGG_FIRST ? (size_t)a.rows * w.ld_in * es : (size_t)a.cols * w.ld_out * es;
     w.off_a = 0;
     w.off_dz = align256(first);
-    size_t dz = act == PLX_ACT_RELU ? (size_t)a.rows * w.ld_out * es : 0;
+    size_t dz = act != PLX_ACT_NONE ? (size_t)a.rows * w.ld_out * es : 0;
     w.off_tn = w.off_dz + align256(dz);
     int64_t R = order == PLX_ORDER_AGG_FIRST ? a.rows : a.cols;
     w.total = w.off_tn + align256(gemm_tn_workspace(R, din, dout));
@@ -402,7 +402,7 @@ static plx_status layer_common_checks(plx_ctx* ctx, const plx_csr* csr, int64_t 
                                       plx_act act, plx_order order) {
     if (!csr) return fail(ctx, PLX_ERR_INVALID, "csr is NULL");
     if (!dtype_ok(dtype)) return fail(ctx, PLX_ERR_INVALID, "unknown dtype %d", (int)dtype);
-    if (act != PLX_ACT_NONE && act != PLX_ACT_RELU) return fail(ctx, PLX_ERR_INVALID, "unknown activation %d", (int)act);
+    if (act != PLX_ACT_NONE && act != PLX_ACT_RELU && act != PLX_ACT_RELU_BITS) return fail(ctx, PLX_ERR_INVALID, "unknown activation %d", (int)act);
     if ((int)order < 0 || (int)order > 2) return fail(ctx, PLX_ERR_INVALID, "unknown order %d", (int)order);
     if (din <= 0 || dout <= 0) return fail(ctx, PLX_ERR_INVALID, "din and dout must be positive");
     return PLX_OK;
@@ -418,7 +418,10 @@ plx_status plx_gcn_layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
     order = resolve_order(order, din, dout);
     if (!H || !W) return fail(ctx, PLX_ERR_INVALID, "H or W is NULL");
     if (!Z && !F) return fail(ctx, PLX_ERR_INVALID, "Z and F are both NULL");
-    if (ldh < din || ldw < dout || (Z && ldz < dout) || (F && ldf < dout))
+    const bool sign_bits = act == PLX_ACT_RELU_BITS;          // Z receives one bit per element instead of the values
+    if (sign_bits && (!Z || !F)) return fail(ctx, PLX_ERR_INVALID, "the sign-bit activation writes both Z (bits) and F");
+    if (sign_bits && (reinterpret_cast<uintptr_t>(Z) & 3)) return fail(ctx, PLX_ERR_INVALID, "the sign bits need a 4-byte aligned Z");
+    if (ldh < din || ldw < dout || (Z && ldz < (sign_bits ? (dout + 31) / 32 : dout)) || (F && ldf < dout))
         return fail(ctx, PLX_ERR_SHAPE, "leading dimension too small");
     if (order == PLX_ORDER_AGG_FIRST) {
         if (!saved) return fail(ctx, PLX_ERR_INVALID, "aggregate-first order needs the `saved` buffer");
@@ -431,20 +434,23 @@ plx_status plx_gcn_layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
 
     // The last product of the layer stores the pre-activation (if wanted) and the activated
     // output (Eq. 2.3) from the same registers.
-    void* plain = Z;
+    void* plain = sign_bits ? nullptr : Z;
     void* activated = nullptr;
+    uint32_t* bits = sign_bits ? static_cast<uint32_t*>(Z) : nullptr;
     if (F) {
-        if (act == PLX_ACT_RELU) activated = F;
+        if (act != PLX_ACT_NONE) activated = F;
         else if (!Z) plain = F;              // no activation and only F wanted: F is the plain output
     }
     const int64_t ld_plain = plain == Z ? ldz : ldf;
     if (order == PLX_ORDER_AGG_FIRST) {
         PLX_TRY(launch_spmm(ctx, a, H, ldh, saved, ldsaved, din, dtype));                    // Eq. 2.1
-        PLX_TRY(launch_gemm(ctx, false, a.rows, dout, din, saved, ldsaved, W, ldw, plain, ld_plain, dtype, activated, ldf));  // Eq. 2.2 (+2.3)
+        PLX_TRY(launch_gemm(ctx, false, a.rows, dout, din, saved, ldsaved, W, ldw, plain, ld_plain, dtype, activated, ldf, bits,
+                            ldz));                                                           // Eq. 2.2 (+2.3)
     } else {
         void* T = static_cast<char*>(ws) + w.off_a;
         PLX_TRY(launch_gemm(ctx, false, a.cols, dout, din, H, ldh, W, ldw, T, w.ld_out, dtype));
         PLX_TRY(launch_spmm(ctx, a, T, w.ld_out, plain, ld_plain, dout, dtype, activated, ldf));
+        if (bits) PLX_TRY(launch_bits_from_act(ctx, a.rows, dout, F, ldf, bits, ldz, dtype));
     }
     if (F && act == PLX_ACT_NONE && Z && F != Z)
         PLX_HIP(ctx, hipMemcpy2DAsync(F, ldf * elt_size(dtype), Z, ldz * elt_size(dtype), dout * elt_size(dtype), a.rows,
@@ -464,8 +470,11 @@ plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
     const Orient& at = csr->o[1 - t];   // the transpose of the layer's adjacency
     order = resolve_order(order, din, dout);
     if (!W || !dF || !dW) return fail(ctx, PLX_ERR_INVALID, "W, dF or dW is NULL");
-    if (act == PLX_ACT_RELU && !Z) return fail(ctx, PLX_ERR_INVALID, "Z is needed for the ReLU derivative");
-    if (ldw < dout || lddf < dout || lddw < dout || (Z && ldz < dout) || (dH && lddh < din))
+    const bool sign_bits = act == PLX_ACT_RELU_BITS;
+    if (act != PLX_ACT_NONE && !Z) return fail(ctx, PLX_ERR_INVALID, "Z is needed for the ReLU derivative");
+    if (sign_bits && (reinterpret_cast<uintptr_t>(Z) & 3)) return fail(ctx, PLX_ERR_INVALID, "the sign bits need a 4-byte aligned Z");
+    if (ldw < dout || lddf < dout || lddw < dout || (Z && ldz < (sign_bits ? (dout + 31) / 32 : dout)) ||
+        (dH && lddh < din))
         return fail(ctx, PLX_ERR_SHAPE, "leading dimension too small");
     if (order == PLX_ORDER_AGG_FIRST) {
         if (!saved) return fail(ctx, PLX_ERR_INVALID, "aggregate-first order needs the `saved` buffer");
@@ -482,20 +491,20 @@ plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
     char* base = static_cast<char*>(ws);
     void* tn_ws = base + w.off_tn;
     size_t tn_bytes = w.total - w.off_tn;
-    const void* mask = act == PLX_ACT_RELU ? Z : nullptr;
+    const void* mask = act != PLX_ACT_NONE ? Z : nullptr;
     if (bwd_dense_supported(din, dout, dtype)) {
         // Eq. 2.4 is applied while the gradient tile is loaded; it is never written back
         if (order == PLX_ORDER_AGG_FIRST) {
             void* dS = dH ? base + w.off_a : nullptr;
             PLX_TRY(launch_bwd_dense(ctx, a.rows, din, dout, saved, ldsaved, dF, lddf, mask, ldz, W, ldw, dS, w.ld_in, dW, lddw,
-                                     dtype, tn_ws, tn_bytes));                               // Eq. 2.4 + 2.5 + 2.6
+                                     dtype, tn_ws, tn_bytes, sign_bits));                    // Eq. 2.4 + 2.5 + 2.6
             if (dH) PLX_TRY(launch_spmm(ctx, at, dS, w.ld_in, dH, lddh, din, dtype));        // Eq. 2.7
         } else {
             const void* dZ = dF;
             int64_t lddz = lddf;
             if (mask) {
                 void* buf = base + w.off_dz;
-                PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, w.ld_out, dtype));
+                PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, w.ld_out, dtype, sign_bits));
                 dZ = buf; lddz = w.ld_out;
             }
             void* G = base + w.off_a;
@@ -509,7 +518,7 @@ plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
     int64_t lddz = lddf;
     if (mask) {                                                                              // Eq. 2.4
         void* buf = base + w.off_dz;
-        PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, w.ld_out, dtype));
+        PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, w.ld_out, dtype, sign_bits));
         dZ = buf; lddz = w.ld_out;
     }
     if (order == PLX_ORDER_AGG_FIRST) {

@@ -149,34 +149,40 @@ void free_orient(plx_ctx* ctx, Orient& o);
 // product to the rows of that row block (other rows of Y are not touched)
 plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* Y, int64_t ldy,
                        int64_t d, plx_dtype dtype, void* Yact = nullptr, int64_t ldyact = 0, int block = -1);
-// C = A op(B) (C may be NULL); if Fact != NULL it also receives max(C, 0)
+// C = A op(B) (C may be NULL); if Fact != NULL it also receives max(C, 0); if bits != NULL it receives
+// the sign bits [C > 0] (bit j % 32 of word j / 32 of row i, ldbits words per row)
 plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                        const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype, void* Fact = nullptr,
-                       int64_t ldf = 0);
+                       int64_t ldf = 0, uint32_t* bits = nullptr, int64_t ldbits = 0);
+// bits[i][j] = [F[i][j] > 0] for an activated matrix F (used where no producing kernel writes the bits itself)
+plx_status launch_bits_from_act(plx_ctx* ctx, int64_t rows, int64_t cols, const void* F, int64_t ldf, uint32_t* bits,
+                                int64_t ldbits, plx_dtype dtype);
 size_t gemm_tn_workspace(int64_t R, int64_t M, int64_t N);
 int64_t tn_rows_per_chunk(int64_t R, int64_t M, int64_t N);
 int tn_kslices(int64_t M, int64_t N);
 plx_status reduce_partials(plx_ctx* ctx, float* part, int64_t chunks, int64_t M, int64_t N, float* C, int64_t ldc);
-// fused Eq. 2.4 + 2.5 + 2.6: dOut = (Q*[Zm>0]) W^T (dOut may be NULL), dW = P^T (Q*[Zm>0]); Zm may be NULL
+// fused Eq. 2.4 + 2.5 + 2.6: dOut = (Q*[Zm>0]) W^T (dOut may be NULL), dW = P^T (Q*[Zm>0]); Zm may be NULL.
+// mask_bits: Zm is not a matrix of values but the sign bits written by a forward product (ldz in words)
 bool bwd_dense_supported(int64_t Mp, int64_t N, plx_dtype dtype);
 plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, const void* P, int64_t ldp, const void* Q,
                             int64_t ldq, const void* Zm, int64_t ldz, const float* W, int64_t ldw, void* dOut, int64_t ldo,
-                            float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes);
+                            float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes, bool mask_bits = false);
 plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const void* A, int64_t lda,
                           const void* B, int64_t ldb, float* C, int64_t ldc, plx_dtype dtype, void* ws, size_t ws_bytes);
 plx_status launch_relu(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, void* F, int64_t ldf,
                        plx_dtype dtype);
 plx_status launch_relu_bwd(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, const void* dF,
-                           int64_t lddf, void* dZ, int64_t lddz, plx_dtype dtype);
+                           int64_t lddf, void* dZ, int64_t lddz, plx_dtype dtype, bool mask_bits = false);
 plx_status launch_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, int64_t ldz, const int64_t* y,
                              void* dZ, int64_t lddz, float* row_loss, float* loss, plx_dtype dtype);
 
 // bf16 storage / fp32 accumulation variants (widths up to 128)
 plx_status launch_gemm_small_bf16(plx_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
-                                  const float* W, int64_t ldw, void* C, int64_t ldc, void* Fact, int64_t ldf);
+                                  const float* W, int64_t ldw, void* C, int64_t ldc, void* Fact, int64_t ldf,
+                                  uint32_t* bits = nullptr, int64_t ldbits = 0);
 plx_status launch_bwd_dense_bf16(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, const void* P, int64_t ldp, const void* Q,
                                  int64_t ldq, const void* Zm, int64_t ldz, const float* W, int64_t ldw, void* dOut,
-                                 int64_t ldo, float* dW, int64_t lddw, void* ws, size_t ws_bytes);
+                                 int64_t ldo, float* dW, int64_t lddw, void* ws, size_t ws_bytes, bool mask_bits = false);
 
 inline size_t elt_size(plx_dtype t) { return t == PLX_BF16 ? 2 : 4; }
 inline size_t align256(size_t b) { return (b + 255) & ~size_t(255); }

@@ -2,15 +2,17 @@
 
 Layer l uses the stored orientation l % 2 (Eq. 5.3-5.4 of the paper: P_r A P_c^T for even layers,
 P_c A P_r^T for odd ones).  All buffers are allocated once, so a training step allocates nothing.
-Hidden layers store only the activated output (its sign serves Eq. 2.4); the last layer stores
-the logits.  The input must be in P_c order and the labels in the order of the last layer's output."""
+Hidden layers store only the activated output (its sign serves Eq. 2.4) and, where the dense product
+of the layer can write them on the fly (aggregate-first order, widths up to 128), that sign packed
+one bit per element, which is all the backward pass then reads of it; the last layer stores the
+logits.  The input must be in P_c order and the labels in the order of the last layer's output."""
 from __future__ import annotations
 
 from typing import List, Optional
 
 import torch
 
-from . import (PLX_ACT_NONE, PLX_ACT_RELU, PLX_BF16, PLX_F32, PLX_ORDER_AUTO, plx_gcn_layer_bwd,
+from . import (PLX_ACT_NONE, PLX_ACT_RELU, PLX_ACT_RELU_BITS, PLX_BF16, PLX_F32, PLX_ORDER_AUTO, plx_gcn_layer_bwd,
                plx_gcn_layer_fwd, plx_gcn_layer_workspace, plx_softmax_ce, plx_sync)
 
 
@@ -23,12 +25,17 @@ def _matrix(rows: int, cols: int, dtype, dev) -> torch.Tensor:
 
 class GcnNetwork:
     def __init__(self, ctx, csr, Ws: List[torch.Tensor], dtype=torch.float32, order: int = PLX_ORDER_AUTO,
-                 keep_preactivation: bool = False):
+                 keep_preactivation: bool = False, sign_bits: bool = True):
         self.ctx, self.csr, self.Ws, self.order = ctx, csr, Ws, order
         self.L = len(Ws)
         dev = Ws[0].device
         code = PLX_F32 if dtype == torch.float32 else PLX_BF16
         self.act = [PLX_ACT_RELU if l + 1 < self.L else PLX_ACT_NONE for l in range(self.L)]
+        for l, W in enumerate(Ws[:-1]):
+            din, dout = W.shape
+            agg_first = order == 1 or (order == PLX_ORDER_AUTO and din < dout)
+            if sign_bits and not keep_preactivation and agg_first and max(din, dout) <= 128:
+                self.act[l] = PLX_ACT_RELU_BITS
         nbytes = 1
         for l, W in enumerate(Ws):
             nbytes = max(nbytes, plx_gcn_layer_workspace(csr, bool(l % 2), W.shape[0], W.shape[1], code, self.act[l], order))
@@ -42,7 +49,10 @@ class GcnNetwork:
             rows, cols = csr.shape(bool(l % 2))
             din, dout = W.shape
             last = l + 1 == self.L
-            self.Z.append(_matrix(rows, dout, dtype, dev) if (last or keep_preactivation) else None)
+            if self.act[l] == PLX_ACT_RELU_BITS:
+                self.Z.append(torch.empty(rows, (dout + 31) // 32, dtype=torch.int32, device=dev))
+            else:
+                self.Z.append(_matrix(rows, dout, dtype, dev) if (last or keep_preactivation) else None)
             self.F.append(None if last else _matrix(rows, dout, dtype, dev))
             agg_first = order == 1 or (order == PLX_ORDER_AUTO and din < dout)
             self.saved.append(_matrix(rows if agg_first else 1, din, dtype, dev))

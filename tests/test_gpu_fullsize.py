@@ -94,9 +94,22 @@ def test_shard_backward_dense_gradient_samples(shard):
     ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, order=order), dtype=torch.uint8, device=DEV)
     F = torch.empty(m, dout, device=DEV); saved = torch.empty(m, din, device=DEV)
     dX = torch.empty(k, din, device=DEV); dW = torch.empty(din, dout, device=DEV)
-    plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, None, F, saved, ws, order=order)
-    plx.plx_gcn_layer_bwd(ctx, csr, False, X, W, F, dF, saved, dX, dW, ws, order=order)
+    # the configuration the benchmark times: the forward call also packs the sign of F into one bit
+    # per element and the backward call reads only those words
+    words = torch.empty(m, (dout + 31) // 32, dtype=torch.int32, device=DEV)
+    plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, words, F, saved, ws, act=plx.PLX_ACT_RELU_BITS, order=order)
+    plx.plx_gcn_layer_bwd(ctx, csr, False, X, W, words, dF, saved, dX, dW, ws, act=plx.PLX_ACT_RELU_BITS, order=order)
     plx.plx_sync(ctx)
+    # every word is the packed [F > 0] of its 32 columns (int64 arithmetic, then the low 32 bits)
+    packed = ((F > 0).view(m, -1, 32).to(torch.int64) << torch.arange(32, device=DEV)).sum(dim=2)
+    assert torch.equal(words.to(torch.int64) & 0xFFFFFFFF, packed)
+    del packed
+    # and the backward pass fed with the value matrix instead returns the same bits
+    dX2 = torch.empty_like(dX); dW2 = torch.empty_like(dW)
+    plx.plx_gcn_layer_bwd(ctx, csr, False, X, W, F, dF, saved, dX2, dW2, ws, act=plx.PLX_ACT_RELU, order=order)
+    plx.plx_sync(ctx)
+    assert torch.equal(dX, dX2) and torch.equal(dW, dW2)
+    del dX2, dW2
     # sampled output rows j of dX and the block rows i that touch them
     J = np.arange(17, k, 70001, dtype=np.int64)
     rowptr, col = h["rowptr"], h["col"]

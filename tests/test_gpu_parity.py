@@ -484,6 +484,61 @@ def test_layer_ragged_widths_in_padded_rows(ctx, din, dout, dtype):
             assert bool(torch.isnan(t[:, wdt:].float()).all())
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("din,dout", [(32, 128), (128, 128), (100, 47), (33, 65), (16, 16), (128, 16), (64, 96), (602, 128)])
+def test_layer_sign_bits(ctx, din, dout, dtype):
+    """ReLU kept as one sign bit per element: the words the forward call writes are exactly the packed
+    [F > 0] of the activated output it writes beside them (zero beyond the width, nothing written
+    beyond the words of a row), and the backward call fed with the words returns bit for bit what it
+    returns when fed with the value matrix; results are checked against the oracle as well.  Widths
+    cover both fused dense kernels, the general product (602: separate sign pass) and both orders."""
+    if dtype == "bf16" and max(din, dout) > 128:
+        pytest.skip("bf16 dense products are built for widths up to 128")
+    m, k = 1237, 1500                                # several tiles and a ragged last one
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    code = plx.PLX_F32 if dtype == "f32" else plx.PLX_BF16
+    tol = TOL32 if dtype == "f32" else 2e-2
+    rowptr, col, val = random_block(m, k, 11 * din + dout)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(5 * din + dout)
+    X = torch.as_tensor(r.standard_normal((k, din)).astype(np.float32)).to(tdt).to(DEV)
+    X64 = X.double().cpu().numpy()
+    W = (r.standard_normal((din, dout)) * 0.2).astype(np.float32)
+    Hagg = oracle.spmm_coo(m, row, c64, v64, X64)
+    Q = oracle.gemm(Hagg, W)
+    dF64 = r.standard_normal((m, dout)) * (np.abs(Q) > 2e-2 * np.abs(Q).max())   # keep clear of the mask's rounding band
+    dF = torch.as_tensor(dF64.astype(np.float32)).to(tdt).to(DEV)
+    dF64 = dF.double().cpu().numpy()
+    dQ = oracle.relu_bwd(Q, dF64)
+    dW = oracle.gemm(Hagg, dQ, ta=True)
+    dX = oracle.spmm_t_coo(k, row, c64, v64, oracle.gemm(dQ, W, tb=True))
+    nw = (dout + 31) // 32
+    for order in (plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_COMBINE_FIRST):
+        ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, dtype=code, act=plx.PLX_ACT_RELU_BITS, order=order),
+                         dtype=torch.uint8, device=DEV)
+        F = torch.empty(m, dout, dtype=tdt, device=DEV); saved = torch.empty(m, din, dtype=tdt, device=DEV)
+        words = torch.full((m, nw + 1), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
+        plx.plx_gcn_layer_fwd(ctx, csr, False, X, dev(W), words[:, :nw], F, saved, ws, act=plx.PLX_ACT_RELU_BITS, order=order)
+        outs = []
+        for act, mask in ((plx.PLX_ACT_RELU_BITS, words[:, :nw]), (plx.PLX_ACT_RELU, F)):
+            gdX = torch.empty(k, din, dtype=tdt, device=DEV); gdW = torch.empty(din, dout, device=DEV)
+            plx.plx_gcn_layer_bwd(ctx, csr, False, X, dev(W), mask, dF, saved, gdX, gdW, ws, act=act, order=order)
+            outs.append((gdX, gdW))
+        plx.plx_sync(ctx)
+        pos = (F.float() > 0).cpu().numpy()
+        padded = np.zeros((m, 32 * nw), dtype=np.uint64)
+        padded[:, :dout] = pos
+        want = (padded.reshape(m, nw, 32) << np.arange(32, dtype=np.uint64)).sum(axis=2).astype(np.uint32)
+        got = words.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got[:, :nw], want)
+        assert np.all(got[:, nw] == 0x5A5A5A5A)
+        assert rel_err(F.float(), oracle.relu(Q)) <= tol
+        assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+        assert rel_err(outs[0][1], dW) <= tol
+        assert rel_err(outs[0][0].float(), dX) <= tol
+
+
 def test_network_step_in_hip_graph():
     """One whole forward + backward of configs[0] recorded into a HIP graph: every replay, with
     eager work and synchronisations in between, reproduces the eager step bit for bit (the
