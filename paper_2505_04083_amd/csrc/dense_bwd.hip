@@ -17,6 +17,7 @@
 //       the whole chunk; block q of the (Mp/32) x (N/32) grid belongs to wavefront q % 4.
 // Chunk partials of dW are summed afterwards in a fixed order (bit-reproducible).
 #include "plx_internal.h"
+#include "buffer_addr.h"
 
 #include <algorithm>
 
@@ -31,41 +32,52 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // loads of the next tile are in flight while the matrix cores work on the current one.
 template <int TR, int COLS> struct TileRegs { float4 v[TR * COLS / 1024]; };   // TR * COLS / 4 float4 over 256 threads
 
-// VEC: rows are 16-byte aligned (base and leading dimension), so a thread's 4 columns are one
-// 128-bit load.  Rows past the end are read from the last valid row and zeroed by a select.  When
-// ncols is not a multiple of 4 the last chunk of a row still lies inside the row's pitch: it is
-// loaded whole and the surplus elements are zeroed -- except on the very last row of the matrix,
-// where the bytes behind the last column need not exist and single loads are used.
+// Byte offsets of a thread's 16-byte pieces inside a tile, computed once per kernel (VEC path: rows are
+// 16-byte aligned, so a piece is one 128-bit buffer load; pieces wholly past the last column get an
+// offset no descriptor reaches and read as 0).
+template <int TR, int COLS> struct TileOffs { uint32_t v[TR * COLS / 1024]; };
+
+template <int TR, int COLS>
+__device__ __forceinline__ void tile_offsets(TileOffs<TR, COLS>& o, int64_t ld, int ncols, int tid) {
+    constexpr int Q4 = COLS / 4;
+#pragma unroll
+    for (int i = 0; i < TR * COLS / 1024; ++i) {
+        const int f = tid + 256 * i, r = f / Q4, q = f % Q4;
+        o.v[i] = (COLS == ncols || 4 * q < ncols) ? (uint32_t)(((uint32_t)r * (uint32_t)ld + 4u * q) * 4u) : kOutOfRange;
+    }
+}
+
+// VEC: the tile's descriptor ends with the last column of the last valid row (of the chunk), so rows
+// past the end and the bytes behind the matrix read as 0 without any per-lane test.  When ncols is
+// not a multiple of 4 the piece that straddles ncols holds padding elements, which are zeroed.
 template <int TR, int COLS, bool VEC>
 __device__ __forceinline__ void fetch_tile(TileRegs<TR, COLS>& t, const float* __restrict__ src, int64_t ld, int64_t r0,
-                                           int64_t r_end, int64_t r_total, int ncols, int tid) {
+                                           int64_t r_end, int64_t r_total, int ncols, int tid, const TileOffs<TR, COLS>& o) {
     constexpr int Q4 = COLS / 4;
+    if constexpr (VEC) {
+        const int64_t left = r_end - r0;
+        const int64_t rows = left < TR ? left : TR;
+        const __amdgpu_buffer_rsrc_t rs = buffer_of(src + r0 * ld, rows > 0 ? (uint32_t)(((rows - 1) * ld + ncols) * 4) : 0u);
+#pragma unroll
+        for (int i = 0; i < TR * COLS / 1024; ++i) t.v[i] = buffer_load4(rs, o.v[i]);
+        if (ncols & 3) {                               // uniform
+#pragma unroll
+            for (int i = 0; i < TR * COLS / 1024; ++i) {
+                const int gc = 4 * ((tid + 256 * i) % Q4);
+                if (gc + 1 >= ncols) t.v[i].y = 0.f;
+                if (gc + 2 >= ncols) t.v[i].z = 0.f;
+                if (gc + 3 >= ncols) t.v[i].w = 0.f;
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TR * COLS / 1024; ++i) {
         const int f = tid + 256 * i, r = f / Q4, q = f % Q4;
         const int64_t gr = r0 + r;
         const int gc = 4 * q;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if constexpr (VEC) {
-            if (COLS == ncols || gc < ncols) {
-                const int64_t rr = gr < r_end ? gr : r_end - 1;
-                const float* p = src + rr * ld + gc;
-                const bool ragged = COLS != ncols && gc + 3 >= ncols;
-                if (!ragged || rr + 1 < r_total) {
-                    v = *reinterpret_cast<const float4*>(p);
-                    if (ragged) {
-                        if (gc + 1 >= ncols) v.y = 0.f;
-                        if (gc + 2 >= ncols) v.z = 0.f;
-                        v.w = 0.f;
-                    }
-                } else {
-                    v.x = p[0];
-                    if (gc + 1 < ncols) v.y = p[1];
-                    if (gc + 2 < ncols) v.z = p[2];
-                }
-                if (gr >= r_end) v = make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        } else if (gr < r_end && gc < ncols) {
+        if (gr < r_end && gc < ncols) {
             const float* p = src + gr * ld + gc;
             v.x = p[0];
             if (gc + 1 < ncols) v.y = p[1];
@@ -87,15 +99,22 @@ enum { kMaskNone = 0, kMaskValues = 1, kMaskBits = 2 };
 template <int TR, int COLS> struct TileBits { uint32_t w; };
 
 template <int TR, int COLS>
-__device__ __forceinline__ void fetch_bits(TileBits<TR, COLS>& t, const uint32_t* __restrict__ bits, int64_t ldbits,
-                                           int64_t r0, int64_t r_end, int ncols, int tid) {
+__device__ __forceinline__ uint32_t bits_offset(int64_t ldbits, int ncols, int tid) {      // byte offset of a lane's word in a tile
     static_assert(TR == 32, "word numbering assumes 32-row tiles");
     constexpr int WPR = COLS / 32;
     const int lane = tid & 63, wv = tid >> 6;
     const int wi = 8 * wv + (lane & 7) + 32 * (lane >> 3);
-    const int64_t gr = r0 + wi / WPR;
     const int cw = wi % WPR;
-    t.w = (lane < 8 * WPR && gr < r_end && 32 * cw < ncols) ? bits[gr * ldbits + cw] : 0u;
+    return (lane < 8 * WPR && 32 * cw < ncols) ? (uint32_t)(((uint32_t)(wi / WPR) * (uint32_t)ldbits + cw) * 4u) : kOutOfRange;
+}
+
+template <int TR, int COLS>
+__device__ __forceinline__ void fetch_bits(TileBits<TR, COLS>& t, const uint32_t* __restrict__ bits, int64_t ldbits,
+                                           int64_t r0, int64_t r_end, int ncols, uint32_t off) {
+    const int64_t left = r_end - r0;
+    const int64_t rows = left < TR ? left : TR;
+    const __amdgpu_buffer_rsrc_t rs = buffer_of(bits + r0 * ldbits, rows > 0 ? (uint32_t)(((rows - 1) * ldbits + (ncols + 31) / 32) * 4) : 0u);
+    t.w = buffer_load1(rs, off);
 }
 
 // registers -> LDS tile [TR][COLS + 4]; with a mask, elements whose mask is <= 0 (whose bit is clear) become 0 (Eq. 2.4)
@@ -112,9 +131,13 @@ __device__ __forceinline__ void commit_tile(float (*dst)[COLS + 4], const TileRe
             v.x = z.x > 0.f ? v.x : 0.f; v.y = z.y > 0.f ? v.y : 0.f;
             v.z = z.z > 0.f ? v.z : 0.f; v.w = z.w > 0.f ? v.w : 0.f;
         } else if (MASK == kMaskBits) {
-            const uint32_t b = __shfl(mb.w, ((tid & 63) >> 3) + 8 * i) >> (4 * (tid & 7));
-            v.x = (b & 1u) ? v.x : 0.f; v.y = (b & 2u) ? v.y : 0.f;
-            v.z = (b & 4u) ? v.z : 0.f; v.w = (b & 8u) ? v.w : 0.f;
+            // bit e of the nibble, sign-extended to a word mask: two vector instructions per element
+            const int b = (int)__shfl(mb.w, ((tid & 63) >> 3) + 8 * i);
+            const unsigned s0 = 4 * (tid & 7);
+            v.x = __uint_as_float(__float_as_uint(v.x) & (unsigned)__builtin_amdgcn_sbfe(b, s0, 1));
+            v.y = __uint_as_float(__float_as_uint(v.y) & (unsigned)__builtin_amdgcn_sbfe(b, s0 + 1, 1));
+            v.z = __uint_as_float(__float_as_uint(v.z) & (unsigned)__builtin_amdgcn_sbfe(b, s0 + 2, 1));
+            v.w = __uint_as_float(__float_as_uint(v.w) & (unsigned)__builtin_amdgcn_sbfe(b, s0 + 3, 1));
         }
         *reinterpret_cast<float4*>(&dst[r][4 * q]) = v;
     }
@@ -176,11 +199,17 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
     TileRegs<kTR, MP> rp;
     TileBits<kTR, NP> zb;
     TileBits<kTR, MP> nb;                  // never read
+    TileOffs<kTR, NP> oq, oz;
+    TileOffs<kTR, MP> op;
+    tile_offsets<kTR, NP>(oq, ldq, N, tid);
+    if (MASK == kMaskValues) tile_offsets<kTR, NP>(oz, ldz, N, tid);
+    tile_offsets<kTR, MP>(op, ldp, Mp, tid);
     const uint32_t* Zbits = reinterpret_cast<const uint32_t*>(Zm);
-    fetch_tile<kTR, NP, VEC>(rq, Q, ldq, r_begin, r_end, R, N, tid);
-    if (MASK == kMaskValues) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, r_begin, r_end, R, N, tid);
-    if (MASK == kMaskBits) fetch_bits<kTR, NP>(zb, Zbits, ldz, r_begin, r_end, N, tid);
-    fetch_tile<kTR, MP, VEC>(rp, P, ldp, r_begin, r_end, R, Mp, tid);
+    const uint32_t ob = MASK == kMaskBits ? bits_offset<kTR, NP>(ldz, N, tid) : 0u;
+    fetch_tile<kTR, NP, VEC>(rq, Q, ldq, r_begin, r_end, R, N, tid, oq);
+    if (MASK == kMaskValues) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, r_begin, r_end, R, N, tid, oz);
+    if (MASK == kMaskBits) fetch_bits<kTR, NP>(zb, Zbits, ldz, r_begin, r_end, N, ob);
+    fetch_tile<kTR, MP, VEC>(rp, P, ldp, r_begin, r_end, R, Mp, tid, op);
     commit_tile<kTR, NP, MASK>(Qs, rq, rz, zb, tid);
     commit_tile<kTR, MP, kMaskNone>(Ps, rp, rp, nb, tid);
     __syncthreads();
@@ -190,10 +219,10 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
         // with straight-line code the only wait for loads sits right before the LDS write and
         // nothing waits for the previous tile's stores to be acknowledged.
         const int64_t rn = r0 + kTR < r_end ? r0 + kTR : r0;
-        fetch_tile<kTR, NP, VEC>(rq, Q, ldq, rn, r_end, R, N, tid);
-        if (MASK == kMaskValues) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, rn, r_end, R, N, tid);
-        if (MASK == kMaskBits) fetch_bits<kTR, NP>(zb, Zbits, ldz, rn, r_end, N, tid);
-        fetch_tile<kTR, MP, VEC>(rp, P, ldp, rn, r_end, R, Mp, tid);
+        fetch_tile<kTR, NP, VEC>(rq, Q, ldq, rn, r_end, R, N, tid, oq);
+        if (MASK == kMaskValues) fetch_tile<kTR, NP, VEC>(rz, Zm, ldz, rn, r_end, R, N, tid, oz);
+        if (MASK == kMaskBits) fetch_bits<kTR, NP>(zb, Zbits, ldz, rn, r_end, N, ob);
+        fetch_tile<kTR, MP, VEC>(rp, P, ldp, rn, r_end, R, Mp, tid, op);
 
         floatx4 acc_o[NRW][NCW];
         if (dOut) {                                                    // Eq. 2.6 on this tile
@@ -231,23 +260,20 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
         commit_tile<kTR, MP, kMaskNone>(Ps, rp, rp, nb, tid);
         if (dOut) {
             const bool full = r0 + kTR <= r_end;                       // uniform: only the last tile is partial
+            const __amdgpu_buffer_rsrc_t ro = buffer_of(dOut + r0 * ldo, (uint32_t)(((kTR - 1) * ldo + Mp) * 4));
 #pragma unroll
             for (int rr = 0; rr < NRW; ++rr) {
-                const int64_t row0 = r0 + 16 * (rb0 + rr) + 4 * lq;
+                const int row0 = 16 * (rb0 + rr);                      // uniform; the lane's rows are row0 + 4*lq + r
+                uint32_t orow = opaque_zero() + (uint32_t)row0 * (uint32_t)ldo * 4u;
 #pragma unroll
-                for (int c = 0; c < NCW; ++c) {
-                    const int gc = 16 * (cb0 + c) + l16;
-                    float* o = dOut + row0 * ldo + gc;
-                    if (gc < Mp) {
-                        if (full) {
+                for (int r = 0; r < 4; ++r) {
 #pragma unroll
-                            for (int r = 0; r < 4; ++r) o[r * ldo] = acc_o[rr][c][r];
-                        } else {
-#pragma unroll
-                            for (int r = 0; r < 4; ++r)
-                                if (row0 + r < r_end) o[r * ldo] = acc_o[rr][c][r];
-                        }
+                    for (int c = 0; c < NCW; ++c) {
+                        const int gc = 16 * (cb0 + c) + l16;
+                        const uint32_t ooff = gc < Mp ? (uint32_t)((4u * lq * (uint32_t)ldo + gc) * 4u) : kOutOfRange;
+                        if (full || r0 + row0 + 4 * lq + r < r_end) buffer_store(ro, ooff, orow, acc_o[rr][c][r]);
                     }
+                    orow += (uint32_t)ldo * 4u;
                 }
             }
         }
@@ -303,6 +329,9 @@ plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, cons
                             int64_t ldq, const void* Zm, int64_t ldz, const float* W, int64_t ldw, void* dOut, int64_t ldo,
                             float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes, bool mask_bits) {
     if (!bwd_dense_supported(Mp, N, dtype)) return fail(ctx, PLX_ERR_INTERNAL, "fused backward called outside its range");
+    // a tile is addressed with 31-bit byte offsets: 32 rows * ld * 4 bytes must fit
+    if (std::max(std::max(ldp, ldq), std::max(ldz, ldo)) >= (int64_t(1) << 23))
+        return fail(ctx, PLX_ERR_UNSUPPORTED, "leading dimensions of 2^23 elements or more are not supported by the fused backward kernels");
     if (dtype == PLX_BF16)
         return launch_bwd_dense_bf16(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, dW, lddw, ws, ws_bytes, mask_bits);
     if (ws_bytes < gemm_tn_workspace(R, Mp, N)) return fail(ctx, PLX_ERR_SHAPE, "workspace too small");

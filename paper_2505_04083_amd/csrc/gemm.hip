@@ -15,8 +15,10 @@
 // workgroup writes its partial tile and a second kernel adds the partials in a fixed order, so
 // the result does not depend on scheduling.
 #include "plx_internal.h"
+#include "buffer_addr.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace plx {
 namespace {
@@ -214,21 +216,29 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
 
     const int64_t n_tiles = (M + TR - 1) / TR;
     float4 reg[NLD];
+    uint32_t toff[NLD];                    // VEC: byte offset of a thread's 16-byte pieces inside a tile
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int f = tid + 256 * i, r = f / (KP / 4), q = f % (KP / 4);
+        toff[i] = (KP == K || 4 * q < K) ? (uint32_t)(((uint32_t)r * (uint32_t)lda + 4u * q) * 4u) : kOutOfRange;
+    }
+    const uint32_t tile_bytes_a = (uint32_t)(((TR - 1) * lda + K) * 4);
     auto fetch = [&](int64_t tile) {
         const int64_t m0 = tile * TR;
+        if constexpr (VEC) {               // the byte count ends with the last valid row: rows past it read as 0
+            const int64_t left = M - m0;
+            const __amdgpu_buffer_rsrc_t ra = buffer_of(A + m0 * lda, left >= TR ? tile_bytes_a : (uint32_t)(((left - 1) * lda + K) * 4));
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) reg[i] = buffer_load4(ra, toff[i]);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int f = tid + 256 * i, r = f / (KP / 4), q = f % (KP / 4);
             const int64_t gr = m0 + r;
             const int gk = 4 * q;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if constexpr (VEC) {           // rows past the end are read from the last row and zeroed by a select
-                if (KP == K || gk < K) {
-                    const int64_t rr = gr < M ? gr : M - 1;
-                    v = *reinterpret_cast<const float4*>(A + rr * lda + gk);
-                    if (gr >= M) v = make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-            } else if (gr < M && gk < K) {
+            if (gr < M && gk < K) {
                 const float* p = A + gr * lda + gk;
                 v.x = p[0];
                 if (gk + 1 < K) v.y = p[1];
@@ -289,7 +299,7 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
                 for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 #pragma unroll
             for (int s0 = 0; s0 < NKS; s0 += CHUNK) {
-                if (KSTEP * s0 >= k_end) break;                          // uniform: no matrix work on k-padding beyond a chunk
+                if (s0 > 0 && KSTEP * s0 >= k_end) break;                // uniform: no matrix work on k-padding beyond a chunk
 #pragma unroll
                 for (int g = s0 / 4; g < (s0 + CHUNK) / 4; ++g) {
                     float4 a4[NRB];
@@ -307,21 +317,35 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
             commit(a_buf(cur ^ 1));
             const int gn = 32 * w + l32;
             if (gn < N) {
+                // lane part of an address: column, and the +4 rows of the upper half-wave; the row part is scalar
+                const uint32_t coff = (uint32_t)((4u * lh * (uint32_t)ldc + gn) * 4u), foff = (uint32_t)((4u * lh * (uint32_t)ldf + gn) * 4u);
+                const int64_t m0 = tile * TR;
+                const __amdgpu_buffer_rsrc_t rc = buffer_of(C ? C + m0 * ldc : nullptr, (uint32_t)(((TR - 1) * ldc + N) * 4));
+                const __amdgpu_buffer_rsrc_t rf = buffer_of(F ? F + m0 * ldf : nullptr, (uint32_t)(((TR - 1) * ldf + N) * 4));
+                auto emit = [&](auto guarded, auto has_c, auto has_f) {
+                    uint32_t crow = opaque_zero(), frow = crow;                      // byte offset of the tile's row `row`
+                    int at = 0;
 #pragma unroll
-                for (int t = 0; t < NRB; ++t) {
-                    const int64_t row0 = tile * TR + 32 * t + 4 * lh;
-                    float* cp = C ? C + row0 * ldc + gn : nullptr;
-                    float* fp = F ? F + row0 * ldf + gn : nullptr;
+                    for (int t = 0; t < NRB; ++t)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int dr = 8 * (r / 4) + (r % 4);
-                        if (full || row0 + dr < M) {
+                        for (int r = 0; r < 16; ++r) {
+                            const int row = 32 * t + 8 * (r / 4) + (r % 4);            // of the lower half-wave
+                            crow += (uint32_t)(row - at) * (uint32_t)ldc * 4u;
+                            frow += (uint32_t)(row - at) * (uint32_t)ldf * 4u;
+                            at = row;
                             const float v = acc[t][r];
-                            if (cp) st_out(cp + dr * ldc, v);
-                            if (fp) st_out(fp + dr * ldf, v > 0.f ? v : 0.f);      // Eq. 2.3 fused into the store
+                            if (!guarded.value || m0 + row + 4 * lh < M) {
+                                if (has_c.value) buffer_store_nt(rc, coff, crow, v);
+                                if (has_f.value) buffer_store_nt(rf, foff, frow, relu0(v));   // Eq. 2.3 fused into the store
+                            }
                         }
-                    }
-                }
+                };
+                auto emit_cf = [&](auto guarded) {
+                    if (C && F) emit(guarded, std::true_type{}, std::true_type{});
+                    else if (F) emit(guarded, std::false_type{}, std::true_type{});
+                    else emit(guarded, std::true_type{}, std::false_type{});
+                };
+                if (full) emit_cf(std::false_type{}); else emit_cf(std::true_type{});
             }
             if (bits) {       // one ballot = 32 columns of two rows (lanes 0-31: row dr, lanes 32-63: row dr + 4); columns >= N give 0
 #pragma unroll
@@ -344,7 +368,7 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
             for (int c = 0; c < NCW; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s0 = 0; s0 < NKS; s0 += CHUNK) {
-                if (KSTEP * s0 >= k_end) break;
+                if (s0 > 0 && KSTEP * s0 >= k_end) break;
 #pragma unroll
                 for (int s = s0; s < s0 + CHUNK; ++s) {
                     const float a = As[16 * rowblk + l16][4 * s + lq];
@@ -353,21 +377,32 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
                 }
             }
             commit(a_buf(cur ^ 1));
-            const int64_t row0 = tile * TR + 16 * rowblk + 4 * lq;
+            {
+                const int64_t m0 = tile * TR;
+                const __amdgpu_buffer_rsrc_t rc = buffer_of(C ? C + m0 * ldc : nullptr, (uint32_t)(((TR - 1) * ldc + N) * 4));
+                const __amdgpu_buffer_rsrc_t rf = buffer_of(F ? F + m0 * ldf : nullptr, (uint32_t)(((TR - 1) * ldf + N) * 4));
+                auto emit = [&](auto has_c, auto has_f) {
 #pragma unroll
-            for (int c = 0; c < NCW; ++c) {
-                const int gn = 16 * col_block(c) + l16;
-                if (gn >= N) continue;
-                float* cp = C ? C + row0 * ldc + gn : nullptr;
-                float* fp = F ? F + row0 * ldf + gn : nullptr;
+                    for (int c = 0; c < NCW; ++c) {
+                        const int gn = 16 * col_block(c) + l16;
+                        if (gn >= N) continue;
+                        const uint32_t coff = (uint32_t)((4u * lq * (uint32_t)ldc + gn) * 4u), foff = (uint32_t)((4u * lq * (uint32_t)ldf + gn) * 4u);
+                        uint32_t crow = opaque_zero() + 16u * rowblk * (uint32_t)ldc * 4u, frow = opaque_zero() + 16u * rowblk * (uint32_t)ldf * 4u;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (full || row0 + r < M) {
-                        const float v = acc[c][r];
-                        if (cp) st_out(cp + r * ldc, v);
-                        if (fp) st_out(fp + r * ldf, v > 0.f ? v : 0.f);            // Eq. 2.3 fused into the store
+                        for (int r = 0; r < 4; ++r) {
+                            if (full || m0 + 16 * rowblk + r + 4 * lq < M) {
+                                const float v = acc[c][r];
+                                if (has_c.value) buffer_store_nt(rc, coff, crow, v);
+                                if (has_f.value) buffer_store_nt(rf, foff, frow, relu0(v));       // Eq. 2.3 fused into the store
+                            }
+                            crow += (uint32_t)ldc * 4u;
+                            frow += (uint32_t)ldf * 4u;
+                        }
                     }
-                }
+                };
+                if (C && F) emit(std::true_type{}, std::true_type{});
+                else if (F) emit(std::false_type{}, std::true_type{});
+                else emit(std::true_type{}, std::false_type{});
             }
             if (bits) {       // one ballot = 16 columns of four rows (lanes 16q .. 16q+15: row 4q + r); columns >= N give 0
                 uint16_t* sh = reinterpret_cast<uint16_t*>(sb) + cur * TR * 8;
@@ -556,7 +591,9 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
     char label[64];
     snprintf(label, sizeof label, "gemm_%s<f32>[M%lld,N%lld,K%lld]", bt ? "nt" : "nn", (long long)M, (long long)N, (long long)K);
     KernelTimer kt(ctx, label);
-    if (!bt && K <= 128 && N <= 128 && K > 0) {
+    // the small-width kernel addresses a tile with 31-bit byte offsets: 64 rows * ld * 4 bytes must fit
+    const bool ld32 = lda < (int64_t(1) << 23) && (!C || ldc < (int64_t(1) << 23)) && (!Fact || ldf < (int64_t(1) << 23));
+    if (!bt && K <= 128 && N <= 128 && K > 0 && ld32) {
         const int tkb = K <= 32 ? 1 : (K <= 64 ? 2 : 4);
         int cb = (int)ceil_div(N, 16);
         if (cb > 4) cb = 8;                    // wide tiles are 128 columns (four 32x32 column blocks)
@@ -572,7 +609,10 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             int per_cu = 0;                    // resident workgroups per CU for this kernel's registers and LDS
             PLX_HIP(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds));
-            if (cb > 4) per_cu = std::min(per_cu, 3);   // measured: a 4th resident workgroup slows the store-bound K = 32 case by 5 %
+#ifndef PLX_FWD_WIDE_CAP
+#define PLX_FWD_WIDE_CAP 3
+#endif
+            if (cb > 4) per_cu = std::min(per_cu, PLX_FWD_WIDE_CAP);   // measured: a 4th resident workgroup slows the store-bound K = 32 case by 5 %
             const int64_t blocks = std::min<int64_t>(ceil_div(M, tr), (int64_t)ctx->n_cu * std::max(1, per_cu));
             kern<<<dim3((unsigned)blocks), 256, lds, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf, bits, ldbits, bits_vec);
             return PLX_OK;

@@ -539,6 +539,34 @@ def test_layer_sign_bits(ctx, din, dout, dtype):
         assert rel_err(outs[0][0].float(), dX) <= tol
 
 
+def test_layer_sign_bits_argument_errors(ctx):
+    m, k, din, dout = 40, 50, 8, 40
+    rowptr, col, val = random_block(m, k, 2)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    X = torch.zeros(k, din, device=DEV); W = torch.zeros(din, dout, device=DEV)
+    F = torch.empty(m, dout, device=DEV); saved = torch.empty(m, din, device=DEV)
+    words = torch.empty(m, 2, dtype=torch.int32, device=DEV)
+    one_word = torch.empty(m, 1, dtype=torch.int32, device=DEV)
+    ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, act=plx.PLX_ACT_RELU_BITS), dtype=torch.uint8, device=DEV)
+    bits_act = plx.PLX_ACT_RELU_BITS
+    with pytest.raises(plx.PlxError) as err:                                   # unknown activation code
+        plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, words, F, saved, ws, act=3)
+    assert err.value.status == plx.PLX_ERR_INVALID
+    with pytest.raises(plx.PlxError) as err:                                   # the words go beside F, not instead of it
+        plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, words, None, saved, ws, act=bits_act)
+    assert err.value.status == plx.PLX_ERR_INVALID
+    with pytest.raises(plx.PlxError) as err:                                   # 40 columns need two words per row
+        plx.plx_gcn_layer_fwd(ctx, csr, False, X, W, one_word, F, saved, ws, act=bits_act)
+    assert err.value.status == plx.PLX_ERR_SHAPE
+    dX = torch.empty(k, din, device=DEV); dW = torch.empty(din, dout, device=DEV)
+    with pytest.raises(plx.PlxError) as err:
+        plx.plx_gcn_layer_bwd(ctx, csr, False, X, W, None, F, saved, dX, dW, ws, act=bits_act)
+    assert err.value.status == plx.PLX_ERR_INVALID
+    with pytest.raises(plx.PlxError) as err:
+        plx.plx_gcn_layer_bwd(ctx, csr, False, X, W, one_word, F, saved, dX, dW, ws, act=bits_act)
+    assert err.value.status == plx.PLX_ERR_SHAPE
+
+
 def test_network_step_in_hip_graph():
     """One whole forward + backward of configs[0] recorded into a HIP graph: every replay, with
     eager work and synchronisations in between, reproduces the eager step bit for bit (the
