@@ -20,6 +20,7 @@
 // Results leave through a small per-wavefront LDS staging area so that every lane stores 16
 // bytes (8 bf16) with one non-temporal store instead of eight 2-byte stores.
 #include "plx_internal.h"
+#include "buffer_addr.h"
 
 #include <algorithm>
 
@@ -42,11 +43,8 @@ union Frag {
     bf16_t e[8];
 };
 
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {   // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {   // round to nearest even: one v_cvt_pk_bf16_f32
+    return __builtin_bit_cast(bf16_t, (__bf16)f);
 }
 __device__ __forceinline__ bool bf16_positive(bf16_t z) { return (z & 0x8000u) == 0 && (z & 0x7fffu) != 0 && (z & 0x7fffu) <= 0x7f80u; }
 
@@ -92,6 +90,74 @@ __device__ __forceinline__ uint4 load8(const bf16_t* __restrict__ src, int64_t l
         }
     }
     return f.u;
+}
+
+// Buffer-addressed form of the same load (16-byte aligned rows): `off` is the piece's byte offset inside
+// the tile, computed once per kernel (pieces wholly past ncols carry an offset the descriptor never
+// reaches), and the descriptor ends with column ncols of the last valid row, so nothing is tested per
+// lane.  Only a piece that straddles ncols (ncols % 8 != 0) needs its surplus elements zeroed.
+__device__ __forceinline__ uint32_t piece_offset(int f, int pieces, int per_row, int64_t ld, int ncols) {
+    const int r = f / per_row, q = f % per_row;
+    return (f < pieces && 8 * q < ncols) ? (uint32_t)(((uint32_t)r * (uint32_t)ld + 8u * q) * 2u) : kOutOfRange;
+}
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_buffer(const bf16_t* base, int64_t ld, int64_t row0, int64_t r_end,
+                                                              int tile_rows, int ncols) {
+    const int64_t left = r_end - row0;
+    const int64_t rows = left < tile_rows ? left : tile_rows;
+    // the range check works on whole 32-bit words: with an odd ncols the word that holds the last column
+    // must count as inside (its other half is padding of the same 16-byte aligned row)
+    return buffer_of(base + row0 * ld, rows > 0 ? (uint32_t)((((rows - 1) * ld + ncols) * 2 + 3) & ~int64_t(3)) : 0u);
+}
+__device__ __forceinline__ uint4 load8_buf(__amdgpu_buffer_rsrc_t rs, uint32_t off, int gc, int ncols) {
+    Frag f;
+    f.u = __builtin_bit_cast(uint4, buffer_load4(rs, off));
+    if (ncols & 7) {                                   // uniform
+#pragma unroll
+        for (int i = 1; i < 8; ++i)
+            if (gc + i >= ncols) f.e[i] = 0;
+    }
+    return f.u;
+}
+
+// Buffer-addressed write-out of a staged block (destination rows 16-byte aligned): the lane's pieces
+// sit at byte offsets `off[k]` inside the block (computed once per kernel; pieces not wholly inside
+// the ncols columns carry an unreachable offset), the descriptor ends with the last valid row.
+// A piece that straddles ncols (ncols % 8 != 0) is written element by element.
+template <int COLS, int NPC>
+__device__ __forceinline__ void stage_store_buf(const bf16_t* stage, int nrows, bf16_t* __restrict__ dst, int64_t ld,
+                                                int64_t row0, int64_t r_end, int col0, int ncols, const uint32_t (&off)[NPC],
+                                                int lane) {
+    constexpr int PITCH = COLS + 8, CH = COLS / 8;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const __amdgpu_buffer_rsrc_t rs = tile_buffer(dst, ld, row0, r_end, nrows, ncols);
+#pragma unroll
+    for (int k = 0; k < NPC; ++k) {
+        const int i = lane + 64 * k, r = i / CH, c = 8 * (i % CH);
+        Frag f;
+        f.u = *reinterpret_cast<const uint4*>(stage + (r % nrows) * PITCH + c);
+        __builtin_amdgcn_raw_buffer_store_b128(f.x, rs, (int)off[k], 0, 2);
+        if ((ncols & 7) && i < nrows * CH) {            // first condition uniform
+            const int gc = col0 + c;
+            const int64_t gr = row0 + r;
+            if (gr < r_end && gc < ncols && gc + 7 >= ncols) {
+                bf16_t* p = dst + gr * ld + gc;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (gc + e < ncols) p[e] = f.e[e];
+            }
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+// byte offset of piece i of a staged nrows x COLS block whose first column is col0 (see stage_store_buf)
+template <int COLS>
+__device__ __forceinline__ uint32_t stage_offset(int i, int nrows, int64_t ld, int col0, int ncols) {
+    constexpr int CH = COLS / 8;
+    const int r = i / CH, gc = col0 + 8 * (i % CH);
+    return (i < nrows * CH && gc + 7 < ncols) ? (uint32_t)(((uint32_t)r * (uint32_t)ld + gc) * 2u) : kOutOfRange;
 }
 
 // One wavefront writes a ROWS16*16 x COLS block of results: the values go through the
@@ -169,13 +235,29 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
 
     const int64_t n_tiles = (M + ROWS - 1) / ROWS;
     uint4 reg[NLD];
+    uint32_t toff[NLD];                                     // vec_a: byte offsets of the thread's pieces inside a tile
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) toff[i] = piece_offset(tid + 256 * i, ROWS * KP / 8, KP / 8, lda, K);
     auto fetch = [&](int64_t tile) {
+        if (vec_a) {                                        // uniform
+            const __amdgpu_buffer_rsrc_t ra = tile_buffer(A, lda, tile * ROWS, M, ROWS, K);
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) reg[i] = load8_buf(ra, toff[i], 8 * ((tid + 256 * i) % (KP / 8)), K);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const int f = tid + 256 * i, r = f / (KP / 8), q = f % (KP / 8);
-            reg[i] = (f < ROWS * KP / 8) ? load8(A, lda, tile * ROWS + r, M, M, 8 * q, K, vec_a) : make_uint4(0, 0, 0, 0);
+            reg[i] = (f < ROWS * KP / 8) ? load8(A, lda, tile * ROWS + r, M, M, 8 * q, K, false) : make_uint4(0, 0, 0, 0);
         }
     };
+    // write-out: piece k of a wavefront's staged 32 x 32 block (see stage_store_buf)
+    uint32_t coff[2], foff[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        coff[k] = stage_offset<32>(lane + 64 * k, 32, ldc, 32 * bj, N);
+        foff[k] = stage_offset<32>(lane + 64 * k, 32, ldf, 32 * bj, N);
+    }
     auto commit = [&](bf16_t* As) {
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
@@ -235,29 +317,33 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
         for (int t = 0; t < NBLK; ++t) {
             const int bi = (w + 4 * t) / TNB;
             if (32 * bj >= N) continue;
+            if (C) {                                        // plain result
 #pragma unroll
-            for (int pass = 0; pass < 2; ++pass) {          // plain result, then its ReLU (Eq. 2.3)
-                bf16_t* dst = pass == 0 ? C : F;
-                if (!dst) continue;
+                for (int r = 0; r < 16; ++r) stage[(8 * (r / 4) + 4 * lh + (r % 4)) * 40 + l32] = f32_to_bf16(acc[t][r]);
+                if (vec_c) stage_store_buf<32, 2>(stage, 32, C, ldc, m0 + 32 * bi, M, 32 * bj, N, coff, lane);
+                else stage_store<32>(stage, 32, C, ldc, m0 + 32 * bi, M, 32 * bj, N, false, lane);
+            }
+            if (F) {                                        // its ReLU (Eq. 2.3), and the sign of the rounded value
+                bf16_t h[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float v = acc[t][r];
-                    stage[(8 * (r / 4) + 4 * lh + (r % 4)) * 40 + l32] = f32_to_bf16(pass == 0 ? v : (v > 0.f ? v : 0.f));
+                    h[r] = f32_to_bf16(relu0(acc[t][r]));
+                    stage[(8 * (r / 4) + 4 * lh + (r % 4)) * 40 + l32] = h[r];
                 }
-                stage_store<32>(stage, 32, dst, pass == 0 ? ldc : ldf, m0 + 32 * bi, M, 32 * bj, N,
-                                pass == 0 ? vec_c : vec_f, lane);
-            }
-            if (bits) {        // sign of the rounded result; one ballot = 32 columns of two rows (lanes 0-31, lanes 32-63)
+                if (vec_f) stage_store_buf<32, 2>(stage, 32, F, ldf, m0 + 32 * bi, M, 32 * bj, N, foff, lane);
+                else stage_store<32>(stage, 32, F, ldf, m0 + 32 * bi, M, 32 * bj, N, false, lane);
+                if (bits) {    // one ballot = 32 columns of two rows (lanes 0-31, lanes 32-63); max(v, 0) rounds to 0 or to a positive value
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    uint32_t wv[4];
+                    for (int g = 0; g < 4; ++g) {
+                        uint32_t wv[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const unsigned long long b = __ballot(bf16_positive(f32_to_bf16(acc[t][4 * g + j])));
-                        wv[j] = lh ? (uint32_t)(b >> 32) : (uint32_t)b;
+                        for (int j = 0; j < 4; ++j) {
+                            const unsigned long long b = __ballot((h[4 * g + j] & 0x7fffu) != 0);
+                            wv[j] = lh ? (uint32_t)(b >> 32) : (uint32_t)b;
+                        }
+                        if (l32 == 0)
+                            *reinterpret_cast<uint4*>(&sb[(cur * 4 + bj) * ROWS + 32 * bi + 8 * g + 4 * lh]) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
                     }
-                    if (l32 == 0)
-                        *reinterpret_cast<uint4*>(&sb[(cur * 4 + bj) * ROWS + 32 * bi + 8 * g + 4 * lh]) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
                 }
             }
         }
@@ -329,27 +415,59 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
     static_assert(MASK != 2 || kTR == 32, "word numbering assumes 32-row tiles");
     uint32_t zb = 0;
     const uint32_t* Zbits = reinterpret_cast<const uint32_t*>(Zm);
+    // byte offsets, inside a tile, of the thread's pieces (vec_q / vec_p) and of its sign word
+    uint32_t oq[NQ], oz[NQ], op[NPR], ob = kOutOfRange;
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+        oq[i] = piece_offset(tid + 256 * i, kTR * NP / 8, NP / 8, ldq, N);
+        oz[i] = MASK == 1 ? piece_offset(tid + 256 * i, kTR * NP / 8, NP / 8, ldz, N) : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < NPR; ++i) op[i] = piece_offset(tid + 256 * i, kTR * MP / 8, MP / 8, ldp, Mp);
+    if (MASK == 2) {
+        constexpr int WPR = NP / 32;
+        const int wi = 16 * w + (lane & 15) + 64 * (lane >> 4), cw = wi % WPR;
+        if (lane < 16 * NQ && wi < 32 * WPR && 32 * cw < N) ob = (uint32_t)(((uint32_t)(wi / WPR) * (uint32_t)ldz + cw) * 4u);
+    }
     auto fetch = [&](int64_t r0) {
+        if (vec_q) {                                                  // uniform
+            const __amdgpu_buffer_rsrc_t bq = tile_buffer(Q, ldq, r0, r_end, kTR, N);
 #pragma unroll
-        for (int i = 0; i < NQ; ++i) {
-            const int f = tid + 256 * i, r = f / (NP / 8), q = f % (NP / 8);
-            const bool in = f < kTR * NP / 8;
-            rq[i] = in ? load8(Q, ldq, r0 + r, r_end, R, 8 * q, N, vec_q) : make_uint4(0, 0, 0, 0);
-            if (MASK == 1) rz[i] = in ? load8(Zm, ldz, r0 + r, r_end, R, 8 * q, N, vec_q) : make_uint4(0, 0, 0, 0);
-        }
+            for (int i = 0; i < NQ; ++i) rq[i] = load8_buf(bq, oq[i], 8 * ((tid + 256 * i) % (NP / 8)), N);
+            if (MASK == 1) {
+                const __amdgpu_buffer_rsrc_t bz = tile_buffer(Zm, ldz, r0, r_end, kTR, N);
 #pragma unroll
-        for (int i = 0; i < NPR; ++i) {
-            const int f = tid + 256 * i, r = f / (MP / 8), q = f % (MP / 8);
-            rp[i] = (f < kTR * MP / 8) ? load8(P, ldp, r0 + r, r_end, R, 8 * q, Mp, vec_p) : make_uint4(0, 0, 0, 0);
+                for (int i = 0; i < NQ; ++i) rz[i] = load8_buf(bz, oz[i], 8 * ((tid + 256 * i) % (NP / 8)), N);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NQ; ++i) {
+                const int f = tid + 256 * i, r = f / (NP / 8), q = f % (NP / 8);
+                const bool in = f < kTR * NP / 8;
+                rq[i] = in ? load8(Q, ldq, r0 + r, r_end, R, 8 * q, N, false) : make_uint4(0, 0, 0, 0);
+                if (MASK == 1) rz[i] = in ? load8(Zm, ldz, r0 + r, r_end, R, 8 * q, N, false) : make_uint4(0, 0, 0, 0);
+            }
         }
-        if (MASK == 2) {
-            constexpr int WPR = NP / 32;
-            const int wi = 16 * w + (lane & 15) + 64 * (lane >> 4);
-            const int64_t gr = r0 + wi / WPR;
-            const int cw = wi % WPR;
-            zb = (lane < 16 * NQ && wi < 32 * WPR && gr < r_end && 32 * cw < N) ? Zbits[gr * ldz + cw] : 0u;
+        if (vec_p) {
+            const __amdgpu_buffer_rsrc_t bp = tile_buffer(P, ldp, r0, r_end, kTR, Mp);
+#pragma unroll
+            for (int i = 0; i < NPR; ++i) rp[i] = load8_buf(bp, op[i], 8 * ((tid + 256 * i) % (MP / 8)), Mp);
+        } else {
+#pragma unroll
+            for (int i = 0; i < NPR; ++i) {
+                const int f = tid + 256 * i, r = f / (MP / 8), q = f % (MP / 8);
+                rp[i] = (f < kTR * MP / 8) ? load8(P, ldp, r0 + r, r_end, R, 8 * q, Mp, false) : make_uint4(0, 0, 0, 0);
+            }
+        }
+        if (MASK == 2) {                                              // descriptor in words: rows past the chunk read 0
+            const int64_t left = r_end - r0;
+            const int64_t rows = left < kTR ? left : kTR;
+            zb = buffer_load1(buffer_of(Zbits + r0 * ldz, rows > 0 ? (uint32_t)(((rows - 1) * ldz + (N + 31) / 32) * 4) : 0u), ob);
         }
     };
+    uint32_t ooff[1];                                                 // write-out of a wavefront's staged 16 x 16*NCW block
+    ooff[0] = stage_offset<16 * NCW>(lane, 16, ldo, 16 * cb0, Mp);
+    static_assert(16 * (16 * NCW / 8) <= 64, "one piece per lane");
     auto commit = [&]() {
 #pragma unroll
         for (int i = 0; i < NQ; ++i) {
@@ -363,10 +481,14 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
                 for (int e = 0; e < 8; ++e)
                     if (!bf16_positive(z.e[e])) v.e[e] = 0;
             } else if (MASK == 2) {
-                const uint32_t b = __shfl(zb, (lane >> 2) + 16 * i) >> (8 * (tid & 3));
+                // two elements per word: bits e and e + 1 of the byte, each spread over its half-word
+                const int b = (int)__shfl(zb, (lane >> 2) + 16 * i);
+                const unsigned s0 = 8 * (tid & 3);
+                u32x4 m;
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (!(b >> e & 1u)) v.e[e] = 0;
+                for (int e = 0; e < 4; ++e)
+                    m[e] = ((unsigned)__builtin_amdgcn_sbfe(b, s0 + 2 * e, 1) & 0xffffu) | ((unsigned)__builtin_amdgcn_sbfe(b, s0 + 2 * e + 1, 1) & 0xffff0000u);
+                v.x &= m;
             }
             if (f < kTR * NP / 8) *reinterpret_cast<uint4*>(Qs + r * SQ + 8 * q) = v.u;
         }
@@ -420,7 +542,8 @@ __global__ __launch_bounds__(256) void k_bwd_dense_bf16(int64_t R, int Mp, int N
                 for (int c = 0; c < NCW; ++c)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) stage[(4 * lq + r) * SO + 16 * c + l16] = f32_to_bf16(acc_o[rr][c][r]);
-                stage_store<16 * NCW>(stage, 16, dOut, ldo, r0 + 16 * (rb0 + rbs * rr), r_end, 16 * cb0, Mp, vec_o, lane);
+                if (vec_o) stage_store_buf<16 * NCW, 1>(stage, 16, dOut, ldo, r0 + 16 * (rb0 + rbs * rr), r_end, 16 * cb0, Mp, ooff, lane);
+                else stage_store<16 * NCW>(stage, 16, dOut, ldo, r0 + 16 * (rb0 + rbs * rr), r_end, 16 * cb0, Mp, false, lane);
             }
         }
         __syncthreads();
@@ -473,6 +596,9 @@ plx_status launch_gemm_small_bf16(plx_ctx* ctx, int64_t M, int64_t N, int64_t K,
                                   const float* W, int64_t ldw, void* C, int64_t ldc, void* Fact, int64_t ldf,
                                   uint32_t* bits, int64_t ldbits) {
     if (K > 128 || N > 128 || K <= 0) return fail(ctx, PLX_ERR_UNSUPPORTED, "bf16 dense products are built for widths up to 128");
+    // a tile (up to 128 rows) is addressed with 31-bit byte offsets
+    if (lda >= (int64_t(1) << 23) || (C && ldc >= (int64_t(1) << 23)) || (Fact && ldf >= (int64_t(1) << 23)))
+        return fail(ctx, PLX_ERR_UNSUPPORTED, "leading dimensions of 2^23 elements or more are not supported by the bf16 dense kernels");
     const int tkb = K <= 32 ? 1 : (K <= 64 ? 2 : 4), tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     const int rb = tnb == 1 ? 4 : 2, rows = 32 * rb;
     const size_t lds = sizeof(bf16_t) * (2 * rows * (32 * tkb + 8) + 4 * 32 * 40) + (bits ? 2 * 4 * rows * 4 : 0);
