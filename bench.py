@@ -297,7 +297,12 @@ def main():
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": measured_traffic(dominant) if (args.scale == 1.0 and args.workload == "shard" and args.dtype == "f32") else None,
                 "algorithmic_bytes_per_launch": int(d_bytes), "avg_launch_ms": round(d_avg, 4)}
-    if achieved > HBM_PEAK_GBS:
+    if kernels[dominant].get("binding") == "mfma":     # a dense product nearer its matrix-core peak than its HBM peak
+        peak = MFMA_PEAK_TFLOPS["bf16" if "<bf16>" in dominant else "f32"]
+        tf = cost[dominant][1] / d_avg / 1e9
+        roofline.update({"bound": "mfma", "achieved": round(tf, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
+                         "algorithmic_flops_per_launch": int(cost[dominant][1])})
+    if roofline["bound"] == "hbm" and achieved > HBM_PEAK_GBS:
         roofline["note"] = ("above the HBM peak: the algorithmic count charges one operand row per stored entry, but the "
                             "column windows (or an operand that fits the Infinity Cache) serve part of the gathers from cache")
     # all sparse-product kernels together, the figure the metric names

@@ -492,7 +492,9 @@ plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
     void* tn_ws = base + w.off_tn;
     size_t tn_bytes = w.total - w.off_tn;
     const void* mask = act != PLX_ACT_NONE ? Z : nullptr;
-    if (bwd_dense_supported(din, dout, dtype)) {
+    // the fused kernels address a tile with 31-bit byte offsets; wider leading dimensions take the separate products
+    const int64_t ld_max = std::max(std::max(ldsaved, ldh), std::max(std::max(lddf, ldz), lddh));
+    if (bwd_dense_supported(din, dout, dtype) && (ld_max < (int64_t(1) << 23) || dtype == PLX_BF16)) {
         // Eq. 2.4 is applied while the gradient tile is loaded; it is never written back
         if (order == PLX_ORDER_AGG_FIRST) {
             void* dS = dH ? base + w.off_a : nullptr;

@@ -539,6 +539,42 @@ def test_layer_sign_bits(ctx, din, dout, dtype):
         assert rel_err(outs[0][0].float(), dX) <= tol
 
 
+def test_layer_very_wide_leading_dimension(ctx):
+    """Rows 2^23 elements apart: the small-width dense kernels address a tile with 31-bit byte offsets
+    and hand such matrices to the kernels with 64-bit addressing; results must not change."""
+    m, k, din, dout, ld = 6, 7, 8, 12, 1 << 23
+    rowptr, col, val = random_block(m, k, 9, empty_rows=False)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(4)
+    X = r.standard_normal((k, din)).astype(np.float32)
+    W = (r.standard_normal((din, dout)) * 0.3).astype(np.float32)
+    dFn = r.standard_normal((m, dout)).astype(np.float32)
+    Hagg = oracle.spmm_coo(m, row, c64, v64, X)
+    Q = oracle.gemm(Hagg, W)
+    dQ = oracle.relu_bwd(Q, dFn)
+    dW = oracle.gemm(Hagg, dQ, ta=True)
+    dX = oracle.spmm_t_coo(k, row, c64, v64, oracle.gemm(dQ, W, tb=True))
+
+    def wide(rows, cols, src=None):
+        t = torch.empty(rows, ld, device=DEV)[:, :cols]
+        if src is not None:
+            t.copy_(torch.as_tensor(src))
+        return t
+
+    for order in (plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_COMBINE_FIRST):
+        ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, order=order), dtype=torch.uint8, device=DEV)
+        Xw, F, saved, dFw, gdX = wide(k, din, X), wide(m, dout), wide(m, din), wide(m, dout, dFn), wide(k, din)
+        gdW = torch.empty(din, dout, device=DEV)
+        plx.plx_gcn_layer_fwd(ctx, csr, False, Xw, dev(W), None, F, saved, ws, order=order)
+        plx.plx_gcn_layer_bwd(ctx, csr, False, Xw, dev(W), F, dFw, saved, gdX, gdW, ws, order=order)
+        plx.plx_sync(ctx)
+        assert rel_err(F, oracle.relu(Q)) <= TOL32
+        assert rel_err(gdW, dW) <= TOL32
+        assert rel_err(gdX, dX) <= TOL32
+        del Xw, F, saved, dFw, gdX
+
+
 def test_layer_sign_bits_argument_errors(ctx):
     m, k, din, dout = 40, 50, 8, 40
     rowptr, col, val = random_block(m, k, 2)
