@@ -61,7 +61,7 @@ typedef enum { PLX_ACT_NONE = 0, PLX_ACT_RELU = 1, PLX_ACT_RELU_BITS = 2 } plx_a
 typedef enum {
     PLX_ORDER_COMBINE_FIRST = 0, /* Z = A^ (H W): the sparse product runs at the output width    */
     PLX_ORDER_AGG_FIRST = 1,     /* Z = (A^ H) W: the order of Eq. 2.1 -> 2.2                      */
-    PLX_ORDER_AUTO = 2           /* whichever runs the sparse product at min(d_in, d_out)         */
+    PLX_ORDER_AUTO = 2           /* whichever runs the sparse product at min(d_in, d_out); AGG_FIRST on a tie */
 } plx_order;
 
 /* Device-memory allocator hooks (e.g. bound to a framework's caching allocator).  `alloc`
@@ -209,8 +209,10 @@ PLX_API plx_status plx_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void
  *   order AGG_FIRST : saved[ma x din] = A H (Eq. 2.1) then Z = saved W (Eq. 2.2); `saved` must
  *                     be given and is needed again by the backward call.
  *   order COMBINE_FIRST: T[ka x dout] = H W in the workspace, then Z = A T; `saved` is unused.
- *   order AUTO      : AGG_FIRST if din < dout, else COMBINE_FIRST (so `saved` must be given
- *                     whenever din < dout).
+ *   order AUTO      : AGG_FIRST if din <= dout, else COMBINE_FIRST (so `saved` must be given
+ *                     whenever din <= dout).  At equal widths both orders move the same bytes
+ *                     through the sparse product, and aggregate-first applies Eq. 2.4 inside the
+ *                     fused backward kernel instead of in a pass of its own.
  *   act RELU_BITS   : as RELU, but all the backward call needs of Z is kept, one bit per element: Z
  *                     (4-byte aligned, both Z and F required) receives uint32 words, ldz counts
  *                     words per row (>= ceil(dout / 32)); bit j % 32 of word j / 32 of row i is

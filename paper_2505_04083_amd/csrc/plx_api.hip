@@ -359,7 +359,7 @@ plx_status plx_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, int
 // ---- one GCN layer ------------------------------------------------------------------------------
 
 static plx_order resolve_order(plx_order order, int64_t din, int64_t dout) {
-    if (order == PLX_ORDER_AUTO) return din < dout ? PLX_ORDER_AGG_FIRST : PLX_ORDER_COMBINE_FIRST;
+    if (order == PLX_ORDER_AUTO) return din <= dout ? PLX_ORDER_AGG_FIRST : PLX_ORDER_COMBINE_FIRST;
     return order;
 }
 

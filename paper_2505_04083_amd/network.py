@@ -33,7 +33,7 @@ class GcnNetwork:
         self.act = [PLX_ACT_RELU if l + 1 < self.L else PLX_ACT_NONE for l in range(self.L)]
         for l, W in enumerate(Ws[:-1]):
             din, dout = W.shape
-            agg_first = order == 1 or (order == PLX_ORDER_AUTO and din < dout)
+            agg_first = order == 1 or (order == PLX_ORDER_AUTO and din <= dout)
             if sign_bits and not keep_preactivation and agg_first and max(din, dout) <= 128:
                 self.act[l] = PLX_ACT_RELU_BITS
         nbytes = 1
@@ -54,7 +54,7 @@ class GcnNetwork:
             else:
                 self.Z.append(_matrix(rows, dout, dtype, dev) if (last or keep_preactivation) else None)
             self.F.append(None if last else _matrix(rows, dout, dtype, dev))
-            agg_first = order == 1 or (order == PLX_ORDER_AUTO and din < dout)
+            agg_first = order == 1 or (order == PLX_ORDER_AUTO and din <= dout)
             self.saved.append(_matrix(rows if agg_first else 1, din, dtype, dev))
             self.dH.append(_matrix(cols, din, dtype, dev))
             self.dW.append(torch.empty(din, dout, dtype=torch.float32, device=dev))

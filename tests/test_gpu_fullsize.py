@@ -180,7 +180,7 @@ def test_graph_workloads_full_size(name, layer):
     W = synth.glorot(cfg.seed, layer, din, dout, DEV)
     ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout), dtype=torch.uint8, device=DEV)
     F = torch.empty(cfg.n, dout, device=DEV)
-    saved = torch.empty(cfg.n if din < dout else 1, din, device=DEV)
+    saved = torch.empty(cfg.n if din <= dout else 1, din, device=DEV)
     plx.plx_gcn_layer_fwd(ctx, csr, False, H, W, None, F, saved, ws)
     plx.plx_sync(ctx)
     need = np.unique(np.concatenate([rows[int(i)][0] for i in S])).astype(np.int64)      # operand rows the samples touch
@@ -191,7 +191,7 @@ def test_graph_workloads_full_size(name, layer):
     Q = oracle.gemm(Hagg, Wd)                                                                       # Eq. 2.2
     Sd = torch.as_tensor(S, device=DEV)
     assert rel_err(F[Sd], oracle.relu(Q)) <= TOL32
-    if din < dout:
+    if din <= dout:
         assert rel_err(saved[Sd], Hagg) <= TOL32
 
     dFs = r.standard_normal((len(S), dout)).astype(np.float32)
