@@ -151,6 +151,54 @@ __global__ __launch_bounds__(256) void k_softmax_ce(int64_t n, int c, const T* _
     if (t == 0) row_loss[i] = -(widen(z[label]) - mx - logf(sum));
 }
 
+// fp32 rows that are 16-byte aligned: lane t of a group of GS lanes holds classes 4t .. 4t+3 as one
+// 128-bit load and writes its part of the gradient as one 128-bit store (c <= 4 * GS)
+template <int GS>
+__global__ __launch_bounds__(256) void k_softmax_ce_v4(int64_t n, int c, const float* __restrict__ Z, int64_t ldz,
+                                                       const int64_t* __restrict__ y, float* __restrict__ dZ, int64_t lddz,
+                                                       float* __restrict__ row_loss, float inv_n) {
+    const int t = threadIdx.x % GS, j0 = 4 * t;
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / GS;
+    const bool live = i < n;
+    const float* z = Z + (live ? i : 0) * ldz;
+    float v[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    if (live && j0 + 3 < c) {
+        const float4 q = *reinterpret_cast<const float4*>(z + j0);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    } else if (live) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (j0 + e < c) v[e] = z[j0 + e];
+    }
+    float mx = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
+#pragma unroll
+    for (int off = GS / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, GS));
+    float sum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        v[e] = (j0 + e < c) ? expf(v[e] - mx) : 0.f;
+        sum += v[e];
+    }
+#pragma unroll
+    for (int off = GS / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off, GS);
+    if (!live) return;
+    const float inv = 1.f / sum;
+    int64_t label = y[i];
+    label = label < 0 ? 0 : (label >= c ? c - 1 : label);   // out-of-range labels are clamped
+    float* g = dZ + i * lddz;
+    float o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (v[e] * inv - (j0 + e == label ? 1.f : 0.f)) * inv_n;
+    if (j0 + 3 < c) {
+        *reinterpret_cast<float4*>(g + j0) = make_float4(o[0], o[1], o[2], o[3]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (j0 + e < c) g[j0 + e] = o[e];
+    }
+    if (t == 0) row_loss[i] = -(z[label] - mx - logf(sum));
+}
+
 // Fixed-order sum: the live slots are `stride` apart; block b adds the 2048 live slots of its range
 // (8 per thread, then a tree in LDS) into the first of them.  Repeated until one slot is left.
 __global__ __launch_bounds__(256) void k_sum_level(float* v, int64_t n_live, int64_t stride, float* out, float scale) {
@@ -269,6 +317,14 @@ plx_status launch_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, 
     char label[64];
     snprintf(label, sizeof label, "softmax_ce[R%lld,C%lld]", (long long)n, (long long)c);
     KernelTimer kt(ctx, label);
+    if (dtype == PLX_F32 && c <= 256 && ldz % 4 == 0 && lddz % 4 == 0 && aligned16(Z) && aligned16(dZ)) {
+        const int q = (int)ceil_div(c, 4);
+        const int g4 = q <= 4 ? 4 : (q <= 8 ? 8 : (q <= 16 ? 16 : (q <= 32 ? 32 : 64)));
+        dim3 grid4((unsigned)ceil_div(n * g4, 256));
+#define PLX_SM4(GSV) k_softmax_ce_v4<GSV><<<grid4, 256, 0, s>>>(n, (int)c, (const float*)Z, ldz, y, (float*)dZ, lddz, row_loss, inv_n)
+        if (g4 == 4) PLX_SM4(4); else if (g4 == 8) PLX_SM4(8); else if (g4 == 16) PLX_SM4(16); else if (g4 == 32) PLX_SM4(32); else PLX_SM4(64);
+#undef PLX_SM4
+    } else {
     const int gs = c <= 32 ? 8 : (c <= 64 ? 16 : (c <= 128 ? 32 : 64));
     dim3 grid((unsigned)ceil_div(n * gs, 256));
 #define PLX_SM(TT, GSV) \
@@ -279,6 +335,7 @@ plx_status launch_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, 
         if (gs == 8) PLX_SM(bf16_t, 8); else if (gs == 16) PLX_SM(bf16_t, 16); else if (gs == 32) PLX_SM(bf16_t, 32); else PLX_SM(bf16_t, 64);
     }
 #undef PLX_SM
+    }
     if (loss) {
         int64_t live = n, stride = 1;
         while (true) {

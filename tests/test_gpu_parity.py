@@ -338,6 +338,27 @@ def test_elementwise_parity(ctx):
     assert abs(loss.item() - ref_loss) / ref_loss <= TOL32
 
 
+@pytest.mark.parametrize("c", [1, 5, 16, 41, 47, 128, 130, 257, 1000])
+@pytest.mark.parametrize("padded", [False, True])
+def test_softmax_ce_widths_and_layouts(ctx, c, padded):
+    """Loss head (Sec. 2.1) over class counts on both sides of every lane-group size, in contiguous
+    rows (the scalar kernel unless c is a multiple of 4) and in rows padded to 16 bytes (the 128-bit
+    kernel up to 256 classes); the padding holds NaN on input and must stay untouched on output."""
+    n = 1237
+    r = np.random.default_rng(c)
+    Z = (r.standard_normal((n, c)) * 4).astype(np.float32)
+    y = r.integers(0, c, n)
+    ld = -(-c // 4) * 4 + (4 if padded else 0) if padded else c
+    Zd = torch.full((n, ld), float("nan"), device=DEV); Zd[:, :c] = dev(Z)
+    g = torch.full((n, ld), 7.0, device=DEV)
+    loss = torch.zeros(1, device=DEV)
+    plx.plx_softmax_ce(ctx, Zd[:, :c], dev(y), g[:, :c], loss=loss); plx.plx_sync(ctx)
+    ref_loss, ref_g = oracle.softmax_ce(Z.astype(np.float64), y)
+    assert rel_err(g[:, :c], ref_g) <= TOL32
+    assert abs(loss.item() - ref_loss) <= TOL32 * max(1.0, abs(ref_loss))
+    assert bool((g[:, c:] == 7.0).all())
+
+
 @pytest.mark.parametrize("order", [plx.PLX_ORDER_COMBINE_FIRST, plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_AUTO])
 def test_three_layer_network_parity(ctx, order):
     """configs[0]: R-MAT N=4096, 65,536 edges, 128-128-128-16, one forward + backward, against
