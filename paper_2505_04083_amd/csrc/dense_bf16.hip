@@ -592,6 +592,10 @@ plx_status run_bwd(plx_ctx* ctx, int64_t R, int Mp, int N, const bf16_t* P, int6
 
 }  // namespace
 
+#ifndef PLX_BF16_FWD_CAP
+#define PLX_BF16_FWD_CAP 3            // resident workgroups per CU of the forward kernel (0: as many as fit); measured: 3 is
+                                      // 5 % faster than 4+ at 32 -> 128 and 19 % faster at 64 -> 128, equal elsewhere; 2 is slower
+#endif
 plx_status launch_gemm_small_bf16(plx_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                                   const float* W, int64_t ldw, void* C, int64_t ldc, void* Fact, int64_t ldf,
                                   uint32_t* bits, int64_t ldbits) {
@@ -616,6 +620,7 @@ plx_status launch_gemm_small_bf16(plx_ctx* ctx, int64_t M, int64_t N, int64_t K,
         PLX_TRY(set_lds(ctx, kern, lds));                                                                       \
         int per_cu = 0;                                                                                         \
         PLX_HIP(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds));                    \
+        if (PLX_BF16_FWD_CAP > 0) per_cu = std::min(per_cu, PLX_BF16_FWD_CAP);                                  \
         const int64_t blocks = std::min<int64_t>(ceil_div(M, rows), (int64_t)ctx->n_cu * std::max(1, per_cu));  \
         kern<<<dim3((unsigned)blocks), 256, lds, ctx->stream>>>(M, (int)N, (int)K, (const bf16_t*)A, lda, W, ldw, \
                                                                (bf16_t*)C, ldc, (bf16_t*)Fact, ldf, bits, ldbits, \

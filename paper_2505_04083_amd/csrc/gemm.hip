@@ -609,10 +609,12 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             int per_cu = 0;                    // resident workgroups per CU for this kernel's registers and LDS
             PLX_HIP(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds));
-#ifndef PLX_FWD_WIDE_CAP
-#define PLX_FWD_WIDE_CAP 3
+#ifndef PLX_FWD_WIDE_CAP_K32
+#define PLX_FWD_WIDE_CAP_K32 2
 #endif
-            if (cb > 4) per_cu = std::min(per_cu, PLX_FWD_WIDE_CAP);   // measured: a 4th resident workgroup slows the store-bound K = 32 case by 5 %
+            // measured: the store-bound K <= 32 case is fastest with 2 resident workgroups per CU (3: +4 %, 4: +8 %),
+            // the matrix-bound K >= 64 cases with as many as fit (4)
+            if (cb > 4 && tkb == 1) per_cu = std::min(per_cu, PLX_FWD_WIDE_CAP_K32);
             const int64_t blocks = std::min<int64_t>(ceil_div(M, tr), (int64_t)ctx->n_cu * std::max(1, per_cu));
             kern<<<dim3((unsigned)blocks), 256, lds, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf, bits, ldbits, bits_vec);
             return PLX_OK;
