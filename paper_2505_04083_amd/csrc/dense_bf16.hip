@@ -333,16 +333,21 @@ __global__ __launch_bounds__(256) void k_gemm_small_bf16(int64_t M, int N, int K
                 if (vec_f) stage_store_buf<32, 2>(stage, 32, F, ldf, m0 + 32 * bi, M, 32 * bj, N, foff, lane);
                 else stage_store<32>(stage, 32, F, ldf, m0 + 32 * bi, M, 32 * bj, N, false, lane);
                 if (bits) {    // one ballot = 32 columns of two rows (lanes 0-31, lanes 32-63); max(v, 0) rounds to 0 or to a positive value
+                    // the ballots are wave-uniform: lane 0 stores both halves, 8 consecutive rows per step
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
-                        uint32_t wv[4];
+                        uint32_t lo[4], hi[4];
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             const unsigned long long b = __ballot((h[4 * g + j] & 0x7fffu) != 0);
-                            wv[j] = lh ? (uint32_t)(b >> 32) : (uint32_t)b;
+                            lo[j] = (uint32_t)b;
+                            hi[j] = (uint32_t)(b >> 32);
                         }
-                        if (l32 == 0)
-                            *reinterpret_cast<uint4*>(&sb[(cur * 4 + bj) * ROWS + 32 * bi + 8 * g + 4 * lh]) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
+                        if (lane == 0) {
+                            uint4* dst = reinterpret_cast<uint4*>(&sb[(cur * 4 + bj) * ROWS + 32 * bi + 8 * g]);
+                            dst[0] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                            dst[1] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                        }
                     }
                 }
             }

@@ -348,18 +348,24 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
                 if (full) emit_cf(std::false_type{}); else emit_cf(std::true_type{});
             }
             if (bits) {       // one ballot = 32 columns of two rows (lanes 0-31: row dr, lanes 32-63: row dr + 4); columns >= N give 0
+                // the ballots are wave-uniform (scalar registers): lane 0 alone stores both halves, 8 consecutive rows per step
+                // (a per-lane choice between the halves turns into 64-bit vector shifts)
 #pragma unroll
                 for (int t = 0; t < NRB; ++t)
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
-                        uint32_t wv[4];
+                        uint32_t lo[4], hi[4];
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             const unsigned long long b = __ballot(acc[t][4 * g + j] > 0.f);
-                            wv[j] = lh ? (uint32_t)(b >> 32) : (uint32_t)b;
+                            lo[j] = (uint32_t)b;
+                            hi[j] = (uint32_t)(b >> 32);
                         }
-                        if (l32 == 0)
-                            *reinterpret_cast<uint4*>(&sb[(cur * 4 + w) * TR + 32 * t + 8 * g + 4 * lh]) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
+                        if (lane == 0) {
+                            uint4* dst = reinterpret_cast<uint4*>(&sb[(cur * 4 + w) * TR + 32 * t + 8 * g]);
+                            dst[0] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                            dst[1] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                        }
                     }
             }
         } else {
