@@ -87,6 +87,13 @@ PLX_API const char* plx_status_string(plx_status s);
  * only rows of 4096 entries and more are split).  Applies to handles built or re-blocked AFTER the
  * call.  1 <= n_windows <= 64, else PLX_ERR_INVALID. */
 PLX_API plx_status plx_ctx_set_column_windows(plx_ctx* ctx, int n_windows);
+/* fp32 dense products whose two small dimensions are both 64 or more are bound by the fp32 matrix
+ * pipe.  By default (on != 0) they are computed through the bf16 matrix instructions instead: every
+ * fp32 operand is the exact sum of three bf16 numbers, and six of the nine bf16 products (all terms
+ * down to 2^-23 of the product, i.e. fp32 rounding) are accumulated in fp32, 2.7 times faster than
+ * the fp32 instructions.  Results agree with the plain fp32 path to fp32 rounding but not bit for
+ * bit; an infinite input turns into NaN.  on == 0 selects the plain fp32 instructions everywhere. */
+PLX_API plx_status plx_ctx_set_split_products(plx_ctx* ctx, int on);
 PLX_API plx_status plx_sync(plx_ctx* ctx);                /* wait for the context's stream */
 
 /* Optional per-kernel timing for benchmarks.  While enabled, every kernel the library

@@ -21,50 +21,12 @@
 // bytes (8 bf16) with one non-temporal store instead of eight 2-byte stores.
 #include "plx_internal.h"
 #include "buffer_addr.h"
+#include "bf16_frag.h"
 
 #include <algorithm>
 
 namespace plx {
 namespace {
-
-typedef uint16_t bf16_t;
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-#define PLX_LDS __attribute__((address_space(3)))
-
-union Frag {
-    uint4 u;
-    u32x4 x;
-    bf16x8 v;
-    bf16x4_t h[2];
-    bf16_t e[8];
-};
-
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {   // round to nearest even: one v_cvt_pk_bf16_f32
-    return __builtin_bit_cast(bf16_t, (__bf16)f);
-}
-__device__ __forceinline__ bool bf16_positive(bf16_t z) { return (z & 0x8000u) == 0 && (z & 0x7fffu) != 0 && (z & 0x7fffu) <= 0x7f80u; }
-
-// 8 consecutive bf16 of one row (16 bytes)
-__device__ __forceinline__ bf16x8 frag_contig(const bf16_t* p) {
-    Frag f;
-    f.u = *reinterpret_cast<const uint4*>(p);
-    return f.v;
-}
-
-// Column fragment of a row-major LDS tile for a 32x32x16 operand: lane l receives rows
-// k0 + 8*(l/32) .. +7 of column c0 + l%32.  Two transpose reads of 4 rows each.
-__device__ __forceinline__ bf16x8 frag_column(const bf16_t* tile, int pitch, int k0, int c0, int lane) {
-    const int L = lane & 15, half = (lane >> 4) & 1, lh = lane >> 5;
-    const bf16_t* p = tile + (k0 + 8 * lh + (L >> 2)) * pitch + c0 + 16 * half + 4 * (L & 3);
-    Frag f;
-    f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((PLX_LDS bf16x4_t*)(p));
-    f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((PLX_LDS bf16x4_t*)(p + 4 * pitch));
-    return f.v;
-}
 
 // guarded load of 8 consecutive bf16 of a global row (zero beyond ncols / the last row).  With
 // vec (16-byte aligned base and leading dimension) a chunk that straddles ncols still lies inside

@@ -18,6 +18,7 @@
 // Chunk partials of dW are summed afterwards in a fixed order (bit-reproducible).
 #include "plx_internal.h"
 #include "buffer_addr.h"
+#include "bf16_frag.h"
 
 #include <algorithm>
 
@@ -294,16 +295,218 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
     }
 }
 
+// ---- the same pass with the fp32 products taken through the bf16 matrix instructions ----------------
+// An fp32 value is the exact sum of three bf16 numbers (each rounded to nearest even from what the
+// others leave: 8 + 8 + 8 significand bits), and a product of two bf16 numbers is exact in fp32.
+// With a = a1 + a2 + a3 and b = b1 + b2 + b3, the six products a1 b1, a1 b2, a2 b1, a2 b2, a1 b3,
+// a3 b1 carry a b up to terms below 2^-23 |a b|, i.e. to fp32 rounding; accumulation is fp32 inside
+// the matrix instruction as before.  Six bf16 instructions cover 16 (32) values of k in the time the
+// fp32 instruction needs for 3 (6): where the fp32 matrix pipe binds (both widths 64 or more) this
+// path is taken instead (an infinite input gives NaN here, inf - inf, where the plain product gives inf).
+// The tiles are split once, when they are written to LDS as three bf16 planes.
+// registers -> three bf16 planes of an LDS tile [3][TR][COLS + 8], masked like commit_tile
+template <int TR, int COLS, int MASK>
+__device__ __forceinline__ void commit_split(bf16_t* dst, const TileRegs<TR, COLS>& t, const TileRegs<TR, COLS>& m,
+                                             const TileBits<TR, COLS>& mb, int tid) {
+    constexpr int Q4 = COLS / 4, PITCH = COLS + 8, PLANE = TR * PITCH;
+#pragma unroll
+    for (int i = 0; i < TR * COLS / 1024; ++i) {
+        const int f = tid + 256 * i, r = f / Q4, q = f % Q4;
+        float4 v = t.v[i];
+        if (MASK == kMaskValues) {
+            const float4 z = m.v[i];
+            v.x = z.x > 0.f ? v.x : 0.f; v.y = z.y > 0.f ? v.y : 0.f;
+            v.z = z.z > 0.f ? v.z : 0.f; v.w = z.w > 0.f ? v.w : 0.f;
+        } else if (MASK == kMaskBits) {
+            const int b = (int)__shfl(mb.w, ((tid & 63) >> 3) + 8 * i);
+            const unsigned s0 = 4 * (tid & 7);
+            v.x = __uint_as_float(__float_as_uint(v.x) & (unsigned)__builtin_amdgcn_sbfe(b, s0, 1));
+            v.y = __uint_as_float(__float_as_uint(v.y) & (unsigned)__builtin_amdgcn_sbfe(b, s0 + 1, 1));
+            v.z = __uint_as_float(__float_as_uint(v.z) & (unsigned)__builtin_amdgcn_sbfe(b, s0 + 2, 1));
+            v.w = __uint_as_float(__float_as_uint(v.w) & (unsigned)__builtin_amdgcn_sbfe(b, s0 + 3, 1));
+        }
+        uint2 pl[3];
+        split3(v, pl);
+#pragma unroll
+        for (int p = 0; p < 3; ++p) *reinterpret_cast<uint2*>(dst + p * PLANE + r * PITCH + 4 * q) = pl[p];
+    }
+}
+
+#ifndef PLX_X3_BWD_WAVES
+#define PLX_X3_BWD_WAVES 2
+#endif
+template <int TMB, int TNB, int MASK>   // 64 <= Mp <= 32*TMB, 64 <= N <= 32*TNB (TMB, TNB in {2, 4}); 16-byte aligned rows
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_BWD_WAVES))) void k_bwd_dense_x3(int64_t R, int Mp, int N, const float* __restrict__ P, int64_t ldp,
+                                                      const float* __restrict__ Q, int64_t ldq,
+                                                      const float* __restrict__ Zm, int64_t ldz,
+                                                      const float* __restrict__ W, int64_t ldw,
+                                                      float* __restrict__ dOut, int64_t ldo, float* __restrict__ part,
+                                                      int64_t rows_per_chunk) {
+    constexpr int MP = 32 * TMB, NP = 32 * TNB, SQ = NP + 8, SP = MP + 8;
+    constexpr int NBLK = TMB * TNB / 4;                       // 32x32 blocks of dW per wavefront (block q belongs to wavefront q % 4)
+    constexpr int NCW = MP / 64, NRW = kTR / 16, NKS = NP / 32;   // dOut: NCW column blocks of 16 per wavefront, both row blocks
+    static_assert(TMB >= 2 && TNB >= 2 && kTR == 32, "shapes of the split path");
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    bf16_t* Qs = reinterpret_cast<bf16_t*>(smem_raw);         // [3][kTR][SQ]
+    bf16_t* Ps = Qs + 3 * kTR * SQ;                           // [3][kTR][SP]
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lh = lane >> 5, l16 = lane & 15, lq = lane >> 4;
+    const int cb0 = w * NCW;
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_chunk;
+    const int64_t r_end = (r_begin + rows_per_chunk < R) ? r_begin + rows_per_chunk : R;
+
+    bf16x8 wreg[NCW][NKS][3];              // planes of W[16*(cb0+c) + l16][32s + 8*lq .. +7]
+#pragma unroll
+    for (int c = 0; c < NCW; ++c) {
+        const int i = 16 * (cb0 + c) + l16;
+#pragma unroll
+        for (int s2 = 0; s2 < NKS; ++s2) {
+            Frag f[3];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int n = 32 * s2 + 8 * lq + 4 * h;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (dOut && i < Mp) {
+                    const float* wp = W + (int64_t)i * ldw + n;
+                    if (n < N) v.x = wp[0];
+                    if (n + 1 < N) v.y = wp[1];
+                    if (n + 2 < N) v.z = wp[2];
+                    if (n + 3 < N) v.w = wp[3];
+                }
+                uint2 pl[3];
+                split3(v, pl);
+#pragma unroll
+                for (int p = 0; p < 3; ++p) { f[p].x[2 * h] = pl[p].x; f[p].x[2 * h + 1] = pl[p].y; }
+            }
+#pragma unroll
+            for (int p = 0; p < 3; ++p) wreg[c][s2][p] = f[p].v;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // weights landed before the row loop (vmcnt(0))
+
+    floatx16 acc_w[NBLK];
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_w[t][r] = 0.f;
+
+    TileRegs<kTR, NP> rq, rz;
+    TileRegs<kTR, MP> rp;
+    TileBits<kTR, NP> zb;
+    TileBits<kTR, MP> nb;                  // never read
+    TileOffs<kTR, NP> oq, oz;
+    TileOffs<kTR, MP> op;
+    tile_offsets<kTR, NP>(oq, ldq, N, tid);
+    if (MASK == kMaskValues) tile_offsets<kTR, NP>(oz, ldz, N, tid);
+    tile_offsets<kTR, MP>(op, ldp, Mp, tid);
+    const uint32_t* Zbits = reinterpret_cast<const uint32_t*>(Zm);
+    const uint32_t ob = MASK == kMaskBits ? bits_offset<kTR, NP>(ldz, N, tid) : 0u;
+    auto fetch = [&](int64_t r0) {
+        fetch_tile<kTR, NP, true>(rq, Q, ldq, r0, r_end, R, N, tid, oq);
+        if (MASK == kMaskValues) fetch_tile<kTR, NP, true>(rz, Zm, ldz, r0, r_end, R, N, tid, oz);
+        if (MASK == kMaskBits) fetch_bits<kTR, NP>(zb, Zbits, ldz, r0, r_end, N, ob);
+        fetch_tile<kTR, MP, true>(rp, P, ldp, r0, r_end, R, Mp, tid, op);
+    };
+    fetch(r_begin);
+    commit_split<kTR, NP, MASK>(Qs, rq, rz, zb, tid);
+    commit_split<kTR, MP, kMaskNone>(Ps, rp, rp, nb, tid);
+    __syncthreads();
+
+    const int n_end = (N + 31) & ~31;
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += kTR) {
+        fetch(r0 + kTR < r_end ? r0 + kTR : r0);                       // unconditional: the last pass re-reads its own tile
+
+        floatx4 acc_o[NRW][NCW];
+        if (dOut) {                                                    // Eq. 2.6 on this tile
+#pragma unroll
+            for (int rr = 0; rr < NRW; ++rr)
+#pragma unroll
+                for (int c = 0; c < NCW; ++c) acc_o[rr][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s2 = 0; s2 < NKS; ++s2) {
+                if (32 * s2 >= n_end) break;                           // uniform
+#pragma unroll
+                for (int rr = 0; rr < NRW; ++rr) {
+                    bf16x8 a[3];
+#pragma unroll
+                    for (int p = 0; p < 3; ++p) a[p] = frag_contig(Qs + p * kTR * SQ + (16 * rr + l16) * SQ + 32 * s2 + 8 * lq);
+#pragma unroll
+                    for (int c = 0; c < NCW; ++c) PLX_X3_16(acc_o[rr][c], a, wreg[c][s2]);
+                }
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < kTR; kk += 16) {                         // Eq. 2.5: 16 rows of the tile per instruction
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) {
+                const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
+                bf16x8 a[3], b[3];
+#pragma unroll
+                for (int p = 0; p < 3; ++p) {
+                    a[p] = frag_column(Ps + p * kTR * SP, SP, kk, 32 * bi, lane);
+                    b[p] = frag_column(Qs + p * kTR * SQ, SQ, kk, 32 * bj, lane);
+                }
+                PLX_X3_32(acc_w[t], a, b);
+            }
+        }
+        __syncthreads();                                               // every wavefront is done reading the tile
+        commit_split<kTR, NP, MASK>(Qs, rq, rz, zb, tid);
+        commit_split<kTR, MP, kMaskNone>(Ps, rp, rp, nb, tid);
+        if (dOut) {
+            const bool full = r0 + kTR <= r_end;                       // uniform: only the last tile is partial
+            const __amdgpu_buffer_rsrc_t ro = buffer_of(dOut + r0 * ldo, (uint32_t)(((kTR - 1) * ldo + Mp) * 4));
+#pragma unroll
+            for (int rr = 0; rr < NRW; ++rr) {
+                const int row0 = 16 * rr;                              // uniform; the lane's rows are row0 + 4*lq + r
+                uint32_t orow = opaque_zero() + (uint32_t)row0 * (uint32_t)ldo * 4u;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+#pragma unroll
+                    for (int c = 0; c < NCW; ++c) {
+                        const int gc = 16 * (cb0 + c) + l16;
+                        const uint32_t ooff = gc < Mp ? (uint32_t)((4u * lq * (uint32_t)ldo + gc) * 4u) : kOutOfRange;
+                        if (full || r0 + row0 + 4 * lq + r < r_end) buffer_store(ro, ooff, orow, acc_o[rr][c][r]);
+                    }
+                    orow += (uint32_t)ldo * 4u;
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    float* out = part + (int64_t)blockIdx.x * Mp * N;
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t) {
+        const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
+        const int gn = 32 * bj + l32;
+        if (gn >= N) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int gm = 32 * bi + 8 * (r / 4) + 4 * lh + (r % 4);
+            if (gm < Mp) out[(int64_t)gm * N + gn] = acc_w[t][r];
+        }
+    }
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 template <int TMB, int TNB, int MASK>
 plx_status run_masked(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
                       const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
-                      int64_t rpc, int64_t chunks) {
+                      int64_t rpc, int64_t chunks, bool vec, bool split) {
     constexpr int MP = 32 * TMB, NP = 32 * TNB;
     const size_t lds = sizeof(float) * (kTR * (NP + 4) + kTR * (MP + 4));
-    const bool vec = aligned16(P) && ldp % 4 == 0 && aligned16(Q) && ldq % 4 == 0 && (MASK != kMaskValues || (aligned16(Zm) && ldz % 4 == 0)) &&
-                     R > 0;
+    if constexpr (TMB >= 2 && TNB >= 2) {
+        if (split) {                                                     // both widths above 32: the fp32 matrix pipe binds
+            const size_t lds3 = sizeof(bf16_t) * 3 * kTR * ((NP + 8) + (MP + 8));
+            auto kern = k_bwd_dense_x3<TMB, TNB, MASK>;
+            if (lds3 > 48 * 1024)
+                PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds3));
+            kern<<<dim3((unsigned)chunks), 256, lds3, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc);
+            PLX_HIP(ctx, hipGetLastError());
+            return PLX_OK;
+        }
+    }
     auto launch = [&](auto kern) -> plx_status {
         kern<<<dim3((unsigned)chunks), 256, lds, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc);
         PLX_HIP(ctx, hipGetLastError());
@@ -315,10 +518,10 @@ plx_status run_masked(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, in
 template <int TMB, int TNB>
 plx_status run(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
                const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
-               int64_t rpc, int64_t chunks, bool mask_bits) {
-    if (!Zm) return run_masked<TMB, TNB, kMaskNone>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks);
-    return mask_bits ? run_masked<TMB, TNB, kMaskBits>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks)
-                     : run_masked<TMB, TNB, kMaskValues>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks);
+               int64_t rpc, int64_t chunks, bool mask_bits, bool vec, bool split) {
+    if (!Zm) return run_masked<TMB, TNB, kMaskNone>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks, vec, split);
+    return mask_bits ? run_masked<TMB, TNB, kMaskBits>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks, vec, split)
+                     : run_masked<TMB, TNB, kMaskValues>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks, vec, split);
 }
 
 }  // namespace
@@ -340,14 +543,19 @@ plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, cons
     float* part = static_cast<float*>(ws);
     const int tmb = Mp <= 32 ? 1 : (Mp <= 64 ? 2 : 4), tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     char label[64];
-    snprintf(label, sizeof label, "bwd_dense<f32>[R%lld,M%lld,N%lld]%s", (long long)R, (long long)Mp, (long long)N,
-             (Zm && mask_bits) ? "bits" : "");
+    // 128-bit tile loads need 16-byte aligned rows; the split path (six bf16 products per fp32 product) serves the
+    // shapes whose fp32 matrix work binds, i.e. both widths above 32
+    const bool values = Zm && !mask_bits;
+    const bool vec = aligned16(P) && ldp % 4 == 0 && aligned16(Q) && ldq % 4 == 0 && (!values || (aligned16(Zm) && ldz % 4 == 0)) && R > 0;
+    const bool split = vec && ctx->split_products && tmb >= 2 && tnb >= 2;
+    snprintf(label, sizeof label, "bwd_dense<f32>[R%lld,M%lld,N%lld]%s%s", (long long)R, (long long)Mp, (long long)N,
+             split ? "x3" : "", (Zm && mask_bits) ? "bits" : "");
     plx_status st;
     {
         KernelTimer kt(ctx, label);
 #define PLX_BD(TM, TN)                                                                                              \
     st = run<TM, TN>(ctx, R, (int)Mp, (int)N, (const float*)P, ldp, (const float*)Q, ldq, (const float*)Zm, ldz, W, ldw, \
-                     (float*)dOut, ldo, part, rpc, chunks, mask_bits)
+                     (float*)dOut, ldo, part, rpc, chunks, mask_bits, vec, split)
         switch (tmb * 10 + tnb) {
             case 11: PLX_BD(1, 1); break;
             case 12: PLX_BD(1, 2); break;

@@ -16,6 +16,7 @@
 // the result does not depend on scheduling.
 #include "plx_internal.h"
 #include "buffer_addr.h"
+#include "bf16_frag.h"
 
 #include <algorithm>
 #include <type_traits>
@@ -428,6 +429,189 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
     if (bits && prev >= 0) flush_bits(cur ^ 1, prev);                    // the last pass ended with a barrier
 }
 
+// ---- the small-width forward product through the bf16 matrix instructions ---------------------------
+// Same persistent structure as k_gemm_small_f32, for the shapes whose fp32 matrix work binds (K and N
+// above 32): every fp32 operand is split into three bf16 numbers (the row tile once, when it is
+// written to LDS as three planes; the weights once, in registers) and six bf16 products replace one
+// fp32 product (see split3).  A workgroup walks tiles of 64 rows; block q = w + 4t of the 2 x TNB grid
+// of 32x32 blocks belongs to wavefront w, which therefore always works on column block w % TNB.
+#ifndef PLX_X3_FWD_WAVES
+#define PLX_X3_FWD_WAVES 2
+#endif
+#ifndef PLX_X3_FWD_CAP
+#define PLX_X3_FWD_CAP 0
+#endif
+template <int TKB, int TNB>   // 32 < K <= 32*TKB, 32 < N <= 32*TNB (TKB, TNB in {2, 4}); 16-byte aligned rows, K % 4 == 0
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_FWD_WAVES))) void k_gemm_small_x3(int64_t M, int N, int K, const float* __restrict__ A,
+                                                       int64_t lda, const float* __restrict__ B, int64_t ldb,
+                                                       float* __restrict__ C, int64_t ldc, float* __restrict__ F,
+                                                       int64_t ldf, uint32_t* __restrict__ bits, int64_t ldbits,
+                                                       int bits_vec) {
+    constexpr int KP = 32 * TKB, ROWS = 64, NBLK = 2 * TNB / 4, NKS = KP / 16, SA = KP + 8, PLANE = ROWS * SA;
+    constexpr int NLD = ROWS * KP / 4 / 256;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);                        // [3][ROWS][SA]
+    uint32_t* sb = reinterpret_cast<uint32_t*>(As + 3 * PLANE);              // sign bits: [2][4 words][ROWS]
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int bj = w % TNB;
+
+    bf16x8 breg[NKS][3];                   // planes of B[16s + 8*lh .. +7][32*bj + l32]
+    {
+        const int n = 32 * bj + l32;
+#pragma unroll
+        for (int s2 = 0; s2 < NKS; ++s2) {
+            Frag f[3];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float x[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int kk = 16 * s2 + 8 * lh + 4 * h + e;
+                    x[e] = (kk < K && n < N) ? B[(int64_t)kk * ldb + n] : 0.f;
+                }
+                uint2 pl[3];
+                split3(make_float4(x[0], x[1], x[2], x[3]), pl);
+#pragma unroll
+                for (int p = 0; p < 3; ++p) { f[p].x[2 * h] = pl[p].x; f[p].x[2 * h + 1] = pl[p].y; }
+            }
+#pragma unroll
+            for (int p = 0; p < 3; ++p) breg[s2][p] = f[p].v;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // weights landed before the row loop (vmcnt(0))
+
+    const int64_t n_tiles = (M + ROWS - 1) / ROWS;
+    float4 reg[NLD];
+    uint32_t toff[NLD];                    // byte offset of a thread's 16-byte pieces inside a tile
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int f = tid + 256 * i, r = f / (KP / 4), q = f % (KP / 4);
+        toff[i] = (KP == K || 4 * q < K) ? (uint32_t)(((uint32_t)r * (uint32_t)lda + 4u * q) * 4u) : kOutOfRange;
+    }
+    const uint32_t tile_bytes_a = (uint32_t)(((ROWS - 1) * lda + K) * 4);
+    auto fetch = [&](int64_t tile) {       // the byte count ends with the last valid row: rows past it read as 0
+        const int64_t m0 = tile * ROWS, left = M - m0;
+        const __amdgpu_buffer_rsrc_t ra = buffer_of(A + m0 * lda, left >= ROWS ? tile_bytes_a : (uint32_t)(((left - 1) * lda + K) * 4));
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) reg[i] = buffer_load4(ra, toff[i]);
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int f = tid + 256 * i, r = f / (KP / 4), q = f % (KP / 4);
+            uint2 pl[3];
+            split3(reg[i], pl);
+#pragma unroll
+            for (int p = 0; p < 3; ++p) *reinterpret_cast<uint2*>(As + p * PLANE + r * SA + 4 * q) = pl[p];
+        }
+    };
+    const int nw = (N + 31) >> 5;
+    auto flush_bits = [&](int buf, int64_t t) {                          // words of tile t, written by the pass before
+        const int64_t row = t * ROWS + tid;
+        if (tid < ROWS && row < M) {
+            uint32_t wds[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wds[j] = j < TNB ? sb[(buf * 4 + j) * ROWS + tid] : 0u;
+            uint32_t* dst = bits + row * ldbits;
+            if (bits_vec == 4) *reinterpret_cast<uint4*>(dst) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+            else if (bits_vec == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(wds[0], wds[1]);
+            else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (j < nw) dst[j] = wds[j];
+            }
+        }
+    };
+
+    int64_t tile = blockIdx.x, prev = -1;
+    int cur = 0;
+    if (tile < n_tiles) { fetch(tile); commit(); }
+    __syncthreads();
+    const int k_end = (K + 15) & ~15;
+    const uint32_t coff = (uint32_t)((4u * lh * (uint32_t)ldc + 32 * bj + l32) * 4u), foff = (uint32_t)((4u * lh * (uint32_t)ldf + 32 * bj + l32) * 4u);
+    for (; tile < n_tiles; tile += gridDim.x) {
+        fetch(tile + gridDim.x < n_tiles ? tile + gridDim.x : tile);     // unconditional: the last pass re-reads its own tile
+        if (bits && prev >= 0) flush_bits(cur ^ 1, prev);
+        prev = tile;
+        floatx16 acc[NBLK];
+#pragma unroll
+        for (int t = 0; t < NBLK; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < NKS; ++s2) {
+            if (s2 > 0 && 16 * s2 >= k_end) break;                       // uniform
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) {
+                const int bi = (w + 4 * t) / TNB;
+                bf16x8 a[3];
+#pragma unroll
+                for (int p = 0; p < 3; ++p) a[p] = frag_contig(As + p * PLANE + (32 * bi + l32) * SA + 16 * s2 + 8 * lh);
+                PLX_X3_32(acc[t], a, breg[s2]);
+            }
+        }
+        __syncthreads();                                                 // every wavefront is done reading the tile
+        commit();
+        const int64_t m0 = tile * ROWS;
+        const bool full = m0 + ROWS <= M;                                // uniform: only the last tile is partial
+        if (32 * bj + l32 < N) {
+            const __amdgpu_buffer_rsrc_t rc = buffer_of(C ? C + m0 * ldc : nullptr, (uint32_t)(((ROWS - 1) * ldc + N) * 4));
+            const __amdgpu_buffer_rsrc_t rf = buffer_of(F ? F + m0 * ldf : nullptr, (uint32_t)(((ROWS - 1) * ldf + N) * 4));
+            auto emit = [&](auto guarded, auto has_c, auto has_f) {
+#pragma unroll
+                for (int t = 0; t < NBLK; ++t) {
+                    const int bi = (w + 4 * t) / TNB;                    // uniform
+                    uint32_t crow = opaque_zero() + 32u * bi * (uint32_t)ldc * 4u, frow = opaque_zero() + 32u * bi * (uint32_t)ldf * 4u;
+                    int at = 0;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = 8 * (r / 4) + (r % 4);             // inside the block, of the lower half-wave
+                        crow += (uint32_t)(row - at) * (uint32_t)ldc * 4u;
+                        frow += (uint32_t)(row - at) * (uint32_t)ldf * 4u;
+                        at = row;
+                        const float v = acc[t][r];
+                        if (!guarded.value || m0 + 32 * bi + row + 4 * lh < M) {
+                            if (has_c.value) buffer_store_nt(rc, coff, crow, v);
+                            if (has_f.value) buffer_store_nt(rf, foff, frow, relu0(v));   // Eq. 2.3 fused into the store
+                        }
+                    }
+                }
+            };
+            auto emit_cf = [&](auto guarded) {
+                if (C && F) emit(guarded, std::true_type{}, std::true_type{});
+                else if (F) emit(guarded, std::false_type{}, std::true_type{});
+                else emit(guarded, std::true_type{}, std::false_type{});
+            };
+            if (full) emit_cf(std::false_type{}); else emit_cf(std::true_type{});
+        }
+        if (bits) {       // one ballot = 32 columns of two rows (lanes 0-31: row dr, lanes 32-63: row dr + 4); columns >= N give 0
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) {
+                const int bi = (w + 4 * t) / TNB;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    uint32_t lo[4], hi[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const unsigned long long b = __ballot(acc[t][4 * g + j] > 0.f);
+                        lo[j] = (uint32_t)b;
+                        hi[j] = (uint32_t)(b >> 32);
+                    }
+                    if (lane == 0) {
+                        uint4* dst = reinterpret_cast<uint4*>(&sb[(cur * 4 + bj) * ROWS + 32 * bi + 8 * g]);
+                        dst[0] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                        dst[1] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+    if (bits && prev >= 0) flush_bits(cur ^ 1, prev);                    // the last pass ended with a barrier
+}
+
 // ---- partial[chunk][M x N] = A[rows of chunk, M]^T * B[rows of chunk, N] ---------------------------
 template <int TMB, int TNB>
 __global__ __launch_bounds__(256) void k_gemm_tn_f32(int64_t R, int M, int N, const float* __restrict__ A, int64_t lda,
@@ -593,12 +777,16 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
     const int tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     dim3 grid((unsigned)ceil_div(M, 128), (unsigned)ceil_div(N, 32 * tnb));
     hipStream_t s = ctx->stream;
-    char label[64];
-    snprintf(label, sizeof label, "gemm_%s<f32>[M%lld,N%lld,K%lld]", bt ? "nt" : "nn", (long long)M, (long long)N, (long long)K);
-    KernelTimer kt(ctx, label);
-    // the small-width kernel addresses a tile with 31-bit byte offsets: 64 rows * ld * 4 bytes must fit
+    // the small-width kernels address a tile with 31-bit byte offsets: 64 rows * ld * 4 bytes must fit
     const bool ld32 = lda < (int64_t(1) << 23) && (!C || ldc < (int64_t(1) << 23)) && (!Fact || ldf < (int64_t(1) << 23));
-    if (!bt && K <= 128 && N <= 128 && K > 0 && ld32) {
+    const bool small = !bt && K <= 128 && N <= 128 && K > 0 && ld32;
+    // K and N above 32: the fp32 matrix pipe would bind, six bf16 products per fp32 product are taken instead
+    const bool split = small && ctx->split_products && vec_a && K % 4 == 0 && M > 0 && K > 32 && N > 32;
+    char label[64];
+    snprintf(label, sizeof label, "gemm_%s<f32>[M%lld,N%lld,K%lld]%s", bt ? "nt" : "nn", (long long)M, (long long)N, (long long)K,
+             split ? "x3" : "");
+    KernelTimer kt(ctx, label);
+    if (small) {
         const int tkb = K <= 32 ? 1 : (K <= 64 ? 2 : 4);
         int cb = (int)ceil_div(N, 16);
         if (cb > 4) cb = 8;                    // wide tiles are 128 columns (four 32x32 column blocks)
@@ -608,6 +796,24 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
         const int nw = (int)ceil_div(N, 32);
         const uintptr_t bp = reinterpret_cast<uintptr_t>(bits);
         const int bits_vec = (nw == 4 && ldbits % 4 == 0 && bp % 16 == 0) ? 4 : ((nw == 2 && ldbits % 2 == 0 && bp % 8 == 0) ? 2 : 1);
+        if (split) {
+            const int tnb3 = N <= 64 ? 2 : 4;
+            const size_t lds3 = sizeof(uint16_t) * 3 * 64 * (32 * tkb + 8) + (bits ? 2 * 4 * 64 * 4 : 0);
+            auto launch_x3 = [&](auto kern) -> plx_status {
+                if (lds3 > 48 * 1024)
+                    PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds3));
+                int per_cu = 0;
+                PLX_HIP(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds3));
+                if (PLX_X3_FWD_CAP > 0) per_cu = std::min(per_cu, PLX_X3_FWD_CAP);
+                const int64_t blocks = std::min<int64_t>(ceil_div(M, 64), (int64_t)ctx->n_cu * std::max(1, per_cu));
+                kern<<<dim3((unsigned)blocks), 256, lds3, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf, bits, ldbits, bits_vec);
+                PLX_HIP(ctx, hipGetLastError());
+                return PLX_OK;
+            };
+            if (tkb == 2) return tnb3 == 2 ? launch_x3(k_gemm_small_x3<2, 2>) : launch_x3(k_gemm_small_x3<2, 4>);
+            return tnb3 == 2 ? launch_x3(k_gemm_small_x3<4, 2>) : launch_x3(k_gemm_small_x3<4, 4>);
+        }
         auto launch_small = [&](auto kern) -> plx_status {
             if (lds > 48 * 1024)
                 PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

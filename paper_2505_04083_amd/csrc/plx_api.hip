@@ -123,6 +123,12 @@ void plx_ctx_destroy(plx_ctx* ctx) {
     delete ctx;
 }
 
+plx_status plx_ctx_set_split_products(plx_ctx* ctx, int on) {
+    if (!ctx) return PLX_ERR_INVALID;
+    ctx->split_products = on != 0;
+    return PLX_OK;
+}
+
 plx_status plx_ctx_set_column_windows(plx_ctx* ctx, int n_windows) {
     if (!ctx) return PLX_ERR_INVALID;
     if (n_windows < 1 || n_windows > 64) return fail(ctx, PLX_ERR_INVALID, "n_windows must be between 1 and 64");

@@ -68,6 +68,7 @@ struct plx_ctx {
     void* scratch = nullptr;  // partial sums of split rows; grown on demand
     size_t scratch_bytes = 0;
     int n_windows = 8;        // column windows for the rows handled through segments (1 = none); measured optimum 4-12
+    bool split_products = true;   // fp32 dense products of the wide layers through six bf16 matrix instructions
     // optional per-kernel timing (plx_timing_enable)
     struct Timed { std::string name; hipEvent_t start, stop; };
     bool timing = false;

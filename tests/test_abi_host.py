@@ -98,5 +98,7 @@ def test_dense_and_elementwise_argument_checks(dry):
     assert L.plx_ctx_set_column_windows(h, 65) == plx.PLX_ERR_INVALID
     assert L.plx_ctx_set_column_windows(h, 8) == plx.PLX_OK
     assert L.plx_ctx_set_column_windows(None, 8) == plx.PLX_ERR_INVALID
+    assert L.plx_ctx_set_split_products(h, 0) == plx.PLX_OK and L.plx_ctx_set_split_products(h, 1) == plx.PLX_OK
+    assert L.plx_ctx_set_split_products(None, 1) == plx.PLX_ERR_INVALID
     assert L.plx_csr_set_row_blocks(h, None, 4) == plx.PLX_ERR_INVALID
     assert L.plx_spmm_block(h, None, 0, 0, p, 4, p, 4, 4, 0) == plx.PLX_ERR_INVALID

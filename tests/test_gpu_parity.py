@@ -596,6 +596,46 @@ def test_layer_very_wide_leading_dimension(ctx):
         del Xw, F, saved, dFw, gdX
 
 
+@pytest.mark.parametrize("din,dout", [(64, 128), (128, 128), (100, 47), (128, 64), (36, 40), (128, 100)])
+def test_split_products_switch(din, dout):
+    """Wide fp32 layers go through six bf16 matrix products per fp32 product (three-way split of both
+    operands) by default and through the fp32 matrix instructions when the switch is off: both must
+    meet the fp32 tolerance against the oracle, and they must agree with each other far below it
+    (the split drops only terms under 2^-23 of a product)."""
+    m, k = 1500, 1300
+    rowptr, col, val = random_block(m, k, 3 * din + dout)
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(din + 11 * dout)
+    X = r.standard_normal((k, din)).astype(np.float32)
+    W = (r.standard_normal((din, dout)) * 0.2).astype(np.float32)
+    Hagg = oracle.spmm_coo(m, row, c64, v64, X)
+    Q = oracle.gemm(Hagg, W)
+    dFn = (r.standard_normal((m, dout)) * (np.abs(Q) > 1e-3 * np.abs(Q).max())).astype(np.float32)
+    dQ = oracle.relu_bwd(Q, dFn)
+    dW = oracle.gemm(Hagg, dQ, ta=True)
+    dX = oracle.spmm_t_coo(k, row, c64, v64, oracle.gemm(dQ, W, tb=True))
+    got = {}
+    for on in (True, False):
+        c = plx.plx_ctx(0)
+        plx.plx_ctx_set_split_products(c, on)
+        csr = plx.plx_csr_import(c, m, k, dev(rowptr), dev(col), dev(val))
+        for order in (plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_COMBINE_FIRST):
+            ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, order=order), dtype=torch.uint8, device=DEV)
+            F = torch.empty(m, dout, device=DEV); saved = torch.empty(m, din, device=DEV)
+            gdX = torch.empty(k, din, device=DEV); gdW = torch.empty(din, dout, device=DEV)
+            plx.plx_gcn_layer_fwd(c, csr, False, dev(X), dev(W), None, F, saved, ws, order=order)
+            plx.plx_gcn_layer_bwd(c, csr, False, dev(X), dev(W), F, dev(dFn), saved, gdX, gdW, ws, order=order)
+            plx.plx_sync(c)
+            assert rel_err(F, oracle.relu(Q)) <= TOL32
+            assert rel_err(gdW, dW) <= TOL32
+            assert rel_err(gdX, dX) <= TOL32
+            got[(on, order)] = (F.cpu().numpy(), gdW.cpu().numpy(), gdX.cpu().numpy())
+        csr.close(); c.close()
+    for order in (plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_COMBINE_FIRST):
+        for a, b in zip(got[(True, order)], got[(False, order)]):
+            assert np.abs(a.astype(np.float64) - b).max() <= 2e-6 * np.abs(b).max()
+
+
 def test_layer_sign_bits_argument_errors(ctx):
     m, k, din, dout = 40, 50, 8, 40
     rowptr, col, val = random_block(m, k, 2)
