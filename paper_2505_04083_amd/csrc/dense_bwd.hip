@@ -304,11 +304,14 @@ __global__ __launch_bounds__(256) void k_bwd_dense_f32(int64_t R, int Mp, int N,
 // fp32 instruction needs for 3 (6): where the fp32 matrix pipe binds (both widths 64 or more) this
 // path is taken instead (an infinite input gives NaN here, inf - inf, where the plain product gives inf).
 // The tiles are split once, when they are written to LDS as three bf16 planes.
+#ifndef PLX_X3_PAD
+#define PLX_X3_PAD 16         // padding of an LDS row of a bf16 plane, in elements (a multiple of 8 keeps rows 16-byte aligned; 16 measured 1-4 % faster than 8: fewer bank conflicts of the transpose reads)
+#endif
 // registers -> three bf16 planes of an LDS tile [3][TR][COLS + 8], masked like commit_tile
 template <int TR, int COLS, int MASK>
 __device__ __forceinline__ void commit_split(bf16_t* dst, const TileRegs<TR, COLS>& t, const TileRegs<TR, COLS>& m,
                                              const TileBits<TR, COLS>& mb, int tid) {
-    constexpr int Q4 = COLS / 4, PITCH = COLS + 8, PLANE = TR * PITCH;
+    constexpr int Q4 = COLS / 4, PITCH = COLS + PLX_X3_PAD, PLANE = TR * PITCH;
 #pragma unroll
     for (int i = 0; i < TR * COLS / 1024; ++i) {
         const int f = tid + 256 * i, r = f / Q4, q = f % Q4;
@@ -342,7 +345,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_BWD_
                                                       const float* __restrict__ W, int64_t ldw,
                                                       float* __restrict__ dOut, int64_t ldo, float* __restrict__ part,
                                                       int64_t rows_per_chunk) {
-    constexpr int MP = 32 * TMB, NP = 32 * TNB, SQ = NP + 8, SP = MP + 8;
+    constexpr int MP = 32 * TMB, NP = 32 * TNB, SQ = NP + PLX_X3_PAD, SP = MP + PLX_X3_PAD;
     constexpr int NBLK = TMB * TNB / 4;                       // 32x32 blocks of dW per wavefront (block q belongs to wavefront q % 4)
     constexpr int NCW = MP / 64, NRW = kTR / 16, NKS = NP / 32;   // dOut: NCW column blocks of 16 per wavefront, both row blocks
     static_assert(TMB >= 2 && TNB >= 2 && kTR == 32, "shapes of the split path");
@@ -437,15 +440,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_BWD_
         }
 #pragma unroll
         for (int kk = 0; kk < kTR; kk += 16) {                         // Eq. 2.5: 16 rows of the tile per instruction
+            bf16x8 b[3];                                               // 4 % TNB == 0: all blocks of a wavefront share the column block w % TNB
+#pragma unroll
+            for (int p = 0; p < 3; ++p) b[p] = frag_column(Qs + p * kTR * SQ, SQ, kk, 32 * (w % TNB), lane);
 #pragma unroll
             for (int t = 0; t < NBLK; ++t) {
-                const int q = w + 4 * t, bi = q / TNB, bj = q % TNB;
-                bf16x8 a[3], b[3];
+                const int bi = (w + 4 * t) / TNB;
+                bf16x8 a[3];
 #pragma unroll
-                for (int p = 0; p < 3; ++p) {
-                    a[p] = frag_column(Ps + p * kTR * SP, SP, kk, 32 * bi, lane);
-                    b[p] = frag_column(Qs + p * kTR * SQ, SQ, kk, 32 * bj, lane);
-                }
+                for (int p = 0; p < 3; ++p) a[p] = frag_column(Ps + p * kTR * SP, SP, kk, 32 * bi, lane);
                 PLX_X3_32(acc_w[t], a, b);
             }
         }
@@ -498,7 +501,7 @@ plx_status run_masked(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, in
     const size_t lds = sizeof(float) * (kTR * (NP + 4) + kTR * (MP + 4));
     if constexpr (TMB >= 2 && TNB >= 2) {
         if (split) {                                                     // both widths above 32: the fp32 matrix pipe binds
-            const size_t lds3 = sizeof(bf16_t) * 3 * kTR * ((NP + 8) + (MP + 8));
+            const size_t lds3 = sizeof(bf16_t) * 3 * kTR * ((NP + PLX_X3_PAD) + (MP + PLX_X3_PAD));
             auto kern = k_bwd_dense_x3<TMB, TNB, MASK>;
             if (lds3 > 48 * 1024)
                 PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds3));
