@@ -92,7 +92,8 @@ PLX_API plx_status plx_ctx_set_column_windows(plx_ctx* ctx, int n_windows);
  * fp32 operand is the exact sum of three bf16 numbers, and six of the nine bf16 products (all terms
  * down to 2^-23 of the product, i.e. fp32 rounding) are accumulated in fp32, 2.7 times faster than
  * the fp32 instructions.  Results agree with the plain fp32 path to fp32 rounding but not bit for
- * bit; an infinite input turns into NaN.  on == 0 selects the plain fp32 instructions everywhere. */
+ * bit; an infinite input, or a finite one within 0.4 % of the largest fp32 value (its leading bf16
+ * part rounds to infinity), turns into NaN.  on == 0 selects the plain fp32 instructions everywhere. */
 PLX_API plx_status plx_ctx_set_split_products(plx_ctx* ctx, int on);
 PLX_API plx_status plx_sync(plx_ctx* ctx);                /* wait for the context's stream */
 
