@@ -654,6 +654,60 @@ def test_split_product_times_identity_is_exact(ctx, k):
     assert np.all(g[A == 0] == 0)
 
 
+def test_layer_seeded_sweep_of_shapes_layouts_and_modes(ctx):
+    """120 seeded draws of (widths, block shape, dtype, order, activation mode, row padding): layer
+    forward and backward against the oracle.  Widths sit on both sides of every tile and lane-group
+    boundary, row paddings make aligned and unaligned layouts (padding holds NaN), the activation is
+    none / ReLU with the value mask / ReLU with sign bits."""
+    rng = np.random.default_rng(20250504)
+    for case in range(120):
+        din = int(rng.choice([1, 3, 8, 16, 31, 32, 33, 47, 64, 65, 96, 100, 127, 128]))
+        dout = int(rng.choice([1, 4, 16, 17, 32, 40, 41, 64, 66, 100, 128]))
+        m, k = int(rng.integers(1, 2500)), int(rng.integers(2, 2500))
+        bf = bool(rng.integers(0, 2))
+        tdt, code, tol = (torch.bfloat16, plx.PLX_BF16, 2e-2) if bf else (torch.float32, plx.PLX_F32, TOL32)
+        order = int(rng.choice([plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_COMBINE_FIRST]))
+        act = int(rng.choice([plx.PLX_ACT_NONE, plx.PLX_ACT_RELU, plx.PLX_ACT_RELU_BITS]))
+        pad = int(rng.choice([0, 1, 8, 16]))
+        tag = f"case {case}: {din}->{dout}, block {m}x{k}, bf16={bf}, order={order}, act={act}, pad={pad}"
+        rowptr, col, val = random_block(m, k, case + 1000, empty_rows=m > 20)
+        csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+        row, c64, v64 = coo_of(rowptr, col, val)
+
+        def mat(a, width):
+            ld = -(-width // pad) * pad if pad in (8, 16) else width + pad
+            t = torch.full((a.shape[0], ld), float("nan"), dtype=tdt, device=DEV)
+            t[:, :width] = torch.as_tensor(a.astype(np.float32)).to(tdt).to(DEV)
+            return t, t[:, :width]
+
+        _, X = mat(rng.standard_normal((k, din)), din)
+        W = (rng.standard_normal((din, dout)) * 0.3).astype(np.float32)
+        Hagg = oracle.spmm_coo(m, row, c64, v64, X.double().cpu().numpy())
+        Q = oracle.gemm(Hagg, W)
+        relu = act != plx.PLX_ACT_NONE
+        Fref = oracle.relu(Q) if relu else Q
+        keep = (np.abs(Q) > (3e-2 if bf else 1e-3) * max(np.abs(Q).max(), 1e-30)) if relu else 1.0   # clear of the mask's rounding band
+        _, dF = mat(rng.standard_normal((m, dout)) * keep, dout)
+        dF64 = dF.double().cpu().numpy()
+        dQ = oracle.relu_bwd(Q, dF64) if relu else dF64
+        dW = oracle.gemm(Hagg, dQ, ta=True)
+        dX = oracle.spmm_t_coo(k, row, c64, v64, oracle.gemm(dQ, W, tb=True))
+        ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, dtype=code, act=act, order=order), dtype=torch.uint8, device=DEV)
+        (Fp, F), (_, saved), (gXp, gdX) = mat(np.zeros((m, dout)), dout), mat(np.zeros((m, din)), din), mat(np.zeros((k, din)), din)
+        gdW = torch.empty(din, dout, device=DEV)
+        Zm = torch.empty(m, (dout + 31) // 32, dtype=torch.int32, device=DEV) if act == plx.PLX_ACT_RELU_BITS else None
+        plx.plx_gcn_layer_fwd(ctx, csr, False, X, dev(W), Zm, F, saved, ws, act=act, order=order)
+        mask = Zm if act == plx.PLX_ACT_RELU_BITS else (F if relu else None)
+        plx.plx_gcn_layer_bwd(ctx, csr, False, X, dev(W), mask, dF, saved, gdX, gdW, ws, act=act, order=order)
+        plx.plx_sync(ctx)
+        for name, g, o in (("F", F, Fref), ("dW", gdW, dW), ("dX", gdX, dX)):
+            err = np.abs(g.double().cpu().numpy() - o).max() / max(np.abs(o).max(), 1e-30)
+            assert err <= tol, f"{tag}: {name} off by {err:.3e}"
+        for t, width in ((Fp, dout), (gXp, din)):                          # padding untouched
+            assert bool(torch.isnan(t[:, width:].float()).all()), tag
+        csr.close()
+
+
 def test_layer_sign_bits_argument_errors(ctx):
     m, k, din, dout = 40, 50, 8, 40
     rowptr, col, val = random_block(m, k, 2)
