@@ -142,7 +142,7 @@ def main():
 
     import torch
     import paper_2505_04083_amd as plx
-    from paper_2505_04083_amd.network import GcnNetwork
+    from paper_2505_04083_amd.network import GcnNetwork, aligned_rows
     import synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -200,7 +200,9 @@ def main():
         csr = plx.plx_build_csr(ctx, cfg.n, src, dst, pr, pc)
         t_build = time.time() - t0
         del src, dst
-        H0 = synth.normal(cfg.seed, synth.S_FEAT, cfg.n, cfg.dims[0], dev, tdt)       # random rows: any order is P_c order
+        # random rows: any order is P_c order; stored like every matrix of the network, rows padded to 16 bytes
+        H0 = aligned_rows(cfg.n, cfg.dims[0], tdt, dev)
+        H0.copy_(synth.normal(cfg.seed, synth.S_FEAT, cfg.n, cfg.dims[0], dev, tdt))
         Ws = cfg.weights(dev)
         y = cfg.labels(dev)
         net = GcnNetwork(ctx, csr, Ws, dtype=tdt, sign_bits=args.mask == "bits")

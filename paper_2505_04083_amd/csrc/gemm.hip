@@ -6,10 +6,13 @@
 // fp32 path: v_mfma_f32_32x32x2_f32.  Operand layout of that instruction for lane l:
 //   a = A[i = l % 32][k = l / 32],  b = B[k = l / 32][j = l % 32],
 //   acc[r] = C[i = 8*(r/4) + 4*(l/32) + r%4][j = l % 32],  r = 0..15.
-// General kernel (any K, N): a workgroup of 4 wavefronts owns a tile of TMB x TNB such 32x32
-// blocks; block q of the tile (row-major) belongs to wavefront q % 4; tiles of both operands are
-// staged through LDS with 128-bit global loads.  Layer-sized products (K, N <= 128) take the
-// persistent kernel further down, which keeps the weights in registers.
+// General kernels (any K, N): a workgroup of 4 wavefronts owns a tile of TMB x TNB such 32x32
+// blocks; block q of the tile (row-major) belongs to wavefront q % 4; slabs of 32 values of k of
+// both operands are staged through LDS.  Operands with 16-byte aligned rows take the variant with
+// buffer loads, two LDS buffers and one barrier per slab (measured on 232965 x 602 by 602 x 128:
+// 68 % of the fp32 matrix peak against 37 % for the element-wise guarded one, which stays for
+// unaligned rows).  Layer-sized products (K, N <= 128) take the persistent kernel further down,
+// which keeps the weights in registers.
 //
 // The transposed product (reduction over the node dimension) is split over row chunks; each
 // workgroup writes its partial tile and a second kernel adds the partials in a fixed order, so
@@ -135,6 +138,175 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
                 if (F) F[gr * ldf + gn] = v > 0.f ? v : 0.f;      // Eq. 2.3 fused into the store
             }
         }
+    }
+}
+
+// ---- the same product for 16-byte aligned operands: buffer loads, two LDS buffers, one barrier per slab ----
+// Tile 128 x 32*TNB; wavefront w owns the column block w % TNB of TNB row blocks.  A slab is 32 values
+// of k; the next one travels global -> registers while the matrix cores work on the current one and
+// is written to the other LDS buffer afterwards, so a slab costs one barrier.  The A tile (and the
+// B tile when BT, whose rows are then k-contiguous as well) is read from LDS 128 bits at a time:
+// instruction j of a group of four takes k = 8g + 4*(l/32) + j (any order of k gives the same sum).
+// Every address step inside the loop is scalar: the lane offsets are computed once.
+template <int TNB, bool BT>
+__global__ __launch_bounds__(256) void k_gemm_deep_f32(int64_t M, int N, int K, const float* __restrict__ A, int64_t lda,
+                                                       const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
+                                                       int64_t ldc, float* __restrict__ F, int64_t ldf) {
+    constexpr int BM = 128, BN = 32 * TNB, AP = kBK + 4;
+    constexpr int BROWS = BT ? BN : kBK, BP = BT ? kBK + 4 : BN + 4;   // the B tile as it lies in memory
+    constexpr int NA = BM * kBK / 4 / 256, NBV = BN * kBK / 4 / 256;   // 16-byte pieces per thread and slab
+    constexpr int NBLK = TNB;                                          // 4 * TNB blocks over 4 wavefronts
+    extern __shared__ __align__(16) float smem[];
+    typedef float (*ATile)[AP];
+    typedef float (*BTile)[BP];
+    auto a_buf = [&](int b) { return reinterpret_cast<ATile>(smem + b * BM * AP); };
+    auto b_buf = [&](int b) { return reinterpret_cast<BTile>(smem + 2 * BM * AP + b * BROWS * BP); };
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+    const int rows = (int)(M - m0 < BM ? M - m0 : BM), cols = N - n0 < BN ? N - n0 : BN;
+    const int bj = w % TNB;
+    auto row_block = [&](int t) { return (w + 4 * t) / TNB; };
+
+    uint32_t offa[NA], offb[NBV];
+    int ka[NA], kb[NBV];                   // first k of a piece inside the slab (pieces of the B tile only when BT)
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int f = tid + 256 * i, r = f >> 3, q = f & 7;
+        offa[i] = (uint32_t)(((uint32_t)r * (uint32_t)lda + 4u * q) * 4u);
+        ka[i] = 4 * q;
+    }
+#pragma unroll
+    for (int i = 0; i < NBV; ++i) {
+        const int f = tid + 256 * i;
+        const int r = BT ? f >> 3 : f / (BN / 4), q = BT ? f & 7 : f % (BN / 4);
+        offb[i] = (uint32_t)(((uint32_t)r * (uint32_t)ldb + 4u * q) * 4u);
+        kb[i] = 4 * q;
+    }
+    const float* a_row = A + m0 * lda;
+    const float* b_base = BT ? B + (int64_t)n0 * ldb : B + n0;
+
+    float4 ra[NA], rb[NBV];
+    // A piece whose four values straddle K keeps only those below it: what lies behind them in memory
+    // (padding, the next row) need not be finite, and 0 * NaN would reach every output of the row.
+    auto clip = [&](float4& v, int left) {
+        v.x = left > 0 ? v.x : 0.f; v.y = left > 1 ? v.y : 0.f; v.z = left > 2 ? v.z : 0.f; v.w = left > 3 ? v.w : 0.f;
+    };
+    auto fetch = [&](int k0) {
+        const int kleft = K - k0;                                        // > 0
+        // byte counts end with the last valid element: rows past the end of a matrix read as 0
+        const __amdgpu_buffer_rsrc_t da = buffer_of(a_row + k0, (uint32_t)(((int64_t)(rows - 1) * lda + kleft) * 4));
+#pragma unroll
+        for (int i = 0; i < NA; ++i) ra[i] = buffer_load4(da, offa[i]);
+        if constexpr (BT) {
+            const __amdgpu_buffer_rsrc_t db = buffer_of(b_base + k0, (uint32_t)(((int64_t)(cols - 1) * ldb + kleft) * 4));
+#pragma unroll
+            for (int i = 0; i < NBV; ++i) rb[i] = buffer_load4(db, offb[i]);
+        } else {
+            const int krows = kleft < kBK ? kleft : kBK;
+            const __amdgpu_buffer_rsrc_t db = buffer_of(b_base + (int64_t)k0 * ldb, (uint32_t)(((int64_t)(krows - 1) * ldb + cols) * 4));
+#pragma unroll
+            for (int i = 0; i < NBV; ++i) rb[i] = buffer_load4(db, offb[i]);
+        }
+        if (kleft < kBK) {                                               // uniform: the last slab of a K that is no multiple of 32
+#pragma unroll
+            for (int i = 0; i < NA; ++i) clip(ra[i], kleft - ka[i]);
+            if constexpr (BT) {
+#pragma unroll
+                for (int i = 0; i < NBV; ++i) clip(rb[i], kleft - kb[i]);
+            }
+        }
+    };
+    auto commit = [&](int b) {
+        ATile As = a_buf(b);
+        BTile Bs = b_buf(b);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int f = tid + 256 * i;
+            *reinterpret_cast<float4*>(&As[f >> 3][4 * (f & 7)]) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < NBV; ++i) {
+            const int f = tid + 256 * i;
+            const int r = BT ? f >> 3 : f / (BN / 4), q = BT ? f & 7 : f % (BN / 4);
+            *reinterpret_cast<float4*>(&Bs[r][4 * q]) = rb[i];
+        }
+    };
+
+    floatx16 acc[NBLK];
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+    fetch(0);
+    commit(0);
+    __syncthreads();
+    int cur = 0;
+    for (int k0 = 0; k0 < K; k0 += kBK) {
+        fetch(k0 + kBK < K ? k0 + kBK : k0);       // no condition around the prefetch: the last pass re-reads its own slab
+        ATile As = a_buf(cur);
+        BTile Bs = b_buf(cur);
+#pragma unroll
+        for (int g = 0; g < kBK / 8; ++g) {
+            float4 b4;
+            if constexpr (BT) {
+                b4 = *reinterpret_cast<const float4*>(&Bs[32 * bj + l32][8 * g + 4 * lh]);
+            } else {
+                b4.x = Bs[8 * g + 4 * lh + 0][32 * bj + l32];
+                b4.y = Bs[8 * g + 4 * lh + 1][32 * bj + l32];
+                b4.z = Bs[8 * g + 4 * lh + 2][32 * bj + l32];
+                b4.w = Bs[8 * g + 4 * lh + 3][32 * bj + l32];
+            }
+            float4 a4[NBLK];
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) a4[t] = *reinterpret_cast<const float4*>(&As[32 * row_block(t) + l32][8 * g + 4 * lh]);
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) {
+                acc[t] = mfma32(a4[t].x, b4.x, acc[t]);
+                acc[t] = mfma32(a4[t].y, b4.y, acc[t]);
+                acc[t] = mfma32(a4[t].z, b4.z, acc[t]);
+                acc[t] = mfma32(a4[t].w, b4.w, acc[t]);
+            }
+        }
+        commit(cur ^ 1);                           // the barrier of the pass before ended every read of that buffer
+        __syncthreads();
+        cur ^= 1;
+    }
+
+    const int gn = 32 * bj + l32;
+    if (gn < cols) {
+        // lane part of an address: column, and the +4 rows of the upper half-wave; the row part is scalar
+        const uint32_t coff = (uint32_t)((4u * lh * (uint32_t)ldc + gn) * 4u), foff = (uint32_t)((4u * lh * (uint32_t)ldf + gn) * 4u);
+        const __amdgpu_buffer_rsrc_t rc = buffer_of(C ? C + m0 * ldc + n0 : nullptr, (uint32_t)(((int64_t)(BM - 1) * ldc + cols) * 4));
+        const __amdgpu_buffer_rsrc_t rf = buffer_of(F ? F + m0 * ldf + n0 : nullptr, (uint32_t)(((int64_t)(BM - 1) * ldf + cols) * 4));
+        auto emit = [&](auto guarded, auto has_c, auto has_f) {
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) {
+                const int rb0 = 32 * row_block(t);                                   // scalar
+                uint32_t crow = (uint32_t)rb0 * (uint32_t)ldc * 4u, frow = (uint32_t)rb0 * (uint32_t)ldf * 4u;
+                int at = 0;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r / 4) + (r % 4);                           // of the lower half-wave, inside the block
+                    crow += (uint32_t)(row - at) * (uint32_t)ldc * 4u;
+                    frow += (uint32_t)(row - at) * (uint32_t)ldf * 4u;
+                    at = row;
+                    const float v = acc[t][r];
+                    if (!guarded.value || rb0 + row + 4 * lh < rows) {
+                        if (has_c.value) buffer_store(rc, coff, crow, v);
+                        if (has_f.value) buffer_store(rf, foff, frow, relu0(v));     // Eq. 2.3 fused into the store
+                    }
+                }
+            }
+        };
+        auto emit_cf = [&](auto guarded) {
+            if (C && F) emit(guarded, std::true_type{}, std::true_type{});
+            else if (F) emit(guarded, std::false_type{}, std::true_type{});
+            else emit(guarded, std::true_type{}, std::false_type{});
+        };
+        if (rows == BM) emit_cf(std::false_type{}); else emit_cf(std::true_type{});
     }
 }
 
@@ -700,6 +872,116 @@ __global__ __launch_bounds__(256) void k_gemm_tn_f32(int64_t R, int M, int N, co
     }
 }
 
+// The same partial products for 16-byte aligned operands: buffer loads with lane offsets computed
+// once, the next slab of 32 rows in flight while the matrix cores work on the current one, two LDS
+// buffers and one barrier per slab.  Block ownership, slot layout and summation order inside a
+// chunk are those of the kernel above.
+template <int TMB, int TNB>
+__global__ __launch_bounds__(256) void k_gemm_tn_deep_f32(int64_t R, int M, int N, const float* __restrict__ A, int64_t lda,
+                                                          const float* __restrict__ B, int64_t ldb,
+                                                          float* __restrict__ part, int64_t rows_per_chunk) {
+    constexpr int BM = 32 * TMB, BN = 32 * TNB, AP = BM + 4, BP = BN + 4;
+    constexpr int NB = TMB * TNB, KS = NB >= 4 ? 1 : 4 / NB, NBLK = NB >= 4 ? NB / 4 : 1;
+    constexpr int NA = (kBK * BM / 4 + 255) / 256, NBV = (kBK * BN / 4 + 255) / 256;   // 16-byte pieces per thread and slab
+    extern __shared__ __align__(16) float smem[];
+    typedef float (*ATile)[AP];
+    typedef float (*BTile)[BP];
+    auto a_buf = [&](int b) { return reinterpret_cast<ATile>(smem + b * kBK * (AP + BP)); };
+    auto b_buf = [&](int b) { return reinterpret_cast<BTile>(smem + b * kBK * (AP + BP) + kBK * AP); };
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wq = NB >= 4 ? w : w % NB, ks = NB >= 4 ? 0 : w / NB;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.z * BN;
+    const int mcols = M - m0 < BM ? M - m0 : BM, ncols = N - n0 < BN ? N - n0 : BN;
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_chunk;
+    const int64_t r_end = (r_begin + rows_per_chunk < R) ? r_begin + rows_per_chunk : R;
+
+    // a 32 x 32 slab is 256 pieces: with BM or BN of 32 every thread has one, else 2 or 4
+    uint32_t offa[NA], offb[NBV];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int f = tid + 256 * i, kk = f / (BM / 4), q = f % (BM / 4);
+        offa[i] = (uint32_t)(((uint32_t)kk * (uint32_t)lda + 4u * q) * 4u);
+    }
+#pragma unroll
+    for (int i = 0; i < NBV; ++i) {
+        const int f = tid + 256 * i, kk = f / (BN / 4), q = f % (BN / 4);
+        offb[i] = (uint32_t)(((uint32_t)kk * (uint32_t)ldb + 4u * q) * 4u);
+    }
+    float4 ra[NA], rb[NBV];
+    auto fetch = [&](int64_t r0) {
+        // byte counts end with the last valid element of the slab: rows past the chunk read as 0; columns past
+        // M or N of the other rows hold whatever follows them in memory and only reach outputs that are not stored
+        const int64_t left = r_end - r0;
+        const int krows = (int)(left < kBK ? left : kBK);
+        const __amdgpu_buffer_rsrc_t da = buffer_of(A + r0 * lda + m0, (uint32_t)(((int64_t)(krows - 1) * lda + mcols) * 4));
+        const __amdgpu_buffer_rsrc_t db = buffer_of(B + r0 * ldb + n0, (uint32_t)(((int64_t)(krows - 1) * ldb + ncols) * 4));
+#pragma unroll
+        for (int i = 0; i < NA; ++i) ra[i] = buffer_load4(da, offa[i]);
+#pragma unroll
+        for (int i = 0; i < NBV; ++i) rb[i] = buffer_load4(db, offb[i]);
+    };
+    auto commit = [&](int b) {
+        ATile As = a_buf(b);
+        BTile Bs = b_buf(b);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int f = tid + 256 * i;
+            *reinterpret_cast<float4*>(&As[f / (BM / 4)][4 * (f % (BM / 4))]) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < NBV; ++i) {
+            const int f = tid + 256 * i;
+            *reinterpret_cast<float4*>(&Bs[f / (BN / 4)][4 * (f % (BN / 4))]) = rb[i];
+        }
+    };
+
+    floatx16 acc[NBLK];
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+    if (r_begin < r_end) {                         // uniform
+        fetch(r_begin);
+        commit(0);
+    }
+    __syncthreads();
+    int cur = 0;
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += kBK) {
+        fetch(r0 + kBK < r_end ? r0 + kBK : r0);   // no condition around the prefetch: the last pass re-reads its own slab
+        ATile As = a_buf(cur);
+        BTile Bs = b_buf(cur);
+#pragma unroll
+        for (int kk = 2 * ks; kk < kBK; kk += 2 * KS) {
+            float a[NBLK], b[NBLK];
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) {
+                const int q = wq + 4 * t, bi = q / TNB, bj = q % TNB;
+                a[t] = As[kk + lh][32 * bi + l32];
+                b[t] = Bs[kk + lh][32 * bj + l32];
+            }
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) acc[t] = mfma32(a[t], b[t], acc[t]);
+        }
+        commit(cur ^ 1);                           // the barrier of the pass before ended every read of that buffer
+        __syncthreads();
+        cur ^= 1;
+    }
+    float* out = part + ((int64_t)blockIdx.x * KS + ks) * M * N;
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t) {
+        const int q = wq + 4 * t, bi = q / TNB, bj = q % TNB;
+        const int gn = n0 + 32 * bj + l32;
+        if (gn >= N) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int gm = m0 + 32 * bi + 8 * (r / 4) + 4 * lh + (r % 4);
+            if (gm < M) out[(int64_t)gm * N + gn] = acc[t][r];
+        }
+    }
+}
+
 // One level of the fixed-order sum of partial tiles: slot g*kFan*stride receives the sum of the
 // live slots (g*kFan + t)*stride, t = 0..kFan-1.  With `final_out` the sums go to C instead.
 constexpr int kFan = 32;
@@ -850,6 +1132,32 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
         PLX_HIP(ctx, hipGetLastError());
         return PLX_OK;
     }
+    // 16-byte aligned operands whose 128-row tiles fit 31-bit byte offsets take the buffer-addressed kernel
+    const int64_t ld_cap = int64_t(1) << 22;
+    const bool deep = vec_a && aligned16(B) && ldb % 4 == 0 && M > 0 && N > 0 && K > 0 && lda < ld_cap && ldb < ld_cap &&
+                      (!C || ldc < ld_cap) && (!Fact || ldf < ld_cap);
+    if (deep) {
+        auto launch_deep = [&](auto kern, size_t lds) -> plx_status {
+            if (lds > 48 * 1024)
+                PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            kern<<<grid, 256, lds, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf);
+            PLX_HIP(ctx, hipGetLastError());
+            return PLX_OK;
+        };
+        const size_t lds_b = bt ? 32 * tnb * (kBK + 4) : kBK * (32 * tnb + 4);
+        const size_t lds = sizeof(float) * 2 * (128 * (kBK + 4) + lds_b);
+        if (bt) {
+            if (tnb == 1) PLX_TRY(launch_deep(k_gemm_deep_f32<1, true>, lds));
+            else if (tnb == 2) PLX_TRY(launch_deep(k_gemm_deep_f32<2, true>, lds));
+            else PLX_TRY(launch_deep(k_gemm_deep_f32<4, true>, lds));
+        } else {
+            if (tnb == 1) PLX_TRY(launch_deep(k_gemm_deep_f32<1, false>, lds));
+            else if (tnb == 2) PLX_TRY(launch_deep(k_gemm_deep_f32<2, false>, lds));
+            else PLX_TRY(launch_deep(k_gemm_deep_f32<4, false>, lds));
+        }
+        if (bits) return launch_bits_from_act(ctx, M, N, Fact, ldf, bits, ldbits, dtype);
+        return PLX_OK;
+    }
 #define PLX_GEMM_CASE(T, BTV) \
     k_gemm_f32<T, BTV><<<grid, 256, 0, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf, vec_a)
     if (bt) {
@@ -882,8 +1190,23 @@ plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const v
     char label[64];
     snprintf(label, sizeof label, "gemm_tn<f32>[R%lld,M%lld,N%lld]", (long long)R, (long long)M, (long long)N);
     KernelTimer* kt = new KernelTimer(ctx, label);
-#define PLX_TN_CASE(TM, TN) \
-    k_gemm_tn_f32<TM, TN><<<grid, 256, 0, s>>>(R, (int)M, (int)N, a, lda, b, ldb, part, rpc, vec_a, vec_b)
+    // 16-byte aligned operands whose 32-row slabs fit 31-bit byte offsets take the buffer-addressed kernel
+    const bool deep = vec_a && vec_b && lda < (int64_t(1) << 22) && ldb < (int64_t(1) << 22);
+    const size_t lds = deep ? sizeof(float) * 2 * kBK * (32 * tmb + 4 + 32 * tnb + 4) : 0;
+    auto launch_deep = [&](auto kern) -> hipError_t {
+        if (lds > 48 * 1024) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        kern<<<grid, 256, lds, s>>>(R, (int)M, (int)N, a, lda, b, ldb, part, rpc);
+        return hipSuccess;
+    };
+    hipError_t attr_err = hipSuccess;
+#define PLX_TN_CASE(TM, TN)                                                                                          \
+    do {                                                                                                             \
+        if (deep) attr_err = launch_deep(k_gemm_tn_deep_f32<TM, TN>);                                                \
+        else k_gemm_tn_f32<TM, TN><<<grid, 256, 0, s>>>(R, (int)M, (int)N, a, lda, b, ldb, part, rpc, vec_a, vec_b); \
+    } while (0)
     switch (tmb * 10 + tnb) {
         case 11: PLX_TN_CASE(1, 1); break;
         case 12: PLX_TN_CASE(1, 2); break;
@@ -897,6 +1220,7 @@ plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const v
     }
 #undef PLX_TN_CASE
     delete kt;
+    PLX_HIP(ctx, attr_err);
     PLX_HIP(ctx, hipGetLastError());
     return reduce_partials(ctx, part, chunks * tn_kslices(M, N), M, N, C, ldc);
 }

@@ -16,8 +16,9 @@ from . import (PLX_ACT_NONE, PLX_ACT_RELU, PLX_ACT_RELU_BITS, PLX_BF16, PLX_F32,
                plx_gcn_layer_fwd, plx_gcn_layer_workspace, plx_softmax_ce, plx_sync)
 
 
-def _matrix(rows: int, cols: int, dtype, dev) -> torch.Tensor:
-    """rows x cols view whose leading dimension is padded to 16 bytes (128-bit row accesses)."""
+def aligned_rows(rows: int, cols: int, dtype, dev) -> torch.Tensor:
+    """rows x cols view whose leading dimension is padded to 16 bytes: the layout every matrix of the
+    network is kept in (128-bit row accesses in the sparse and the dense kernels)."""
     q = 4 if dtype == torch.float32 else 8
     ld = (cols + q - 1) // q * q
     return torch.empty(rows, ld, dtype=dtype, device=dev)[:, :cols]
@@ -52,14 +53,14 @@ class GcnNetwork:
             if self.act[l] == PLX_ACT_RELU_BITS:
                 self.Z.append(torch.empty(rows, (dout + 31) // 32, dtype=torch.int32, device=dev))
             else:
-                self.Z.append(_matrix(rows, dout, dtype, dev) if (last or keep_preactivation) else None)
-            self.F.append(None if last else _matrix(rows, dout, dtype, dev))
+                self.Z.append(aligned_rows(rows, dout, dtype, dev) if (last or keep_preactivation) else None)
+            self.F.append(None if last else aligned_rows(rows, dout, dtype, dev))
             agg_first = order == 1 or (order == PLX_ORDER_AUTO and din <= dout)
-            self.saved.append(_matrix(rows if agg_first else 1, din, dtype, dev))
-            self.dH.append(_matrix(cols, din, dtype, dev))
+            self.saved.append(aligned_rows(rows if agg_first else 1, din, dtype, dev))
+            self.dH.append(aligned_rows(cols, din, dtype, dev))
             self.dW.append(torch.empty(din, dout, dtype=torch.float32, device=dev))
         rows_last = csr.shape(bool((self.L - 1) % 2))[0]
-        self.dZ_last = _matrix(rows_last, Ws[-1].shape[1], dtype, dev)
+        self.dZ_last = aligned_rows(rows_last, Ws[-1].shape[1], dtype, dev)
         self.row_loss = torch.empty(max(1, rows_last), dtype=torch.float32, device=dev)
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
 

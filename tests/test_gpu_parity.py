@@ -303,6 +303,40 @@ def test_gemm_parity(ctx, M, N, K):
     assert rel_err(dW, oracle.gemm(A, G, ta=True)) <= TOL32
 
 
+@pytest.mark.parametrize("M,N,K", [(300, 128, 602), (1000, 200, 70), (513, 130, 300), (64, 129, 133), (129, 33, 37),
+                                   (257, 602, 128), (128, 64, 256), (385, 96, 32), (1, 1, 1), (131, 100, 601)])
+def test_gemm_deep_products_on_aligned_padded_rows(ctx, M, N, K):
+    """The products outside the layer-sized range (K or N above 128, and every A B^T) on 16-byte
+    aligned rows take the slab kernel with 128-bit buffer loads.  Rows are padded to a multiple of
+    four elements (plus one more piece for odd sizes) and the padding holds NaN: a piece that
+    straddles K, a row past M or a column past N that reached a product, or a store outside the
+    result's width, shows up."""
+    r = np.random.default_rng(3 * M + 5 * N + 7 * K)
+    extra = 4 * ((M + N + K) % 2)
+
+    def padded(a):
+        ld = -(-a.shape[1] // 4) * 4 + extra
+        t = torch.full((a.shape[0], ld), float("nan"), device=DEV)
+        t[:, :a.shape[1]] = dev(a.astype(np.float32))
+        return t, t[:, :a.shape[1]]
+
+    A = r.standard_normal((M, K)); B = r.standard_normal((K, N)); G = r.standard_normal((M, N))
+    (_, Av), (_, Bv), (_, Btv), (_, Gv) = padded(A), padded(B), padded(np.ascontiguousarray(B.T)), padded(G)
+    A32, B32, G32 = A.astype(np.float32), B.astype(np.float32), G.astype(np.float32)
+    Cp, Cv = padded(np.zeros((M, N)))
+    plx.plx_gemm_nn(ctx, Av, Bv, Cv)
+    assert rel_err(Cv, oracle.gemm(A32, B32)) <= TOL32
+    assert bool(torch.isnan(Cp[:, N:]).all())
+    Cp2, Cv2 = padded(np.zeros((M, N)))
+    plx.plx_gemm_nt(ctx, Av, Btv, Cv2)
+    assert rel_err(Cv2, oracle.gemm(A32, np.ascontiguousarray(B32.T), tb=True)) <= TOL32
+    assert bool(torch.isnan(Cp2[:, N:]).all())
+    dWp, dWv = padded(np.zeros((K, N)))
+    plx.plx_gemm_tn(ctx, Av, Gv, dWv)
+    assert rel_err(dWv, oracle.gemm(A32, G32, ta=True)) <= TOL32
+    assert bool(torch.isnan(dWp[:, N:]).all())
+
+
 def test_gemm_tn_long_reduction_and_padding(ctx):
     R, M, N = 300_000, 32, 128
     A = synth.normal(5, 1, R, M, DEV)
