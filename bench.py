@@ -63,6 +63,15 @@ def parse():
     return ap.parse_args()
 
 
+def mfma_peak_of(name):
+    """(matrix-core peak in TFLOP/s a dense kernel is measured against, the reason if it is not its storage type's)."""
+    if "]x3" in name:                                 # fp32 product = six bf16 matrix products: the pipe that binds is the bf16 one
+        return MFMA_PEAK_TFLOPS["bf16"] / 6.0, "bf16 / 6 (six bf16 products per fp32 product)"
+    if "]w32" in name:                                # bf16 storage widened on load, multiplied by the fp32 instructions
+        return MFMA_PEAK_TFLOPS["f32"], "fp32 (bf16 inputs widened on load)"
+    return MFMA_PEAK_TFLOPS["bf16" if "<bf16>" in name else "f32"], None
+
+
 def kernel_cost(name, bins, names=()):
     """(algorithmic HBM bytes, flops) of one launch, from the sizes in the timing label.
 
@@ -288,10 +297,9 @@ def main():
         if b:
             kernels[name]["frac_hbm"] = round(b / avg / 1e6 / HBM_PEAK_GBS, 4)
         if fl and not name.startswith("spmm_"):      # dense products run on the matrix cores
-            peak = MFMA_PEAK_TFLOPS["bf16" if "<bf16>" in name else "f32"]
-            if "]x3" in name:                         # fp32 product = six bf16 matrix products: the pipe that binds is the bf16 one
-                peak = MFMA_PEAK_TFLOPS["bf16"] / 6.0
-                kernels[name]["mfma_peak_used"] = "bf16 / 6 (six bf16 products per fp32 product)"
+            peak, why = mfma_peak_of(name)
+            if why:
+                kernels[name]["mfma_peak_used"] = why
             kernels[name]["frac_mfma"] = round(fl / avg / 1e9 / peak, 4)
             kernels[name]["binding"] = "hbm" if kernels[name]["frac_hbm"] >= kernels[name]["frac_mfma"] else "mfma"
     dominant = max((n for n in timing if cost[n][0]), key=lambda n: timing[n][1])
@@ -303,9 +311,7 @@ def main():
                 "traffic": measured_traffic(dominant) if (args.scale == 1.0 and args.workload == "shard" and args.dtype == "f32") else None,
                 "algorithmic_bytes_per_launch": int(d_bytes), "avg_launch_ms": round(d_avg, 4)}
     if kernels[dominant].get("binding") == "mfma":     # a dense product nearer its matrix-core peak than its HBM peak
-        peak = MFMA_PEAK_TFLOPS["bf16" if "<bf16>" in dominant else "f32"]
-        if "]x3" in dominant:
-            peak = round(MFMA_PEAK_TFLOPS["bf16"] / 6.0, 1)
+        peak = round(mfma_peak_of(dominant)[0], 1)
         tf = cost[dominant][1] / d_avg / 1e9
         roofline.update({"bound": "mfma", "achieved": round(tf, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
                          "algorithmic_flops_per_launch": int(cost[dominant][1])})

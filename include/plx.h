@@ -181,8 +181,13 @@ PLX_API plx_status plx_spmm_block(plx_ctx* ctx, const plx_csr* csr, int transpos
  *               workgroups; partial sums are combined in a fixed order).  C is always fp32 for
  *               plx_gemm_tn; ws is device workspace of at least plx_gemm_tn_workspace bytes.
  * A, C of nn/nt have dtype `dtype`; the small operand B (a weight matrix) is always fp32.
- * All device, row-major.  PLX_BF16: nn only, K and N up to 128 and leading dimensions below 2^23
- * elements, else PLX_ERR_UNSUPPORTED (the same limits hold for the bf16 layer calls). */
+ * All device, row-major.  PLX_BF16: products with K or N (tn: M or N) above 128, and every nt
+ * product, need 16-byte aligned rows of their bf16 inputs (A; for tn A and B: base pointer
+ * 16-byte aligned, leading dimension a multiple of 8) and leading dimensions below 2^22
+ * elements, else PLX_ERR_UNSUPPORTED; the inputs are widened to fp32 (exact) and multiplied by the
+ * fp32 matrix instructions.  The narrower nn and tn products take bf16 matrix instructions (B
+ * rounded to bf16) with leading dimensions below 2^23.  The same holds for the products inside
+ * the bf16 layer calls. */
 PLX_API plx_status plx_gemm_nn(plx_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                                const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype);
 PLX_API plx_status plx_gemm_nt(plx_ctx* ctx, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,

@@ -148,14 +148,53 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int N, int K, const
 // B tile when BT, whose rows are then k-contiguous as well) is read from LDS 128 bits at a time:
 // instruction j of a group of four takes k = 8g + 4*(l/32) + j (any order of k gives the same sum).
 // Every address step inside the loop is scalar: the lane offsets are computed once.
-template <int TNB, bool BT>
-__global__ __launch_bounds__(256) void k_gemm_deep_f32(int64_t M, int N, int K, const float* __restrict__ A, int64_t lda,
-                                                       const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
-                                                       int64_t ldc, float* __restrict__ F, int64_t ldf) {
+// TA = bf16_t: A, C and F hold bf16; A is widened on its way into LDS (exact), so the products are
+// those of the fp32 kernel on bf16-valued inputs, and the results are rounded to nearest even.
+
+// a 16-byte piece of a row as fp32 values: 4 of an fp32 row, 8 of a bf16 row
+template <typename T> struct RowPiece;
+template <> struct RowPiece<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void widen(const float4& raw, float4 (&v)[1]) { v[0] = raw; }
+};
+template <> struct RowPiece<bf16_t> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void widen(const float4& raw, float4 (&v)[2]) {
+        const uint4 u = __builtin_bit_cast(uint4, raw);
+        v[0] = make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                           __uint_as_float(u.y & 0xffff0000u));
+        v[1] = make_float4(__uint_as_float(u.z << 16), __uint_as_float(u.z & 0xffff0000u), __uint_as_float(u.w << 16),
+                           __uint_as_float(u.w & 0xffff0000u));
+    }
+};
+// A piece whose values straddle the end of the reduction keeps only those before it: what lies behind
+// them in memory (padding, the next row) need not be finite, and 0 * NaN would reach a whole output row.
+__device__ __forceinline__ void clip_piece(float4& v, int left) {
+    v.x = left > 0 ? v.x : 0.f; v.y = left > 1 ? v.y : 0.f; v.z = left > 2 ? v.z : 0.f; v.w = left > 3 ? v.w : 0.f;
+}
+// bytes up to and including element (last_row, cols - 1) of a matrix of T, rounded up to the 4-byte
+// granularity of the range check (bf16 rows are padded to 16 bytes, so the extra element exists)
+template <typename T>
+__device__ __forceinline__ uint32_t extent_bytes(int last_row, int64_t ld, int cols) {
+    return (uint32_t)((((int64_t)last_row * ld + cols) * (int64_t)sizeof(T) + 3) & ~int64_t(3));
+}
+__device__ __forceinline__ void store_elt(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t row_off, float v, float*) {
+    buffer_store(r, lane_off, row_off, v);
+}
+__device__ __forceinline__ void store_elt(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t row_off, float v, bf16_t*) {
+    __builtin_amdgcn_raw_buffer_store_b16((short)f32_to_bf16(v), r, (int)lane_off, (int)row_off, 0);
+}
+
+template <int TNB, bool BT, typename TA, bool BV>   // BV: the rows of B are 16-byte aligned as well (else four 4-byte loads per piece)
+__global__ __launch_bounds__(256) void k_gemm_deep(int64_t M, int N, int K, const TA* __restrict__ A, int64_t lda,
+                                                   const float* __restrict__ B, int64_t ldb, TA* __restrict__ C,
+                                                   int64_t ldc, TA* __restrict__ F, int64_t ldf) {
     constexpr int BM = 128, BN = 32 * TNB, AP = kBK + 4;
     constexpr int BROWS = BT ? BN : kBK, BP = BT ? kBK + 4 : BN + 4;   // the B tile as it lies in memory
-    constexpr int NA = BM * kBK / 4 / 256, NBV = BN * kBK / 4 / 256;   // 16-byte pieces per thread and slab
+    constexpr int NE = RowPiece<TA>::N, PPR = kBK / NE;                // elements per piece, pieces per row of an A slab
+    constexpr int NA = BM * PPR / 256, NBV = BN * kBK / 4 / 256;       // 16-byte pieces per thread and slab
     constexpr int NBLK = TNB;                                          // 4 * TNB blocks over 4 wavefronts
+    constexpr uint32_t ES = sizeof(TA);
     extern __shared__ __align__(16) float smem[];
     typedef float (*ATile)[AP];
     typedef float (*BTile)[BP];
@@ -170,66 +209,67 @@ __global__ __launch_bounds__(256) void k_gemm_deep_f32(int64_t M, int N, int K, 
     auto row_block = [&](int t) { return (w + 4 * t) / TNB; };
 
     uint32_t offa[NA], offb[NBV];
-    int ka[NA], kb[NBV];                   // first k of a piece inside the slab (pieces of the B tile only when BT)
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
-        const int f = tid + 256 * i, r = f >> 3, q = f & 7;
-        offa[i] = (uint32_t)(((uint32_t)r * (uint32_t)lda + 4u * q) * 4u);
-        ka[i] = 4 * q;
+        const int f = tid + 256 * i, r = f / PPR, q = f % PPR;
+        offa[i] = ((uint32_t)r * (uint32_t)lda + (uint32_t)(NE * q)) * ES;
     }
 #pragma unroll
     for (int i = 0; i < NBV; ++i) {
         const int f = tid + 256 * i;
         const int r = BT ? f >> 3 : f / (BN / 4), q = BT ? f & 7 : f % (BN / 4);
         offb[i] = (uint32_t)(((uint32_t)r * (uint32_t)ldb + 4u * q) * 4u);
-        kb[i] = 4 * q;
     }
-    const float* a_row = A + m0 * lda;
+    const int ka = NE * (tid % PPR), kb = 4 * (tid & 7);     // first k of a thread's pieces inside a slab (B: when BT)
+    const TA* a_row = A + m0 * lda;
     const float* b_base = BT ? B + (int64_t)n0 * ldb : B + n0;
 
     float4 ra[NA], rb[NBV];
-    // A piece whose four values straddle K keeps only those below it: what lies behind them in memory
-    // (padding, the next row) need not be finite, and 0 * NaN would reach every output of the row.
-    auto clip = [&](float4& v, int left) {
-        v.x = left > 0 ? v.x : 0.f; v.y = left > 1 ? v.y : 0.f; v.z = left > 2 ? v.z : 0.f; v.w = left > 3 ? v.w : 0.f;
+    int kleft_fetched = 0;                                   // K - k0 of the slab the registers hold
+    auto load_b = [&](__amdgpu_buffer_rsrc_t d, uint32_t off) {
+        if constexpr (BV) return buffer_load4(d, off);
+        else   // the range check is per 4-byte word, so the four words of a piece may end anywhere in a row
+            return make_float4(__uint_as_float(buffer_load1(d, off)), __uint_as_float(buffer_load1(d, off + 4)),
+                               __uint_as_float(buffer_load1(d, off + 8)), __uint_as_float(buffer_load1(d, off + 12)));
     };
     auto fetch = [&](int k0) {
-        const int kleft = K - k0;                                        // > 0
+        const int kleft = K - k0;                            // > 0
+        kleft_fetched = kleft;
         // byte counts end with the last valid element: rows past the end of a matrix read as 0
-        const __amdgpu_buffer_rsrc_t da = buffer_of(a_row + k0, (uint32_t)(((int64_t)(rows - 1) * lda + kleft) * 4));
+        const __amdgpu_buffer_rsrc_t da = buffer_of(a_row + k0, extent_bytes<TA>(rows - 1, lda, kleft));
 #pragma unroll
         for (int i = 0; i < NA; ++i) ra[i] = buffer_load4(da, offa[i]);
         if constexpr (BT) {
-            const __amdgpu_buffer_rsrc_t db = buffer_of(b_base + k0, (uint32_t)(((int64_t)(cols - 1) * ldb + kleft) * 4));
+            const __amdgpu_buffer_rsrc_t db = buffer_of(b_base + k0, extent_bytes<float>(cols - 1, ldb, kleft));
 #pragma unroll
-            for (int i = 0; i < NBV; ++i) rb[i] = buffer_load4(db, offb[i]);
+            for (int i = 0; i < NBV; ++i) rb[i] = load_b(db, offb[i]);
         } else {
             const int krows = kleft < kBK ? kleft : kBK;
-            const __amdgpu_buffer_rsrc_t db = buffer_of(b_base + (int64_t)k0 * ldb, (uint32_t)(((int64_t)(krows - 1) * ldb + cols) * 4));
+            const __amdgpu_buffer_rsrc_t db = buffer_of(b_base + (int64_t)k0 * ldb, extent_bytes<float>(krows - 1, ldb, cols));
 #pragma unroll
-            for (int i = 0; i < NBV; ++i) rb[i] = buffer_load4(db, offb[i]);
-        }
-        if (kleft < kBK) {                                               // uniform: the last slab of a K that is no multiple of 32
-#pragma unroll
-            for (int i = 0; i < NA; ++i) clip(ra[i], kleft - ka[i]);
-            if constexpr (BT) {
-#pragma unroll
-                for (int i = 0; i < NBV; ++i) clip(rb[i], kleft - kb[i]);
-            }
+            for (int i = 0; i < NBV; ++i) rb[i] = load_b(db, offb[i]);
         }
     };
     auto commit = [&](int b) {
         ATile As = a_buf(b);
         BTile Bs = b_buf(b);
+        const bool tail = kleft_fetched < kBK;               // uniform: the last slab of a K that is no multiple of 32
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             const int f = tid + 256 * i;
-            *reinterpret_cast<float4*>(&As[f >> 3][4 * (f & 7)]) = ra[i];
+            float4 v[NE / 4];
+            RowPiece<TA>::widen(ra[i], v);
+#pragma unroll
+            for (int j = 0; j < NE / 4; ++j) {
+                if (tail) clip_piece(v[j], kleft_fetched - ka - 4 * j);
+                *reinterpret_cast<float4*>(&As[f / PPR][NE * (f % PPR) + 4 * j]) = v[j];
+            }
         }
 #pragma unroll
         for (int i = 0; i < NBV; ++i) {
             const int f = tid + 256 * i;
             const int r = BT ? f >> 3 : f / (BN / 4), q = BT ? f & 7 : f % (BN / 4);
+            if (BT && tail) clip_piece(rb[i], kleft_fetched - kb);
             *reinterpret_cast<float4*>(&Bs[r][4 * q]) = rb[i];
         }
     };
@@ -278,25 +318,25 @@ __global__ __launch_bounds__(256) void k_gemm_deep_f32(int64_t M, int N, int K, 
     const int gn = 32 * bj + l32;
     if (gn < cols) {
         // lane part of an address: column, and the +4 rows of the upper half-wave; the row part is scalar
-        const uint32_t coff = (uint32_t)((4u * lh * (uint32_t)ldc + gn) * 4u), foff = (uint32_t)((4u * lh * (uint32_t)ldf + gn) * 4u);
-        const __amdgpu_buffer_rsrc_t rc = buffer_of(C ? C + m0 * ldc + n0 : nullptr, (uint32_t)(((int64_t)(BM - 1) * ldc + cols) * 4));
-        const __amdgpu_buffer_rsrc_t rf = buffer_of(F ? F + m0 * ldf + n0 : nullptr, (uint32_t)(((int64_t)(BM - 1) * ldf + cols) * 4));
+        const uint32_t coff = (4u * lh * (uint32_t)ldc + gn) * ES, foff = (4u * lh * (uint32_t)ldf + gn) * ES;
+        const __amdgpu_buffer_rsrc_t rc = buffer_of(C ? C + m0 * ldc + n0 : nullptr, extent_bytes<TA>(BM - 1, ldc, cols));
+        const __amdgpu_buffer_rsrc_t rf = buffer_of(F ? F + m0 * ldf + n0 : nullptr, extent_bytes<TA>(BM - 1, ldf, cols));
         auto emit = [&](auto guarded, auto has_c, auto has_f) {
 #pragma unroll
             for (int t = 0; t < NBLK; ++t) {
                 const int rb0 = 32 * row_block(t);                                   // scalar
-                uint32_t crow = (uint32_t)rb0 * (uint32_t)ldc * 4u, frow = (uint32_t)rb0 * (uint32_t)ldf * 4u;
+                uint32_t crow = (uint32_t)rb0 * (uint32_t)ldc * ES, frow = (uint32_t)rb0 * (uint32_t)ldf * ES;
                 int at = 0;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = 8 * (r / 4) + (r % 4);                           // of the lower half-wave, inside the block
-                    crow += (uint32_t)(row - at) * (uint32_t)ldc * 4u;
-                    frow += (uint32_t)(row - at) * (uint32_t)ldf * 4u;
+                    crow += (uint32_t)(row - at) * (uint32_t)ldc * ES;
+                    frow += (uint32_t)(row - at) * (uint32_t)ldf * ES;
                     at = row;
                     const float v = acc[t][r];
                     if (!guarded.value || rb0 + row + 4 * lh < rows) {
-                        if (has_c.value) buffer_store(rc, coff, crow, v);
-                        if (has_f.value) buffer_store(rf, foff, frow, relu0(v));     // Eq. 2.3 fused into the store
+                        if (has_c.value) store_elt(rc, coff, crow, v, C);
+                        if (has_f.value) store_elt(rf, foff, frow, relu0(v), F);     // Eq. 2.3 fused into the store
                     }
                 }
             }
@@ -875,14 +915,17 @@ __global__ __launch_bounds__(256) void k_gemm_tn_f32(int64_t R, int M, int N, co
 // The same partial products for 16-byte aligned operands: buffer loads with lane offsets computed
 // once, the next slab of 32 rows in flight while the matrix cores work on the current one, two LDS
 // buffers and one barrier per slab.  Block ownership, slot layout and summation order inside a
-// chunk are those of the kernel above.
-template <int TMB, int TNB>
-__global__ __launch_bounds__(256) void k_gemm_tn_deep_f32(int64_t R, int M, int N, const float* __restrict__ A, int64_t lda,
-                                                          const float* __restrict__ B, int64_t ldb,
-                                                          float* __restrict__ part, int64_t rows_per_chunk) {
+// chunk are those of the kernel above.  T = bf16_t: both operands hold bf16 and are widened on
+// their way into LDS (exact); the partial sums and the result stay fp32.
+template <int TMB, int TNB, typename T>
+__global__ __launch_bounds__(256) void k_gemm_tn_deep(int64_t R, int M, int N, const T* __restrict__ A, int64_t lda,
+                                                      const T* __restrict__ B, int64_t ldb,
+                                                      float* __restrict__ part, int64_t rows_per_chunk) {
     constexpr int BM = 32 * TMB, BN = 32 * TNB, AP = BM + 4, BP = BN + 4;
     constexpr int NB = TMB * TNB, KS = NB >= 4 ? 1 : 4 / NB, NBLK = NB >= 4 ? NB / 4 : 1;
-    constexpr int NA = (kBK * BM / 4 + 255) / 256, NBV = (kBK * BN / 4 + 255) / 256;   // 16-byte pieces per thread and slab
+    constexpr int NE = RowPiece<T>::N;
+    constexpr int PA = kBK * BM / NE, PB = kBK * BN / NE;               // 16-byte pieces of a slab: 128 (bf16, 32 wide) .. 1024
+    constexpr int NA = (PA + 255) / 256, NBV = (PB + 255) / 256;        // per thread
     extern __shared__ __align__(16) float smem[];
     typedef float (*ATile)[AP];
     typedef float (*BTile)[BP];
@@ -896,17 +939,16 @@ __global__ __launch_bounds__(256) void k_gemm_tn_deep_f32(int64_t R, int M, int 
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_chunk;
     const int64_t r_end = (r_begin + rows_per_chunk < R) ? r_begin + rows_per_chunk : R;
 
-    // a 32 x 32 slab is 256 pieces: with BM or BN of 32 every thread has one, else 2 or 4
-    uint32_t offa[NA], offb[NBV];
+    uint32_t offa[NA], offb[NBV];                  // threads beyond a slab's pieces (PA or PB = 128) load nothing and write nothing
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
-        const int f = tid + 256 * i, kk = f / (BM / 4), q = f % (BM / 4);
-        offa[i] = (uint32_t)(((uint32_t)kk * (uint32_t)lda + 4u * q) * 4u);
+        const int f = tid + 256 * i, kk = f / (BM / NE), q = f % (BM / NE);
+        offa[i] = f < PA ? ((uint32_t)kk * (uint32_t)lda + (uint32_t)(NE * q)) * (uint32_t)sizeof(T) : kOutOfRange;
     }
 #pragma unroll
     for (int i = 0; i < NBV; ++i) {
-        const int f = tid + 256 * i, kk = f / (BN / 4), q = f % (BN / 4);
-        offb[i] = (uint32_t)(((uint32_t)kk * (uint32_t)ldb + 4u * q) * 4u);
+        const int f = tid + 256 * i, kk = f / (BN / NE), q = f % (BN / NE);
+        offb[i] = f < PB ? ((uint32_t)kk * (uint32_t)ldb + (uint32_t)(NE * q)) * (uint32_t)sizeof(T) : kOutOfRange;
     }
     float4 ra[NA], rb[NBV];
     auto fetch = [&](int64_t r0) {
@@ -914,8 +956,8 @@ __global__ __launch_bounds__(256) void k_gemm_tn_deep_f32(int64_t R, int M, int 
         // M or N of the other rows hold whatever follows them in memory and only reach outputs that are not stored
         const int64_t left = r_end - r0;
         const int krows = (int)(left < kBK ? left : kBK);
-        const __amdgpu_buffer_rsrc_t da = buffer_of(A + r0 * lda + m0, (uint32_t)(((int64_t)(krows - 1) * lda + mcols) * 4));
-        const __amdgpu_buffer_rsrc_t db = buffer_of(B + r0 * ldb + n0, (uint32_t)(((int64_t)(krows - 1) * ldb + ncols) * 4));
+        const __amdgpu_buffer_rsrc_t da = buffer_of(A + r0 * lda + m0, extent_bytes<T>(krows - 1, lda, mcols));
+        const __amdgpu_buffer_rsrc_t db = buffer_of(B + r0 * ldb + n0, extent_bytes<T>(krows - 1, ldb, ncols));
 #pragma unroll
         for (int i = 0; i < NA; ++i) ra[i] = buffer_load4(da, offa[i]);
 #pragma unroll
@@ -927,12 +969,22 @@ __global__ __launch_bounds__(256) void k_gemm_tn_deep_f32(int64_t R, int M, int 
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             const int f = tid + 256 * i;
-            *reinterpret_cast<float4*>(&As[f / (BM / 4)][4 * (f % (BM / 4))]) = ra[i];
+            float4 v[NE / 4];
+            RowPiece<T>::widen(ra[i], v);
+            if (PA % 256 == 0 || f < PA) {
+#pragma unroll
+                for (int j = 0; j < NE / 4; ++j) *reinterpret_cast<float4*>(&As[f / (BM / NE)][NE * (f % (BM / NE)) + 4 * j]) = v[j];
+            }
         }
 #pragma unroll
         for (int i = 0; i < NBV; ++i) {
             const int f = tid + 256 * i;
-            *reinterpret_cast<float4*>(&Bs[f / (BN / 4)][4 * (f % (BN / 4))]) = rb[i];
+            float4 v[NE / 4];
+            RowPiece<T>::widen(rb[i], v);
+            if (PB % 256 == 0 || f < PB) {
+#pragma unroll
+                for (int j = 0; j < NE / 4; ++j) *reinterpret_cast<float4*>(&Bs[f / (BN / NE)][NE * (f % (BN / NE)) + 4 * j]) = v[j];
+            }
         }
     };
 
@@ -1043,15 +1095,66 @@ size_t gemm_tn_workspace(int64_t R, int64_t M, int64_t N) {
     return (size_t)chunks * tn_kslices(M, N) * (size_t)M * (size_t)N * sizeof(float);
 }
 
+namespace {
+
+// what the slab kernels need: 16-byte aligned rows (the lane offsets are 16-byte pieces) and tiles whose byte
+// offsets fit 31 bits (128 rows of up to 2^22 elements)
+bool deep_operand(const void* p, int64_t ld, plx_dtype dtype) {
+    return aligned16(p) && ld % (16 / (int64_t)elt_size(dtype)) == 0 && ld < (int64_t(1) << 22);
+}
+
+template <int TNB, bool BT, typename TA>
+auto gemm_deep_kernel(bool bv) { return bv ? k_gemm_deep<TNB, BT, TA, true> : k_gemm_deep<TNB, BT, TA, false>; }
+
+template <typename TA>
+plx_status launch_gemm_deep(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const float* B,
+                            int64_t ldb, void* C, int64_t ldc, void* Fact, int64_t ldf) {
+    const int tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
+    const dim3 grid((unsigned)ceil_div(M, 128), (unsigned)ceil_div(N, 32 * tnb));
+    const size_t lds_b = bt ? 32 * tnb * (kBK + 4) : kBK * (32 * tnb + 4);
+    const size_t lds = sizeof(float) * 2 * (128 * (kBK + 4) + lds_b);
+    auto launch = [&](auto kern) -> plx_status {
+        if (lds > 48 * 1024)
+            PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        kern<<<grid, 256, lds, ctx->stream>>>(M, (int)N, (int)K, static_cast<const TA*>(A), lda, B, ldb, static_cast<TA*>(C), ldc,
+                                              static_cast<TA*>(Fact), ldf);
+        PLX_HIP(ctx, hipGetLastError());
+        return PLX_OK;
+    };
+    const bool bv = aligned16(B) && ldb % 4 == 0;      // the weight matrix may have rows of any length (41, 47 classes)
+    if (bt) {
+        if (tnb == 1) return launch(gemm_deep_kernel<1, true, TA>(bv));
+        if (tnb == 2) return launch(gemm_deep_kernel<2, true, TA>(bv));
+        return launch(gemm_deep_kernel<4, true, TA>(bv));
+    }
+    if (tnb == 1) return launch(gemm_deep_kernel<1, false, TA>(bv));
+    if (tnb == 2) return launch(gemm_deep_kernel<2, false, TA>(bv));
+    return launch(gemm_deep_kernel<4, false, TA>(bv));
+}
+
+}  // namespace
+
 plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                        const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype, void* Fact, int64_t ldf,
                        uint32_t* bits, int64_t ldbits) {
     if (bits && !Fact) return fail(ctx, PLX_ERR_INTERNAL, "sign bits are written next to the activated output");
-    if (dtype == PLX_BF16) {
-        if (bt) return fail(ctx, PLX_ERR_UNSUPPORTED, "the bf16 A B^T product exists only inside the fused backward kernel");
-        return launch_gemm_small_bf16(ctx, M, N, K, A, lda, B, ldb, C, ldc, Fact, ldf, bits, ldbits);
-    }
     if (N >= (int64_t(1) << 20) || K >= (int64_t(1) << 30)) return fail(ctx, PLX_ERR_UNSUPPORTED, "N or K too large");
+    const bool deep = M > 0 && N > 0 && K > 0 && deep_operand(A, lda, dtype) && ldb < (int64_t(1) << 22) &&
+                      (!C || ldc < (int64_t(1) << 22)) && (!Fact || ldf < (int64_t(1) << 22));
+    if (dtype == PLX_BF16) {
+        if (!bt && K <= 128 && N <= 128) return launch_gemm_small_bf16(ctx, M, N, K, A, lda, B, ldb, C, ldc, Fact, ldf, bits, ldbits);
+        // wider layers (and A B^T outside the fused backward kernel): the slab kernel, bf16 widened on load
+        if (!deep)
+            return fail(ctx, PLX_ERR_UNSUPPORTED, "bf16 products with K or N above 128, and A B^T, need 16-byte aligned rows of A (lda %% 8 == 0) and leading dimensions below 2^22 elements");
+        char label[64];
+        snprintf(label, sizeof label, "gemm_%s<bf16>[M%lld,N%lld,K%lld]w32", bt ? "nt" : "nn", (long long)M, (long long)N, (long long)K);
+        {
+            KernelTimer kt(ctx, label);
+            PLX_TRY(launch_gemm_deep<bf16_t>(ctx, bt, M, N, K, A, lda, B, ldb, C, ldc, Fact, ldf));
+        }
+        if (bits) return launch_bits_from_act(ctx, M, N, Fact, ldf, bits, ldbits, dtype);
+        return PLX_OK;
+    }
     const float* a = static_cast<const float*>(A);
     float* c = static_cast<float*>(C);
     float* fa = static_cast<float*>(Fact);
@@ -1132,29 +1235,8 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
         PLX_HIP(ctx, hipGetLastError());
         return PLX_OK;
     }
-    // 16-byte aligned operands whose 128-row tiles fit 31-bit byte offsets take the buffer-addressed kernel
-    const int64_t ld_cap = int64_t(1) << 22;
-    const bool deep = vec_a && aligned16(B) && ldb % 4 == 0 && M > 0 && N > 0 && K > 0 && lda < ld_cap && ldb < ld_cap &&
-                      (!C || ldc < ld_cap) && (!Fact || ldf < ld_cap);
-    if (deep) {
-        auto launch_deep = [&](auto kern, size_t lds) -> plx_status {
-            if (lds > 48 * 1024)
-                PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            kern<<<grid, 256, lds, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf);
-            PLX_HIP(ctx, hipGetLastError());
-            return PLX_OK;
-        };
-        const size_t lds_b = bt ? 32 * tnb * (kBK + 4) : kBK * (32 * tnb + 4);
-        const size_t lds = sizeof(float) * 2 * (128 * (kBK + 4) + lds_b);
-        if (bt) {
-            if (tnb == 1) PLX_TRY(launch_deep(k_gemm_deep_f32<1, true>, lds));
-            else if (tnb == 2) PLX_TRY(launch_deep(k_gemm_deep_f32<2, true>, lds));
-            else PLX_TRY(launch_deep(k_gemm_deep_f32<4, true>, lds));
-        } else {
-            if (tnb == 1) PLX_TRY(launch_deep(k_gemm_deep_f32<1, false>, lds));
-            else if (tnb == 2) PLX_TRY(launch_deep(k_gemm_deep_f32<2, false>, lds));
-            else PLX_TRY(launch_deep(k_gemm_deep_f32<4, false>, lds));
-        }
+    if (deep) {        // 16-byte aligned operands: the buffer-addressed slab kernel
+        PLX_TRY(launch_gemm_deep<float>(ctx, bt, M, N, K, A, lda, B, ldb, C, ldc, Fact, ldf));
         if (bits) return launch_bits_from_act(ctx, M, N, Fact, ldf, bits, ldbits, dtype);
         return PLX_OK;
     }
@@ -1173,39 +1255,44 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
 
 plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const void* A, int64_t lda, const void* B,
                           int64_t ldb, float* C, int64_t ldc, plx_dtype dtype, void* ws, size_t ws_bytes) {
-    if (dtype == PLX_BF16)   // the fused kernel without its second product and without a mask
+    if (dtype == PLX_BF16 && M <= 128 && N <= 128)   // the fused kernel without its second product and without a mask
         return launch_bwd_dense_bf16(ctx, R, M, N, A, lda, B, ldb, nullptr, 0, nullptr, 0, nullptr, 0, C, ldc, ws, ws_bytes);
     if (M >= (int64_t(1) << 20) || N >= (int64_t(1) << 20)) return fail(ctx, PLX_ERR_UNSUPPORTED, "M or N too large");
     if (ws_bytes < gemm_tn_workspace(R, M, N)) return fail(ctx, PLX_ERR_SHAPE, "workspace too small");
-    const float* a = static_cast<const float*>(A);
-    const float* b = static_cast<const float*>(B);
     float* part = static_cast<float*>(ws);
     const int64_t rpc = tn_rows_per_chunk(R, M, N);
     const int64_t chunks = std::max<int64_t>(1, ceil_div(R, rpc));
+    // 16-byte aligned operands whose 32-row slabs fit 31-bit byte offsets take the buffer-addressed kernel
+    const bool deep = deep_operand(A, lda, dtype) && deep_operand(B, ldb, dtype);
+    if (dtype == PLX_BF16 && !deep)
+        return fail(ctx, PLX_ERR_UNSUPPORTED, "bf16 A^T B with M or N above 128 needs 16-byte aligned rows (ld %% 8 == 0) below 2^22 elements");
     const int vec_a = aligned16(A) && lda % 4 == 0, vec_b = aligned16(B) && ldb % 4 == 0;
     const int tmb = M <= 32 ? 1 : (M <= 64 ? 2 : 4);
     const int tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     dim3 grid((unsigned)chunks, (unsigned)ceil_div(M, 32 * tmb), (unsigned)ceil_div(N, 32 * tnb));
     hipStream_t s = ctx->stream;
     char label[64];
-    snprintf(label, sizeof label, "gemm_tn<f32>[R%lld,M%lld,N%lld]", (long long)R, (long long)M, (long long)N);
+    snprintf(label, sizeof label, "gemm_tn<%s>[R%lld,M%lld,N%lld]%s", dtype == PLX_BF16 ? "bf16" : "f32", (long long)R, (long long)M,
+             (long long)N, dtype == PLX_BF16 ? "w32" : "");
     KernelTimer* kt = new KernelTimer(ctx, label);
-    // 16-byte aligned operands whose 32-row slabs fit 31-bit byte offsets take the buffer-addressed kernel
-    const bool deep = vec_a && vec_b && lda < (int64_t(1) << 22) && ldb < (int64_t(1) << 22);
     const size_t lds = deep ? sizeof(float) * 2 * kBK * (32 * tmb + 4 + 32 * tnb + 4) : 0;
-    auto launch_deep = [&](auto kern) -> hipError_t {
+    auto launch_deep = [&](auto kern, auto elt) -> hipError_t {
+        typedef decltype(elt) T;
         if (lds > 48 * 1024) {
             const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        kern<<<grid, 256, lds, s>>>(R, (int)M, (int)N, a, lda, b, ldb, part, rpc);
+        kern<<<grid, 256, lds, s>>>(R, (int)M, (int)N, static_cast<const T*>(A), lda, static_cast<const T*>(B), ldb, part, rpc);
         return hipSuccess;
     };
     hipError_t attr_err = hipSuccess;
-#define PLX_TN_CASE(TM, TN)                                                                                          \
-    do {                                                                                                             \
-        if (deep) attr_err = launch_deep(k_gemm_tn_deep_f32<TM, TN>);                                                \
-        else k_gemm_tn_f32<TM, TN><<<grid, 256, 0, s>>>(R, (int)M, (int)N, a, lda, b, ldb, part, rpc, vec_a, vec_b); \
+#define PLX_TN_CASE(TM, TN)                                                                                  \
+    do {                                                                                                     \
+        if (dtype == PLX_BF16) attr_err = launch_deep(k_gemm_tn_deep<TM, TN, bf16_t>, bf16_t{});             \
+        else if (deep) attr_err = launch_deep(k_gemm_tn_deep<TM, TN, float>, float{});                       \
+        else                                                                                                 \
+            k_gemm_tn_f32<TM, TN><<<grid, 256, 0, s>>>(R, (int)M, (int)N, static_cast<const float*>(A), lda, \
+                                                       static_cast<const float*>(B), ldb, part, rpc, vec_a, vec_b); \
     } while (0)
     switch (tmb * 10 + tnb) {
         case 11: PLX_TN_CASE(1, 1); break;

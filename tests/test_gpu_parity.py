@@ -303,38 +303,57 @@ def test_gemm_parity(ctx, M, N, K):
     assert rel_err(dW, oracle.gemm(A, G, ta=True)) <= TOL32
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("M,N,K", [(300, 128, 602), (1000, 200, 70), (513, 130, 300), (64, 129, 133), (129, 33, 37),
                                    (257, 602, 128), (128, 64, 256), (385, 96, 32), (1, 1, 1), (131, 100, 601)])
-def test_gemm_deep_products_on_aligned_padded_rows(ctx, M, N, K):
+def test_gemm_deep_products_on_aligned_padded_rows(ctx, M, N, K, dtype):
     """The products outside the layer-sized range (K or N above 128, and every A B^T) on 16-byte
-    aligned rows take the slab kernel with 128-bit buffer loads.  Rows are padded to a multiple of
-    four elements (plus one more piece for odd sizes) and the padding holds NaN: a piece that
-    straddles K, a row past M or a column past N that reached a product, or a store outside the
-    result's width, shows up."""
+    aligned rows take the slab kernel with 128-bit buffer loads; with bf16 storage the inputs are
+    widened on load and the results rounded to bf16.  Rows are padded to a multiple of 16 bytes
+    (plus one more piece for odd sizes) and the padding holds NaN: a piece that straddles K, a row
+    past M or a column past N that reached a product, or a store outside the result's width, shows
+    up.  The oracle sees the stored (bf16-rounded) inputs in fp64."""
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    tol = TOL32 if dtype == "f32" else 2e-2
     r = np.random.default_rng(3 * M + 5 * N + 7 * K)
-    extra = 4 * ((M + N + K) % 2)
 
-    def padded(a):
-        ld = -(-a.shape[1] // 4) * 4 + extra
-        t = torch.full((a.shape[0], ld), float("nan"), device=DEV)
-        t[:, :a.shape[1]] = dev(a.astype(np.float32))
-        return t, t[:, :a.shape[1]]
+    def padded(a, t=tdt):
+        q = 4 if t == torch.float32 else 8
+        ld = -(-a.shape[1] // q) * q + q * ((M + N + K) % 2)
+        buf = torch.full((a.shape[0], ld), float("nan"), dtype=t, device=DEV)
+        buf[:, :a.shape[1]] = torch.as_tensor(a.astype(np.float32)).to(t).to(DEV)
+        return buf, buf[:, :a.shape[1]]
 
-    A = r.standard_normal((M, K)); B = r.standard_normal((K, N)); G = r.standard_normal((M, N))
-    (_, Av), (_, Bv), (_, Btv), (_, Gv) = padded(A), padded(B), padded(np.ascontiguousarray(B.T)), padded(G)
-    A32, B32, G32 = A.astype(np.float32), B.astype(np.float32), G.astype(np.float32)
+    B = r.standard_normal((K, N)).astype(np.float32)          # the weight operand is fp32 in both modes
+    (_, Av), (_, Gv) = padded(r.standard_normal((M, K))), padded(r.standard_normal((M, N)))
+    (_, Bv), (_, Btv) = padded(B, torch.float32), padded(np.ascontiguousarray(B.T), torch.float32)
+    A64, G64 = Av.double().cpu().numpy(), Gv.double().cpu().numpy()
     Cp, Cv = padded(np.zeros((M, N)))
     plx.plx_gemm_nn(ctx, Av, Bv, Cv)
-    assert rel_err(Cv, oracle.gemm(A32, B32)) <= TOL32
-    assert bool(torch.isnan(Cp[:, N:]).all())
+    assert rel_err(Cv.float(), oracle.gemm(A64, B)) <= tol
+    assert bool(torch.isnan(Cp[:, N:].float()).all())
     Cp2, Cv2 = padded(np.zeros((M, N)))
     plx.plx_gemm_nt(ctx, Av, Btv, Cv2)
-    assert rel_err(Cv2, oracle.gemm(A32, np.ascontiguousarray(B32.T), tb=True)) <= TOL32
-    assert bool(torch.isnan(Cp2[:, N:]).all())
-    dWp, dWv = padded(np.zeros((K, N)))
+    assert rel_err(Cv2.float(), oracle.gemm(A64, np.ascontiguousarray(B.T), tb=True)) <= tol
+    assert bool(torch.isnan(Cp2[:, N:].float()).all())
+    dWp, dWv = padded(np.zeros((K, N)), torch.float32)
     plx.plx_gemm_tn(ctx, Av, Gv, dWv)
-    assert rel_err(dWv, oracle.gemm(A32, G32, ta=True)) <= TOL32
+    assert rel_err(dWv, oracle.gemm(A64, G64, ta=True)) <= tol
     assert bool(torch.isnan(dWp[:, N:]).all())
+
+
+def test_gemm_bf16_wide_products_need_aligned_rows(ctx):
+    """bf16 products beyond the layer-sized kernels exist only for 16-byte aligned rows: anything else
+    is refused with PLX_ERR_UNSUPPORTED, nothing is computed on a slower path."""
+    A = torch.zeros(64, 301, dtype=torch.bfloat16, device=DEV)        # 602-byte rows
+    B = torch.zeros(301, 128, device=DEV)
+    C = torch.zeros(64, 128, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(plx.PlxError) as e:
+        plx.plx_gemm_nn(ctx, A, B, C)
+    assert e.value.status == plx.PLX_ERR_UNSUPPORTED
+    with pytest.raises(plx.PlxError) as e:
+        plx.plx_gemm_tn(ctx, A, C, torch.zeros(301, 128, device=DEV))
+    assert e.value.status == plx.PLX_ERR_UNSUPPORTED
 
 
 def test_gemm_tn_long_reduction_and_padding(ctx):
@@ -547,23 +566,26 @@ def test_layer_sign_bits(ctx, din, dout, dtype):
     beyond the words of a row), and the backward call fed with the words returns bit for bit what it
     returns when fed with the value matrix; results are checked against the oracle as well.  Widths
     cover both fused dense kernels, the general product (602: separate sign pass) and both orders."""
-    if dtype == "bf16" and max(din, dout) > 128:
-        pytest.skip("bf16 dense products are built for widths up to 128")
     m, k = 1237, 1500                                # several tiles and a ragged last one
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+
+    def matrix(rows, cols, t=tdt):                   # bf16 widths above 128 need 16-byte aligned rows
+        ld = -(-cols // 8) * 8 if (dtype == "bf16" and max(din, dout) > 128) else cols
+        return torch.zeros(rows, ld, dtype=t, device=DEV)[:, :cols]
+
     code = plx.PLX_F32 if dtype == "f32" else plx.PLX_BF16
     tol = TOL32 if dtype == "f32" else 2e-2
     rowptr, col, val = random_block(m, k, 11 * din + dout)
     csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
     row, c64, v64 = coo_of(rowptr, col, val)
     r = np.random.default_rng(5 * din + dout)
-    X = torch.as_tensor(r.standard_normal((k, din)).astype(np.float32)).to(tdt).to(DEV)
+    X = matrix(k, din); X.copy_(torch.as_tensor(r.standard_normal((k, din)).astype(np.float32)))
     X64 = X.double().cpu().numpy()
     W = (r.standard_normal((din, dout)) * 0.2).astype(np.float32)
     Hagg = oracle.spmm_coo(m, row, c64, v64, X64)
     Q = oracle.gemm(Hagg, W)
     dF64 = r.standard_normal((m, dout)) * (np.abs(Q) > 2e-2 * np.abs(Q).max())   # keep clear of the mask's rounding band
-    dF = torch.as_tensor(dF64.astype(np.float32)).to(tdt).to(DEV)
+    dF = matrix(m, dout); dF.copy_(torch.as_tensor(dF64.astype(np.float32)))
     dF64 = dF.double().cpu().numpy()
     dQ = oracle.relu_bwd(Q, dF64)
     dW = oracle.gemm(Hagg, dQ, ta=True)
@@ -572,12 +594,12 @@ def test_layer_sign_bits(ctx, din, dout, dtype):
     for order in (plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_COMBINE_FIRST):
         ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, dtype=code, act=plx.PLX_ACT_RELU_BITS, order=order),
                          dtype=torch.uint8, device=DEV)
-        F = torch.empty(m, dout, dtype=tdt, device=DEV); saved = torch.empty(m, din, dtype=tdt, device=DEV)
+        F = matrix(m, dout); saved = matrix(m, din)
         words = torch.full((m, nw + 1), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
         plx.plx_gcn_layer_fwd(ctx, csr, False, X, dev(W), words[:, :nw], F, saved, ws, act=plx.PLX_ACT_RELU_BITS, order=order)
         outs = []
         for act, mask in ((plx.PLX_ACT_RELU_BITS, words[:, :nw]), (plx.PLX_ACT_RELU, F)):
-            gdX = torch.empty(k, din, dtype=tdt, device=DEV); gdW = torch.empty(din, dout, device=DEV)
+            gdX = matrix(k, din); gdW = torch.empty(din, dout, device=DEV)
             plx.plx_gcn_layer_bwd(ctx, csr, False, X, dev(W), mask, dF, saved, gdX, gdW, ws, act=act, order=order)
             outs.append((gdX, gdW))
         plx.plx_sync(ctx)
@@ -868,6 +890,50 @@ def test_layer_bf16_both_orders(ctx, din, dout):
         assert rel_err(F, oracle.relu(Q)) <= TOLBF
         assert rel_err(gdW, dW) <= TOLBF
         assert rel_err(gdX, dX) <= TOLBF
+
+
+@pytest.mark.parametrize("din,dout", [(602, 128), (200, 150), (96, 200), (301, 41)])
+def test_layer_bf16_wide_widths_on_aligned_rows(ctx, din, dout):
+    """bf16 layers with a width above 128 (the 602-feature input layer of the social workload): the
+    separate dense products on 16-byte aligned rows, both orders, with the ReLU mask as values."""
+    m, k = 1300, 1700
+    rowptr, col, val = random_block(m, k, 7 * din + dout)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(din + 2 * dout)
+
+    def rows16(a):
+        ld = -(-a.shape[1] // 8) * 8
+        t = torch.full((a.shape[0], ld), float("nan"), dtype=torch.bfloat16, device=DEV)
+        t[:, :a.shape[1]] = torch.as_tensor(np.asarray(a, np.float32)).to(torch.bfloat16).to(DEV)
+        return t, t[:, :a.shape[1]]
+
+    _, Xd = rows16(r.standard_normal((k, din)))
+    X64 = Xd.double().cpu().numpy()
+    W = (r.standard_normal((din, dout)) * 0.2).astype(np.float32)
+    Hagg = oracle.spmm_coo(m, row, c64, v64, X64)
+    Q = oracle.gemm(Hagg, W)
+    dF = r.standard_normal((m, dout)) * (np.abs(Q) > 2e-2 * np.abs(Q).max())      # keep clear of the mask's rounding band
+    _, dFd = rows16(dF)
+    dF64 = dFd.double().cpu().numpy()
+    dQ = oracle.relu_bwd(Q, dF64)
+    dW = oracle.gemm(Hagg, dQ, ta=True)
+    dX = oracle.spmm_t_coo(k, row, c64, v64, oracle.gemm(dQ, W, tb=True))
+    for order in (plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_COMBINE_FIRST):
+        nbytes = plx.plx_gcn_layer_workspace(csr, False, din, dout, dtype=plx.PLX_BF16, order=order)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+        Fp, F = rows16(np.zeros((m, dout)))
+        _, saved = rows16(np.zeros((m, din)))
+        gXp, gdX = rows16(np.zeros((k, din)))
+        gdW = torch.empty(din, dout, device=DEV)
+        plx.plx_gcn_layer_fwd(ctx, csr, False, Xd, dev(W), None, F, saved, ws, order=order)
+        plx.plx_gcn_layer_bwd(ctx, csr, False, Xd, dev(W), F, dFd, saved, gdX, gdW, ws, order=order)
+        plx.plx_sync(ctx)
+        assert rel_err(F.float(), oracle.relu(Q)) <= TOLBF
+        assert rel_err(gdW, dW) <= TOLBF
+        assert rel_err(gdX.float(), dX) <= TOLBF
+        for t, wdt in ((Fp, dout), (gXp, din)):                                  # padding untouched
+            assert bool(torch.isnan(t[:, wdt:].float()).all())
 
 
 def test_three_layer_network_bf16(ctx):
