@@ -99,12 +99,17 @@ def kernel_cost(name, bins, names=()):
         s = 4 if m.group(1) == "f32" else 2
         R, M, N = map(int, m.groups()[1:])
         return s * R * (M + N) + 4 * M * N, 2 * R * M * N
-    m = re.match(r"bwd_dense<(f32|bf16)>\[R(\d+),M(\d+),N(\d+)\]", name)
-    if m:       # reads the gradient, the mask source (values, or one bit per element) and P; writes dOut; two products
+    m = re.match(r"bwd_dense<(f32|bf16)>\[R(\d+),M(\d+),N(\d+)\](.*)", name)
+    if m:       # reads the gradient (or its factor dT), the mask source (values, or one bit per element) and P; writes dOut
         s = 4 if m.group(1) == "f32" else 2
-        R, M, N = map(int, m.groups()[1:])
-        mask = 4 * R * ((N + 31) // 32) if name.endswith("bits") else s * R * N
-        return s * R * (N + 2 * M) + mask + 4 * M * N, 4 * R * M * N
+        R, M, N = map(int, m.groups()[1:4])
+        tail = m.group(5)
+        mask = 0 if "nomask" in tail else (4 * R * ((N + 31) // 32) if "bits" in tail else s * R * N)
+        f = re.search(r"fact(\d+)", tail)
+        dn = int(f.group(1)) if f else 0
+        grad = s * R * (dn if f else N)
+        dout = 0 if "dWonly" in tail else 1
+        return grad + s * R * M * (1 + dout) + mask + 4 * M * N, 2 * R * M * N * (1 + dout) + 2 * R * N * dn
     m = re.match(r"(relu|relu_bwd|softmax_ce)\[R(\d+),C(\d+)\]", name)
     if m:
         R, C = int(m.group(2)), int(m.group(3))

@@ -254,6 +254,45 @@ PLX_API plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int trans
                                      int64_t din, int64_t dout, plx_dtype dtype, plx_act act, plx_order order,
                                      void* dH, int64_t lddh, float* dW, int64_t lddw, void* ws, size_t ws_bytes);
 
+/* ---- backward of two consecutive layers without the gradient between them -------------------------
+ * Layer l+1 in combine-first order computes T = H W, Z = A T (Eq. 2.1-2.2 in that order); its
+ * backward pass is dT = A^T dZ, dW = H^T dT (Eq. 2.5) and dH = dT W^T (Eq. 2.6).  dH[ka x din] is
+ * the dF of layer l and, on a graph of low degree, the largest matrix a step moves.  The two calls
+ * below leave it out: the first stops before Eq. 2.6 and hands out dT (ka x dout, far narrower),
+ * the second takes the pair (dT, W) of the following layer in place of dF and forms dF = dT W^T tile
+ * by tile inside its fused backward kernel.
+ *
+ * plx_gcn_layer_bwd_dt: as plx_gcn_layer_bwd in combine-first order with dH == NULL, except that
+ *   dT[ka x dout] (dtype `dtype`, device, caller's) receives A^T (dF * [Z > 0]).  W is not read.
+ *   ws: plx_gcn_layer_workspace(..., PLX_ORDER_COMBINE_FIRST) bytes.
+ * plx_gcn_layer_bwd_chained: as plx_gcn_layer_bwd with dF = dTn Wn^T, where dTn[ma x dn] (dtype
+ *   `dtype`) is the dT of the following layer and Wn[dout x dn] (fp32) its weight matrix.  The
+ *   product is formed inside the fused kernel for fp32, aggregate-first order, 32 < din <= 128,
+ *   64 < dout <= 128, dn <= 32, no mask or the sign-bit mask, 16-byte aligned rows of `saved` and
+ *   dTn, split products on; in every other case it is formed once in the workspace and the call
+ *   proceeds as plx_gcn_layer_bwd would (same results, no saving).
+ *   ws: plx_gcn_layer_bwd_chained_workspace(...) bytes: the layer workspace, plus room for that
+ *   formed gradient unless the shapes (and the context's split-product switch) put the product
+ *   inside the kernel.  The query takes 16-byte aligned rows for granted; if the call then meets
+ *   unaligned ones and the workspace lacks the room, it fails with PLX_ERR_SHAPE and names the size.
+ * Errors as plx_gcn_layer_bwd; PLX_ERR_INVALID if dT / dTn / Wn is NULL or dn <= 0, PLX_ERR_SHAPE
+ * if lddt < dout, lddtn < dn or ldwn < dn. */
+PLX_API plx_status plx_gcn_layer_bwd_dt(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
+                                        const void* H, int64_t ldh, const void* Z, int64_t ldz,
+                                        const void* dF, int64_t lddf, int64_t din, int64_t dout,
+                                        plx_dtype dtype, plx_act act, void* dT, int64_t lddt,
+                                        float* dW, int64_t lddw, void* ws, size_t ws_bytes);
+PLX_API size_t plx_gcn_layer_bwd_chained_workspace(const plx_ctx* ctx, const plx_csr* csr, int transposed_A,
+                                                   int64_t din, int64_t dout, int64_t dn,
+                                                   plx_dtype dtype, plx_act act, plx_order order);
+PLX_API plx_status plx_gcn_layer_bwd_chained(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
+                                             const void* H, int64_t ldh, const float* W, int64_t ldw,
+                                             const void* Z, int64_t ldz, const void* dTn, int64_t lddtn,
+                                             const float* Wn, int64_t ldwn, int64_t dn,
+                                             const void* saved, int64_t ldsaved,
+                                             int64_t din, int64_t dout, plx_dtype dtype, plx_act act, plx_order order,
+                                             void* dH, int64_t lddh, float* dW, int64_t lddw, void* ws, size_t ws_bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,6 +28,7 @@ EXPORTED = [
     "plx_csr_set_row_blocks", "plx_csr_row_blocks", "plx_spmm_block", "plx_spmm", "plx_spmm_t", "plx_gemm_nn", "plx_gemm_nt", "plx_gemm_tn_workspace", "plx_gemm_tn",
     "plx_relu", "plx_relu_bwd", "plx_softmax_ce",
     "plx_gcn_layer_workspace", "plx_gcn_layer_fwd", "plx_gcn_layer_bwd",
+    "plx_gcn_layer_bwd_dt", "plx_gcn_layer_bwd_chained_workspace", "plx_gcn_layer_bwd_chained",
 ]
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
@@ -74,6 +75,11 @@ def _load() -> ctypes.CDLL:
                                      _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz]),
         "plx_gcn_layer_bwd": (_int, [_vp, _vp, _int, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64,
                                      _i64, _i64, _int, _int, _int, _vp, _i64, _vp, _i64, _vp, _sz]),
+        "plx_gcn_layer_bwd_dt": (_int, [_vp, _vp, _int, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _int, _int,
+                                        _vp, _i64, _vp, _i64, _vp, _sz]),
+        "plx_gcn_layer_bwd_chained_workspace": (_sz, [_vp, _vp, _int, _i64, _i64, _i64, _int, _int, _int]),
+        "plx_gcn_layer_bwd_chained": (_int, [_vp, _vp, _int, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64,
+                                             _vp, _i64, _i64, _i64, _int, _int, _int, _vp, _i64, _vp, _i64, _vp, _sz]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)          # AttributeError if the library lacks a declared symbol
@@ -380,3 +386,31 @@ def plx_gcn_layer_bwd(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, H: Optiona
     ctx.check(_lib.plx_gcn_layer_bwd(ctx.handle, csr.handle, int(transposed_A), hp, ldh, wp, ldw, zp, ldz, gp, ldg,
                                      sp, lds, din, dout, _dtype_code(dF), act, order, dhp, lddh, dwp, lddw,
                                      ws.data_ptr(), ws.numel()))
+
+
+def plx_gcn_layer_bwd_dt(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, H: torch.Tensor, Z: Optional[torch.Tensor],
+                         dF: torch.Tensor, dT: torch.Tensor, dW: torch.Tensor, ws: torch.Tensor,
+                         act: int = PLX_ACT_RELU) -> None:
+    """Combine-first backward up to dT = A^T (dF * [Z > 0]) and dW = H^T dT; dH = dT W^T is left to the consumer."""
+    (hp, ldh), (zp, ldz), (gp, ldg), (tp, ldt), (dwp, lddw) = _mat(H), _mat(Z), _mat(dF), _mat(dT), _mat(dW)
+    din, dout = dW.shape
+    ctx.check(_lib.plx_gcn_layer_bwd_dt(ctx.handle, csr.handle, int(transposed_A), hp, ldh, zp, ldz, gp, ldg, din, dout,
+                                        _dtype_code(dF), act, tp, ldt, dwp, lddw, ws.data_ptr(), ws.numel()))
+
+
+def plx_gcn_layer_bwd_chained_workspace(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, din: int, dout: int, dn: int,
+                                        dtype: int = PLX_F32, act: int = PLX_ACT_RELU, order: int = PLX_ORDER_AUTO) -> int:
+    return int(_lib.plx_gcn_layer_bwd_chained_workspace(ctx.handle, csr.handle, int(transposed_A), din, dout, dn, dtype, act, order))
+
+
+def plx_gcn_layer_bwd_chained(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, H: Optional[torch.Tensor], W: torch.Tensor,
+                              Z: Optional[torch.Tensor], dTn: torch.Tensor, Wn: torch.Tensor, saved: Optional[torch.Tensor],
+                              dH: Optional[torch.Tensor], dW: torch.Tensor, ws: torch.Tensor,
+                              act: int = PLX_ACT_RELU, order: int = PLX_ORDER_AUTO) -> None:
+    """plx_gcn_layer_bwd with the upstream gradient given as the following layer's (dT, W): dF = dTn Wn^T."""
+    (hp, ldh), (wp, ldw), (zp, ldz), (gp, ldg), (wnp, ldwn), (sp, lds) = _mat(H), _mat(W), _mat(Z), _mat(dTn), _mat(Wn), _mat(saved)
+    (dhp, lddh), (dwp, lddw) = _mat(dH), _mat(dW)
+    din, dout = W.shape
+    ctx.check(_lib.plx_gcn_layer_bwd_chained(ctx.handle, csr.handle, int(transposed_A), hp, ldh, wp, ldw, zp, ldz, gp, ldg,
+                                             wnp, ldwn, Wn.shape[1], sp, lds, din, dout, _dtype_code(dTn), act, order,
+                                             dhp, lddh, dwp, lddw, ws.data_ptr(), ws.numel()))

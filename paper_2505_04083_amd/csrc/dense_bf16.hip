@@ -619,8 +619,8 @@ plx_status launch_bwd_dense_bf16(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N,
     float* part = static_cast<float*>(ws);
     const int tmb = Mp <= 32 ? 1 : (Mp <= 64 ? 2 : 4), tnb = N <= 32 ? 1 : (N <= 64 ? 2 : 4);
     char label[64];
-    snprintf(label, sizeof label, "bwd_dense<bf16>[R%lld,M%lld,N%lld]%s", (long long)R, (long long)Mp, (long long)N,
-             (Zm && mask_bits) ? "bits" : "");
+    snprintf(label, sizeof label, "bwd_dense<bf16>[R%lld,M%lld,N%lld]%s%s", (long long)R, (long long)Mp, (long long)N,
+             !Zm ? "nomask" : (mask_bits ? "bits" : ""), dOut ? "" : "dWonly");
     plx_status st;
     {
         KernelTimer kt(ctx, label);

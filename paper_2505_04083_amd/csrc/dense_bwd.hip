@@ -338,13 +338,22 @@ __device__ __forceinline__ void commit_split(bf16_t* dst, const TileRegs<TR, COL
 #ifndef PLX_X3_BWD_WAVES
 #define PLX_X3_BWD_WAVES 2
 #endif
-template <int TMB, int TNB, int MASK>   // 64 <= Mp <= 32*TMB, 64 <= N <= 32*TNB (TMB, TNB in {2, 4}); 16-byte aligned rows
+// DNS > 0: the gradient arrives in factored form, Q = Gf Wn^T with Gf[R x dn] and Wn[N x dn], dn <= 16*DNS (the
+// following combine-first layer's A^T dZ and its weights, Eq. 2.6 of that layer; DNS <= 2): the 32 x N tile of Q is formed
+// here, by the same split products, and goes straight to LDS, so the R x N gradient is neither written by
+// that layer nor read by this one.  Wavefront w forms columns 32w .. 32w+31 (TNB == 4) as Q^T = Wn Gf^T, which
+// leaves a lane with four consecutive columns of one row per group of accumulator registers: the layout
+// the masking and the split already work on.  Mask: none or sign bits.
+template <int TMB, int TNB, int MASK, int DNS>   // 64 <= Mp <= 32*TMB, 64 <= N <= 32*TNB (TMB, TNB in {2, 4}); 16-byte aligned rows
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_BWD_WAVES))) void k_bwd_dense_x3(int64_t R, int Mp, int N, const float* __restrict__ P, int64_t ldp,
                                                       const float* __restrict__ Q, int64_t ldq,
                                                       const float* __restrict__ Zm, int64_t ldz,
                                                       const float* __restrict__ W, int64_t ldw,
                                                       float* __restrict__ dOut, int64_t ldo, float* __restrict__ part,
-                                                      int64_t rows_per_chunk) {
+                                                      int64_t rows_per_chunk, const float* __restrict__ Gf, int64_t ldg,
+                                                      const float* __restrict__ Wn, int64_t ldwn, int dn) {
+    constexpr bool FACT = DNS > 0;
+    static_assert(!FACT || (TNB == 4 && MASK != kMaskValues), "shapes of the factored gradient");
     constexpr int MP = 32 * TMB, NP = 32 * TNB, SQ = NP + PLX_X3_PAD, SP = MP + PLX_X3_PAD;
     constexpr int NBLK = TMB * TNB / 4;                       // 32x32 blocks of dW per wavefront (block q belongs to wavefront q % 4)
     constexpr int NCW = MP / 64, NRW = kTR / 16, NKS = NP / 32;   // dOut: NCW column blocks of 16 per wavefront, both row blocks
@@ -399,19 +408,115 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_BWD_
     TileBits<kTR, MP> nb;                  // never read
     TileOffs<kTR, NP> oq, oz;
     TileOffs<kTR, MP> op;
-    tile_offsets<kTR, NP>(oq, ldq, N, tid);
+    if (!FACT) tile_offsets<kTR, NP>(oq, ldq, N, tid);
     if (MASK == kMaskValues) tile_offsets<kTR, NP>(oz, ldz, N, tid);
     tile_offsets<kTR, MP>(op, ldp, Mp, tid);
     const uint32_t* Zbits = reinterpret_cast<const uint32_t*>(Zm);
-    const uint32_t ob = MASK == kMaskBits ? bits_offset<kTR, NP>(ldz, N, tid) : 0u;
+    const uint32_t ob = (MASK == kMaskBits && !FACT) ? bits_offset<kTR, NP>(ldz, N, tid) : 0u;
+
+    // factored gradient: planes of Wn[32w + l32][16s + 8*lh .. +7] for the whole kernel; per tile a lane fetches
+    // Gf[row l32][16s + 8*lh .. +7] (two 16-byte pieces per s) and the sign word of (row l32, columns 32w ..)
+    constexpr int NS = FACT ? DNS : 1;
+    bf16x8 wnreg[NS][3];
+    uint32_t goff[NS][2];
+    float4 gq[NS][2];
+    uint32_t zw = 0;
+    const uint32_t zoff = (FACT && MASK == kMaskBits && 32 * w < N) ? (uint32_t)(((uint32_t)l32 * (uint32_t)ldz + w) * 4u) : kOutOfRange;
+    if constexpr (FACT) {
+        const int n = 32 * w + l32;
+#pragma unroll
+        for (int s2 = 0; s2 < NS; ++s2) {
+            Frag f[3];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int k = 16 * s2 + 8 * lh + 4 * h;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (n < N) {
+                    const float* wp = Wn + (int64_t)n * ldwn + k;
+                    if (k < dn) v.x = wp[0];
+                    if (k + 1 < dn) v.y = wp[1];
+                    if (k + 2 < dn) v.z = wp[2];
+                    if (k + 3 < dn) v.w = wp[3];
+                }
+                uint2 pl[3];
+                split3(v, pl);
+#pragma unroll
+                for (int p = 0; p < 3; ++p) { f[p].x[2 * h] = pl[p].x; f[p].x[2 * h + 1] = pl[p].y; }
+                goff[s2][h] = k < dn ? (uint32_t)(((uint32_t)l32 * (uint32_t)ldg + k) * 4u) : kOutOfRange;
+            }
+#pragma unroll
+            for (int p = 0; p < 3; ++p) wnreg[s2][p] = f[p].v;
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+    }
     auto fetch = [&](int64_t r0) {
-        fetch_tile<kTR, NP, true>(rq, Q, ldq, r0, r_end, R, N, tid, oq);
-        if (MASK == kMaskValues) fetch_tile<kTR, NP, true>(rz, Zm, ldz, r0, r_end, R, N, tid, oz);
-        if (MASK == kMaskBits) fetch_bits<kTR, NP>(zb, Zbits, ldz, r0, r_end, N, ob);
+        if constexpr (FACT) {
+            const int64_t left = r_end - r0;
+            const int64_t rows = left < kTR ? left : kTR;
+            const __amdgpu_buffer_rsrc_t rg = buffer_of(Gf + r0 * ldg, rows > 0 ? (uint32_t)(((rows - 1) * ldg + dn) * 4) : 0u);
+#pragma unroll
+            for (int s2 = 0; s2 < NS; ++s2)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) gq[s2][h] = buffer_load4(rg, goff[s2][h]);
+            if (MASK == kMaskBits) {
+                const __amdgpu_buffer_rsrc_t rb = buffer_of(Zbits + r0 * ldz, rows > 0 ? (uint32_t)(((rows - 1) * ldz + (N + 31) / 32) * 4) : 0u);
+                zw = buffer_load1(rb, zoff);
+            }
+        } else {
+            fetch_tile<kTR, NP, true>(rq, Q, ldq, r0, r_end, R, N, tid, oq);
+            if (MASK == kMaskValues) fetch_tile<kTR, NP, true>(rz, Zm, ldz, r0, r_end, R, N, tid, oz);
+            if (MASK == kMaskBits) fetch_bits<kTR, NP>(zb, Zbits, ldz, r0, r_end, N, ob);
+        }
         fetch_tile<kTR, MP, true>(rp, P, ldp, r0, r_end, R, Mp, tid, op);
     };
+    // registers -> the three planes of the (masked) gradient tile in LDS
+    auto commit_q = [&]() {
+        if constexpr (FACT) {
+            floatx16 qt;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) qt[r] = 0.f;
+#pragma unroll
+            for (int s2 = 0; s2 < NS; ++s2) {
+                if (s2 > 0 && 16 * s2 >= dn) break;                          // uniform
+                Frag f[3];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    float4 v = gq[s2][h];
+                    if (dn & 3) {                                            // uniform: the piece that straddles dn holds padding
+                        const int k = 16 * s2 + 8 * lh + 4 * h;
+                        if (k + 1 >= dn) v.y = 0.f;
+                        if (k + 2 >= dn) v.z = 0.f;
+                        if (k + 3 >= dn) v.w = 0.f;
+                    }
+                    uint2 pl[3];
+                    split3(v, pl);
+#pragma unroll
+                    for (int p = 0; p < 3; ++p) { f[p].x[2 * h] = pl[p].x; f[p].x[2 * h + 1] = pl[p].y; }
+                }
+                bf16x8 b[3] = {f[0].v, f[1].v, f[2].v};
+                PLX_X3_32(qt, wnreg[s2], b);                                 // qt[r] = Q[row l32][32w + 8*(r/4) + 4*lh + r%4]
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float4 v = make_float4(qt[4 * g], qt[4 * g + 1], qt[4 * g + 2], qt[4 * g + 3]);
+                if (MASK == kMaskBits) {
+                    const unsigned s0 = 8 * g + 4 * lh;
+                    v.x = __uint_as_float(__float_as_uint(v.x) & (unsigned)__builtin_amdgcn_sbfe((int)zw, s0, 1));
+                    v.y = __uint_as_float(__float_as_uint(v.y) & (unsigned)__builtin_amdgcn_sbfe((int)zw, s0 + 1, 1));
+                    v.z = __uint_as_float(__float_as_uint(v.z) & (unsigned)__builtin_amdgcn_sbfe((int)zw, s0 + 2, 1));
+                    v.w = __uint_as_float(__float_as_uint(v.w) & (unsigned)__builtin_amdgcn_sbfe((int)zw, s0 + 3, 1));
+                }
+                uint2 pl[3];
+                split3(v, pl);
+#pragma unroll
+                for (int p = 0; p < 3; ++p) *reinterpret_cast<uint2*>(Qs + p * kTR * SQ + l32 * SQ + 32 * w + 8 * g + 4 * lh) = pl[p];
+            }
+        } else {
+            commit_split<kTR, NP, MASK>(Qs, rq, rz, zb, tid);
+        }
+    };
     fetch(r_begin);
-    commit_split<kTR, NP, MASK>(Qs, rq, rz, zb, tid);
+    commit_q();
     commit_split<kTR, MP, kMaskNone>(Ps, rp, rp, nb, tid);
     __syncthreads();
 
@@ -453,7 +558,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_BWD_
             }
         }
         __syncthreads();                                               // every wavefront is done reading the tile
-        commit_split<kTR, NP, MASK>(Qs, rq, rz, zb, tid);
+        commit_q();
         commit_split<kTR, MP, kMaskNone>(Ps, rp, rp, nb, tid);
         if (dOut) {
             const bool full = r0 + kTR <= r_end;                       // uniform: only the last tile is partial
@@ -493,23 +598,43 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_BWD_
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+// the gradient in factored form, Q = G Wn^T (G: R x dn, Wn: N x dn); G == NULL: Q is given
+struct Factor {
+    const float* G = nullptr;
+    int64_t ldg = 0;
+    const float* Wn = nullptr;
+    int64_t ldwn = 0;
+    int dn = 0;
+};
+
 template <int TMB, int TNB, int MASK>
 plx_status run_masked(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
                       const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
-                      int64_t rpc, int64_t chunks, bool vec, bool split) {
+                      int64_t rpc, int64_t chunks, bool vec, bool split, const Factor& fac) {
     constexpr int MP = 32 * TMB, NP = 32 * TNB;
     const size_t lds = sizeof(float) * (kTR * (NP + 4) + kTR * (MP + 4));
     if constexpr (TMB >= 2 && TNB >= 2) {
         if (split) {                                                     // both widths above 32: the fp32 matrix pipe binds
             const size_t lds3 = sizeof(bf16_t) * 3 * kTR * ((NP + PLX_X3_PAD) + (MP + PLX_X3_PAD));
-            auto kern = k_bwd_dense_x3<TMB, TNB, MASK>;
-            if (lds3 > 48 * 1024)
-                PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds3));
-            kern<<<dim3((unsigned)chunks), 256, lds3, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc);
-            PLX_HIP(ctx, hipGetLastError());
-            return PLX_OK;
+            auto launch3 = [&](auto kern) -> plx_status {
+                if (lds3 > 48 * 1024)
+                    PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds3));
+                kern<<<dim3((unsigned)chunks), 256, lds3, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc,
+                                                                        fac.G, fac.ldg, fac.Wn, fac.ldwn, fac.dn);
+                PLX_HIP(ctx, hipGetLastError());
+                return PLX_OK;
+            };
+            if (fac.G) {
+                if constexpr (TNB == 4 && MASK != kMaskValues) {
+                    if (fac.dn <= 16) return launch3(k_bwd_dense_x3<TMB, TNB, MASK, 1>);
+                    return launch3(k_bwd_dense_x3<TMB, TNB, MASK, 2>);
+                }
+                return fail(ctx, PLX_ERR_INTERNAL, "factored gradient outside the fused kernel's range");
+            }
+            return launch3(k_bwd_dense_x3<TMB, TNB, MASK, 0>);
         }
     }
+    if (fac.G) return fail(ctx, PLX_ERR_INTERNAL, "factored gradient outside the fused kernel's range");
     auto launch = [&](auto kern) -> plx_status {
         kern<<<dim3((unsigned)chunks), 256, lds, ctx->stream>>>(R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc);
         PLX_HIP(ctx, hipGetLastError());
@@ -521,23 +646,37 @@ plx_status run_masked(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, in
 template <int TMB, int TNB>
 plx_status run(plx_ctx* ctx, int64_t R, int Mp, int N, const float* P, int64_t ldp, const float* Q, int64_t ldq,
                const float* Zm, int64_t ldz, const float* W, int64_t ldw, float* dOut, int64_t ldo, float* part,
-               int64_t rpc, int64_t chunks, bool mask_bits, bool vec, bool split) {
-    if (!Zm) return run_masked<TMB, TNB, kMaskNone>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks, vec, split);
-    return mask_bits ? run_masked<TMB, TNB, kMaskBits>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks, vec, split)
-                     : run_masked<TMB, TNB, kMaskValues>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks, vec, split);
+               int64_t rpc, int64_t chunks, bool mask_bits, bool vec, bool split, const Factor& fac) {
+    if (!Zm) return run_masked<TMB, TNB, kMaskNone>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks, vec, split, fac);
+    return mask_bits ? run_masked<TMB, TNB, kMaskBits>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks, vec, split, fac)
+                     : run_masked<TMB, TNB, kMaskValues>(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, part, rpc, chunks, vec, split, fac);
 }
 
 }  // namespace
 
 bool bwd_dense_supported(int64_t Mp, int64_t N, plx_dtype dtype) { return (dtype == PLX_F32 || dtype == PLX_BF16) && Mp <= 128 && N <= 128; }
 
+// Can the fused kernel form its gradient tile from the factors G[R x dn] Wn[N x dn]^T itself?  Only the split fp32
+// kernel with four column blocks does (64 < N <= 128, 32 < Mp <= 128, no value mask, 16-byte aligned rows), and
+// only for dn <= 32: every 16 values of dn add six matrix instructions and two splits per tile and 12 registers
+// to a kernel that is bound by exactly those (measured: dn = 47, four steps, spills and doubles the kernel's time).
+bool bwd_dense_factor_supported(const plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, int64_t dn, plx_dtype dtype, const void* P,
+                                int64_t ldp, const void* G, int64_t ldg, int64_t ldz, int64_t ldo, bool value_mask) {
+    return dtype == PLX_F32 && ctx->split_products && R > 0 && Mp > 32 && Mp <= 128 && N > 64 && N <= 128 && dn > 0 && dn <= 32 &&
+           !value_mask && aligned16(P) && ldp % 4 == 0 && aligned16(G) && ldg % 4 == 0 &&
+           std::max(std::max(ldp, ldg), std::max(ldz, ldo)) < (int64_t(1) << 23);
+}
+
 plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, const void* P, int64_t ldp, const void* Q,
                             int64_t ldq, const void* Zm, int64_t ldz, const float* W, int64_t ldw, void* dOut, int64_t ldo,
-                            float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes, bool mask_bits) {
+                            float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes, bool mask_bits,
+                            const float* G, int64_t ldg, const float* Wn, int64_t ldwn, int64_t dn) {
     if (!bwd_dense_supported(Mp, N, dtype)) return fail(ctx, PLX_ERR_INTERNAL, "fused backward called outside its range");
     // a tile is addressed with 31-bit byte offsets: 32 rows * ld * 4 bytes must fit
     if (std::max(std::max(ldp, ldq), std::max(ldz, ldo)) >= (int64_t(1) << 23))
         return fail(ctx, PLX_ERR_UNSUPPORTED, "leading dimensions of 2^23 elements or more are not supported by the fused backward kernels");
+    if (G && !bwd_dense_factor_supported(ctx, R, Mp, N, dn, dtype, P, ldp, G, ldg, ldz, ldo, Zm && !mask_bits))
+        return fail(ctx, PLX_ERR_INTERNAL, "factored gradient outside the fused kernel's range");
     if (dtype == PLX_BF16)
         return launch_bwd_dense_bf16(ctx, R, Mp, N, P, ldp, Q, ldq, Zm, ldz, W, ldw, dOut, ldo, dW, lddw, ws, ws_bytes, mask_bits);
     if (ws_bytes < gemm_tn_workspace(R, Mp, N)) return fail(ctx, PLX_ERR_SHAPE, "workspace too small");
@@ -549,16 +688,22 @@ plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, cons
     // 128-bit tile loads need 16-byte aligned rows; the split path (six bf16 products per fp32 product) serves the
     // shapes whose fp32 matrix work binds, i.e. both widths above 32
     const bool values = Zm && !mask_bits;
-    const bool vec = aligned16(P) && ldp % 4 == 0 && aligned16(Q) && ldq % 4 == 0 && (!values || (aligned16(Zm) && ldz % 4 == 0)) && R > 0;
+    const bool vec = aligned16(P) && ldp % 4 == 0 && (G || (aligned16(Q) && ldq % 4 == 0)) && (!values || (aligned16(Zm) && ldz % 4 == 0)) && R > 0;
     const bool split = vec && ctx->split_products && tmb >= 2 && tnb >= 2;
-    snprintf(label, sizeof label, "bwd_dense<f32>[R%lld,M%lld,N%lld]%s%s", (long long)R, (long long)Mp, (long long)N,
-             split ? "x3" : "", (Zm && mask_bits) ? "bits" : "");
+    Factor fac;
+    fac.G = G; fac.ldg = ldg; fac.Wn = Wn; fac.ldwn = ldwn; fac.dn = (int)dn;
+    char fact[16] = "";
+    if (G) snprintf(fact, sizeof fact, "fact%lld", (long long)dn);
+    // suffixes: x3 split products, bits / nomask how Eq. 2.4 arrives (default: a value matrix), fact<dn> factored gradient,
+    // dWonly Eq. 2.6 not wanted
+    snprintf(label, sizeof label, "bwd_dense<f32>[R%lld,M%lld,N%lld]%s%s%s%s", (long long)R, (long long)Mp, (long long)N,
+             split ? "x3" : "", !Zm ? "nomask" : (mask_bits ? "bits" : ""), fact, dOut ? "" : "dWonly");
     plx_status st;
     {
         KernelTimer kt(ctx, label);
 #define PLX_BD(TM, TN)                                                                                              \
     st = run<TM, TN>(ctx, R, (int)Mp, (int)N, (const float*)P, ldp, (const float*)Q, ldq, (const float*)Zm, ldz, W, ldw, \
-                     (float*)dOut, ldo, part, rpc, chunks, mask_bits, vec, split)
+                     (float*)dOut, ldo, part, rpc, chunks, mask_bits, vec, split, fac)
         switch (tmb * 10 + tnb) {
             case 11: PLX_BD(1, 1); break;
             case 12: PLX_BD(1, 2); break;

@@ -464,18 +464,51 @@ plx_status plx_gcn_layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
     return PLX_OK;
 }
 
-plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* H, int64_t ldh,
-                             const float* W, int64_t ldw, const void* Z, int64_t ldz, const void* dF, int64_t lddf,
-                             const void* saved, int64_t ldsaved, int64_t din, int64_t dout, plx_dtype dtype,
-                             plx_act act, plx_order order, void* dH, int64_t lddh, float* dW, int64_t lddw, void* ws,
-                             size_t ws_bytes) {
+}  // extern "C"
+
+namespace {
+
+// How a backward call departs from plx_gcn_layer_bwd (all zero: it does not).
+struct BwdVariant {
+    // the upstream gradient in factored form, dF = Gn Wn^T (Gn: ma x dn, dtype of the layer; Wn: dout x dn), instead of dF
+    const void* Gn = nullptr;
+    int64_t ldgn = 0;
+    const float* Wn = nullptr;
+    int64_t ldwn = 0, dn = 0;
+    // combine-first order: A^T dZ goes here instead of into the workspace, and Eq. 2.6 (dH) is left to the caller
+    void* dT = nullptr;
+    int64_t lddt = 0;
+};
+
+// bytes of the formed gradient behind the layer workspace (layer_bwd with factors outside the fused kernel's range)
+size_t formed_gradient_bytes(const Orient& a, int64_t dout, plx_dtype dtype) {
+    return align256((size_t)a.rows * pad16(dout, dtype) * elt_size(dtype));
+}
+
+plx_status layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* H, int64_t ldh,
+                     const float* W, int64_t ldw, const void* Z, int64_t ldz, const void* dF, int64_t lddf,
+                     const void* saved, int64_t ldsaved, int64_t din, int64_t dout, plx_dtype dtype,
+                     plx_act act, plx_order order, void* dH, int64_t lddh, float* dW, int64_t lddw, void* ws,
+                     size_t ws_bytes, const BwdVariant& var) {
     if (!ctx) return PLX_ERR_INVALID;
     PLX_TRY(layer_common_checks(ctx, csr, din, dout, dtype, act, order));
     const int t = transposed_A ? 1 : 0;
     const Orient& a = csr->o[t];
     const Orient& at = csr->o[1 - t];   // the transpose of the layer's adjacency
     order = resolve_order(order, din, dout);
-    if (!W || !dF || !dW) return fail(ctx, PLX_ERR_INVALID, "W, dF or dW is NULL");
+    if (var.dT) {
+        if (order != PLX_ORDER_COMBINE_FIRST) return fail(ctx, PLX_ERR_INVALID, "the gradient of H W exists only in combine-first order");
+        if (var.lddt < dout) return fail(ctx, PLX_ERR_SHAPE, "lddt smaller than dout");
+        if (dH) return fail(ctx, PLX_ERR_INTERNAL, "dT and dH are alternatives");
+    } else if (!W) {
+        return fail(ctx, PLX_ERR_INVALID, "W is NULL");
+    }
+    if (var.Gn) {
+        if (!var.Wn || var.dn <= 0) return fail(ctx, PLX_ERR_INVALID, "Wn is NULL or dn is not positive");
+        if (var.ldgn < var.dn || var.ldwn < var.dn) return fail(ctx, PLX_ERR_SHAPE, "leading dimension of a factor smaller than dn");
+        lddf = dout;          // dF is formed here: its own leading dimension is not the caller's
+    }
+    if ((!dF && !var.Gn) || !dW) return fail(ctx, PLX_ERR_INVALID, "dF or dW is NULL");
     const bool sign_bits = act == PLX_ACT_RELU_BITS;
     if (act != PLX_ACT_NONE && !Z) return fail(ctx, PLX_ERR_INVALID, "Z is needed for the ReLU derivative");
     if (sign_bits && (reinterpret_cast<uintptr_t>(Z) & 3)) return fail(ctx, PLX_ERR_INVALID, "the sign bits need a 4-byte aligned Z");
@@ -490,17 +523,39 @@ plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
         if (ldh < din) return fail(ctx, PLX_ERR_SHAPE, "ldh smaller than din");
     }
     LayerWs w = layer_ws(a, din, dout, dtype, act, order);
-    if (!ws || ws_bytes < w.total)
-        return fail(ctx, PLX_ERR_SHAPE, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, w.total);
+    const void* mask = act != PLX_ACT_NONE ? Z : nullptr;
+    // the fused kernels address a tile with 31-bit byte offsets; wider leading dimensions take the separate products
+    const int64_t ld_max = std::max(std::max(ldsaved, ldh), std::max(std::max(lddf, ldz), lddh));
+    const bool fused = bwd_dense_supported(din, dout, dtype) && (ld_max < (int64_t(1) << 23) || dtype == PLX_BF16);
+    // factors: does the fused kernel form dF itself, or is it formed once behind the layer workspace?
+    const bool in_kernel = var.Gn && fused && order == PLX_ORDER_AGG_FIRST &&
+                           bwd_dense_factor_supported(ctx, a.rows, din, dout, var.dn, dtype, saved, ldsaved, var.Gn, var.ldgn, ldz,
+                                                      w.ld_in, mask && !sign_bits);
+    const size_t need = w.total + ((var.Gn && !in_kernel) ? formed_gradient_bytes(a, dout, dtype) : 0);
+    if (!ws || ws_bytes < need)
+        return fail(ctx, PLX_ERR_SHAPE, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
     if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
 
     char* base = static_cast<char*>(ws);
     void* tn_ws = base + w.off_tn;
     size_t tn_bytes = w.total - w.off_tn;
-    const void* mask = act != PLX_ACT_NONE ? Z : nullptr;
-    // the fused kernels address a tile with 31-bit byte offsets; wider leading dimensions take the separate products
-    const int64_t ld_max = std::max(std::max(ldsaved, ldh), std::max(std::max(lddf, ldz), lddh));
-    if (bwd_dense_supported(din, dout, dtype) && (ld_max < (int64_t(1) << 23) || dtype == PLX_BF16)) {
+    if (var.Gn) {
+        if (in_kernel) {
+            // Eq. 2.6 of the following layer, then Eq. 2.4 + 2.5 + 2.6 of this one, tile by tile: dF never exists in memory
+            void* dS = dH ? base + w.off_a : nullptr;
+            PLX_TRY(launch_bwd_dense(ctx, a.rows, din, dout, saved, ldsaved, nullptr, 0, mask, ldz, W, ldw, dS, w.ld_in, dW, lddw,
+                                     dtype, tn_ws, tn_bytes, sign_bits, static_cast<const float*>(var.Gn), var.ldgn, var.Wn, var.ldwn,
+                                     var.dn));
+            if (dH) PLX_TRY(launch_spmm(ctx, at, dS, w.ld_in, dH, lddh, din, dtype));        // Eq. 2.7
+            return PLX_OK;
+        }
+        // elsewhere the product is formed once, behind the layer workspace, and the call goes on as with a given dF
+        void* formed = base + w.total;
+        PLX_TRY(launch_gemm(ctx, true, a.rows, dout, var.dn, var.Gn, var.ldgn, var.Wn, var.ldwn, formed, w.ld_out, dtype));
+        dF = formed;
+        lddf = w.ld_out;
+    }
+    if (fused) {
         // Eq. 2.4 is applied while the gradient tile is loaded; it is never written back
         if (order == PLX_ORDER_AGG_FIRST) {
             void* dS = dH ? base + w.off_a : nullptr;
@@ -515,9 +570,10 @@ plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
                 PLX_TRY(launch_relu_bwd(ctx, a.rows, dout, Z, ldz, dF, lddf, buf, w.ld_out, dtype, sign_bits));
                 dZ = buf; lddz = w.ld_out;
             }
-            void* G = base + w.off_a;
-            PLX_TRY(launch_spmm(ctx, at, dZ, lddz, G, w.ld_out, dout, dtype));               // A^T dZ
-            PLX_TRY(launch_bwd_dense(ctx, a.cols, din, dout, H, ldh, G, w.ld_out, nullptr, 0, W, ldw, dH, lddh, dW, lddw, dtype,
+            void* G = var.dT ? var.dT : base + w.off_a;
+            const int64_t ldg = var.dT ? var.lddt : w.ld_out;
+            PLX_TRY(launch_spmm(ctx, at, dZ, lddz, G, ldg, dout, dtype));                    // A^T dZ
+            PLX_TRY(launch_bwd_dense(ctx, a.cols, din, dout, H, ldh, G, ldg, nullptr, 0, W, ldw, dH, lddh, dW, lddw, dtype,
                                      tn_ws, tn_bytes));
         }
         return PLX_OK;
@@ -537,12 +593,65 @@ plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
             PLX_TRY(launch_spmm(ctx, at, dS, w.ld_in, dH, lddh, din, dtype));                // Eq. 2.7
         }
     } else {
-        void* G = base + w.off_a;
-        PLX_TRY(launch_spmm(ctx, at, dZ, lddz, G, w.ld_out, dout, dtype));                   // A^T dZ
-        PLX_TRY(launch_gemm_tn(ctx, a.cols, din, dout, H, ldh, G, w.ld_out, dW, lddw, dtype, tn_ws, tn_bytes));
-        if (dH) PLX_TRY(launch_gemm(ctx, true, a.cols, din, dout, G, w.ld_out, W, ldw, dH, lddh, dtype));
+        void* G = var.dT ? var.dT : base + w.off_a;
+        const int64_t ldg = var.dT ? var.lddt : w.ld_out;
+        PLX_TRY(launch_spmm(ctx, at, dZ, lddz, G, ldg, dout, dtype));                        // A^T dZ
+        PLX_TRY(launch_gemm_tn(ctx, a.cols, din, dout, H, ldh, G, ldg, dW, lddw, dtype, tn_ws, tn_bytes));
+        if (dH) PLX_TRY(launch_gemm(ctx, true, a.cols, din, dout, G, ldg, W, ldw, dH, lddh, dtype));
     }
     return PLX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* H, int64_t ldh,
+                             const float* W, int64_t ldw, const void* Z, int64_t ldz, const void* dF, int64_t lddf,
+                             const void* saved, int64_t ldsaved, int64_t din, int64_t dout, plx_dtype dtype,
+                             plx_act act, plx_order order, void* dH, int64_t lddh, float* dW, int64_t lddw, void* ws,
+                             size_t ws_bytes) {
+    return layer_bwd(ctx, csr, transposed_A, H, ldh, W, ldw, Z, ldz, dF, lddf, saved, ldsaved, din, dout, dtype, act, order, dH,
+                     lddh, dW, lddw, ws, ws_bytes, BwdVariant{});
+}
+
+plx_status plx_gcn_layer_bwd_dt(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* H, int64_t ldh,
+                                const void* Z, int64_t ldz, const void* dF, int64_t lddf, int64_t din, int64_t dout,
+                                plx_dtype dtype, plx_act act, void* dT, int64_t lddt, float* dW, int64_t lddw, void* ws,
+                                size_t ws_bytes) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!dT) return fail(ctx, PLX_ERR_INVALID, "dT is NULL");
+    BwdVariant var;
+    var.dT = dT; var.lddt = lddt;
+    return layer_bwd(ctx, csr, transposed_A, H, ldh, nullptr, dout, Z, ldz, dF, lddf, nullptr, 0, din, dout, dtype, act,
+                     PLX_ORDER_COMBINE_FIRST, nullptr, 0, dW, lddw, ws, ws_bytes, var);
+}
+
+size_t plx_gcn_layer_bwd_chained_workspace(const plx_ctx* ctx, const plx_csr* csr, int transposed_A, int64_t din, int64_t dout,
+                                           int64_t dn, plx_dtype dtype, plx_act act, plx_order order) {
+    const size_t base = plx_gcn_layer_workspace(csr, transposed_A, din, dout, dtype, act, order);
+    if (base == 0 || !ctx || dn <= 0) return 0;
+    const Orient& a = csr->o[transposed_A ? 1 : 0];
+    // with 16-byte aligned rows (checked with the pointers, at the call) these shapes never form dF in memory
+    const int64_t ld4 = 4;
+    const bool in_kernel = resolve_order(order, din, dout) == PLX_ORDER_AGG_FIRST && act != PLX_ACT_RELU &&
+                           bwd_dense_factor_supported(ctx, a.rows, din, dout, dn, dtype, nullptr, ld4, nullptr, ld4, 0, 0, false);
+    return base + (in_kernel ? 0 : formed_gradient_bytes(a, dout, dtype));
+}
+
+plx_status plx_gcn_layer_bwd_chained(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* H, int64_t ldh,
+                                     const float* W, int64_t ldw, const void* Z, int64_t ldz, const void* dTn, int64_t lddtn,
+                                     const float* Wn, int64_t ldwn, int64_t dn, const void* saved, int64_t ldsaved,
+                                     int64_t din, int64_t dout, plx_dtype dtype, plx_act act, plx_order order, void* dH,
+                                     int64_t lddh, float* dW, int64_t lddw, void* ws, size_t ws_bytes) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!csr) return fail(ctx, PLX_ERR_INVALID, "csr is NULL");
+    if (!dTn) return fail(ctx, PLX_ERR_INVALID, "dTn is NULL");
+    if (!dtype_ok(dtype) || dout <= 0) return fail(ctx, PLX_ERR_INVALID, "unknown dtype or dout not positive");
+    BwdVariant var;
+    var.Gn = dTn; var.ldgn = lddtn; var.Wn = Wn; var.ldwn = ldwn; var.dn = dn;
+    return layer_bwd(ctx, csr, transposed_A, H, ldh, W, ldw, Z, ldz, nullptr, 0, saved, ldsaved, din, dout, dtype, act, order, dH,
+                     lddh, dW, lddw, ws, ws_bytes, var);
 }
 
 }  // extern "C"

@@ -167,7 +167,11 @@ plx_status reduce_partials(plx_ctx* ctx, float* part, int64_t chunks, int64_t M,
 bool bwd_dense_supported(int64_t Mp, int64_t N, plx_dtype dtype);
 plx_status launch_bwd_dense(plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, const void* P, int64_t ldp, const void* Q,
                             int64_t ldq, const void* Zm, int64_t ldz, const float* W, int64_t ldw, void* dOut, int64_t ldo,
-                            float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes, bool mask_bits = false);
+                            float* dW, int64_t lddw, plx_dtype dtype, void* ws, size_t ws_bytes, bool mask_bits = false,
+                            const float* G = nullptr, int64_t ldg = 0, const float* Wn = nullptr, int64_t ldwn = 0, int64_t dn = 0);
+// G != NULL: Q is not given but formed tile by tile as G[R x dn] Wn[N x dn]^T; only where this holds:
+bool bwd_dense_factor_supported(const plx_ctx* ctx, int64_t R, int64_t Mp, int64_t N, int64_t dn, plx_dtype dtype, const void* P,
+                                int64_t ldp, const void* G, int64_t ldg, int64_t ldz, int64_t ldo, bool value_mask);
 plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const void* A, int64_t lda,
                           const void* B, int64_t ldb, float* C, int64_t ldc, plx_dtype dtype, void* ws, size_t ws_bytes);
 plx_status launch_relu(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, void* F, int64_t ldf,

@@ -5,7 +5,9 @@ P_c A P_r^T for odd ones).  All buffers are allocated once, so a training step a
 Hidden layers store only the activated output (its sign serves Eq. 2.4) and, where the dense product
 of the layer can write them on the fly (aggregate-first order, widths up to 128), that sign packed
 one bit per element, which is all the backward pass then reads of it; the last layer stores the
-logits.  The input must be in P_c order and the labels in the order of the last layer's output."""
+logits.  Where a combine-first layer follows an aggregate-first one of fitting widths, the gradient
+matrix between them is never formed: the later layer's backward call stops at dT = A^T dZ and the
+earlier one takes (dT, W) in its place (`chain`).  The input must be in P_c order and the labels in the order of the last layer's output."""
 from __future__ import annotations
 
 from typing import List, Optional
@@ -13,7 +15,8 @@ from typing import List, Optional
 import torch
 
 from . import (PLX_ACT_NONE, PLX_ACT_RELU, PLX_ACT_RELU_BITS, PLX_BF16, PLX_F32, PLX_ORDER_AUTO, plx_gcn_layer_bwd,
-               plx_gcn_layer_fwd, plx_gcn_layer_workspace, plx_softmax_ce, plx_sync)
+               plx_gcn_layer_bwd_chained, plx_gcn_layer_bwd_chained_workspace, plx_gcn_layer_bwd_dt, plx_gcn_layer_fwd,
+               plx_gcn_layer_workspace, plx_softmax_ce, plx_sync)
 
 
 def aligned_rows(rows: int, cols: int, dtype, dev) -> torch.Tensor:
@@ -26,25 +29,41 @@ def aligned_rows(rows: int, cols: int, dtype, dev) -> torch.Tensor:
 
 class GcnNetwork:
     def __init__(self, ctx, csr, Ws: List[torch.Tensor], dtype=torch.float32, order: int = PLX_ORDER_AUTO,
-                 keep_preactivation: bool = False, sign_bits: bool = True):
+                 keep_preactivation: bool = False, sign_bits: bool = True, chain: bool = True):
         self.ctx, self.csr, self.Ws, self.order = ctx, csr, Ws, order
         self.L = len(Ws)
         dev = Ws[0].device
         code = PLX_F32 if dtype == torch.float32 else PLX_BF16
         self.act = [PLX_ACT_RELU if l + 1 < self.L else PLX_ACT_NONE for l in range(self.L)]
+        agg = [order == 1 or (order == PLX_ORDER_AUTO and W.shape[0] <= W.shape[1]) for W in Ws]
         for l, W in enumerate(Ws[:-1]):
             din, dout = W.shape
-            agg_first = order == 1 or (order == PLX_ORDER_AUTO and din <= dout)
-            if sign_bits and not keep_preactivation and agg_first and max(din, dout) <= 128:
+            if sign_bits and not keep_preactivation and agg[l] and max(din, dout) <= 128:
                 self.act[l] = PLX_ACT_RELU_BITS
+        # chained[l]: layer l+1 (combine-first) hands layer l its dT and W instead of the gradient matrix between them,
+        # taken where the fused backward kernel of layer l forms that gradient itself (the shapes the C header lists)
+        # in one 16-column step: measured on the road graph (64-128-16, 50 M nodes) the step costs layer l's kernel
+        # 3 % and saves layer l+1's kernel the 25.6 GB write of the gradient (10.5 -> 4.9 ms)
+        self.chained = [False] * self.L
+        for l in range(self.L - 1):
+            din, dout = Ws[l].shape
+            dn = Ws[l + 1].shape[1]
+            self.chained[l] = (chain and dtype == torch.float32 and agg[l] and not agg[l + 1] and 32 < din <= 128
+                               and 64 < dout <= 128 and dn <= 16 and self.act[l] != PLX_ACT_RELU)
         nbytes = 1
         for l, W in enumerate(Ws):
-            nbytes = max(nbytes, plx_gcn_layer_workspace(csr, bool(l % 2), W.shape[0], W.shape[1], code, self.act[l], order))
+            if self.chained[l]:
+                need = plx_gcn_layer_bwd_chained_workspace(ctx, csr, bool(l % 2), W.shape[0], W.shape[1], Ws[l + 1].shape[1], code,
+                                                           self.act[l], order)
+            else:
+                need = plx_gcn_layer_workspace(csr, bool(l % 2), W.shape[0], W.shape[1], code, self.act[l], order)
+            nbytes = max(nbytes, need)
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
         self.Z: List[Optional[torch.Tensor]] = []
         self.F: List[Optional[torch.Tensor]] = []
         self.saved: List[torch.Tensor] = []
-        self.dH: List[torch.Tensor] = []
+        self.dH: List[Optional[torch.Tensor]] = []
+        self.dT: List[Optional[torch.Tensor]] = []
         self.dW: List[torch.Tensor] = []
         for l, W in enumerate(Ws):
             rows, cols = csr.shape(bool(l % 2))
@@ -55,9 +74,10 @@ class GcnNetwork:
             else:
                 self.Z.append(aligned_rows(rows, dout, dtype, dev) if (last or keep_preactivation) else None)
             self.F.append(None if last else aligned_rows(rows, dout, dtype, dev))
-            agg_first = order == 1 or (order == PLX_ORDER_AUTO and din <= dout)
-            self.saved.append(aligned_rows(rows if agg_first else 1, din, dtype, dev))
-            self.dH.append(aligned_rows(cols, din, dtype, dev))
+            self.saved.append(aligned_rows(rows if agg[l] else 1, din, dtype, dev))
+            hands_dt = l > 0 and self.chained[l - 1]             # then dH[l] is never formed: dT[l] goes to layer l-1
+            self.dH.append(None if hands_dt else aligned_rows(cols, din, dtype, dev))
+            self.dT.append(aligned_rows(cols, dout, dtype, dev) if hands_dt else None)
             self.dW.append(torch.empty(din, dout, dtype=torch.float32, device=dev))
         rows_last = csr.shape(bool((self.L - 1) % 2))[0]
         self.dZ_last = aligned_rows(rows_last, Ws[-1].shape[1], dtype, dev)
@@ -79,9 +99,18 @@ class GcnNetwork:
         for l in range(self.L - 1, -1, -1):
             h = H0 if l == 0 else self.F[l - 1]
             mask_src = None if self.act[l] == PLX_ACT_NONE else (self.Z[l] if self.Z[l] is not None else self.F[l])
-            plx_gcn_layer_bwd(self.ctx, self.csr, bool(l % 2), h, self.Ws[l], mask_src, grad, self.saved[l],
-                              self.dH[l], self.dW[l], self.ws, act=self.act[l], order=self.order)
-            grad = self.dH[l]
+            if l + 1 < self.L and self.chained[l]:               # grad is the dT of layer l+1
+                plx_gcn_layer_bwd_chained(self.ctx, self.csr, bool(l % 2), h, self.Ws[l], mask_src, grad, self.Ws[l + 1],
+                                          self.saved[l], self.dH[l], self.dW[l], self.ws, act=self.act[l], order=self.order)
+                grad = self.dH[l]
+            elif l > 0 and self.chained[l - 1]:                  # stops at dT; layer l-1 forms its dF from (dT, W)
+                plx_gcn_layer_bwd_dt(self.ctx, self.csr, bool(l % 2), h, mask_src, grad, self.dT[l], self.dW[l], self.ws,
+                                     act=self.act[l])
+                grad = self.dT[l]
+            else:
+                plx_gcn_layer_bwd(self.ctx, self.csr, bool(l % 2), h, self.Ws[l], mask_src, grad, self.saved[l],
+                                  self.dH[l], self.dW[l], self.ws, act=self.act[l], order=self.order)
+                grad = self.dH[l]
 
     def step(self, H0: torch.Tensor, y: torch.Tensor) -> None:
         self.forward(H0)

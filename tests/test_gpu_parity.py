@@ -439,6 +439,36 @@ def test_three_layer_network_parity(ctx, order):
     assert rel_err(run.dF0[pc.to(DEV)], ref.dF[0]) <= TOL32
 
 
+def test_three_layer_network_as_the_bench_runs_it(ctx):
+    """configs[0] through the sequencer's default storage (activations only, sign bits, and the
+    backward chain that never forms the gradient between layers 1 and 2) against the oracle, and
+    against the same network with the chain switched off."""
+    from paper_2505_04083_amd.network import GcnNetwork
+    cfg = synth.CONFIGS["tiny"]
+    src, dst = cfg.edges()
+    pr, pc = cfg.perms()
+    F0, Ws, y = cfg.features(), cfg.weights(), cfg.labels()
+    adj = oracle.adjacency(cfg.n, src.numpy(), dst.numpy())
+    ref = ogcn.forward_backward(adj, F0.numpy(), [w.numpy() for w in Ws], y.numpy())
+    csr = plx.plx_build_csr(ctx, cfg.n, src.to(DEV), dst.to(DEV), pr.to(DEV), pc.to(DEV))
+    H0 = torch.empty_like(F0); H0[pc] = F0
+    L = len(Ws)
+    y_gpu = torch.empty_like(y); y_gpu[pr if (L - 1) % 2 == 0 else pc] = y
+    nets = []
+    for chain in (True, False):
+        net = GcnNetwork(ctx, csr, [w.to(DEV) for w in Ws], chain=chain)
+        net.step(H0.to(DEV), y_gpu.to(DEV)); net.sync()
+        nets.append(net)
+        assert abs(net.loss.item() - ref.loss) / ref.loss <= TOL32
+        for l in range(L):
+            assert rel_err(net.dW[l], ref.dW[l]) <= TOL32, f"dW of layer {l}, chain={chain}"
+        assert rel_err(net.dH[0][pc.to(DEV)], ref.dF[0]) <= TOL32
+    assert nets[0].chained == [False, True, False] and nets[0].dH[2] is None and nets[0].dT[2] is not None
+    assert nets[1].chained == [False, False, False]
+    for l in range(L):
+        assert rel_err(nets[0].dW[l], nets[1].dW[l].double().cpu().numpy()) <= 2e-5
+
+
 def test_layer_on_rectangular_block_both_orders(ctx):
     """One layer on an imported rectangular block (the shape of configs[3], shrunk): forward
     and backward in both multiplication orders against the oracle's Eq. 2.1-2.7."""
@@ -614,6 +644,94 @@ def test_layer_sign_bits(ctx, din, dout, dtype):
         assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
         assert rel_err(outs[0][1], dW) <= tol
         assert rel_err(outs[0][0].float(), dX) <= tol
+
+
+@pytest.mark.parametrize("din,dout,dn,dtype,act", [
+    (64, 128, 16, "f32", "bits"), (128, 128, 32, "f32", "bits"), (100, 128, 17, "f32", "bits"), (128, 128, 41, "f32", "bits"),
+    (64, 96, 16, "f32", "bits"), (96, 128, 31, "f32", "none"), (64, 128, 3, "f32", "bits"),
+    (32, 128, 16, "f32", "bits"), (64, 64, 16, "f32", "bits"), (128, 128, 100, "f32", "bits"), (64, 128, 16, "f32", "values"),
+    (602, 128, 16, "f32", "bits"), (64, 128, 16, "bf16", "bits"), (64, 128, 16, "f32", "bits-combine")])
+def test_chained_backward_of_two_layers(ctx, din, dout, dn, dtype, act):
+    """Backward of two consecutive layers without the gradient between them: the second layer
+    (combine-first, transposed adjacency) stops at dT = A^T dZ, the first takes (dT, Wn) in place of dF.
+    Shapes cover the fused kernel (one and two 16-column steps of dn, ragged dn and widths, a
+    wavefront without columns, no mask) and every fall-back (narrow widths, wide dn, value mask,
+    general products, bf16, combine-first order).  Checked against the oracle and against the
+    unchained calls."""
+    m, k = 1237, 1500
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    code = plx.PLX_F32 if dtype == "f32" else plx.PLX_BF16
+    tol = TOL32 if dtype == "f32" else 2e-2
+    order = plx.PLX_ORDER_COMBINE_FIRST if act.endswith("combine") else plx.PLX_ORDER_AGG_FIRST
+    actc = {"bits": plx.PLX_ACT_RELU_BITS, "bits-combine": plx.PLX_ACT_RELU_BITS, "values": plx.PLX_ACT_RELU, "none": plx.PLX_ACT_NONE}[act]
+    rowptr, col, val = random_block(m, k, 3 * din + 5 * dout + dn)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(din + dout + dn)
+
+    def matrix(rows, cols, src=None, t=tdt):         # rows padded to 16 bytes, as the network keeps them
+        q = 16 // torch.empty(0, dtype=t).element_size()
+        buf = torch.zeros(rows, -(-cols // q) * q, dtype=t, device=DEV)[:, :cols]
+        if src is not None:
+            buf.copy_(torch.as_tensor(np.asarray(src, np.float32)))
+        return buf
+
+    X = matrix(k, din, r.standard_normal((k, din)))
+    W = (r.standard_normal((din, dout)) * 0.2).astype(np.float32)
+    Wn = (r.standard_normal((dout, dn)) * 0.2).astype(np.float32)
+    dZn = matrix(k, dn, r.standard_normal((k, dn)))
+    X64, dZn64 = X.double().cpu().numpy(), dZn.double().cpu().numpy()
+    # oracle: layer l (A, ReLU or none), layer l+1 (A^T, combine-first, no activation); F is taken from the GPU's
+    # stored activation for the second layer's products, so that bf16 storage rounding is shared
+    S = oracle.spmm_coo(m, row, c64, v64, X64)
+    Q = oracle.gemm(S, W)
+    nbytes = plx.plx_gcn_layer_bwd_chained_workspace(ctx, csr, False, din, dout, dn, dtype=code, act=actc, order=order)
+    ws1 = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    ws2 = torch.empty(plx.plx_gcn_layer_workspace(csr, True, dout, dn, dtype=code, act=plx.PLX_ACT_NONE,
+                                                  order=plx.PLX_ORDER_COMBINE_FIRST), dtype=torch.uint8, device=DEV)
+    F = matrix(m, dout); saved = matrix(m, din)
+    words = torch.zeros(m, (dout + 31) // 32, dtype=torch.int32, device=DEV)
+    Zarg = words if actc == plx.PLX_ACT_RELU_BITS else None
+    plx.plx_gcn_layer_fwd(ctx, csr, False, X, dev(W), Zarg, F, saved, ws1, act=actc, order=order)
+    mask_src = {plx.PLX_ACT_RELU_BITS: words, plx.PLX_ACT_RELU: F, plx.PLX_ACT_NONE: None}[actc]
+    # chained
+    dT = matrix(m, dn); gdWn = torch.empty(dout, dn, device=DEV)
+    plx.plx_gcn_layer_bwd_dt(ctx, csr, True, F, None, dZn, dT, gdWn, ws2, act=plx.PLX_ACT_NONE)
+    gdX = matrix(k, din); gdW = torch.empty(din, dout, device=DEV)
+    plx.plx_sync(ctx); plx.plx_timing_enable(ctx, True); plx.plx_timing_report(ctx)
+    plx.plx_gcn_layer_bwd_chained(ctx, csr, False, X, dev(W), mask_src, dT, dev(Wn), saved, gdX, gdW, ws1, act=actc, order=order)
+    launched = plx.plx_timing_report(ctx); plx.plx_timing_enable(ctx, False)
+    # which path ran: the kernel that forms dF itself where the header says it does, one extra product elsewhere
+    in_kernel = (dtype == "f32" and order == plx.PLX_ORDER_AGG_FIRST and 32 < din <= 128 and 64 < dout <= 128 and dn <= 32
+                 and act != "values")
+    assert any(name.endswith(f"fact{dn}") for name in launched) == in_kernel, launched
+    plain = plx.plx_gcn_layer_workspace(csr, False, din, dout, dtype=code, act=actc, order=order)
+    assert nbytes == plain if in_kernel else nbytes >= plain + m * dout * (4 if dtype == "f32" else 2)
+    assert any(name.startswith("gemm_nt") and f"K{dn}]" in name for name in launched) == (not in_kernel), launched
+    # unchained
+    dF = matrix(m, dout); gdWn2 = torch.empty(dout, dn, device=DEV)
+    plx.plx_gcn_layer_bwd(ctx, csr, True, F, dev(Wn), None, dZn, None, dF, gdWn2, ws2, act=plx.PLX_ACT_NONE,
+                          order=plx.PLX_ORDER_COMBINE_FIRST)
+    gdX2 = matrix(k, din); gdW2 = torch.empty(din, dout, device=DEV)
+    plx.plx_gcn_layer_bwd(ctx, csr, False, X, dev(W), mask_src, dF, saved, gdX2, gdW2, ws1, act=actc, order=order)
+    plx.plx_sync(ctx)
+    F64 = F.double().cpu().numpy()
+    dT64 = oracle.spmm_coo(m, row, c64, v64, dZn64)                       # (A^T)^T dZ'
+    assert rel_err(dT.float(), dT64) <= tol
+    assert rel_err(gdWn, oracle.gemm(F64, dT64, ta=True)) <= tol
+    assert torch.equal(gdWn, gdWn2)
+    # the two GPU paths see the same mask and the same dT: they must agree closely everywhere
+    close = 2e-5 if dtype == "f32" else 2e-2                             # bf16: the unchained dF is rounded once more when stored
+    assert rel_err(gdW, gdW2.double().cpu().numpy()) <= close
+    assert rel_err(gdX.float(), gdX2.double().cpu().numpy()) <= close
+    # against the oracle, from the stored dT (as both GPU paths take it) and with the mask decided where the GPU
+    # decides it: the sign of its stored activation
+    dQ = oracle.gemm(dT.double().cpu().numpy(), Wn, tb=True)
+    if actc != plx.PLX_ACT_NONE:
+        dQ = dQ * (F64 > 0)
+    assert Q.shape == dQ.shape
+    assert rel_err(gdW, oracle.gemm(S, dQ, ta=True)) <= tol
+    assert rel_err(gdX.float(), oracle.spmm_t_coo(k, row, c64, v64, oracle.gemm(dQ, W, tb=True))) <= tol
 
 
 def test_layer_very_wide_leading_dimension(ctx):
