@@ -93,7 +93,9 @@ def kernel_cost(name, bins, names=()):
     if m:
         s = 4 if m.group(2) == "f32" else 2
         M, N, K = map(int, m.groups()[2:])
-        return s * (M * K + M * N) + 4 * K * N, 2 * M * N * K
+        nxt = re.search(r"next(\d+)$", name)              # also writes T = result x Wn[N x dn] for the following layer
+        dn = int(nxt.group(1)) if nxt else 0
+        return s * (M * K + M * N + M * dn) + 4 * K * N, 2 * M * N * (K + dn)
     m = re.match(r"gemm_tn<(f32|bf16)>\[R(\d+),M(\d+),N(\d+)\]", name)
     if m:
         s = 4 if m.group(1) == "f32" else 2

@@ -254,6 +254,29 @@ PLX_API plx_status plx_gcn_layer_bwd(plx_ctx* ctx, const plx_csr* csr, int trans
                                      int64_t din, int64_t dout, plx_dtype dtype, plx_act act, plx_order order,
                                      void* dH, int64_t lddh, float* dW, int64_t lddw, void* ws, size_t ws_bytes);
 
+/* ---- forward of two consecutive layers without re-reading the activation between them --------------
+ * Layer l+1 in combine-first order starts with T = F W (Eq. 2.2 first), a product over the rows of
+ * layer l's output F.  plx_gcn_layer_fwd_chained is plx_gcn_layer_fwd of layer l that also writes
+ * Tn[ma x dn] = F Wn (F: this layer's activated output, or Z when act == NONE; Wn[dout x dn] fp32,
+ * the following layer's weights; Tn has dtype `dtype`), and plx_gcn_layer_fwd_from_t is the rest of
+ * layer l+1: Z = A T, F = act(Z) for a given T[ka x dout].  F of layer l is still written (the
+ * backward pass needs it) but not read again in the forward pass.
+ * The extra product runs inside the kernel that writes F for fp32, aggregate-first order,
+ * 32 < din <= 128, 32 < dout <= 128, din % 4 == 0, dn <= 16, 16-byte aligned rows of `saved`,
+ * split products on; in every other case it is a product of its own after the layer (same result
+ * up to rounding order, no saving).  With act != NONE F must be given.
+ * Errors as plx_gcn_layer_fwd; PLX_ERR_INVALID if Tn / Wn / T is NULL or dn <= 0, PLX_ERR_SHAPE if
+ * ldwn < dn, ldtn < dn or ldt < dout.  plx_gcn_layer_fwd_from_t uses no workspace. */
+PLX_API plx_status plx_gcn_layer_fwd_chained(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
+                                             const void* H, int64_t ldh, const float* W, int64_t ldw,
+                                             int64_t din, int64_t dout, plx_dtype dtype, plx_act act, plx_order order,
+                                             void* Z, int64_t ldz, void* F, int64_t ldf, void* saved, int64_t ldsaved,
+                                             const float* Wn, int64_t ldwn, int64_t dn, void* Tn, int64_t ldtn,
+                                             void* ws, size_t ws_bytes);
+PLX_API plx_status plx_gcn_layer_fwd_from_t(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
+                                            const void* T, int64_t ldt, int64_t dout, plx_dtype dtype, plx_act act,
+                                            void* Z, int64_t ldz, void* F, int64_t ldf);
+
 /* ---- backward of two consecutive layers without the gradient between them -------------------------
  * Layer l+1 in combine-first order computes T = H W, Z = A T (Eq. 2.1-2.2 in that order); its
  * backward pass is dT = A^T dZ, dW = H^T dT (Eq. 2.5) and dH = dT W^T (Eq. 2.6).  dH[ka x din] is

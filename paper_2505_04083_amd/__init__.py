@@ -29,6 +29,7 @@ EXPORTED = [
     "plx_relu", "plx_relu_bwd", "plx_softmax_ce",
     "plx_gcn_layer_workspace", "plx_gcn_layer_fwd", "plx_gcn_layer_bwd",
     "plx_gcn_layer_bwd_dt", "plx_gcn_layer_bwd_chained_workspace", "plx_gcn_layer_bwd_chained",
+    "plx_gcn_layer_fwd_chained", "plx_gcn_layer_fwd_from_t",
 ]
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
@@ -75,6 +76,9 @@ def _load() -> ctypes.CDLL:
                                      _vp, _i64, _vp, _i64, _vp, _i64, _vp, _sz]),
         "plx_gcn_layer_bwd": (_int, [_vp, _vp, _int, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64,
                                      _i64, _i64, _int, _int, _int, _vp, _i64, _vp, _i64, _vp, _sz]),
+        "plx_gcn_layer_fwd_chained": (_int, [_vp, _vp, _int, _vp, _i64, _vp, _i64, _i64, _i64, _int, _int, _int,
+                                             _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp, _sz]),
+        "plx_gcn_layer_fwd_from_t": (_int, [_vp, _vp, _int, _vp, _i64, _i64, _int, _int, _vp, _i64, _vp, _i64]),
         "plx_gcn_layer_bwd_dt": (_int, [_vp, _vp, _int, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _int, _int,
                                         _vp, _i64, _vp, _i64, _vp, _sz]),
         "plx_gcn_layer_bwd_chained_workspace": (_sz, [_vp, _vp, _int, _i64, _i64, _i64, _int, _int, _int]),
@@ -414,3 +418,24 @@ def plx_gcn_layer_bwd_chained(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, H:
     ctx.check(_lib.plx_gcn_layer_bwd_chained(ctx.handle, csr.handle, int(transposed_A), hp, ldh, wp, ldw, zp, ldz, gp, ldg,
                                              wnp, ldwn, Wn.shape[1], sp, lds, din, dout, _dtype_code(dTn), act, order,
                                              dhp, lddh, dwp, lddw, ws.data_ptr(), ws.numel()))
+
+
+def plx_gcn_layer_fwd_chained(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, H: torch.Tensor, W: torch.Tensor,
+                              Z: Optional[torch.Tensor], F: Optional[torch.Tensor], saved: Optional[torch.Tensor],
+                              Wn: torch.Tensor, Tn: torch.Tensor, ws: Optional[torch.Tensor],
+                              act: int = PLX_ACT_RELU, order: int = PLX_ORDER_AUTO) -> None:
+    """plx_gcn_layer_fwd that also writes Tn = (this layer's output) Wn, the first product of a following combine-first layer."""
+    (hp, ldh), (wp, ldw), (zp, ldz), (fp, ldf), (sp, lds) = _mat(H), _mat(W), _mat(Z), _mat(F), _mat(saved)
+    (wnp, ldwn), (tp, ldt) = _mat(Wn), _mat(Tn)
+    din, dout = W.shape
+    ctx.check(_lib.plx_gcn_layer_fwd_chained(ctx.handle, csr.handle, int(transposed_A), hp, ldh, wp, ldw, din, dout,
+                                             _dtype_code(H), act, order, zp, ldz, fp, ldf, sp, lds, wnp, ldwn, Wn.shape[1], tp, ldt,
+                                             None if ws is None else ws.data_ptr(), 0 if ws is None else ws.numel()))
+
+
+def plx_gcn_layer_fwd_from_t(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, T: torch.Tensor, Z: Optional[torch.Tensor],
+                             F: Optional[torch.Tensor], act: int = PLX_ACT_RELU) -> None:
+    """Z = A T, F = act(Z): a combine-first layer whose T = H W already exists."""
+    (tp, ldt), (zp, ldz), (fp, ldf) = _mat(T), _mat(Z), _mat(F)
+    ctx.check(_lib.plx_gcn_layer_fwd_from_t(ctx.handle, csr.handle, int(transposed_A), tp, ldt, T.shape[1], _dtype_code(T), act,
+                                            zp, ldz, fp, ldf))

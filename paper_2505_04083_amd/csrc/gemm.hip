@@ -653,17 +653,25 @@ __global__ __launch_bounds__(256) void k_gemm_small_f32(int64_t M, int N, int K,
 #ifndef PLX_X3_FWD_CAP
 #define PLX_X3_FWD_CAP 0
 #endif
-template <int TKB, int TNB>   // 32 < K <= 32*TKB, 32 < N <= 32*TNB (TKB, TNB in {2, 4}); 16-byte aligned rows, K % 4 == 0
+// NEXT: the tile of the result (activated if F is written) also goes to LDS in fp32 and is multiplied there by
+// Wn[N x dn], dn <= 16: Tn[M x dn] = act(A B) Wn, the combine step (Eq. 2.2) of a following combine-first layer,
+// which then does not read the M x N result back.  Wavefront w forms rows 16w .. 16w+15 of the tile's Tn with
+// v_mfma_f32_16x16x4_f32 (lane l: a = tile[16w + l%16][4s + l/16], b = Wn[4s + l/16][l%16], in registers for the
+// whole kernel; acc[r] = Tn[16w + 4*(l/16) + r][l%16]).
+template <int TKB, int TNB, bool NEXT>   // 32 < K <= 32*TKB, 32 < N <= 32*TNB (TKB, TNB in {2, 4}); 16-byte aligned rows, K % 4 == 0
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_FWD_WAVES))) void k_gemm_small_x3(int64_t M, int N, int K, const float* __restrict__ A,
                                                        int64_t lda, const float* __restrict__ B, int64_t ldb,
                                                        float* __restrict__ C, int64_t ldc, float* __restrict__ F,
                                                        int64_t ldf, uint32_t* __restrict__ bits, int64_t ldbits,
-                                                       int bits_vec) {
+                                                       int bits_vec, const float* __restrict__ Wn, int64_t ldwn, int dn,
+                                                       float* __restrict__ Tn, int64_t ldtn) {
     constexpr int KP = 32 * TKB, ROWS = 64, NBLK = 2 * TNB / 4, NKS = KP / 16, SA = KP + 8, PLANE = ROWS * SA;
     constexpr int NLD = ROWS * KP / 4 / 256;
+    constexpr int NPC = 32 * TNB, FP = NPC + 4;                              // the fp32 copy of the result tile: [ROWS][FP]
     extern __shared__ __align__(16) unsigned char smem_raw[];
     bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);                        // [3][ROWS][SA]
     uint32_t* sb = reinterpret_cast<uint32_t*>(As + 3 * PLANE);              // sign bits: [2][4 words][ROWS]
+    float* Ft = reinterpret_cast<float*>(sb + 2 * 4 * ROWS);                 // only with NEXT
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, lh = lane >> 5;
     const int bj = w % TNB;
@@ -689,6 +697,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_FWD_
             }
 #pragma unroll
             for (int p = 0; p < 3; ++p) breg[s2][p] = f[p].v;
+        }
+    }
+    constexpr int NWS = NEXT ? NPC / 4 : 1;
+    float wn[NWS];                         // wn[s] = Wn[4s + l/16][l%16]
+    if constexpr (NEXT) {
+        const int l16 = lane & 15, lq = lane >> 4;
+#pragma unroll
+        for (int s4 = 0; s4 < NWS; ++s4) {
+            const int k = 4 * s4 + lq;
+            wn[s4] = (k < N && l16 < dn) ? Wn[(int64_t)k * ldwn + l16] : 0.f;
         }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);    // weights landed before the row loop (vmcnt(0))
@@ -763,6 +781,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_FWD_
                 PLX_X3_32(acc[t], a, breg[s2]);
             }
         }
+        if constexpr (NEXT) {                                            // what the following layer reads: act(result), columns >= N are 0
+#pragma unroll
+            for (int t = 0; t < NBLK; ++t) {
+                const int bi = (w + 4 * t) / TNB;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float v = acc[t][r];
+                    Ft[(32 * bi + 8 * (r / 4) + 4 * lh + (r % 4)) * FP + 32 * bj + l32] = F ? relu0(v) : v;
+                }
+            }
+        }
         __syncthreads();                                                 // every wavefront is done reading the tile
         commit();
         const int64_t m0 = tile * ROWS;
@@ -815,6 +844,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_FWD_
                         dst[0] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
                         dst[1] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
                     }
+                }
+            }
+        }
+        if constexpr (NEXT) {                                            // Tn rows 16w .. 16w+15 of this tile
+            const int l16 = lane & 15, lq = lane >> 4;
+            floatx4 tacc = floatx4{0.f, 0.f, 0.f, 0.f};
+            const float* frow = Ft + (16 * w + l16) * FP + lq;
+            const int n_end4 = (N + 3) / 4;
+#pragma unroll
+            for (int s4 = 0; s4 < NWS; ++s4) {
+                if (s4 >= n_end4) break;                                 // uniform
+                tacc = __builtin_amdgcn_mfma_f32_16x16x4f32(frow[4 * s4], wn[s4], tacc, 0, 0, 0);
+            }
+            if (l16 < dn) {
+                const __amdgpu_buffer_rsrc_t rt = buffer_of(Tn + m0 * ldtn, (uint32_t)(((ROWS - 1) * ldtn + dn) * 4));
+                const uint32_t toffs = (uint32_t)((4u * lq * (uint32_t)ldtn + l16) * 4u);
+                uint32_t trow = opaque_zero() + 16u * w * (uint32_t)ldtn * 4u;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if (full || m0 + 16 * w + 4 * lq + r < M) buffer_store(rt, toffs, trow, tacc[r]);
+                    trow += (uint32_t)ldtn * 4u;
                 }
             }
         }
@@ -1134,10 +1184,21 @@ plx_status launch_gemm_deep(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t
 
 }  // namespace
 
+// Does the nn product of these shapes go through the split kernel, which can multiply its result tile by a
+// following layer's Wn[N x dn] on the way out?
+bool gemm_next_supported(const plx_ctx* ctx, int64_t M, int64_t N, int64_t K, int64_t dn, plx_dtype dtype, const void* A, int64_t lda,
+                         int64_t ldc, int64_t ldf, int64_t ldtn) {
+    const int64_t cap = int64_t(1) << 23;
+    return dtype == PLX_F32 && ctx->split_products && M > 0 && K > 32 && K <= 128 && N > 32 && N <= 128 && K % 4 == 0 && dn > 0 &&
+           dn <= 16 && aligned16(A) && lda % 4 == 0 && lda < cap && ldc < cap && ldf < cap && ldtn < cap;
+}
+
 plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                        const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype, void* Fact, int64_t ldf,
-                       uint32_t* bits, int64_t ldbits) {
+                       uint32_t* bits, int64_t ldbits, const float* Wn, int64_t ldwn, int64_t dn, float* Tn, int64_t ldtn) {
     if (bits && !Fact) return fail(ctx, PLX_ERR_INTERNAL, "sign bits are written next to the activated output");
+    if (Tn && (bt || !gemm_next_supported(ctx, M, N, K, dn, dtype, A, lda, C ? ldc : 0, Fact ? ldf : 0, ldtn)))
+        return fail(ctx, PLX_ERR_INTERNAL, "chained product outside the split kernel's range");
     if (N >= (int64_t(1) << 20) || K >= (int64_t(1) << 30)) return fail(ctx, PLX_ERR_UNSUPPORTED, "N or K too large");
     const bool deep = M > 0 && N > 0 && K > 0 && deep_operand(A, lda, dtype) && ldb < (int64_t(1) << 22) &&
                       (!C || ldc < (int64_t(1) << 22)) && (!Fact || ldf < (int64_t(1) << 22));
@@ -1168,8 +1229,10 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
     // K and N above 32: the fp32 matrix pipe would bind, six bf16 products per fp32 product are taken instead
     const bool split = small && ctx->split_products && vec_a && K % 4 == 0 && M > 0 && K > 32 && N > 32;
     char label[64];
-    snprintf(label, sizeof label, "gemm_%s<f32>[M%lld,N%lld,K%lld]%s", bt ? "nt" : "nn", (long long)M, (long long)N, (long long)K,
-             split ? "x3" : "");
+    char next[16] = "";
+    if (Tn) snprintf(next, sizeof next, "next%lld", (long long)dn);    // also multiplies its result by the following layer's weights
+    snprintf(label, sizeof label, "gemm_%s<f32>[M%lld,N%lld,K%lld]%s%s", bt ? "nt" : "nn", (long long)M, (long long)N, (long long)K,
+             split ? "x3" : "", next);
     KernelTimer kt(ctx, label);
     if (small) {
         const int tkb = K <= 32 ? 1 : (K <= 64 ? 2 : 4);
@@ -1183,7 +1246,8 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
         const int bits_vec = (nw == 4 && ldbits % 4 == 0 && bp % 16 == 0) ? 4 : ((nw == 2 && ldbits % 2 == 0 && bp % 8 == 0) ? 2 : 1);
         if (split) {
             const int tnb3 = N <= 64 ? 2 : 4;
-            const size_t lds3 = sizeof(uint16_t) * 3 * 64 * (32 * tkb + 8) + (bits ? 2 * 4 * 64 * 4 : 0);
+            const size_t lds3 = sizeof(uint16_t) * 3 * 64 * (32 * tkb + 8) + ((bits || Tn) ? 2 * 4 * 64 * 4 : 0) +
+                                (Tn ? sizeof(float) * 64 * (32 * tnb3 + 4) : 0);
             auto launch_x3 = [&](auto kern) -> plx_status {
                 if (lds3 > 48 * 1024)
                     PLX_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1192,12 +1256,17 @@ plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, c
                 PLX_HIP(ctx, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, lds3));
                 if (PLX_X3_FWD_CAP > 0) per_cu = std::min(per_cu, PLX_X3_FWD_CAP);
                 const int64_t blocks = std::min<int64_t>(ceil_div(M, 64), (int64_t)ctx->n_cu * std::max(1, per_cu));
-                kern<<<dim3((unsigned)blocks), 256, lds3, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf, bits, ldbits, bits_vec);
+                kern<<<dim3((unsigned)blocks), 256, lds3, s>>>(M, (int)N, (int)K, a, lda, B, ldb, c, ldc, fa, ldf, bits, ldbits, bits_vec,
+                                                               Wn, ldwn, (int)dn, Tn, ldtn);
                 PLX_HIP(ctx, hipGetLastError());
                 return PLX_OK;
             };
-            if (tkb == 2) return tnb3 == 2 ? launch_x3(k_gemm_small_x3<2, 2>) : launch_x3(k_gemm_small_x3<2, 4>);
-            return tnb3 == 2 ? launch_x3(k_gemm_small_x3<4, 2>) : launch_x3(k_gemm_small_x3<4, 4>);
+            if (Tn) {
+                if (tkb == 2) return tnb3 == 2 ? launch_x3(k_gemm_small_x3<2, 2, true>) : launch_x3(k_gemm_small_x3<2, 4, true>);
+                return tnb3 == 2 ? launch_x3(k_gemm_small_x3<4, 2, true>) : launch_x3(k_gemm_small_x3<4, 4, true>);
+            }
+            if (tkb == 2) return tnb3 == 2 ? launch_x3(k_gemm_small_x3<2, 2, false>) : launch_x3(k_gemm_small_x3<2, 4, false>);
+            return tnb3 == 2 ? launch_x3(k_gemm_small_x3<4, 2, false>) : launch_x3(k_gemm_small_x3<4, 4, false>);
         }
         auto launch_small = [&](auto kern) -> plx_status {
             if (lds > 48 * 1024)

@@ -414,27 +414,52 @@ static plx_status layer_common_checks(plx_ctx* ctx, const plx_csr* csr, int64_t 
     return PLX_OK;
 }
 
-plx_status plx_gcn_layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* H, int64_t ldh,
-                             const float* W, int64_t ldw, int64_t din, int64_t dout, plx_dtype dtype, plx_act act,
-                             plx_order order, void* Z, int64_t ldz, void* F, int64_t ldf, void* saved,
-                             int64_t ldsaved, void* ws, size_t ws_bytes) {
+}  // extern "C"
+
+namespace {
+
+// How a forward call departs from plx_gcn_layer_fwd (all zero: it does not).
+struct FwdVariant {
+    // also Tn[ma x dn] = (this layer's output) Wn, the combine step of the following layer (Wn: dout x dn)
+    const float* Wn = nullptr;
+    int64_t ldwn = 0, dn = 0;
+    void* Tn = nullptr;
+    int64_t ldtn = 0;
+    // combine-first order with T = H W given by the caller (ka x dout): H and W are not read
+    const void* T = nullptr;
+    int64_t ldt = 0;
+};
+
+plx_status layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* H, int64_t ldh,
+                     const float* W, int64_t ldw, int64_t din, int64_t dout, plx_dtype dtype, plx_act act,
+                     plx_order order, void* Z, int64_t ldz, void* F, int64_t ldf, void* saved,
+                     int64_t ldsaved, void* ws, size_t ws_bytes, const FwdVariant& var) {
     if (!ctx) return PLX_ERR_INVALID;
     PLX_TRY(layer_common_checks(ctx, csr, din, dout, dtype, act, order));
     const Orient& a = csr->o[transposed_A ? 1 : 0];
     order = resolve_order(order, din, dout);
-    if (!H || !W) return fail(ctx, PLX_ERR_INVALID, "H or W is NULL");
+    if (var.T) {
+        if (var.ldt < dout) return fail(ctx, PLX_ERR_SHAPE, "ldt smaller than dout");
+    } else if (!H || !W) {
+        return fail(ctx, PLX_ERR_INVALID, "H or W is NULL");
+    }
+    if (var.Tn) {
+        if (!var.Wn || var.dn <= 0) return fail(ctx, PLX_ERR_INVALID, "Wn is NULL or dn is not positive");
+        if (var.ldwn < var.dn || var.ldtn < var.dn) return fail(ctx, PLX_ERR_SHAPE, "ldwn or ldtn smaller than dn");
+        if (act != PLX_ACT_NONE && !F) return fail(ctx, PLX_ERR_INVALID, "the following layer reads F: it must be given");
+    }
     if (!Z && !F) return fail(ctx, PLX_ERR_INVALID, "Z and F are both NULL");
     const bool sign_bits = act == PLX_ACT_RELU_BITS;          // Z receives one bit per element instead of the values
     if (sign_bits && (!Z || !F)) return fail(ctx, PLX_ERR_INVALID, "the sign-bit activation writes both Z (bits) and F");
     if (sign_bits && (reinterpret_cast<uintptr_t>(Z) & 3)) return fail(ctx, PLX_ERR_INVALID, "the sign bits need a 4-byte aligned Z");
-    if (ldh < din || ldw < dout || (Z && ldz < (sign_bits ? (dout + 31) / 32 : dout)) || (F && ldf < dout))
+    if ((!var.T && (ldh < din || ldw < dout)) || (Z && ldz < (sign_bits ? (dout + 31) / 32 : dout)) || (F && ldf < dout))
         return fail(ctx, PLX_ERR_SHAPE, "leading dimension too small");
     if (order == PLX_ORDER_AGG_FIRST) {
         if (!saved) return fail(ctx, PLX_ERR_INVALID, "aggregate-first order needs the `saved` buffer");
         if (ldsaved < din) return fail(ctx, PLX_ERR_SHAPE, "ldsaved smaller than din");
     }
     LayerWs w = layer_ws(a, din, dout, dtype, act, order);
-    if (order == PLX_ORDER_COMBINE_FIRST && (!ws || ws_bytes < w.total))
+    if (order == PLX_ORDER_COMBINE_FIRST && !var.T && (!ws || ws_bytes < w.total))
         return fail(ctx, PLX_ERR_SHAPE, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, w.total);
     if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
 
@@ -448,20 +473,74 @@ plx_status plx_gcn_layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A,
         else if (!Z) plain = F;              // no activation and only F wanted: F is the plain output
     }
     const int64_t ld_plain = plain == Z ? ldz : ldf;
+    bool next_done = false;                  // Tn written by the product that wrote this layer's output
     if (order == PLX_ORDER_AGG_FIRST) {
         PLX_TRY(launch_spmm(ctx, a, H, ldh, saved, ldsaved, din, dtype));                    // Eq. 2.1
-        PLX_TRY(launch_gemm(ctx, false, a.rows, dout, din, saved, ldsaved, W, ldw, plain, ld_plain, dtype, activated, ldf, bits,
-                            ldz));                                                           // Eq. 2.2 (+2.3)
+        if (var.Tn && gemm_next_supported(ctx, a.rows, dout, din, var.dn, dtype, saved, ldsaved, plain ? ld_plain : 0,
+                                          activated ? ldf : 0, var.ldtn)) {
+            // Eq. 2.2 (+2.3) of this layer and Eq. 2.2 of the next one from the same tile
+            PLX_TRY(launch_gemm(ctx, false, a.rows, dout, din, saved, ldsaved, W, ldw, plain, ld_plain, dtype, activated, ldf, bits,
+                                ldz, var.Wn, var.ldwn, var.dn, static_cast<float*>(var.Tn), var.ldtn));
+            next_done = true;
+        } else {
+            PLX_TRY(launch_gemm(ctx, false, a.rows, dout, din, saved, ldsaved, W, ldw, plain, ld_plain, dtype, activated, ldf, bits,
+                                ldz));                                                       // Eq. 2.2 (+2.3)
+        }
     } else {
-        void* T = static_cast<char*>(ws) + w.off_a;
-        PLX_TRY(launch_gemm(ctx, false, a.cols, dout, din, H, ldh, W, ldw, T, w.ld_out, dtype));
-        PLX_TRY(launch_spmm(ctx, a, T, w.ld_out, plain, ld_plain, dout, dtype, activated, ldf));
+        const void* T = var.T;
+        int64_t ldt = var.ldt;
+        if (!T) {
+            void* Tw = static_cast<char*>(ws) + w.off_a;
+            PLX_TRY(launch_gemm(ctx, false, a.cols, dout, din, H, ldh, W, ldw, Tw, w.ld_out, dtype));
+            T = Tw; ldt = w.ld_out;
+        }
+        PLX_TRY(launch_spmm(ctx, a, T, ldt, plain, ld_plain, dout, dtype, activated, ldf));
         if (bits) PLX_TRY(launch_bits_from_act(ctx, a.rows, dout, F, ldf, bits, ldz, dtype));
     }
     if (F && act == PLX_ACT_NONE && Z && F != Z)
         PLX_HIP(ctx, hipMemcpy2DAsync(F, ldf * elt_size(dtype), Z, ldz * elt_size(dtype), dout * elt_size(dtype), a.rows,
                                       hipMemcpyDeviceToDevice, ctx->stream));
+    if (var.Tn && !next_done) {              // elsewhere the following layer's product is a product of its own
+        const void* out = act != PLX_ACT_NONE ? F : (plain == Z ? Z : F);
+        const int64_t ldout = out == Z ? ldz : ldf;
+        PLX_TRY(launch_gemm(ctx, false, a.rows, var.dn, dout, out, ldout, var.Wn, var.ldwn, var.Tn, var.ldtn, dtype));
+    }
     return PLX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+plx_status plx_gcn_layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* H, int64_t ldh,
+                             const float* W, int64_t ldw, int64_t din, int64_t dout, plx_dtype dtype, plx_act act,
+                             plx_order order, void* Z, int64_t ldz, void* F, int64_t ldf, void* saved,
+                             int64_t ldsaved, void* ws, size_t ws_bytes) {
+    return layer_fwd(ctx, csr, transposed_A, H, ldh, W, ldw, din, dout, dtype, act, order, Z, ldz, F, ldf, saved, ldsaved, ws,
+                     ws_bytes, FwdVariant{});
+}
+
+plx_status plx_gcn_layer_fwd_chained(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* H, int64_t ldh,
+                                     const float* W, int64_t ldw, int64_t din, int64_t dout, plx_dtype dtype, plx_act act,
+                                     plx_order order, void* Z, int64_t ldz, void* F, int64_t ldf, void* saved,
+                                     int64_t ldsaved, const float* Wn, int64_t ldwn, int64_t dn, void* Tn, int64_t ldtn,
+                                     void* ws, size_t ws_bytes) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!Tn) return fail(ctx, PLX_ERR_INVALID, "Tn is NULL");
+    FwdVariant var;
+    var.Wn = Wn; var.ldwn = ldwn; var.dn = dn; var.Tn = Tn; var.ldtn = ldtn;
+    return layer_fwd(ctx, csr, transposed_A, H, ldh, W, ldw, din, dout, dtype, act, order, Z, ldz, F, ldf, saved, ldsaved, ws,
+                     ws_bytes, var);
+}
+
+plx_status plx_gcn_layer_fwd_from_t(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const void* T, int64_t ldt,
+                                    int64_t dout, plx_dtype dtype, plx_act act, void* Z, int64_t ldz, void* F, int64_t ldf) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!T) return fail(ctx, PLX_ERR_INVALID, "T is NULL");
+    FwdVariant var;
+    var.T = T; var.ldt = ldt;
+    return layer_fwd(ctx, csr, transposed_A, nullptr, 0, nullptr, 0, dout, dout, dtype, act, PLX_ORDER_COMBINE_FIRST, Z, ldz, F, ldf,
+                     nullptr, 0, nullptr, 0, var);
 }
 
 }  // extern "C"

@@ -154,7 +154,11 @@ plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx
 // the sign bits [C > 0] (bit j % 32 of word j / 32 of row i, ldbits words per row)
 plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
                        const float* B, int64_t ldb, void* C, int64_t ldc, plx_dtype dtype, void* Fact = nullptr,
-                       int64_t ldf = 0, uint32_t* bits = nullptr, int64_t ldbits = 0);
+                       int64_t ldf = 0, uint32_t* bits = nullptr, int64_t ldbits = 0, const float* Wn = nullptr, int64_t ldwn = 0,
+                       int64_t dn = 0, float* Tn = nullptr, int64_t ldtn = 0);
+// Tn != NULL: the nn product also writes Tn[M x dn] = act(A B) Wn (Wn: N x dn); only where this holds:
+bool gemm_next_supported(const plx_ctx* ctx, int64_t M, int64_t N, int64_t K, int64_t dn, plx_dtype dtype, const void* A, int64_t lda,
+                         int64_t ldc, int64_t ldf, int64_t ldtn);
 // bits[i][j] = [F[i][j] > 0] for an activated matrix F (used where no producing kernel writes the bits itself)
 plx_status launch_bits_from_act(plx_ctx* ctx, int64_t rows, int64_t cols, const void* F, int64_t ldf, uint32_t* bits,
                                 int64_t ldbits, plx_dtype dtype);

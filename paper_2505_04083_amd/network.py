@@ -7,7 +7,8 @@ of the layer can write them on the fly (aggregate-first order, widths up to 128)
 one bit per element, which is all the backward pass then reads of it; the last layer stores the
 logits.  Where a combine-first layer follows an aggregate-first one of fitting widths, the gradient
 matrix between them is never formed: the later layer's backward call stops at dT = A^T dZ and the
-earlier one takes (dT, W) in its place (`chain`).  The input must be in P_c order and the labels in the order of the last layer's output."""
+earlier one takes (dT, W) in its place; in the forward pass the earlier layer's last product also
+forms the later layer's T = F W, so F is written for the backward pass but not read back (`chain`).  The input must be in P_c order and the labels in the order of the last layer's output."""
 from __future__ import annotations
 
 from typing import List, Optional
@@ -16,7 +17,7 @@ import torch
 
 from . import (PLX_ACT_NONE, PLX_ACT_RELU, PLX_ACT_RELU_BITS, PLX_BF16, PLX_F32, PLX_ORDER_AUTO, plx_gcn_layer_bwd,
                plx_gcn_layer_bwd_chained, plx_gcn_layer_bwd_chained_workspace, plx_gcn_layer_bwd_dt, plx_gcn_layer_fwd,
-               plx_gcn_layer_workspace, plx_softmax_ce, plx_sync)
+               plx_gcn_layer_fwd_chained, plx_gcn_layer_fwd_from_t, plx_gcn_layer_workspace, plx_softmax_ce, plx_sync)
 
 
 def aligned_rows(rows: int, cols: int, dtype, dev) -> torch.Tensor:
@@ -50,6 +51,13 @@ class GcnNetwork:
             dn = Ws[l + 1].shape[1]
             self.chained[l] = (chain and dtype == torch.float32 and agg[l] and not agg[l + 1] and 32 < din <= 128
                                and 64 < dout <= 128 and dn <= 16 and self.act[l] != PLX_ACT_RELU)
+        # fwd_chained[l]: the product that writes layer l's output also forms T = F W of layer l+1 (combine-first), which then
+        # starts from T instead of reading F back; same shapes, any mask form
+        self.fwd_chained = [False] * self.L
+        for l in range(self.L - 1):
+            din, dout = Ws[l].shape
+            self.fwd_chained[l] = (chain and dtype == torch.float32 and agg[l] and not agg[l + 1] and 32 < din <= 128
+                                   and din % 4 == 0 and 32 < dout <= 128 and Ws[l + 1].shape[1] <= 16)
         nbytes = 1
         for l, W in enumerate(Ws):
             if self.chained[l]:
@@ -64,6 +72,7 @@ class GcnNetwork:
         self.saved: List[torch.Tensor] = []
         self.dH: List[Optional[torch.Tensor]] = []
         self.dT: List[Optional[torch.Tensor]] = []
+        self.T: List[Optional[torch.Tensor]] = []               # T[l] = F[l-1] W[l], written by layer l-1's forward call
         self.dW: List[torch.Tensor] = []
         for l, W in enumerate(Ws):
             rows, cols = csr.shape(bool(l % 2))
@@ -78,6 +87,7 @@ class GcnNetwork:
             hands_dt = l > 0 and self.chained[l - 1]             # then dH[l] is never formed: dT[l] goes to layer l-1
             self.dH.append(None if hands_dt else aligned_rows(cols, din, dtype, dev))
             self.dT.append(aligned_rows(cols, dout, dtype, dev) if hands_dt else None)
+            self.T.append(aligned_rows(cols, dout, dtype, dev) if (l > 0 and self.fwd_chained[l - 1]) else None)
             self.dW.append(torch.empty(din, dout, dtype=torch.float32, device=dev))
         rows_last = csr.shape(bool((self.L - 1) % 2))[0]
         self.dZ_last = aligned_rows(rows_last, Ws[-1].shape[1], dtype, dev)
@@ -87,8 +97,14 @@ class GcnNetwork:
     def forward(self, H0: torch.Tensor) -> torch.Tensor:
         h = H0
         for l, W in enumerate(self.Ws):
-            plx_gcn_layer_fwd(self.ctx, self.csr, bool(l % 2), h, W, self.Z[l], self.F[l], self.saved[l], self.ws,
-                              act=self.act[l], order=self.order)
+            if l > 0 and self.fwd_chained[l - 1]:                # T of this layer came out of the previous call
+                plx_gcn_layer_fwd_from_t(self.ctx, self.csr, bool(l % 2), self.T[l], self.Z[l], self.F[l], act=self.act[l])
+            elif l + 1 < self.L and self.fwd_chained[l]:
+                plx_gcn_layer_fwd_chained(self.ctx, self.csr, bool(l % 2), h, W, self.Z[l], self.F[l], self.saved[l],
+                                          self.Ws[l + 1], self.T[l + 1], self.ws, act=self.act[l], order=self.order)
+            else:
+                plx_gcn_layer_fwd(self.ctx, self.csr, bool(l % 2), h, W, self.Z[l], self.F[l], self.saved[l], self.ws,
+                                  act=self.act[l], order=self.order)
             if l + 1 < self.L:
                 h = self.F[l]
         return self.Z[-1]

@@ -464,7 +464,9 @@ def test_three_layer_network_as_the_bench_runs_it(ctx):
             assert rel_err(net.dW[l], ref.dW[l]) <= TOL32, f"dW of layer {l}, chain={chain}"
         assert rel_err(net.dH[0][pc.to(DEV)], ref.dF[0]) <= TOL32
     assert nets[0].chained == [False, True, False] and nets[0].dH[2] is None and nets[0].dT[2] is not None
-    assert nets[1].chained == [False, False, False]
+    assert nets[0].fwd_chained == [False, True, False] and nets[0].T[2] is not None
+    assert nets[1].chained == [False, False, False] and nets[1].fwd_chained == [False, False, False]
+    assert rel_err(nets[0].Z[-1], nets[1].Z[-1].double().cpu().numpy()) <= 2e-5
     for l in range(L):
         assert rel_err(nets[0].dW[l], nets[1].dW[l].double().cpu().numpy()) <= 2e-5
 
@@ -732,6 +734,74 @@ def test_chained_backward_of_two_layers(ctx, din, dout, dn, dtype, act):
     assert Q.shape == dQ.shape
     assert rel_err(gdW, oracle.gemm(S, dQ, ta=True)) <= tol
     assert rel_err(gdX.float(), oracle.spmm_t_coo(k, row, c64, v64, oracle.gemm(dQ, W, tb=True))) <= tol
+
+
+@pytest.mark.parametrize("din,dout,dn,dtype,act", [
+    (64, 128, 16, "f32", "bits"), (128, 128, 16, "f32", "values"), (100, 96, 7, "f32", "none"), (64, 64, 16, "f32", "bits"),
+    (128, 33, 1, "f32", "values"),
+    (32, 128, 16, "f32", "bits"), (64, 128, 17, "f32", "bits"), (602, 128, 16, "f32", "values"), (64, 128, 16, "bf16", "bits"),
+    (64, 128, 16, "f32", "values-combine")])
+def test_chained_forward_of_two_layers(ctx, din, dout, dn, dtype, act):
+    """Forward of two consecutive layers where the first layer's last product also forms T = F Wn of the
+    second (combine-first) layer, which then starts from T.  Shapes cover the kernel with the extra
+    product (both tile widths, ragged widths, every activation form) and every fall-back (narrow or
+    wide layer, dn above 16, bf16, combine-first first layer).  Against the oracle; F, the sign words
+    and the saved aggregation must be bit-identical to the plain call's."""
+    m, k = 1237, 1500
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    code = plx.PLX_F32 if dtype == "f32" else plx.PLX_BF16
+    tol = TOL32 if dtype == "f32" else 2e-2
+    order = plx.PLX_ORDER_COMBINE_FIRST if act.endswith("combine") else plx.PLX_ORDER_AGG_FIRST
+    actc = {"bits": plx.PLX_ACT_RELU_BITS, "values": plx.PLX_ACT_RELU, "values-combine": plx.PLX_ACT_RELU, "none": plx.PLX_ACT_NONE}[act]
+    rowptr, col, val = random_block(m, k, 7 * din + 3 * dout + dn)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(2 * din + dout + dn)
+
+    def matrix(rows, cols, src=None, t=tdt, fill=0.0):       # rows padded to 16 bytes, as the network keeps them
+        q = 16 // torch.empty(0, dtype=t).element_size()
+        buf = torch.full((rows, -(-cols // q) * q), fill, dtype=t, device=DEV)
+        if src is not None:
+            buf[:, :cols] = torch.as_tensor(np.asarray(src, np.float32)).to(t).to(DEV)
+        return buf, buf[:, :cols]
+
+    _, X = matrix(k, din, r.standard_normal((k, din)))
+    W = (r.standard_normal((din, dout)) * 0.2).astype(np.float32)
+    Wn = (r.standard_normal((dout, dn)) * 0.2).astype(np.float32)
+    X64 = X.double().cpu().numpy()
+    Q = oracle.gemm(oracle.spmm_coo(m, row, c64, v64, X64), W)
+    ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, dtype=code, act=actc, order=order), dtype=torch.uint8, device=DEV)
+    nw = (dout + 31) // 32
+    outs = []
+    for chained in (True, False):
+        _, F = matrix(m, dout); _, saved = matrix(m, din)
+        Tp, T = matrix(m, dn, fill=float("nan"))
+        words = torch.zeros(m, nw, dtype=torch.int32, device=DEV)
+        Zarg = words if actc == plx.PLX_ACT_RELU_BITS else None
+        if chained:
+            plx.plx_sync(ctx); plx.plx_timing_enable(ctx, True); plx.plx_timing_report(ctx)
+            plx.plx_gcn_layer_fwd_chained(ctx, csr, False, X, dev(W), Zarg, F, saved, dev(Wn), T, ws, act=actc, order=order)
+            launched = plx.plx_timing_report(ctx); plx.plx_timing_enable(ctx, False)
+            in_kernel = (dtype == "f32" and order == plx.PLX_ORDER_AGG_FIRST and 32 < din <= 128 and din % 4 == 0
+                         and 32 < dout <= 128 and dn <= 16)
+            assert any(name.endswith(f"next{dn}") for name in launched) == in_kernel, launched
+            assert any(f"N{dn},K{dout}]" in name for name in launched) == (not in_kernel), launched
+        else:
+            plx.plx_gcn_layer_fwd(ctx, csr, False, X, dev(W), Zarg, F, saved, ws, act=actc, order=order)
+            plx.plx_gemm_nn(ctx, F, dev(Wn), T)
+        _, Z2 = matrix(k, dn)
+        plx.plx_gcn_layer_fwd_from_t(ctx, csr, True, T, Z2, None, act=plx.PLX_ACT_NONE)
+        plx.plx_sync(ctx)
+        outs.append((F, words, saved, T, Z2))
+        F64 = F.double().cpu().numpy()
+        assert rel_err(F.float(), oracle.relu(Q) if actc != plx.PLX_ACT_NONE else Q) <= tol
+        T64 = oracle.gemm(F64, Wn)                                   # from the stored output, as the following layer sees it
+        assert rel_err(T.float(), T64) <= tol
+        assert bool(torch.isnan(Tp[:, dn:].float()).all())           # nothing written past dn
+        assert rel_err(Z2.float(), oracle.spmm_t_coo(k, row, c64, v64, T.double().cpu().numpy())) <= tol
+    for a, b in zip(outs[0][:3], outs[1][:3]):
+        assert torch.equal(a, b)
+    assert rel_err(outs[0][3].float(), outs[1][3].double().cpu().numpy()) <= (2e-5 if dtype == "f32" else 2e-2)
 
 
 def test_layer_very_wide_leading_dimension(ctx):
