@@ -92,6 +92,19 @@ def test_dense_and_elementwise_argument_checks(dry):
     assert L.plx_spmm(h, None, p, 4, p, 4, 4, 0) == plx.PLX_ERR_INVALID                                  # no handle
     assert L.plx_gcn_layer_fwd(h, None, 0, p, 4, p, 4, 4, 4, 0, 1, 0, p, 4, None, 0, None, 0, None, 0) == plx.PLX_ERR_INVALID
     assert L.plx_gcn_layer_workspace(None, 0, 4, 4, 0, 1, 0) == 0
+    # the layer-pair calls: no handle, no context, missing outputs
+    assert L.plx_gcn_layer_fwd_chained(h, None, 0, p, 4, p, 4, 4, 4, 0, 1, 0, p, 4, p, 4, p, 4, p, 4, 4, p, 4, None, 0) == plx.PLX_ERR_INVALID
+    assert L.plx_gcn_layer_fwd_chained(h, None, 0, p, 4, p, 4, 4, 4, 0, 1, 0, p, 4, p, 4, p, 4, p, 4, 4, None, 4, None, 0) == plx.PLX_ERR_INVALID
+    assert b"Tn is NULL" in L.plx_last_error(h)
+    assert L.plx_gcn_layer_fwd_from_t(h, None, 0, p, 4, 4, 0, 1, p, 4, None, 0) == plx.PLX_ERR_INVALID
+    assert L.plx_gcn_layer_fwd_from_t(h, None, 0, None, 4, 4, 0, 1, p, 4, None, 0) == plx.PLX_ERR_INVALID
+    assert b"T is NULL" in L.plx_last_error(h)
+    assert L.plx_gcn_layer_bwd_dt(h, None, 0, p, 4, None, 0, p, 4, 4, 4, 0, 0, p, 4, p, 4, p, 64) == plx.PLX_ERR_INVALID
+    assert L.plx_gcn_layer_bwd_dt(h, None, 0, p, 4, None, 0, p, 4, 4, 4, 0, 0, None, 4, p, 4, p, 64) == plx.PLX_ERR_INVALID
+    assert b"dT is NULL" in L.plx_last_error(h)
+    assert L.plx_gcn_layer_bwd_chained(h, None, 0, p, 4, p, 4, None, 0, p, 4, p, 4, 4, p, 4, 4, 4, 0, 0, 0, p, 4, p, 4, p, 64) == plx.PLX_ERR_INVALID
+    assert L.plx_gcn_layer_bwd_chained(None, None, 0, p, 4, p, 4, None, 0, p, 4, p, 4, 4, p, 4, 4, 4, 0, 0, 0, p, 4, p, 4, p, 64) == plx.PLX_ERR_INVALID
+    assert L.plx_gcn_layer_bwd_chained_workspace(h, None, 0, 4, 4, 4, 0, 1, 0) == 0
     assert L.plx_csr_dims(None, None, None, None) == plx.PLX_ERR_INVALID
     # tuning knob and blocked aggregation: argument rules hold without a device
     assert L.plx_ctx_set_column_windows(h, 0) == plx.PLX_ERR_INVALID

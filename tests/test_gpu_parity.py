@@ -804,6 +804,59 @@ def test_chained_forward_of_two_layers(ctx, din, dout, dn, dtype, act):
     assert rel_err(outs[0][3].float(), outs[1][3].double().cpu().numpy()) <= (2e-5 if dtype == "f32" else 2e-2)
 
 
+def test_layer_pair_argument_errors(ctx):
+    """Argument rules of the layer-pair calls that need a real adjacency handle."""
+    m, k, din, dout, dn = 300, 400, 64, 128, 16
+    rowptr, col, val = random_block(m, k, 77)
+    csr = plx.plx_csr_import(ctx, m, k, dev(rowptr), dev(col), dev(val))
+    X = torch.zeros(k, din, device=DEV); W = torch.zeros(din, dout, device=DEV); Wn = torch.zeros(dout, dn, device=DEV)
+    F = torch.zeros(m, dout, device=DEV); saved = torch.zeros(m, din, device=DEV); T = torch.zeros(m, dn, device=DEV)
+    dZn = torch.zeros(k, dn, device=DEV); gdX = torch.zeros(k, din, device=DEV)
+    gdW = torch.zeros(din, dout, device=DEV); gdWn = torch.zeros(dout, dn, device=DEV)
+    ws = torch.empty(plx.plx_gcn_layer_bwd_chained_workspace(ctx, csr, False, din, dout, dn, act=plx.PLX_ACT_NONE), dtype=torch.uint8, device=DEV)
+    ws2 = torch.empty(plx.plx_gcn_layer_workspace(csr, True, dout, dn, act=plx.PLX_ACT_NONE, order=plx.PLX_ORDER_COMBINE_FIRST),
+                      dtype=torch.uint8, device=DEV)
+
+    def status(fn, *a, **kw):
+        with pytest.raises(plx.PlxError) as e:
+            fn(*a, **kw)
+        return e.value.status
+
+    # with an activation the following layer reads F: it must be given
+    assert status(plx.plx_gcn_layer_fwd_chained, ctx, csr, False, X, W, torch.zeros(m, dout, device=DEV), None, saved, Wn, T, ws,
+                  act=plx.PLX_ACT_RELU) == plx.PLX_ERR_INVALID
+    # leading dimensions
+    L = plx._lib
+    h, c = ctx.handle, csr.handle
+    assert L.plx_gcn_layer_fwd_chained(h, c, 0, X.data_ptr(), din, W.data_ptr(), dout, din, dout, 0, 0, 1, None, 0, F.data_ptr(), dout,
+                                       saved.data_ptr(), din, Wn.data_ptr(), dn - 1, dn, T.data_ptr(), dn, ws.data_ptr(), ws.numel()) == plx.PLX_ERR_SHAPE
+    assert L.plx_gcn_layer_fwd_chained(h, c, 0, X.data_ptr(), din, W.data_ptr(), dout, din, dout, 0, 0, 1, None, 0, F.data_ptr(), dout,
+                                       saved.data_ptr(), din, Wn.data_ptr(), dn, 0, T.data_ptr(), dn, ws.data_ptr(), ws.numel()) == plx.PLX_ERR_INVALID
+    assert L.plx_gcn_layer_fwd_from_t(h, c, 1, T.data_ptr(), dn - 1, dn, 0, 0, dZn.data_ptr(), dn, None, 0) == plx.PLX_ERR_SHAPE
+    assert L.plx_gcn_layer_bwd_dt(h, c, 1, F.data_ptr(), dout, None, 0, dZn.data_ptr(), dn, dout, dn, 0, 0, T.data_ptr(), dn - 1,
+                                  gdWn.data_ptr(), dn, ws2.data_ptr(), ws2.numel()) == plx.PLX_ERR_SHAPE
+    assert L.plx_gcn_layer_bwd_dt(h, c, 1, F.data_ptr(), dout, None, 0, dZn.data_ptr(), dn, dout, dn, 0, 0, T.data_ptr(), dn,
+                                  gdWn.data_ptr(), dn, ws2.data_ptr(), ws2.numel() - 1) == plx.PLX_ERR_SHAPE
+    args = [h, c, 0, X.data_ptr(), din, W.data_ptr(), dout, None, 0, T.data_ptr(), dn, Wn.data_ptr(), dn, dn, saved.data_ptr(), din,
+            din, dout, 0, 0, 1, gdX.data_ptr(), din, gdW.data_ptr(), dout, ws.data_ptr(), ws.numel()]
+    assert L.plx_gcn_layer_bwd_chained(*args) == plx.PLX_OK
+    bad = list(args); bad[10] = dn - 1                                       # lddtn < dn
+    assert L.plx_gcn_layer_bwd_chained(*bad) == plx.PLX_ERR_SHAPE
+    bad = list(args); bad[11] = None                                         # Wn
+    assert L.plx_gcn_layer_bwd_chained(*bad) == plx.PLX_ERR_INVALID
+    bad = list(args); bad[13] = 0                                            # dn
+    assert L.plx_gcn_layer_bwd_chained(*bad) == plx.PLX_ERR_INVALID
+    # unaligned rows of dT put the product outside the kernel: the workspace sized for the in-kernel path is then too small
+    odd = torch.zeros(m, dn + 1, device=DEV)[:, :dn]
+    bad = list(args); bad[9] = odd.data_ptr(); bad[10] = dn + 1
+    assert L.plx_gcn_layer_bwd_chained(*bad) == plx.PLX_ERR_SHAPE
+    assert b"smaller than" in L.plx_last_error(h)
+    big = torch.empty(ws.numel() + m * dout * 4 + 256, dtype=torch.uint8, device=DEV)
+    bad[-2] = big.data_ptr(); bad[-1] = big.numel()
+    assert L.plx_gcn_layer_bwd_chained(*bad) == plx.PLX_OK
+    plx.plx_sync(ctx)
+
+
 def test_layer_very_wide_leading_dimension(ctx):
     """Rows 2^23 elements apart: the small-width dense kernels address a tile with 31-bit byte offsets
     and hand such matrices to the kernels with 64-bit addressing; results must not change."""
