@@ -10,12 +10,12 @@ import paper_2505_04083_amd as plx
 from paper_2505_04083_amd.network import GcnNetwork
 
 
-class GpuRun:
+class NetworkRun:
     pass
 
 
 def run_network(ctx, csr, H0: torch.Tensor, Ws: List[torch.Tensor], y: torch.Tensor, order=plx.PLX_ORDER_AUTO,
-                backward: bool = True) -> GpuRun:
+                backward: bool = True) -> NetworkRun:
     """Layer l uses orientation l % 2 (Eq. 5.3-5.4).  H0 is in P_c order; y in the order of the
     last layer's output.  Pre-activations are kept so that tests can compare every layer."""
     net = GcnNetwork(ctx, csr, Ws, dtype=H0.dtype, order=order, keep_preactivation=True)
@@ -23,7 +23,7 @@ def run_network(ctx, csr, H0: torch.Tensor, Ws: List[torch.Tensor], y: torch.Ten
     if backward:
         net.backward(H0, y)
     net.sync()
-    run = GpuRun()
+    run = NetworkRun()
     run.Z, run.F, run.dW, run.dF0, run.loss = net.Z, net.F, net.dW, net.dH[0], net.loss
     return run
 
