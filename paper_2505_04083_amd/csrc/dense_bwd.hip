@@ -16,6 +16,11 @@
 //   dW (Mp x N): v_mfma_f32_32x32x2_f32 over the 32 rows of the tile, accumulated in registers for
 //       the whole chunk; block q of the (Mp/32) x (N/32) grid belongs to wavefront q % 4.
 // Chunk partials of dW are summed afterwards in a fixed order (bit-reproducible).
+//
+// Where both widths exceed 32 the fp32 products are formed from six bf16 matrix products each
+// (k_bwd_dense_x3); that kernel can also take the gradient in factored form, Q = G Wn^T with G
+// the narrow A^T dZ of a following combine-first layer, and form the tile itself (Eq. 2.6 of
+// that layer fused into this pass), so that the R x N gradient never exists in memory.
 #include "plx_internal.h"
 #include "buffer_addr.h"
 #include "bf16_frag.h"

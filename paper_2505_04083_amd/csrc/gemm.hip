@@ -14,6 +14,10 @@
 // unaligned rows).  Layer-sized products (K, N <= 128) take the persistent kernel further down,
 // which keeps the weights in registers.
 //
+// Where K and N both exceed 32 the persistent kernel forms its fp32 products from six bf16 matrix
+// products each (k_gemm_small_x3); that kernel can also multiply its result tile by the weights
+// of a following combine-first layer on the way out (T = F Wn), so that layer does not read F back.
+//
 // The transposed product (reduction over the node dimension) is split over row chunks; each
 // workgroup writes its partial tile and a second kernel adds the partials in a fixed order, so
 // the result does not depend on scheduling.
