@@ -169,7 +169,7 @@ def windows(args):
             csr = plx.plx_build_csr(ctx, cfg.n, src, dst, pr, pc)
         case = {"n_windows": nw}
         for d in widths:
-            ld = -(-d // 16) * 16                    # rows padded to 64 bytes, as the network sequencer stores them
+            ld = -(-d // 16) * 16                    # rows padded to 64 bytes
             X = torch.zeros(k, ld, device=DEV)[:, :d]; X.copy_(synth.normal(cfg.seed, synth.S_FEAT, k, d, DEV))
             G = torch.zeros(m, ld, device=DEV)[:, :d]; G.copy_(synth.normal(cfg.seed, synth.S_AUX, m, d, DEV))
             Y = torch.empty(m, ld, device=DEV)[:, :d]
