@@ -372,14 +372,16 @@ static plx_order resolve_order(plx_order order, int64_t din, int64_t dout) {
 // Workspace layout (each region 256-byte aligned):
 //   COMBINE_FIRST: T / G  [ka x dout]   | dZ [ma x dout] (if act)  | dW partial sums
 //   AGG_FIRST    : dS     [ma x din]    | dZ [ma x dout] (if act)  | dW partial sums
-// Internal matrices get a leading dimension padded to 16 bytes so every row allows 128-bit accesses.
+// Internal matrices get a leading dimension padded to 16 bytes so every row allows 128-bit accesses; rows shorter
+// than 256 bytes get a 64-byte pitch, so that a gathered row never touches a cache line more than it must.
 struct LayerWs {
     size_t off_a = 0, off_dz = 0, off_tn = 0, total = 0;
     int64_t ld_in = 0, ld_out = 0;   // padded din / dout in elements
 };
 
 static int64_t pad16(int64_t cols, plx_dtype dtype) {
-    const int64_t q = 16 / (int64_t)elt_size(dtype);
+    const int64_t es = (int64_t)elt_size(dtype);
+    const int64_t q = (cols * es < 256 ? 64 : 16) / es;
     return (cols + q - 1) / q * q;
 }
 
