@@ -35,3 +35,14 @@ def rel_err(gpu, ref: np.ndarray) -> float:
     if denom == 0:
         return float(np.abs(g).max())
     return float(np.abs(g - ref).max() / denom)
+
+
+def elt_err(gpu, ref: np.ndarray, floor: float = 1e-3) -> float:
+    """Element-wise form of the tolerance: max over elements of |g - o| / max(|o|, floor * max |o|).  Unlike
+    rel_err it weighs an error in a small entry (a low-degree row next to a hub) by that entry's own size,
+    down to `floor` of the tensor's largest magnitude."""
+    g = gpu.detach().double().cpu().numpy() if isinstance(gpu, torch.Tensor) else np.asarray(gpu, np.float64)
+    top = np.abs(ref).max() if ref.size else 0.0
+    if top == 0:
+        return float(np.abs(g).max()) if g.size else 0.0
+    return float((np.abs(g - ref) / np.maximum(np.abs(ref), floor * top)).max())
