@@ -157,6 +157,21 @@ PLX_API plx_status plx_spmm(plx_ctx* ctx, const plx_csr* csr, const void* X, int
 PLX_API plx_status plx_spmm_t(plx_ctx* ctx, const plx_csr* csr, const void* X, int64_t ldx, void* Y, int64_t ldy,
                               int64_t d, plx_dtype dtype);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): plx_spmm (transposed == 0) or plx_spmm_t (transposed != 0) with the same
+ * arguments and bit-identical results, except that the partial sums of split rows go to a fixed
+ * 32 MiB buffer inside the library (one per GPU, held until the process ends) instead of a buffer the
+ * context allocates on demand.  The call allocates nothing, frees nothing, records no timing events
+ * (plx_timing_report does not list it) and does not wait.  Limit: (number of segments of the
+ * orientation) x (floats per segment: d rounded up to a power-of-two number of 16-byte vectors, at
+ * most 256 per pass) x 4 bytes <= 32 MiB, else PLX_ERR_UNSUPPORTED before anything is queued; a
+ * handle without rows of 256 or more entries has no segments and always fits.  The buffer needs no
+ * clearing (every segment's partial sums are fully rewritten before they are read), but all calls on
+ * one GPU share it: two calls that overlap in time on the same GPU, from any context or stream, race.
+ * PLX_ERR_DEVICE if the buffer's address could not be obtained when the context was created. */
+PLX_API plx_status plx_spmm_static(plx_ctx* ctx, const plx_csr* csr, int transposed, const void* X, int64_t ldx,
+                                   void* Y, int64_t ldy, int64_t d, plx_dtype dtype);
+
 /* Blocked aggregation (Sec. 5.2: the adjacency is cut into row blocks, the product of each block
  * is formed -- and, on several GPUs, all-reduced -- separately, and the blocks are concatenated).
  * plx_csr_set_row_blocks re-bins both orientations into n_blocks (1..64) blocks of

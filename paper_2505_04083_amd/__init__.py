@@ -25,7 +25,7 @@ EXPORTED = [
     "plx_ctx_create", "plx_ctx_destroy", "plx_ctx_set_column_windows", "plx_ctx_set_split_products", "plx_last_error", "plx_status_string", "plx_sync",
     "plx_timing_enable", "plx_timing_report",
     "plx_build_csr", "plx_csr_import", "plx_csr_dims", "plx_csr_export", "plx_csr_bins", "plx_csr_destroy",
-    "plx_csr_set_row_blocks", "plx_csr_row_blocks", "plx_spmm_block", "plx_spmm", "plx_spmm_t", "plx_gemm_nn", "plx_gemm_nt", "plx_gemm_tn_workspace", "plx_gemm_tn",
+    "plx_csr_set_row_blocks", "plx_csr_row_blocks", "plx_spmm_block", "plx_spmm", "plx_spmm_t", "plx_spmm_static", "plx_gemm_nn", "plx_gemm_nt", "plx_gemm_tn_workspace", "plx_gemm_tn",
     "plx_relu", "plx_relu_bwd", "plx_softmax_ce",
     "plx_gcn_layer_workspace", "plx_gcn_layer_fwd", "plx_gcn_layer_bwd",
     "plx_gcn_layer_bwd_dt", "plx_gcn_layer_bwd_chained_workspace", "plx_gcn_layer_bwd_chained",
@@ -63,6 +63,7 @@ def _load() -> ctypes.CDLL:
         "plx_csr_row_blocks": (_int, [_vp, _int, ctypes.POINTER(_int), ctypes.POINTER(_i64)]),
         "plx_spmm_block": (_int, [_vp, _vp, _int, _int, _vp, _i64, _vp, _i64, _i64, _int]),
         "plx_spmm": (_int, [_vp, _vp, _vp, _i64, _vp, _i64, _i64, _int]),
+        "plx_spmm_static": (_int, [_vp, _vp, _int, _vp, _i64, _vp, _i64, _i64, _int]),
         "plx_spmm_t": (_int, [_vp, _vp, _vp, _i64, _vp, _i64, _i64, _int]),
         "plx_gemm_nn": (_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int]),
         "plx_gemm_nt": (_int, [_vp, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int]),
@@ -313,6 +314,17 @@ def plx_spmm(ctx: plx_ctx, csr: plx_csr, X: torch.Tensor, Y: torch.Tensor, d: Op
 def plx_spmm_t(ctx: plx_ctx, csr: plx_csr, X: torch.Tensor, Y: torch.Tensor, d: Optional[int] = None) -> torch.Tensor:
     """Y[k x d] = A^T X[m x d]."""
     return _spmm(_lib.plx_spmm_t, ctx, csr, X, Y, d)
+
+
+def plx_spmm_static(ctx: plx_ctx, csr: plx_csr, transposed: bool, X: torch.Tensor, Y: torch.Tensor,
+                    d: Optional[int] = None) -> torch.Tensor:
+    """plx_spmm / plx_spmm_t through the library's fixed partial-sum buffer: the call allocates nothing."""
+    xp, ldx = _mat(X)
+    yp, ldy = _mat(Y)
+    if d is None:
+        d = X.shape[1]
+    ctx.check(_lib.plx_spmm_static(ctx.handle, csr.handle, int(transposed), xp, ldx, yp, ldy, d, _dtype_code(X)))
+    return Y
 
 
 def plx_gemm_nn(ctx: plx_ctx, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor) -> torch.Tensor:

@@ -109,6 +109,9 @@ plx_status plx_ctx_create(int device, void* hip_stream, plx_alloc_fn alloc, plx_
         }
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0) c->n_cu = cus;
+        // the fixed buffer of plx_spmm_static: its address on this GPU is looked up here, once, so that the call
+        // itself does no set-up work; a failure is reported by that call, not by this one
+        (void)static_partials(c, nullptr);
     }
 
     *out = c;
@@ -268,6 +271,24 @@ plx_status plx_spmm_block(plx_ctx* ctx, const plx_csr* csr, int transposed, int 
     if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
     if (d == 0 || o.rows == 0) return PLX_OK;
     return launch_spmm(ctx, o, X, ldx, Y, ldy, d, dtype, nullptr, 0, block);
+}
+
+plx_status plx_spmm_static(plx_ctx* ctx, const plx_csr* csr, int transposed, const void* X, int64_t ldx, void* Y,
+                           int64_t ldy, int64_t d, plx_dtype dtype) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!csr) return fail(ctx, PLX_ERR_INVALID, "csr is NULL");
+    if (!dtype_ok(dtype)) return fail(ctx, PLX_ERR_INVALID, "unknown dtype %d", (int)dtype);
+    if (d < 0) return fail(ctx, PLX_ERR_INVALID, "d = %lld is negative", (long long)d);
+    const Orient& o = csr->o[transposed ? 1 : 0];
+    if (d > 0 && ((o.cols > 0 && !X) || (o.rows > 0 && !Y))) return fail(ctx, PLX_ERR_INVALID, "X or Y is NULL");
+    if (ldx < d || ldy < d) return fail(ctx, PLX_ERR_SHAPE, "leading dimension (%lld, %lld) smaller than d = %lld",
+                                        (long long)ldx, (long long)ldy, (long long)d);
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    if (d == 0 || o.rows == 0) return PLX_OK;
+    size_t bytes = 0;
+    float* part = static_partials(ctx, &bytes);    // a table look-up after plx_ctx_create
+    if (!part) return fail(ctx, PLX_ERR_DEVICE, "the address of the fixed partial-sum buffer could not be obtained on device %d", ctx->device);
+    return launch_spmm(ctx, o, X, ldx, Y, ldy, d, dtype, nullptr, 0, -1, part, bytes);
 }
 
 plx_status plx_spmm(plx_ctx* ctx, const plx_csr* csr, const void* X, int64_t ldx, void* Y, int64_t ldy, int64_t d,

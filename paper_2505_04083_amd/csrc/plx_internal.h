@@ -119,7 +119,7 @@ struct KernelTimer {
     plx_ctx* ctx;
     bool on;
     plx_ctx::Timed t;
-    KernelTimer(plx_ctx* c, const std::string& name) : ctx(c), on(c->timing) {
+    KernelTimer(plx_ctx* c, const std::string& name, bool allowed = true) : ctx(c), on(c->timing && allowed) {
         if (!on) return;
         t.name = name;
         if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) { on = false; return; }
@@ -149,7 +149,12 @@ void free_orient(plx_ctx* ctx, Orient& o);
 // Y = A X (Y may be NULL); if Yact != NULL it also receives max(A X, 0).  block >= 0 restricts the
 // product to the rows of that row block (other rows of Y are not touched)
 plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* Y, int64_t ldy,
-                       int64_t d, plx_dtype dtype, void* Yact = nullptr, int64_t ldyact = 0, int block = -1);
+                       int64_t d, plx_dtype dtype, void* Yact = nullptr, int64_t ldyact = 0, int block = -1,
+                       float* partials = nullptr, size_t partials_bytes = 0);
+// partials != NULL: the partial sums of split rows go there instead of into the context's buffer; the call then
+// allocates nothing, records no timing events, and fails with PLX_ERR_UNSUPPORTED if partials_bytes is too small.
+// The fixed per-GPU buffer of plx_spmm_static (resolved once per device, with that device current; NULL on failure):
+float* static_partials(plx_ctx* ctx, size_t* bytes);
 // C = A op(B) (C may be NULL); if Fact != NULL it also receives max(C, 0); if bits != NULL it receives
 // the sign bits [C > 0] (bit j % 32 of word j / 32 of row i, ldbits words per row)
 plx_status launch_gemm(plx_ctx* ctx, bool bt, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,

@@ -20,6 +20,7 @@
 #include "plx_internal.h"
 
 #include <algorithm>
+#include <mutex>
 
 namespace plx {
 namespace {
@@ -286,8 +287,16 @@ __global__ __launch_bounds__(256) void k_spmm_combine(int64_t n_long, const int3
     if (out.ya) out.ya[row * out.ldya + j] = narrow<T>(s > 0.f ? s : 0.f);
 }
 
+// Where the partial sums of the segments go.  `given` == NULL: the context's own buffer, grown on demand.
+// Otherwise the caller of launch_spmm brought the memory (the allocation-free entry point): it is used as
+// it is, nothing is allocated or timed (the timer creates events), and a product that needs more fails.
+struct Partials {
+    float* given = nullptr;
+    size_t bytes = 0;
+};
+
 template <typename T, int G, int VW>
-plx_status run_pass(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t ldx, Out<T> out, int d) {
+plx_status run_pass(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t ldx, Out<T> out, int d, const Partials& pt) {
     hipStream_t s = ctx->stream;
     const int64_t s0 = o.off(blk, 0);                                  // first slot of this row block
     const int64_t n_sub = o.off(blk, kSubwaveMaxClass + 1) - s0;
@@ -295,11 +304,12 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t 
     const int64_t n_long = o.long0[blk + 1] - o.long0[blk], l0 = o.long0[blk];
     const int64_t n_seg = o.seg0b[blk + 1] - o.seg0b[blk], g0 = o.seg0b[blk];
     constexpr int WPB = 256 / kWave;   // wavefronts per block
+    const bool timed = ctx->timing && !pt.given;
     char label[64];
-    snprintf(label, sizeof label, "<%s,G%d,VW%d,d%d>[%s]", sizeof(T) == 4 ? "f32" : "bf16", G, VW, d, o.tag ? "At" : "A");
+    if (timed) snprintf(label, sizeof label, "<%s,G%d,VW%d,d%d>[%s]", sizeof(T) == 4 ? "f32" : "bf16", G, VW, d, o.tag ? "At" : "A");
     const int64_t sub_count = n_sub;
     if (sub_count > 0) {
-        KernelTimer kt(ctx, std::string("spmm_subwave") + label);
+        KernelTimer kt(ctx, timed ? std::string("spmm_subwave") + label : std::string(), timed);
         constexpr int R = kWave / G;
         int64_t blocks = ceil_div(ceil_div(sub_count, R), WPB);
 #if PLX_SUB_PERSIST
@@ -309,15 +319,23 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t 
                                                                          ldx, out, d);
     }
     if (n_wave > 0) {
-        KernelTimer kt(ctx, std::string("spmm_wave") + label);
+        KernelTimer kt(ctx, timed ? std::string("spmm_wave") + label : std::string(), timed);
         int64_t blocks = ceil_div(n_wave, WPB);
         k_spmm_wave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + s0 + n_sub, n_wave, o.bptr + s0 + n_sub, o.col,
                                                                       o.val, X, ldx, out, d);
     }
     if (n_seg > 0) {
-        PLX_TRY(ensure_scratch(ctx, (size_t)o.n_seg * G * VW * sizeof(float)));
-        float* part = static_cast<float*>(ctx->scratch);                // indexed by the global segment number
-        KernelTimer kt(ctx, std::string("spmm_split") + label);
+        const size_t need = (size_t)o.n_seg * G * VW * sizeof(float);
+        float* part = pt.given;                                         // indexed by the global segment number
+        if (part) {
+            if (need > pt.bytes)
+                return fail(ctx, PLX_ERR_UNSUPPORTED, "the partial sums of %lld segments at this width take %zu bytes, the fixed "
+                            "buffer holds %zu", (long long)o.n_seg, need, pt.bytes);
+        } else {
+            PLX_TRY(ensure_scratch(ctx, need));
+            part = static_cast<float*>(ctx->scratch);
+        }
+        KernelTimer kt(ctx, timed ? std::string("spmm_split") + label : std::string(), timed);
         k_spmm_segment<T, G, VW><<<dim3((unsigned)ceil_div(n_seg, WPB)), 256, 0, s>>>(n_seg, o.seg_launch + g0, o.seg_lo, o.seg_len,
                                                                                        o.col, o.val, X, ldx, part, d);
         int64_t total = n_long * d;
@@ -329,7 +347,7 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t 
 }
 
 template <typename T, int VW>
-plx_status run_vw(plx_ctx* ctx, const Orient& o, int block, const T* X, int64_t ldx, Out<T> out, int64_t d) {
+plx_status run_vw(plx_ctx* ctx, const Orient& o, int block, const T* X, int64_t ldx, Out<T> out, int64_t d, const Partials& pt) {
     const int tile = kWave * VW;                        // widest pass one wavefront covers
     for (int64_t t0 = 0; t0 < d; t0 += tile) {
         int dp = (int)std::min<int64_t>(tile, d - t0);
@@ -342,13 +360,13 @@ plx_status run_vw(plx_ctx* ctx, const Orient& o, int block, const T* X, int64_t 
         for (int blk = b_lo; blk < b_hi; ++blk) {
         plx_status st;
         switch (G) {
-            case 1: st = run_pass<T, 1, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
-            case 2: st = run_pass<T, 2, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
-            case 4: st = run_pass<T, 4, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
-            case 8: st = run_pass<T, 8, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
-            case 16: st = run_pass<T, 16, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
-            case 32: st = run_pass<T, 32, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
-            default: st = run_pass<T, 64, VW>(ctx, o, blk, Xp, ldx, op, dp); break;
+            case 1: st = run_pass<T, 1, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
+            case 2: st = run_pass<T, 2, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
+            case 4: st = run_pass<T, 4, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
+            case 8: st = run_pass<T, 8, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
+            case 16: st = run_pass<T, 16, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
+            case 32: st = run_pass<T, 32, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
+            default: st = run_pass<T, 64, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
         }
         PLX_TRY(st);
         }
@@ -358,10 +376,39 @@ plx_status run_vw(plx_ctx* ctx, const Orient& o, int block, const T* X, int64_t 
 
 bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// Fixed buffer for the partial sums of split rows, for callers that cannot allocate (plx_spmm_static).  Every GPU
+// the library runs on holds its own copy of this array, at its own address, until the process ends.  In host code
+// the array's name is only a stand-in for hipGetSymbolAddress: kernels are given the resolved address.
+constexpr size_t kStaticPartialsBytes = size_t(32) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticPartialsBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+float* g_static_ptr[kMaxDevices];       // per device ordinal, resolved with that device current
+
 }  // namespace
 
+float* static_partials(plx_ctx* ctx, size_t* bytes) {
+    if (bytes) *bytes = kStaticPartialsBytes;
+    if (ctx->dry || ctx->device < 0 || ctx->device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[ctx->device]) {
+        int current = -1;
+        if (hipGetDevice(&current) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        if (current != ctx->device && hipSetDevice(ctx->device) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (current != ctx->device) (void)hipSetDevice(current);
+        if (e != hipSuccess || !p) { (void)hipGetLastError(); return nullptr; }
+        g_static_ptr[ctx->device] = static_cast<float*>(p);
+    }
+    return g_static_ptr[ctx->device];
+}
+
 plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* Y, int64_t ldy, int64_t d,
-                       plx_dtype dtype, void* Yact, int64_t ldyact, int block) {
+                       plx_dtype dtype, void* Yact, int64_t ldyact, int block, float* partials, size_t partials_bytes) {
+    Partials pt;
+    pt.given = partials; pt.bytes = partials_bytes;
     if (o.rows >= (int64_t(1) << 31) || o.nnz >= (int64_t(1) << 31))
         return fail(ctx, PLX_ERR_UNSUPPORTED, "matrix too large for 32-bit ids");
     // widest vector the layout allows: base pointers and row pitches must keep every row aligned
@@ -370,18 +417,29 @@ plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx
                (!Y || (aligned_to(Y, bytes) && (ldy * es) % bytes == 0)) &&
                (!Yact || (aligned_to(Yact, bytes) && (ldyact * es) % bytes == 0));
     };
+    if (partials && o.n_seg > 0) {
+        // checked before anything is queued: the widest pass covers min(d, 64 VW) columns with G VW floats per segment
+        const int vw = dtype == PLX_F32 ? (fits(16, 4) ? 4 : fits(8, 4) ? 2 : 1) : (fits(16, 2) ? 8 : fits(8, 2) ? 4 : 1);
+        const int64_t dp = std::min<int64_t>(d, (int64_t)kWave * vw);
+        int64_t g = 1;
+        while (g * vw < dp) g <<= 1;
+        const size_t need = (size_t)o.n_seg * (size_t)(g * vw) * sizeof(float);
+        if (need > partials_bytes)
+            return fail(ctx, PLX_ERR_UNSUPPORTED, "the partial sums of %lld segments at width %lld take %zu bytes, more than the "
+                        "%zu bytes of the fixed buffer", (long long)o.n_seg, (long long)d, need, partials_bytes);
+    }
     if (dtype == PLX_F32) {
         const float* x = static_cast<const float*>(X);
         Out<float> out{static_cast<float*>(Y), ldy, static_cast<float*>(Yact), ldyact};
-        if (fits(16, 4)) return run_vw<float, 4>(ctx, o, block, x, ldx, out, d);
-        if (fits(8, 4)) return run_vw<float, 2>(ctx, o, block, x, ldx, out, d);
-        return run_vw<float, 1>(ctx, o, block, x, ldx, out, d);
+        if (fits(16, 4)) return run_vw<float, 4>(ctx, o, block, x, ldx, out, d, pt);
+        if (fits(8, 4)) return run_vw<float, 2>(ctx, o, block, x, ldx, out, d, pt);
+        return run_vw<float, 1>(ctx, o, block, x, ldx, out, d, pt);
     }
     const bf16_t* x = static_cast<const bf16_t*>(X);
     Out<bf16_t> out{static_cast<bf16_t*>(Y), ldy, static_cast<bf16_t*>(Yact), ldyact};
-    if (fits(16, 2)) return run_vw<bf16_t, 8>(ctx, o, block, x, ldx, out, d);
-    if (fits(8, 2)) return run_vw<bf16_t, 4>(ctx, o, block, x, ldx, out, d);
-    return run_vw<bf16_t, 1>(ctx, o, block, x, ldx, out, d);
+    if (fits(16, 2)) return run_vw<bf16_t, 8>(ctx, o, block, x, ldx, out, d, pt);
+    if (fits(8, 2)) return run_vw<bf16_t, 4>(ctx, o, block, x, ldx, out, d, pt);
+    return run_vw<bf16_t, 1>(ctx, o, block, x, ldx, out, d, pt);
 }
 
 }  // namespace plx
