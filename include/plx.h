@@ -104,6 +104,10 @@ PLX_API plx_status plx_sync(plx_ctx* ctx);                /* wait for the contex
  * buf_bytes -- into the HOST buffer `buf`, and clears the record. */
 PLX_API plx_status plx_timing_enable(plx_ctx* ctx, int on);
 PLX_API plx_status plx_timing_report(plx_ctx* ctx, char* buf, size_t buf_bytes);
+/* The same record unaggregated: one line per timed launch, in launch order, "<name> <ms>\n" (a benchmark
+ * uses the order to match the launches of a step with a profiler's dispatch list).  Waits for the stream
+ * and clears the record like plx_timing_report; PLX_ERR_SHAPE if buf_bytes is too small for all lines. */
+PLX_API plx_status plx_timing_trace(plx_ctx* ctx, char* buf, size_t buf_bytes);
 
 /* ---- adjacency set-up (Sec. 2.1 preprocessing + Sec. 5.1 double permutation) -----------------
  * plx_build_csr: src/dst are device int64[n_edges] node ids in [0, n), any order, either or

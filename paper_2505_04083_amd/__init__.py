@@ -23,7 +23,7 @@ PLX_ORDER_COMBINE_FIRST, PLX_ORDER_AGG_FIRST, PLX_ORDER_AUTO = 0, 1, 2
 
 EXPORTED = [
     "plx_ctx_create", "plx_ctx_destroy", "plx_ctx_set_column_windows", "plx_ctx_set_split_products", "plx_last_error", "plx_status_string", "plx_sync",
-    "plx_timing_enable", "plx_timing_report",
+    "plx_timing_enable", "plx_timing_report", "plx_timing_trace",
     "plx_build_csr", "plx_csr_import", "plx_csr_dims", "plx_csr_export", "plx_csr_bins", "plx_csr_destroy",
     "plx_csr_set_row_blocks", "plx_csr_row_blocks", "plx_spmm_block", "plx_spmm", "plx_spmm_t", "plx_spmm_static", "plx_gemm_nn", "plx_gemm_nt", "plx_gemm_tn_workspace", "plx_gemm_tn",
     "plx_relu", "plx_relu_bwd", "plx_softmax_ce",
@@ -51,6 +51,7 @@ def _load() -> ctypes.CDLL:
         "plx_sync": (_int, [_vp]),
         "plx_timing_enable": (_int, [_vp, _int]),
         "plx_timing_report": (_int, [_vp, ctypes.c_char_p, _sz]),
+        "plx_timing_trace": (_int, [_vp, ctypes.c_char_p, _sz]),
         "plx_build_csr": (_int, [_vp, _i64, _i64, _vp, _vp, _vp, _vp, ctypes.POINTER(_vp)]),
         "plx_csr_import": (_int, [_vp, _i64, _i64, _i64, _vp, _vp, _vp, ctypes.POINTER(_vp)]),
         "plx_csr_dims": (_int, [_vp, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.POINTER(_i64)]),
@@ -261,6 +262,17 @@ def plx_timing_report(ctx: plx_ctx):
     for line in buf.value.decode().splitlines():
         name, count, ms = line.rsplit(" ", 2)
         out[name] = (int(count), float(ms))
+    return out
+
+
+def plx_timing_trace(ctx: plx_ctx, max_bytes: int = 1 << 22):
+    """[(kernel name, ms)] of every timed launch since the last report, in launch order."""
+    buf = ctypes.create_string_buffer(max_bytes)
+    ctx.check(_lib.plx_timing_trace(ctx.handle, buf, len(buf)))
+    out = []
+    for line in buf.value.decode().splitlines():
+        name, ms = line.rsplit(" ", 1)
+        out.append((name, float(ms)))
     return out
 
 

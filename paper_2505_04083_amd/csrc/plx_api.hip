@@ -233,6 +233,29 @@ plx_status plx_timing_report(plx_ctx* ctx, char* buf, size_t buf_bytes) {
     return PLX_OK;
 }
 
+plx_status plx_timing_trace(plx_ctx* ctx, char* buf, size_t buf_bytes) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (!buf || buf_bytes == 0) return fail(ctx, PLX_ERR_INVALID, "buf is NULL or empty");
+    if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+    PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    std::string out;
+    for (auto& t : ctx->timed) {
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, t.start, t.stop);
+        (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+        char line[256];
+        snprintf(line, sizeof line, "%s %.6f\n", t.name.c_str(), ms);
+        out += line;
+    }
+    ctx->timed.clear();
+    if (out.size() + 1 > buf_bytes)
+        return fail(ctx, PLX_ERR_SHAPE, "the trace takes %zu bytes, the buffer holds %zu (the record was cleared)", out.size() + 1, buf_bytes);
+    memcpy(buf, out.data(), out.size());
+    buf[out.size()] = 0;
+    return PLX_OK;
+}
+
 // ---- sparse x dense ---------------------------------------------------------------------------
 
 static plx_status spmm_entry(plx_ctx* ctx, const plx_csr* csr, int t, const void* X, int64_t ldx, void* Y,
