@@ -9,7 +9,7 @@ layer, whose Q are the logits), and backward dQ = dF' * ReLU'(Q) (Eq. 2.4), dW =
 from __future__ import annotations
 
 from dataclasses import dataclass, field
-from typing import List, Sequence
+from typing import List, Optional, Sequence
 
 import numpy as np
 
@@ -46,19 +46,32 @@ def forward(adj: Adjacency, F0, Ws: Sequence) -> Trace:
     return t
 
 
-def forward_backward(adj: Adjacency, F0, Ws: Sequence, y) -> Trace:
-    t = forward(adj, F0, Ws)
+def backward_from(adj: Adjacency, t: Trace, Ws: Sequence, dQ_last, masks: Optional[Sequence] = None) -> Trace:
+    """Eq. 2.4-2.7 for every layer, starting from the gradient dQ_last with respect to the last layer's Q.
+
+    masks (optional): masks[l] is a 0/1 array that takes the place of [Q_l > 0] in Eq. 2.4.  The sign of Q_l is an
+    integer decision; when the implementation under test stores its activations in a narrower type, that decision is
+    taken in ITS precision and handed in here, so that both sides differentiate the same piecewise-linear function."""
     L = len(Ws)
-    t.loss, dQ = softmax_ce(t.Q[-1], y)
+    dQ = np.asarray(dQ_last, np.float64)
     t.dQ = [None] * L; t.dW = [None] * L; t.dH = [None] * L; t.dF = [None] * L
     for l in range(L - 1, -1, -1):
         if l + 1 < L:
-            dQ = relu_bwd(t.Q[l], t.dF[l + 1])                     # Eq. 2.4
+            if masks is not None and masks[l] is not None:
+                dQ = t.dF[l + 1] * np.asarray(masks[l], np.float64)  # Eq. 2.4, decision given
+            else:
+                dQ = relu_bwd(t.Q[l], t.dF[l + 1])                 # Eq. 2.4
         t.dQ[l] = dQ
         t.dW[l] = gemm(t.H[l], dQ, ta=True)                        # Eq. 2.5
         t.dH[l] = gemm(dQ, np.asarray(Ws[l], np.float64), tb=True)  # Eq. 2.6
         t.dF[l] = spmm_t_coo(adj.n, adj.row, adj.col, adj.val, t.dH[l])   # Eq. 2.7
     return t
+
+
+def forward_backward(adj: Adjacency, F0, Ws: Sequence, y, masks: Optional[Sequence] = None) -> Trace:
+    t = forward(adj, F0, Ws)
+    t.loss, dQ = softmax_ce(t.Q[-1], y)
+    return backward_from(adj, t, Ws, dQ, masks)
 
 
 def loss_only(adj: Adjacency, F0, Ws: Sequence, y) -> float:

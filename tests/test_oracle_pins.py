@@ -336,3 +336,83 @@ def test_sampled_rows_against_dense_brute_force():
         assert np.all(np.diff(cols) > 0)
         dense_row = np.zeros(n, np.float32); dense_row[cols] = vals
         assert np.array_equal(dense_row, B[i])
+
+
+def distinct_edges(n, e, seed):
+    r = np.random.default_rng(seed)
+    pairs = {(min(u, v), max(u, v)) for u, v in zip(r.integers(0, n, e).tolist(), r.integers(0, n, e).tolist()) if u != v}
+    return np.array([p[0] for p in pairs]), np.array([p[1] for p in pairs])
+
+
+def test_sampled_adjacency_rows_against_dense_brute_force():
+    from oracle import sampled as osampled
+    n = 41
+    src, dst = distinct_edges(n, 90, 8)
+    A, d = odense.dense_adjacency(n, src, dst)
+    rows = osampled.adjacency_rows(n, src, dst, osampled.degrees(n, src, dst), np.array([0, 5, 17, 40]))
+    for u, (ids, vals) in rows.items():
+        dense_row = np.zeros(n); dense_row[ids] = vals
+        assert np.array_equal(ids, np.nonzero(A[u])[0])
+        assert np.allclose(dense_row, A[u], rtol=1e-15, atol=0)
+
+
+@pytest.mark.parametrize("dims", [(5, 6, 3), (4, 7, 5, 3)])
+def test_network_on_samples_equals_the_whole_graph_network(dims):
+    """oracle.sampled.network_on_samples (the network evaluated on the receptive field of a few nodes, used at
+    full size) against the dense brute force on the whole graph with the same loss gradient: logits on the
+    samples, dW of every layer, dF0 on the field, zero dF0 outside it."""
+    from oracle import sampled as osampled
+    n = 60
+    src, dst = distinct_edges(n, 55, 3)                       # sparse: the field of 4 nodes is not the whole graph
+    r = np.random.default_rng(11)
+    F0 = r.standard_normal((n, dims[0]))
+    Ws = [r.standard_normal((dims[l], dims[l + 1])) * 0.5 for l in range(len(dims) - 1)]
+    nodes = np.array([3, 31, 32, 58])
+    g = r.standard_normal((len(nodes), dims[-1]))
+    V, logits, dW, dF0, Q = osampled.network_on_samples(n, src, dst, osampled.degrees(n, src, dst), lambda ids: F0[ids], Ws, nodes, g)
+    assert len(V[-1]) < n
+    # the whole graph, dense numpy: forward, then Eq. 2.4-2.7 from the same gradient
+    A, _ = odense.dense_adjacency(n, src, dst)
+    F, Hs, Qs = F0, [], []
+    for l, W in enumerate(Ws):
+        Hs.append(A @ F); Qs.append(Hs[l] @ W)
+        F = np.maximum(Qs[l], 0.0)
+    dQ = np.zeros((n, dims[-1])); dQ[nodes] = g
+    for l in range(len(Ws) - 1, -1, -1):
+        if l + 1 < len(Ws):
+            dQ = dF * (Qs[l] > 0)
+        assert np.allclose(dW[l], Hs[l].T @ dQ, rtol=1e-11, atol=1e-13), l
+        dF = A.T @ (dQ @ Ws[l].T)
+    assert np.allclose(logits, Qs[-1][nodes], rtol=1e-12, atol=1e-13)
+    assert np.allclose(dF0, dF[V[-1]], rtol=1e-11, atol=1e-14)
+    outside = np.setdiff1d(np.arange(n), V[-1])
+    assert np.all(dF[outside] == 0.0)
+    assert np.allclose(Q[0], Qs[0][V[len(Ws) - 1]], rtol=1e-12, atol=1e-13)
+
+
+def test_backward_with_given_masks():
+    """masks = [Q > 0] reproduces the plain backward pass; a flipped entry changes exactly what a finite difference of
+    the correspondingly modified activation function gives (here: checked through the dense form)."""
+    n, src, dst, F0, Ws, y = tiny_problem()
+    adj = oracle.adjacency(n, src, dst)
+    t = ogcn.forward_backward(adj, F0, Ws, y)
+    masks = [(q > 0) for q in t.Q[:-1]] + [None]
+    t2 = ogcn.forward_backward(adj, F0, Ws, y, masks=masks)
+    for a, b in zip(t.dW + [t.dF[0]], t2.dW + [t2.dF[0]]):
+        assert np.array_equal(a, b)
+    flipped = [m.copy() for m in masks[:-1]] + [None]
+    flipped[0][2, 1] = ~flipped[0][2, 1]
+    t3 = ogcn.forward_backward(adj, F0, Ws, y, masks=flipped)
+    A, _ = odense.dense_adjacency(n, src, dst)
+    # dense reference with the same decisions
+    F, Hs, Qs = F0, [], []
+    for l, W in enumerate(Ws):
+        Hs.append(A @ F); Qs.append(Hs[l] @ W); F = np.maximum(Qs[l], 0.0)
+    e = np.exp(Qs[-1] - Qs[-1].max(axis=1, keepdims=True)); p = e / e.sum(axis=1, keepdims=True)
+    dQ = p.copy(); dQ[np.arange(n), y] -= 1.0; dQ /= n
+    for l in range(len(Ws) - 1, -1, -1):
+        if l + 1 < len(Ws):
+            dQ = dF * flipped[l]
+        assert np.allclose(t3.dW[l], Hs[l].T @ dQ, rtol=1e-11, atol=1e-14)
+        dF = A.T @ (dQ @ Ws[l].T)
+    assert not np.allclose(t3.dW[0], t.dW[0], rtol=1e-9, atol=0)
