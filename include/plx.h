@@ -91,9 +91,10 @@ PLX_API plx_status plx_ctx_set_column_windows(plx_ctx* ctx, int n_windows);
  * pipe.  By default (on != 0) they are computed through the bf16 matrix instructions instead: every
  * fp32 operand is the exact sum of three bf16 numbers, and six of the nine bf16 products (all terms
  * down to 2^-23 of the product, i.e. fp32 rounding) are accumulated in fp32, 2.7 times faster than
- * the fp32 instructions.  Results agree with the plain fp32 path to fp32 rounding but not bit for
- * bit; an infinite input, or a finite one within 0.4 % of the largest fp32 value (its leading bf16
- * part rounds to infinity), turns into NaN.  on == 0 selects the plain fp32 instructions everywhere. */
+ * the fp32 instructions.  For finite inputs of any magnitude the results agree with the plain fp32 path
+ * to fp32 rounding, but not bit for bit.  An infinite or NaN input makes every result that depends on it
+ * NaN (the fp32 instructions give +-infinity where no opposite infinity or zero factor meets it): the
+ * same results are non-finite in both paths.  on == 0 selects the plain fp32 instructions everywhere. */
 PLX_API plx_status plx_ctx_set_split_products(plx_ctx* ctx, int on);
 PLX_API plx_status plx_sync(plx_ctx* ctx);                /* wait for the context's stream */
 
@@ -118,8 +119,9 @@ PLX_API plx_status plx_timing_trace(plx_ctx* ctx, char* buf, size_t buf_bytes);
  * stores  A_fwd = P_r A^ P_c^T  and  A_bwd = A_fwd^T = P_c A^ P_r^T, both as CSR with strictly
  * ascending columns inside a row, plus the degrees in original id order.
  * Errors: PLX_ERR_INVALID for an id outside [0,n) or a permutation that is not a bijection
- * (detected on the GPU; the call waits for that answer); n >= 2^31 or more than 2^31-1 stored
- * entries is PLX_ERR_UNSUPPORTED. */
+ * (detected on the GPU; the call waits for that answer); n >= 2^31, or 2 n_edges + n >= 2^31 (the
+ * candidate entries before duplicates are dropped: both directions of every listed edge plus the
+ * self-loops; an upper bound on the stored entries), is PLX_ERR_UNSUPPORTED. */
 PLX_API plx_status plx_build_csr(plx_ctx* ctx, int64_t n, int64_t n_edges, const int64_t* src, const int64_t* dst,
                                  const int64_t* perm_r, const int64_t* perm_c, plx_csr** out);
 
@@ -334,6 +336,20 @@ PLX_API plx_status plx_gcn_layer_bwd_chained(plx_ctx* ctx, const plx_csr* csr, i
                                              const void* saved, int64_t ldsaved,
                                              int64_t din, int64_t dout, plx_dtype dtype, plx_act act, plx_order order,
                                              void* dH, int64_t lddh, float* dW, int64_t lddw, void* ws, size_t ws_bytes);
+
+/* What a sequencer of several layers should ask of the calls above for one layer, so that it holds no copy of the
+ * kernels' shape limits.  The layer is din -> dout in `order`; dn > 0 is the output width of a following layer that
+ * runs in `next_order` (dn == 0: no following layer, or it is not to be paired); keep_values != 0 says the caller
+ * keeps the ReLU mask as a value matrix (PLX_ACT_RELU) whatever is possible.  Host outputs (any may be NULL):
+ *   agg_first: the order PLX_ORDER_AUTO / `order` resolves to is aggregate-first;
+ *   sign_bits: PLX_ACT_RELU_BITS is worth using (the layer's own dense kernels write the bits on the fly);
+ *   chain_fwd: plx_gcn_layer_fwd_chained + plx_gcn_layer_fwd_from_t form T = F Wn inside this layer's product;
+ *   chain_bwd: plx_gcn_layer_bwd_dt + plx_gcn_layer_bwd_chained form the gradient inside this layer's fused kernel.
+ * The answers depend on the context's split-product switch and assume 16-byte aligned rows.  PLX_ERR_INVALID for a
+ * NULL context, non-positive widths or unknown enums. */
+PLX_API plx_status plx_gcn_layer_plan(const plx_ctx* ctx, int64_t din, int64_t dout, int64_t dn, plx_dtype dtype,
+                                      plx_order order, plx_order next_order, int keep_values, int* agg_first,
+                                      int* sign_bits, int* chain_fwd, int* chain_bwd);
 
 #ifdef __cplusplus
 }

@@ -23,7 +23,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "plx_oracle.c")
-_SO = os.path.join(_HERE, "libplx_oracle.so")
+# PLX_ORACLE_SANITIZE=1: an AddressSanitizer + UndefinedBehaviorSanitizer build of the same source, kept beside the
+# plain one (the process must then run with the ASan runtime preloaded; tests/test_oracle_sanitized.py does that)
+_SANITIZE = os.environ.get("PLX_ORACLE_SANITIZE", "") == "1"
+_SO = os.path.join(_HERE, "libplx_oracle_san.so" if _SANITIZE else "libplx_oracle.so")
 
 _i64p = ctypes.POINTER(ctypes.c_int64)
 _i32p = ctypes.POINTER(ctypes.c_int32)
@@ -37,6 +40,8 @@ def build(force: bool = False) -> str:
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-ffp-contract=off",
                "-fvisibility=hidden", "-o", _SO, _SRC, "-lm"]
+        if _SANITIZE:
+            cmd[1:2] = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=all"]
         subprocess.check_call(cmd)
     return _SO
 

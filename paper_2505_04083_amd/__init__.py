@@ -29,7 +29,7 @@ EXPORTED = [
     "plx_relu", "plx_relu_bwd", "plx_softmax_ce",
     "plx_gcn_layer_workspace", "plx_gcn_layer_fwd", "plx_gcn_layer_bwd",
     "plx_gcn_layer_bwd_dt", "plx_gcn_layer_bwd_chained_workspace", "plx_gcn_layer_bwd_chained",
-    "plx_gcn_layer_fwd_chained", "plx_gcn_layer_fwd_from_t",
+    "plx_gcn_layer_fwd_chained", "plx_gcn_layer_fwd_from_t", "plx_gcn_layer_plan",
 ]
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
@@ -83,6 +83,8 @@ def _load() -> ctypes.CDLL:
         "plx_gcn_layer_fwd_from_t": (_int, [_vp, _vp, _int, _vp, _i64, _i64, _int, _int, _vp, _i64, _vp, _i64]),
         "plx_gcn_layer_bwd_dt": (_int, [_vp, _vp, _int, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _int, _int,
                                         _vp, _i64, _vp, _i64, _vp, _sz]),
+        "plx_gcn_layer_plan": (_int, [_vp, _i64, _i64, _i64, _int, _int, _int, _int, ctypes.POINTER(_int), ctypes.POINTER(_int),
+                                      ctypes.POINTER(_int), ctypes.POINTER(_int)]),
         "plx_gcn_layer_bwd_chained_workspace": (_sz, [_vp, _vp, _int, _i64, _i64, _i64, _int, _int, _int]),
         "plx_gcn_layer_bwd_chained": (_int, [_vp, _vp, _int, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64,
                                              _vp, _i64, _i64, _i64, _int, _int, _int, _vp, _i64, _vp, _i64, _vp, _sz]),
@@ -119,6 +121,28 @@ def _mat(t: Optional[torch.Tensor]) -> Tuple[Optional[int], int]:
         raise ValueError("expected a row-major 2-D tensor")
     ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0))
     return t.data_ptr(), int(ld)
+
+
+def _check(ctx: "plx_ctx", name: str, t: Optional[torch.Tensor], rows: int, cols: int, dtype=None) -> None:
+    """The C ABI sees pointers and leading dimensions only: that the memory behind them is on the context's GPU, of
+    the element type the call says and large enough is checked here, before the call (ValueError / TypeError)."""
+    if t is None:
+        return
+    if ctx.device >= 0 and (not t.is_cuda or t.device.index != ctx.device):
+        raise ValueError(f"{name}: tensor on {t.device}, the context runs on cuda:{ctx.device}")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if t.dim() != 2 or t.shape[0] < rows or t.shape[1] < cols:
+        raise ValueError(f"{name}: shape {tuple(t.shape)} smaller than the {rows} x {cols} the call addresses")
+
+
+def _check_ws(ctx: "plx_ctx", ws: Optional[torch.Tensor]) -> None:
+    if ws is None:
+        return
+    if ctx.device >= 0 and (not ws.is_cuda or ws.device.index != ctx.device):
+        raise ValueError(f"workspace on {ws.device}, the context runs on cuda:{ctx.device}")
+    if ws.dtype != torch.uint8 or not ws.is_contiguous():
+        raise TypeError("the workspace is a contiguous uint8 tensor")
 
 
 def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
@@ -305,6 +329,8 @@ def plx_spmm_block(ctx: plx_ctx, csr: plx_csr, transposed: bool, block: int, X: 
     yp, ldy = _mat(Y)
     if d is None:
         d = X.shape[1]
+    rows, cols = csr.shape(transposed)
+    _check(ctx, "X", X, cols, d); _check(ctx, "Y", Y, rows, d, X.dtype)
     ctx.check(_lib.plx_spmm_block(ctx.handle, csr.handle, int(transposed), block, xp, ldx, yp, ldy, d, _dtype_code(X)))
     return Y
 
@@ -314,6 +340,8 @@ def _spmm(fn, ctx, csr, X, Y, d):
     yp, ldy = _mat(Y)
     if d is None:
         d = X.shape[1]
+    rows, cols = csr.shape(fn is _lib.plx_spmm_t)
+    _check(ctx, "X", X, cols, d); _check(ctx, "Y", Y, rows, d, X.dtype)
     ctx.check(fn(ctx.handle, csr.handle, xp, ldx, yp, ldy, d, _dtype_code(X)))
     return Y
 
@@ -335,6 +363,8 @@ def plx_spmm_static(ctx: plx_ctx, csr: plx_csr, transposed: bool, X: torch.Tenso
     yp, ldy = _mat(Y)
     if d is None:
         d = X.shape[1]
+    rows, cols = csr.shape(transposed)
+    _check(ctx, "X", X, cols, d); _check(ctx, "Y", Y, rows, d, X.dtype)
     ctx.check(_lib.plx_spmm_static(ctx.handle, csr.handle, int(transposed), xp, ldx, yp, ldy, d, _dtype_code(X)))
     return Y
 
@@ -342,6 +372,8 @@ def plx_spmm_static(ctx: plx_ctx, csr: plx_csr, transposed: bool, X: torch.Tenso
 def plx_gemm_nn(ctx: plx_ctx, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor) -> torch.Tensor:
     """C[M x N] = A[M x K] B[K x N]; B fp32."""
     (ap, lda), (bp, ldb), (cp, ldc) = _mat(A), _mat(B), _mat(C)
+    _check(ctx, "B", B, A.shape[1], B.shape[1], torch.float32); _check(ctx, "A", A, A.shape[0], A.shape[1])
+    _check(ctx, "C", C, A.shape[0], B.shape[1], A.dtype)
     ctx.check(_lib.plx_gemm_nn(ctx.handle, A.shape[0], B.shape[1], A.shape[1], ap, lda, bp, ldb, cp, ldc, _dtype_code(A)))
     return C
 
@@ -349,6 +381,8 @@ def plx_gemm_nn(ctx: plx_ctx, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor)
 def plx_gemm_nt(ctx: plx_ctx, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor) -> torch.Tensor:
     """C[M x N] = A[M x K] B[N x K]^T; B fp32."""
     (ap, lda), (bp, ldb), (cp, ldc) = _mat(A), _mat(B), _mat(C)
+    _check(ctx, "B", B, B.shape[0], A.shape[1], torch.float32); _check(ctx, "A", A, A.shape[0], A.shape[1])
+    _check(ctx, "C", C, A.shape[0], B.shape[0], A.dtype)
     ctx.check(_lib.plx_gemm_nt(ctx.handle, A.shape[0], B.shape[0], A.shape[1], ap, lda, bp, ldb, cp, ldc, _dtype_code(A)))
     return C
 
@@ -361,6 +395,7 @@ def plx_gemm_tn(ctx: plx_ctx, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor,
     """C[M x N] (fp32) = A[R x M]^T B[R x N]."""
     (ap, lda), (bp, ldb), (cp, ldc) = _mat(A), _mat(B), _mat(C)
     R, M, N = A.shape[0], A.shape[1], B.shape[1]
+    _check(ctx, "A", A, R, M); _check(ctx, "B", B, R, N, A.dtype); _check(ctx, "C", C, M, N, torch.float32); _check_ws(ctx, ws)
     if ws is None:
         ws = torch.empty(max(1, plx_gemm_tn_workspace(R, M, N)), dtype=torch.uint8, device=A.device)
     ctx.check(_lib.plx_gemm_tn(ctx.handle, R, M, N, ap, lda, bp, ldb, cp, ldc, _dtype_code(A), ws.data_ptr(), ws.numel()))
@@ -369,12 +404,15 @@ def plx_gemm_tn(ctx: plx_ctx, A: torch.Tensor, B: torch.Tensor, C: torch.Tensor,
 
 def plx_relu(ctx: plx_ctx, Z: torch.Tensor, F: torch.Tensor) -> torch.Tensor:
     (zp, ldz), (fp, ldf) = _mat(Z), _mat(F)
+    _check(ctx, "Z", Z, Z.shape[0], Z.shape[1]); _check(ctx, "F", F, Z.shape[0], Z.shape[1], Z.dtype)
     ctx.check(_lib.plx_relu(ctx.handle, Z.shape[0], Z.shape[1], zp, ldz, fp, ldf, _dtype_code(Z)))
     return F
 
 
 def plx_relu_bwd(ctx: plx_ctx, Z: torch.Tensor, dF: torch.Tensor, dZ: torch.Tensor) -> torch.Tensor:
     (zp, ldz), (gp, ldg), (op, ldo) = _mat(Z), _mat(dF), _mat(dZ)
+    _check(ctx, "Z", Z, Z.shape[0], Z.shape[1]); _check(ctx, "dF", dF, Z.shape[0], Z.shape[1], Z.dtype)
+    _check(ctx, "dZ", dZ, Z.shape[0], Z.shape[1], Z.dtype)
     ctx.check(_lib.plx_relu_bwd(ctx.handle, Z.shape[0], Z.shape[1], zp, ldz, gp, ldg, op, ldo, _dtype_code(Z)))
     return dZ
 
@@ -384,9 +422,40 @@ def plx_softmax_ce(ctx: plx_ctx, Z: torch.Tensor, y: torch.Tensor, dZ: torch.Ten
     (zp, ldz), (gp, ldg) = _mat(Z), _mat(dZ)
     if row_loss is None:
         row_loss = torch.empty(max(1, Z.shape[0]), dtype=torch.float32, device=Z.device)
+    _check(ctx, "Z", Z, Z.shape[0], Z.shape[1]); _check(ctx, "dZ", dZ, Z.shape[0], Z.shape[1], Z.dtype)
+    for name, t, count in (("y", y, Z.shape[0]), ("row_loss", row_loss, Z.shape[0]), ("loss", loss, 1)):
+        if t is not None and (t.numel() < count or (ctx.device >= 0 and (not t.is_cuda or t.device.index != ctx.device))):
+            raise ValueError(f"{name}: {t.numel()} elements on {t.device}, the call needs {count} on the context's GPU")
     ctx.check(_lib.plx_softmax_ce(ctx.handle, Z.shape[0], Z.shape[1], zp, ldz, _ptr(y, torch.int64), gp, ldg,
                                   _ptr(row_loss, torch.float32), _ptr(loss, torch.float32), _dtype_code(Z)))
     return dZ
+
+
+def plx_gcn_layer_plan(ctx: plx_ctx, din: int, dout: int, dn: int = 0, dtype: int = PLX_F32, order: int = PLX_ORDER_AUTO,
+                       next_order: int = PLX_ORDER_AUTO, keep_values: bool = False):
+    """(agg_first, sign_bits, chain_fwd, chain_bwd) for a layer din -> dout followed (dn > 0) by a layer dout -> dn."""
+    out = [_int() for _ in range(4)]
+    ctx.check(_lib.plx_gcn_layer_plan(ctx.handle, din, dout, dn, dtype, order, next_order, int(keep_values),
+                                      *[ctypes.byref(o) for o in out]))
+    return tuple(bool(o.value) for o in out)
+
+
+def _check_layer(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, din: int, dout: int, tdt, act: int, order: int, dn: int = 0,
+                 **ops) -> None:
+    """Every tensor of a layer call against the shapes the handle and the widths imply (see _check)."""
+    ma, ka = csr.shape(transposed_A)
+    agg = plx_gcn_layer_plan(ctx, din, dout, 0, PLX_F32 if tdt == torch.float32 else PLX_BF16, order)[0] if din > 0 and dout > 0 else True
+    spec = {"H": (ka, din, tdt), "W": (din, dout, torch.float32), "F": (ma, dout, tdt), "dF": (ma, dout, tdt),
+            "saved": (ma if agg else 0, din if agg else 0, tdt), "dH": (ka, din, tdt), "dW": (din, dout, torch.float32),
+            "dT": (ka, dout, tdt), "T": (ka, dout, tdt), "Wn": (dout, dn, torch.float32), "Tn": (ma, dn, tdt), "dTn": (ma, dn, tdt),
+            "Z": (ma, (dout + 31) // 32, torch.int32) if act == PLX_ACT_RELU_BITS else (ma, dout, tdt)}
+    for name, t in ops.items():
+        if name == "ws":
+            _check_ws(ctx, t)
+        elif name == "Z" and act == PLX_ACT_RELU and t is not None:       # only the sign is read: any matrix of the layer's type
+            _check(ctx, name, t, ma, dout, tdt)
+        else:
+            _check(ctx, name, t, *spec[name])
 
 
 def plx_gcn_layer_workspace(csr: plx_csr, transposed_A: bool, din: int, dout: int, dtype: int = PLX_F32,
@@ -399,6 +468,7 @@ def plx_gcn_layer_fwd(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, H: torch.T
                       act: int = PLX_ACT_RELU, order: int = PLX_ORDER_AUTO) -> None:
     (hp, ldh), (wp, ldw), (zp, ldz), (fp, ldf), (sp, lds) = _mat(H), _mat(W), _mat(Z), _mat(F), _mat(saved)
     din, dout = W.shape
+    _check_layer(ctx, csr, transposed_A, din, dout, H.dtype, act, order, H=H, W=W, Z=Z, F=F, saved=saved, ws=ws)
     ctx.check(_lib.plx_gcn_layer_fwd(ctx.handle, csr.handle, int(transposed_A), hp, ldh, wp, ldw, din, dout,
                                      _dtype_code(H), act, order, zp, ldz, fp, ldf, sp, lds,
                                      None if ws is None else ws.data_ptr(), 0 if ws is None else ws.numel()))
@@ -411,6 +481,7 @@ def plx_gcn_layer_bwd(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, H: Optiona
     (hp, ldh), (wp, ldw), (zp, ldz), (gp, ldg), (sp, lds) = _mat(H), _mat(W), _mat(Z), _mat(dF), _mat(saved)
     (dhp, lddh), (dwp, lddw) = _mat(dH), _mat(dW)
     din, dout = W.shape
+    _check_layer(ctx, csr, transposed_A, din, dout, dF.dtype, act, order, H=H, W=W, Z=Z, dF=dF, saved=saved, dH=dH, dW=dW, ws=ws)
     ctx.check(_lib.plx_gcn_layer_bwd(ctx.handle, csr.handle, int(transposed_A), hp, ldh, wp, ldw, zp, ldz, gp, ldg,
                                      sp, lds, din, dout, _dtype_code(dF), act, order, dhp, lddh, dwp, lddw,
                                      ws.data_ptr(), ws.numel()))
@@ -422,6 +493,7 @@ def plx_gcn_layer_bwd_dt(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, H: torc
     """Combine-first backward up to dT = A^T (dF * [Z > 0]) and dW = H^T dT; dH = dT W^T is left to the consumer."""
     (hp, ldh), (zp, ldz), (gp, ldg), (tp, ldt), (dwp, lddw) = _mat(H), _mat(Z), _mat(dF), _mat(dT), _mat(dW)
     din, dout = dW.shape
+    _check_layer(ctx, csr, transposed_A, din, dout, dF.dtype, act, PLX_ORDER_COMBINE_FIRST, H=H, Z=Z, dF=dF, dT=dT, dW=dW, ws=ws)
     ctx.check(_lib.plx_gcn_layer_bwd_dt(ctx.handle, csr.handle, int(transposed_A), hp, ldh, zp, ldz, gp, ldg, din, dout,
                                         _dtype_code(dF), act, tp, ldt, dwp, lddw, ws.data_ptr(), ws.numel()))
 
@@ -439,6 +511,8 @@ def plx_gcn_layer_bwd_chained(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, H:
     (hp, ldh), (wp, ldw), (zp, ldz), (gp, ldg), (wnp, ldwn), (sp, lds) = _mat(H), _mat(W), _mat(Z), _mat(dTn), _mat(Wn), _mat(saved)
     (dhp, lddh), (dwp, lddw) = _mat(dH), _mat(dW)
     din, dout = W.shape
+    _check_layer(ctx, csr, transposed_A, din, dout, dTn.dtype, act, order, Wn.shape[1], H=H, W=W, Z=Z, dTn=dTn, Wn=Wn, saved=saved,
+                 dH=dH, dW=dW, ws=ws)
     ctx.check(_lib.plx_gcn_layer_bwd_chained(ctx.handle, csr.handle, int(transposed_A), hp, ldh, wp, ldw, zp, ldz, gp, ldg,
                                              wnp, ldwn, Wn.shape[1], sp, lds, din, dout, _dtype_code(dTn), act, order,
                                              dhp, lddh, dwp, lddw, ws.data_ptr(), ws.numel()))
@@ -452,6 +526,8 @@ def plx_gcn_layer_fwd_chained(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, H:
     (hp, ldh), (wp, ldw), (zp, ldz), (fp, ldf), (sp, lds) = _mat(H), _mat(W), _mat(Z), _mat(F), _mat(saved)
     (wnp, ldwn), (tp, ldt) = _mat(Wn), _mat(Tn)
     din, dout = W.shape
+    _check_layer(ctx, csr, transposed_A, din, dout, H.dtype, act, order, Wn.shape[1], H=H, W=W, Z=Z, F=F, saved=saved, Wn=Wn, Tn=Tn,
+                 ws=ws)
     ctx.check(_lib.plx_gcn_layer_fwd_chained(ctx.handle, csr.handle, int(transposed_A), hp, ldh, wp, ldw, din, dout,
                                              _dtype_code(H), act, order, zp, ldz, fp, ldf, sp, lds, wnp, ldwn, Wn.shape[1], tp, ldt,
                                              None if ws is None else ws.data_ptr(), 0 if ws is None else ws.numel()))
@@ -461,5 +537,6 @@ def plx_gcn_layer_fwd_from_t(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, T: 
                              F: Optional[torch.Tensor], act: int = PLX_ACT_RELU) -> None:
     """Z = A T, F = act(Z): a combine-first layer whose T = H W already exists."""
     (tp, ldt), (zp, ldz), (fp, ldf) = _mat(T), _mat(Z), _mat(F)
+    _check_layer(ctx, csr, transposed_A, T.shape[1], T.shape[1], T.dtype, act, PLX_ORDER_COMBINE_FIRST, T=T, Z=Z, F=F)
     ctx.check(_lib.plx_gcn_layer_fwd_from_t(ctx.handle, csr.handle, int(transposed_A), tp, ldt, T.shape[1], _dtype_code(T), act,
                                             zp, ldz, fp, ldf))

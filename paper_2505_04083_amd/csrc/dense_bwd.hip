@@ -391,7 +391,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_BWD_
                     if (n + 3 < N) v.w = wp[3];
                 }
                 uint2 pl[3];
-                split3(v, pl);
+                split3<true>(v, pl);
 #pragma unroll
                 for (int p = 0; p < 3; ++p) { f[p].x[2 * h] = pl[p].x; f[p].x[2 * h + 1] = pl[p].y; }
             }
@@ -444,7 +444,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_BWD_
                     if (k + 3 < dn) v.w = wp[3];
                 }
                 uint2 pl[3];
-                split3(v, pl);
+                split3<true>(v, pl);
 #pragma unroll
                 for (int p = 0; p < 3; ++p) { f[p].x[2 * h] = pl[p].x; f[p].x[2 * h + 1] = pl[p].y; }
                 goff[s2][h] = k < dn ? (uint32_t)(((uint32_t)l32 * (uint32_t)ldg + k) * 4u) : kOutOfRange;

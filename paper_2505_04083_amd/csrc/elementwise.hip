@@ -224,6 +224,14 @@ __global__ __launch_bounds__(256) void k_sum_level(float* v, int64_t n_live, int
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+// rows x cols elements of `bytes_per_elt` bytes each set to zero (a kernel, not a memset: memset nodes recorded
+// into a HIP graph have replayed wrongly on this platform)
+__global__ __launch_bounds__(256) void k_zero(int64_t rows, int64_t row_bytes, unsigned char* p, int64_t pitch_bytes) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= row_bytes) return;
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) p[r * pitch_bytes + b] = 0;
+}
+
 dim3 grid2d(int64_t rows, int64_t cols) {
     unsigned gx = (unsigned)ceil_div(cols, 256);
     unsigned gy = (unsigned)std::min<int64_t>(rows, std::max<int64_t>(1, 65535));
@@ -265,6 +273,15 @@ plx_status relu_bwd_t(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, i
 }
 
 }  // namespace
+
+plx_status launch_zero(plx_ctx* ctx, int64_t rows, int64_t cols, void* p, int64_t ld, size_t elt_bytes) {
+    if (rows <= 0 || cols <= 0 || !p) return PLX_OK;
+    const int64_t row_bytes = cols * (int64_t)elt_bytes;
+    dim3 grid((unsigned)ceil_div(row_bytes, 256), (unsigned)std::min<int64_t>(rows, 65535));
+    k_zero<<<grid, 256, 0, ctx->stream>>>(rows, row_bytes, static_cast<unsigned char*>(p), ld * (int64_t)elt_bytes);
+    PLX_HIP(ctx, hipGetLastError());
+    return PLX_OK;
+}
 
 plx_status launch_relu(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, void* F, int64_t ldf,
                        plx_dtype dtype) {
@@ -310,8 +327,7 @@ plx_status launch_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, 
                              int64_t lddz, float* row_loss, float* loss, plx_dtype dtype) {
     hipStream_t s = ctx->stream;
     if (n == 0) {
-        if (loss) PLX_HIP(ctx, hipMemsetAsync(loss, 0, sizeof(float), s));
-        return PLX_OK;
+        return launch_zero(ctx, 1, 1, loss, 1, sizeof(float));
     }
     const float inv_n = (float)(1.0 / (double)n);
     char label[64];

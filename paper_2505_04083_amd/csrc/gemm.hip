@@ -695,7 +695,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_FWD_
                     x[e] = (kk < K && n < N) ? B[(int64_t)kk * ldb + n] : 0.f;
                 }
                 uint2 pl[3];
-                split3(make_float4(x[0], x[1], x[2], x[3]), pl);
+                split3<true>(make_float4(x[0], x[1], x[2], x[3]), pl);
 #pragma unroll
                 for (int p = 0; p < 3; ++p) { f[p].x[2 * h] = pl[p].x; f[p].x[2 * h + 1] = pl[p].y; }
             }

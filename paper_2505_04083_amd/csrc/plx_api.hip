@@ -509,6 +509,17 @@ plx_status layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const v
         return fail(ctx, PLX_ERR_SHAPE, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, w.total);
     if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
 
+    if (a.rows == 0) return PLX_OK;          // no output rows
+    if (a.cols == 0 || a.nnz == 0) {
+        // an adjacency without entries: every output is zero (A H = 0, ReLU(0) = 0, sign bits 0, F Wn = 0)
+        const size_t es = elt_size(dtype);
+        if (order == PLX_ORDER_AGG_FIRST) PLX_TRY(launch_zero(ctx, a.rows, din, saved, ldsaved, es));
+        if (sign_bits) PLX_TRY(launch_zero(ctx, a.rows, (dout + 31) / 32, Z, ldz, sizeof(uint32_t)));
+        else PLX_TRY(launch_zero(ctx, a.rows, dout, Z, ldz, es));
+        PLX_TRY(launch_zero(ctx, a.rows, dout, F, ldf, es));
+        PLX_TRY(launch_zero(ctx, a.rows, var.dn, var.Tn, var.ldtn, es));
+        return PLX_OK;
+    }
     // The last product of the layer stores the pre-activation (if wanted) and the activated
     // output (Eq. 2.3) from the same registers.
     void* plain = sign_bits ? nullptr : Z;
@@ -650,7 +661,7 @@ plx_status layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const v
     LayerWs w = layer_ws(a, din, dout, dtype, act, order);
     const void* mask = act != PLX_ACT_NONE ? Z : nullptr;
     // the fused kernels address a tile with 31-bit byte offsets; wider leading dimensions take the separate products
-    const int64_t ld_max = std::max(std::max(ldsaved, ldh), std::max(std::max(lddf, ldz), lddh));
+    const int64_t ld_max = std::max(std::max(std::max(ldsaved, ldh), std::max(std::max(lddf, ldz), lddh)), std::max(var.lddt, var.ldgn));
     const bool fused = bwd_dense_supported(din, dout, dtype) && (ld_max < (int64_t(1) << 23) || dtype == PLX_BF16);
     // factors: does the fused kernel form dF itself, or is it formed once behind the layer workspace?
     const bool in_kernel = var.Gn && fused && order == PLX_ORDER_AGG_FIRST &&
@@ -661,6 +672,13 @@ plx_status layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const v
         return fail(ctx, PLX_ERR_SHAPE, "workspace of %zu bytes is smaller than the %zu needed", ws_bytes, need);
     if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
 
+    if (a.nnz == 0) {
+        // an adjacency without entries (or without rows or columns): A H = 0 and A^T dZ = 0, so every gradient is zero
+        PLX_TRY(launch_zero(ctx, din, dout, dW, lddw, sizeof(float)));
+        PLX_TRY(launch_zero(ctx, a.cols, din, dH, lddh, elt_size(dtype)));
+        PLX_TRY(launch_zero(ctx, a.cols, dout, var.dT, var.lddt, elt_size(dtype)));
+        return PLX_OK;
+    }
     char* base = static_cast<char*>(ws);
     void* tn_ws = base + w.off_tn;
     size_t tn_bytes = w.total - w.off_tn;
@@ -750,6 +768,31 @@ plx_status plx_gcn_layer_bwd_dt(plx_ctx* ctx, const plx_csr* csr, int transposed
     var.dT = dT; var.lddt = lddt;
     return layer_bwd(ctx, csr, transposed_A, H, ldh, nullptr, dout, Z, ldz, dF, lddf, nullptr, 0, din, dout, dtype, act,
                      PLX_ORDER_COMBINE_FIRST, nullptr, 0, dW, lddw, ws, ws_bytes, var);
+}
+
+plx_status plx_gcn_layer_plan(const plx_ctx* ctx, int64_t din, int64_t dout, int64_t dn, plx_dtype dtype, plx_order order,
+                              plx_order next_order, int keep_values, int* agg_first, int* sign_bits, int* chain_fwd,
+                              int* chain_bwd) {
+    if (!ctx) return PLX_ERR_INVALID;
+    if (din <= 0 || dout <= 0 || dn < 0 || !dtype_ok(dtype) || (int)order < 0 || (int)order > 2 || (int)next_order < 0 ||
+        (int)next_order > 2)
+        return PLX_ERR_INVALID;
+    const bool agg = resolve_order(order, din, dout) == PLX_ORDER_AGG_FIRST;
+    // the dense kernels of an aggregate-first layer of widths up to 128 pack the sign of their result while they write it
+    const bool bits = !keep_values && agg && din <= 128 && dout <= 128;
+    // a following combine-first layer starts with a product over this layer's output rows and ends with one: both can
+    // run inside this layer's dense kernels (16-byte aligned rows are the caller's to provide: the calls fall back to
+    // separate products otherwise).  One 16-column step of dn only: wider factors were measured slower than the matrix
+    // they avoid.
+    const bool pair = dn > 0 && dn <= 16 && agg && resolve_order(next_order, dout, dn) == PLX_ORDER_COMBINE_FIRST;
+    const int64_t ld4 = 4;
+    if (agg_first) *agg_first = agg;
+    if (sign_bits) *sign_bits = bits;
+    if (chain_fwd) *chain_fwd = pair && gemm_next_supported(ctx, 1, dout, din, dn, dtype, nullptr, ld4, ld4, ld4, ld4);
+    if (chain_bwd) *chain_bwd = pair && bwd_dense_supported(din, dout, dtype) &&
+                                bwd_dense_factor_supported(ctx, 1, din, dout, dn, dtype, nullptr, ld4, nullptr, ld4, 0, 0,
+                                                           /*value_mask=*/keep_values != 0);
+    return PLX_OK;
 }
 
 size_t plx_gcn_layer_bwd_chained_workspace(const plx_ctx* ctx, const plx_csr* csr, int transposed_A, int64_t din, int64_t dout,

@@ -183,6 +183,8 @@ bool bwd_dense_factor_supported(const plx_ctx* ctx, int64_t R, int64_t Mp, int64
                                 int64_t ldp, const void* G, int64_t ldg, int64_t ldz, int64_t ldo, bool value_mask);
 plx_status launch_gemm_tn(plx_ctx* ctx, int64_t R, int64_t M, int64_t N, const void* A, int64_t lda,
                           const void* B, int64_t ldb, float* C, int64_t ldc, plx_dtype dtype, void* ws, size_t ws_bytes);
+// rows x cols elements of elt_bytes each set to zero by a kernel (p may be NULL: nothing happens)
+plx_status launch_zero(plx_ctx* ctx, int64_t rows, int64_t cols, void* p, int64_t ld, size_t elt_bytes);
 plx_status launch_relu(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, void* F, int64_t ldf,
                        plx_dtype dtype);
 plx_status launch_relu_bwd(plx_ctx* ctx, int64_t rows, int64_t cols, const void* Z, int64_t ldz, const void* dF,

@@ -17,7 +17,7 @@ import torch
 
 from . import (PLX_ACT_NONE, PLX_ACT_RELU, PLX_ACT_RELU_BITS, PLX_BF16, PLX_F32, PLX_ORDER_AUTO, plx_gcn_layer_bwd,
                plx_gcn_layer_bwd_chained, plx_gcn_layer_bwd_chained_workspace, plx_gcn_layer_bwd_dt, plx_gcn_layer_fwd,
-               plx_gcn_layer_fwd_chained, plx_gcn_layer_fwd_from_t, plx_gcn_layer_workspace, plx_softmax_ce, plx_sync)
+               plx_gcn_layer_fwd_chained, plx_gcn_layer_fwd_from_t, plx_gcn_layer_plan, plx_gcn_layer_workspace, plx_softmax_ce, plx_sync)
 
 
 def aligned_rows(rows: int, cols: int, dtype, dev) -> torch.Tensor:
@@ -40,28 +40,26 @@ class GcnNetwork:
         dev = Ws[0].device
         code = PLX_F32 if dtype == torch.float32 else PLX_BF16
         self.act = [PLX_ACT_RELU if l + 1 < self.L else PLX_ACT_NONE for l in range(self.L)]
-        agg = [order == 1 or (order == PLX_ORDER_AUTO and W.shape[0] <= W.shape[1]) for W in Ws]
-        for l, W in enumerate(Ws[:-1]):
-            din, dout = W.shape
-            if sign_bits and not keep_preactivation and agg[l] and max(din, dout) <= 128:
-                self.act[l] = PLX_ACT_RELU_BITS
-        # chained[l]: layer l+1 (combine-first) hands layer l its dT and W instead of the gradient matrix between them,
-        # taken where the fused backward kernel of layer l forms that gradient itself (the shapes the C header lists)
-        # in one 16-column step: measured on the road graph (64-128-16, 50 M nodes) the step costs layer l's kernel
-        # 3 % and saves layer l+1's kernel the 25.6 GB write of the gradient (10.5 -> 4.9 ms)
+        # Which layers keep their ReLU mask as sign bits, and which consecutive pairs are chained, is the library's answer
+        # (plx_gcn_layer_plan): the shape limits of the kernels are stated in one place, the C side.
+        #   chained[l]: layer l+1 (combine-first) hands layer l its dT and W instead of the gradient matrix between them,
+        #     which layer l's fused backward kernel then forms tile by tile (road graph, 64-128-16, 50 M nodes: the step costs
+        #     layer l's kernel 3 % and saves layer l+1's kernel the 25.6 GB write of the gradient, 10.5 -> 4.9 ms);
+        #   fwd_chained[l]: the product that writes layer l's output also forms T = F W of layer l+1, which then starts
+        #     from T instead of reading F back.
+        agg = []
         self.chained = [False] * self.L
-        for l in range(self.L - 1):
-            din, dout = Ws[l].shape
-            dn = Ws[l + 1].shape[1]
-            self.chained[l] = (chain and dtype == torch.float32 and agg[l] and not agg[l + 1] and 32 < din <= 128
-                               and 64 < dout <= 128 and dn <= 16 and self.act[l] != PLX_ACT_RELU)
-        # fwd_chained[l]: the product that writes layer l's output also forms T = F W of layer l+1 (combine-first), which then
-        # starts from T instead of reading F back; same shapes, any mask form
         self.fwd_chained = [False] * self.L
-        for l in range(self.L - 1):
-            din, dout = Ws[l].shape
-            self.fwd_chained[l] = (chain and dtype == torch.float32 and agg[l] and not agg[l + 1] and 32 < din <= 128
-                                   and din % 4 == 0 and 32 < dout <= 128 and Ws[l + 1].shape[1] <= 16)
+        for l, W in enumerate(Ws):
+            din, dout = W.shape
+            last = l + 1 == self.L
+            dn = 0 if (last or not chain) else Ws[l + 1].shape[1]
+            a, bits, cf, cb = plx_gcn_layer_plan(ctx, din, dout, dn, code, order, order,
+                                                 keep_values=keep_preactivation or not sign_bits or last)
+            agg.append(a)
+            if bits and not last:
+                self.act[l] = PLX_ACT_RELU_BITS
+            self.chained[l], self.fwd_chained[l] = cb, cf
         nbytes = 1
         for l, W in enumerate(Ws):
             if self.chained[l]:
@@ -115,7 +113,10 @@ class GcnNetwork:
 
     def backward(self, H0: torch.Tensor, y: torch.Tensor) -> None:
         plx_softmax_ce(self.ctx, self.Z[-1], y, self.dZ_last, row_loss=self.row_loss, loss=self.loss)
-        grad = self.dZ_last
+        self.backward_from(H0, self.dZ_last)
+
+    def backward_from(self, H0: torch.Tensor, grad: torch.Tensor) -> None:
+        """The backward calls of every layer for a given gradient with respect to the last layer's output."""
         for l in range(self.L - 1, -1, -1):
             h = H0 if l == 0 else self.F[l - 1]
             mask_src = None if self.act[l] == PLX_ACT_NONE else (self.Z[l] if self.Z[l] is not None else self.F[l])

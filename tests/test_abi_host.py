@@ -115,3 +115,89 @@ def test_dense_and_elementwise_argument_checks(dry):
     assert L.plx_ctx_set_split_products(None, 1) == plx.PLX_ERR_INVALID
     assert L.plx_csr_set_row_blocks(h, None, 4) == plx.PLX_ERR_INVALID
     assert L.plx_spmm_block(h, None, 0, 0, p, 4, p, 4, 4, 0) == plx.PLX_ERR_INVALID
+
+
+# ---- the binding's own checks: what the C side cannot see (device, element type, extent of a tensor) ------------
+
+class FakeHandle:
+    """Stands in for an adjacency handle: the binding reads only its shape before it validates the tensors."""
+    handle = None
+
+    def __init__(self, m, k):
+        self.m, self.k = m, k
+
+    def shape(self, transposed=False):
+        return (self.k, self.m) if transposed else (self.m, self.k)
+
+
+class OnGpu0:
+    """A context that claims GPU 0 (no call reaches the library with it)."""
+    device = 0
+    handle = None
+
+
+def test_binding_rejects_wrong_shaped_or_typed_tensors(dry):
+    csr = FakeHandle(10, 20)
+    X = torch.zeros(20, 8); Y = torch.zeros(10, 8)
+    with pytest.raises(ValueError, match="X: shape"):
+        plx.plx_spmm(dry, csr, torch.zeros(19, 8), Y)                    # X shorter than the handle's column count
+    with pytest.raises(ValueError, match="Y: shape"):
+        plx.plx_spmm(dry, csr, X, torch.zeros(9, 8))
+    with pytest.raises(ValueError, match="Y: shape"):
+        plx.plx_spmm_t(dry, csr, torch.zeros(10, 8), torch.zeros(10, 8))  # transposed: Y has the handle's 20 columns as rows
+    with pytest.raises(TypeError, match="Y: expected"):
+        plx.plx_spmm(dry, csr, X.bfloat16(), Y)                           # one element type per call
+    with pytest.raises(ValueError, match="Y: shape"):
+        plx.plx_spmm_static(dry, csr, False, X, torch.zeros(10, 4))
+    with pytest.raises(ValueError, match="C: shape"):
+        plx.plx_gemm_nn(dry, torch.zeros(8, 4), torch.zeros(4, 6), torch.zeros(8, 5))
+    with pytest.raises(TypeError, match="B: expected"):
+        plx.plx_gemm_nn(dry, torch.zeros(8, 4), torch.zeros(4, 6).bfloat16(), torch.zeros(8, 6))
+    with pytest.raises(ValueError, match="y:"):
+        plx.plx_softmax_ce(dry, torch.zeros(8, 4), torch.zeros(7, dtype=torch.int64), torch.zeros(8, 4))
+    # a layer: every operand against the handle and the widths
+    W = torch.zeros(8, 16); H = torch.zeros(20, 8); F = torch.zeros(10, 16); saved = torch.zeros(10, 8)
+    ws = torch.zeros(64, dtype=torch.uint8)
+    with pytest.raises(ValueError, match="H: shape"):
+        plx.plx_gcn_layer_fwd(dry, csr, False, torch.zeros(10, 8), W, None, F, saved, ws)
+    with pytest.raises(ValueError, match="saved: shape"):
+        plx.plx_gcn_layer_fwd(dry, csr, False, H, W, None, F, torch.zeros(1, 8), ws, order=plx.PLX_ORDER_AGG_FIRST)
+    with pytest.raises(TypeError, match="Z: expected torch.int32"):
+        plx.plx_gcn_layer_fwd(dry, csr, False, H, W, torch.zeros(10, 1), F, saved, ws, act=plx.PLX_ACT_RELU_BITS)
+    with pytest.raises(TypeError, match="F: expected"):
+        plx.plx_gcn_layer_fwd(dry, csr, False, H, W, None, F.bfloat16(), saved, ws)
+    with pytest.raises(ValueError, match="dH: shape"):
+        plx.plx_gcn_layer_bwd(dry, csr, False, H, W, F, torch.zeros(10, 16), saved, torch.zeros(10, 8), torch.zeros(8, 16), ws)
+    with pytest.raises(TypeError, match="workspace"):
+        plx.plx_gcn_layer_bwd(dry, csr, False, H, W, F, torch.zeros(10, 16), saved, torch.zeros(20, 8), torch.zeros(8, 16),
+                              torch.zeros(64))
+    with pytest.raises(ValueError, match="dTn: shape"):
+        plx.plx_gcn_layer_bwd_chained(dry, csr, False, H, W, None, torch.zeros(9, 4), torch.zeros(16, 4), saved, torch.zeros(20, 8),
+                                      torch.zeros(8, 16), ws, act=plx.PLX_ACT_NONE)
+    with pytest.raises(ValueError, match="T: shape"):
+        plx.plx_gcn_layer_fwd_from_t(dry, csr, False, torch.zeros(19, 16), None, F, act=plx.PLX_ACT_NONE)
+    # a combine-first layer never reads `saved`: a placeholder of any size passes the binding (and reaches the C checks)
+    expect(plx.PLX_ERR_DEVICE, plx.plx_gemm_nn, dry, torch.zeros(8, 4), torch.zeros(4, 6), torch.zeros(8, 6))
+
+
+def test_binding_rejects_tensors_on_another_device():
+    with pytest.raises(ValueError, match="the context runs on cuda:0"):
+        plx._check(OnGpu0(), "X", torch.zeros(4, 4), 4, 4)
+    with pytest.raises(ValueError, match="workspace on cpu"):
+        plx._check_ws(OnGpu0(), torch.zeros(4, dtype=torch.uint8))
+
+
+def test_layer_plan_without_a_device(dry):
+    """The sequencer's questions are answered on the host: no device needed, one place for the kernels' shape limits."""
+    assert plx.plx_gcn_layer_plan(dry, 64, 128, 16) == (True, True, True, True)           # the road network's pair
+    assert plx.plx_gcn_layer_plan(dry, 64, 128, 16, keep_values=True) == (True, False, True, False)
+    assert plx.plx_gcn_layer_plan(dry, 128, 128, 47) == (True, True, False, False)         # wide factor: not worth forming in the kernel
+    assert plx.plx_gcn_layer_plan(dry, 602, 128, 16) == (False, False, False, False)       # combine-first layer
+    assert plx.plx_gcn_layer_plan(dry, 32, 128, 16) == (True, True, False, False)          # narrow input: fp32 instructions, no pairing
+    assert plx.plx_gcn_layer_plan(dry, 64, 128, 16, dtype=plx.PLX_BF16) == (True, True, False, False)
+    assert plx.plx_gcn_layer_plan(dry, 64, 128, 16, next_order=plx.PLX_ORDER_AGG_FIRST)[2:] == (False, False)
+    plx.plx_ctx_set_split_products(dry, False)
+    assert plx.plx_gcn_layer_plan(dry, 64, 128, 16) == (True, True, False, False)          # the pairing lives in the split kernels
+    plx.plx_ctx_set_split_products(dry, True)
+    assert plx._lib.plx_gcn_layer_plan(dry.handle, 0, 128, 16, 0, 2, 2, 0, None, None, None, None) == plx.PLX_ERR_INVALID
+    assert plx._lib.plx_gcn_layer_plan(None, 64, 128, 16, 0, 2, 2, 0, None, None, None, None) == plx.PLX_ERR_INVALID
