@@ -449,6 +449,8 @@ def _check_layer(ctx: plx_ctx, csr: plx_csr, transposed_A: bool, din: int, dout:
             "saved": (ma if agg else 0, din if agg else 0, tdt), "dH": (ka, din, tdt), "dW": (din, dout, torch.float32),
             "dT": (ka, dout, tdt), "T": (ka, dout, tdt), "Wn": (dout, dn, torch.float32), "Tn": (ma, dn, tdt), "dTn": (ma, dn, tdt),
             "Z": (ma, (dout + 31) // 32, torch.int32) if act == PLX_ACT_RELU_BITS else (ma, dout, tdt)}
+    if act not in (PLX_ACT_NONE, PLX_ACT_RELU, PLX_ACT_RELU_BITS):
+        ops.pop("Z", None)                                                 # an unknown code is the library's to reject
     for name, t in ops.items():
         if name == "ws":
             _check_ws(ctx, t)
