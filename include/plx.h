@@ -21,9 +21,10 @@
  * Ownership.  The caller owns every dense buffer and workspace it passes.  The library owns
  * what is inside a plx_csr (obtained through the context's allocator) until plx_csr_destroy.
  *
- * Execution.  All work is queued on the context's HIP stream and returns without waiting,
- * except plx_build_csr, plx_csr_import and plx_csr_export, which wait for their own work
- * (they are set-up calls).  Calls on one context must not overlap in time.
+ * Execution.  All work is queued on the context's HIP stream and returns without waiting and
+ * without allocating device memory (what a product needs beyond its operands is part of the
+ * handle or of the caller's workspace), except plx_build_csr, plx_csr_import, plx_csr_export and
+ * plx_csr_set_row_blocks, which allocate and wait for their own work (they are set-up calls).  Calls on one context must not overlap in time.
  *
  * Errors.  Every entry point returns a plx_status; nothing aborts or throws across the
  * ABI.  Arguments are checked on the host before any GPU call (NULL, negative sizes,
@@ -166,11 +167,11 @@ PLX_API plx_status plx_spmm_t(plx_ctx* ctx, const plx_csr* csr, const void* X, i
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
  * harnesses that forbid it): plx_spmm (transposed == 0) or plx_spmm_t (transposed != 0) with the same
  * arguments and bit-identical results, except that the partial sums of split rows go to a fixed
- * 32 MiB buffer inside the library (one per GPU, held until the process ends) instead of a buffer the
- * context allocates on demand.  The call allocates nothing, frees nothing, records no timing events
+ * 32 MiB buffer inside the library (one per GPU, held until the process ends) instead of the buffer
+ * the handle holds for them (512 bytes per segment, allocated when the handle is built).  The call allocates nothing, frees nothing, records no timing events
  * (plx_timing_report does not list it) and does not wait.  Limit: (number of segments of the
  * orientation) x (floats per segment: d rounded up to a power-of-two number of 16-byte vectors, at
- * most 256 per pass) x 4 bytes <= 32 MiB, else PLX_ERR_UNSUPPORTED before anything is queued; a
+ * most 128 per pass) x 4 bytes <= 32 MiB, else PLX_ERR_UNSUPPORTED before anything is queued; a
  * handle without rows of 256 or more entries has no segments and always fits.  The buffer needs no
  * clearing (every segment's partial sums are fully rewritten before they are read), but all calls on
  * one GPU share it: two calls that overlap in time on the same GPU, from any context or stream, race.

@@ -462,6 +462,10 @@ plx_status build_bins(plx_ctx* ctx, Orient& o, int n_blocks) {
             o.seg0b[b] = v;
         }
     }
+    if (o.n_seg > 0) {
+        o.part = static_cast<float*>(dev_alloc(ctx, sizeof(float) * (size_t)o.n_seg * kPartFloats));
+        if (!o.part) return PLX_ERR_OOM;
+    }
     PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
     PLX_HIP(ctx, hipGetLastError());
     return PLX_OK;
@@ -483,6 +487,7 @@ plx_status unbin(plx_ctx* ctx, Orient& o) {
     dev_free(ctx, o.row_order); dev_free(ctx, o.bptr);
     dev_free(ctx, o.long_row); dev_free(ctx, o.long_seg0); dev_free(ctx, o.seg_lo); dev_free(ctx, o.seg_len);
     dev_free(ctx, o.seg_launch); o.seg_launch = nullptr;
+    dev_free(ctx, o.part); o.part = nullptr;
     o.row_order = nullptr; o.bptr = nullptr; o.long_row = nullptr; o.long_seg0 = nullptr; o.seg_lo = nullptr; o.seg_len = nullptr;
     o.n_long = o.n_seg = 0;
     return PLX_OK;

@@ -38,27 +38,11 @@ void dev_free(plx_ctx* ctx, void* p) {
     else (void)hipFree(p);
 }
 
-plx_status ensure_scratch(plx_ctx* ctx, size_t bytes) {
-    if (bytes <= ctx->scratch_bytes) return PLX_OK;
-    if (ctx->scratch) {
-        // work queued earlier may still read the old buffer
-        PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        dev_free(ctx, ctx->scratch);
-        ctx->scratch = nullptr;
-        ctx->scratch_bytes = 0;
-    }
-    size_t want = align256(bytes + bytes / 4);
-    ctx->scratch = dev_alloc(ctx, want);
-    if (!ctx->scratch) return PLX_ERR_OOM;
-    ctx->scratch_bytes = want;
-    return PLX_OK;
-}
-
 void free_orient(plx_ctx* ctx, Orient& o) {
     dev_free(ctx, o.rowptr); dev_free(ctx, o.col); dev_free(ctx, o.val); dev_free(ctx, o.row_order);
     dev_free(ctx, o.bptr);
     dev_free(ctx, o.long_row); dev_free(ctx, o.long_seg0); dev_free(ctx, o.seg_lo); dev_free(ctx, o.seg_len);
-    dev_free(ctx, o.seg_launch);
+    dev_free(ctx, o.seg_launch); dev_free(ctx, o.part);
     o = Orient();
 }
 
@@ -122,7 +106,6 @@ void plx_ctx_destroy(plx_ctx* ctx) {
     if (!ctx) return;
     if (!ctx->dry) (void)hipStreamSynchronize(ctx->stream);
     for (auto& t : ctx->timed) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
-    if (ctx->scratch) dev_free(ctx, ctx->scratch);
     delete ctx;
 }
 

@@ -18,6 +18,7 @@ constexpr int kNumClasses = 34;      // row-length classes: 0 = empty, c = 1 + f
 constexpr int kSubwaveMaxClass = 8;  // rows shorter than 2^8 are handled by a group of lanes
 constexpr int kLongClass = 13;       // without column windows only rows with len >= 2^12 are split into segments
 constexpr int64_t kSegLen = 2048;    // most nonzeros a segment may hold
+constexpr int kPartFloats = 128;     // partial-sum floats a handle keeps per segment: the widest pass of the segment kernels
 
 // One stored orientation of the adjacency (CSR) plus its row binning.
 struct Orient {
@@ -52,6 +53,8 @@ struct Orient {
     int32_t* long_seg0 = nullptr;  // device [n_long + 1] first segment of each long row
     int64_t* seg_lo = nullptr;     // device [n_seg] first entry of the segment (binned storage)
     int32_t* seg_len = nullptr;    // device [n_seg] nonzeros in the segment
+    float* part = nullptr;         // device [n_seg * kPartFloats] partial sums of the segments (sized with the handle, so that
+                                   // a product allocates nothing and never waits)
 };
 
 }  // namespace plx
@@ -65,8 +68,6 @@ struct plx_ctx {
     plx_free_fn release = nullptr;
     void* user = nullptr;
     std::string err;
-    void* scratch = nullptr;  // partial sums of split rows; grown on demand
-    size_t scratch_bytes = 0;
     int n_windows = 8;        // column windows for the rows handled through segments (1 = none); measured optimum 4-12
     bool split_products = true;   // fp32 dense products of the wide layers through six bf16 matrix instructions
     // optional per-kernel timing (plx_timing_enable)
@@ -86,7 +87,6 @@ namespace plx {
 plx_status fail(plx_ctx* ctx, plx_status s, const char* fmt, ...);
 void* dev_alloc(plx_ctx* ctx, size_t bytes);   // NULL on failure (error recorded)
 void dev_free(plx_ctx* ctx, void* p);
-plx_status ensure_scratch(plx_ctx* ctx, size_t bytes);
 
 #define PLX_HIP(ctx, call)                                                                   \
     do {                                                                                     \

@@ -287,35 +287,33 @@ __global__ __launch_bounds__(256) void k_spmm_combine(int64_t n_long, const int3
     if (out.ya) out.ya[row * out.ldya + j] = narrow<T>(s > 0.f ? s : 0.f);
 }
 
-// Where the partial sums of the segments go.  `given` == NULL: the context's own buffer, grown on demand.
-// Otherwise the caller of launch_spmm brought the memory (the allocation-free entry point): it is used as
-// it is, nothing is allocated or timed (the timer creates events), and a product that needs more fails.
+// Where the partial sums of the segments go: the handle's own buffer (kPartFloats floats per segment, sized when the
+// handle was built), or memory the caller of launch_spmm brought (`given`, the allocation-free entry point: used as it
+// is, and nothing is timed there because the timer creates events).  Either way a product allocates nothing.
 struct Partials {
     float* given = nullptr;
     size_t bytes = 0;
 };
 
+constexpr int WPB = 256 / kWave;   // wavefronts per block
+
+// Rows below the segment threshold: one group of lanes per row (and one wavefront per row where the column windows are off).
 template <typename T, int G, int VW>
-plx_status run_pass(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t ldx, Out<T> out, int d, const Partials& pt) {
+plx_status run_short(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t ldx, Out<T> out, int d, bool timed) {
     hipStream_t s = ctx->stream;
     const int64_t s0 = o.off(blk, 0);                                  // first slot of this row block
     const int64_t n_sub = o.off(blk, kSubwaveMaxClass + 1) - s0;
     const int64_t n_wave = o.off(blk, o.long_class) - s0 - n_sub;      // none when every such row goes through segments
-    const int64_t n_long = o.long0[blk + 1] - o.long0[blk], l0 = o.long0[blk];
-    const int64_t n_seg = o.seg0b[blk + 1] - o.seg0b[blk], g0 = o.seg0b[blk];
-    constexpr int WPB = 256 / kWave;   // wavefronts per block
-    const bool timed = ctx->timing && !pt.given;
     char label[64];
     if (timed) snprintf(label, sizeof label, "<%s,G%d,VW%d,d%d>[%s]", sizeof(T) == 4 ? "f32" : "bf16", G, VW, d, o.tag ? "At" : "A");
-    const int64_t sub_count = n_sub;
-    if (sub_count > 0) {
+    if (n_sub > 0) {
         KernelTimer kt(ctx, timed ? std::string("spmm_subwave") + label : std::string(), timed);
         constexpr int R = kWave / G;
-        int64_t blocks = ceil_div(ceil_div(sub_count, R), WPB);
+        int64_t blocks = ceil_div(ceil_div(n_sub, R), WPB);
 #if PLX_SUB_PERSIST
         blocks = std::min<int64_t>(blocks, (int64_t)ctx->n_cu * PLX_SUB_PERSIST);
 #endif
-        k_spmm_subwave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + s0, sub_count, o.bptr + s0, o.col, o.val, X,
+        k_spmm_subwave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + s0, n_sub, o.bptr + s0, o.col, o.val, X,
                                                                          ldx, out, d);
     }
     if (n_wave > 0) {
@@ -324,51 +322,70 @@ plx_status run_pass(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t 
         k_spmm_wave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + s0 + n_sub, n_wave, o.bptr + s0 + n_sub, o.col,
                                                                       o.val, X, ldx, out, d);
     }
-    if (n_seg > 0) {
-        const size_t need = (size_t)o.n_seg * G * VW * sizeof(float);
-        float* part = pt.given;                                         // indexed by the global segment number
-        if (part) {
-            if (need > pt.bytes)
-                return fail(ctx, PLX_ERR_UNSUPPORTED, "the partial sums of %lld segments at this width take %zu bytes, the fixed "
-                            "buffer holds %zu", (long long)o.n_seg, need, pt.bytes);
-        } else {
-            PLX_TRY(ensure_scratch(ctx, need));
-            part = static_cast<float*>(ctx->scratch);
-        }
-        KernelTimer kt(ctx, timed ? std::string("spmm_split") + label : std::string(), timed);
-        k_spmm_segment<T, G, VW><<<dim3((unsigned)ceil_div(n_seg, WPB)), 256, 0, s>>>(n_seg, o.seg_launch + g0, o.seg_lo, o.seg_len,
-                                                                                       o.col, o.val, X, ldx, part, d);
-        int64_t total = n_long * d;
-        k_spmm_combine<T><<<dim3((unsigned)ceil_div(total, 256)), 256, 0, s>>>(n_long, o.long_row + l0, o.long_seg0 + l0, part,
-                                                                               G * VW, out, d);
-    }
     PLX_HIP(ctx, hipGetLastError());
     return PLX_OK;
 }
 
+// Rows cut into segments: partial sums per segment, then the sums of each row in segment order.
+template <typename T, int G, int VW>
+plx_status run_long(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t ldx, Out<T> out, int d, float* part, bool timed) {
+    hipStream_t s = ctx->stream;
+    const int64_t n_long = o.long0[blk + 1] - o.long0[blk], l0 = o.long0[blk];
+    const int64_t n_seg = o.seg0b[blk + 1] - o.seg0b[blk], g0 = o.seg0b[blk];
+    if (n_seg <= 0) return PLX_OK;
+    char label[64];
+    if (timed) snprintf(label, sizeof label, "<%s,G%d,VW%d,d%d>[%s]", sizeof(T) == 4 ? "f32" : "bf16", G, VW, d, o.tag ? "At" : "A");
+    KernelTimer kt(ctx, timed ? std::string("spmm_split") + label : std::string(), timed);
+    k_spmm_segment<T, G, VW><<<dim3((unsigned)ceil_div(n_seg, WPB)), 256, 0, s>>>(n_seg, o.seg_launch + g0, o.seg_lo, o.seg_len,
+                                                                                   o.col, o.val, X, ldx, part, d);
+    const int64_t total = n_long * d;
+    k_spmm_combine<T><<<dim3((unsigned)ceil_div(total, 256)), 256, 0, s>>>(n_long, o.long_row + l0, o.long_seg0 + l0, part,
+                                                                           G * VW, out, d);
+    PLX_HIP(ctx, hipGetLastError());
+    return PLX_OK;
+}
+
+template <typename T, int VW, bool LONG>
+plx_status dispatch(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t ldx, Out<T> out, int d, float* part, bool timed) {
+    int G = 1;
+    while (G * VW < d) G <<= 1;
+#define PLX_SPMM_CASE(GV)                                                                    \
+    case GV:                                                                                 \
+        if constexpr (LONG) return run_long<T, GV, VW>(ctx, o, blk, X, ldx, out, d, part, timed); \
+        else return run_short<T, GV, VW>(ctx, o, blk, X, ldx, out, d, timed)
+    switch (G) {
+        PLX_SPMM_CASE(1); PLX_SPMM_CASE(2); PLX_SPMM_CASE(4); PLX_SPMM_CASE(8); PLX_SPMM_CASE(16); PLX_SPMM_CASE(32);
+        default: if constexpr (LONG) return run_long<T, 64, VW>(ctx, o, blk, X, ldx, out, d, part, timed);
+                 else return run_short<T, 64, VW>(ctx, o, blk, X, ldx, out, d, timed);
+    }
+#undef PLX_SPMM_CASE
+}
+
 template <typename T, int VW>
 plx_status run_vw(plx_ctx* ctx, const Orient& o, int block, const T* X, int64_t ldx, Out<T> out, int64_t d, const Partials& pt) {
+    const bool timed = ctx->timing && !pt.given;
     const int tile = kWave * VW;                        // widest pass one wavefront covers
-    for (int64_t t0 = 0; t0 < d; t0 += tile) {
-        int dp = (int)std::min<int64_t>(tile, d - t0);
-        int chunks = (dp + VW - 1) / VW;
-        int G = 1;
-        while (G < chunks) G <<= 1;
-        const T* Xp = X + t0;
-        Out<T> op{out.y ? out.y + t0 : nullptr, out.ldy, out.ya ? out.ya + t0 : nullptr, out.ldya};
-        const int b_lo = block < 0 ? 0 : block, b_hi = block < 0 ? o.n_blocks : block + 1;
-        for (int blk = b_lo; blk < b_hi; ++blk) {
-        plx_status st;
-        switch (G) {
-            case 1: st = run_pass<T, 1, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
-            case 2: st = run_pass<T, 2, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
-            case 4: st = run_pass<T, 4, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
-            case 8: st = run_pass<T, 8, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
-            case 16: st = run_pass<T, 16, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
-            case 32: st = run_pass<T, 32, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
-            default: st = run_pass<T, 64, VW>(ctx, o, blk, Xp, ldx, op, dp, pt); break;
+    // the segment kernels work in passes of at most this many columns: what a segment's slot of partial sums holds
+    int64_t part_floats = kPartFloats;
+    float* part = o.part;
+    if (pt.given) {         // the same pass widths as with the handle's buffer (the results are then bit-identical), if they fit
+        part = pt.given;
+        if (o.n_seg > 0) part_floats = std::min<int64_t>(part_floats, (int64_t)(pt.bytes / sizeof(float)) / o.n_seg);
+    }
+    int long_tile = VW;
+    while (2 * long_tile <= std::min<int64_t>(part_floats, tile)) long_tile *= 2;
+    const int b_lo = block < 0 ? 0 : block, b_hi = block < 0 ? o.n_blocks : block + 1;
+    for (int blk = b_lo; blk < b_hi; ++blk) {
+        for (int64_t t0 = 0; t0 < d; t0 += tile) {
+            const int dp = (int)std::min<int64_t>(tile, d - t0);
+            Out<T> op{out.y ? out.y + t0 : nullptr, out.ldy, out.ya ? out.ya + t0 : nullptr, out.ldya};
+            PLX_TRY((dispatch<T, VW, false>(ctx, o, blk, X + t0, ldx, op, dp, nullptr, timed)));
         }
-        PLX_TRY(st);
+        if (o.seg0b[blk + 1] - o.seg0b[blk] <= 0) continue;
+        for (int64_t t0 = 0; t0 < d; t0 += long_tile) {
+            const int dp = (int)std::min<int64_t>(long_tile, d - t0);
+            Out<T> op{out.y ? out.y + t0 : nullptr, out.ldy, out.ya ? out.ya + t0 : nullptr, out.ldya};
+            PLX_TRY((dispatch<T, VW, true>(ctx, o, blk, X + t0, ldx, op, dp, part, timed)));
         }
     }
     return PLX_OK;
@@ -417,16 +434,20 @@ plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx
                (!Y || (aligned_to(Y, bytes) && (ldy * es) % bytes == 0)) &&
                (!Yact || (aligned_to(Yact, bytes) && (ldyact * es) % bytes == 0));
     };
-    if (partials && o.n_seg > 0) {
-        // checked before anything is queued: the widest pass covers min(d, 64 VW) columns with G VW floats per segment
+    if (o.n_seg > 0) {
+        // checked before anything is queued: a segment's partial sums need room for at least one vector per lane group
         const int vw = dtype == PLX_F32 ? (fits(16, 4) ? 4 : fits(8, 4) ? 2 : 1) : (fits(16, 2) ? 8 : fits(8, 2) ? 4 : 1);
-        const int64_t dp = std::min<int64_t>(d, (int64_t)kWave * vw);
-        int64_t g = 1;
-        while (g * vw < dp) g <<= 1;
-        const size_t need = (size_t)o.n_seg * (size_t)(g * vw) * sizeof(float);
-        if (need > partials_bytes)
-            return fail(ctx, PLX_ERR_UNSUPPORTED, "the partial sums of %lld segments at width %lld take %zu bytes, more than the "
-                        "%zu bytes of the fixed buffer", (long long)o.n_seg, (long long)d, need, partials_bytes);
+        if (partials) {
+            const int64_t dp = std::min<int64_t>(d, std::min<int64_t>((int64_t)kWave * vw, kPartFloats));
+            int64_t g = 1;
+            while (g * vw < dp) g <<= 1;
+            const size_t need = (size_t)o.n_seg * (size_t)(g * vw) * sizeof(float);
+            if (need > partials_bytes)
+                return fail(ctx, PLX_ERR_UNSUPPORTED, "the partial sums of %lld segments at width %lld take %zu bytes, more than the "
+                            "%zu bytes of the fixed buffer", (long long)o.n_seg, (long long)d, need, partials_bytes);
+        } else if (!o.part) {
+            return fail(ctx, PLX_ERR_INTERNAL, "the handle holds segments but no buffer for their partial sums");
+        }
     }
     if (dtype == PLX_F32) {
         const float* x = static_cast<const float*>(X);

@@ -143,10 +143,9 @@ class GcnNetwork:
     def capture(self, H0: torch.Tensor, y: torch.Tensor, stream: torch.cuda.Stream) -> "torch.cuda.CUDAGraph":
         """Record one forward + backward into a HIP graph (for small, launch-bound graphs the ~30
         launches of a step then cost one graph launch).  `stream` must be the non-default stream the
-        context was created on.  One eager step runs first so that every scratch buffer has its
-        final size: the recorded step then allocates nothing.  Per-kernel timing must be off."""
-        self.step(H0, y)
-        self.sync()
+        context was created on.  A step allocates nothing and never waits (every buffer belongs to
+        this object, to the adjacency handle or to the workspace), so it can be recorded as it is.
+        Per-kernel timing must be off."""
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream, capture_error_mode="thread_local"):
             self.step(H0, y)

@@ -1144,6 +1144,41 @@ def test_network_step_in_hip_graph():
     csr.close(); gctx.close()
 
 
+def test_first_step_recorded_into_a_hip_graph_without_an_eager_one():
+    """A step allocates nothing and never waits -- the partial sums of split rows live in the adjacency handle -- so the
+    very first step of a network can be recorded into a HIP graph (no eager step before it to size any buffer).  Graph
+    with rows far above the segment threshold (social recipe); the replays must equal the eager step that follows."""
+    from paper_2505_04083_amd.network import GcnNetwork
+    cfg = synth.CONFIGS["social"].scaled(0.05)
+    cfg.dims = [64, 128, 128, 41]
+    side = torch.cuda.Stream(device=DEV)
+    gctx = plx.plx_ctx(0, stream=side.cuda_stream)
+    src, dst = cfg.edges(DEV)
+    pr, pc = cfg.perms(DEV)
+    H0 = cfg.features(DEV); Ws = cfg.weights(DEV); y = cfg.labels(DEV)
+    torch.cuda.synchronize()
+    csr = plx.plx_build_csr(gctx, cfg.n, src, dst, pr, pc)
+    assert plx.plx_csr_bins(csr, False)[0][1] + plx.plx_csr_bins(csr, False)[0][2] > 100     # rows that go through segments
+    net = GcnNetwork(gctx, csr, Ws)
+    live = len(gctx._live)
+    graph = net.capture(H0, y, side)
+    assert len(gctx._live) == live                                  # recording obtained nothing from the allocator
+    got = []
+    for rep in range(2):
+        for t in net.dW + [net.dH[0], net.loss]:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got.append([t.clone() for t in net.dW + [net.dH[0], net.loss]])
+    net.step(H0, y); net.sync()
+    for g in got:
+        for a, b in zip(g, net.dW + [net.dH[0], net.loss]):
+            assert torch.equal(a, b)
+    del graph
+    csr.close(); gctx.close()
+
+
 # ---------------------------------------------------------------- bf16 storage, fp32 accumulation
 TOLBF = 2e-2
 

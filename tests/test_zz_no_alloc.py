@@ -70,7 +70,7 @@ def test_static_buffer_limit_is_an_error_before_any_work():
     """More segments than 32 MiB of partial sums hold: PLX_ERR_UNSUPPORTED, output untouched; the same handle at a
     narrower width fits and runs."""
     ctx = plx.plx_ctx(0)
-    m, k = 6000, 8192
+    m, k = 9000, 8192
     r = np.random.default_rng(3)
     lens = np.full(m, 2100, np.int64)                          # every row: 8 windows, > 8 segments
     rowptr = np.zeros(m + 1, np.int64); rowptr[1:] = np.cumsum(lens)
@@ -80,7 +80,7 @@ def test_static_buffer_limit_is_an_error_before_any_work():
     csr = plx.plx_csr_import(ctx, m, k, t(rowptr), t(col), t(val))
     X = torch.randn(k, 256, device=DEV)
     Y = torch.full((m, 256), 7.0, device=DEV)
-    with pytest.raises(plx.PlxError) as err:                   # >= 48000 segments x 1 KiB > 32 MiB
+    with pytest.raises(plx.PlxError) as err:                   # >= 72000 segments x 512 B (128 floats per pass) > 32 MiB
         plx.plx_spmm_static(ctx, csr, False, X, Y)
     assert err.value.status == plx.PLX_ERR_UNSUPPORTED and "fixed buffer" in str(err.value)
     plx.plx_sync(ctx)
