@@ -241,6 +241,15 @@ __global__ void k_seg_fill(int64_t n_long, const int32_t* __restrict__ long_slot
     }
 }
 
+// the segments in launch order, one 16-byte record each
+__global__ void k_seg_desc(int64_t n_seg, const int32_t* __restrict__ launch, const int64_t* __restrict__ seg_lo,
+                           const int32_t* __restrict__ seg_len, int4* __restrict__ desc) {
+    GRID_STRIDE(pos, n_seg) {
+        const int32_t seg = launch[pos];
+        desc[pos] = make_int4((int32_t)seg_lo[seg], seg_len[seg], seg, 0);
+    }
+}
+
 // length of the row held by each slot of the binned order (slot `rows` gets 0 for the scan)
 __global__ void k_slot_len(int64_t rows, const int32_t* row_order, const int64_t* rowptr, int32_t* len) {
     GRID_STRIDE(s, rows + 1) {
@@ -464,7 +473,9 @@ plx_status build_bins(plx_ctx* ctx, Orient& o, int n_blocks) {
     }
     if (o.n_seg > 0) {
         o.part = static_cast<float*>(dev_alloc(ctx, sizeof(float) * (size_t)o.n_seg * kPartFloats));
-        if (!o.part) return PLX_ERR_OOM;
+        o.seg_desc = static_cast<int4*>(dev_alloc(ctx, sizeof(int4) * (size_t)o.n_seg));
+        if (!o.part || !o.seg_desc) return PLX_ERR_OOM;
+        k_seg_desc<<<grid_for(o.n_seg), kThreads, 0, ctx->stream>>>(o.n_seg, o.seg_launch, o.seg_lo, o.seg_len, o.seg_desc);
     }
     PLX_HIP(ctx, hipStreamSynchronize(ctx->stream));
     PLX_HIP(ctx, hipGetLastError());
@@ -488,6 +499,7 @@ plx_status unbin(plx_ctx* ctx, Orient& o) {
     dev_free(ctx, o.long_row); dev_free(ctx, o.long_seg0); dev_free(ctx, o.seg_lo); dev_free(ctx, o.seg_len);
     dev_free(ctx, o.seg_launch); o.seg_launch = nullptr;
     dev_free(ctx, o.part); o.part = nullptr;
+    dev_free(ctx, o.seg_desc); o.seg_desc = nullptr;
     o.row_order = nullptr; o.bptr = nullptr; o.long_row = nullptr; o.long_seg0 = nullptr; o.seg_lo = nullptr; o.seg_len = nullptr;
     o.n_long = o.n_seg = 0;
     return PLX_OK;

@@ -42,7 +42,7 @@ void free_orient(plx_ctx* ctx, Orient& o) {
     dev_free(ctx, o.rowptr); dev_free(ctx, o.col); dev_free(ctx, o.val); dev_free(ctx, o.row_order);
     dev_free(ctx, o.bptr);
     dev_free(ctx, o.long_row); dev_free(ctx, o.long_seg0); dev_free(ctx, o.seg_lo); dev_free(ctx, o.seg_len);
-    dev_free(ctx, o.seg_launch); dev_free(ctx, o.part);
+    dev_free(ctx, o.seg_launch); dev_free(ctx, o.part); dev_free(ctx, o.seg_desc);
     o = Orient();
 }
 

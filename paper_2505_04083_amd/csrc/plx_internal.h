@@ -53,6 +53,8 @@ struct Orient {
     int32_t* long_seg0 = nullptr;  // device [n_long + 1] first segment of each long row
     int64_t* seg_lo = nullptr;     // device [n_seg] first entry of the segment (binned storage)
     int32_t* seg_len = nullptr;    // device [n_seg] nonzeros in the segment
+    int4* seg_desc = nullptr;      // device [n_seg], launch order: {first entry, nonzeros, segment id, 0} -- what a wavefront of
+                                   // the segment kernel needs, in one 16-byte load at a wave-uniform address
     float* part = nullptr;         // device [n_seg * kPartFloats] partial sums of the segments (sized with the handle, so that
                                    // a product allocates nothing and never waits)
 };

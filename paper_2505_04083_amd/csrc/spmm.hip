@@ -127,13 +127,33 @@ __device__ __forceinline__ void gather_accumulate(int64_t first, int64_t hi, int
 #pragma unroll
             for (int i = 0; i < VW; ++i) acc[i] = fmaf(v[t], x[t][i], acc[i]);
     }
-    for (; e < hi; e += stride) {
-        int32_t c = col[e];
-        float v = val[e];
-        float x[VW];
-        load_vec<T, VW>(xb + (int64_t)c * ldx, x);
+    if (e < hi) {
+        // what is left is fewer than kUnroll entries: one more trip with the missing ones masked off, so that the
+        // remaining gathers are in flight together too (a segment of a long row is often shorter than one full trip)
+        int32_t c[kUnroll];
+        float v[kUnroll];
+        bool ok[kUnroll];
 #pragma unroll
-        for (int i = 0; i < VW; ++i) acc[i] = fmaf(v, x[i], acc[i]);
+        for (int t = 0; t < kUnroll; ++t) {
+            const int64_t idx = e + t * stride;
+            ok[t] = idx < hi;
+            c[t] = ok[t] ? col[idx] : 0;
+            v[t] = ok[t] ? val[idx] : 0.f;
+        }
+        float x[kUnroll][VW];
+#pragma unroll
+        for (int t = 0; t < kUnroll; ++t) {
+            if (ok[t]) {
+                load_vec<T, VW>(xb + (int64_t)c[t] * ldx, x[t]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < VW; ++i) x[t][i] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < kUnroll; ++t)
+#pragma unroll
+            for (int i = 0; i < VW; ++i) acc[i] = fmaf(v[t], x[t][i], acc[i]);
     }
 }
 
@@ -243,22 +263,23 @@ __global__ __launch_bounds__(256) void k_spmm_wave(const int32_t* __restrict__ r
     if (g == 0 && active) emit<T, VW>(out, row, c0, acc, d - c0);
 }
 
-// Long rows, stage 1: one wavefront per segment, fp32 partial sums to part[seg][G*VW].
+// Long rows, stage 1: one wavefront per segment, fp32 partial sums to part[seg][G*VW].  The segment's record sits at a
+// wave-uniform address (scalar loads: the chain record -> columns -> operand rows has one vector-memory step less).
 template <typename T, int G, int VW>
-__global__ __launch_bounds__(256) void k_spmm_segment(int64_t n_seg, const int32_t* __restrict__ launch,
-                                                      const int64_t* __restrict__ seg_lo,
-                                                      const int32_t* __restrict__ seg_len,
+__global__ __launch_bounds__(256) void k_spmm_segment(int64_t n_seg, const int4* __restrict__ desc,
                                                       const int32_t* __restrict__ col, const float* __restrict__ val,
                                                       const T* __restrict__ X, int64_t ldx, float* __restrict__ part,
                                                       int d) {
     constexpr int NG = kWave / G;
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t pos = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int64_t pos = (int64_t)blockIdx.x * (blockDim.x / kWave) + wv;
     if (pos >= n_seg) return;
-    const int64_t seg = launch[pos];                 // launch order (column window by window) -> segment id
+    const int4 rec = desc[pos];                      // launch order (column window by window)
+    const int64_t seg = rec.z;
     const int g = lane / G, c0 = (lane % G) * VW;
     const bool active = c0 < d;
-    const int64_t lo = seg_lo[seg], hi = lo + seg_len[seg];
+    const int64_t lo = rec.x, hi = lo + rec.y;
     float acc[VW];
 #pragma unroll
     for (int i = 0; i < VW; ++i) acc[i] = 0.f;
@@ -336,8 +357,7 @@ plx_status run_long(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t 
     char label[64];
     if (timed) snprintf(label, sizeof label, "<%s,G%d,VW%d,d%d>[%s]", sizeof(T) == 4 ? "f32" : "bf16", G, VW, d, o.tag ? "At" : "A");
     KernelTimer kt(ctx, timed ? std::string("spmm_split") + label : std::string(), timed);
-    k_spmm_segment<T, G, VW><<<dim3((unsigned)ceil_div(n_seg, WPB)), 256, 0, s>>>(n_seg, o.seg_launch + g0, o.seg_lo, o.seg_len,
-                                                                                   o.col, o.val, X, ldx, part, d);
+    k_spmm_segment<T, G, VW><<<dim3((unsigned)ceil_div(n_seg, WPB)), 256, 0, s>>>(n_seg, o.seg_desc + g0, o.col, o.val, X, ldx, part, d);
     const int64_t total = n_long * d;
     k_spmm_combine<T><<<dim3((unsigned)ceil_div(total, 256)), 256, 0, s>>>(n_long, o.long_row + l0, o.long_seg0 + l0, part,
                                                                            G * VW, out, d);
