@@ -74,6 +74,8 @@ def parse():
     ap.add_argument("--mask", choices=["bits", "values"], default="bits",
                     help="what the backward pass reads for the ReLU derivative: one sign bit per element written by the "
                          "forward pass, or the activated output itself")
+    ap.add_argument("--fused-aggregation", action="store_true",
+                    help="aggregate-first forward with the combination in the sparse kernels' epilogue (a measured alternative, off by default)")
     ap.add_argument("--windows", type=int, default=0, help="column windows of the sparse product (0 = the library's default)")
     ap.add_argument("--graph", action="store_true",
                     help="graph workloads only: also record the step into a HIP graph and time K replays (graph_ms_per_step)")
@@ -120,6 +122,14 @@ def kernel_cost(name, bins, names=()):
             e, r = e + ent[1], r + rows[1]       # column windows on: the segment kernels take every row of 256+ entries
         fixed = e * 8 + r * (4 + s * d)
         return fixed + e * s * d, fixed + min(e, cols) * s * d, 2 * e * d
+    m = re.match(r"spmm_subwave_combine<f32,d(\d+),N(\d+)>\[(A|At)\]", name)
+    if m:       # the short rows' sparse product plus, per row, the N-wide result (and its sign bits) instead of a re-read of H
+        d, N, o = int(m.group(1)), int(m.group(2)), m.group(3)
+        rows, ent = bins[o]
+        cols = sum(bins["At" if o == "A" else "A"][0])
+        e, r = ent[0], rows[0]
+        fixed = e * 8 + r * (4 + 4 * d + 4 * N + 4 * ((N + 31) // 32))
+        return fixed + e * 4 * d, fixed + min(e, cols) * 4 * d, 2 * e * d + 2 * r * d * N
     m = re.match(r"gemm_(nn|nt)<(f32|bf16)>\[M(\d+),N(\d+),K(\d+)\]", name)
     if m:
         s = 4 if m.group(2) == "f32" else 2
@@ -167,6 +177,7 @@ _SOURCES = [
 ]
 # kernels a timed launch may consist of: (label prefix, kernel-name prefixes, most kernels; 0 = any number)
 _SYMBOLS = [
+    ("spmm_subwave_combine", ["k_spmm_subwave_combine"], 1), ("rows_combine", ["k_rows_combine"], 1),
     ("spmm_subwave", ["k_spmm_subwave"], 1), ("spmm_wave", ["k_spmm_wave"], 1),
     ("spmm_split", ["k_spmm_segment", "k_spmm_combine"], 2),
     ("gemm_tn", ["k_gemm_tn"], 1), ("gemm_n", ["k_gemm_f32", "k_gemm_deep", "k_gemm_small"], 1),
@@ -355,6 +366,8 @@ def main():
     ctx = plx.plx_ctx(0, stream=side.cuda_stream) if side else plx.plx_ctx(0)
     if args.windows:
         plx.plx_ctx_set_column_windows(ctx, args.windows)
+    if args.fused_aggregation:
+        plx.plx_ctx_set_fused_aggregation(ctx, True)
     shard_state = None
 
     t0 = time.time()
@@ -483,7 +496,7 @@ def main():
         graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # ---- per-kernel accounting ------------------------------------------------------------------------
-    traffic = Traffic(args.workload, args.dtype, usable=args.scale == 1.0 and not args.windows)
+    traffic = Traffic(args.workload, args.dtype, usable=args.scale == 1.0 and not args.windows and not args.fused_aggregation)
     bins = {"A": plx.plx_csr_bins(csr, False), "At": plx.plx_csr_bins(csr, True)}
     cost = {name: kernel_cost(name, bins, timing) for name in timing}
     meas = {name: traffic.of(name) for name in timing}

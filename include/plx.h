@@ -97,6 +97,14 @@ PLX_API plx_status plx_ctx_set_column_windows(plx_ctx* ctx, int n_windows);
  * NaN (the fp32 instructions give +-infinity where no opposite infinity or zero factor meets it): the
  * same results are non-finite in both paths.  on == 0 selects the plain fp32 instructions everywhere. */
 PLX_API plx_status plx_ctx_set_split_products(plx_ctx* ctx, int on);
+/* Aggregate-first layers (Eq. 2.1 then 2.2) normally run the sparse product and the dense product as separate kernels, the
+ * aggregation H = A F making a round trip through memory between them.  With on != 0, plx_gcn_layer_fwd keeps the
+ * aggregated rows on chip and multiplies them by W in the epilogue of the sparse kernels (H is still written once: the
+ * backward pass reads it), for fp32 layers with 16 < din <= 32, dout <= 128 and 16-byte aligned rows; other layers are not
+ * affected.  Results agree with the separate kernels to fp32 rounding.  Off by default: on the 7M x 28M shard layer the
+ * fused kernels were measured slower (the matrix-core epilogue takes registers and LDS from a kernel whose speed is the
+ * number of gathers in flight) than the 0.9 GB re-read they save. */
+PLX_API plx_status plx_ctx_set_fused_aggregation(plx_ctx* ctx, int on);
 PLX_API plx_status plx_sync(plx_ctx* ctx);                /* wait for the context's stream */
 
 /* Optional per-kernel timing for benchmarks.  While enabled, every kernel the library

@@ -22,7 +22,7 @@ PLX_ACT_NONE, PLX_ACT_RELU, PLX_ACT_RELU_BITS = 0, 1, 2
 PLX_ORDER_COMBINE_FIRST, PLX_ORDER_AGG_FIRST, PLX_ORDER_AUTO = 0, 1, 2
 
 EXPORTED = [
-    "plx_ctx_create", "plx_ctx_destroy", "plx_ctx_set_column_windows", "plx_ctx_set_split_products", "plx_last_error", "plx_status_string", "plx_sync",
+    "plx_ctx_create", "plx_ctx_destroy", "plx_ctx_set_column_windows", "plx_ctx_set_split_products", "plx_ctx_set_fused_aggregation", "plx_last_error", "plx_status_string", "plx_sync",
     "plx_timing_enable", "plx_timing_report", "plx_timing_trace",
     "plx_build_csr", "plx_csr_import", "plx_csr_dims", "plx_csr_export", "plx_csr_bins", "plx_csr_destroy",
     "plx_csr_set_row_blocks", "plx_csr_row_blocks", "plx_spmm_block", "plx_spmm", "plx_spmm_t", "plx_spmm_static", "plx_gemm_nn", "plx_gemm_nt", "plx_gemm_tn_workspace", "plx_gemm_tn",
@@ -60,6 +60,7 @@ def _load() -> ctypes.CDLL:
         "plx_csr_destroy": (None, [_vp, _vp]),
         "plx_ctx_set_column_windows": (_int, [_vp, _int]),
         "plx_ctx_set_split_products": (_int, [_vp, _int]),
+        "plx_ctx_set_fused_aggregation": (_int, [_vp, _int]),
         "plx_csr_set_row_blocks": (_int, [_vp, _vp, _int]),
         "plx_csr_row_blocks": (_int, [_vp, _int, ctypes.POINTER(_int), ctypes.POINTER(_i64)]),
         "plx_spmm_block": (_int, [_vp, _vp, _int, _int, _vp, _i64, _vp, _i64, _i64, _int]),
@@ -302,6 +303,11 @@ def plx_timing_trace(ctx: plx_ctx, max_bytes: int = 1 << 22):
 
 def plx_ctx_set_split_products(ctx: plx_ctx, on: bool) -> None:
     ctx.check(_lib.plx_ctx_set_split_products(ctx.handle, int(bool(on))))
+
+
+def plx_ctx_set_fused_aggregation(ctx: plx_ctx, on: bool) -> None:
+    """Aggregate-first forward with the combination in the sparse kernels' epilogue (narrow fp32 layers; off by default)."""
+    ctx.check(_lib.plx_ctx_set_fused_aggregation(ctx.handle, int(bool(on))))
 
 
 def plx_ctx_set_column_windows(ctx: plx_ctx, n_windows: int) -> None:

@@ -115,6 +115,12 @@ plx_status plx_ctx_set_split_products(plx_ctx* ctx, int on) {
     return PLX_OK;
 }
 
+plx_status plx_ctx_set_fused_aggregation(plx_ctx* ctx, int on) {
+    if (!ctx) return PLX_ERR_INVALID;
+    ctx->fused_aggregation = on != 0;
+    return PLX_OK;
+}
+
 plx_status plx_ctx_set_column_windows(plx_ctx* ctx, int n_windows) {
     if (!ctx) return PLX_ERR_INVALID;
     if (n_windows < 1 || n_windows > 64) return fail(ctx, PLX_ERR_INVALID, "n_windows must be between 1 and 64");
@@ -514,7 +520,11 @@ plx_status layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const v
     }
     const int64_t ld_plain = plain == Z ? ldz : ldf;
     bool next_done = false;                  // Tn written by the product that wrote this layer's output
-    if (order == PLX_ORDER_AGG_FIRST) {
+    if (order == PLX_ORDER_AGG_FIRST && ctx->fused_aggregation && !var.Tn &&
+        spmm_combine_supported(a, H, ldh, saved, ldsaved, din, dout, dtype)) {
+        // Eq. 2.1, 2.2 and 2.3 in one pass over the adjacency: the aggregated tile is multiplied by W before it leaves the chip
+        PLX_TRY(launch_spmm_combine(ctx, a, H, ldh, saved, ldsaved, W, ldw, din, dout, plain, ld_plain, activated, ldf, bits, ldz));
+    } else if (order == PLX_ORDER_AGG_FIRST) {
         PLX_TRY(launch_spmm(ctx, a, H, ldh, saved, ldsaved, din, dtype));                    // Eq. 2.1
         if (var.Tn && gemm_next_supported(ctx, a.rows, dout, din, var.dn, dtype, saved, ldsaved, plain ? ld_plain : 0,
                                           activated ? ldf : 0, var.ldtn)) {

@@ -72,6 +72,7 @@ struct plx_ctx {
     std::string err;
     int n_windows = 8;        // column windows for the rows handled through segments (1 = none); measured optimum 4-12
     bool split_products = true;   // fp32 dense products of the wide layers through six bf16 matrix instructions
+    bool fused_aggregation = false;   // aggregate-first forward: Eq. 2.2-2.3 in the epilogue of the sparse kernels (measured slower)
     // optional per-kernel timing (plx_timing_enable)
     struct Timed { std::string name; hipEvent_t start, stop; };
     bool timing = false;
@@ -153,6 +154,12 @@ void free_orient(plx_ctx* ctx, Orient& o);
 plx_status launch_spmm(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* Y, int64_t ldy,
                        int64_t d, plx_dtype dtype, void* Yact = nullptr, int64_t ldyact = 0, int block = -1,
                        float* partials = nullptr, size_t partials_bytes = 0);
+// Eq. 2.1 with Eq. 2.2 (+ 2.3) in its epilogue: S = A X is written, and C = S W, Fact = max(S W, 0), sign bits as wanted
+bool spmm_combine_supported(const Orient& o, const void* X, int64_t ldx, const void* S, int64_t lds_, int64_t din, int64_t dout,
+                            plx_dtype dtype);
+plx_status launch_spmm_combine(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* S, int64_t lds_, const float* W,
+                               int64_t ldw, int64_t din, int64_t dout, void* C, int64_t ldc, void* Fact, int64_t ldf, uint32_t* bits,
+                               int64_t ldbits);
 // partials != NULL: the partial sums of split rows go there instead of into the context's buffer; the call then
 // allocates nothing, records no timing events, and fails with PLX_ERR_UNSUPPORTED if partials_bytes is too small.
 // The fixed per-GPU buffer of plx_spmm_static (resolved once per device, with that device current; NULL on failure):

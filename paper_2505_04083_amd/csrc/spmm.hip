@@ -21,11 +21,13 @@
 
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 
 namespace plx {
 namespace {
 
 typedef uint16_t bf16_t;
+typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {   // round to nearest even
@@ -308,6 +310,161 @@ __global__ __launch_bounds__(256) void k_spmm_combine(int64_t n_long, const int3
     if (out.ya) out.ya[row * out.ldya + j] = narrow<T>(s > 0.f ? s : 0.f);
 }
 
+// ---- aggregation with the combination in its epilogue (Eq. 2.1 -> 2.2 -> 2.3 in one pass over the short rows) -------
+// The short-row kernel above, for fp32 rows of 17..32 elements (G = 8 lanes per row, 8 rows per wavefront and trip),
+// that keeps the aggregated rows on chip: four trips fill a wave-private 32 x 32 tile of H = A X in LDS (H is still
+// written out: Eq. 2.5 reads it in the backward pass), and the tile is multiplied by W[din x dout] (in LDS, once per
+// workgroup) with v_mfma_f32_32x32x2_f32 -- lane l: a = H[row l%32][k = 2s + l/32], b = W[2s + l/32][32 nb + l%32],
+// acc[r] = result[row 8(r/4) + 4(l/32) + r%4][32 nb + l%32] -- and leaves as Q and / or ReLU(Q) and / or its sign bits
+// for the rows' ids.  What it saves is the combination's re-read of H; what it costs is registers and LDS in a kernel
+// that lives on the number of gathers in flight.
+constexpr int kEpiRows = 32, kEpiHP = 33;
+
+template <int TNB>
+struct EpiLds {
+    static constexpr int WP = 32 * TNB + 4;
+    static constexpr size_t floats = 32 * WP + (256 / kWave) * kEpiRows * kEpiHP;
+    static constexpr size_t bytes = floats * sizeof(float) + (256 / kWave) * kEpiRows * sizeof(int) +
+                                    (256 / kWave) * kEpiRows * 4 * sizeof(uint32_t);
+};
+
+template <int TNB>
+__device__ __forceinline__ void epi_load_weights(float* Wl, const float* __restrict__ W, int64_t ldw, int din, int dout) {
+    constexpr int WP = EpiLds<TNB>::WP;
+    for (int i = threadIdx.x; i < 32 * 32 * TNB; i += 256) {
+        const int k = i / (32 * TNB), n = i % (32 * TNB);
+        Wl[k * WP + n] = (k < din && n < dout) ? W[(int64_t)k * ldw + n] : 0.f;
+    }
+}
+
+// one wavefront: result rows of its 32 x 32 tile Ht (row ids in rid, -1 = no row) times Wl, written out
+template <int TNB>
+__device__ __forceinline__ void epi_tile(const float* Ht, const int* rid, uint32_t* wb, const float* Wl, int din, int dout,
+                                         float* __restrict__ C, int64_t ldc, float* __restrict__ F, int64_t ldf,
+                                         uint32_t* __restrict__ bits, int64_t ldbits, int lane) {
+    constexpr int WP = EpiLds<TNB>::WP;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int ks = (din + 1) / 2;
+    int rows[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) rows[r] = rid[8 * (r / 4) + 4 * lh + (r % 4)];
+#pragma unroll
+    for (int nb = 0; nb < TNB; ++nb) {
+        if (32 * nb >= dout) break;                                      // uniform
+        floatx16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll 4
+        for (int s2 = 0; s2 < ks; ++s2)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(Ht[l32 * kEpiHP + 2 * s2 + lh], Wl[(2 * s2 + lh) * WP + 32 * nb + l32], acc, 0, 0, 0);
+        const int n = 32 * nb + l32;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float v = acc[r];
+            if (rows[r] >= 0 && n < dout) {
+                if (C) __builtin_nontemporal_store(v, C + (int64_t)rows[r] * ldc + n);
+                if (F) __builtin_nontemporal_store(v > 0.f ? v : 0.f, F + (int64_t)rows[r] * ldf + n);
+            }
+            if (bits) {                                                   // 32 columns of two rows per ballot; columns >= dout give 0
+                const unsigned long long b = __ballot(v > 0.f && n < dout);
+                if (lane == 0) {
+                    const int t0 = 8 * (r / 4) + (r % 4);
+                    wb[t0 * 4 + nb] = (uint32_t)b;
+                    wb[(t0 + 4) * 4 + nb] = (uint32_t)(b >> 32);
+                }
+            }
+        }
+    }
+    if (bits) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int nw = (dout + 31) >> 5;
+        if (lane < kEpiRows && rid[lane] >= 0) {
+            uint32_t* dst = bits + (int64_t)rid[lane] * ldbits;
+            for (int j = 0; j < nw; ++j) dst[j] = wb[lane * 4 + j];
+        }
+    }
+}
+
+template <int TNB>
+__global__ __launch_bounds__(256) void k_spmm_subwave_combine(const int32_t* __restrict__ row_order, int64_t count,
+                                                              const int32_t* __restrict__ bptr, const int32_t* __restrict__ col,
+                                                              const float* __restrict__ val, const float* __restrict__ X, int64_t ldx,
+                                                              float* __restrict__ S, int64_t lds_, const float* __restrict__ W,
+                                                              int64_t ldw, int din, int dout, float* __restrict__ C, int64_t ldc,
+                                                              float* __restrict__ F, int64_t ldf, uint32_t* __restrict__ bits,
+                                                              int64_t ldbits) {
+    constexpr int G = 8, VW = 4, R = kWave / G;
+    extern __shared__ __align__(16) float epi_smem[];
+    float* Wl = epi_smem;
+    const int lane = threadIdx.x & (kWave - 1), wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    float* Ht = Wl + 32 * EpiLds<TNB>::WP + wv * (kEpiRows * kEpiHP);
+    int* rid = reinterpret_cast<int*>(Wl + EpiLds<TNB>::floats) + wv * kEpiRows;
+    uint32_t* wb = reinterpret_cast<uint32_t*>(reinterpret_cast<int*>(Wl + EpiLds<TNB>::floats) + (256 / kWave) * kEpiRows) + wv * kEpiRows * 4;
+    epi_load_weights<TNB>(Wl, W, ldw, din, dout);
+    __syncthreads();
+    const int c0 = (lane % G) * VW;
+    const bool active = c0 < din;
+    const int64_t stride = (int64_t)gridDim.x * (blockDim.x / kWave) * R;
+    int filled = 0;                                                      // trips in the tile so far (uniform)
+    for (int64_t base = ((int64_t)blockIdx.x * (blockDim.x / kWave) + wv) * R; base < count; base += stride) {
+        const int64_t slot = base + lane / G;
+        const bool valid = slot < count;
+        const int32_t row = valid ? row_order[slot] : -1;
+        const int64_t lo = valid ? bptr[slot] : 0, hi = valid ? bptr[slot + 1] : 0;
+        float acc[VW];
+#pragma unroll
+        for (int i = 0; i < VW; ++i) acc[i] = 0.f;
+        gather_staged<float, G, VW>(lo, hi, col, val, X + c0, ldx, active, lane, acc);
+        if (valid && active) store_vec<float, VW>(S + (int64_t)row * lds_ + c0, acc, din - c0);      // H itself (Eq. 2.1)
+        const int tr = filled * R + lane / G;
+#pragma unroll
+        for (int i = 0; i < VW; ++i) Ht[tr * kEpiHP + c0 + i] = c0 + i < din ? acc[i] : 0.f;   // beyond din a vector holds the row's padding
+        if (lane % G == 0) rid[tr] = row;
+        if (++filled == kEpiRows / R) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            epi_tile<TNB>(Ht, rid, wb, Wl, din, dout, C, ldc, F, ldf, bits, ldbits, lane);
+            __builtin_amdgcn_wave_barrier();
+            filled = 0;
+        }
+    }
+    if (filled > 0) {                                                    // a last, partial tile: the missing rows have no id
+        for (int t = filled * R + lane; t < kEpiRows; t += kWave) rid[t] = -1;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        epi_tile<TNB>(Ht, rid, wb, Wl, din, dout, C, ldc, F, ldf, bits, ldbits, lane);
+    }
+}
+
+// The same epilogue for listed rows whose H is already in memory (the rows summed from segments): one wavefront per
+// 32 rows of the list.
+template <int TNB>
+__global__ __launch_bounds__(256) void k_rows_combine(int64_t n_rows, const int32_t* __restrict__ list, const float* __restrict__ S,
+                                                      int64_t lds_, const float* __restrict__ W, int64_t ldw, int din, int dout,
+                                                      float* __restrict__ C, int64_t ldc, float* __restrict__ F, int64_t ldf,
+                                                      uint32_t* __restrict__ bits, int64_t ldbits) {
+    extern __shared__ __align__(16) float epi_smem[];
+    float* Wl = epi_smem;
+    const int lane = threadIdx.x & (kWave - 1), wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    float* Ht = Wl + 32 * EpiLds<TNB>::WP + wv * (kEpiRows * kEpiHP);
+    int* rid = reinterpret_cast<int*>(Wl + EpiLds<TNB>::floats) + wv * kEpiRows;
+    uint32_t* wb = reinterpret_cast<uint32_t*>(reinterpret_cast<int*>(Wl + EpiLds<TNB>::floats) + (256 / kWave) * kEpiRows) + wv * kEpiRows * 4;
+    epi_load_weights<TNB>(Wl, W, ldw, din, dout);
+    __syncthreads();
+    const int64_t q0 = ((int64_t)blockIdx.x * (blockDim.x / kWave) + wv) * kEpiRows;
+    if (q0 >= n_rows) return;                                            // uniform per wavefront
+    if (lane < kEpiRows) rid[lane] = q0 + lane < n_rows ? list[q0 + lane] : -1;
+    for (int i = lane; i < kEpiRows * 32; i += kWave) {
+        const int t = i / 32, k = i % 32;
+        const int64_t q = q0 + t;
+        Ht[t * kEpiHP + k] = (q < n_rows && k < din) ? S[(int64_t)list[q] * lds_ + k] : 0.f;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    epi_tile<TNB>(Ht, rid, wb, Wl, din, dout, C, ldc, F, ldf, bits, ldbits, lane);
+}
+
 // Where the partial sums of the segments go: the handle's own buffer (kPartFloats floats per segment, sized when the
 // handle was built), or memory the caller of launch_spmm brought (`given`, the allocation-free entry point: used as it
 // is, and nothing is timed there because the timer creates events).  Either way a product allocates nothing.
@@ -424,6 +581,52 @@ std::mutex g_static_mutex;
 float* g_static_ptr[kMaxDevices];       // per device ordinal, resolved with that device current
 
 }  // namespace
+
+bool spmm_combine_supported(const Orient& o, const void* X, int64_t ldx, const void* S, int64_t lds_, int64_t din, int64_t dout,
+                            plx_dtype dtype) {
+    return dtype == PLX_F32 && din > 16 && din <= 32 && dout > 0 && dout <= 128 && o.n_blocks == 1 && o.long_class == kSubwaveMaxClass + 1 &&
+           aligned_to(X, 16) && ldx % 4 == 0 && aligned_to(S, 16) && lds_ % 4 == 0;
+}
+
+plx_status launch_spmm_combine(plx_ctx* ctx, const Orient& o, const void* X, int64_t ldx, void* S, int64_t lds_, const float* W,
+                               int64_t ldw, int64_t din, int64_t dout, void* C, int64_t ldc, void* Fact, int64_t ldf, uint32_t* bits,
+                               int64_t ldbits) {
+    if (!spmm_combine_supported(o, X, ldx, S, lds_, din, dout, PLX_F32)) return fail(ctx, PLX_ERR_INTERNAL, "fused aggregation outside its range");
+    hipStream_t s = ctx->stream;
+    const float* x = static_cast<const float*>(X);
+    float* sp = static_cast<float*>(S);
+    float* c = static_cast<float*>(C);
+    float* f = static_cast<float*>(Fact);
+    const int tnb = (int)ceil_div(dout, 32);
+    const int64_t n_sub = o.off(0, kSubwaveMaxClass + 1) - o.off(0, 0);
+    char label[96];
+    snprintf(label, sizeof label, "<f32,d%lld,N%lld>[%s]", (long long)din, (long long)dout, o.tag ? "At" : "A");
+    auto launch = [&](auto tag) -> plx_status {
+        constexpr int TNB = decltype(tag)::value;
+        const size_t lds = EpiLds<TNB>::bytes;
+        if (n_sub > 0) {
+            KernelTimer kt(ctx, ctx->timing ? std::string("spmm_subwave_combine") + label : std::string());
+            const int64_t blocks = std::min<int64_t>(ceil_div(ceil_div(n_sub, 8), WPB), (int64_t)ctx->n_cu * PLX_SUB_PERSIST);
+            k_spmm_subwave_combine<TNB><<<dim3((unsigned)blocks), 256, lds, s>>>(o.row_order, n_sub, o.bptr, o.col, o.val, x, ldx, sp, lds_,
+                                                                                W, ldw, (int)din, (int)dout, c, ldc, f, ldf, bits, ldbits);
+        }
+        if (o.n_long > 0) {
+            Out<float> out{sp, lds_, nullptr, 0};
+            PLX_TRY((dispatch<float, 4, true>(ctx, o, 0, x, ldx, out, (int)din, o.part, ctx->timing)));   // segments, then the rows' sums
+            KernelTimer kt(ctx, ctx->timing ? std::string("rows_combine") + label : std::string());
+            k_rows_combine<TNB><<<dim3((unsigned)ceil_div(ceil_div(o.n_long, kEpiRows), WPB)), 256, lds, s>>>(
+                o.n_long, o.long_row, sp, lds_, W, ldw, (int)din, (int)dout, c, ldc, f, ldf, bits, ldbits);
+        }
+        PLX_HIP(ctx, hipGetLastError());
+        return PLX_OK;
+    };
+    switch (tnb) {
+        case 1: return launch(std::integral_constant<int, 1>{});
+        case 2: return launch(std::integral_constant<int, 2>{});
+        case 3: return launch(std::integral_constant<int, 3>{});
+        default: return launch(std::integral_constant<int, 4>{});
+    }
+}
 
 float* static_partials(plx_ctx* ctx, size_t* bytes) {
     if (bytes) *bytes = kStaticPartialsBytes;

@@ -1379,3 +1379,59 @@ def test_allocator_failure_is_reported_and_leaks_nothing():
             assert not live, f"{name}: {len(live)} buffers leaked when allocation {fail_from + 1} of {total} failed"
     L.plx_ctx_destroy(h)
     assert not live
+
+
+@pytest.mark.parametrize("din,dout,act", [(32, 128, "bits"), (32, 128, "relu"), (20, 47, "bits"), (32, 16, "none"), (17, 100, "relu"),
+                                          (24, 96, "bits")])
+def test_fused_aggregation_forward(din, dout, act):
+    """Aggregate-first forward with Eq. 2.2-2.3 in the epilogue of the sparse kernels (plx_ctx_set_fused_aggregation):
+    both row bins (lane-group rows, and rows summed from segments with the row-list epilogue), empty rows, a partial
+    last tile; against the oracle, and against the separate kernels (H bit-identical, results to rounding, sign words
+    exactly the packed [F > 0]); the backward call then runs on what the fused forward left."""
+    m, k = 1237, 3000
+    rowptr, col, val = random_block(m, k, 5 * din + dout, giant_row=33)
+    row, c64, v64 = coo_of(rowptr, col, val)
+    r = np.random.default_rng(din * dout)
+    X = r.standard_normal((k, din)).astype(np.float32)
+    W = (r.standard_normal((din, dout)) * 0.3).astype(np.float32)
+    Hagg = oracle.spmm_coo(m, row, c64, v64, X)
+    Q = oracle.gemm(Hagg, W)
+    actc = {"bits": plx.PLX_ACT_RELU_BITS, "relu": plx.PLX_ACT_RELU, "none": plx.PLX_ACT_NONE}[act]
+    dF = (r.standard_normal((m, dout)) * (np.abs(Q) > BAND32 * np.abs(Q).max())).astype(np.float32)
+    dQ = oracle.relu_bwd(Q, dF) if act != "none" else dF.astype(np.float64)
+    nw = (dout + 31) // 32
+    got = {}
+    for fused in (True, False):
+        c = plx.plx_ctx(0)
+        plx.plx_ctx_set_fused_aggregation(c, fused)
+        csr = plx.plx_csr_import(c, m, k, dev(rowptr), dev(col), dev(val))
+        (sub, wave, split), _ = plx.plx_csr_bins(csr, False)
+        assert sub > 0 and wave + split > 0
+        ws = torch.empty(plx.plx_gcn_layer_workspace(csr, False, din, dout, act=actc, order=plx.PLX_ORDER_AGG_FIRST), dtype=torch.uint8, device=DEV)
+        ld = -(-din // 4) * 4                                             # rows padded to 16 bytes, the padding holds NaN
+        Xd = torch.full((k, ld), float("nan"), device=DEV)[:, :din]; Xd.copy_(dev(X))
+        F = torch.full((m, dout), 7.0, device=DEV); saved = torch.full((m, ld), float("nan"), device=DEV)[:, :din]
+        words = torch.full((m, nw), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
+        plx.plx_timing_enable(c, True); plx.plx_timing_report(c)
+        plx.plx_gcn_layer_fwd(c, csr, False, Xd, dev(W), words if act == "bits" else None, F, saved, ws, act=actc,
+                              order=plx.PLX_ORDER_AGG_FIRST)
+        launched = plx.plx_timing_report(c); plx.plx_timing_enable(c, False)
+        assert any(n.startswith("spmm_subwave_combine") for n in launched) == fused, launched
+        assert any(n.startswith("rows_combine") for n in launched) == fused, launched
+        close(saved, Hagg, TOL32)
+        close(F, oracle.relu(Q) if act != "none" else Q, TOL32)
+        if act == "bits":
+            pos = (F > 0).cpu().numpy()
+            padded = np.zeros((m, 32 * nw), dtype=np.uint64); padded[:, :dout] = pos
+            want = (padded.reshape(m, nw, 32) << np.arange(32, dtype=np.uint64)).sum(axis=2).astype(np.uint32)
+            assert np.array_equal(words.cpu().numpy().view(np.uint32), want)
+        gdX = torch.empty(k, din, device=DEV); gdW = torch.empty(din, dout, device=DEV)
+        mask = {"bits": words, "relu": F, "none": None}[act]
+        plx.plx_gcn_layer_bwd(c, csr, False, Xd, dev(W), mask, dev(dF), saved, gdX, gdW, ws, act=actc, order=plx.PLX_ORDER_AGG_FIRST)
+        plx.plx_sync(c)
+        close(gdW, oracle.gemm(Hagg, dQ, ta=True), TOL32)
+        close(gdX, oracle.spmm_t_coo(k, row, c64, v64, oracle.gemm(dQ, W, tb=True)), TOL32)
+        got[fused] = (saved.cpu().numpy(), F.cpu().numpy())
+        csr.close(); c.close()
+    assert np.array_equal(got[True][0], got[False][0])                    # the aggregation itself: same kernel code, same bits
+    assert np.abs(got[True][1].astype(np.float64) - got[False][1]).max() <= 2e-6 * np.abs(got[False][1]).max()
