@@ -12,6 +12,10 @@ synthetic workloads (the paper's datasets are not available).  Each prints one J
       adjacency block has K/g columns, the dense operand keeps width 128) against V_g (full K,
       dense operand 128/g wide), g = 1, 4, 16, 64.
 
+  python studies.py skinny --launch-log DIR/<run>/launches.txt   (under rocprofv3 --pmc), then
+  python studies.py skinny-table --dir DIR
+      The same cases with hardware counters per case: HBM bytes read and written, L2 hit rate, wavefronts launched.
+
   python studies.py blocks [--scale 1.0]
       Blocked aggregation (Sec. 5.2) on the shard block: the forward product at width 32 and the
       transposed product (also width 32, as in the layer's backward pass) with the rows cut into 1, 2, 4, 8, 16, 32 blocks -- the
@@ -97,6 +101,7 @@ def skinny(args):
     ctx = plx.plx_ctx(0)
     m, k, samples, width = 2_000_000, 8_000_000, 64_000_000, 128
     out = {"study": "tall-skinny sensitivity at equal flops (Table 2 analogue)", "m": m, "k": k, "cases": []}
+    log = open(args.launch_log, "w") if args.launch_log else None       # profiler runs: ONE product per case, its launches named
     for g in (1, 4, 16, 64):
         for label, kk, ss, d in (("U", k // g, samples // g, width), ("V", k, samples, width // g)):
             if g == 1 and label == "V":
@@ -105,6 +110,15 @@ def skinny(args):
             csr = plx.plx_csr_import(ctx, m, kk, rowptr, col, val)
             X = synth.normal(7, synth.S_FEAT, kk, d, DEV)
             Y = torch.empty(m, d, device=DEV)
+            if log:
+                plx.plx_timing_enable(ctx, True)
+                plx.plx_spmm(ctx, csr, X, Y)
+                for name, ms in plx.plx_timing_trace(ctx):
+                    log.write(f"{label}_{g} {name} {ms:.4f}\n")
+                plx.plx_timing_enable(ctx, False)
+                csr.close()
+                del rowptr, col, val, X, Y
+                continue
             ms = time_spmm(ctx, csr, X, Y)
             out["cases"].append({"config": f"{label}_{g}", "cols": kk, "nnz": csr.nnz, "width": d,
                                  "GFLOP": round(2 * csr.nnz * d / 1e9, 2), "spmm_ms": round(ms, 3),
@@ -112,7 +126,54 @@ def skinny(args):
                                  "algorithmic_GBps": round(spmm_bytes(csr, d) / ms / 1e6, 1)})
             csr.close()
             del rowptr, col, val, X, Y
+    if log:
+        log.close()
+        return
     print(json.dumps(out))
+
+
+def skinny_table(args):
+    """Table 2 analogue from profiler output: DIR/a and DIR/b hold `rocprofv3 --pmc ... --kernel-include-regex k_spmm` runs of
+    `studies.py skinny --launch-log DIR/<run>/launches.txt` (a: FETCH_SIZE SQ_WAVES, b: WRITE_SIZE TCC_HIT_sum TCC_MISS_sum)."""
+    import csv
+    import glob
+    import re
+    d = args.dir
+    per_case = {}
+    for run in ("a", "b"):
+        f = glob.glob(os.path.join(d, run, "**", "*counter_collection.csv"), recursive=True)[0]
+        disp = {}
+        for r in csv.DictReader(open(f)):
+            if "k_spmm" not in r["Kernel_Name"]:
+                continue
+            e = disp.setdefault(int(r["Dispatch_Id"]), {"kernel": re.sub(r".*(k_spmm_\w+).*", r"\1", r["Kernel_Name"]), "grid": int(r["Grid_Size"])})
+            e[r["Counter_Name"]] = float(r["Counter_Value"])
+        disp = [disp[i] for i in sorted(disp)]
+        i = 0
+        for line in open(os.path.join(d, run, "launches.txt")):
+            case, name, ms = line.split()
+            n = 2 if name.startswith("spmm_split") else 1           # segment + combine kernels
+            c = per_case.setdefault(case, {"ms": 0.0, "grid": 0})
+            if run == "a":
+                c["ms"] += float(ms)
+            for e in disp[i:i + n]:
+                kind = name.split("<")[0].replace("spmm_", "")
+                assert {"subwave": "k_spmm_subwave", "wave": "k_spmm_wave", "split": "k_spmm_"}[kind] in e["kernel"], (case, name, e)
+                for k_, v in e.items():
+                    if k_ not in ("kernel", "grid"):
+                        c[k_] = c.get(k_, 0.0) + v
+                if run == "a":
+                    c["grid"] += e["grid"]
+            i += n
+        assert i == len(disp), (run, i, len(disp))
+    print("| case | ms (one product, under the profiler) | HBM read GB | HBM written GB | HBM GB/s | % of 8 TB/s | L2 hit % | wavefronts | work-items launched |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for case, c in per_case.items():
+        rd, wr = c["FETCH_SIZE"] * 1024 * 2.0, c["WRITE_SIZE"] * 1024          # FETCH_SIZE counts half of what a plain copy reads
+        hit = c["TCC_HIT_sum"] / max(c["TCC_HIT_sum"] + c["TCC_MISS_sum"], 1.0)
+        bw = (rd + wr) / c["ms"] / 1e6
+        print(f"| {case} | {c['ms']:.3f} | {rd / 1e9:.2f} | {wr / 1e9:.2f} | {bw:.0f} | {bw / 80:.0f} | {hit * 100:.0f} | "
+              f"{int(c['SQ_WAVES'])} | {c['grid']} |")
 
 
 def blocks(args):
@@ -190,10 +251,14 @@ def windows(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["balance", "skinny", "blocks", "windows"])
+    ap.add_argument("study", choices=["balance", "skinny", "skinny-table", "blocks", "windows"])
+    ap.add_argument("--launch-log", default="", help="skinny: run ONE product per case and write its timed launches here (profiler runs)")
+    ap.add_argument("--dir", default="", help="skinny-table: directory with the profiler output")
     ap.add_argument("--workload", default="road", choices=["tiny", "social", "copurchase", "road", "shard"])
     ap.add_argument("--scale", type=float, default=1.0)
     args = ap.parse_args()
+    if args.study == "skinny-table":
+        return skinny_table(args)
     assert torch.cuda.is_available(), "studies.py needs a GPU"
     torch.cuda.set_device(DEV)
     {"balance": balance, "skinny": skinny, "blocks": blocks, "windows": windows}[args.study](args)
