@@ -343,6 +343,11 @@ __device__ __forceinline__ void commit_split(bf16_t* dst, const TileRegs<TR, COL
 #ifndef PLX_X3_BWD_WAVES
 #define PLX_X3_BWD_WAVES 2
 #endif
+// Wavefronts per SIMD the register allocation aims at.  The 64 x 128 kernel with a factored gradient fits three with
+// five spilled registers and gains 3.5 % from the third wavefront (road network, 50 M rows); the 128-wide kernels would
+// spill over a hundred registers at three (measured 2.2 times slower) and stay at two.
+constexpr int x3_bwd_waves(int tmb, int tnb, int dns) { return (tmb == 2 && tnb == 4 && dns == 1) ? 3 : PLX_X3_BWD_WAVES; }
+
 // DNS > 0: the gradient arrives in factored form, Q = Gf Wn^T with Gf[R x dn] and Wn[N x dn], dn <= 16*DNS (the
 // following combine-first layer's A^T dZ and its weights, Eq. 2.6 of that layer; DNS <= 2): the 32 x N tile of Q is formed
 // here, by the same split products, and goes straight to LDS, so the R x N gradient is neither written by
@@ -350,7 +355,7 @@ __device__ __forceinline__ void commit_split(bf16_t* dst, const TileRegs<TR, COL
 // leaves a lane with four consecutive columns of one row per group of accumulator registers: the layout
 // the masking and the split already work on.  Mask: none or sign bits.
 template <int TMB, int TNB, int MASK, int DNS>   // 64 <= Mp <= 32*TMB, 64 <= N <= 32*TNB (TMB, TNB in {2, 4}); 16-byte aligned rows
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PLX_X3_BWD_WAVES))) void k_bwd_dense_x3(int64_t R, int Mp, int N, const float* __restrict__ P, int64_t ldp,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(x3_bwd_waves(TMB, TNB, DNS)))) void k_bwd_dense_x3(int64_t R, int Mp, int N, const float* __restrict__ P, int64_t ldp,
                                                       const float* __restrict__ Q, int64_t ldq,
                                                       const float* __restrict__ Zm, int64_t ldz,
                                                       const float* __restrict__ W, int64_t ldw,
