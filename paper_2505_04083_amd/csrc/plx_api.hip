@@ -473,6 +473,8 @@ plx_status layer_fwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const v
     PLX_TRY(layer_common_checks(ctx, csr, din, dout, dtype, act, order));
     const Orient& a = csr->o[transposed_A ? 1 : 0];
     order = resolve_order(order, din, dout);
+    if (a.rows == 0 && a.cols == 0)        // the adjacency of a graph without nodes: no matrix of the layer has a row (pointers may be NULL)
+        return ctx->dry ? fail(ctx, PLX_ERR_DEVICE, "validate-only context") : PLX_OK;
     if (var.T) {
         if (var.ldt < dout) return fail(ctx, PLX_ERR_SHAPE, "ldt smaller than dout");
     } else if (!H || !W) {
@@ -625,6 +627,11 @@ plx_status layer_bwd(plx_ctx* ctx, const plx_csr* csr, int transposed_A, const v
     const Orient& a = csr->o[t];
     const Orient& at = csr->o[1 - t];   // the transpose of the layer's adjacency
     order = resolve_order(order, din, dout);
+    if (a.rows == 0 && a.cols == 0) {      // a graph without nodes: only dW exists, and it is zero
+        if (!dW || lddw < dout) return fail(ctx, !dW ? PLX_ERR_INVALID : PLX_ERR_SHAPE, "dW is NULL or lddw smaller than dout");
+        if (ctx->dry) return fail(ctx, PLX_ERR_DEVICE, "validate-only context");
+        return launch_zero(ctx, din, dout, dW, lddw, sizeof(float));
+    }
     if (var.dT) {
         if (order != PLX_ORDER_COMBINE_FIRST) return fail(ctx, PLX_ERR_INVALID, "the gradient of H W exists only in combine-first order");
         if (var.lddt < dout) return fail(ctx, PLX_ERR_SHAPE, "lddt smaller than dout");

@@ -1435,3 +1435,41 @@ def test_fused_aggregation_forward(din, dout, act):
         csr.close(); c.close()
     assert np.array_equal(got[True][0], got[False][0])                    # the aggregation itself: same kernel code, same bits
     assert np.abs(got[True][1].astype(np.float64) - got[False][1]).max() <= 2e-6 * np.abs(got[False][1]).max()
+
+
+def test_layers_on_an_adjacency_without_entries_or_without_nodes(ctx):
+    """A block with rows and columns but no stored entry: A H = 0, so the forward outputs (values, sign words, the
+    aggregation, the following layer's T) are zero and so is every gradient; nothing is launched with an empty grid.
+    A graph without nodes: the layer calls succeed and dW is zero."""
+    m, k, din, dout, dn = 5, 7, 64, 128, 16
+    csr = plx.plx_csr_import(ctx, m, k, dev(np.zeros(m + 1, np.int64)), dev(np.zeros(0, np.int32)), dev(np.zeros(0, np.float32)))
+    for order in (plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_COMBINE_FIRST):
+        H = torch.randn(k, din, device=DEV); W = torch.randn(din, dout, device=DEV); Wn = torch.randn(dout, dn, device=DEV)
+        ws = torch.empty(max(1, plx.plx_gcn_layer_bwd_chained_workspace(ctx, csr, False, din, dout, dn, act=plx.PLX_ACT_RELU_BITS, order=order)),
+                         dtype=torch.uint8, device=DEV)
+        F = torch.full((m, dout), 7.0, device=DEV); saved = torch.full((m, din), 7.0, device=DEV); T = torch.full((m, dn), 7.0, device=DEV)
+        words = torch.full((m, 4), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
+        plx.plx_gcn_layer_fwd_chained(ctx, csr, False, H, W, words, F, saved, Wn, T, ws, act=plx.PLX_ACT_RELU_BITS, order=order)
+        plx.plx_sync(ctx)
+        assert float(F.abs().max()) == 0 and float(T.abs().max()) == 0 and int(words.abs().max()) == 0
+        if order == plx.PLX_ORDER_AGG_FIRST:
+            assert float(saved.abs().max()) == 0
+        dH = torch.full((k, din), 7.0, device=DEV); dW = torch.full((din, dout), 7.0, device=DEV)
+        plx.plx_gcn_layer_bwd(ctx, csr, False, H, W, words, torch.randn(m, dout, device=DEV), saved, dH, dW, ws, act=plx.PLX_ACT_RELU_BITS, order=order)
+        plx.plx_sync(ctx)
+        assert float(dH.abs().max()) == 0 and float(dW.abs().max()) == 0
+    Y = torch.full((m, 8), 7.0, device=DEV)
+    plx.plx_spmm(ctx, csr, torch.randn(k, 8, device=DEV), Y); plx.plx_sync(ctx)
+    assert float(Y.abs().max()) == 0
+    csr.close()
+    e = torch.zeros(0, dtype=torch.int64, device=DEV)
+    none = plx.plx_build_csr(ctx, 0, e, e)
+    assert none.nnz == 0 and none.m == 0
+    W = torch.randn(din, dout, device=DEV); dW = torch.full((din, dout), 7.0, device=DEV)
+    z = lambda c, t=torch.float32: torch.empty(0, c, dtype=t, device=DEV)
+    ws = torch.empty(256, dtype=torch.uint8, device=DEV)
+    plx.plx_gcn_layer_fwd(ctx, none, False, z(din), W, None, z(dout), z(din), ws)
+    plx.plx_gcn_layer_bwd(ctx, none, False, z(din), W, z(dout), z(dout), z(din), z(din), dW, ws)
+    plx.plx_sync(ctx)
+    assert float(dW.abs().max()) == 0
+    none.close()
