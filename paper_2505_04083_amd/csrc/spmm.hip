@@ -489,7 +489,12 @@ plx_status run_short(plx_ctx* ctx, const Orient& o, int blk, const T* X, int64_t
         constexpr int R = kWave / G;
         int64_t blocks = ceil_div(ceil_div(n_sub, R), WPB);
 #if PLX_SUB_PERSIST
-        blocks = std::min<int64_t>(blocks, (int64_t)ctx->n_cu * PLX_SUB_PERSIST);
+        // A persistent grid evens out rows of unequal length (a power-law bin holds rows of 1 to 255 entries).  Where
+        // practically every row fits one trip of 8 entries (a road-like graph: fewer than 1 in 1000 rows is longer) there
+        // is nothing to even out and one row per group of lanes is faster (road network: -5 to -12 % on its four
+        // short-row launches; the shard's bins, with 10 % longer rows, lose 15 - 24 % that way and keep the persistent grid).
+        const int64_t n_longer = o.off(blk, kSubwaveMaxClass + 1) - o.off(blk, 4);      // rows of 8 and more entries
+        if (n_longer * 1000 >= n_sub) blocks = std::min<int64_t>(blocks, (int64_t)ctx->n_cu * PLX_SUB_PERSIST);
 #endif
         k_spmm_subwave<T, G, VW><<<dim3((unsigned)blocks), 256, 0, s>>>(o.row_order + s0, n_sub, o.bptr + s0, o.col, o.val, X,
                                                                          ldx, out, d);

@@ -91,3 +91,34 @@ def test_static_buffer_limit_is_an_error_before_any_work():
     plx.plx_sync(ctx)
     assert torch.equal(Yn, Yr)
     csr.close(); ctx.close()
+
+
+def test_static_buffer_call_recorded_into_a_hip_graph():
+    """What the entry point is for: a caller under HIP graph capture.  Both orientations of a block with split rows are
+    recorded (nothing is allocated while recording), the graph is replayed with eager work and synchronisations in
+    between, and every replay equals the eager plx_spmm / plx_spmm_t results bit for bit."""
+    side = torch.cuda.Stream(device=DEV)
+    ctx = plx.plx_ctx(0, stream=side.cuda_stream)
+    m, k, d = 2000, 9000, 48
+    rowptr, col, val = block(m, k, 21, 150)
+    t = lambda a: torch.as_tensor(a).to(DEV).contiguous()
+    csr = plx.plx_csr_import(ctx, m, k, t(rowptr), t(col), t(val))
+    X = torch.randn(k, d, device=DEV); G = torch.randn(m, d, device=DEV)
+    Y = torch.empty(m, d, device=DEV); Yt = torch.empty(k, d, device=DEV)
+    Ys = torch.empty(m, d, device=DEV); Yts = torch.empty(k, d, device=DEV)
+    torch.cuda.synchronize()
+    plx.plx_spmm(ctx, csr, X, Y); plx.plx_spmm_t(ctx, csr, G, Yt); plx.plx_sync(ctx)
+    live, allocated = len(ctx._live), torch.cuda.memory_allocated()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side, capture_error_mode="thread_local"):
+        plx.plx_spmm_static(ctx, csr, False, X, Ys)
+        plx.plx_spmm_static(ctx, csr, True, G, Yts)
+    assert len(ctx._live) == live and torch.cuda.memory_allocated() == allocated
+    for rep in range(3):
+        Ys.fill_(float("nan")); Yts.fill_(float("nan"))                 # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Ys, Y) and torch.equal(Yts, Yt), f"replay {rep}"
+    del graph
+    csr.close(); ctx.close()
