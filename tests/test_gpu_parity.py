@@ -163,6 +163,39 @@ def test_import_transpose_bit_exact(ctx):
         assert err.value.status == plx.PLX_ERR_INVALID
 
 
+def test_timing_trace_lists_launches_in_order(ctx):
+    """plx_timing_trace: one line per timed launch, in launch order; the aggregated report of the same calls has the
+    same names and counts; a buffer too small for all lines is an error, and either call clears the record."""
+    import ctypes
+    n = 3000
+    src, dst = synth.rmat_edges(3, n, 20000)
+    csr = plx.plx_build_csr(ctx, n, dev(src), dev(dst))
+    X = torch.randn(n, 16, device=DEV); Y = torch.empty(n, 16, device=DEV)
+    A = torch.randn(n, 40, device=DEV); B = torch.randn(40, 24, device=DEV); C = torch.empty(n, 24, device=DEV)
+    def calls():
+        plx.plx_spmm(ctx, csr, X, Y)
+        plx.plx_gemm_nn(ctx, A, B, C)
+        plx.plx_spmm_t(ctx, csr, X, Y)
+    plx.plx_sync(ctx); plx.plx_timing_enable(ctx, True); plx.plx_timing_report(ctx)
+    calls()
+    trace = plx.plx_timing_trace(ctx)
+    names = [name for name, _ in trace]
+    g = [i for i, name in enumerate(names) if name.startswith("gemm_nn")]
+    assert len(g) == 1 and 0 < g[0] < len(names) - 1                       # the dense product between the two sparse ones
+    assert all(name.startswith("spmm_") and name.endswith("[A]") for name in names[:g[0]])
+    assert all(name.startswith("spmm_") and name.endswith("[At]") for name in names[g[0] + 1:])
+    assert all(ms > 0 for _, ms in trace)
+    assert plx.plx_timing_trace(ctx) == []                                  # cleared
+    calls()
+    report = plx.plx_timing_report(ctx)
+    assert {name: names.count(name) for name in names} == {name: cnt for name, (cnt, _) in report.items()}
+    calls()
+    small = ctypes.create_string_buffer(8)
+    assert plx._lib.plx_timing_trace(ctx.handle, small, len(small)) == plx.PLX_ERR_SHAPE
+    plx.plx_timing_report(ctx); plx.plx_timing_enable(ctx, False)
+    csr.close()
+
+
 @pytest.mark.parametrize("d,pad", [(1, 0), (2, 0), (4, 0), (8, 0), (8, 1), (16, 0), (32, 0), (41, 0), (41, 3), (47, 1), (64, 0), (100, 0),
                                    (128, 0), (128, 4), (300, 0), (30, 2)])
 def test_spmm_and_transpose_parity(ctx, d, pad):
