@@ -77,6 +77,9 @@ def parse():
     ap.add_argument("--fused-aggregation", action="store_true",
                     help="aggregate-first forward with the combination in the sparse kernels' epilogue (a measured alternative, off by default)")
     ap.add_argument("--windows", type=int, default=0, help="column windows of the sparse product (0 = the library's default)")
+    ap.add_argument("--no-input-grad", action="store_true",
+                    help="graph workloads only: leave out the gradient with respect to the input features (Eq. 2.6-2.7 of the "
+                         "first layer, which no weight update needs); NOT the headline configuration, named in config.workload")
     ap.add_argument("--graph", action="store_true",
                     help="graph workloads only: also record the step into a HIP graph and time K replays (graph_ms_per_step)")
     ap.add_argument("--copy-ref", action="store_true",
@@ -416,14 +419,15 @@ def main():
         H0.copy_(synth.normal(cfg.seed, synth.S_FEAT, cfg.n, cfg.dims[0], dev, tdt))
         Ws = cfg.weights(dev)
         y = cfg.labels(dev)
-        net = GcnNetwork(ctx, csr, Ws, dtype=tdt, sign_bits=args.mask == "bits")
+        net = GcnNetwork(ctx, csr, Ws, dtype=tdt, sign_bits=args.mask == "bits", input_grad=not args.no_input_grad)
 
         def step():
             net.step(H0, y)
 
         idx = {"tiny": 0, "social": 1, "copurchase": 2, "road": 4, "road_full": 4}[args.workload]
         workload = (f"configs[{idx}]: {args.workload} graph, {args.dtype}, {len(Ws)}-layer GCN "
-                    + "-".join(map(str, cfg.dims)) + ", whole forward + backward with loss head, AUTO order")
+                    + "-".join(map(str, cfg.dims)) + ", whole forward + backward with loss head, AUTO order"
+                    + (", WITHOUT the gradient of the input features" if args.no_input_grad else ""))
         unit = f"ms per {len(Ws)}-layer network fwd+bwd"
         shape = {"n": cfg.n, "dims": cfg.dims}
     if args.scale != 1.0:

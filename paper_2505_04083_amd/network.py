@@ -34,7 +34,9 @@ def aligned_rows(rows: int, cols: int, dtype, dev) -> torch.Tensor:
 
 class GcnNetwork:
     def __init__(self, ctx, csr, Ws: List[torch.Tensor], dtype=torch.float32, order: int = PLX_ORDER_AUTO,
-                 keep_preactivation: bool = False, sign_bits: bool = True, chain: bool = True):
+                 keep_preactivation: bool = False, sign_bits: bool = True, chain: bool = True, input_grad: bool = True):
+        """input_grad=False: the gradient with respect to the network's input features (Eq. 2.6-2.7 of the first layer,
+        which no weight update needs) is not formed; dH[0] is then None and every dW is unchanged."""
         self.ctx, self.csr, self.Ws, self.order = ctx, csr, Ws, order
         self.L = len(Ws)
         dev = Ws[0].device
@@ -87,7 +89,7 @@ class GcnNetwork:
             self.F.append(None if last else aligned_rows(rows, dout, dtype, dev))
             self.saved.append(aligned_rows(rows if agg[l] else 1, din, dtype, dev))
             hands_dt = l > 0 and self.chained[l - 1]             # then dH[l] is never formed: dT[l] goes to layer l-1
-            self.dH.append(None if hands_dt else aligned_rows(cols, din, dtype, dev))
+            self.dH.append(None if (hands_dt or (l == 0 and not input_grad)) else aligned_rows(cols, din, dtype, dev))
             self.dT.append(aligned_rows(cols, dout, dtype, dev) if hands_dt else None)
             self.T.append(aligned_rows(cols, dout, dtype, dev) if (l > 0 and self.fwd_chained[l - 1]) else None)
             self.dW.append(torch.empty(din, dout, dtype=torch.float32, device=dev))

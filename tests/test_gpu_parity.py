@@ -522,6 +522,40 @@ def test_three_layer_network_as_the_bench_runs_it(ctx):
         assert rel_err(nets[0].dW[l], nets[1].dW[l].double().cpu().numpy()) <= 2e-5
 
 
+@pytest.mark.parametrize("dims", [(128, 128, 128, 16), (64, 128, 16), (200, 64, 10)])
+def test_network_without_the_input_feature_gradient(ctx, dims):
+    """GcnNetwork(input_grad=False) leaves out Eq. 2.6-2.7 of the first layer only: logits, loss and every dW are those of
+    the full backward pass bit for bit (the same kernels form them), dW also agrees with the oracle, and dH[0] does not
+    exist.  The shapes cover a first layer in aggregate-first order with and without the chained kernel behind it
+    (64-128-16 is the road network's: its fused backward kernel then runs without its Eq. 2.6 product) and one in
+    combine-first order (200 -> 64)."""
+    from paper_2505_04083_amd.network import GcnNetwork
+    n = 3000
+    src, dst = synth.rmat_edges(11, n, 24000)
+    g = torch.Generator().manual_seed(5)
+    pr, pc = torch.randperm(n, generator=g), torch.randperm(n, generator=g)
+    F0 = torch.randn(n, dims[0], generator=g)
+    Ws = [torch.randn(dims[l], dims[l + 1], generator=g) / dims[l] ** 0.5 for l in range(len(dims) - 1)]
+    y = torch.randint(0, dims[-1], (n,), generator=g)
+    adj = oracle.adjacency(n, src.numpy(), dst.numpy())
+    ref = ogcn.forward_backward(adj, F0.numpy(), [w.numpy() for w in Ws], y.numpy())
+    csr = plx.plx_build_csr(ctx, n, dev(src), dev(dst), dev(pr), dev(pc))
+    H0 = torch.empty_like(F0); H0[pc] = F0
+    L = len(Ws)
+    y_gpu = torch.empty_like(y); y_gpu[pr if (L - 1) % 2 == 0 else pc] = y
+    full = GcnNetwork(ctx, csr, [dev(w) for w in Ws])
+    lean = GcnNetwork(ctx, csr, [dev(w) for w in Ws], input_grad=False)
+    for net in (full, lean):
+        net.step(dev(H0), dev(y_gpu)); net.sync()
+    assert lean.dH[0] is None and full.dH[0] is not None
+    assert torch.equal(lean.Z[-1], full.Z[-1]) and lean.loss.item() == full.loss.item()
+    for l in range(L):
+        assert torch.equal(lean.dW[l], full.dW[l]), f"dW of layer {l}"
+        close(lean.dW[l], ref.dW[l], TOL32)
+    close(full.dH[0][dev(pc)], ref.dF[0], TOL32)
+    csr.close()
+
+
 def test_layer_on_rectangular_block_both_orders(ctx):
     """One layer on an imported rectangular block (the shape of configs[3], shrunk): forward
     and backward in both multiplication orders against the oracle's Eq. 2.1-2.7."""
