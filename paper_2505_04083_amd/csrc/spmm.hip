@@ -108,10 +108,16 @@ __device__ __forceinline__ void emit(const Out<T>& o, int64_t row, int c0, float
 #ifndef PLX_SPMM_UNROLL
 #define PLX_SPMM_UNROLL 8
 #endif
-constexpr int kUnroll = PLX_SPMM_UNROLL;
+#ifndef PLX_SPMM_UNROLL_WIDE
+#define PLX_SPMM_UNROLL_WIDE 4
+#endif
+// Gathers a lane keeps in flight per trip.  Their rows wait in registers as VW floats each: 8 x 4 for fp32 and 4 x 8 for
+// bf16 are the same 32 registers (8 x 8 leaves a bf16 kernel with too few resident wavefronts: measured 7-25 % slower on
+// the segment kernels and on the staged short-row kernel of every workload).
+template <int VW> constexpr int gathers_per_trip() { return VW > 4 ? PLX_SPMM_UNROLL_WIDE : PLX_SPMM_UNROLL; }
 
-// acc += sum over entries e = first, first + stride, ... < hi of val[e] * X[col[e], c0 .. c0+VW)
-template <typename T, int VW>
+// acc += sum over entries e = first, first + stride, ... < hi of val[e] * X[col[e], c0 .. c0+VW), kUnroll gathers per trip
+template <typename T, int VW, int kUnroll = gathers_per_trip<VW>()>
 __device__ __forceinline__ void gather_accumulate(int64_t first, int64_t hi, int64_t stride,
                                                   const int32_t* __restrict__ col, const float* __restrict__ val,
                                                   const T* __restrict__ xb, int64_t ldx, float (&acc)[VW]) {
@@ -174,7 +180,7 @@ template <typename T, int G, int VW>
 __device__ __forceinline__ void gather_staged(int64_t lo, int64_t hi, const int32_t* __restrict__ col,
                                               const float* __restrict__ val, const T* __restrict__ xb, int64_t ldx,
                                               bool active, int lane, float (&acc)[VW]) {
-    constexpr int CH = G < 8 ? G : 8;
+    constexpr int CH = G < gathers_per_trip<VW>() ? G : gathers_per_trip<VW>();
     const int j = lane % G, gbase = lane - j;
     for (int64_t e = lo; e < hi; e += CH) {
         const int n = (hi - e) < CH ? (int)(hi - e) : CH;
@@ -226,7 +232,7 @@ __global__ __launch_bounds__(256) void k_spmm_subwave(const int32_t* __restrict_
         for (int i = 0; i < VW; ++i) acc[i] = 0.f;
 #if PLX_SUB_STAGED
         if constexpr (G >= 8) gather_staged<T, G, VW>(lo, hi, col, val, X + c0, ldx, active, lane, acc);
-        else if (active) gather_accumulate<T, VW>(lo, hi, 1, col, val, X + c0, ldx, acc);
+        else if (active) gather_accumulate<T, VW, PLX_SPMM_UNROLL>(lo, hi, 1, col, val, X + c0, ldx, acc);   // narrow rows (G < 8): 8 per trip measured better for either type
 #else
         if (active) gather_accumulate<T, VW>(lo, hi, 1, col, val, X + c0, ldx, acc);
 #endif
