@@ -52,16 +52,32 @@ template <> struct Ext<4> { typedef uint32_t type; };
 template <> struct Ext<8> { typedef uint32_t type __attribute__((ext_vector_type(2))); };
 template <> struct Ext<16> { typedef uint32_t type __attribute__((ext_vector_type(4))); };
 
-// load VW consecutive elements as one transaction and widen to fp32
+// Gathered rows wait in registers as they were loaded (a bf16 row of 8 is 4 registers, not 8 floats): one transaction
+// now, widened and accumulated when the row is used.
+template <typename T, int VW> struct RowRegs { typename Raw<sizeof(T) * VW>::type raw; };
 template <typename T, int VW>
-__device__ __forceinline__ void load_vec(const T* p, float (&r)[VW]) {
-    typedef typename Raw<sizeof(T) * VW>::type raw_t;
-    union { raw_t raw; T e[VW]; } u;
-    u.raw = *reinterpret_cast<const raw_t*>(p);
+__device__ __forceinline__ RowRegs<T, VW> load_row(const T* p) {
+    RowRegs<T, VW> r;
+    r.raw = *reinterpret_cast<const typename Raw<sizeof(T) * VW>::type*>(p);
+    return r;
+}
+template <typename T, int VW>
+__device__ __forceinline__ RowRegs<T, VW> zero_row() {
+    RowRegs<T, VW> r;
+    union { typename Raw<sizeof(T) * VW>::type raw; T e[VW]; } u;
+#pragma unroll
+    for (int i = 0; i < VW; ++i) u.e[i] = T(0);
+    r.raw = u.raw;
+    return r;
+}
+template <typename T, int VW>
+__device__ __forceinline__ void fma_row(float v, const RowRegs<T, VW>& r, float (&acc)[VW]) {
+    union { typename Raw<sizeof(T) * VW>::type raw; T e[VW]; } u;
+    u.raw = r.raw;
 #pragma unroll
     for (int i = 0; i < VW; ++i) {
-        if constexpr (sizeof(T) == 4) r[i] = u.e[i];
-        else r[i] = bf16_to_f32(u.e[i]);
+        if constexpr (sizeof(T) == 4) acc[i] = fmaf(v, u.e[i], acc[i]);
+        else acc[i] = fmaf(v, bf16_to_f32(u.e[i]), acc[i]);
     }
 }
 
@@ -127,13 +143,11 @@ __device__ __forceinline__ void gather_accumulate(int64_t first, int64_t hi, int
         float v[kUnroll];
 #pragma unroll
         for (int t = 0; t < kUnroll; ++t) { c[t] = col[e + t * stride]; v[t] = val[e + t * stride]; }
-        float x[kUnroll][VW];
+        RowRegs<T, VW> x[kUnroll];
 #pragma unroll
-        for (int t = 0; t < kUnroll; ++t) load_vec<T, VW>(xb + (int64_t)c[t] * ldx, x[t]);
+        for (int t = 0; t < kUnroll; ++t) x[t] = load_row<T, VW>(xb + (int64_t)c[t] * ldx);
 #pragma unroll
-        for (int t = 0; t < kUnroll; ++t)
-#pragma unroll
-            for (int i = 0; i < VW; ++i) acc[i] = fmaf(v[t], x[t][i], acc[i]);
+        for (int t = 0; t < kUnroll; ++t) fma_row<T, VW>(v[t], x[t], acc);
     }
     if (e < hi) {
         // what is left is fewer than kUnroll entries: one more trip with the missing ones masked off, so that the
@@ -148,20 +162,11 @@ __device__ __forceinline__ void gather_accumulate(int64_t first, int64_t hi, int
             c[t] = ok[t] ? col[idx] : 0;
             v[t] = ok[t] ? val[idx] : 0.f;
         }
-        float x[kUnroll][VW];
+        RowRegs<T, VW> x[kUnroll];
 #pragma unroll
-        for (int t = 0; t < kUnroll; ++t) {
-            if (ok[t]) {
-                load_vec<T, VW>(xb + (int64_t)c[t] * ldx, x[t]);
-            } else {
+        for (int t = 0; t < kUnroll; ++t) x[t] = ok[t] ? load_row<T, VW>(xb + (int64_t)c[t] * ldx) : zero_row<T, VW>();
 #pragma unroll
-                for (int i = 0; i < VW; ++i) x[t][i] = 0.f;
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < kUnroll; ++t)
-#pragma unroll
-            for (int i = 0; i < VW; ++i) acc[i] = fmaf(v[t], x[t][i], acc[i]);
+        for (int t = 0; t < kUnroll; ++t) fma_row<T, VW>(v[t], x[t], acc);
     }
 }
 
@@ -191,20 +196,11 @@ __device__ __forceinline__ void gather_staged(int64_t lo, int64_t hi, const int3
         float v[CH];
 #pragma unroll
         for (int t = 0; t < CH; ++t) { c[t] = __shfl(cj, gbase + t, kWave); v[t] = __shfl(vj, gbase + t, kWave); }
-        float x[CH][VW];
+        RowRegs<T, VW> x[CH];
 #pragma unroll
-        for (int t = 0; t < CH; ++t) {
-            if (active && t < n) {
-                load_vec<T, VW>(xb + (int64_t)c[t] * ldx, x[t]);
-            } else {
+        for (int t = 0; t < CH; ++t) x[t] = (active && t < n) ? load_row<T, VW>(xb + (int64_t)c[t] * ldx) : zero_row<T, VW>();
 #pragma unroll
-                for (int i = 0; i < VW; ++i) x[t][i] = 0.f;
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < CH; ++t)
-#pragma unroll
-            for (int i = 0; i < VW; ++i) acc[i] = fmaf(v[t], x[t][i], acc[i]);
+        for (int t = 0; t < CH; ++t) fma_row<T, VW>(v[t], x[t], acc);
     }
 }
 
