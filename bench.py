@@ -269,6 +269,11 @@ def read_dispatches(path, value_col=None):
     return [(s, v) for _, s, v in rows], (ref[len(ref) // 2] if len(ref) == 4 else None)
 
 
+def newest(files):
+    """A directory that several profiler runs wrote into holds one file per run: only the latest one counts."""
+    return sorted(files, key=os.path.getmtime, reverse=True)[:1]
+
+
 def summarize_counters(args):
     """DIR/fetch and DIR/write: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script with --copy-ref and
     --launch-log DIR/<kind>/launches.txt; DIR/trace (optional): a --kernel-trace --stats run with its launch log."""
@@ -277,7 +282,7 @@ def summarize_counters(args):
     per_label = {}
     scale = {}
     for kind, counter in (("fetch", "FETCH_SIZE"), ("write", "WRITE_SIZE")):
-        f = glob.glob(os.path.join(d, kind, "**", "*counter_collection.csv"), recursive=True)
+        f = newest(glob.glob(os.path.join(d, kind, "**", "*counter_collection.csv"), recursive=True))
         if not f:
             raise SystemExit(f"no counter_collection.csv under {d}/{kind}")
         disp, copy = read_dispatches(f[0], "Counter_Value")
@@ -289,13 +294,13 @@ def summarize_counters(args):
             e = per_label.setdefault(lab, {"fetch": [], "write": [], "symbols": sorted({disp[i][0] for i in idx})})
             e[kind].append(sum(disp[i][1] for i in idx) * 1024 * scale[kind])
     trace_us, stats_lines = {}, []
-    tf = glob.glob(os.path.join(d, "trace", "**", "*kernel_trace.csv"), recursive=True)
+    tf = newest(glob.glob(os.path.join(d, "trace", "**", "*kernel_trace.csv"), recursive=True))
     if tf:
         disp, _ = read_dispatches(tf[0])
         labels = open(os.path.join(d, "trace", "launches.txt")).read().split()
         for lab, idx in zip(labels, match_launches(labels, [s for s, _ in disp])):
             trace_us.setdefault(lab, []).append(sum(disp[i][1][1] - disp[i][1][0] for i in idx) / 1e3)
-        for sf in glob.glob(os.path.join(d, "trace", "**", "*kernel_stats.csv"), recursive=True):
+        for sf in newest(glob.glob(os.path.join(d, "trace", "**", "*kernel_stats.csv"), recursive=True)):
             for r in csv.DictReader(open(sf)):
                 if "plx::" in r["Name"]:
                     stats_lines.append((float(r["Percentage"]), f"| `{short_symbol(r['Name'])}` | {r['Calls']} | "
