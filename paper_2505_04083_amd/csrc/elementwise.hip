@@ -199,6 +199,59 @@ __global__ __launch_bounds__(256) void k_softmax_ce_v4(int64_t n, int c, const f
     if (t == 0) row_loss[i] = -(z[label] - mx - logf(sum));
 }
 
+// bf16 rows that are 16-byte aligned: the same with 8 classes per lane (c <= 8 * GS)
+template <int GS>
+__global__ __launch_bounds__(256) void k_softmax_ce_v8(int64_t n, int c, const bf16_t* __restrict__ Z, int64_t ldz,
+                                                       const int64_t* __restrict__ y, bf16_t* __restrict__ dZ, int64_t lddz,
+                                                       float* __restrict__ row_loss, float inv_n) {
+    const int t = threadIdx.x % GS, j0 = 8 * t;
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / GS;
+    const bool live = i < n;
+    const bf16_t* z = Z + (live ? i : 0) * ldz;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = -INFINITY;
+    if (live && j0 + 7 < c) {
+        union { uint4 raw; bf16_t e[8]; } u;
+        u.raw = *reinterpret_cast<const uint4*>(z + j0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = widen(u.e[e]);
+    } else if (live) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (j0 + e < c) v[e] = widen(z[j0 + e]);
+    }
+    float mx = v[0];
+#pragma unroll
+    for (int e = 1; e < 8; ++e) mx = fmaxf(mx, v[e]);
+#pragma unroll
+    for (int off = GS / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, GS));
+    float sum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        v[e] = (j0 + e < c) ? expf(v[e] - mx) : 0.f;
+        sum += v[e];
+    }
+#pragma unroll
+    for (int off = GS / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off, GS);
+    if (!live) return;
+    const float inv = 1.f / sum;
+    int64_t label = y[i];
+    label = label < 0 ? 0 : (label >= c ? c - 1 : label);   // out-of-range labels are clamped
+    bf16_t* g = dZ + i * lddz;
+    union { uint4 raw; bf16_t e[8]; } o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o.e[e] = narrow<bf16_t>((v[e] * inv - (j0 + e == label ? 1.f : 0.f)) * inv_n);
+    if (j0 + 7 < c) {
+        *reinterpret_cast<uint4*>(g + j0) = o.raw;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (j0 + e < c) g[j0 + e] = o.e[e];
+    }
+    if (t == 0) row_loss[i] = -(widen(z[label]) - mx - logf(sum));
+}
+
 // Fixed-order sum: the live slots are `stride` apart; block b adds the 2048 live slots of its range
 // (8 per thread, then a tree in LDS) into the first of them.  Repeated until one slot is left.
 __global__ __launch_bounds__(256) void k_sum_level(float* v, int64_t n_live, int64_t stride, float* out, float scale) {
@@ -340,6 +393,14 @@ plx_status launch_softmax_ce(plx_ctx* ctx, int64_t n, int64_t c, const void* Z, 
 #define PLX_SM4(GSV) k_softmax_ce_v4<GSV><<<grid4, 256, 0, s>>>(n, (int)c, (const float*)Z, ldz, y, (float*)dZ, lddz, row_loss, inv_n)
         if (g4 == 4) PLX_SM4(4); else if (g4 == 8) PLX_SM4(8); else if (g4 == 16) PLX_SM4(16); else if (g4 == 32) PLX_SM4(32); else PLX_SM4(64);
 #undef PLX_SM4
+    } else if (dtype == PLX_BF16 && c <= 512 && ldz % 8 == 0 && lddz % 8 == 0 && aligned16(Z) && aligned16(dZ)) {
+        const int q = (int)ceil_div(c, 8);
+        const int g8 = q <= 2 ? 2 : (q <= 4 ? 4 : (q <= 8 ? 8 : (q <= 16 ? 16 : (q <= 32 ? 32 : 64))));
+        dim3 grid8((unsigned)ceil_div(n * g8, 256));
+#define PLX_SM8(GSV) k_softmax_ce_v8<GSV><<<grid8, 256, 0, s>>>(n, (int)c, (const bf16_t*)Z, ldz, y, (bf16_t*)dZ, lddz, row_loss, inv_n)
+        if (g8 == 2) PLX_SM8(2); else if (g8 == 4) PLX_SM8(4); else if (g8 == 8) PLX_SM8(8); else if (g8 == 16) PLX_SM8(16);
+        else if (g8 == 32) PLX_SM8(32); else PLX_SM8(64);
+#undef PLX_SM8
     } else {
     const int gs = c <= 32 ? 8 : (c <= 64 ? 16 : (c <= 128 ? 32 : 64));
     dim3 grid((unsigned)ceil_div(n * gs, 256));

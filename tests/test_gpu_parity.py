@@ -463,6 +463,28 @@ def test_softmax_ce_widths_and_layouts(ctx, c, padded):
     assert bool((g[:, c:] == 7.0).all())
 
 
+@pytest.mark.parametrize("c", [1, 5, 16, 41, 47, 128, 130, 257, 600])
+@pytest.mark.parametrize("padded", [False, True])
+def test_softmax_ce_bf16_widths_and_layouts(ctx, c, padded):
+    """The loss head on bf16 logits: contiguous rows (the scalar kernel unless c is a multiple of 8) and rows padded to
+    16 bytes (eight classes per lane, 128-bit accesses, up to 512 classes).  The oracle sees the logits as stored; the
+    gradient comes back rounded to bf16 (2^-9 of an element), the loss in fp32; padding holds NaN on input and must stay
+    untouched on output."""
+    n = 1237
+    r = np.random.default_rng(100 + c)
+    Zb = torch.from_numpy((r.standard_normal((n, c)) * 4).astype(np.float32)).to(torch.bfloat16)
+    y = r.integers(0, c, n)
+    ld = -(-c // 8) * 8 + 8 if padded else c
+    Zd = torch.full((n, ld), float("nan"), device=DEV, dtype=torch.bfloat16); Zd[:, :c] = Zb.to(DEV)
+    g = torch.full((n, ld), 7.0, device=DEV, dtype=torch.bfloat16)
+    loss = torch.zeros(1, device=DEV)
+    plx.plx_softmax_ce(ctx, Zd[:, :c], dev(y), g[:, :c], loss=loss); plx.plx_sync(ctx)
+    ref_loss, ref_g = oracle.softmax_ce(Zb.double().numpy(), y)
+    assert rel_err(g[:, :c].float(), ref_g) <= 4e-3
+    assert abs(loss.item() - ref_loss) <= TOL32 * max(1.0, abs(ref_loss))
+    assert bool((g[:, c:] == 7.0).all())
+
+
 @pytest.mark.parametrize("order", [plx.PLX_ORDER_COMBINE_FIRST, plx.PLX_ORDER_AGG_FIRST, plx.PLX_ORDER_AUTO])
 def test_three_layer_network_parity(ctx, order):
     """configs[0]: R-MAT N=4096, 65,536 edges, 128-128-128-16, one forward + backward, against
